@@ -1,0 +1,74 @@
+"""Pure-Python (lists + math, no numpy) brute force for toy layers -- TEST INFRASTRUCTURE ONLY.
+
+An independent second statement of the same definitions as ``clada_oracle.c``,
+usable only on tiny shapes (d, d_ff, T <= ~16).  The C oracle is pinned against
+this; the two share no code.
+"""
+import math
+
+
+def silu(g):
+    return g / (1.0 + math.exp(-g))
+
+
+def dot(u, v):
+    s = 0.0
+    for a, b in zip(u, v):
+        s += a * b
+    return s
+
+
+def neuron_terms(w_gate, w_up, x):
+    """(a_j, u_j, h_j) of every neuron for one token x."""
+    out = []
+    for wg, wu in zip(w_gate, w_up):
+        a = silu(dot(wg, x))
+        u = dot(wu, x)
+        out.append((a, u, a * u))
+    return out
+
+
+def ffn_for_subset(w_gate, w_up, w_down, x, subset):
+    """y = sum_{j in subset} h_j * W_down[j,:], j ascending."""
+    d = len(x)
+    terms = neuron_terms(w_gate, w_up, x)
+    y = [0.0] * d
+    for j in sorted(subset):
+        h = terms[j][2]
+        for i in range(d):
+            y[i] += h * w_down[j][i]
+    return y
+
+
+def kept_set(w_gate, x, tau):
+    """Neurons with |SiLU(gate)| >= tau (cut iff strictly below)."""
+    return [j for j, wg in enumerate(w_gate) if abs(silu(dot(wg, x))) >= tau]
+
+
+def all_subset_outputs(w_gate, w_up, w_down, x):
+    """Outputs of all 2^F masks of a toy layer, keyed by the mask's bit pattern."""
+    F = len(w_gate)
+    return {bits: ffn_for_subset(w_gate, w_up, w_down, x,
+                                 [j for j in range(F) if bits >> j & 1])
+            for bits in range(1 << F)}
+
+
+def neuron_magnitude(w_gate, w_up, w_down, X, j):
+    """A_j of the neuron-activation equation by its literal reading: the
+    Frobenius norm of the rank-one T x d matrix h_{:,j} W_down[j,:]."""
+    s = 0.0
+    for x in X:
+        h = silu(dot(w_gate[j], x)) * dot(w_up[j], x)
+        for wd in w_down[j]:
+            s += (h * wd) ** 2
+    return math.sqrt(s)
+
+
+def softmax_signals(z, tok):
+    """(surprisal, entropy) of one logits row by direct normalisation."""
+    m = max(z)
+    e = [math.exp(v - m) for v in z]
+    Z = sum(e)
+    p = [v / Z for v in e]
+    H = -sum(q * math.log(q) for q in p if q > 0.0)
+    return -math.log(p[tok]), H

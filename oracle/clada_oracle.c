@@ -1,0 +1,358 @@
+/*
+ * CLADA fp64 CPU oracle  --  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, obviously-correct implementation of the thresholded sparse
+ * SwiGLU FFN path of CLADA (arXiv 2502.19078), written straight from the
+ * paper's definitions.  It exists so that the GPU library can be checked
+ * against something that shares no code with it.  Only tests, the smoke check
+ * and the benchmark's cpu_baseline leg may call it; the product never does.
+ *
+ * Conventions
+ *   - every input is the exact stored value (fp32, or bf16 widened to fp32,
+ *     which is exact), passed as float; every arithmetic step is fp64 with no
+ *     intermediate rounding, no blocking, no reordering beyond what the
+ *     definition states (sums run over ascending index).
+ *   - weights are neuron-major: row j of W_gate / W_up is neuron j's input
+ *     projection row, row j of W_down is neuron j's output-projection column
+ *     (section 3.2.1, text under the neuron-activation equation).
+ *   - OpenMP only splits loops whose iterations are independent, so results
+ *     do not depend on the thread count.
+ *
+ * Pins (see tests/test_oracle_*.py): library fp64 matmul, scalar hand cases,
+ * tau=0 => dense, tau=+inf => zero, pure-Python brute force on 8-neuron toys,
+ * closed forms for entropy/surprisal, the printed lambda/gamma factor table,
+ * numpy.partition order statistics.  No function here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* sigma in the neuron-activation equation, read as SiLU for gated (SwiGLU)
+ * FFNs: sigma(g) = g * sigmoid(g) = g / (1 + exp(-g)). */
+static double silu(double g) { return g / (1.0 + exp(-g)); }
+
+static double dot_fd(const float *w, const float *x, int n)
+{
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += (double)w[i] * (double)x[i];
+    return s;
+}
+
+int clada_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------
+ * Prefill: dense FFN over the prefix plus per-neuron aggregates.
+ * (section 3.2.1, neuron-activation equation; Algorithm "CLADA Inference",
+ * prefill phase.)
+ *
+ *   g_tj = W_gate[j,:] . X[t,:]      u_tj = W_up[j,:] . X[t,:]
+ *   a_tj = SiLU(g_tj)                h_tj = a_tj * u_tj
+ *   Y[t,:] = sum_j h_tj * W_down[j,:]
+ *   sum_abs_act[j] = sum_t |a_tj|    sum_sq_act[j] = sum_t a_tj^2
+ *   max_abs_act[j] = max_t |a_tj|    sum_sq_h[j]   = sum_t h_tj^2
+ *   A[j] = || h_{:,j} W_down[j,:] ||_F = sqrt(sum_sq_h[j]) * ||W_down[j,:]||_2
+ *   pool[t][j] = |a_tj|
+ * Any output pointer may be NULL.
+ * ---------------------------------------------------------------------- */
+int clada_oracle_prefix_stats(const float *w_gate, const float *w_up,
+                              const float *w_down, int d, int d_ff,
+                              const float *x, int T, double *y,
+                              double *sum_abs_act, double *sum_sq_act,
+                              double *max_abs_act, double *sum_sq_h, double *A,
+                              double *pool)
+{
+    if (!w_gate || !w_up || !w_down || !x || d <= 0 || d_ff <= 0 || T < 0) return 1;
+    double *h = NULL;
+    if (y) {
+        h = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * (size_t)d_ff);
+        if (!h) return 2;
+    }
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < d_ff; ++j) {
+        const float *wg = w_gate + (size_t)j * d;
+        const float *wu = w_up + (size_t)j * d;
+        const float *wd = w_down + (size_t)j * d;
+        double s_abs = 0.0, s_sq = 0.0, mx = 0.0, s_h2 = 0.0;
+        for (int t = 0; t < T; ++t) {
+            const float *xt = x + (size_t)t * d;
+            double g = dot_fd(wg, xt, d);
+            double u = dot_fd(wu, xt, d);
+            double a = silu(g);
+            double hv = a * u;
+            double aa = fabs(a);
+            s_abs += aa;
+            s_sq += a * a;
+            if (aa != aa) mx = aa;                       /* a NaN sticks */
+            else if (mx == mx && aa > mx) mx = aa;
+            s_h2 += hv * hv;
+            if (pool) pool[(size_t)t * d_ff + j] = aa;
+            if (h) h[(size_t)t * d_ff + j] = hv;
+        }
+        double wn2 = 0.0;
+        for (int i = 0; i < d; ++i) wn2 += (double)wd[i] * (double)wd[i];
+        if (sum_abs_act) sum_abs_act[j] = s_abs;
+        if (sum_sq_act) sum_sq_act[j] = s_sq;
+        if (max_abs_act) max_abs_act[j] = mx;
+        if (sum_sq_h) sum_sq_h[j] = s_h2;
+        if (A) A[j] = sqrt(s_h2) * sqrt(wn2);
+    }
+    if (y) {
+#pragma omp parallel for schedule(static)
+        for (int t = 0; t < T; ++t) {
+            double *yt = y + (size_t)t * d;
+            for (int i = 0; i < d; ++i) yt[i] = 0.0;
+            for (int j = 0; j < d_ff; ++j) {
+                double hv = h[(size_t)t * d_ff + j];
+                const float *wd = w_down + (size_t)j * d;
+                for (int i = 0; i < d; ++i) yt[i] += hv * (double)wd[i];
+            }
+        }
+        free(h);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Base-threshold calibration, percentile stand-in for the CETT search of
+ * section 3.2.2: tau_base = the k-th smallest of the pooled prefix magnitudes,
+ * k = max(1, ceil(q * n)) (nearest-rank quantile).  q is the fp32 value the
+ * caller holds, widened; the rank is taken in fp64.
+ * ---------------------------------------------------------------------- */
+static int cmp_double(const void *a, const void *b)
+{
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+int64_t clada_oracle_quantile_rank(int64_t n, float q)
+{
+    double r = ceil((double)q * (double)n);
+    int64_t k = (int64_t)r;
+    if (k < 1) k = 1;
+    if (k > n) k = n;
+    return k;
+}
+
+int clada_oracle_calibrate(const double *pool, int64_t n, float q, double *tau_base)
+{
+    if (!pool || !tau_base || n <= 0 || !(q >= 0.0f) || !(q < 1.0f)) return 1;
+    double *tmp = (double *)malloc(sizeof(double) * (size_t)n);
+    if (!tmp) return 2;
+    memcpy(tmp, pool, sizeof(double) * (size_t)n);
+    qsort(tmp, (size_t)n, sizeof(double), cmp_double);
+    *tau_base = tmp[clada_oracle_quantile_rank(n, q) - 1];
+    free(tmp);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Cognitive-load signals (section 2.3.1, surprisal and entropy equations):
+ *   P = softmax(z) over the vocabulary (natural log, raw nats)
+ *   s = -log P[tok] = lse - z_tok
+ *   H = -sum_v P_v log P_v, terms with P_v = 0 contribute 0
+ * A row holding NaN or +inf, or nothing but -inf, has no distribution:
+ * s = H = NaN.  A token id outside [0, V) gives s = NaN, H still defined.
+ * ---------------------------------------------------------------------- */
+int clada_oracle_signals(const float *logits, int B, int V, const int32_t *tok,
+                         double *surprisal, double *entropy)
+{
+    if (!logits || !tok || !surprisal || !entropy || B < 0 || V <= 0) return 1;
+    for (int b = 0; b < B; ++b) {
+        const float *z = logits + (size_t)b * V;
+        double m = -INFINITY;
+        int bad = 0;
+        for (int v = 0; v < V; ++v) {
+            double zv = (double)z[v];
+            if (zv != zv || zv == INFINITY) bad = 1;
+            if (zv > m) m = zv;
+        }
+        if (bad || m == -INFINITY) {
+            surprisal[b] = NAN;
+            entropy[b] = NAN;
+            continue;
+        }
+        double Z = 0.0;
+        for (int v = 0; v < V; ++v) Z += exp((double)z[v] - m);
+        double lse = m + log(Z);
+        double H = 0.0;
+        for (int v = 0; v < V; ++v) {
+            double logp = (double)z[v] - lse;
+            double p = exp(logp);
+            if (p > 0.0) H -= p * logp;
+        }
+        entropy[b] = H;
+        surprisal[b] = (tok[b] >= 0 && tok[b] < V) ? lse - (double)z[tok[b]] : NAN;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Token-aware threshold (section 3.2.3, final-threshold equation):
+ *   tau_final[l][b] = tau_base[l] * (1 + lambda[l]*[s_b > tau_s]
+ *                                      + gamma[l]*[H_b > tau_H])
+ * Strict '>' as printed; signed coefficients, no clamp.
+ * ---------------------------------------------------------------------- */
+int clada_oracle_threshold(const double *tau_base, const double *lambda,
+                           const double *gamma, int L, const double *surprisal,
+                           const double *entropy, int B, double tau_s,
+                           double tau_H, double *tau_final)
+{
+    if (!tau_base || !lambda || !gamma || !surprisal || !entropy || !tau_final ||
+        L < 0 || B < 0)
+        return 1;
+    for (int l = 0; l < L; ++l)
+        for (int b = 0; b < B; ++b) {
+            double is = surprisal[b] > tau_s ? 1.0 : 0.0;
+            double ih = entropy[b] > tau_H ? 1.0 : 0.0;
+            tau_final[(size_t)l * B + b] = tau_base[l] * (1.0 + lambda[l] * is + gamma[l] * ih);
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Decode-time activations of one layer: a_bj = SiLU(W_gate[j,:] . x_b).
+ * ---------------------------------------------------------------------- */
+int clada_oracle_gate_act(const float *w_gate, int d, int d_ff, const float *x,
+                          int B, double *act /* [B][d_ff] */)
+{
+    if (!w_gate || !x || !act || d <= 0 || d_ff <= 0 || B < 0) return 1;
+    for (int b = 0; b < B; ++b) {
+        const float *xb = x + (size_t)b * d;
+#pragma omp parallel for schedule(static)
+        for (int j = 0; j < d_ff; ++j)
+            act[(size_t)b * d_ff + j] = silu(dot_fd(w_gate + (size_t)j * d, xb, d));
+    }
+    return 0;
+}
+
+/* y_b = sum over kept j (ascending) of a_bj * (W_up[j,:] . x_b) * W_down[j,:]
+ * with the kept set given per token.  mask == NULL keeps every neuron. */
+static void ffn_given_mask(const float *w_gate, const float *w_up,
+                           const float *w_down, int d, int d_ff, const float *x,
+                           int B, const uint8_t *mask, const double *act_in,
+                           double *y)
+{
+    double *h = (double *)malloc(sizeof(double) * (size_t)d_ff);
+    for (int b = 0; b < B; ++b) {
+        const float *xb = x + (size_t)b * d;
+        const uint8_t *mb = mask ? mask + (size_t)b * d_ff : NULL;
+#pragma omp parallel for schedule(static)
+        for (int j = 0; j < d_ff; ++j) {
+            if (mb && !mb[j]) {
+                h[j] = 0.0;
+                continue;
+            }
+            double a = act_in ? act_in[(size_t)b * d_ff + j]
+                              : silu(dot_fd(w_gate + (size_t)j * d, xb, d));
+            double u = dot_fd(w_up + (size_t)j * d, xb, d);
+            h[j] = a * u;
+        }
+        double *yb = y + (size_t)b * d;
+        /* each thread owns a block of output columns and walks j upward */
+#pragma omp parallel
+        {
+#ifdef _OPENMP
+            int nt = omp_get_num_threads(), id = omp_get_thread_num();
+#else
+            int nt = 1, id = 0;
+#endif
+            int lo = (int)((int64_t)d * id / nt), hi = (int)((int64_t)d * (id + 1) / nt);
+            for (int i = lo; i < hi; ++i) yb[i] = 0.0;
+            for (int j = 0; j < d_ff; ++j) {
+                if (mb && !mb[j]) continue;
+                double hv = h[j];
+                const float *wd = w_down + (size_t)j * d;
+                for (int i = lo; i < hi; ++i) yb[i] += hv * (double)wd[i];
+            }
+        }
+    }
+    free(h);
+}
+
+/* ------------------------------------------------------------------------
+ * Sparse decode of one layer (Algorithm "CLADA Inference", generation phase:
+ * regenerate the mask by thresholding, then the sparse forward pass).
+ *   keep_bj = (|a_bj| >= tau_b)      (cut iff strictly below; NaN is cut)
+ *   y_b     = sum_{j kept for b} a_bj u_bj W_down[j,:]
+ *   active_idx = ascending { j : kept for some b },  n_active[0] = its size,
+ *   n_active[1+b] = kept count of token b.
+ * Optional outputs: act [B][d_ff], mask [B][d_ff] (0/1), active_idx [d_ff],
+ * n_active [1+B].
+ * ---------------------------------------------------------------------- */
+int clada_oracle_sparse_decode(const float *w_gate, const float *w_up,
+                               const float *w_down, int d, int d_ff,
+                               const float *x, int B, const double *tau,
+                               double *y, double *act, uint8_t *mask,
+                               int32_t *active_idx, int32_t *n_active)
+{
+    if (!w_gate || !w_up || !w_down || !x || !tau || !y || d <= 0 || d_ff <= 0 || B < 0)
+        return 1;
+    size_t n = (size_t)(B > 0 ? B : 1) * (size_t)d_ff;
+    double *a = (double *)malloc(sizeof(double) * n);
+    uint8_t *m = (uint8_t *)malloc(n);
+    if (!a || !m) return 2;
+    clada_oracle_gate_act(w_gate, d, d_ff, x, B, a);
+    for (int b = 0; b < B; ++b)
+        for (int j = 0; j < d_ff; ++j)
+            m[(size_t)b * d_ff + j] = (fabs(a[(size_t)b * d_ff + j]) >= tau[b]) ? 1 : 0;
+    ffn_given_mask(w_gate, w_up, w_down, d, d_ff, x, B, m, a, y);
+    if (n_active || active_idx) {
+        int32_t nu = 0;
+        for (int j = 0; j < d_ff; ++j) {
+            int any = 0;
+            for (int b = 0; b < B; ++b) any |= m[(size_t)b * d_ff + j];
+            if (any) {
+                if (active_idx) active_idx[nu] = j;
+                ++nu;
+            }
+        }
+        if (n_active) {
+            n_active[0] = nu;
+            for (int b = 0; b < B; ++b) {
+                int32_t c = 0;
+                for (int j = 0; j < d_ff; ++j) c += m[(size_t)b * d_ff + j];
+                n_active[1 + b] = c;
+            }
+        }
+    }
+    if (act) memcpy(act, a, sizeof(double) * (size_t)B * d_ff);
+    if (mask) memcpy(mask, m, (size_t)B * d_ff);
+    free(a);
+    free(m);
+    return 0;
+}
+
+/* The same forward pass on a kept set supplied by the caller (used to check a
+ * device result whose mask differs from the oracle's only inside the allowed
+ * band around the threshold). */
+int clada_oracle_decode_given_mask(const float *w_gate, const float *w_up,
+                                   const float *w_down, int d, int d_ff,
+                                   const float *x, int B, const uint8_t *mask,
+                                   double *y)
+{
+    if (!w_gate || !w_up || !w_down || !x || !mask || !y || d <= 0 || d_ff <= 0 || B < 0)
+        return 1;
+    ffn_given_mask(w_gate, w_up, w_down, d, d_ff, x, B, mask, NULL, y);
+    return 0;
+}
+
+/* Dense twin: every neuron kept (the paper's "Dense" column). */
+int clada_oracle_dense_decode(const float *w_gate, const float *w_up,
+                              const float *w_down, int d, int d_ff,
+                              const float *x, int B, double *y)
+{
+    if (!w_gate || !w_up || !w_down || !x || !y || d <= 0 || d_ff <= 0 || B < 0) return 1;
+    ffn_given_mask(w_gate, w_up, w_down, d, d_ff, x, B, NULL, NULL, y);
+    return 0;
+}
