@@ -1,0 +1,173 @@
+/*
+ * clada.h -- C ABI of the MI355X (gfx950) implementation of CLADA's decode-time
+ * hot path: the thresholded sparse SwiGLU FFN and the small calls that feed it
+ * (arXiv 2502.19078, section 3.2 "Dynamic Threshold Strategy" and the
+ * algorithm "CLADA Inference").
+ *
+ * General rules
+ *   - Every tensor pointer is BORROWED DEVICE memory owned by the caller; it
+ *     must stay valid until the work enqueued by the call has finished.  The
+ *     only host pointers are the context, the small descriptor structs and the
+ *     scalars.  `hip_stream` is a hipStream_t passed as void* (NULL = the
+ *     default stream).
+ *   - Calls validate their arguments on the host before touching HIP, enqueue
+ *     kernels on `hip_stream` and return without synchronising.  They allocate
+ *     nothing: scratch lives in the context's workspace, sized at
+ *     clada_create() with clada_workspace_bytes().
+ *   - A context serves one stream at a time; calls issued to one context from
+ *     several threads or streams at once race on its workspace.
+ *   - Every call returns a clada_status and never throws or aborts;
+ *     clada_last_error() gives the text of the last failure of that context.
+ *   - Weights are neuron-major: W_gate[d_ff][d], W_up[d_ff][d], W_down[d_ff][d],
+ *     row-major, row j holding neuron j's two input-projection rows and its
+ *     output-projection column (text under the neuron-activation equation of
+ *     section 3.2.1).  Rows must be 16-byte aligned: d*sizeof(elem) % 16 == 0.
+ *   - Activations x/y use the layer's dtype; statistics, signals, thresholds
+ *     are fp32; indices are int32.
+ */
+#ifndef CLADA_H
+#define CLADA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct clada_ctx clada_ctx; /* opaque; owns only its workspace */
+
+typedef enum {
+    CLADA_OK = 0,
+    CLADA_ERR_NULL = 1,      /* a required pointer is NULL */
+    CLADA_ERR_SHAPE = 2,     /* a size is non-positive, too large, or violates a divisibility rule */
+    CLADA_ERR_DTYPE = 3,     /* unknown clada_dtype */
+    CLADA_ERR_ALIGN = 4,     /* a pointer is not 16-byte aligned */
+    CLADA_ERR_WORKSPACE = 5, /* the context's workspace is too small for this call */
+    CLADA_ERR_VALUE = 6,     /* a scalar argument is out of its domain */
+    CLADA_ERR_HIP = 7        /* a HIP runtime call failed (text in clada_last_error) */
+} clada_status;
+
+typedef enum { CLADA_F32 = 0, CLADA_BF16 = 1 } clada_dtype;
+
+/* Limits checked by every call (CLADA_ERR_SHAPE beyond them). */
+#define CLADA_MAX_D 8192       /* model width d; also d*sizeof(elem) <= 16384 */
+#define CLADA_MAX_DFF 262144   /* FFN width d_ff           */
+#define CLADA_MAX_BATCH 64     /* decode batch B           */
+#define CLADA_MAX_LAYERS 4096  /* layers L in clada_threshold */
+
+/* Context.  workspace_bytes == 0 creates a context that touches no GPU (every
+ * compute call then fails with CLADA_ERR_WORKSPACE after validation); otherwise
+ * the workspace is allocated on device `device_id`, which must be the device
+ * the caller's tensors and stream live on. */
+clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes);
+void clada_destroy(clada_ctx *ctx);
+const char *clada_status_str(clada_status s);
+const char *clada_last_error(const clada_ctx *ctx);
+
+/* Launch-shape tuning knobs; results never depend on them beyond fp32 summation
+ * order.  Names: "decode.wgs_per_cu" (1 or 2 workgroups of the decode kernel per
+ * compute unit), "decode.variant" (0 = default kernel variant).  Unknown names or
+ * out-of-range values give CLADA_ERR_VALUE and change nothing. */
+clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);
+
+/* Upper bound of the workspace any call needs for these sizes.  Pass 0 for a
+ * size whose call will not be used (T for prefix_stats/calibrate, V for
+ * cognitive_signals, B for the decode calls). */
+size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int32_t V);
+
+typedef struct {
+    const void *w_gate, *w_up, *w_down; /* device, each [d_ff][d] neuron-major */
+    int32_t d, d_ff;
+    clada_dtype dtype;
+} clada_layer;
+
+typedef struct {            /* device outputs, caller-allocated; any may be NULL to skip */
+    float *sum_abs_act;     /* [d_ff]  sum_t |a_tj|                                   */
+    float *sum_sq_act;      /* [d_ff]  sum_t a_tj^2                                   */
+    float *max_abs_act;     /* [d_ff]  max_t |a_tj|                                   */
+    float *sum_sq_h;        /* [d_ff]  sum_t h_tj^2,  h = a * u                        */
+    float *A;               /* [d_ff]  neuron activation magnitude A_j (section 3.2.1) */
+    float *abs_act_pool;    /* [T][d_ff]  |a_tj|, the pool the base threshold is a quantile of */
+} clada_prefix_out;
+
+/* Prefill statistics (section 3.2.1 "Neuron Activation Prefilling"; algorithm
+ * "CLADA Inference", prefill phase).  Dense SwiGLU FFN over the prefix
+ * x [T][d]:  a = SiLU(x W_gate^T), h = a .* (x W_up^T), y = h W_down, and the
+ * per-neuron aggregates of clada_prefix_out, with
+ *   A_j = || h_{:,j} W_down[j,:] ||_F = sqrt(sum_t h_tj^2) * ||W_down[j,:]||_2.
+ * y [T][d] (layer dtype) may be NULL.  T >= 1.  bf16 layers use bf16 MFMA with
+ * fp32 accumulation (h is rounded to bf16 before the down projection); fp32
+ * layers use fp32 MFMA. */
+clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *layer, const void *x,
+                                int32_t T, void *y, const clada_prefix_out *out,
+                                void *hip_stream);
+
+/* Base threshold from the pooled prefix magnitudes: the nearest-rank
+ * q-quantile, i.e. the k-th smallest of abs_act_pool[0..n), k = max(1,
+ * ceil(q*n)) taken in fp64.  This is the percentile stand-in for the
+ * error-bounded threshold search of section 3.2.2.  Values must be
+ * non-negative finite floats (or +inf); NaN entries make the result
+ * unspecified.  q in [0,1), n >= 1.  Result: one fp32 on the device. */
+clada_status clada_threshold_calibrate(clada_ctx *ctx, const float *abs_act_pool, int64_t n,
+                                       float target_sparsity, float *tau_base_out,
+                                       void *hip_stream);
+
+/* Cognitive-load signals (section 2.3.1, surprisal and entropy equations), per
+ * row b of logits [B][V] (fp32 or bf16), natural log:
+ *   surprisal[b] = -log softmax(z_b)[token_ids[b]],  entropy[b] = -sum_v p_v log p_v.
+ * One pass over the logits (online log-sum-exp).  A row holding NaN or +inf, or
+ * only -inf, yields NaN for both; a token id outside [0,V) yields NaN surprisal.
+ * These are device-side values: no status is raised for them. */
+clada_status clada_cognitive_signals(clada_ctx *ctx, const void *logits,
+                                     clada_dtype logits_dtype, int32_t B, int32_t V,
+                                     const int32_t *token_ids, float *surprisal,
+                                     float *entropy, void *hip_stream);
+
+/* Token-aware threshold (section 3.2.3, final-threshold equation):
+ *   tau_final[l][b] = tau_base[l] * (1 + lambda[l]*[s_b > tau_s] + gamma[l]*[H_b > tau_H]).
+ * Strict '>', signed coefficients, no clamping.  tau_s / tau_H may be +-inf to
+ * force the indicators off / on.  All arrays on the device. */
+clada_status clada_threshold(clada_ctx *ctx, const float *tau_base, const float *lambda,
+                             const float *gamma, int32_t L, const float *surprisal,
+                             const float *entropy, int32_t B, float tau_s, float tau_H,
+                             float *tau_final, void *hip_stream);
+
+/* Thresholded sparse SwiGLU FFN for one layer at decode time (algorithm "CLADA
+ * Inference", generation phase: regenerate the mask by thresholding, then the
+ * sparse forward pass).  For each token b of x [B][d]:
+ *   a_bj = SiLU(W_gate[j,:] . x_b)          (dense gate projection, fp32 accumulate)
+ *   keep_bj = |a_bj| >= tau_final[b]        (fp32 compare; NaN is cut)
+ *   y_b = sum_{j kept} a_bj (W_up[j,:] . x_b) W_down[j,:]
+ * Only rows of W_up / W_down of neurons kept by at least one token are read.
+ * tau_final [B] is this layer's row of clada_threshold's output.
+ * Optional outputs (NULL to skip): active_idx [d_ff] ascending indices of the
+ * union of kept neurons (entries past the count are left untouched);
+ * n_active [1+B] = {union count, per-token counts}; mask_bits
+ * [B][ceil(d_ff/32)] bit j%32 of word j/32 set iff keep_bj.
+ * The result is bit-reproducible from run to run (fixed summation order). */
+clada_status clada_sparse_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
+                                     int32_t B, const float *tau_final, void *y,
+                                     int32_t *active_idx, int32_t *n_active,
+                                     uint32_t *mask_bits, void *hip_stream);
+
+/* Dense twin of clada_sparse_ffn_decode (every neuron kept; the paper's "Dense"
+ * column): same layout and reduction order, gate/up/down rows all read. */
+clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
+                                    int32_t B, void *y, void *hip_stream);
+
+/* Measurement helpers (no part of the method).  clada_diag_stream_read reads
+ * `bytes` of device memory once with 16-byte loads from blocks_per_cu*CUs
+ * workgroups and discards them: the practical HBM read ceiling the decode
+ * kernels are compared with.  clada_diag_copy copies `bytes` from src to dst:
+ * the known-size transfer the profiler's fetch/write counters are scaled by.
+ * Pointers and sizes must be multiples of 16 bytes. */
+clada_status clada_diag_stream_read(clada_ctx *ctx, const void *src, size_t bytes,
+                                    int32_t blocks_per_cu, void *hip_stream);
+clada_status clada_diag_copy(clada_ctx *ctx, const void *src, void *dst, size_t bytes,
+                             void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLADA_H */

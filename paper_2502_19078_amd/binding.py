@@ -1,0 +1,241 @@
+"""ctypes binding of libclada (argument marshalling only; no arithmetic here).
+
+Function names mirror the C ABI in ``include/clada.h``.  Tensors are torch CUDA
+tensors; kernels are enqueued on torch's current stream of the tensor's device.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libclada.so")
+_lib = None
+
+F32, BF16 = 0, 1
+_STATUS = ["CLADA_OK", "CLADA_ERR_NULL", "CLADA_ERR_SHAPE", "CLADA_ERR_DTYPE", "CLADA_ERR_ALIGN",
+           "CLADA_ERR_WORKSPACE", "CLADA_ERR_VALUE", "CLADA_ERR_HIP"]
+
+
+class CladaError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        self.status = status
+        name = _STATUS[status] if 0 <= status < len(_STATUS) else f"status {status}"
+        super().__init__(f"{name}: {text}")
+
+
+class _CLayer(C.Structure):
+    _fields_ = [("w_gate", C.c_void_p), ("w_up", C.c_void_p), ("w_down", C.c_void_p),
+                ("d", C.c_int32), ("d_ff", C.c_int32), ("dtype", C.c_int)]
+
+
+class _CPrefixOut(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("sum_abs_act", "sum_sq_act", "max_abs_act", "sum_sq_h", "A", "abs_act_pool")]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> C.CDLL:
+    """Load libclada.so; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                           f"`python -m paper_2502_19078_amd.build` (hipcc, gfx950)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
+    lib.clada_create.argtypes = [C.POINTER(vp), C.c_int, C.c_size_t]
+    lib.clada_destroy.argtypes = [vp]
+    lib.clada_destroy.restype = None
+    lib.clada_status_str.argtypes = [C.c_int]
+    lib.clada_status_str.restype = C.c_char_p
+    lib.clada_last_error.argtypes = [vp]
+    lib.clada_last_error.restype = C.c_char_p
+    lib.clada_set_option.argtypes = [vp, C.c_char_p, i32]
+    lib.clada_workspace_bytes.argtypes = [i32] * 5
+    lib.clada_workspace_bytes.restype = C.c_size_t
+    lib.clada_prefix_stats.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, C.POINTER(_CPrefixOut), vp]
+    lib.clada_threshold_calibrate.argtypes = [vp, vp, C.c_int64, f32, vp, vp]
+    lib.clada_cognitive_signals.argtypes = [vp, vp, C.c_int, i32, i32, vp, vp, vp, vp]
+    lib.clada_threshold.argtypes = [vp, vp, vp, vp, i32, vp, vp, i32, f32, f32, vp, vp]
+    lib.clada_sparse_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.clada_dense_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp]
+    lib.clada_diag_stream_read.argtypes = [vp, vp, C.c_size_t, i32, vp]
+    lib.clada_diag_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
+    for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
+                 "clada_cognitive_signals", "clada_threshold", "clada_sparse_ffn_decode",
+                 "clada_dense_ffn_decode"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def workspace_bytes(d: int, d_ff: int, B: int, T: int, V: int) -> int:
+    return int(load_library().clada_workspace_bytes(d, d_ff, B, T, V))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(t: torch.Tensor):
+    return C.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+class Context:
+    """Owns a libclada context (its device workspace)."""
+
+    def __init__(self, device: int = 0, workspace_bytes: int = 0):
+        self._lib = load_library()
+        h = C.c_void_p()
+        st = self._lib.clada_create(C.byref(h), int(device), int(workspace_bytes))
+        if st != 0:
+            raise CladaError(st, self._lib.clada_last_error(None).decode())
+        self._h = h
+        self.device = device
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.clada_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def check(self, st: int):
+        if st != 0:
+            raise CladaError(st, self._lib.clada_last_error(self._h).decode())
+
+    def set_option(self, name: str, value: int):
+        self.check(self._lib.clada_set_option(self._h, name.encode(), int(value)))
+
+
+@dataclass
+class Layer:
+    """Neuron-major weights of one FFN layer, each [d_ff][d] on the GPU."""
+    w_gate: torch.Tensor
+    w_up: torch.Tensor
+    w_down: torch.Tensor
+
+    def c_struct(self) -> _CLayer:
+        F, d = self.w_gate.shape
+        for w in (self.w_gate, self.w_up, self.w_down):
+            assert w.is_cuda and w.is_contiguous() and tuple(w.shape) == (F, d) and w.dtype == self.w_gate.dtype
+        return _CLayer(self.w_gate.data_ptr(), self.w_up.data_ptr(), self.w_down.data_ptr(), d, F,
+                       _dtype_code(self.w_gate))
+
+
+@dataclass
+class PrefixStats:
+    sum_abs_act: torch.Tensor
+    sum_sq_act: torch.Tensor
+    max_abs_act: torch.Tensor
+    sum_sq_h: torch.Tensor
+    A: torch.Tensor
+    abs_act_pool: torch.Tensor | None
+    y: torch.Tensor | None
+
+
+def prefix_stats(ctx: Context, layer: Layer, x: torch.Tensor, want_y: bool = True,
+                 want_pool: bool = True) -> PrefixStats:
+    cl = layer.c_struct()
+    T = x.shape[0]
+    assert x.is_cuda and x.is_contiguous() and x.shape == (T, cl.d) and x.dtype == layer.w_gate.dtype
+    f = lambda *s: torch.empty(*s, dtype=torch.float32, device=x.device)
+    stats = [f(cl.d_ff) for _ in range(5)]
+    pool = f(T, cl.d_ff) if want_pool else None
+    y = torch.empty_like(x) if want_y else None
+    out = _CPrefixOut(*[s.data_ptr() for s in stats], pool.data_ptr() if want_pool else None)
+    ctx.check(ctx._lib.clada_prefix_stats(ctx._h, C.byref(cl), _ptr(x), T, _ptr(y), C.byref(out), _stream(x)))
+    return PrefixStats(*stats, pool, y)
+
+
+def threshold_calibrate(ctx: Context, abs_act_pool: torch.Tensor, target_sparsity: float,
+                        out: torch.Tensor | None = None) -> torch.Tensor:
+    p = abs_act_pool
+    assert p.is_cuda and p.is_contiguous() and p.dtype == torch.float32
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=p.device)
+    ctx.check(ctx._lib.clada_threshold_calibrate(ctx._h, _ptr(p), p.numel(), float(target_sparsity),
+                                                 _ptr(out), _stream(p)))
+    return out
+
+
+def cognitive_signals(ctx: Context, logits: torch.Tensor, token_ids: torch.Tensor):
+    B, V = logits.shape
+    assert logits.is_cuda and logits.is_contiguous()
+    assert token_ids.is_cuda and token_ids.dtype == torch.int32 and token_ids.numel() == B
+    s = torch.empty(B, dtype=torch.float32, device=logits.device)
+    h = torch.empty(B, dtype=torch.float32, device=logits.device)
+    ctx.check(ctx._lib.clada_cognitive_signals(ctx._h, _ptr(logits), _dtype_code(logits), B, V,
+                                               _ptr(token_ids), _ptr(s), _ptr(h), _stream(logits)))
+    return s, h
+
+
+def threshold(ctx: Context, tau_base, lam, gam, surprisal, entropy, tau_s: float, tau_H: float,
+              out: torch.Tensor | None = None) -> torch.Tensor:
+    L, B = tau_base.numel(), surprisal.numel()
+    for t in (tau_base, lam, gam, surprisal, entropy):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    assert lam.numel() == L and gam.numel() == L and entropy.numel() == B
+    if out is None:
+        out = torch.empty(L, B, dtype=torch.float32, device=tau_base.device)
+    ctx.check(ctx._lib.clada_threshold(ctx._h, _ptr(tau_base), _ptr(lam), _ptr(gam), L, _ptr(surprisal),
+                                       _ptr(entropy), B, float(tau_s), float(tau_H), _ptr(out),
+                                       _stream(tau_base)))
+    return out
+
+
+def sparse_ffn_decode(ctx: Context, layer: Layer, x: torch.Tensor, tau_final: torch.Tensor,
+                      y: torch.Tensor | None = None, want_lists: bool = False):
+    """Returns y, or (y, active_idx, n_active, mask_bits) when want_lists."""
+    cl = layer.c_struct()
+    B = x.shape[0]
+    assert x.is_cuda and x.is_contiguous() and x.shape == (B, cl.d) and x.dtype == layer.w_gate.dtype
+    assert tau_final.is_cuda and tau_final.dtype == torch.float32 and tau_final.numel() == B
+    assert tau_final.is_contiguous()
+    if y is None:
+        y = torch.empty_like(x)
+    idx = cnt = bits = None
+    if want_lists:
+        idx = torch.full((cl.d_ff,), -1, dtype=torch.int32, device=x.device)
+        cnt = torch.empty(1 + B, dtype=torch.int32, device=x.device)
+        bits = torch.empty(B, (cl.d_ff + 31) // 32, dtype=torch.int32, device=x.device)
+    ctx.check(ctx._lib.clada_sparse_ffn_decode(ctx._h, C.byref(cl), _ptr(x), B, _ptr(tau_final), _ptr(y),
+                                               _ptr(idx), _ptr(cnt), _ptr(bits), _stream(x)))
+    return (y, idx, cnt, bits) if want_lists else y
+
+
+def dense_ffn_decode(ctx: Context, layer: Layer, x: torch.Tensor, y: torch.Tensor | None = None):
+    cl = layer.c_struct()
+    B = x.shape[0]
+    assert x.is_cuda and x.is_contiguous() and x.shape == (B, cl.d) and x.dtype == layer.w_gate.dtype
+    if y is None:
+        y = torch.empty_like(x)
+    ctx.check(ctx._lib.clada_dense_ffn_decode(ctx._h, C.byref(cl), _ptr(x), B, _ptr(y), _stream(x)))
+    return y
+
+
+def diag_stream_read(ctx: Context, src: torch.Tensor, blocks_per_cu: int = 8):
+    ctx.check(ctx._lib.clada_diag_stream_read(ctx._h, _ptr(src), src.numel() * src.element_size(),
+                                              blocks_per_cu, _stream(src)))
+
+
+def diag_copy(ctx: Context, src: torch.Tensor, dst: torch.Tensor):
+    assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    ctx.check(ctx._lib.clada_diag_copy(ctx._h, _ptr(src), _ptr(dst), src.numel() * src.element_size(),
+                                       _stream(src)))

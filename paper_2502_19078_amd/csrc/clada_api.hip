@@ -1,0 +1,130 @@
+// Context management, status strings and shared argument validation of libclada.
+#include <stdarg.h>
+#include <stdlib.h>
+
+#include <new>
+
+#include "clada_internal.h"
+
+static thread_local char g_err_no_ctx[256] = "";
+
+clada_status clada_fail(clada_ctx *ctx, clada_status s, const char *fmt, ...)
+{
+    char *dst = ctx ? ctx->err : g_err_no_ctx;
+    size_t cap = ctx ? sizeof(ctx->err) : sizeof(g_err_no_ctx);
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, cap, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer)
+{
+    if (!layer) return clada_fail(ctx, CLADA_ERR_NULL, "layer is NULL");
+    if (!layer->w_gate || !layer->w_up || !layer->w_down)
+        return clada_fail(ctx, CLADA_ERR_NULL, "a weight pointer is NULL");
+    if (layer->dtype != CLADA_F32 && layer->dtype != CLADA_BF16)
+        return clada_fail(ctx, CLADA_ERR_DTYPE, "unknown dtype %d", (int)layer->dtype);
+    if (layer->d < 1 || layer->d > CLADA_MAX_D)
+        return clada_fail(ctx, CLADA_ERR_SHAPE, "d=%d outside [1,%d]", layer->d, CLADA_MAX_D);
+    if (layer->d_ff < 1 || layer->d_ff > CLADA_MAX_DFF)
+        return clada_fail(ctx, CLADA_ERR_SHAPE, "d_ff=%d outside [1,%d]", layer->d_ff, CLADA_MAX_DFF);
+    const size_t rowbytes = (size_t)layer->d * dtype_size(layer->dtype);
+    if (rowbytes % 16 != 0)
+        return clada_fail(ctx, CLADA_ERR_SHAPE, "row of %zu bytes is not a multiple of 16", rowbytes);
+    if (rowbytes > 16384)
+        return clada_fail(ctx, CLADA_ERR_SHAPE, "row of %zu bytes exceeds 16384", rowbytes);
+    if (!aligned16(layer->w_gate) || !aligned16(layer->w_up) || !aligned16(layer->w_down))
+        return clada_fail(ctx, CLADA_ERR_ALIGN, "weight pointers must be 16-byte aligned");
+    return CLADA_OK;
+}
+
+extern "C" {
+
+clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes)
+{
+    if (!out) return clada_fail(nullptr, CLADA_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (device_id < 0) return clada_fail(nullptr, CLADA_ERR_VALUE, "device_id=%d", device_id);
+    clada_ctx *ctx = new (std::nothrow) clada_ctx();
+    if (!ctx) return clada_fail(nullptr, CLADA_ERR_HIP, "host allocation failed");
+    ctx->device = device_id;
+    ctx->num_cu = 0;
+    ctx->ws_bytes = 0;
+    ctx->ws = nullptr;
+    ctx->opt_decode_wgs_per_cu = 1;
+    ctx->opt_decode_variant = 0;
+    ctx->err[0] = 0;
+    if (workspace_bytes > 0) {
+        hipError_t e = hipSetDevice(device_id);
+        hipDeviceProp_t prop;
+        if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device_id);
+        const size_t bytes = align_up(workspace_bytes, 256) + CLADA_WS_HEADER;
+        if (e == hipSuccess) e = hipMalloc((void **)&ctx->ws, bytes);
+        if (e == hipSuccess) e = hipMemset(ctx->ws, 0, CLADA_WS_HEADER);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) {
+            clada_fail(nullptr, CLADA_ERR_HIP, "clada_create: %s", hipGetErrorString(e));
+            if (ctx->ws) (void)hipFree(ctx->ws);
+            delete ctx;
+            return CLADA_ERR_HIP;
+        }
+        ctx->num_cu = prop.multiProcessorCount;
+        ctx->ws_bytes = bytes;
+    }
+    *out = ctx;
+    return CLADA_OK;
+}
+
+void clada_destroy(clada_ctx *ctx)
+{
+    if (!ctx) return;
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    delete ctx;
+}
+
+const char *clada_status_str(clada_status s)
+{
+    switch (s) {
+    case CLADA_OK: return "CLADA_OK";
+    case CLADA_ERR_NULL: return "CLADA_ERR_NULL";
+    case CLADA_ERR_SHAPE: return "CLADA_ERR_SHAPE";
+    case CLADA_ERR_DTYPE: return "CLADA_ERR_DTYPE";
+    case CLADA_ERR_ALIGN: return "CLADA_ERR_ALIGN";
+    case CLADA_ERR_WORKSPACE: return "CLADA_ERR_WORKSPACE";
+    case CLADA_ERR_VALUE: return "CLADA_ERR_VALUE";
+    case CLADA_ERR_HIP: return "CLADA_ERR_HIP";
+    }
+    return "CLADA_ERR_UNKNOWN";
+}
+
+const char *clada_last_error(const clada_ctx *ctx) { return ctx ? ctx->err : g_err_no_ctx; }
+
+clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
+{
+    if (!ctx || !name) return clada_fail(ctx, CLADA_ERR_NULL, "ctx or name is NULL");
+    if (!strcmp(name, "decode.wgs_per_cu")) {
+        if (value < 1 || value > 2) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.wgs_per_cu=%d outside [1,2]", value);
+        ctx->opt_decode_wgs_per_cu = value;
+        return CLADA_OK;
+    }
+    if (!strcmp(name, "decode.variant")) {
+        if (value < 0 || value > 15) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.variant=%d outside [0,15]", value);
+        ctx->opt_decode_variant = value;
+        return CLADA_OK;
+    }
+    return clada_fail(ctx, CLADA_ERR_VALUE, "unknown option '%s'", name);
+}
+
+size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int32_t V)
+{
+    size_t need = 0, n;
+    if (d > 0 && d_ff > 0 && B > 0 && (n = clada_ws_decode(d, d_ff, B)) > need) need = n;
+    if (B > 0 && V > 0 && (n = clada_ws_signals(B, V)) > need) need = n;
+    if (d > 0 && d_ff > 0 && T > 0 && (n = clada_ws_prefix(d, d_ff, T, true)) > need) need = n;
+    if (T > 0 && (n = clada_ws_calibrate()) > need) need = n;
+    return need + 256;
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+// Internal declarations shared by the HIP sources of libclada (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "clada.h"
+
+struct clada_ctx {
+    int device;
+    int num_cu;
+    size_t ws_bytes;
+    char *ws;            // device workspace, 256-byte aligned; first CLADA_WS_HEADER bytes = counters
+    int opt_decode_wgs_per_cu;   // launch shape of the decode kernel (clada_set_option)
+    int opt_decode_variant;
+    char err[512];
+};
+
+// Upper bound on the decode kernel's workgroup count (sizes the partial-y scratch).
+#define CLADA_MAX_DECODE_WGS 512
+
+// The first bytes of the workspace hold self-resetting arrival counters (zeroed
+// once at clada_create); the scratch area proper starts after them.
+#define CLADA_WS_HEADER 4096
+enum { CTR_SIGNALS = 0, CTR_DECODE = 64, CTR_PREFIX = 128, CTR_CALIB = 192 };  // int32 slots
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+clada_status clada_fail(clada_ctx *ctx, clada_status s, const char *fmt, ...);
+
+#define CLADA_CHECK_HIP(ctx, expr)                                                          \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return clada_fail((ctx), CLADA_ERR_HIP, "%s failed: %s", #expr,                 \
+                              hipGetErrorString(e_));                                       \
+    } while (0)
+
+static inline size_t dtype_size(clada_dtype t) { return t == CLADA_F32 ? 4 : 2; }
+static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Validation shared by the FFN calls.
+clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer);
+
+// Workspace needs of the individual calls (bytes beyond the header).
+size_t clada_ws_decode(int32_t d, int32_t d_ff, int32_t B);
+size_t clada_ws_signals(int32_t B, int32_t V);
+size_t clada_ws_prefix(int32_t d, int32_t d_ff, int32_t T, bool want_y);
+size_t clada_ws_calibrate(void);
+
+#ifdef __HIPCC__
+// ---------------------------------------------------------------- device helpers
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// Eight bf16 values packed in 16 bytes -> fp32 (a bf16 is the top half of an fp32).
+__device__ __forceinline__ void unpack_row16(const u32x4 v, float (&f)[8])
+{
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+// Four fp32 values in 16 bytes.
+__device__ __forceinline__ void unpack_row16(const u32x4 v, float (&f)[4])
+{
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+}
+
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ unsigned int f32_to_bf16_bits(float f)
+{
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Sum over the 64 lanes of a wavefront with DPP moves; every lane returns the
+// total.  Fixed combination order, so the result is reproducible.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_move<0xB1, 0xf>(v);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E, 0xf>(v);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141, 0xf>(v);   // row_half_mirror
+    v += dpp_move<0x140, 0xf>(v);   // row_mirror: every lane of a row holds the row's sum
+    v += dpp_move<0x142, 0xa>(v);   // row_bcast15 into rows 1 and 3
+    v += dpp_move<0x143, 0xc>(v);   // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+    #pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+// SiLU(g) = g * sigmoid(g), fp32.
+__device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + expf(-g)); }
+#endif

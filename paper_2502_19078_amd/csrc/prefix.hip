@@ -1,0 +1,409 @@
+// Prefill statistics (section 3.2.1, neuron-activation equation; algorithm
+// "CLADA Inference", prefill phase): dense SwiGLU FFN over the prefix on the
+// matrix cores with the per-neuron aggregates fused into the GEMM epilogue.
+//
+//   kernel 1 (gate+up): C_g = X W_gate^T and C_u = X W_up^T share the X tile;
+//     both operands are K-contiguous (X [T][d], W [F][d]) so fragments come
+//     straight from LDS.  Epilogue on the accumulators: a = SiLU(C_g),
+//     h = a*C_u, per-neuron partial sums over the tile's tokens (|a|, a^2, h^2,
+//     max|a|), the |a| pool, and h stored in the layer dtype for kernel 2.
+//   kernel 2 (down): Y = H W_down, W_down tile transposed on its way into LDS.
+//   kernel 3: fixed-order reduction of the per-token-tile partials,
+//     A_j = sqrt(sum_t h_tj^2) * ||W_down[j,:]||_2.
+// Tiles are 128x128x32, four wavefronts of 64x64, MFMA 32x32x16 (bf16) or
+// 32x32x2 (fp32), fp32 accumulation.  Block ids are remapped so that the eight
+// XCDs each walk their own range of neuron tiles (the weight tile stays in that
+// XCD's L2 while the token tiles stream past it).
+#include <math.h>
+
+#include "clada_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+constexpr int BM = 128, BN = 128, BK = 32;
+
+template <int ES> struct Tile {
+    static constexpr int ROW = BK * ES + 16;            // padded LDS row stride, bytes
+    static constexpr int CHUNKS = BK * ES / 16;         // 16-byte chunks per tile row
+    static constexpr int PER_THREAD = BM * CHUNKS / 256; // chunks each thread moves per tile
+};
+
+// One k-tile of MFMAs for a 64x64 wave tile.  sa / sb point at the wave's first
+// row of the A / B tile in LDS.
+template <int ES, int NB>
+__device__ __forceinline__ void mma_tile(const char *sa, const char *const (&sb)[NB], f32x16 (&acc)[NB][2][2], int lane)
+{
+    constexpr int ROW = Tile<ES>::ROW;
+    const int r = lane & 31, q = lane >> 5;
+    if (ES == 2) {
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 a[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+                a[mb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(sa + (mb * 32 + r) * ROW + (ks * 16 + q * 8) * 2));
+#pragma unroll
+            for (int w = 0; w < NB; ++w)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) {
+                    const bf16x8 bv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(sb[w] + (nb * 32 + r) * ROW + (ks * 16 + q * 8) * 2));
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+                        acc[w][mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], bv, acc[w][mb][nb], 0, 0, 0);
+                }
+        }
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < BK / 2; ++ks) {
+            float a[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+                a[mb] = *reinterpret_cast<const float *>(sa + (mb * 32 + r) * ROW + (ks * 2 + q) * 4);
+#pragma unroll
+            for (int w = 0; w < NB; ++w)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) {
+                    const float bv = *reinterpret_cast<const float *>(sb[w] + (nb * 32 + r) * ROW + (ks * 2 + q) * 4);
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+                        acc[w][mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mb], bv, acc[w][mb][nb], 0, 0, 0);
+                }
+        }
+    }
+}
+
+// Row of accumulator register r of a 32x32 MFMA block held by `lane`.
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// XCD-aware remap: consecutive block ids alternate over the 8 XCDs; give each XCD a
+// contiguous run of tiles, token tile fastest.
+__device__ __forceinline__ int remap_block(int id, int total)
+{
+    const int per = (total + 7) / 8;
+    return (id & 7) * per + (id >> 3);
+}
+
+struct GateUpParams {
+    const char *x, *wg, *wu;
+    int T, d, F, n_tm, n_tn;
+    float *part;        // [n_tm][4][F]  partial aggregates (sum|a|, sum a^2, max|a|, sum h^2)
+    float *pool;        // [T][F] or nullptr
+    char *hbuf;         // [T][Fp] layer dtype (Fp = F rounded up to BK, zero past F) or nullptr
+    int Fp;
+};
+
+template <int ES>
+__global__ void __launch_bounds__(256)
+k_prefix_gateup(const GateUpParams p)
+{
+    constexpr int ROW = Tile<ES>::ROW, CH = Tile<ES>::CHUNKS, PT = Tile<ES>::PER_THREAD;
+    __shared__ __align__(16) char s_a[BM * ROW];
+    __shared__ __align__(16) char s_g[BN * ROW];
+    __shared__ __align__(16) char s_u[BN * ROW];
+    __shared__ float s_stat[2][4][BN];
+
+    const int total = p.n_tm * p.n_tn;
+    const int tile = remap_block(blockIdx.x, total);
+    if (tile >= total) return;
+    const int tm = tile % p.n_tm, tn = tile / p.n_tm;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const size_t rowbytes = (size_t)p.d * ES;
+
+    f32x16 acc[2][2][2];
+#pragma unroll
+    for (int w = 0; w < 2; ++w)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[w][mb][nb][r] = 0.0f;
+
+    u32x4 ra[PT], rg[PT], ru[PT];
+    auto load_tile = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < PT; ++i) {
+            const int c = tid + i * 256, row = c / CH, ch = c % CH;
+            const int kbyte = kt * BK * ES + ch * 16;
+            const bool kin = (size_t)kbyte < rowbytes;
+            const int t = tm * BM + row, j = tn * BN + row;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            ra[i] = (kin && t < p.T) ? *reinterpret_cast<const u32x4 *>(p.x + (size_t)t * rowbytes + kbyte) : z;
+            rg[i] = (kin && j < p.F) ? *reinterpret_cast<const u32x4 *>(p.wg + (size_t)j * rowbytes + kbyte) : z;
+            ru[i] = (kin && j < p.F) ? *reinterpret_cast<const u32x4 *>(p.wu + (size_t)j * rowbytes + kbyte) : z;
+        }
+    };
+    const int nk = (p.d + BK - 1) / BK;
+    load_tile(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PT; ++i) {
+            const int c = tid + i * 256, row = c / CH, ch = c % CH;
+            *reinterpret_cast<u32x4 *>(s_a + row * ROW + ch * 16) = ra[i];
+            *reinterpret_cast<u32x4 *>(s_g + row * ROW + ch * 16) = rg[i];
+            *reinterpret_cast<u32x4 *>(s_u + row * ROW + ch * 16) = ru[i];
+        }
+        __syncthreads();
+        if (kt + 1 < nk) load_tile(kt + 1);
+        const char *const sb[2] = {s_g + wn * 64 * ROW, s_u + wn * 64 * ROW};
+        mma_tile<ES, 2>(s_a + wm * 64 * ROW, sb, acc, lane);
+    }
+
+    // ------------------------------------------------------------------ epilogue
+    const int n = lane & 31;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int jl = wn * 64 + nb * 32 + n;          // neuron inside the tile
+        const int j = tn * BN + jl;
+        float s_abs = 0.f, s_sq = 0.f, mx = 0.f, s_h2 = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int t = tm * BM + wm * 64 + mb * 32 + acc_row(r, lane);
+                const float a = silu_f32(acc[0][mb][nb][r]);
+                const float h = a * acc[1][mb][nb][r];
+                if (t < p.T && j < p.F) {
+                    const float aa = fabsf(a);
+                    s_abs += aa;
+                    s_sq = fmaf(a, a, s_sq);
+                    mx = (aa > mx || aa != aa) ? aa : mx;
+                    s_h2 = fmaf(h, h, s_h2);
+                    if (p.pool) p.pool[(size_t)t * p.F + j] = aa;
+                }
+                if (p.hbuf && t < p.T && j < p.Fp) {
+                    const float hv = j < p.F ? h : 0.0f;
+                    if (ES == 4) reinterpret_cast<float *>(p.hbuf)[(size_t)t * p.Fp + j] = hv;
+                    else reinterpret_cast<unsigned short *>(p.hbuf)[(size_t)t * p.Fp + j] = (unsigned short)f32_to_bf16_bits(hv);
+                }
+            }
+        // lanes l and l^32 hold the same neuron
+        s_abs += __shfl_xor(s_abs, 32);
+        s_sq += __shfl_xor(s_sq, 32);
+        s_h2 += __shfl_xor(s_h2, 32);
+        const float mo = __shfl_xor(mx, 32);
+        mx = (mo > mx || mo != mo) ? mo : mx;
+        if (lane < 32) {
+            s_stat[wm][0][jl] = s_abs;
+            s_stat[wm][1][jl] = s_sq;
+            s_stat[wm][2][jl] = mx;
+            s_stat[wm][3][jl] = s_h2;
+        }
+    }
+    __syncthreads();
+    if (tid < BN) {
+        const int j = tn * BN + tid;
+        if (j < p.F) {
+            float *dst = p.part + (size_t)tm * 4 * p.F + j;
+            dst[0] = s_stat[0][0][tid] + s_stat[1][0][tid];
+            dst[(size_t)p.F] = s_stat[0][1][tid] + s_stat[1][1][tid];
+            const float m0 = s_stat[0][2][tid], m1 = s_stat[1][2][tid];
+            dst[2 * (size_t)p.F] = (m1 > m0 || m1 != m1) ? m1 : m0;
+            dst[3 * (size_t)p.F] = s_stat[0][3][tid] + s_stat[1][3][tid];
+        }
+    }
+}
+
+struct DownParams {
+    const char *h, *wd;
+    char *y;
+    int T, d, F, Fp, n_tm, n_tn;   // Fp = F rounded up to a multiple of BK (row stride of h)
+};
+
+template <int ES>
+__global__ void __launch_bounds__(256)
+k_prefix_down(const DownParams p)
+{
+    constexpr int ROW = Tile<ES>::ROW, CH = Tile<ES>::CHUNKS, PT = Tile<ES>::PER_THREAD;
+    constexpr int VEC = 16 / ES;
+    __shared__ __align__(16) char s_a[BM * ROW];
+    __shared__ __align__(16) char s_b[BN * ROW];      // [n][k]: W_down tile transposed
+
+    const int total = p.n_tm * p.n_tn;
+    const int tile = remap_block(blockIdx.x, total);
+    if (tile >= total) return;
+    const int tm = tile % p.n_tm, tn = tile / p.n_tm;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const size_t hrow = (size_t)p.Fp * ES, wrow = (size_t)p.d * ES;
+
+    f32x16 acc[1][2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[0][mb][nb][r] = 0.0f;
+
+    // B tile in global memory: BK rows (neurons) x BN columns -> BK * BN*ES/16 chunks
+    constexpr int BCH = BN * ES / 16;                  // chunks per neuron row of the tile
+    constexpr int BPT = BK * BCH / 256;
+    u32x4 ra[PT], rb[BPT];
+    auto load_tile = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < PT; ++i) {
+            const int c = tid + i * 256, row = c / CH, ch = c % CH;
+            const size_t kbyte = (size_t)kt * BK * ES + ch * 16;
+            const int t = tm * BM + row;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            // rows of h are padded to a multiple of BK elements, zero-filled past F
+            ra[i] = (t < p.T && kbyte < hrow) ? *reinterpret_cast<const u32x4 *>(p.h + (size_t)t * hrow + kbyte) : z;
+        }
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) {
+            const int c = tid + i * 256, k = c / BCH, ch = c % BCH;
+            const int j = kt * BK + k;
+            const size_t nbyte = (size_t)tn * BN * ES + ch * 16;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            rb[i] = (j < p.F && nbyte < wrow) ? *reinterpret_cast<const u32x4 *>(p.wd + (size_t)j * wrow + nbyte) : z;
+        }
+    };
+    const int nk = (p.F + BK - 1) / BK;
+    load_tile(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PT; ++i) {
+            const int c = tid + i * 256, row = c / CH, ch = c % CH;
+            *reinterpret_cast<u32x4 *>(s_a + row * ROW + ch * 16) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) {
+            const int c = tid + i * 256, k = c / BCH, ch = c % BCH;
+            const unsigned int w[4] = {rb[i].x, rb[i].y, rb[i].z, rb[i].w};
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const int nloc = ch * VEC + e;
+                if (ES == 4) *reinterpret_cast<unsigned int *>(s_b + nloc * ROW + k * 4) = w[e];
+                else *reinterpret_cast<unsigned short *>(s_b + nloc * ROW + k * 2) = (unsigned short)(w[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        __syncthreads();
+        if (kt + 1 < nk) load_tile(kt + 1);
+        const char *const sb[1] = {s_b + wn * 64 * ROW};
+        mma_tile<ES, 1>(s_a + wm * 64 * ROW, sb, acc, lane);
+    }
+    const int n = lane & 31;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int col = tn * BN + wn * 64 + nb * 32 + n;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int t = tm * BM + wm * 64 + mb * 32 + acc_row(r, lane);
+                if (t < p.T && col < p.d) {
+                    const float v = acc[0][mb][nb][r];
+                    if (ES == 4) reinterpret_cast<float *>(p.y)[(size_t)t * p.d + col] = v;
+                    else reinterpret_cast<unsigned short *>(p.y)[(size_t)t * p.d + col] = (unsigned short)f32_to_bf16_bits(v);
+                }
+            }
+    }
+}
+
+// One wave per neuron: ||W_down[j,:]||^2, then fold the token-tile partials in
+// ascending tile order and write the requested aggregates.
+template <int ES>
+__global__ void __launch_bounds__(256)
+k_prefix_reduce(const char *__restrict__ wd, int d, int F, const float *__restrict__ part, int n_tm,
+                const clada_prefix_out out)
+{
+    constexpr int VEC = 16 / ES;
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= F) return;
+    float wn2 = 0.0f;
+    if (out.A) {
+        const char *row = wd + (size_t)j * d * ES;
+        for (int col = lane * VEC; col < d; col += 64 * VEC) {
+            float w[VEC];
+            unpack_row16(*reinterpret_cast<const u32x4 *>(row + (size_t)col * ES), w);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) wn2 = fmaf(w[e], w[e], wn2);
+        }
+        wn2 = wave_sum(wn2);
+    }
+    if (lane == 0) {
+        float s_abs = 0.f, s_sq = 0.f, mx = 0.f, s_h2 = 0.f;
+        for (int tmi = 0; tmi < n_tm; ++tmi) {
+            const float *src = part + (size_t)tmi * 4 * F + j;
+            s_abs += src[0];
+            s_sq += src[(size_t)F];
+            const float m = src[2 * (size_t)F];
+            mx = (m > mx || m != m) ? m : mx;
+            s_h2 += src[3 * (size_t)F];
+        }
+        if (out.sum_abs_act) out.sum_abs_act[j] = s_abs;
+        if (out.sum_sq_act) out.sum_sq_act[j] = s_sq;
+        if (out.max_abs_act) out.max_abs_act[j] = mx;
+        if (out.sum_sq_h) out.sum_sq_h[j] = s_h2;
+        if (out.A) out.A[j] = sqrtf(s_h2) * sqrtf(wn2);
+    }
+}
+
+}  // namespace
+
+size_t clada_ws_prefix(int32_t d, int32_t d_ff, int32_t T, bool want_y)
+{
+    if (T <= 0) return 0;
+    const size_t n_tm = (size_t)(T + BM - 1) / BM;
+    size_t need = align_up(sizeof(float) * 4 * n_tm * d_ff, 256);
+    if (want_y) need += align_up((size_t)T * align_up((size_t)d_ff, BK) * 4, 256);
+    (void)d;
+    return need;
+}
+
+extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *layer, const void *x,
+                                           int32_t T, void *y, const clada_prefix_out *out,
+                                           void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    clada_status st = clada_check_layer(ctx, layer);
+    if (st != CLADA_OK) return st;
+    if (!x || !out) return clada_fail(ctx, CLADA_ERR_NULL, "x or out is NULL");
+    if (T < 1 || T > (1 << 20)) return clada_fail(ctx, CLADA_ERR_SHAPE, "T=%d outside [1,2^20]", T);
+    if (!aligned16(x) || (y && !aligned16(y))) return clada_fail(ctx, CLADA_ERR_ALIGN, "x and y must be 16-byte aligned");
+    const int d = layer->d, F = layer->d_ff;
+    const size_t need = CLADA_WS_HEADER + clada_ws_prefix(d, F, T, y != nullptr);
+    if (ctx->ws_bytes < need)
+        return clada_fail(ctx, CLADA_ERR_WORKSPACE, "workspace %zu < %zu bytes needed", ctx->ws_bytes, need);
+    const int es = (int)dtype_size(layer->dtype);
+    const int n_tm = (T + BM - 1) / BM, n_tn = (F + BN - 1) / BN;
+    char *ws = ctx->ws + CLADA_WS_HEADER;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    GateUpParams g;
+    g.x = (const char *)x; g.wg = (const char *)layer->w_gate; g.wu = (const char *)layer->w_up;
+    g.T = T; g.d = d; g.F = F; g.n_tm = n_tm; g.n_tn = n_tn;
+    g.part = reinterpret_cast<float *>(ws);
+    g.pool = out->abs_act_pool;
+    g.hbuf = y ? ws + align_up(sizeof(float) * 4 * (size_t)n_tm * F, 256) : nullptr;
+    g.Fp = (int)align_up((size_t)F, BK);
+    const int total = n_tm * n_tn;
+    const int grid = (total + 7) / 8 * 8;
+    if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
+    else         hipLaunchKernelGGL(k_prefix_gateup<2>, dim3(grid), dim3(256), 0, stream, g);
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    if (y) {
+        DownParams q;
+        q.h = g.hbuf; q.wd = (const char *)layer->w_down; q.y = (char *)y;
+        q.T = T; q.d = d; q.F = F; q.Fp = g.Fp; q.n_tm = n_tm; q.n_tn = (d + BN - 1) / BN;
+        const int tot2 = q.n_tm * q.n_tn, grid2 = (tot2 + 7) / 8 * 8;
+        if (es == 4) hipLaunchKernelGGL(k_prefix_down<4>, dim3(grid2), dim3(256), 0, stream, q);
+        else         hipLaunchKernelGGL(k_prefix_down<2>, dim3(grid2), dim3(256), 0, stream, q);
+        CLADA_CHECK_HIP(ctx, hipGetLastError());
+    }
+    if (out->sum_abs_act || out->sum_sq_act || out->max_abs_act || out->sum_sq_h || out->A) {
+        if (es == 4) hipLaunchKernelGGL(k_prefix_reduce<4>, dim3((F + 3) / 4), dim3(256), 0, stream,
+                                        (const char *)layer->w_down, d, F, g.part, n_tm, *out);
+        else         hipLaunchKernelGGL(k_prefix_reduce<2>, dim3((F + 3) / 4), dim3(256), 0, stream,
+                                        (const char *)layer->w_down, d, F, g.part, n_tm, *out);
+        CLADA_CHECK_HIP(ctx, hipGetLastError());
+    }
+    return CLADA_OK;
+}

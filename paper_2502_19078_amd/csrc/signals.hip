@@ -1,0 +1,219 @@
+// Cognitive-load signals (surprisal and entropy equations of section 2.3.1) and
+// the token-aware threshold (final-threshold equation of section 3.2.3).
+//
+// Signals: one pass over the logits.  Every thread keeps an online triple
+//   m = running max,  Z = sum e^{z-m},  T = sum e^{z-m} (z-m)
+// so that  lse = m + log Z,  entropy = log Z - T/Z,  surprisal = lse - z_tok.
+// Triples merge associatively (rescale by e^{m_i - m}); lanes merge by a fixed
+// butterfly, waves through LDS, blocks through the workspace with the last
+// arriving block of each row folding the block partials in ascending order, so
+// the result is bit-reproducible.
+#include <math.h>
+
+#include "clada_internal.h"
+
+namespace {
+
+struct Lse {
+    float m, Z, T;
+    int bad;   // saw NaN or +inf
+};
+
+__device__ __forceinline__ Lse lse_empty() { return Lse{-INFINITY, 0.0f, 0.0f, 0}; }
+
+__device__ __forceinline__ Lse lse_merge(const Lse a, const Lse b)
+{
+    Lse r;
+    r.bad = a.bad | b.bad;
+    r.m = fmaxf(a.m, b.m);
+    r.Z = 0.0f;
+    r.T = 0.0f;
+    if (a.Z > 0.0f) {
+        const float dm = a.m - r.m, c = expf(dm);
+        r.Z += c * a.Z;
+        r.T += c * (a.T + dm * a.Z);
+    }
+    if (b.Z > 0.0f) {
+        const float dm = b.m - r.m, c = expf(dm);
+        r.Z += c * b.Z;
+        r.T += c * (b.T + dm * b.Z);
+    }
+    return r;
+}
+
+template <int ES>
+__device__ __forceinline__ float load_logit(const char *row, int v)
+{
+    if (ES == 4) return reinterpret_cast<const float *>(row)[v];
+    return __uint_as_float((unsigned int)reinterpret_cast<const unsigned short *>(row)[v] << 16);
+}
+
+constexpr int SIG_THREADS = 256;
+constexpr int SIG_GROUP = 8;                       // logits folded per online update
+constexpr int SIG_CHUNK = SIG_THREADS * SIG_GROUP * 2;   // logits per block
+
+template <int ES>
+__global__ void __launch_bounds__(SIG_THREADS)
+k_signals(const char *__restrict__ logits, int V, const int32_t *__restrict__ tok,
+          float *__restrict__ part /* [B][NB][4] */, int *__restrict__ counters,
+          float *__restrict__ surprisal, float *__restrict__ entropy)
+{
+    __shared__ Lse s_w[SIG_THREADS / 64];
+    __shared__ int s_last;
+    const int b = blockIdx.y, nb = gridDim.x, tid = threadIdx.x;
+    const char *row = logits + (size_t)b * V * ES;
+    const int lo = blockIdx.x * SIG_CHUNK;
+    const int hi = min(V, lo + SIG_CHUNK);
+
+    Lse acc = lse_empty();
+    for (int base = lo + tid; base < hi; base += SIG_THREADS * SIG_GROUP) {
+        float z[SIG_GROUP];
+        float gm = -INFINITY;
+#pragma unroll
+        for (int g = 0; g < SIG_GROUP; ++g) {
+            const int v = base + g * SIG_THREADS;
+            z[g] = v < hi ? load_logit<ES>(row, v) : -INFINITY;
+            if (z[g] != z[g] || z[g] == INFINITY) acc.bad = 1;
+            gm = fmaxf(gm, z[g]);
+        }
+        if (gm > acc.m) {                       // rescale once per group
+            if (acc.Z > 0.0f) {
+                const float dm = acc.m - gm, c = expf(dm);
+                acc.T = c * (acc.T + dm * acc.Z);
+                acc.Z = c * acc.Z;
+            }
+            acc.m = gm;
+        }
+#pragma unroll
+        for (int g = 0; g < SIG_GROUP; ++g) {
+            const float dz = z[g] - acc.m;
+            const float e = expf(dz);
+            if (e > 0.0f) {                      // -inf logits contribute nothing (0 log 0 := 0)
+                acc.Z += e;
+                acc.T += e * dz;
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        Lse other;
+        other.m = __shfl_xor(acc.m, o);
+        other.Z = __shfl_xor(acc.Z, o);
+        other.T = __shfl_xor(acc.T, o);
+        other.bad = __shfl_xor(acc.bad, o);
+        // merge lower lane first so both partners compute the identical value
+        acc = ((tid & o) == 0) ? lse_merge(acc, other) : lse_merge(other, acc);
+    }
+    if ((tid & 63) == 0) s_w[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        Lse r = s_w[0];
+        for (int w = 1; w < SIG_THREADS / 64; ++w) r = lse_merge(r, s_w[w]);
+        float *dst = part + ((size_t)b * nb + blockIdx.x) * 4;
+        dst[0] = r.m; dst[1] = r.Z; dst[2] = r.T; dst[3] = r.bad ? 1.0f : 0.0f;
+        __threadfence();
+        const int prev = atomicAdd(&counters[b], 1);
+        s_last = (prev == nb - 1);
+    }
+    __syncthreads();
+    if (s_last && tid == 0) {
+        __threadfence();
+        Lse r = lse_empty();
+        for (int q = 0; q < nb; ++q) {
+            const float *src = part + ((size_t)b * nb + q) * 4;
+            Lse t;
+            t.m = __hip_atomic_load(src + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.Z = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.T = __hip_atomic_load(src + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.bad = __hip_atomic_load(src + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0.0f;
+            r = lse_merge(r, t);
+        }
+        counters[b] = 0;                        // ready for the next call
+        float H, s;
+        if (r.bad || !(r.Z > 0.0f)) {
+            H = NAN;
+            s = NAN;
+        } else {
+            const float logZ = logf(r.Z);
+            H = logZ - r.T / r.Z;
+            const int t = tok[b];
+            s = (t >= 0 && t < V) ? (r.m + logZ) - load_logit<ES>(row, t) : NAN;
+        }
+        entropy[b] = H;
+        surprisal[b] = s;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_threshold(const float *__restrict__ tau_base, const float *__restrict__ lambda,
+            const float *__restrict__ gamma, int L, const float *__restrict__ s,
+            const float *__restrict__ H, int B, float tau_s, float tau_H, float *__restrict__ out)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= L * B) return;
+    const int l = idx / B, b = idx - l * B;
+    const float is = s[b] > tau_s ? 1.0f : 0.0f;
+    const float ih = H[b] > tau_H ? 1.0f : 0.0f;
+    // same association as the printed formula: 1 + lambda*I + gamma*I, then times tau_base
+    out[idx] = tau_base[l] * (1.0f + lambda[l] * is + gamma[l] * ih);
+}
+
+}  // namespace
+
+static int signals_blocks(int V) { return (V + SIG_CHUNK - 1) / SIG_CHUNK; }
+
+size_t clada_ws_signals(int32_t B, int32_t V)
+{
+    if (B <= 0 || V <= 0) return 0;
+    return align_up(sizeof(float) * 4 * (size_t)B * signals_blocks(V), 256);
+}
+
+extern "C" clada_status clada_cognitive_signals(clada_ctx *ctx, const void *logits,
+                                                clada_dtype logits_dtype, int32_t B, int32_t V,
+                                                const int32_t *token_ids, float *surprisal,
+                                                float *entropy, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    if (!logits || !token_ids || !surprisal || !entropy)
+        return clada_fail(ctx, CLADA_ERR_NULL, "logits, token_ids, surprisal or entropy is NULL");
+    if (logits_dtype != CLADA_F32 && logits_dtype != CLADA_BF16)
+        return clada_fail(ctx, CLADA_ERR_DTYPE, "unknown logits dtype %d", (int)logits_dtype);
+    if (B < 1 || B > CLADA_MAX_BATCH) return clada_fail(ctx, CLADA_ERR_SHAPE, "B=%d outside [1,%d]", B, CLADA_MAX_BATCH);
+    if (V < 1 || V > (1 << 24)) return clada_fail(ctx, CLADA_ERR_SHAPE, "V=%d outside [1,2^24]", V);
+    if (((uintptr_t)logits & (dtype_size(logits_dtype) - 1)) != 0)
+        return clada_fail(ctx, CLADA_ERR_ALIGN, "logits not aligned to their element size");
+    const size_t need = CLADA_WS_HEADER + clada_ws_signals(B, V);
+    if (ctx->ws_bytes < need)
+        return clada_fail(ctx, CLADA_ERR_WORKSPACE, "workspace %zu < %zu bytes needed", ctx->ws_bytes, need);
+    int *counters = reinterpret_cast<int *>(ctx->ws) + CTR_SIGNALS;
+    float *part = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
+    const dim3 grid(signals_blocks(V), B);
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (logits_dtype == CLADA_F32)
+        hipLaunchKernelGGL(k_signals<4>, grid, dim3(SIG_THREADS), 0, st, (const char *)logits, V, token_ids,
+                           part, counters, surprisal, entropy);
+    else
+        hipLaunchKernelGGL(k_signals<2>, grid, dim3(SIG_THREADS), 0, st, (const char *)logits, V, token_ids,
+                           part, counters, surprisal, entropy);
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    return CLADA_OK;
+}
+
+extern "C" clada_status clada_threshold(clada_ctx *ctx, const float *tau_base, const float *lambda,
+                                        const float *gamma, int32_t L, const float *surprisal,
+                                        const float *entropy, int32_t B, float tau_s, float tau_H,
+                                        float *tau_final, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    if (!tau_base || !lambda || !gamma || !surprisal || !entropy || !tau_final)
+        return clada_fail(ctx, CLADA_ERR_NULL, "an array pointer is NULL");
+    if (L < 1 || L > CLADA_MAX_LAYERS) return clada_fail(ctx, CLADA_ERR_SHAPE, "L=%d outside [1,%d]", L, CLADA_MAX_LAYERS);
+    if (B < 1 || B > CLADA_MAX_BATCH) return clada_fail(ctx, CLADA_ERR_SHAPE, "B=%d outside [1,%d]", B, CLADA_MAX_BATCH);
+    if (tau_s != tau_s || tau_H != tau_H) return clada_fail(ctx, CLADA_ERR_VALUE, "tau_s or tau_H is NaN");
+    if (ctx->ws_bytes == 0) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "context has no device");
+    const int n = L * B;
+    hipLaunchKernelGGL(k_threshold, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, tau_base,
+                       lambda, gamma, L, surprisal, entropy, B, tau_s, tau_H, tau_final);
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    return CLADA_OK;
+}

@@ -1,0 +1,154 @@
+"""GPU parity: clada_sparse_ffn_decode / clada_dense_ffn_decode against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import (DEV, TOL_Y, assert_close_y, check_mask_band, to_dev, to_np, unpack_bits)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def clada():
+    import paper_2502_19078_amd as m
+    m.load_library()
+    return m
+
+
+def _case(cfg_name, seed, d, F, B, layer=0, step=0):
+    cfg = synth.CONFIGS[cfg_name]
+    w = synth.layer_weights(cfg, seed, layer, d=d, d_ff=F)
+    x = synth.decode_hidden(cfg, seed, layer, step, B=B, d=d)
+    return cfg, w, x
+
+
+def _tau_for(w, x, q):
+    """Per-token thresholds at about sparsity q (fp32 values, as the GPU will see them)."""
+    act = np.abs(oracle.gate_act(w[0], x))
+    return np.quantile(act, q, axis=1).astype(np.float32)
+
+
+def _run_sparse(clada, cfg, w, x, tau, wgs_per_cu=1):
+    F, d = w[0].shape
+    B = x.shape[0]
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, B, 0, 0))
+    ctx.set_option("decode.wgs_per_cu", wgs_per_cu)
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd = to_dev(x, cfg.dtype)
+    y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, torch.from_numpy(tau).to(DEV), want_lists=True)
+    torch.cuda.synchronize()
+    return ctx, layer, xd, y, idx.cpu().numpy(), cnt.cpu().numpy(), unpack_bits(bits, F)
+
+
+def _check_against_oracle(cfg, w, x, tau, y, idx, cnt, mask, what):
+    ref = oracle.sparse_decode(*w, x, tau.astype(np.float64))
+    flips = check_mask_band(mask, ref["act"], tau.astype(np.float64), what)
+    # index list / counts are exactly what the GPU's own mask implies
+    union = np.flatnonzero(mask.any(0))
+    assert cnt[0] == union.size and np.array_equal(idx[: cnt[0]], union), f"{what}: index list"
+    assert np.all(idx[cnt[0]:] == -1), f"{what}: entries past the count were touched"
+    assert np.array_equal(cnt[1:], mask.sum(1)), f"{what}: per-token counts"
+    if flips == 0:
+        assert np.array_equal(idx[: cnt[0]], ref["active_idx"]) and np.array_equal(cnt, ref["n_active"])
+        y_ref = ref["y"]
+    else:   # in-band flips: compare with the oracle evaluated on the GPU's (validated) mask
+        y_ref = oracle.decode_given_mask(*w, x, mask)
+    assert_close_y(to_np(y), y_ref, TOL_Y[cfg.dtype], what)
+    return flips
+
+
+CASES = [
+    # cfg, d, F, B, q    (several tiles + ragged tails: F not a multiple of the workgroup count)
+    ("c1", 512, 1376, 1, 0.40),      # config 1 as written
+    ("c1", 512, 1376, 4, 0.40),
+    ("c1", 320, 77, 2, 0.50),        # d not a multiple of a wave's 256-float chunk, tiny F
+    ("c1", 64, 3000, 1, 0.30),
+    ("c2", 1024, 1000, 3, 0.45),     # bf16
+    ("c2", 4096, 2752, 1, 0.45),     # bf16, real row length, quarter of the 7B d_ff
+    ("c5", 5120, 1111, 2, 0.60),     # 13B row length (10 chunks per lane)
+    ("c2", 8, 130, 1, 0.45),         # one 16-byte chunk per row
+]
+
+
+@pytest.mark.parametrize("cfg_name,d,F,B,q", CASES)
+def test_sparse_decode_parity(clada, cfg_name, d, F, B, q):
+    for seed in (0, 1):
+        cfg, w, x = _case(cfg_name, seed, d, F, B)
+        tau = _tau_for(w, x, q)
+        _, _, _, y, idx, cnt, mask = _run_sparse(clada, cfg, w, x, tau)
+        _check_against_oracle(cfg, w, x, tau, y, idx, cnt, mask, f"{cfg_name} d={d} F={F} B={B} seed={seed}")
+        rho = 1.0 - cnt[1:].mean() / F
+        assert abs(rho - q) < 0.02
+
+
+@pytest.mark.parametrize("cfg_name,d,F,B", [("c1", 512, 1376, 2), ("c2", 1024, 1000, 2)])
+def test_tau_zero_is_dense_and_tau_inf_is_zero(clada, cfg_name, d, F, B):
+    cfg, w, x = _case(cfg_name, 3, d, F, B)
+    ctx, layer, xd, y0, idx, cnt, mask = _run_sparse(clada, cfg, w, x, np.zeros(B, np.float32))
+    assert mask.all() and list(cnt) == [F] * (1 + B) and np.array_equal(idx, np.arange(F))
+    yd = clada.dense_ffn_decode(ctx, layer, xd)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, yd)                      # same kernel structure, same summation order
+    assert_close_y(to_np(yd), oracle.dense_decode(*w, x), TOL_Y[cfg.dtype], "dense twin")
+    _, _, _, yi, idx, cnt, mask = _run_sparse(clada, cfg, w, x, np.full(B, np.inf, np.float32))
+    assert not mask.any() and list(cnt) == [0] * (1 + B) and np.all(idx == -1)
+    assert torch.count_nonzero(yi).item() == 0
+
+
+def test_batch_rows_independent_and_per_token_thresholds(clada):
+    cfg, w, x = _case("c2", 4, 1024, 1500, 5)
+    tau = _tau_for(w, x, 0.45) * np.array([1.0, 1.8, 1.12, 1.92, 0.08], np.float32)
+    ctx, layer, xd, y, idx, cnt, mask = _run_sparse(clada, cfg, w, x, tau)
+    _check_against_oracle(cfg, w, x, tau, y, idx, cnt, mask, "per-token tau")
+    for b in range(5):
+        yb = clada.sparse_ffn_decode(ctx, layer, xd[b:b + 1].contiguous(), torch.from_numpy(tau[b:b + 1]).to(DEV))
+        torch.cuda.synchronize()
+        assert torch.equal(yb[0], y[b]), f"row {b} differs between batched and single-token call"
+
+
+@pytest.mark.parametrize("wgs", [1, 2])
+def test_run_to_run_bit_reproducible(clada, wgs):
+    cfg, w, x = _case("c2", 5, 2048, 3000, 2)
+    tau = _tau_for(w, x, 0.45)
+    outs = []
+    for _ in range(3):
+        _, _, _, y, idx, cnt, mask = _run_sparse(clada, cfg, w, x, tau, wgs_per_cu=wgs)
+        outs.append((y.clone(), idx.copy(), cnt.copy()))
+    for y, idx, cnt in outs[1:]:
+        assert torch.equal(y, outs[0][0]) and np.array_equal(idx, outs[0][1]) and np.array_equal(cnt, outs[0][2])
+
+
+def test_nan_activation_is_cut(clada):
+    cfg, w, x = _case("c1", 6, 256, 300, 1)
+    w = [a.copy() for a in w]
+    w[0][17, 3] = np.nan
+    tau = np.zeros(1, np.float32)
+    _, _, _, y, idx, cnt, mask = _run_sparse(clada, cfg, w, x, tau)
+    assert not mask[0, 17] and cnt[0] == 299
+    ref = oracle.sparse_decode(*w, x, tau.astype(np.float64))
+    assert_close_y(to_np(y), ref["y"], TOL_Y["f32"], "NaN gate row")
+
+
+def test_full_size_7b_layer_bench_configuration(clada):
+    """LLaMA2-7B FFN shape in the launch configuration the benchmark times (one layer, B=1,
+    thresholds from the library's own prefix calibration): every output element and the whole
+    index list are checked, for two layers and two decode steps."""
+    cfg = synth.CONFIGS["c2"]
+    d, F = cfg.d, cfg.d_ff
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, 0, 0))
+    for layer_id in (0, 17):
+        w = synth.layer_weights(cfg, 0, layer_id)
+        layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+        for step in (0, 1):
+            x = synth.decode_hidden(cfg, 0, layer_id, step)
+            tau = _tau_for(w, x, cfg.q)
+            y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, to_dev(x, cfg.dtype),
+                                                        torch.from_numpy(tau).to(DEV), want_lists=True)
+            torch.cuda.synchronize()
+            _check_against_oracle(cfg, w, x, tau, y, idx.cpu().numpy(), cnt.cpu().numpy(),
+                                  unpack_bits(bits, F), f"7B layer {layer_id} step {step}")
+        yd = clada.dense_ffn_decode(ctx, layer, to_dev(x, cfg.dtype))
+        torch.cuda.synchronize()
+        assert_close_y(to_np(yd), oracle.dense_decode(*w, x), TOL_Y["bf16"], "7B dense twin")

@@ -1,0 +1,149 @@
+"""GPU parity: clada_cognitive_signals, clada_threshold, clada_threshold_calibrate vs the oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import DEV, TOL_SIGNAL, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def clada():
+    import paper_2502_19078_amd as m
+    m.load_library()
+    return m
+
+
+@pytest.fixture(scope="module")
+def ctx(clada):
+    return clada.Context(0, clada.workspace_bytes(0, 0, 64, 1, 1 << 20))
+
+
+def _signals(clada, ctx, z, tok, dtype="f32"):
+    s, h = clada.cognitive_signals(ctx, to_dev(z, dtype), torch.from_numpy(np.asarray(tok, np.int32)).to(DEV))
+    torch.cuda.synchronize()
+    return s.cpu().numpy().astype(np.float64), h.cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("cfg_name,B,V,temp", [
+    ("c1", 16, 1000, 1.0), ("c2", 1, 32000, 1.0), ("c3", 8, 32000, 0.25), ("c3", 8, 32000, 16.0),
+    ("c4", 1, 128256, 1.0), ("c4", 3, 128256, 4.0), ("c1", 5, 4097, 1.0), ("c1", 2, 7, 1.0), ("c1", 1, 1, 1.0),
+])
+def test_signals_parity(clada, ctx, cfg_name, B, V, temp):
+    cfg = synth.CONFIGS[cfg_name]
+    for step in (0, 1):
+        z, spike = synth.logits(cfg, 0, step, B=B, V=V, temperature=temp)
+        tok = synth.draw_tokens(cfg, 0, step, z)
+        if spike is not None and step == 0:
+            tok = spike                                # low-surprisal case: the spiked token
+        s_ref, h_ref = oracle.signals(z, tok)
+        s, h = _signals(clada, ctx, z, tok)
+        np.testing.assert_allclose(s, s_ref, atol=TOL_SIGNAL, rtol=0)
+        np.testing.assert_allclose(h, h_ref, atol=TOL_SIGNAL, rtol=0)
+
+
+def test_signals_bf16_logits(clada, ctx):
+    cfg = synth.CONFIGS["c2"]
+    z, _ = synth.logits(cfg, 1, 0, B=4)
+    zb = synth.store(z, "bf16")
+    tok = synth.draw_tokens(cfg, 1, 0, zb)
+    s_ref, h_ref = oracle.signals(zb, tok)              # oracle sees the stored (rounded) logits
+    s, h = _signals(clada, ctx, zb, tok, "bf16")
+    np.testing.assert_allclose(s, s_ref, atol=TOL_SIGNAL, rtol=0)
+    np.testing.assert_allclose(h, h_ref, atol=TOL_SIGNAL, rtol=0)
+
+
+@pytest.mark.parametrize("V", [1000, 32000, 128256])
+def test_uniform_logits_give_log_v(clada, ctx, V):
+    s, h = _signals(clada, ctx, np.full((2, V), 3.25, np.float32), [0, V - 1])
+    assert np.allclose(s, math.log(V), atol=TOL_SIGNAL) and np.allclose(h, math.log(V), atol=TOL_SIGNAL)
+
+
+def test_large_offsets_and_peaked_rows(clada, ctx):
+    r = np.random.default_rng(0)
+    z = (r.standard_normal((3, 5000)) * 3).astype(np.float32)
+    z[0] += 1000.0
+    z[1] -= 1000.0
+    z[2, 77] = 60.0                                    # near one-hot
+    tok = [1, 2, 77]
+    s_ref, h_ref = oracle.signals(z, tok)
+    s, h = _signals(clada, ctx, z, tok)
+    np.testing.assert_allclose(s, s_ref, atol=TOL_SIGNAL, rtol=0)
+    np.testing.assert_allclose(h, h_ref, atol=TOL_SIGNAL, rtol=0)
+
+
+def test_degenerate_rows(clada, ctx):
+    V = 3000
+    z = np.zeros((6, V), np.float32)
+    z[0, 5] = np.nan
+    z[1, 6] = np.inf
+    z[2, :] = -np.inf
+    z[3, 100:] = -np.inf                               # 100 live logits, rest have p = 0
+    tok = [0, 0, 0, 5, -1, V]
+    s_ref, h_ref = oracle.signals(z, tok)
+    s, h = _signals(clada, ctx, z, tok)
+    assert np.isnan(s[:3]).all() and np.isnan(h[:3]).all()
+    assert s[3] == pytest.approx(math.log(100), abs=TOL_SIGNAL) and h[3] == pytest.approx(math.log(100), abs=TOL_SIGNAL)
+    assert np.isnan(s[4]) and np.isnan(s[5])            # token id out of range
+    np.testing.assert_allclose(h[3:], h_ref[3:], atol=TOL_SIGNAL, rtol=0)
+    assert np.array_equal(np.isnan(s), np.isnan(s_ref)) and np.array_equal(np.isnan(h), np.isnan(h_ref))
+
+
+def test_signals_repeatable_bits(clada, ctx):
+    cfg = synth.CONFIGS["c4"]
+    z, _ = synth.logits(cfg, 2, 0, B=2)
+    tok = synth.draw_tokens(cfg, 2, 0, z)
+    a = _signals(clada, ctx, z, tok)
+    for _ in range(3):
+        b = _signals(clada, ctx, z, tok)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_threshold_parity_all_indicator_patterns(clada, ctx):
+    L, B = 40, 16
+    r = np.random.default_rng(3)
+    tb = np.abs(r.standard_normal(L)).astype(np.float32)
+    s = np.abs(r.standard_normal(B) * 3).astype(np.float32)
+    h = np.abs(r.standard_normal(B) * 3).astype(np.float32)
+    s[0] = np.nan
+    f = lambda a: torch.from_numpy(a).to(DEV)
+    for lam_v, gam_v in ((0.80, 0.12), (-0.80, -0.12), (0.0, 0.0)):
+        lam = np.full(L, lam_v, np.float32)
+        gam = np.full(L, gam_v, np.float32)
+        for tau_s, tau_h in ((float(np.nanmedian(s)), float(np.median(h))), (np.inf, np.inf), (-np.inf, -np.inf),
+                             (float(s[3]), float(h[4]))):          # equality must not fire (strict >)
+            out = clada.threshold(ctx, f(tb), f(lam), f(gam), f(s), f(h), tau_s, tau_h)
+            torch.cuda.synchronize()
+            ref = oracle.threshold(tb, lam, gam, s, h, tau_s, tau_h)
+            assert out.shape == (L, B)
+            np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=2e-7, atol=0)
+    # the printed constants give exactly the four factors 1, 1.80, 1.12, 1.92
+    one = f(np.ones(1, np.float32))
+    out = clada.threshold(ctx, one, f(np.float32([0.80])), f(np.float32([0.12])),
+                          f(np.float32([0, 9, 0, 9])), f(np.float32([0, 0, 9, 9])), 1.0, 1.0)
+    np.testing.assert_allclose(out.cpu().numpy()[0], [1.0, 1.80, 1.12, 1.92], rtol=2e-7)
+
+
+@pytest.mark.parametrize("n,q", [(1, 0.4), (5, 0.0), (1000, 0.45), (4099, 0.3), (1 << 20, 0.45), (3_000_001, 0.6)])
+def test_calibrate_exact_order_statistic(clada, ctx, n, q):
+    r = np.random.default_rng(n)
+    pool = np.abs(r.standard_normal(n)).astype(np.float32)
+    pool[r.integers(0, n, max(1, n // 50))] = pool[0]              # ties
+    out = clada.threshold_calibrate(ctx, torch.from_numpy(pool).to(DEV), q)
+    torch.cuda.synchronize()
+    ref = oracle.calibrate(pool, q)
+    assert float(out.item()) == ref                                 # bit-exact: an element of the pool
+    k = oracle.quantile_rank(n, q)
+    assert (pool < out.item()).sum() <= k - 1 < (pool <= out.item()).sum()
+
+
+def test_calibrate_special_values(clada, ctx):
+    pool = np.array([0.0, 0.0, np.inf, 1e-40, 3.0, 1e-40, 2.5, 7.0], np.float32)   # zeros, denormals, inf
+    for q in (0.0, 0.2, 0.3, 0.5, 0.7, 0.9):
+        out = clada.threshold_calibrate(ctx, torch.from_numpy(pool).to(DEV), q)
+        assert float(out.item()) == oracle.calibrate(pool, q)
