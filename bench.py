@@ -1,0 +1,320 @@
+#!/usr/bin/env python3
+"""Benchmark of the CLADA sparse-FFN decode path on one MI355X.
+
+A "step" is one decode step of the whole hot path over the FFN stack of the
+configuration: cognitive signals from the previous step's logits -> per-layer
+token-aware thresholds -> L x thresholded sparse SwiGLU FFN (one call per layer),
+with all inputs resident in HBM.  The once-per-sequence prefill (prefix statistics
+on MFMA + base-threshold calibration) runs before the timed region and is reported
+separately.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debug)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (see DESIGN.md, sharding note)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2502_19078_amd as clada
+    import synth
+    from paper_2502_19078_amd import binding
+
+    clada.load_library()           # fail loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.config]
+    L = args.layers or cfg.L
+    d, F, B, T, V = cfg.d, cfg.d_ff, cfg.B, cfg.T, cfg.V
+    K, W = args.steps, args.warmup
+    nsteps = K + W
+    es = 2 if cfg.dtype == "bf16" else 4
+    tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    t_setup = time.time()
+
+    def to_dev(a):
+        if cfg.dtype == "bf16":
+            return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+
+    # ---------------------------------------------------------------- inputs (seeded, synthetic)
+    n_host = 0 if args.no_cpu_baseline else min(4, L)   # layers whose host copy the oracle leg keeps
+    host_w = {}
+
+    def make_layer(l):
+        w = synth.layer_weights(cfg, args.seed, l)
+        if l < n_host:
+            host_w[l] = w
+        return l, [synth.bf16_bits(a).view(np.int16) if cfg.dtype == "bf16" else a for a in w]
+
+    layers = [None] * L
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        for l, arrs in ex.map(make_layer, range(L)):
+            ts = [torch.from_numpy(a).to(dev) for a in arrs]
+            if cfg.dtype == "bf16":
+                ts = [t.view(torch.bfloat16) for t in ts]
+            layers[l] = clada.Layer(*ts)
+    x_host = np.stack([np.stack([synth.decode_hidden(cfg, args.seed, l, s) for l in range(L)]) for s in range(nsteps)])
+    x_all = to_dev(x_host.reshape(nsteps, L, B, d))                       # [step][layer][B][d]
+    z_host = np.stack([synth.logits(cfg, args.seed, s)[0] for s in range(nsteps)])   # [step][B][V]
+    tok_host = np.stack([synth.draw_tokens(cfg, args.seed, s, z_host[s]) for s in range(nsteps)])
+    z_all = torch.from_numpy(z_host).to(dev)
+    tok_all = torch.from_numpy(tok_host).to(dev)
+
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, B, T, V))
+    for opt in args.option:
+        k, v = opt.split("=")
+        ctx.set_option(k, int(v))
+
+    # ---------------------------------------------------------------- prefill: stats + calibration
+    tau_base = torch.empty(L, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for l in range(L):
+        Xp = to_dev(synth.prefix_hidden(cfg, args.seed, l))
+        st = clada.prefix_stats(ctx, layers[l], Xp, want_y=False, want_pool=True)
+        clada.threshold_calibrate(ctx, st.abs_act_pool, cfg.q, out=tau_base[l:l + 1])
+    torch.cuda.synchronize()
+    prefill_wall_ms = (time.time() - t0) * 1e3
+    # GPU-only prefill time of one layer (inputs resident)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    st = clada.prefix_stats(ctx, layers[L - 1], Xp, want_y=True, want_pool=True)
+    clada.threshold_calibrate(ctx, st.abs_act_pool, cfg.q, out=tau_base[L - 1:L])
+    e1.record()
+    torch.cuda.synchronize()
+    prefill_layer_ms = e0.elapsed_time(e1)
+    del st, Xp
+
+    lam = torch.full((L,), 0.80, dtype=torch.float32, device=dev)     # printed coefficients
+    gam = torch.full((L,), 0.12, dtype=torch.float32, device=dev)
+    # universal signal thresholds (not given in the paper): medians of this run's own signal
+    # streams, computed by the library over all steps before timing
+    s_all, h_all = [], []
+    for s in range(nsteps):
+        a, b = clada.cognitive_signals(ctx, z_all[s], tok_all[s])
+        s_all.append(a)
+        h_all.append(b)
+    tau_s = float(torch.stack(s_all).median().item())
+    tau_H = float(torch.stack(h_all).median().item())
+
+    # ---------------------------------------------------------------- one decode step
+    x_cur = torch.empty(L, B, d, dtype=tdtype, device=dev)
+    z_cur = torch.empty(B, V, dtype=torch.float32, device=dev)
+    tok_cur = torch.empty(B, dtype=torch.int32, device=dev)
+    sur = torch.empty(B, dtype=torch.float32, device=dev)
+    ent = torch.empty(B, dtype=torch.float32, device=dev)
+    tau_final = torch.empty(L, B, dtype=torch.float32, device=dev)
+    y_out = torch.empty(L, B, d, dtype=tdtype, device=dev)
+    lib, h = ctx._lib, ctx._h
+    import ctypes as C
+    cl = [l.c_struct() for l in layers]
+
+    def stream_ptr():
+        return C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+
+    def step_body(dense=False):
+        sp = stream_ptr()
+        ctx.check(lib.clada_cognitive_signals(h, z_cur.data_ptr(), binding.F32, B, V, tok_cur.data_ptr(),
+                                              sur.data_ptr(), ent.data_ptr(), sp))
+        ctx.check(lib.clada_threshold(h, tau_base.data_ptr(), lam.data_ptr(), gam.data_ptr(), L, sur.data_ptr(),
+                                      ent.data_ptr(), B, tau_s, tau_H, tau_final.data_ptr(), sp))
+        for l in range(L):
+            if dense:
+                ctx.check(lib.clada_dense_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
+                                                     y_out[l].data_ptr(), sp))
+            else:
+                ctx.check(lib.clada_sparse_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
+                                                      tau_final[l].data_ptr(), y_out[l].data_ptr(),
+                                                      None, None, None, sp))
+
+    def load_inputs(s):
+        x_cur.copy_(x_all[s], non_blocking=True)
+        z_cur.copy_(z_all[s], non_blocking=True)
+        tok_cur.copy_(tok_all[s], non_blocking=True)
+
+    graphs = {}
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        for dense in (False, True):
+            load_inputs(0)
+            with torch.cuda.stream(side):
+                step_body(dense)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                step_body(dense)
+            graphs[dense] = g
+        torch.cuda.synchronize()
+
+    def run_step(s, dense=False):
+        load_inputs(s)
+        if args.no_graph:
+            step_body(dense)
+        else:
+            graphs[dense].replay()
+
+    def timed(dense):
+        for s in range(W):
+            run_step(s, dense)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(W, W + K):
+            run_step(s, dense)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / K
+
+    ms_sparse = timed(False)
+    ms_dense = timed(True)
+
+    # ---------------------------------------------------------------- measured sparsity (untimed pass)
+    n_act = np.zeros((K, L), np.int64)
+    cnt = torch.empty(K, L, 1 + B, dtype=torch.int32, device=dev)
+    for i, s in enumerate(range(W, W + K)):
+        load_inputs(s)
+        sp = stream_ptr()
+        ctx.check(lib.clada_cognitive_signals(h, z_cur.data_ptr(), binding.F32, B, V, tok_cur.data_ptr(),
+                                              sur.data_ptr(), ent.data_ptr(), sp))
+        ctx.check(lib.clada_threshold(h, tau_base.data_ptr(), lam.data_ptr(), gam.data_ptr(), L, sur.data_ptr(),
+                                      ent.data_ptr(), B, tau_s, tau_H, tau_final.data_ptr(), sp))
+        for l in range(L):
+            ctx.check(lib.clada_sparse_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
+                                                  tau_final[l].data_ptr(), y_out[l].data_ptr(), None,
+                                                  cnt[i, l].data_ptr(), None, sp))
+    torch.cuda.synchronize()
+    cnt_np = cnt.cpu().numpy()
+    n_act = cnt_np[:, :, 0].astype(np.int64)                    # union count per (step, layer)
+    rho_union = 1.0 - n_act.mean() / F
+    rho_token = 1.0 - cnt_np[:, :, 1:].mean() / F
+    bytes_layer = (F + 2.0 * n_act.mean()) * d * es            # algorithmic bytes of one sparse layer call
+    bytes_dense = 3.0 * F * d * es
+
+    # ---------------------------------------------------------------- per-call duration with HIP events
+    # events on the launch stream around every per-layer call of the timed steps' inputs
+    nprobe = min(K, 8)
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+           for _ in range(nprobe)]
+    for i in range(nprobe):
+        load_inputs(W + i)
+        sp = stream_ptr()
+        ctx.check(lib.clada_cognitive_signals(h, z_cur.data_ptr(), binding.F32, B, V, tok_cur.data_ptr(),
+                                              sur.data_ptr(), ent.data_ptr(), sp))
+        ctx.check(lib.clada_threshold(h, tau_base.data_ptr(), lam.data_ptr(), gam.data_ptr(), L, sur.data_ptr(),
+                                      ent.data_ptr(), B, tau_s, tau_H, tau_final.data_ptr(), sp))
+        for l in range(L):
+            evs[i][l][0].record()
+            ctx.check(lib.clada_sparse_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
+                                                  tau_final[l].data_ptr(), y_out[l].data_ptr(),
+                                                  None, None, None, sp))
+            evs[i][l][1].record()
+    torch.cuda.synchronize()
+    call_us = float(np.mean([[a.elapsed_time(b) for a, b in row] for row in evs])) * 1e3
+    # lower bound of the same figure from the whole-step time (includes signals+threshold and gaps)
+    step_us_per_layer = ms_sparse * 1e3 / L
+
+    # stream-read ceiling on the same weights
+    def ceiling():
+        for l in range(min(L, 8)):
+            binding.diag_stream_read(ctx, layers[l].w_gate, 16)
+    ceiling()
+    torch.cuda.synchronize()
+    e0.record()
+    ceiling()
+    e1.record()
+    torch.cuda.synchronize()
+    ceil_gbs = min(L, 8) * F * d * es / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    achieved = bytes_layer / (call_us * 1e-6) / 1e9
+    out = {
+        "metric": "sparse-FFN decode tokens/s (7B shape, bs=1), HBM GB/s on bytes touched, speedup vs dense",
+        "value": round(B * 1e3 / ms_sparse, 2),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_sparse, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.config}: {cfg.name} FFN stack, L={L}, d={d}, d_ff={F}, {cfg.dtype}, "
+                               f"decode batch {B}, prefix {T}, V={V}, target sparsity {cfg.q}",
+                   "weights": f"N(0, std {cfg.w_std:g})", "hidden": "N(0,1)",
+                   "lambda": 0.80, "gamma": 0.12, "tau_s": round(tau_s, 4), "tau_H": round(tau_H, 4),
+                   "graph": not args.no_graph, "options": args.option},
+        "sparsity_per_token": round(float(rho_token), 4),
+        "sparsity_union": round(float(rho_union), 4),
+        "dense_ms_per_step": round(ms_dense, 4),
+        "speedup_vs_dense": round(ms_dense / ms_sparse, 4),
+        "ideal_speedup": round(3.0 / (3.0 - 2.0 * rho_union), 4),
+        "step_gbs_on_bytes_touched": round(bytes_layer * L / (ms_sparse * 1e-3) / 1e9, 1),
+        "dense_step_gbs": round(bytes_dense * L / (ms_dense * 1e-3) / 1e9, 1),
+        "stream_read_ceiling_gbs": round(ceil_gbs, 1),
+        "prefill": {"layer_ms_gpu": round(prefill_layer_ms, 3), "stack_wall_ms_incl_h2d": round(prefill_wall_ms, 1),
+                    "tflops_layer": round(6.0 * T * d * F / (prefill_layer_ms * 1e-3) / 1e12, 1)},
+        "roofline": {"bound": "hbm", "kernel": "clada_sparse_ffn_decode (per-layer call)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "bytes_per_launch": round(bytes_layer), "us_per_launch": round(call_us, 2),
+                     "us_per_layer_in_step": round(step_us_per_layer, 2),
+                     "traffic": _traffic()},
+        "setup_s": round(time.time() - t_setup, 1),
+    }
+
+    # ---------------------------------------------------------------- CPU baseline: the oracle itself
+    if not args.no_cpu_baseline:
+        import oracle
+        budget, t_used, n_done = 12.0, 0.0, 0
+        tf = tau_final.cpu().numpy().astype(np.float64)       # thresholds of the last step run
+        for s in range(W, W + K):
+            for l in range(n_host):
+                t0 = time.perf_counter()
+                oracle.sparse_decode(*host_w[l], x_host[s, l], tf[l])
+                t_used += time.perf_counter() - t0
+                n_done += 1
+            if t_used > budget:
+                break
+        per_layer = t_used / n_done
+        out["cpu_baseline"] = {"value": round(B / (per_layer * L), 3), "unit": "tokens/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"{n_done} layer-steps (layers 0..{n_host - 1}) of the same workload, "
+                                         f"{per_layer * 1e3:.1f} ms each, extrapolated linearly to L={L}"}
+    print(json.dumps(out))
+
+
+def _traffic():
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if present."""
+    p = os.path.join(ROOT, "profiles", "traffic_sparse_ffn_decode_c2.json")
+    try:
+        with open(p) as f:
+            return json.load(f).get("hbm_bytes_per_launch")
+    except Exception:
+        return None
+
+
+if __name__ == "__main__":
+    main()

@@ -298,6 +298,294 @@ k_ffn_lists(const unsigned char *__restrict__ keep, int B, int F, int32_t *__res
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Cooperative single-kernel path for decode batch 1 (the configuration the method is
+// timed on).  Same gate / compaction / up-down structure as k_ffn_decode, plus:
+//   * load balancing: a workgroup's kept count is binomial, so with a static neuron split
+//     the slowest workgroup would set the kernel time.  Each workgroup publishes its keep
+//     mask (<= 56 neurons -> one 64-bit word, tagged with the call's epoch) and its
+//     activations, processes its own first K0 kept neurons, then reads all P masks and
+//     takes its share of the pooled surplus so that every workgroup handles floor/ceil(k/P)
+//     neurons.  The assignment is a function of the masks only, so the summation order --
+//     and the result -- stays bit-reproducible.
+//   * the cross-workgroup reduction of the partial y's runs in the same kernel: after
+//     publishing its partial every workgroup waits for all P "done" tags and adds its own
+//     slice of columns over the partials in fixed order (no separate finalize launch).
+// All P workgroups must be co-resident (checked on the host: P <= CUs * occupancy).
+// Cross-workgroup data goes through agent-scope release stores / acquire loads.
+struct CoopParams {
+    const char *wg, *wu, *wd, *x;
+    const float *tau;
+    char *y;
+    unsigned long long *rec;    // [P] keep mask of the workgroup's neurons (bit i = neuron blk + P*i)
+    unsigned int *rec_tag;      // [P] epoch tag, stored (release) after the mask and activations
+    float *apub;                // [P][64] published activations a_i of the workgroup's neurons
+    float *partial;             // [P][d]
+    unsigned int *done;         // [P] epoch tag once partial[p] is complete
+    unsigned int *epoch;        // device-side call counter (survives graph replays)
+    unsigned int *fin;          // arrival counter of finished workgroups
+    unsigned char *keep;        // [F] or nullptr
+    int d, F, K0, CW;           // CW = columns each workgroup reduces (multiple of 4)
+};
+
+__device__ __forceinline__ int select_bit(unsigned long long m, int t)
+{   // index of the t-th set bit of m (t < popcount(m))
+    int i = 0;
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+        const int c = __popcll(m & ((1ull << s) - 1ull));
+        if (t >= c) { t -= c; m >>= s; i += s; }
+    }
+    return i;
+}
+
+__device__ __forceinline__ int block_excl_scan(int v, int tid, int *s_tmp, int nwaves, int *total)
+{   // exclusive prefix sum over the workgroup's threads (all threads must call)
+    const int lane = tid & 63, wave = tid >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) s_tmp[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int w = 0; w < nwaves; ++w) {
+        const int c = s_tmp[w];
+        if (w < wave) base += c;
+        tot += c;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+template <int ES, int NCH, int NW, bool DENSE>
+__global__ void __launch_bounds__(NW * 64)
+k_ffn_decode_coop(const CoopParams p)
+{
+    constexpr int VEC = 16 / ES;
+    constexpr int ROWB = NCH * 1024;                       // full rows only: d*ES == NCH*1024
+    __shared__ float s_a[64];
+    __shared__ int s_flag[64];
+    __shared__ int s_list[64];
+    __shared__ int s_l2row[64];
+    __shared__ float s_l2a[64];
+    __shared__ int s_tmp[NW];
+    __shared__ int s_misc[4];
+    extern __shared__ __align__(16) unsigned char smem_coop[];
+    float *s_red = reinterpret_cast<float *>(smem_coop);   // fold buffers, later the reduction staging
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int blk = blockIdx.x, P = gridDim.x;
+    const int F = p.F;
+    const int ni = blk < F ? (F - blk + P - 1) / P : 0;    // <= 56
+    unsigned int ep = *p.epoch + 1u;                        // this call's tag (0 is never used)
+    if (ep == 0u) ep = 1u;
+    const int loff = lane * 16;
+
+    float xr[NCH][VEC];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+        unpack_row16(*reinterpret_cast<const u32x4 *>(p.x + c * 1024 + loff), xr[c]);
+    const float tau = DENSE ? 0.0f : p.tau[0];
+
+    // ---------------------------------------------------------------- gate phase
+    for (int i = wave; i < ni; i += NW) {
+        const char *row = p.wg + (size_t)(blk + P * i) * ROWB + loff;
+        u32x4 buf[NCH];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) buf[c] = ld_stream16(row + c * 1024);
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            float w[VEC];
+            unpack_row16(buf[c], w);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s = fmaf(w[e], xr[c][e], s);
+        }
+        s = wave_sum(s);
+        const float a = silu_f32(s);
+        const bool keep = DENSE ? true : (fabsf(a) >= tau);
+        if (lane == 0) {
+            s_a[i] = a;
+            s_flag[i] = keep ? 1 : 0;
+            if (p.keep) p.keep[blk + P * i] = keep ? 1 : 0;
+        }
+    }
+    __syncthreads();
+
+    // every wave derives the same mask and list (no second barrier needed)
+    const unsigned long long mask = __ballot(lane < ni && s_flag[lane] != 0);
+    const int kp = __popcll(mask);
+    if ((mask >> lane) & 1ull) s_list[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
+    const int own = DENSE ? kp : min(kp, p.K0);
+    if (!DENSE && wave == 0) {                              // publish activations and mask, then the tag
+        if (lane < ni) p.apub[blk * 64 + lane] = s_a[lane];
+        if (lane == 0) {
+            p.rec[blk] = mask;
+            __hip_atomic_store(p.rec_tag + blk, ep, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+
+    float acc[NCH][VEC];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[c][e] = 0.0f;
+
+    auto updown = [&](int row_j, float a) {
+        const size_t off = (size_t)row_j * ROWB + loff;
+        u32x4 ub[NCH], db[NCH];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) ub[c] = ld_stream16(p.wu + off + c * 1024);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) db[c] = ld_stream16(p.wd + off + c * 1024);
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            float w[VEC];
+            unpack_row16(ub[c], w);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s = fmaf(w[e], xr[c][e], s);
+        }
+        const float h = a * wave_sum(s);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            float w[VEC];
+            unpack_row16(db[c], w);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[c][e] = fmaf(h, w[e], acc[c][e]);
+        }
+    };
+
+    // ------------------------------------------- own kept neurons (first `own` of the list)
+    for (int t = wave; t < own; t += NW) {
+        const int i = s_list[t];
+        updown(blk + P * i, s_a[i]);
+    }
+
+    // ------------------------------------------- share of the pooled surplus
+    int n2 = 0;
+    if (!DENSE) {
+        unsigned long long mq = 0ull;
+        if (tid < P) {
+            const unsigned int *r = p.rec_tag + tid;
+            while (__hip_atomic_load(r, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != ep) __builtin_amdgcn_s_sleep(2);
+            mq = __hip_atomic_load(p.rec + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const int kq = __popcll(mq);
+        const int oq = min(kq, p.K0), sq = kq - oq;
+        int K, S, Etot;
+        const int kpre = block_excl_scan(kq, tid, s_tmp, NW, &K);
+        const int spre = block_excl_scan(sq, tid, s_tmp, NW, &S);
+        // target count of workgroup q: floor((q+1)K/P) - floor(qK/P); extra beyond its own first rows
+        const int tgt = tid < P ? (int)(((long long)(tid + 1) * K) / P - ((long long)tid * K) / P) : 0;
+        const int eq = max(0, tgt - oq);
+        const int epre = block_excl_scan(eq, tid, s_tmp, NW, &Etot);
+        (void)kpre; (void)Etot;
+        if (tid == blk) {
+            s_misc[0] = min(epre, S);
+            s_misc[1] = min(epre + eq, S);
+        }
+        __syncthreads();
+        const int lo = s_misc[0], hi = s_misc[1];
+        n2 = hi - lo;
+        // thread q hands over the part of its surplus [spre, spre+sq) that falls into [lo, hi)
+        const int a0 = max(lo, spre), a1 = min(hi, spre + sq);
+        for (int r = a0; r < a1; ++r) {
+            const int i = select_bit(mq, oq + (r - spre));
+            s_l2row[r - lo] = tid + P * i;
+            s_l2a[r - lo] = __hip_atomic_load(p.apub + tid * 64 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        const int shift = own % NW;                         // wave that would take list entry `own`
+        for (int r = (wave - shift + NW) % NW; r < n2; r += NW) updown(s_l2row[r], s_l2a[r]);
+    }
+
+    // ------------------------------------ fixed-order fold of the waves' accumulators
+#pragma unroll
+    for (int s = NW / 2; s >= 1; s >>= 1) {
+        if (wave >= s && wave < 2 * s) {
+            float *dst = s_red + (size_t)(wave - s) * (NCH * 64 * VEC);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                for (int e = 0; e < VEC; e += 4)
+                    *reinterpret_cast<float4 *>(dst + (c * 64 + lane) * VEC + e) =
+                        make_float4(acc[c][e], acc[c][e + 1], acc[c][e + 2], acc[c][e + 3]);
+        }
+        __syncthreads();
+        if (wave < s) {
+            const float *src = s_red + (size_t)wave * (NCH * 64 * VEC);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+#pragma unroll
+                for (int e = 0; e < VEC; e += 4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(src + (c * 64 + lane) * VEC + e);
+                    acc[c][e] += v.x; acc[c][e + 1] += v.y; acc[c][e + 2] += v.z; acc[c][e + 3] += v.w;
+                }
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+        float *dst = p.partial + (size_t)blk * p.d;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int e = 0; e < VEC; e += 4)
+                *reinterpret_cast<float4 *>(dst + (c * 64 + lane) * VEC + e) =
+                    make_float4(acc[c][e], acc[c][e + 1], acc[c][e + 2], acc[c][e + 3]);
+        if (lane == 0) __hip_atomic_store(p.done + blk, ep, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // ------------------------------------ cross-workgroup reduction of this workgroup's columns
+    // s_red is free again: [P][CW] staging, then a two-level fixed-order sum over q.
+    const int CW = p.CW, c0 = blk * CW;
+    if (tid < P) {
+        const unsigned int *dn = p.done + tid;
+        while (__hip_atomic_load(dn, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != ep) __builtin_amdgcn_s_sleep(2);
+        for (int c = 0; c < CW; c += 4) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c0 + c < p.d) {
+                const float *src = p.partial + (size_t)tid * p.d + c0 + c;
+                v.x = __hip_atomic_load(src + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v.y = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v.z = __hip_atomic_load(src + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v.w = __hip_atomic_load(src + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            *reinterpret_cast<float4 *>(s_red + tid * CW + c) = v;
+        }
+    }
+    __syncthreads();
+    // level 1: thread (g, c) adds 16 consecutive q; level 2: thread c adds the 16 group sums
+    const int ngrp = (P + 15) / 16;
+    for (int idx = tid; idx < ngrp * CW; idx += NW * 64) {
+        const int g = idx / CW, c = idx - g * CW;
+        float sum = 0.0f;
+        const int q1 = min(P, g * 16 + 16);
+        for (int q = g * 16; q < q1; ++q) sum += s_red[q * CW + c];
+        s_red[P * CW + idx] = sum;
+    }
+    __syncthreads();
+    if (tid < CW && c0 + tid < p.d) {
+        float sum = 0.0f;
+        for (int g = 0; g < ngrp; ++g) sum += s_red[P * CW + g * CW + tid];
+        if (ES == 4) reinterpret_cast<float *>(p.y)[c0 + tid] = sum;
+        else reinterpret_cast<unsigned short *>(p.y)[c0 + tid] = (unsigned short)f32_to_bf16_bits(sum);
+    }
+    if (tid == 0) {
+        const unsigned int prev = atomicAdd(p.fin, 1u);
+        if (prev == (unsigned int)P - 1u) {                 // everyone has read the epoch long ago
+            *p.fin = 0u;
+            __hip_atomic_store(p.epoch, ep, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 template <int ES, int NCH, int NW, int GB, int UB>
 hipError_t launch_decode(const DecodeParams &p, int P, int B, bool dense, hipStream_t st)
 {
@@ -311,6 +599,30 @@ hipError_t launch_decode(const DecodeParams &p, int P, int B, bool dense, hipStr
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(P, B), dim3(NW * 64), lds, st, p);
+    return hipGetLastError();
+}
+
+// Cooperative launch; returns hipErrorNotSupported when the shape is not eligible.
+template <int ES, int NCH>
+hipError_t launch_coop(clada_ctx *ctx, const CoopParams &p, int P, bool dense, hipStream_t st)
+{
+    constexpr int NW = 8, VEC = 16 / ES;
+    const size_t fold = sizeof(float) * (size_t)(NW / 2) * NCH * 64 * VEC;
+    const size_t red = sizeof(float) * ((size_t)P * p.CW + (size_t)((P + 15) / 16) * p.CW);
+    const size_t lds = fold > red ? fold : red;
+    auto kern = dense ? k_ffn_decode_coop<ES, NCH, NW, true> : k_ffn_decode_coop<ES, NCH, NW, false>;
+    static int occ_cache[2] = {-1, -1};                    // per instantiation (template statics)
+    if (occ_cache[dense] < 0) {
+        hipError_t e = hipSuccess;
+        if (lds > 48 * 1024)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        int nb = 0;
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, NW * 64, lds);
+        if (e != hipSuccess) return e;
+        occ_cache[dense] = nb;
+    }
+    if ((long long)occ_cache[dense] * ctx->num_cu < P) return hipErrorNotSupported;   // not co-resident
+    hipLaunchKernelGGL(kern, dim3(P), dim3(NW * 64), lds, st, p);
     return hipGetLastError();
 }
 
@@ -345,14 +657,62 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
 
     const int nch = (d * es + 1023) / 1024;
     hipError_t e = hipErrorInvalidValue;
+
+    // ---- cooperative single-kernel path (decode batch 1, whole-KiB rows, <= 56 neurons per workgroup)
+    if (ctx->opt_decode_coop && B == 1 && (d * es) % 1024 == 0 && (nch == 2 || nch == 8 || nch == 10)) {
+        int Pc = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
+        if (Pc > F) Pc = F;
+        const int ni_c = (F + Pc - 1) / Pc;
+        const int CW = ((d + Pc - 1) / Pc + 3) / 4 * 4;
+        if (ni_c <= 56 && CW <= 32) {
+            CoopParams c;
+            c.wg = p.wg; c.wu = p.wu; c.wd = p.wd; c.x = p.x; c.tau = tau; c.y = (char *)y;
+            c.rec = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_REC);
+            c.rec_tag = reinterpret_cast<unsigned int *>(ctx->ws + COOP_REC_TAG);
+            c.apub = reinterpret_cast<float *>(ctx->ws + COOP_APUB);
+            c.partial = p.partial;
+            c.done = reinterpret_cast<unsigned int *>(ctx->ws + COOP_DONE);
+            c.epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
+            c.fin = reinterpret_cast<unsigned int *>(ctx->ws + COOP_FIN);
+            c.keep = p.keep;
+            c.d = d; c.F = F; c.CW = CW;
+            c.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : (ni_c / 6 > 1 ? ni_c / 6 : 1);
+            hipError_t ec = hipErrorNotSupported;
+            if (es == 2 && nch == 8) ec = launch_coop<2, 8>(ctx, c, Pc, dense, stream);
+            else if (es == 2 && nch == 10) ec = launch_coop<2, 10>(ctx, c, Pc, dense, stream);
+            else if (es == 2 && nch == 2) ec = launch_coop<2, 2>(ctx, c, Pc, dense, stream);
+            else if (es == 4 && nch == 2) ec = launch_coop<4, 2>(ctx, c, Pc, dense, stream);
+            else if (es == 4 && nch == 8) ec = launch_coop<4, 8>(ctx, c, Pc, dense, stream);
+            if (ec == hipSuccess) {
+                if (lists) {
+                    hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
+                    CLADA_CHECK_HIP(ctx, hipGetLastError());
+                }
+                return CLADA_OK;
+            }
+            if (ec != hipErrorNotSupported) CLADA_CHECK_HIP(ctx, ec);
+        }
+    }
 #define CLADA_DECODE_CASE(ES_, NCH_, NW_, GB_, UB_)                                        \
     if (es == ES_ && nch <= NCH_ && e == hipErrorInvalidValue)                             \
         e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, dense, stream);
+    if (es == 2 && nch == 8) {      // experimental launch shapes for the 4096-wide bf16 row
+        switch (ctx->opt_decode_variant) {
+        case 1: e = launch_decode<2, 8, 8, 1, 1>(p, P, B, dense, stream); break;
+        case 2: e = launch_decode<2, 8, 8, 3, 1>(p, P, B, dense, stream); break;
+        case 3: e = launch_decode<2, 8, 4, 4, 2>(p, P, B, dense, stream); break;
+        case 4: e = launch_decode<2, 8, 4, 6, 3>(p, P, B, dense, stream); break;
+        case 5: e = launch_decode<2, 8, 4, 3, 1>(p, P, B, dense, stream); break;
+        case 6: e = launch_decode<2, 8, 4, 2, 1>(p, P, B, dense, stream); break;
+        case 7: e = launch_decode<2, 8, 16, 1, 1>(p, P, B, dense, stream); break;
+        default: break;
+        }
+    }
     CLADA_DECODE_CASE(2, 1, 8, 2, 2)
     CLADA_DECODE_CASE(2, 2, 8, 2, 2)
     CLADA_DECODE_CASE(2, 4, 8, 2, 2)
     CLADA_DECODE_CASE(2, 8, 8, 2, 1)
-    CLADA_DECODE_CASE(2, 10, 8, 2, 1)
+    CLADA_DECODE_CASE(2, 10, 8, 1, 1)
     CLADA_DECODE_CASE(2, 16, 8, 1, 1)
     CLADA_DECODE_CASE(4, 1, 8, 2, 2)
     CLADA_DECODE_CASE(4, 2, 8, 2, 2)

@@ -152,3 +152,70 @@ def test_full_size_7b_layer_bench_configuration(clada):
         yd = clada.dense_ffn_decode(ctx, layer, to_dev(x, cfg.dtype))
         torch.cuda.synchronize()
         assert_close_y(to_np(yd), oracle.dense_decode(*w, x), TOL_Y["bf16"], "7B dense twin")
+
+
+def test_cooperative_and_generic_paths_agree(clada):
+    """Batch-1 calls take the single-kernel cooperative path; the generic multi-kernel path must
+    give the same mask and the same output up to fp32 summation order."""
+    for cfg_name, d, F in (("c2", 4096, 5000), ("c1", 512, 1376), ("c5", 5120, 13824)):
+        cfg, w, x = _case(cfg_name, 7, d, F, 1)
+        tau = _tau_for(w, x, 0.45)
+        ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, 0, 0))
+        layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+        xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
+        outs = {}
+        for coop in (1, 0):
+            ctx.set_option("decode.coop", coop)
+            y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, td, want_lists=True)
+            yd = clada.dense_ffn_decode(ctx, layer, xd)
+            torch.cuda.synchronize()
+            outs[coop] = (to_np(y), idx.cpu().numpy(), cnt.cpu().numpy(), to_np(yd))
+            _check_against_oracle(cfg, w, x, tau, y, idx.cpu().numpy(), cnt.cpu().numpy(), unpack_bits(bits, F),
+                                  f"{cfg_name} coop={coop}")
+        assert np.array_equal(outs[1][1], outs[0][1]) and np.array_equal(outs[1][2], outs[0][2])
+        assert_close_y(outs[1][0], outs[0][0], TOL_Y[cfg.dtype], "coop vs generic")
+        assert_close_y(outs[1][3], outs[0][3], TOL_Y[cfg.dtype], "dense coop vs generic")
+
+
+@pytest.mark.parametrize("own_first", [1, 3, 20, 56])
+def test_cooperative_balancing_any_own_first(clada, own_first):
+    """The surplus hand-over must be exact for every split between own and pooled neurons,
+    including very sparse and fully dense masks."""
+    cfg, w, x = _case("c2", 8, 4096, 11008, 1)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+    ctx.set_option("decode.own_first", own_first)
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd = to_dev(x, cfg.dtype)
+    for q in (0.0, 0.45, 0.9, 0.999):
+        tau = _tau_for(w, x, q) if q > 0 else np.zeros(1, np.float32)
+        y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, torch.from_numpy(tau).to(DEV), want_lists=True)
+        torch.cuda.synchronize()
+        _check_against_oracle(cfg, w, x, tau, y, idx.cpu().numpy(), cnt.cpu().numpy(), unpack_bits(bits, 11008),
+                              f"own_first={own_first} q={q}")
+
+
+def test_graph_replay_matches_eager(clada):
+    """The decode call reads its epoch from device memory, so a captured launch can be replayed;
+    every replay (with eager calls in between) must reproduce the eager bits."""
+    cfg, w, x = _case("c2", 9, 4096, 11008, 1)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd = to_dev(x, cfg.dtype)
+    td = torch.from_numpy(_tau_for(w, x, 0.45)).to(DEV)
+    y_eager = clada.sparse_ffn_decode(ctx, layer, xd, td).clone()
+    y_g = torch.empty_like(y_eager)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        clada.sparse_ffn_decode(ctx, layer, xd, td, y=y_g)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        clada.sparse_ffn_decode(ctx, layer, xd, td, y=y_g)
+    for _ in range(4):
+        y_g.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_g, y_eager)
+        y2 = clada.sparse_ffn_decode(ctx, layer, xd, td)          # eager call between replays
+        torch.cuda.synchronize()
+        assert torch.equal(y2, y_eager)
