@@ -209,26 +209,39 @@ k_ffn_decode(const DecodeParams p)
     }
 }
 
-// y[b][col] = sum_p partial[p][b][col], p ascending within each of 16 strided
-// slices, slices folded by a fixed tree; one rounding to the output dtype.
+// y[b][col] = sum_p partial[p][b][col].  A workgroup owns 32 columns; thread (slice, colgroup)
+// adds the partials p = slice, slice+32, ... (all loads issued together), the 32 slices are
+// folded by a fixed tree; one rounding to the output dtype.
 template <int ES>
 __global__ void __launch_bounds__(256)
-k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict__ y)
+k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict__ y, unsigned int *epoch)
 {
-    __shared__ float4 s_sum[16][16];
-    const int cg = threadIdx.x & 15, sl = threadIdx.x >> 4;
-    const int col = blockIdx.x * 64 + cg * 4;
+    if (epoch && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *epoch += 1u;   // cooperative call counter
+    __shared__ float4 s_sum[32][8];
+    const int cg = threadIdx.x & 7, sl = threadIdx.x >> 3;
+    const int col = blockIdx.x * 32 + cg * 4;
     const int b = blockIdx.y, B = gridDim.y;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (col < d)
-        for (int q = sl; q < P; q += 16) {
-            const float4 v = *reinterpret_cast<const float4 *>(partial + ((size_t)q * B + b) * d + col);
+    if (col < d) {
+        const float *base = partial + (size_t)b * d + col;
+        const size_t pstride = (size_t)B * d;
+        int q = sl;
+        for (; q + 7 * 32 < P; q += 8 * 32) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4 *>(base + (size_t)(q + u * 32) * pstride);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+        }
+        for (; q < P; q += 32) {
+            const float4 v = *reinterpret_cast<const float4 *>(base + (size_t)q * pstride);
             s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
         }
+    }
     s_sum[sl][cg] = s;
     __syncthreads();
 #pragma unroll
-    for (int h = 8; h >= 1; h >>= 1) {
+    for (int h = 16; h >= 1; h >>= 1) {
         if (sl < h) {
             const float4 v = s_sum[sl + h][cg];
             s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
@@ -246,6 +259,13 @@ k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict
             *reinterpret_cast<uint2 *>(y + ((size_t)b * d + col) * 2) = o;
         }
     }
+}
+
+void launch_finalize(int es, const float *partial, int P, int B, int d, char *y, unsigned int *epoch, hipStream_t stream)
+{
+    const dim3 grid((d + 31) / 32, B);
+    if (es == 4) hipLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, partial, P, d, y, epoch);
+    else         hipLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, partial, P, d, y, epoch);
 }
 
 // Ascending union index list, counts and per-token bit masks from the keep
@@ -318,15 +338,13 @@ struct CoopParams {
     const char *wg, *wu, *wd, *x;
     const float *tau;
     char *y;
-    unsigned long long *rec;    // [P] keep mask of the workgroup's neurons (bit i = neuron blk + P*i)
-    unsigned int *rec_tag;      // [P] epoch tag, stored (release) after the mask and activations
+    unsigned long long *rec;    // [P] keep mask of the workgroup's neurons (bit i = neuron blk + P*i,
+                                //     i < 56) | 8-bit epoch tag in bits 56..63, stored with release
     float *apub;                // [P][64] published activations a_i of the workgroup's neurons
     float *partial;             // [P][d]
-    unsigned int *done;         // [P] epoch tag once partial[p] is complete
-    unsigned int *epoch;        // device-side call counter (survives graph replays)
-    unsigned int *fin;          // arrival counter of finished workgroups
+    const unsigned int *epoch;  // device-side call counter (survives graph replays); advanced by k_ffn_finalize
     unsigned char *keep;        // [F] or nullptr
-    int d, F, K0, CW;           // CW = columns each workgroup reduces (multiple of 4)
+    int d, F, K0;
 };
 
 __device__ __forceinline__ int select_bit(unsigned long long m, int t)
@@ -372,7 +390,7 @@ k_ffn_decode_coop(const CoopParams p)
     __shared__ int s_flag[64];
     __shared__ int s_list[64];
     __shared__ int s_l2row[64];
-    __shared__ float s_l2a[64];
+    __shared__ int s_l2a[64];
     __shared__ int s_tmp[NW];
     __shared__ int s_misc[4];
     extern __shared__ __align__(16) unsigned char smem_coop[];
@@ -383,8 +401,10 @@ k_ffn_decode_coop(const CoopParams p)
     const int blk = blockIdx.x, P = gridDim.x;
     const int F = p.F;
     const int ni = blk < F ? (F - blk + P - 1) / P : 0;    // <= 56
-    unsigned int ep = *p.epoch + 1u;                        // this call's tag (0 is never used)
-    if (ep == 0u) ep = 1u;
+    // Every cooperative call (sparse or dense) rewrites all P records, so a stale record is
+    // exactly one call old and an 8-bit tag tells it apart.
+    const unsigned int ep = *p.epoch + 1u;
+    const unsigned long long tag = (unsigned long long)(ep & 0xffu) << 56;
     const int loff = lane * 16;
 
     float xr[NCH][VEC];
@@ -423,12 +443,14 @@ k_ffn_decode_coop(const CoopParams p)
     const int kp = __popcll(mask);
     if ((mask >> lane) & 1ull) s_list[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
     const int own = DENSE ? kp : min(kp, p.K0);
-    if (!DENSE && wave == 0) {                              // publish activations and mask, then the tag
-        if (lane < ni) p.apub[blk * 64 + lane] = s_a[lane];
-        if (lane == 0) {
-            p.rec[blk] = mask;
-            __hip_atomic_store(p.rec_tag + blk, ep, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        }
+    if (wave == 0) {
+        // Publish activations, then the tagged mask.  Both go out as agent-scope atomic stores
+        // (written through to memory), so ordering them needs only the wait for the first
+        // stores' acknowledgements (a workgroup-scope release fence), not an L2 write-back.
+        if (!DENSE && lane < ni)
+            __hip_atomic_store(p.apub + blk * 64 + lane, s_a[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (lane == 0) __hip_atomic_store(p.rec + blk, mask | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     float acc[NCH][VEC];
@@ -437,9 +459,11 @@ k_ffn_decode_coop(const CoopParams p)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[c][e] = 0.0f;
 
-    auto updown = [&](int row_j, float a) {
+    auto updown = [&](int row_j, float a, const float *a_pub) {
         const size_t off = (size_t)row_j * ROWB + loff;
         u32x4 ub[NCH], db[NCH];
+        // a borrowed neuron's activation travels with its weight rows (same round trip)
+        if (a_pub) a = __hip_atomic_load(a_pub, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int c = 0; c < NCH; ++c) ub[c] = ld_stream16(p.wu + off + c * 1024);
 #pragma unroll
@@ -465,28 +489,35 @@ k_ffn_decode_coop(const CoopParams p)
     // ------------------------------------------- own kept neurons (first `own` of the list)
     for (int t = wave; t < own; t += NW) {
         const int i = s_list[t];
-        updown(blk + P * i, s_a[i]);
+        updown(blk + P * i, s_a[i], nullptr);
     }
 
     // ------------------------------------------- share of the pooled surplus
     int n2 = 0;
     if (!DENSE) {
+        // thread q polls record q (relaxed loads that go to memory, spaced by s_sleep); all cross-
+        // workgroup reads below are agent-scope atomic loads, so no cache invalidation is needed
         unsigned long long mq = 0ull;
         if (tid < P) {
-            const unsigned int *r = p.rec_tag + tid;
-            while (__hip_atomic_load(r, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != ep) __builtin_amdgcn_s_sleep(2);
-            mq = __hip_atomic_load(p.rec + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (;;) {
+                mq = __hip_atomic_load(p.rec + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((mq & (0xffull << 56)) == tag) break;
+                __builtin_amdgcn_s_sleep(8);
+            }
+            mq &= ~(0xffull << 56);
         }
         const int kq = __popcll(mq);
         const int oq = min(kq, p.K0), sq = kq - oq;
-        int K, S, Etot;
-        const int kpre = block_excl_scan(kq, tid, s_tmp, NW, &K);
-        const int spre = block_excl_scan(sq, tid, s_tmp, NW, &S);
+        int K, S;
+        (void)block_excl_scan(kq, tid, s_tmp, NW, &K);
         // target count of workgroup q: floor((q+1)K/P) - floor(qK/P); extra beyond its own first rows
         const int tgt = tid < P ? (int)(((long long)(tid + 1) * K) / P - ((long long)tid * K) / P) : 0;
         const int eq = max(0, tgt - oq);
-        const int epre = block_excl_scan(eq, tid, s_tmp, NW, &Etot);
-        (void)kpre; (void)Etot;
+        // one scan for both prefixes: surplus counts in the low half, extras in the high half
+        int SE;
+        const int sepre = block_excl_scan(sq | (eq << 16), tid, s_tmp, NW, &SE);
+        const int spre = sepre & 0xffff, epre = sepre >> 16;
+        S = SE & 0xffff;
         if (tid == blk) {
             s_misc[0] = min(epre, S);
             s_misc[1] = min(epre + eq, S);
@@ -499,11 +530,11 @@ k_ffn_decode_coop(const CoopParams p)
         for (int r = a0; r < a1; ++r) {
             const int i = select_bit(mq, oq + (r - spre));
             s_l2row[r - lo] = tid + P * i;
-            s_l2a[r - lo] = __hip_atomic_load(p.apub + tid * 64 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_l2a[r - lo] = tid * 64 + i;
         }
         __syncthreads();
         const int shift = own % NW;                         // wave that would take list entry `own`
-        for (int r = (wave - shift + NW) % NW; r < n2; r += NW) updown(s_l2row[r], s_l2a[r]);
+        for (int r = (wave - shift + NW) % NW; r < n2; r += NW) updown(s_l2row[r], 0.0f, p.apub + s_l2a[r]);
     }
 
     // ------------------------------------ fixed-order fold of the waves' accumulators
@@ -539,51 +570,8 @@ k_ffn_decode_coop(const CoopParams p)
             for (int e = 0; e < VEC; e += 4)
                 *reinterpret_cast<float4 *>(dst + (c * 64 + lane) * VEC + e) =
                     make_float4(acc[c][e], acc[c][e + 1], acc[c][e + 2], acc[c][e + 3]);
-        if (lane == 0) __hip_atomic_store(p.done + blk, ep, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
-
-    // ------------------------------------ cross-workgroup reduction of this workgroup's columns
-    // s_red is free again: [P][CW] staging, then a two-level fixed-order sum over q.
-    const int CW = p.CW, c0 = blk * CW;
-    if (tid < P) {
-        const unsigned int *dn = p.done + tid;
-        while (__hip_atomic_load(dn, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) != ep) __builtin_amdgcn_s_sleep(2);
-        for (int c = 0; c < CW; c += 4) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (c0 + c < p.d) {
-                const float *src = p.partial + (size_t)tid * p.d + c0 + c;
-                v.x = __hip_atomic_load(src + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                v.y = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                v.z = __hip_atomic_load(src + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                v.w = __hip_atomic_load(src + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            *reinterpret_cast<float4 *>(s_red + tid * CW + c) = v;
-        }
-    }
-    __syncthreads();
-    // level 1: thread (g, c) adds 16 consecutive q; level 2: thread c adds the 16 group sums
-    const int ngrp = (P + 15) / 16;
-    for (int idx = tid; idx < ngrp * CW; idx += NW * 64) {
-        const int g = idx / CW, c = idx - g * CW;
-        float sum = 0.0f;
-        const int q1 = min(P, g * 16 + 16);
-        for (int q = g * 16; q < q1; ++q) sum += s_red[q * CW + c];
-        s_red[P * CW + idx] = sum;
-    }
-    __syncthreads();
-    if (tid < CW && c0 + tid < p.d) {
-        float sum = 0.0f;
-        for (int g = 0; g < ngrp; ++g) sum += s_red[P * CW + g * CW + tid];
-        if (ES == 4) reinterpret_cast<float *>(p.y)[c0 + tid] = sum;
-        else reinterpret_cast<unsigned short *>(p.y)[c0 + tid] = (unsigned short)f32_to_bf16_bits(sum);
-    }
-    if (tid == 0) {
-        const unsigned int prev = atomicAdd(p.fin, 1u);
-        if (prev == (unsigned int)P - 1u) {                 // everyone has read the epoch long ago
-            *p.fin = 0u;
-            __hip_atomic_store(p.epoch, ep, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
+    // the epoch is advanced by the finalize kernel that follows on the stream
 }
 
 template <int ES, int NCH, int NW, int GB, int UB>
@@ -607,9 +595,7 @@ template <int ES, int NCH>
 hipError_t launch_coop(clada_ctx *ctx, const CoopParams &p, int P, bool dense, hipStream_t st)
 {
     constexpr int NW = 8, VEC = 16 / ES;
-    const size_t fold = sizeof(float) * (size_t)(NW / 2) * NCH * 64 * VEC;
-    const size_t red = sizeof(float) * ((size_t)P * p.CW + (size_t)((P + 15) / 16) * p.CW);
-    const size_t lds = fold > red ? fold : red;
+    const size_t lds = sizeof(float) * (size_t)(NW / 2) * NCH * 64 * VEC;
     auto kern = dense ? k_ffn_decode_coop<ES, NCH, NW, true> : k_ffn_decode_coop<ES, NCH, NW, false>;
     static int occ_cache[2] = {-1, -1};                    // per instantiation (template statics)
     if (occ_cache[dense] < 0) {
@@ -660,23 +646,19 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
 
     // ---- cooperative single-kernel path (decode batch 1, whole-KiB rows, <= 56 neurons per workgroup)
     if (ctx->opt_decode_coop && B == 1 && (d * es) % 1024 == 0 && (nch == 2 || nch == 8 || nch == 10)) {
-        int Pc = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
-        if (Pc > F) Pc = F;
+        // the record tags rely on every cooperative call using the same P
+        const int Pc = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
         const int ni_c = (F + Pc - 1) / Pc;
-        const int CW = ((d + Pc - 1) / Pc + 3) / 4 * 4;
-        if (ni_c <= 56 && CW <= 32) {
+        if (F >= Pc && ni_c <= 56) {
             CoopParams c;
             c.wg = p.wg; c.wu = p.wu; c.wd = p.wd; c.x = p.x; c.tau = tau; c.y = (char *)y;
             c.rec = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_REC);
-            c.rec_tag = reinterpret_cast<unsigned int *>(ctx->ws + COOP_REC_TAG);
             c.apub = reinterpret_cast<float *>(ctx->ws + COOP_APUB);
             c.partial = p.partial;
-            c.done = reinterpret_cast<unsigned int *>(ctx->ws + COOP_DONE);
             c.epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
-            c.fin = reinterpret_cast<unsigned int *>(ctx->ws + COOP_FIN);
             c.keep = p.keep;
-            c.d = d; c.F = F; c.CW = CW;
-            c.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : (ni_c / 6 > 1 ? ni_c / 6 : 1);
+            c.d = d; c.F = F;
+            c.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : (ni_c / 3 > 1 ? ni_c / 3 : 1);
             hipError_t ec = hipErrorNotSupported;
             if (es == 2 && nch == 8) ec = launch_coop<2, 8>(ctx, c, Pc, dense, stream);
             else if (es == 2 && nch == 10) ec = launch_coop<2, 10>(ctx, c, Pc, dense, stream);
@@ -684,6 +666,8 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             else if (es == 4 && nch == 2) ec = launch_coop<4, 2>(ctx, c, Pc, dense, stream);
             else if (es == 4 && nch == 8) ec = launch_coop<4, 8>(ctx, c, Pc, dense, stream);
             if (ec == hipSuccess) {
+                launch_finalize(es, p.partial, Pc, 1, d, (char *)y, reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH), stream);
+                CLADA_CHECK_HIP(ctx, hipGetLastError());
                 if (lists) {
                     hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
                     CLADA_CHECK_HIP(ctx, hipGetLastError());
@@ -722,9 +706,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
 #undef CLADA_DECODE_CASE
     CLADA_CHECK_HIP(ctx, e);
 
-    dim3 fgrid((d + 63) / 64, B);
-    if (es == 4) hipLaunchKernelGGL(k_ffn_finalize<4>, fgrid, dim3(256), 0, stream, p.partial, P, d, (char *)y);
-    else         hipLaunchKernelGGL(k_ffn_finalize<2>, fgrid, dim3(256), 0, stream, p.partial, P, d, (char *)y);
+    launch_finalize(es, p.partial, P, B, d, (char *)y, nullptr, stream);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     if (lists) {
         hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);

@@ -108,9 +108,9 @@ def test_batch_rows_independent_and_per_token_thresholds(clada):
         assert torch.equal(yb[0], y[b]), f"row {b} differs between batched and single-token call"
 
 
-@pytest.mark.parametrize("wgs", [1, 2])
-def test_run_to_run_bit_reproducible(clada, wgs):
-    cfg, w, x = _case("c2", 5, 2048, 3000, 2)
+@pytest.mark.parametrize("wgs,B", [(1, 2), (2, 2), (1, 1)])
+def test_run_to_run_bit_reproducible(clada, wgs, B):
+    cfg, w, x = _case("c2", 5, 2048, 3000, B)
     tau = _tau_for(w, x, 0.45)
     outs = []
     for _ in range(3):
