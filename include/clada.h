@@ -66,9 +66,12 @@ const char *clada_status_str(clada_status s);
 const char *clada_last_error(const clada_ctx *ctx);
 
 /* Launch-shape tuning knobs; results never depend on them beyond fp32 summation
- * order.  Names: "decode.wgs_per_cu" (1 or 2 workgroups of the decode kernel per
- * compute unit), "decode.variant" (0 = default kernel variant).  Unknown names or
- * out-of-range values give CLADA_ERR_VALUE and change nothing. */
+ * order.  Names: "decode.b1" (batch-1 decode kernel: 1 = split-d kernel with
+ * cross-workgroup load balancing [default], 2 = split-d kernel without balancing,
+ * 0 = the generic kernels used for batch > 1), "decode.own_first" (1..14, neurons a
+ * workgroup keeps for itself before the balanced hand-over; 0 = default),
+ * "decode.wgs_per_cu" (1 or 2 workgroups per compute unit for the generic kernel).
+ * Unknown names or out-of-range values give CLADA_ERR_VALUE and change nothing. */
 clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);
 
 /* Upper bound of the workspace any call needs for these sizes.  Pass 0 for a

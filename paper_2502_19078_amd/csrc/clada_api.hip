@@ -54,8 +54,7 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->ws_bytes = 0;
     ctx->ws = nullptr;
     ctx->opt_decode_wgs_per_cu = 1;
-    ctx->opt_decode_variant = 0;
-    ctx->opt_decode_coop = 1;
+    ctx->opt_decode_b1 = 1;
     ctx->opt_decode_own_first = 0;
     ctx->err[0] = 0;
     if (workspace_bytes > 0) {
@@ -111,18 +110,13 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
         ctx->opt_decode_wgs_per_cu = value;
         return CLADA_OK;
     }
-    if (!strcmp(name, "decode.variant")) {
-        if (value < 0 || value > 15) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.variant=%d outside [0,15]", value);
-        ctx->opt_decode_variant = value;
-        return CLADA_OK;
-    }
-    if (!strcmp(name, "decode.coop")) {
-        if (value < 0 || value > 1) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.coop=%d outside [0,1]", value);
-        ctx->opt_decode_coop = value;
+    if (!strcmp(name, "decode.b1")) {
+        if (value < 0 || value > 2) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.b1=%d outside [0,2]", value);
+        ctx->opt_decode_b1 = value;
         return CLADA_OK;
     }
     if (!strcmp(name, "decode.own_first")) {
-        if (value < 0 || value > 56) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.own_first=%d outside [0,56]", value);
+        if (value < 0 || value > 14) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.own_first=%d outside [0,14]", value);
         ctx->opt_decode_own_first = value;
         return CLADA_OK;
     }

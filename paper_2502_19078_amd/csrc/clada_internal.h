@@ -13,9 +13,8 @@ struct clada_ctx {
     size_t ws_bytes;
     char *ws;            // device workspace, 256-byte aligned; first CLADA_WS_HEADER bytes = counters
     int opt_decode_wgs_per_cu;   // launch shape of the decode kernel (clada_set_option)
-    int opt_decode_variant;
-    int opt_decode_coop;         // 1: single cooperative kernel for B=1 where eligible
-    int opt_decode_own_first;    // K0 of the cooperative kernel; 0 = derive from the tile size
+    int opt_decode_b1;           // batch-1 split-d kernel: 0 off (generic kernels), 1 with balancing, 2 without
+    int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
     char err[512];
 };
 
@@ -28,7 +27,7 @@ struct clada_ctx {
 enum { CTR_SIGNALS = 0, CTR_DECODE = 64, CTR_PREFIX = 128, CTR_CALIB = 192 };  // int32 slots
 // Control words of the cooperative decode kernel inside the header (byte offsets).
 #define COOP_MAX_WGS 256
-enum { COOP_EPOCH = 1024, COOP_FIN = 1028, COOP_REC_TAG = 2048, COOP_DONE = 3072, COOP_REC = 4096,
+enum { COOP_EPOCH = 1024, COOP_REC = 4096,
        COOP_APUB = 8192 /* 256*64 floats = 64 KiB */ };
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

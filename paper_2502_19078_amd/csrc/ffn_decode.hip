@@ -17,6 +17,8 @@
 //                  adds the P partials in fixed order and rounds once to the
 //                  output dtype.  No atomics on floating point anywhere, so
 //                  results are bit-reproducible.
+#include <type_traits>
+
 #include "clada_internal.h"
 
 namespace {
@@ -319,34 +321,6 @@ k_ffn_lists(const unsigned char *__restrict__ keep, int B, int F, int32_t *__res
 }
 
 
-// ---------------------------------------------------------------------------------------
-// Cooperative single-kernel path for decode batch 1 (the configuration the method is
-// timed on).  Same gate / compaction / up-down structure as k_ffn_decode, plus:
-//   * load balancing: a workgroup's kept count is binomial, so with a static neuron split
-//     the slowest workgroup would set the kernel time.  Each workgroup publishes its keep
-//     mask (<= 56 neurons -> one 64-bit word, tagged with the call's epoch) and its
-//     activations, processes its own first K0 kept neurons, then reads all P masks and
-//     takes its share of the pooled surplus so that every workgroup handles floor/ceil(k/P)
-//     neurons.  The assignment is a function of the masks only, so the summation order --
-//     and the result -- stays bit-reproducible.
-//   * the cross-workgroup reduction of the partial y's runs in the same kernel: after
-//     publishing its partial every workgroup waits for all P "done" tags and adds its own
-//     slice of columns over the partials in fixed order (no separate finalize launch).
-// All P workgroups must be co-resident (checked on the host: P <= CUs * occupancy).
-// Cross-workgroup data goes through agent-scope release stores / acquire loads.
-struct CoopParams {
-    const char *wg, *wu, *wd, *x;
-    const float *tau;
-    char *y;
-    unsigned long long *rec;    // [P] keep mask of the workgroup's neurons (bit i = neuron blk + P*i,
-                                //     i < 56) | 8-bit epoch tag in bits 56..63, stored with release
-    float *apub;                // [P][64] published activations a_i of the workgroup's neurons
-    float *partial;             // [P][d]
-    const unsigned int *epoch;  // device-side call counter (survives graph replays); advanced by k_ffn_finalize
-    unsigned char *keep;        // [F] or nullptr
-    int d, F, K0;
-};
-
 __device__ __forceinline__ int select_bit(unsigned long long m, int t)
 {   // index of the t-th set bit of m (t < popcount(m))
     int i = 0;
@@ -358,75 +332,136 @@ __device__ __forceinline__ int select_bit(unsigned long long m, int t)
     return i;
 }
 
-__device__ __forceinline__ int block_excl_scan(int v, int tid, int *s_tmp, int nwaves, int *total)
-{   // exclusive prefix sum over the workgroup's threads (all threads must call)
-    const int lane = tid & 63, wave = tid >> 6;
+// ---------------------------------------------------------------------------------------
+// Split-d kernel for decode batch 1 (whole-KiB rows, <= 64 neurons per workgroup).
+//   gate  : as above, one whole row per wave, next row prefetched while the current one is
+//           reduced (loads never depend on a branch: out-of-range prefetches read x).
+//   list  : every wave ballots the flags into the same ascending list (one barrier).
+//   down  : the workgroup's kept neurons are taken DCH at a time.  Every wave owns a fixed
+//           slice of the d columns (chunk c = wave, wave+NW, ...) and issues its 16-byte
+//           loads of W_down[j, slice] for the whole chunk of neurons at once -- these loads
+//           need only the list, not h, so up to DCH KiB per wave stream while ...
+//   up    : ... the same waves take the chunk's W_up rows round-robin (two in flight),
+//           h = a * (W_up[j,:].x) goes to LDS; after one barrier each wave adds
+//           h * W_down[j, slice] into its 8 (bf16) or 4 (fp32) accumulators per chunk.
+//   No cross-wave fold (each wave owns its columns) and plenty of bytes in flight, so a
+//   workgroup with more kept neurons than its neighbours simply streams longer at its own rate.
+#ifdef CLADA_TIMESTAMPS
+// Development aid: per-workgroup wall-clock stamps at the phase boundaries of k_ffn_decode_b1.
+__device__ long long g_b1_stamps[512 * 8];
+#define B1_STAMP(slot) do { if (tid == 0) g_b1_stamps[blk * 8 + (slot)] = wall_clock64(); } while (0)
+extern "C" int clada_debug_fetch_stamps(long long *host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_b1_stamps), sizeof(long long) * n);
+}
+#else
+#define B1_STAMP(slot) do { } while (0)
+#endif
+
+struct B1Params {
+    const char *wg, *wu, *wd, *x;
+    const float *tau;
+    float *partial;             // [P][d]
+    unsigned char *keep;        // [F] or nullptr
+    unsigned long long *rec;    // [P] keep mask (bit i = neuron blk + P*i, i < 56) | epoch tag in bits 56..63
+    float *apub;                // [P][64] published activations
+    const unsigned int *epoch;  // device-side counter of balanced calls, advanced by k_ffn_finalize
+                                // (read at kernel start, so graph replays stay correct)
+    int d, F, K0;
+};
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+// fp32 += bf16 pair . bf16 pair (exact products, fp32 accumulate).  The operands go through
+// plain scalars: bit-casting a vector element expression directly was seen to pick lane 0.
+__device__ __forceinline__ float dot2_bf16(unsigned int a, unsigned int b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
+template <int ES>
+__device__ __forceinline__ float dot16(const u32x4 w, const u32x4 x, float acc)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const unsigned int wk = w[k], xk = x[k];
+        acc = ES == 2 ? dot2_bf16(wk, xk, acc) : fmaf(__uint_as_float(wk), __uint_as_float(xk), acc);
+    }
+    return acc;
+}
+
+// Exclusive prefix sum over the 64 lanes of a wave (no barrier); *total gets the wave sum.
+__device__ __forceinline__ int wave_excl_scan(int v, int lane, int *total)
+{
     int inc = v;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
         const int t = __shfl_up(inc, o);
         if (lane >= o) inc += t;
     }
-    if (lane == 63) s_tmp[wave] = inc;
-    __syncthreads();
-    int base = 0, tot = 0;
-    for (int w = 0; w < nwaves; ++w) {
-        const int c = s_tmp[w];
-        if (w < wave) base += c;
-        tot += c;
-    }
-    __syncthreads();
-    *total = tot;
-    return base + inc - v;
+    *total = __shfl(inc, 63);
+    return inc - v;
 }
 
-template <int ES, int NCH, int NW, bool DENSE>
+// BAL = cross-workgroup load balancing (sparse calls): a workgroup's kept count is binomial, and
+// measured per-workgroup timelines show the busiest workgroup finishing ~5 us after the average
+// one.  After the gate phase every workgroup publishes its keep mask (<= 56 neurons -> one 64-bit
+// word with an 8-bit epoch tag) and its activations with agent-scope write-through stores, takes
+// its own first K0 kept neurons as chunk 0, and while those loads stream wave 0 alone reads all P
+// masks, prefix-sums them and hands the workgroup its share of the pooled surplus, so that every
+// workgroup ends up with floor/ceil(k/P) neurons.  The assignment is a function of the masks
+// only: summation order and result stay bit-reproducible.  Needs all P workgroups co-resident.
+// (A variant that also ran the cross-workgroup reduction of the partial y's inside this kernel --
+// write-through partials, "done" tags, every workgroup adding its d/P columns -- was measured
+// 7 us slower than the separate k_ffn_finalize launch: each agent-scope round trip costs ~3 us
+// here.  For the same reason balancing only pays when chunk 0 is long enough to hide two hops.)
+template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL>
 __global__ void __launch_bounds__(NW * 64)
-k_ffn_decode_coop(const CoopParams p)
+k_ffn_decode_b1(const B1Params p)
 {
     constexpr int VEC = 16 / ES;
-    constexpr int ROWB = NCH * 1024;                       // full rows only: d*ES == NCH*1024
+    constexpr int ROWB = NCH * 1024;
+    constexpr int SL = (NCH + NW - 1) / NW;                 // column chunks owned by a wave
+    constexpr int UPB = (DCH + NW - 1) / NW;                // W_up rows a wave takes per chunk
+    constexpr int K0MAX = 2 * (NW - 1);                     // own-first chunk: two W_up rows for waves 1..NW-1
+    static_assert(!(DENSE && BAL), "the dense twin needs no balancing");
     __shared__ float s_a[64];
     __shared__ int s_flag[64];
     __shared__ int s_list[64];
-    __shared__ int s_l2row[64];
-    __shared__ int s_l2a[64];
-    __shared__ int s_tmp[NW];
-    __shared__ int s_misc[4];
-    extern __shared__ __align__(16) unsigned char smem_coop[];
-    float *s_red = reinterpret_cast<float *>(smem_coop);   // fold buffers, later the reduction staging
+    __shared__ float s_h[2][DCH > K0MAX ? DCH : K0MAX];
+    __shared__ int s_l2row[64];                             // balanced share: weight row ...
+    __shared__ int s_l2a[64];                               // ... and index of its published activation
+    __shared__ int s_n2;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int blk = blockIdx.x, P = gridDim.x;
     const int F = p.F;
-    const int ni = blk < F ? (F - blk + P - 1) / P : 0;    // <= 56
-    // Every cooperative call (sparse or dense) rewrites all P records, so a stale record is
-    // exactly one call old and an 8-bit tag tells it apart.
-    const unsigned int ep = *p.epoch + 1u;
-    const unsigned long long tag = (unsigned long long)(ep & 0xffu) << 56;
+    const int ni = blk < F ? (F - blk + P - 1) / P : 0;     // <= 64 (<= 56 when BAL)
+
     const int loff = lane * 16;
+    B1_STAMP(0);
 
-    float xr[NCH][VEC];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c)
-        unpack_row16(*reinterpret_cast<const u32x4 *>(p.x + c * 1024 + loff), xr[c]);
-    const float tau = DENSE ? 0.0f : p.tau[0];
-
-    // ---------------------------------------------------------------- gate phase
-    for (int i = wave; i < ni; i += NW) {
-        const char *row = p.wg + (size_t)(blk + P * i) * ROWB + loff;
-        u32x4 buf[NCH];
+    auto load_row = [&](u32x4 (&buf)[NCH], const char *w, int j) {
+        const char *row = w + (size_t)j * ROWB + loff;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) buf[c] = ld_stream16(row + c * 1024);
+    };
+
+    // first gate row on its way before anything else
+    u32x4 ga[NCH], gb[NCH];
+    if (wave < ni) load_row(ga, p.wg, blk + P * wave);
+    u32x4 xr[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) xr[c] = *reinterpret_cast<const u32x4 *>(p.x + c * 1024 + loff);
+    const float tau = DENSE ? 0.0f : p.tau[0];
+    unsigned long long tag = 0ull;
+    if (BAL) tag = (unsigned long long)((*p.epoch + 1u) & 0xffu) << 56;
+
+    auto gate_finish = [&](const u32x4 (&buf)[NCH], int i) {
         float s = 0.0f;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            float w[VEC];
-            unpack_row16(buf[c], w);
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) s = fmaf(w[e], xr[c][e], s);
-        }
+        for (int c = 0; c < NCH; ++c) s = dot16<ES>(buf[c], xr[c], s);
         s = wave_sum(s);
         const float a = silu_f32(s);
         const bool keep = DENSE ? true : (fabsf(a) >= tau);
@@ -435,143 +470,280 @@ k_ffn_decode_coop(const CoopParams p)
             s_flag[i] = keep ? 1 : 0;
             if (p.keep) p.keep[blk + P * i] = keep ? 1 : 0;
         }
+    };
+    // ---------------------------------------------------------------- gate phase: the next row is
+    // requested before the current one is reduced; every path has a fixed number of loads in flight
+    for (int i = wave; i < ni; i += 2 * NW) {
+        if (i + NW < ni) {
+            load_row(gb, p.wg, blk + P * (i + NW));
+            gate_finish(ga, i);
+            if (i + 2 * NW < ni) {
+                load_row(ga, p.wg, blk + P * (i + 2 * NW));
+                gate_finish(gb, i + NW);
+            } else {
+                gate_finish(gb, i + NW);
+            }
+        } else {
+            gate_finish(ga, i);
+        }
     }
+    B1_STAMP(1);
     __syncthreads();
+    B1_STAMP(2);
 
-    // every wave derives the same mask and list (no second barrier needed)
+    // every wave derives the same ascending list
     const unsigned long long mask = __ballot(lane < ni && s_flag[lane] != 0);
     const int kp = __popcll(mask);
     if ((mask >> lane) & 1ull) s_list[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
-    const int own = DENSE ? kp : min(kp, p.K0);
-    if (wave == 0) {
-        // Publish activations, then the tagged mask.  Both go out as agent-scope atomic stores
-        // (written through to memory), so ordering them needs only the wait for the first
-        // stores' acknowledgements (a workgroup-scope release fence), not an L2 write-back.
-        if (!DENSE && lane < ni)
-            __hip_atomic_store(p.apub + blk * 64 + lane, s_a[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        if (lane == 0) __hip_atomic_store(p.rec + blk, mask | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
 
-    float acc[NCH][VEC];
+    float acc[SL][VEC];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c)
+    for (int s = 0; s < SL; ++s)
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[c][e] = 0.0f;
+        for (int e = 0; e < VEC; ++e) acc[s][e] = 0.0f;
 
-    auto updown = [&](int row_j, float a, const float *a_pub) {
-        const size_t off = (size_t)row_j * ROWB + loff;
-        u32x4 ub[NCH], db[NCH];
-        // a borrowed neuron's activation travels with its weight rows (same round trip)
-        if (a_pub) a = __hip_atomic_load(a_pub, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // h * W_down[j, slice] for one chunk of neurons, straight from the loaded registers
+    auto down_fma = [&](auto dnc, const u32x4 (&dn)[decltype(dnc)::value][SL], const float *hs, int nvalid) {
+        constexpr int N = decltype(dnc)::value;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) ub[c] = ld_stream16(p.wu + off + c * 1024);
+        for (int e = 0; e < N; ++e) {
+            const float h = e < nvalid ? hs[e] : 0.0f;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) db[c] = ld_stream16(p.wd + off + c * 1024);
-        float s = 0.0f;
+            for (int s = 0; s < SL; ++s) {
+                float w[VEC];
+                unpack_row16(dn[e][s], w);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            float w[VEC];
-            unpack_row16(ub[c], w);
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) s = fmaf(w[e], xr[c][e], s);
+                for (int k = 0; k < VEC; ++k) acc[s][k] = fmaf(h, w[k], acc[s][k]);
+            }
         }
-        const float h = a * wave_sum(s);
+    };
+    auto down_load = [&](auto dnc, u32x4 (&dn)[decltype(dnc)::value][SL], const int *rows, int nvalid, bool local) {
+        constexpr int N = decltype(dnc)::value;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            float w[VEC];
-            unpack_row16(db[c], w);
+        for (int e = 0; e < N; ++e) {
+            if (e < nvalid) {
+                const int j = local ? blk + P * rows[e] : rows[e];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[c][e] = fmaf(h, w[e], acc[c][e]);
+                for (int s = 0; s < SL; ++s) {
+                    const int c = wave + s * NW;
+                    if (c < NCH) dn[e][s] = ld_stream16(p.wd + (size_t)j * ROWB + c * 1024 + loff);
+                    else dn[e][s] = u32x4{0u, 0u, 0u, 0u};
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < SL; ++s) dn[e][s] = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+    };
+    // R W_up rows of this wave in flight together: entries first, first+stride, ... of a list
+    auto up_rows = [&](auto rc, const int *rows, const int *aidx, bool local, int first, int stride, float *hs) {
+        constexpr int R = decltype(rc)::value;
+        u32x4 up[R][NCH];
+        float av[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int e = first + r * stride;
+            const int j = local ? blk + P * rows[e] : rows[e];
+            if (local) av[r] = s_a[rows[e]];
+            else av[r] = __hip_atomic_load(p.apub + aidx[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            load_row(up[r], p.wu, j);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float s0 = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xr[c], s0);
+            s0 = wave_sum(s0);
+            if (lane == 0) hs[first + r * stride] = av[r] * s0;
         }
     };
 
-    // ------------------------------------------- own kept neurons (first `own` of the list)
-    for (int t = wave; t < own; t += NW) {
-        const int i = s_list[t];
-        updown(blk + P * i, s_a[i], nullptr);
-    }
-
-    // ------------------------------------------- share of the pooled surplus
-    int n2 = 0;
-    if (!DENSE) {
-        // thread q polls record q (relaxed loads that go to memory, spaced by s_sleep); all cross-
-        // workgroup reads below are agent-scope atomic loads, so no cache invalidation is needed
-        unsigned long long mq = 0ull;
-        if (tid < P) {
+    int par = 0;
+    if (BAL) {
+        // ------------------------------------------------ publish, then chunk 0 = own first K0 neurons
+        const int K0 = min(p.K0, K0MAX);
+        const int own = min(kp, K0);
+        if (wave == 0) {
+            if (lane < ni)
+                __hip_atomic_store(p.apub + blk * 64 + lane, s_a[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // = wait for the stores' acknowledgements
+            if (lane == 0) __hip_atomic_store(p.rec + blk, mask | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        u32x4 dn0[K0MAX][SL];
+        down_load(std::integral_constant<int, K0MAX>{}, dn0, s_list, own, true);
+        if (wave > 0) {                                     // W_up rows of chunk 0 go to waves 1..NW-1
+            const int first = wave - 1;
+            const int nup = first < own ? (own - first + NW - 2) / (NW - 1) : 0;
+            if (nup == 1) up_rows(std::integral_constant<int, 1>{}, s_list, nullptr, true, first, NW - 1, s_h[0]);
+            else if (nup == 2) up_rows(std::integral_constant<int, 2>{}, s_list, nullptr, true, first, NW - 1, s_h[0]);
+        } else {
+            // wave 0: read all P masks (lane handles records 4*lane .. 4*lane+3), no barriers
+            unsigned long long m[4];
             for (;;) {
-                mq = __hip_atomic_load(p.rec + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((mq & (0xffull << 56)) == tag) break;
+                bool ok = true;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = 4 * lane + u;
+                    m[u] = q < P ? __hip_atomic_load(p.rec + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : tag;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) ok = ok && ((m[u] & (0xffull << 56)) == tag);
+                if (__ballot(ok) == ~0ull) break;
                 __builtin_amdgcn_s_sleep(8);
             }
-            mq &= ~(0xffull << 56);
-        }
-        const int kq = __popcll(mq);
-        const int oq = min(kq, p.K0), sq = kq - oq;
-        int K, S;
-        (void)block_excl_scan(kq, tid, s_tmp, NW, &K);
-        // target count of workgroup q: floor((q+1)K/P) - floor(qK/P); extra beyond its own first rows
-        const int tgt = tid < P ? (int)(((long long)(tid + 1) * K) / P - ((long long)tid * K) / P) : 0;
-        const int eq = max(0, tgt - oq);
-        // one scan for both prefixes: surplus counts in the low half, extras in the high half
-        int SE;
-        const int sepre = block_excl_scan(sq | (eq << 16), tid, s_tmp, NW, &SE);
-        const int spre = sepre & 0xffff, epre = sepre >> 16;
-        S = SE & 0xffff;
-        if (tid == blk) {
-            s_misc[0] = min(epre, S);
-            s_misc[1] = min(epre + eq, S);
-        }
-        __syncthreads();
-        const int lo = s_misc[0], hi = s_misc[1];
-        n2 = hi - lo;
-        // thread q hands over the part of its surplus [spre, spre+sq) that falls into [lo, hi)
-        const int a0 = max(lo, spre), a1 = min(hi, spre + sq);
-        for (int r = a0; r < a1; ++r) {
-            const int i = select_bit(mq, oq + (r - spre));
-            s_l2row[r - lo] = tid + P * i;
-            s_l2a[r - lo] = tid * 64 + i;
-        }
-        __syncthreads();
-        const int shift = own % NW;                         // wave that would take list entry `own`
-        for (int r = (wave - shift + NW) % NW; r < n2; r += NW) updown(s_l2row[r], 0.0f, p.apub + s_l2a[r]);
-    }
-
-    // ------------------------------------ fixed-order fold of the waves' accumulators
+            int kq[4], oq[4], sq[4], ksum = 0;
 #pragma unroll
-    for (int s = NW / 2; s >= 1; s >>= 1) {
-        if (wave >= s && wave < 2 * s) {
-            float *dst = s_red + (size_t)(wave - s) * (NCH * 64 * VEC);
+            for (int u = 0; u < 4; ++u) {
+                m[u] &= ~(0xffull << 56);
+                kq[u] = __popcll(m[u]);
+                oq[u] = min(kq[u], K0);
+                sq[u] = kq[u] - oq[u];
+                ksum += kq[u];
+            }
+            int K;
+            (void)wave_excl_scan(ksum, lane, &K);
+            // target of workgroup q: floor((q+1)K/P) - floor(qK/P); extra = target - own-first, >= 0
+            int eq[4], se = 0;
 #pragma unroll
-            for (int c = 0; c < NCH; ++c)
+            for (int u = 0; u < 4; ++u) {
+                const int q = 4 * lane + u;
+                const int tgt = q < P ? (int)(((long long)(q + 1) * K) / P - ((long long)q * K) / P) : 0;
+                eq[u] = max(0, tgt - oq[u]);
+                se += sq[u] | (eq[u] << 16);
+            }
+            int SE;
+            int pre = wave_excl_scan(se, lane, &SE);        // surplus prefix (low half) | extra prefix (high half)
+            const int S = SE & 0xffff;
+            // this workgroup's slice [lo, hi) of the pooled surplus
+            int spre[4], epre[4];
 #pragma unroll
-                for (int e = 0; e < VEC; e += 4)
-                    *reinterpret_cast<float4 *>(dst + (c * 64 + lane) * VEC + e) =
-                        make_float4(acc[c][e], acc[c][e + 1], acc[c][e + 2], acc[c][e + 3]);
-        }
-        __syncthreads();
-        if (wave < s) {
-            const float *src = s_red + (size_t)wave * (NCH * 64 * VEC);
+            for (int u = 0; u < 4; ++u) {
+                spre[u] = pre & 0xffff;
+                epre[u] = pre >> 16;
+                pre += sq[u] | (eq[u] << 16);
+            }
+            int lo_l = 0, hi_l = 0;
 #pragma unroll
-            for (int c = 0; c < NCH; ++c)
+            for (int u = 0; u < 4; ++u)
+                if (4 * lane + u == blk) { lo_l = min(epre[u], S); hi_l = min(epre[u] + eq[u], S); }
+            const int lo = __shfl(lo_l, blk >> 2), hi = __shfl(hi_l, blk >> 2);
+            // record q hands over the part of its surplus [spre, spre+sq) that falls into [lo, hi)
 #pragma unroll
-                for (int e = 0; e < VEC; e += 4) {
-                    const float4 v = *reinterpret_cast<const float4 *>(src + (c * 64 + lane) * VEC + e);
-                    acc[c][e] += v.x; acc[c][e + 1] += v.y; acc[c][e + 2] += v.z; acc[c][e + 3] += v.w;
+            for (int u = 0; u < 4; ++u) {
+                const int q = 4 * lane + u;
+                const int a0 = max(lo, spre[u]), a1 = min(hi, spre[u] + sq[u]);
+                for (int r = a0; r < a1; ++r) {
+                    const int i = select_bit(m[u], oq[u] + (r - spre[u]));
+                    s_l2row[r - lo] = q + P * i;
+                    s_l2a[r - lo] = q * 64 + i;
                 }
+            }
+            if (lane == 0) s_n2 = hi - lo;
         }
+        B1_STAMP(7);
         __syncthreads();
-    }
-    if (wave == 0) {
-        float *dst = p.partial + (size_t)blk * p.d;
+        // first chunk of the balanced share: its loads go out before chunk 0 is consumed
+        const int n2 = s_n2;
+        {
+            const int nc = min(DCH, n2);
+            u32x4 dn[DCH][SL];
+            down_load(std::integral_constant<int, DCH>{}, dn, s_l2row, nc, false);
+            const int nup = wave < nc ? (nc - wave + NW - 1) / NW : 0;
+            // W_up rows requested now, reduced after chunk 0's accumulation
+            u32x4 up[UPB][NCH];
+            float av[UPB];
 #pragma unroll
-        for (int c = 0; c < NCH; ++c)
+            for (int r = 0; r < UPB; ++r)
+                if (r < nup) {
+                    const int e = wave + r * NW;
+                    av[r] = __hip_atomic_load(p.apub + s_l2a[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    load_row(up[r], p.wu, s_l2row[e]);
+                }
+            down_fma(std::integral_constant<int, K0MAX>{}, dn0, s_h[0], own);
 #pragma unroll
-            for (int e = 0; e < VEC; e += 4)
-                *reinterpret_cast<float4 *>(dst + (c * 64 + lane) * VEC + e) =
-                    make_float4(acc[c][e], acc[c][e + 1], acc[c][e + 2], acc[c][e + 3]);
+            for (int r = 0; r < UPB; ++r)
+                if (r < nup) {
+                    float s0 = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xr[c], s0);
+                    s0 = wave_sum(s0);
+                    if (lane == 0) s_h[1][wave + r * NW] = av[r] * s0;
+                }
+            B1_STAMP(3);
+            __syncthreads();
+            B1_STAMP(4);
+            down_fma(std::integral_constant<int, DCH>{}, dn, s_h[1], nc);
+        }
+        // rest of the share (rare: more than DCH extra neurons)
+        par = 0;
+        for (int c0 = DCH; c0 < n2; c0 += DCH, par ^= 1) {
+            const int nc = min(DCH, n2 - c0);
+            u32x4 dn[DCH][SL];
+            down_load(std::integral_constant<int, DCH>{}, dn, s_l2row + c0, nc, false);
+            const int nup = wave < nc ? (nc - wave + NW - 1) / NW : 0;
+            if (nup == 1) up_rows(std::integral_constant<int, 1>{}, s_l2row + c0, s_l2a + c0, false, wave, NW, s_h[par]);
+            else if (nup == 2) up_rows(std::integral_constant<int, UPB >= 2 ? 2 : 1>{}, s_l2row + c0, s_l2a + c0, false, wave, NW, s_h[par]);
+            else if (nup == 3) up_rows(std::integral_constant<int, UPB >= 3 ? 3 : 1>{}, s_l2row + c0, s_l2a + c0, false, wave, NW, s_h[par]);
+            __syncthreads();
+            down_fma(std::integral_constant<int, DCH>{}, dn, s_h[par], nc);
+        }
+    } else {
+        // ------------------------------------------------ no balancing: the workgroup's own list, DCH at a time
+        for (int c0 = 0; c0 < kp; c0 += DCH, par ^= 1) {
+            const int nc = min(DCH, kp - c0);
+            u32x4 dn[DCH][SL];
+            down_load(std::integral_constant<int, DCH>{}, dn, s_list + c0, nc, true);
+            const int nup = wave < nc ? (nc - wave + NW - 1) / NW : 0;
+            static_assert(UPB <= 3, "add cases");
+            if (nup == 1) up_rows(std::integral_constant<int, 1>{}, s_list + c0, nullptr, true, wave, NW, s_h[par]);
+            else if (nup == 2) up_rows(std::integral_constant<int, UPB >= 2 ? 2 : 1>{}, s_list + c0, nullptr, true, wave, NW, s_h[par]);
+            else if (nup == 3) up_rows(std::integral_constant<int, UPB >= 3 ? 3 : 1>{}, s_list + c0, nullptr, true, wave, NW, s_h[par]);
+            B1_STAMP(3);
+            __syncthreads();
+            B1_STAMP(4);
+            down_fma(std::integral_constant<int, DCH>{}, dn, s_h[par], nc);
+        }
     }
-    // the epoch is advanced by the finalize kernel that follows on the stream
+    B1_STAMP(5);
+    // each wave owns its columns: straight to the partial, no fold
+    float *dst = p.partial + (size_t)blk * p.d;
+#pragma unroll
+    for (int s = 0; s < SL; ++s) {
+        const int c = wave + s * NW;
+        if (c < NCH) {
+#pragma unroll
+            for (int k = 0; k < VEC; k += 4)
+                *reinterpret_cast<float4 *>(dst + (c * 64 + lane) * VEC + k) =
+                    make_float4(acc[s][k], acc[s][k + 1], acc[s][k + 2], acc[s][k + 3]);
+        }
+    }
+    B1_STAMP(6);
+}
+
+template <int ES, int NCH, int DCH, bool DENSE, bool BAL>
+hipError_t launch_b1_variant(clada_ctx *ctx, const B1Params &p, int P, hipStream_t st)
+{
+    auto kern = k_ffn_decode_b1<ES, NCH, 8, DCH, DENSE, BAL>;
+    if (BAL) {          // spinning on other workgroups' records needs every workgroup resident at once
+        static int occ = -1;
+        if (occ < 0) {
+            int nb = 0;
+            hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, 512, 0);
+            if (e != hipSuccess) return e;
+            occ = nb;
+        }
+        if ((long long)occ * ctx->num_cu < P) return hipErrorNotSupported;
+    }
+    hipLaunchKernelGGL(kern, dim3(P), dim3(512), 0, st, p);
+    return hipGetLastError();
+}
+
+template <int ES, int NCH, int DCH>
+hipError_t launch_b1(clada_ctx *ctx, const B1Params &p, int P, bool dense, bool balance, hipStream_t st)
+{
+    if (dense) return launch_b1_variant<ES, NCH, DCH, true, false>(ctx, p, P, st);
+    if (balance) return launch_b1_variant<ES, NCH, DCH, false, true>(ctx, p, P, st);
+    return launch_b1_variant<ES, NCH, DCH, false, false>(ctx, p, P, st);
 }
 
 template <int ES, int NCH, int NW, int GB, int UB>
@@ -587,28 +759,6 @@ hipError_t launch_decode(const DecodeParams &p, int P, int B, bool dense, hipStr
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(P, B), dim3(NW * 64), lds, st, p);
-    return hipGetLastError();
-}
-
-// Cooperative launch; returns hipErrorNotSupported when the shape is not eligible.
-template <int ES, int NCH>
-hipError_t launch_coop(clada_ctx *ctx, const CoopParams &p, int P, bool dense, hipStream_t st)
-{
-    constexpr int NW = 8, VEC = 16 / ES;
-    const size_t lds = sizeof(float) * (size_t)(NW / 2) * NCH * 64 * VEC;
-    auto kern = dense ? k_ffn_decode_coop<ES, NCH, NW, true> : k_ffn_decode_coop<ES, NCH, NW, false>;
-    static int occ_cache[2] = {-1, -1};                    // per instantiation (template statics)
-    if (occ_cache[dense] < 0) {
-        hipError_t e = hipSuccess;
-        if (lds > 48 * 1024)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        int nb = 0;
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, NW * 64, lds);
-        if (e != hipSuccess) return e;
-        occ_cache[dense] = nb;
-    }
-    if ((long long)occ_cache[dense] * ctx->num_cu < P) return hipErrorNotSupported;   // not co-resident
-    hipLaunchKernelGGL(kern, dim3(P), dim3(NW * 64), lds, st, p);
     return hipGetLastError();
 }
 
@@ -644,64 +794,52 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     const int nch = (d * es + 1023) / 1024;
     hipError_t e = hipErrorInvalidValue;
 
-    // ---- cooperative single-kernel path (decode batch 1, whole-KiB rows, <= 56 neurons per workgroup)
-    if (ctx->opt_decode_coop && B == 1 && (d * es) % 1024 == 0 && (nch == 2 || nch == 8 || nch == 10)) {
-        // the record tags rely on every cooperative call using the same P
-        const int Pc = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
-        const int ni_c = (F + Pc - 1) / Pc;
-        if (F >= Pc && ni_c <= 56) {
-            CoopParams c;
-            c.wg = p.wg; c.wu = p.wu; c.wd = p.wd; c.x = p.x; c.tau = tau; c.y = (char *)y;
-            c.rec = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_REC);
-            c.apub = reinterpret_cast<float *>(ctx->ws + COOP_APUB);
-            c.partial = p.partial;
-            c.epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
-            c.keep = p.keep;
-            c.d = d; c.F = F;
-            c.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : (ni_c / 3 > 1 ? ni_c / 3 : 1);
-            hipError_t ec = hipErrorNotSupported;
-            if (es == 2 && nch == 8) ec = launch_coop<2, 8>(ctx, c, Pc, dense, stream);
-            else if (es == 2 && nch == 10) ec = launch_coop<2, 10>(ctx, c, Pc, dense, stream);
-            else if (es == 2 && nch == 2) ec = launch_coop<2, 2>(ctx, c, Pc, dense, stream);
-            else if (es == 4 && nch == 2) ec = launch_coop<4, 2>(ctx, c, Pc, dense, stream);
-            else if (es == 4 && nch == 8) ec = launch_coop<4, 8>(ctx, c, Pc, dense, stream);
-            if (ec == hipSuccess) {
-                launch_finalize(es, p.partial, Pc, 1, d, (char *)y, reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH), stream);
-                CLADA_CHECK_HIP(ctx, hipGetLastError());
-                if (lists) {
-                    hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
-                    CLADA_CHECK_HIP(ctx, hipGetLastError());
-                }
-                return CLADA_OK;
+    // ---- split-d path (decode batch 1, whole-KiB rows, <= 64 neurons per workgroup)
+    if (ctx->opt_decode_b1 >= 1 && B == 1 && (d * es) % 1024 == 0 && (nch == 2 || nch == 8 || nch == 10)) {
+        const int Pb = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
+        const int ni_b = (F + Pb - 1) / Pb;
+        if (F >= Pb && ni_b <= 64) {
+            B1Params b;
+            b.wg = p.wg; b.wu = p.wu; b.wd = p.wd; b.x = p.x; b.tau = tau; b.partial = p.partial; b.keep = p.keep;
+            b.rec = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_REC);
+            b.apub = reinterpret_cast<float *>(ctx->ws + COOP_APUB);
+            unsigned int *epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
+            b.epoch = epoch;
+            b.d = d; b.F = F;
+            b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
+            bool balance = !dense && ctx->opt_decode_b1 == 1 && ni_b <= 56;
+            hipError_t eb = hipErrorNotSupported;
+            for (int attempt = 0; attempt < 2 && eb == hipErrorNotSupported; ++attempt) {
+                if (es == 2 && nch == 8) eb = launch_b1<2, 8, 16>(ctx, b, Pb, dense, balance, stream);
+                else if (es == 2 && nch == 10) eb = launch_b1<2, 10, 8>(ctx, b, Pb, dense, balance, stream);
+                else if (es == 2 && nch == 2) eb = launch_b1<2, 2, 16>(ctx, b, Pb, dense, balance, stream);
+                else if (es == 4 && nch == 2) eb = launch_b1<4, 2, 16>(ctx, b, Pb, dense, balance, stream);
+                else if (es == 4 && nch == 8) eb = launch_b1<4, 8, 16>(ctx, b, Pb, dense, balance, stream);
+                if (eb == hipErrorNotSupported) balance = false;      // not co-resident: plain split-d
             }
-            if (ec != hipErrorNotSupported) CLADA_CHECK_HIP(ctx, ec);
+            CLADA_CHECK_HIP(ctx, eb);
+            launch_finalize(es, p.partial, Pb, 1, d, (char *)y, balance ? epoch : nullptr, stream);
+            CLADA_CHECK_HIP(ctx, hipGetLastError());
+            if (lists) {
+                hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
+                CLADA_CHECK_HIP(ctx, hipGetLastError());
+            }
+            return CLADA_OK;
         }
     }
 #define CLADA_DECODE_CASE(ES_, NCH_, NW_, GB_, UB_)                                        \
     if (es == ES_ && nch <= NCH_ && e == hipErrorInvalidValue)                             \
         e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, dense, stream);
-    if (es == 2 && nch == 8) {      // experimental launch shapes for the 4096-wide bf16 row
-        switch (ctx->opt_decode_variant) {
-        case 1: e = launch_decode<2, 8, 8, 1, 1>(p, P, B, dense, stream); break;
-        case 2: e = launch_decode<2, 8, 8, 3, 1>(p, P, B, dense, stream); break;
-        case 3: e = launch_decode<2, 8, 4, 4, 2>(p, P, B, dense, stream); break;
-        case 4: e = launch_decode<2, 8, 4, 6, 3>(p, P, B, dense, stream); break;
-        case 5: e = launch_decode<2, 8, 4, 3, 1>(p, P, B, dense, stream); break;
-        case 6: e = launch_decode<2, 8, 4, 2, 1>(p, P, B, dense, stream); break;
-        case 7: e = launch_decode<2, 8, 16, 1, 1>(p, P, B, dense, stream); break;
-        default: break;
-        }
-    }
     CLADA_DECODE_CASE(2, 1, 8, 2, 2)
     CLADA_DECODE_CASE(2, 2, 8, 2, 2)
     CLADA_DECODE_CASE(2, 4, 8, 2, 2)
-    CLADA_DECODE_CASE(2, 8, 8, 2, 1)
+    CLADA_DECODE_CASE(2, 8, 8, 1, 1)
     CLADA_DECODE_CASE(2, 10, 8, 1, 1)
     CLADA_DECODE_CASE(2, 16, 8, 1, 1)
     CLADA_DECODE_CASE(4, 1, 8, 2, 2)
     CLADA_DECODE_CASE(4, 2, 8, 2, 2)
     CLADA_DECODE_CASE(4, 4, 8, 2, 2)
-    CLADA_DECODE_CASE(4, 8, 8, 2, 1)
+    CLADA_DECODE_CASE(4, 8, 8, 1, 1)
     CLADA_DECODE_CASE(4, 16, 8, 1, 1)
 #undef CLADA_DECODE_CASE
     CLADA_CHECK_HIP(ctx, e);

@@ -103,6 +103,15 @@ def test_batch_rows_independent_and_per_token_thresholds(clada):
     ctx, layer, xd, y, idx, cnt, mask = _run_sparse(clada, cfg, w, x, tau)
     _check_against_oracle(cfg, w, x, tau, y, idx, cnt, mask, "per-token tau")
     for b in range(5):
+        # a single-token call runs a different kernel (other fp32 summation order): same mask,
+        # same output within the parity tolerance
+        yb, idx_b, cnt_b, bits_b = clada.sparse_ffn_decode(ctx, layer, xd[b:b + 1].contiguous(),
+                                                           torch.from_numpy(tau[b:b + 1]).to(DEV), want_lists=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(unpack_bits(bits_b, 1500)[0], mask[b]), f"row {b}: mask differs"
+        assert_close_y(to_np(yb), to_np(y[b:b + 1]), TOL_Y[cfg.dtype], f"row {b} batched vs single-token")
+    ctx.set_option("decode.b1", 0)            # same kernel for both: bit-identical rows
+    for b in range(5):
         yb = clada.sparse_ffn_decode(ctx, layer, xd[b:b + 1].contiguous(), torch.from_numpy(tau[b:b + 1]).to(DEV))
         torch.cuda.synchronize()
         assert torch.equal(yb[0], y[b]), f"row {b} differs between batched and single-token call"
@@ -154,8 +163,8 @@ def test_full_size_7b_layer_bench_configuration(clada):
         assert_close_y(to_np(yd), oracle.dense_decode(*w, x), TOL_Y["bf16"], "7B dense twin")
 
 
-def test_cooperative_and_generic_paths_agree(clada):
-    """Batch-1 calls take the single-kernel cooperative path; the generic multi-kernel path must
+def test_batch1_and_generic_paths_agree(clada):
+    """Batch-1 calls take the single-kernel split-d kernel; the generic multi-kernel path must
     give the same mask and the same output up to fp32 summation order."""
     for cfg_name, d, F in (("c2", 4096, 5000), ("c1", 512, 1376), ("c5", 5120, 13824)):
         cfg, w, x = _case(cfg_name, 7, d, F, 1)
@@ -164,21 +173,22 @@ def test_cooperative_and_generic_paths_agree(clada):
         layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
         xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
         outs = {}
-        for coop in (1, 0):
-            ctx.set_option("decode.coop", coop)
+        for coop in (2, 1, 0):
+            ctx.set_option("decode.b1", coop)
             y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, td, want_lists=True)
             yd = clada.dense_ffn_decode(ctx, layer, xd)
             torch.cuda.synchronize()
             outs[coop] = (to_np(y), idx.cpu().numpy(), cnt.cpu().numpy(), to_np(yd))
             _check_against_oracle(cfg, w, x, tau, y, idx.cpu().numpy(), cnt.cpu().numpy(), unpack_bits(bits, F),
                                   f"{cfg_name} coop={coop}")
-        assert np.array_equal(outs[1][1], outs[0][1]) and np.array_equal(outs[1][2], outs[0][2])
-        assert_close_y(outs[1][0], outs[0][0], TOL_Y[cfg.dtype], "coop vs generic")
-        assert_close_y(outs[1][3], outs[0][3], TOL_Y[cfg.dtype], "dense coop vs generic")
+        for c in (1, 2):
+            assert np.array_equal(outs[c][1], outs[0][1]) and np.array_equal(outs[c][2], outs[0][2])
+            assert_close_y(outs[c][0], outs[0][0], TOL_Y[cfg.dtype], "batch-1 path vs generic")
+            assert_close_y(outs[c][3], outs[0][3], TOL_Y[cfg.dtype], "dense batch-1 path vs generic")
 
 
-@pytest.mark.parametrize("own_first", [1, 3, 20, 56])
-def test_cooperative_balancing_any_own_first(clada, own_first):
+@pytest.mark.parametrize("own_first", [1, 5, 9, 14])
+def test_balancing_any_own_first(clada, own_first):
     """The surplus hand-over must be exact for every split between own and pooled neurons,
     including very sparse and fully dense masks."""
     cfg, w, x = _case("c2", 8, 4096, 11008, 1)
