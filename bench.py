@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="run only a short fixed call sequence (for rocprofv3 --pmc counter runs) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (see DESIGN.md, sharding note)",
@@ -52,6 +54,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS[args.config]
+    if args.pmc_probe:
+        return pmc_probe(cfg, args, clada, binding, synth, torch, dev)
     L = args.layers or cfg.L
     d, F, B, T, V = cfg.d, cfg.d_ff, cfg.B, cfg.T, cfg.V
     K, W = args.steps, args.warmup
@@ -304,6 +308,44 @@ def main():
                                "sample": f"{n_done} layer-steps (layers 0..{n_host - 1}) of the same workload, "
                                          f"{per_layer * 1e3:.1f} ms each, extrapolated linearly to L={L}"}
     print(json.dumps(out))
+
+
+def pmc_probe(cfg, args, clada, binding, synth, torch, dev):
+    """Short fixed workload for hardware-counter runs: 4 seeded layers of the configuration, 3 rounds of
+    sparse calls at two sparsities (0.45 and 0.62), 4 dense-twin calls, 3 copies of a 256 MiB buffer
+    (the known-size transfer the FETCH_SIZE / WRITE_SIZE counters are scaled by)."""
+    d, F = cfg.d, cfg.d_ff
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, 0, 0))
+    for opt in args.option:
+        k, v = opt.split("=")
+        ctx.set_option(k, int(v))
+
+    def to_dev(a):
+        if cfg.dtype == "bf16":
+            return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+
+    layers = [clada.Layer(*[to_dev(a) for a in synth.layer_weights(cfg, args.seed, l)]) for l in range(4)]
+    x = to_dev(synth.decode_hidden(cfg, args.seed, 0, 0, B=1))
+    # thresholds at the two sparsities from the library's own prefill statistics of layer 0
+    st = clada.prefix_stats(ctx := clada.Context(0, clada.workspace_bytes(d, F, 1, cfg.T, 0)), layers[0],
+                            to_dev(synth.prefix_hidden(cfg, args.seed, 0)), want_y=False)
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for q in (0.45, 0.62):
+        tau = clada.threshold_calibrate(ctx, st.abs_act_pool, q)
+        kept = []
+        for _ in range(3):
+            for layer in layers:
+                _, _, cnt, _ = clada.sparse_ffn_decode(ctx, layer, x, tau, want_lists=True)
+                kept.append(int(cnt[0]))
+        print(f"pmc-probe q={q}: kept per call {kept}")
+    for layer in layers:
+        clada.dense_ffn_decode(ctx, layer, x)
+    for _ in range(3):
+        binding.diag_copy(ctx, src, dst)
+    torch.cuda.synchronize()
+    print(f"pmc-probe copy bytes {src.numel()}")
 
 
 def _traffic():

@@ -229,3 +229,26 @@ def test_graph_replay_matches_eager(clada):
         y2 = clada.sparse_ffn_decode(ctx, layer, xd, td)          # eager call between replays
         torch.cuda.synchronize()
         assert torch.equal(y2, y_eager)
+
+
+@pytest.mark.parametrize("cfg_name,layer_id", [("c3", 5), ("c4", 11), ("c5", 20)])
+def test_full_size_other_configurations(clada, cfg_name, layer_id):
+    """One full-size layer of the Mistral-7B (B=8), LLaMA-3-8B (B=1) and LLaMA2-13B (B=16)
+    shapes, per-token thresholds spread by the four indicator factors; every output element,
+    every mask bit and the union list are checked against the oracle."""
+    cfg = synth.CONFIGS[cfg_name]
+    d, F, B = cfg.d, cfg.d_ff, cfg.B
+    w = synth.layer_weights(cfg, 0, layer_id)
+    x = synth.decode_hidden(cfg, 0, layer_id, 0)
+    factors = np.resize(np.array([1.0, 1.80, 1.12, 1.92], np.float32), B)
+    tau = _tau_for(w, x, cfg.q) * factors
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, B, 0, 0))
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV),
+                                                want_lists=True)
+    torch.cuda.synchronize()
+    cnt = cnt.cpu().numpy()
+    _check_against_oracle(cfg, w, x, tau, y, idx.cpu().numpy(), cnt, unpack_bits(bits, F),
+                          f"{cfg_name} layer {layer_id}")
+    if B > 1:       # independent tokens: the union is nearly everything, each row keeps its own sparsity
+        assert cnt[0] > 0.95 * F and np.all(cnt[1:] < 0.75 * F)
