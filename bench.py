@@ -315,7 +315,7 @@ def pmc_probe(cfg, args, clada, binding, synth, torch, dev):
     sparse calls at two sparsities (0.45 and 0.62), 4 dense-twin calls, 3 copies of a 256 MiB buffer
     (the known-size transfer the FETCH_SIZE / WRITE_SIZE counters are scaled by)."""
     d, F = cfg.d, cfg.d_ff
-    ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, 0, 0))
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, cfg.T, 0))
     for opt in args.option:
         k, v = opt.split("=")
         ctx.set_option(k, int(v))
@@ -328,8 +328,7 @@ def pmc_probe(cfg, args, clada, binding, synth, torch, dev):
     layers = [clada.Layer(*[to_dev(a) for a in synth.layer_weights(cfg, args.seed, l)]) for l in range(4)]
     x = to_dev(synth.decode_hidden(cfg, args.seed, 0, 0, B=1))
     # thresholds at the two sparsities from the library's own prefill statistics of layer 0
-    st = clada.prefix_stats(ctx := clada.Context(0, clada.workspace_bytes(d, F, 1, cfg.T, 0)), layers[0],
-                            to_dev(synth.prefix_hidden(cfg, args.seed, 0)), want_y=False)
+    st = clada.prefix_stats(ctx, layers[0], to_dev(synth.prefix_hidden(cfg, args.seed, 0)), want_y=False)
     src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
     for q in (0.45, 0.62):

@@ -55,6 +55,7 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->ws = nullptr;
     ctx->opt_decode_wgs_per_cu = 1;
     ctx->opt_decode_b1 = 1;
+    ctx->opt_decode_batched = 1;
     ctx->opt_decode_own_first = 0;
     ctx->err[0] = 0;
     if (workspace_bytes > 0) {
@@ -113,6 +114,11 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
     if (!strcmp(name, "decode.b1")) {
         if (value < 0 || value > 2) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.b1=%d outside [0,2]", value);
         ctx->opt_decode_b1 = value;
+        return CLADA_OK;
+    }
+    if (!strcmp(name, "decode.batched")) {
+        if (value < 0 || value > 1) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.batched=%d outside [0,1]", value);
+        ctx->opt_decode_batched = value;
         return CLADA_OK;
     }
     if (!strcmp(name, "decode.own_first")) {

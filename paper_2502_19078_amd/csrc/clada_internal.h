@@ -15,6 +15,7 @@ struct clada_ctx {
     int opt_decode_wgs_per_cu;   // launch shape of the decode kernel (clada_set_option)
     int opt_decode_b1;           // batch-1 split-d kernel: 0 off (generic kernels), 1 with balancing, 2 without
     int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
+    int opt_decode_batched;      // 1: MFMA path for 2 <= B <= 16 (bf16), 0: generic kernels
     char err[512];
 };
 
@@ -47,6 +48,14 @@ static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; 
 
 // Validation shared by the FFN calls.
 clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer);
+
+// Batched (B >= 2, bf16) MFMA decode path; *ran tells whether the shape was eligible and it ran.
+clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, const void *x, int32_t B,
+                                  const float *tau, void *y, unsigned char *keep, float *partial,
+                                  char *scratch, bool dense, hipStream_t stream, bool *ran);
+size_t clada_ws_decode_batched(int32_t d_ff);
+// Fixed-order sum of P partial y's [P][B][d] (fp32) into y (element size es).
+void clada_launch_finalize(int es, const float *partial, int P, int B, int d, char *y, hipStream_t stream);
 
 // Workspace needs of the individual calls (bytes beyond the header).
 size_t clada_ws_decode(int32_t d, int32_t d_ff, int32_t B);

@@ -827,6 +827,21 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             return CLADA_OK;
         }
     }
+    // ---- batched MFMA path (2 <= B <= 16, bf16, supported widths)
+    if (B >= 2 && ctx->opt_decode_batched) {
+        unsigned char *keep_region = reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256));
+        char *scratch = reinterpret_cast<char *>(keep_region) + align_up((size_t)B * F, 256);
+        bool ran = false;
+        st = clada_decode_batched(ctx, layer, x, B, tau, y, p.keep, p.partial, scratch, dense, stream, &ran);
+        if (st != CLADA_OK) return st;
+        if (ran) {
+            if (lists) {
+                hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
+                CLADA_CHECK_HIP(ctx, hipGetLastError());
+            }
+            return CLADA_OK;
+        }
+    }
 #define CLADA_DECODE_CASE(ES_, NCH_, NW_, GB_, UB_)                                        \
     if (es == ES_ && nch <= NCH_ && e == hipErrorInvalidValue)                             \
         e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, dense, stream);
@@ -855,10 +870,16 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
 
 }  // namespace
 
+void clada_launch_finalize(int es, const float *partial, int P, int B, int d, char *y, hipStream_t stream)
+{
+    launch_finalize(es, partial, P, B, d, y, nullptr, stream);
+}
+
 size_t clada_ws_decode(int32_t d, int32_t d_ff, int32_t B)
 {
     if (B <= 0) return 0;
-    return align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256) + align_up((size_t)B * d_ff, 256);
+    return align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256) + align_up((size_t)B * d_ff, 256) +
+           clada_ws_decode_batched(d_ff);
 }
 
 extern "C" clada_status clada_sparse_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,

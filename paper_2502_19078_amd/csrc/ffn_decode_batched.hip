@@ -1,0 +1,340 @@
+// Batched (2 <= B <= 16) thresholded sparse SwiGLU FFN at decode time on the matrix cores
+// (algorithm "CLADA Inference", generation phase; bf16 layers).  With B tokens every weight
+// element feeds B multiply-adds, which the vector ALUs cannot sustain at HBM speed, so the
+// three projections run as MFMA 16x16x32 (bf16 in, fp32 accumulate) with the tokens as the
+// 16-wide M dimension.  Weights are still read once, and only for neurons kept by at least
+// one token (the union); every output row uses its own mask.
+//
+//   kernel A (gate + up -> h): workgroup p owns the 16-neuron tiles p, p+P, ...  Its 8 waves
+//     split the d (= K) dimension: wave w keeps its slice of x as MFMA A-fragments in registers
+//     for the whole kernel and streams its slice of the 16 weight rows as B-fragments (lane =
+//     (neuron, 16-byte k-group): a row's 64 bytes per instruction, the row's whole slice over
+//     the k loop).  The 8 partial 16x16 tiles are summed through LDS in fixed order; SiLU, the
+//     per-token fp32 compare and the per-neuron 16-bit keep masks follow.  A ballot compacts
+//     the workgroup's union-kept neurons; the same MFMA loop over W_up rows gathered through
+//     that list gives u, and h = keep ? a*u : 0 goes to a [16][d_ff] fp32 buffer.
+//   kernel B (down): 2-D split -- column groups of 256 x row groups of the compacted union
+//     list (a fixed contiguous range each), so only R partial y's exist instead of one per
+//     workgroup.  W_down rows arrive as 512-byte segments, are staged per wave in LDS and read
+//     back K-major with ds_read_b64_tr_b16 as MFMA B-fragments; h is split into bf16 hi + lo
+//     A-fragments (two MFMAs), so the down projection keeps ~fp32 accuracy of h.
+//   kernel C: k_ffn_finalize adds the R partials in fixed order.
+#include "clada_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+struct BatParams {
+    const char *wg, *wu, *wd, *x;
+    const float *tau;           // [B]
+    float *hbuf;                // [16][F] fp32, written for union-kept neurons only
+    int *ulist;                 // [P][64] neuron ids of each workgroup's union-kept neurons (ascending)
+    int *ucnt;                  // [P]
+    unsigned char *keep;        // [B][F] or nullptr
+    float *partial;             // [RG][B][d]
+    int d, F, B, P, RG, CG;
+};
+
+__device__ __forceinline__ f32x4 mfma16(const u32x4 a, const u32x4 b, const f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+constexpr int MAX_TILES = 8;    // 16-neuron tiles per workgroup in kernel A
+
+// KSTEPS = k-steps of 32 per wave: d = 8 waves * KSTEPS * 32.
+template <int KSTEPS, bool DENSE>
+__global__ void __launch_bounds__(512)
+k_bat_gateup(const BatParams p)
+{
+    __shared__ float s_part[2][8][256];
+    __shared__ float s_a[MAX_TILES][16][16];
+    __shared__ int s_km[MAX_TILES * 16];
+    __shared__ int s_ul[MAX_TILES * 16];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, q = lane >> 4;
+    const int blk = blockIdx.x, P = gridDim.x;
+    const int d = p.d, F = p.F, B = p.B;
+    const size_t rowb = (size_t)d * 2;
+    const int koff = (wave * KSTEPS * 32 + 8 * q) * 2;      // byte offset of this lane's first k-group
+    const int nt = (F + 15) / 16;
+    const int ni = blk < nt ? (nt - blk + P - 1) / P : 0;   // <= MAX_TILES
+
+    if (tid < MAX_TILES * 16) s_km[tid] = 0;
+    // this wave's slice of x as A-fragments: lane = (token n, k-group q)
+    u32x4 xa[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (n < B) v = *reinterpret_cast<const u32x4 *>(p.x + (size_t)n * rowb + koff + ks * 64);
+        xa[ks] = v;
+    }
+    __syncthreads();
+
+    // D = X_slice * W_slice^T for 16 weight rows given per lane, partial over this wave's k-slice
+    auto tile_partial = [&](const char *w, int row, int buf) {
+        const char *src = w + (size_t)row * rowb + koff;
+        u32x4 wf[KSTEPS];
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) wf[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + ks * 64));
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) acc = mfma16(xa[ks], wf[ks], acc);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s_part[buf][wave][r * 64 + lane] = acc[r];
+    };
+    // element (r, ln) of the 16x16 tile: token m = 4*(ln/16) + r, neuron ln%16; waves summed in order
+    auto tile_sum = [&](int buf, int e) {
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) s += s_part[buf][w][e];
+        return s;
+    };
+
+    // ---------------------------------------------------------------- gate tiles
+    for (int i = 0; i < ni; ++i) {
+        const int t = blk + P * i;
+        tile_partial(p.wg, min(16 * t + n, F - 1), i & 1);
+        __syncthreads();
+        if (tid < 256) {
+            const int r = tid >> 6, ln = tid & 63;
+            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = 16 * t + nn;
+            const float a = silu_f32(tile_sum(i & 1, tid));
+            const bool valid = m < B && j < F;
+            const bool keep = valid && (DENSE ? true : (fabsf(a) >= p.tau[m]));
+            s_a[i][m][nn] = a;
+            if (keep) atomicOr(&s_km[i * 16 + nn], 1 << m);
+            if (p.keep && valid) p.keep[(size_t)m * F + j] = keep ? 1 : 0;
+        }
+    }
+    __syncthreads();
+
+    // ---------------------------------------------------------------- union compaction (every wave)
+    const bool mine = lane < ni * 16 && s_km[lane] != 0;
+    const unsigned long long bal = __ballot(mine);
+    const int ku = __popcll(bal);
+    if (mine) s_ul[__popcll(bal & ((1ull << lane) - 1ull))] = lane;
+    if (wave == 0) {
+        if (mine) p.ulist[blk * 64 + __popcll(bal & ((1ull << lane) - 1ull))] = 16 * (blk + P * (lane >> 4)) + (lane & 15);
+        if (lane == 0) p.ucnt[blk] = ku;
+    }
+
+    // ---------------------------------------------------------------- up tiles over the union list
+    const int nu = (ku + 15) / 16;
+    for (int u = 0; u < nu; ++u) {
+        const int e = 16 * u + n;
+        const int li = s_ul[e < ku ? e : 0];
+        tile_partial(p.wu, 16 * (blk + P * (li >> 4)) + (li & 15), u & 1);
+        __syncthreads();
+        if (tid < 256) {
+            const int r = tid >> 6, ln = tid & 63;
+            const int m = 4 * (ln >> 4) + r, nn = ln & 15;
+            const int e2 = 16 * u + nn;
+            if (e2 < ku) {
+                const int l2 = s_ul[e2];
+                const int j = 16 * (blk + P * (l2 >> 4)) + (l2 & 15);
+                const float usum = tile_sum(u & 1, tid);
+                const bool keep = (s_km[l2] >> m) & 1;
+                p.hbuf[(size_t)m * F + j] = keep ? s_a[l2 >> 4][m][l2 & 15] * usum : 0.0f;
+            }
+        }
+    }
+}
+
+constexpr int DN_COLS = 256;                    // columns per workgroup in kernel B
+constexpr int DN_SUB = 128;                     // columns staged per pass
+constexpr int DN_PITCH = DN_SUB * 2 + 32;       // LDS row pitch (bytes): 4 rows of a transpose read hit distinct banks
+constexpr int DN_TILE_BYTES = 32 * DN_PITCH;    // one wave's staging tile: 32 neurons x 128 columns
+constexpr int DN_MAX_ROWS = 2048;               // union neurons per row group
+
+__global__ void __launch_bounds__(512)
+k_bat_down(const BatParams p)
+{
+    extern __shared__ __align__(16) unsigned char smem_dn[];
+    unsigned char *s_tile = smem_dn;                                    // [8][DN_TILE_BYTES], later the fold buffers
+    int *s_rows = reinterpret_cast<int *>(smem_dn + 8 * DN_TILE_BYTES); // [DN_MAX_ROWS]
+    __shared__ int s_scan[8];
+    __shared__ int s_rng[2];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cg = blockIdx.x % p.CG, rg = blockIdx.x / p.CG;
+    const int d = p.d, F = p.F, B = p.B;
+    const size_t rowb = (size_t)d * 2;
+    const int col0 = cg * DN_COLS;
+
+    // ---- this row group's contiguous range of the compacted union list (workgroup-major order)
+    const int cnt = tid < p.P ? p.ucnt[tid] : 0;
+    int inc = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) s_scan[wave] = inc;
+    __syncthreads();
+    int base = 0, K = 0;
+    for (int w = 0; w < 8; ++w) {
+        if (w < wave) base += s_scan[w];
+        K += s_scan[w];
+    }
+    const int pre = base + inc - cnt;
+    const int lo = (int)((long long)rg * K / p.RG), hi = (int)((long long)(rg + 1) * K / p.RG);
+    const int nrows = hi - lo;                                          // <= DN_MAX_ROWS (host check on F)
+    for (int r = max(lo, pre); r < min(hi, pre + cnt); ++r) s_rows[r - lo] = p.ulist[tid * 64 + (r - pre)];
+    __syncthreads();
+
+    f32x4 acc[DN_COLS / 16];
+#pragma unroll
+    for (int t = 0; t < DN_COLS / 16; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int n = lane & 15, q = lane >> 4;
+    unsigned char *tile = s_tile + wave * DN_TILE_BYTES;
+    const int nkb = (nrows + 31) / 32;
+    for (int kb = wave; kb < nkb; kb += 8) {
+        // A-fragments: h[token n][8 consecutive list entries], split into bf16 hi + lo
+        u32x4 ahi, alo;
+        {
+            unsigned int hi16[8], lo16[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = 32 * kb + 8 * q + i;
+                const float hv = (e < nrows && n < B) ? p.hbuf[(size_t)n * F + s_rows[e]] : 0.0f;
+                hi16[i] = f32_to_bf16_bits(hv);
+                lo16[i] = f32_to_bf16_bits(hv - __uint_as_float(hi16[i] << 16));
+            }
+            ahi = u32x4{hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
+            alo = u32x4{lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
+        }
+#pragma unroll
+        for (int sub = 0; sub < DN_COLS / DN_SUB; ++sub) {
+            // stage W_down[32 list entries][128 columns]: lane pair halves read 256-byte row pieces
+            u32x4 wv[8];
+#pragma unroll
+            for (int ii = 0; ii < 8; ++ii) {
+                const int c = lane + 64 * ii, row = c >> 4, cc = c & 15;
+                const int e = 32 * kb + row;
+                const int col = col0 + sub * DN_SUB + 8 * cc;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (e < nrows && col < d)
+                    v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.wd + (size_t)s_rows[e] * rowb + (size_t)col * 2));
+                wv[ii] = v;
+            }
+#pragma unroll
+            for (int ii = 0; ii < 8; ++ii) {
+                const int c = lane + 64 * ii, row = c >> 4, cc = c & 15;
+                *reinterpret_cast<u32x4 *>(tile + row * DN_PITCH + cc * 16) = wv[ii];
+            }
+            // K-major B-fragments by transpose reads: in each 16-lane group lane t = 4r + c4 supplies
+            // row 8q + r, columns 4*c4 .. 4*c4+3 and receives column t of rows 8q .. 8q+3
+            const int r = (lane & 15) >> 2, c4 = lane & 3;
+#pragma unroll
+            for (int t = 0; t < DN_SUB / 16; ++t) {
+                const unsigned char *src = tile + (8 * q + r) * DN_PITCH + (t * 16 + 4 * c4) * 2;
+                const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)src);
+                const s16x4 b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(src + 4 * DN_PITCH));
+                const uint2 u0 = __builtin_bit_cast(uint2, b0), u1 = __builtin_bit_cast(uint2, b1);
+                const u32x4 bf = {u0.x, u0.y, u1.x, u1.y};
+                const int ti = sub * (DN_SUB / 16) + t;
+                acc[ti] = mfma16(ahi, bf, acc[ti]);
+                acc[ti] = mfma16(alo, bf, acc[ti]);
+            }
+        }
+    }
+
+    // ---- fixed-order fold of the waves' accumulators through LDS, then the partial y of this row group
+    __syncthreads();
+    float *s_red = reinterpret_cast<float *>(s_tile);                   // [4][16 tiles][4][64]
+    constexpr int ACC_FLOATS = (DN_COLS / 16) * 4 * 64;
+#pragma unroll
+    for (int s = 4; s >= 1; s >>= 1) {
+        if (wave >= s && wave < 2 * s) {
+            float *dst = s_red + (size_t)(wave - s) * ACC_FLOATS;
+#pragma unroll
+            for (int t = 0; t < DN_COLS / 16; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dst[(t * 4 + r) * 64 + lane] = acc[t][r];
+        }
+        __syncthreads();
+        if (wave < s) {
+            const float *src = s_red + (size_t)wave * ACC_FLOATS;
+#pragma unroll
+            for (int t = 0; t < DN_COLS / 16; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[t][r] += src[(t * 4 + r) * 64 + lane];
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+#pragma unroll
+        for (int t = 0; t < DN_COLS / 16; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = 4 * q + r, col = col0 + t * 16 + n;
+                if (m < B && col < d) p.partial[((size_t)rg * B + m) * d + col] = acc[t][r];
+            }
+    }
+}
+
+}  // namespace
+
+size_t clada_ws_decode_batched(int32_t d_ff)
+{
+    return align_up(sizeof(float) * 16 * (size_t)d_ff, 256) + align_up(sizeof(int) * 65 * COOP_MAX_WGS, 256);
+}
+
+// Returns CLADA_OK when the batched MFMA path ran, CLADA_ERR_SHAPE (without touching ctx->err) when
+// the shape is not eligible and the caller should use the generic kernels.
+clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, const void *x, int32_t B,
+                                  const float *tau, void *y, unsigned char *keep, float *partial,
+                                  char *scratch, bool dense, hipStream_t stream, bool *ran)
+{
+    *ran = false;
+    const int d = layer->d, F = layer->d_ff;
+    if (layer->dtype != CLADA_BF16 || B < 2 || B > 16) return CLADA_OK;
+    if (d % 256 != 0 || (d != 4096 && d != 5120 && d != 1024 && d != 2048)) return CLADA_OK;
+    const int P = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
+    const int nt = (F + 15) / 16;
+    if ((nt + P - 1) / P > MAX_TILES) return CLADA_OK;
+    const int CG = (d + DN_COLS - 1) / DN_COLS;
+    int RG = P / CG;
+    if (RG < 1) RG = 1;
+    if (RG > 16) RG = 16;
+    if ((F + RG - 1) / RG + 64 > DN_MAX_ROWS) return CLADA_OK;
+
+    BatParams p;
+    p.wg = (const char *)layer->w_gate; p.wu = (const char *)layer->w_up; p.wd = (const char *)layer->w_down;
+    p.x = (const char *)x; p.tau = tau;
+    p.hbuf = reinterpret_cast<float *>(scratch);
+    p.ulist = reinterpret_cast<int *>(scratch + align_up(sizeof(float) * 16 * (size_t)F, 256));
+    p.ucnt = p.ulist + 64 * COOP_MAX_WGS;
+    p.keep = keep; p.partial = partial;
+    p.d = d; p.F = F; p.B = B; p.P = P; p.RG = RG; p.CG = CG;
+
+#define CLADA_BAT_CASE(KS)                                                                            \
+    if (d == 8 * 32 * KS) {                                                                            \
+        if (dense) hipLaunchKernelGGL((k_bat_gateup<KS, true>), dim3(P), dim3(512), 0, stream, p);    \
+        else       hipLaunchKernelGGL((k_bat_gateup<KS, false>), dim3(P), dim3(512), 0, stream, p);   \
+    }
+    CLADA_BAT_CASE(4) CLADA_BAT_CASE(8) CLADA_BAT_CASE(16) CLADA_BAT_CASE(20)
+#undef CLADA_BAT_CASE
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    const size_t lds = 8 * (size_t)DN_TILE_BYTES + sizeof(int) * DN_MAX_ROWS;
+    static bool attr_set = false;
+    if (!attr_set) {
+        CLADA_CHECK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_bat_down),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_bat_down, dim3(CG * RG), dim3(512), lds, stream, p);
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    clada_launch_finalize(2, partial, RG, B, d, (char *)y, stream);
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    *ran = true;
+    return CLADA_OK;
+}

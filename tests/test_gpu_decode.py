@@ -110,7 +110,10 @@ def test_batch_rows_independent_and_per_token_thresholds(clada):
         torch.cuda.synchronize()
         assert np.array_equal(unpack_bits(bits_b, 1500)[0], mask[b]), f"row {b}: mask differs"
         assert_close_y(to_np(yb), to_np(y[b:b + 1]), TOL_Y[cfg.dtype], f"row {b} batched vs single-token")
-    ctx.set_option("decode.b1", 0)            # same kernel for both: bit-identical rows
+    # generic kernels for both the batched and the single-token call: bit-identical rows
+    ctx.set_option("decode.b1", 0)
+    ctx.set_option("decode.batched", 0)
+    y = clada.sparse_ffn_decode(ctx, layer, xd, torch.from_numpy(tau).to(DEV))
     for b in range(5):
         yb = clada.sparse_ffn_decode(ctx, layer, xd[b:b + 1].contiguous(), torch.from_numpy(tau[b:b + 1]).to(DEV))
         torch.cuda.synchronize()
