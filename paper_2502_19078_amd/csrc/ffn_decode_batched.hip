@@ -12,10 +12,11 @@
 //     the k loop).  The 8 partial 16x16 tiles are summed through LDS in fixed order; SiLU, the
 //     per-token fp32 compare and the per-neuron 16-bit keep masks follow.  A ballot compacts
 //     the workgroup's union-kept neurons; the same MFMA loop over W_up rows gathered through
-//     that list gives u, and h = keep ? a*u : 0 goes to a [16][d_ff] fp32 buffer.
-//   kernel B (down): 2-D split -- column groups of 256 x row groups of the compacted union
-//     list (a fixed contiguous range each), so only R partial y's exist instead of one per
-//     workgroup.  W_down rows arrive as 512-byte segments, are staged per wave in LDS and read
+//     that list gives u, and h = keep ? a*u : 0 goes to a [16][d_ff] fp32 buffer, together with
+//     one union flag per neuron.
+//   kernel B (down): 2-D split -- column groups of 256 x row groups (a fixed range of neuron
+//     indices each, its kept neurons compacted from the union flags by ballot + scan), so only
+//     R partial y's exist instead of one per workgroup.  W_down rows arrive as 512-byte segments, are staged per wave in LDS and read
 //     back K-major with ds_read_b64_tr_b16 as MFMA B-fragments; h is split into bf16 hi + lo
 //     A-fragments (two MFMAs), so the down projection keeps ~fp32 accuracy of h.
 //   kernel C: k_ffn_finalize adds the R partials in fixed order.
@@ -31,8 +32,7 @@ struct BatParams {
     const char *wg, *wu, *wd, *x;
     const float *tau;           // [B]
     float *hbuf;                // [16][F] fp32, written for union-kept neurons only
-    int *ulist;                 // [P][64] neuron ids of each workgroup's union-kept neurons (ascending)
-    int *ucnt;                  // [P]
+    unsigned char *uflag;       // [F] 1 iff the neuron is kept by at least one token
     unsigned char *keep;        // [B][F] or nullptr
     float *partial;             // [RG][B][d]
     int d, F, B, P, RG, CG;
@@ -43,7 +43,7 @@ __device__ __forceinline__ f32x4 mfma16(const u32x4 a, const u32x4 b, const f32x
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-constexpr int MAX_TILES = 8;    // 16-neuron tiles per workgroup in kernel A
+constexpr int MAX_TILES = 4;    // 16-neuron tiles per workgroup in kernel A (one 64-lane ballot compacts them)
 
 // KSTEPS = k-steps of 32 per wave: d = 8 waves * KSTEPS * 32.
 template <int KSTEPS, bool DENSE>
@@ -76,17 +76,47 @@ k_bat_gateup(const BatParams p)
     }
     __syncthreads();
 
-    // D = X_slice * W_slice^T for 16 weight rows given per lane, partial over this wave's k-slice
-    auto tile_partial = [&](const char *w, int row, int buf) {
-        const char *src = w + (size_t)row * rowb + koff;
-        u32x4 wf[KSTEPS];
+    // B-fragments of 16 weight rows (one per lane n): half h of this wave's k-slice
+    constexpr int KH = KSTEPS / 2;
+    auto half_load = [&](u32x4 (&wf)[KH], const char *w, int row, int h) {
+        const char *src = w + (size_t)row * rowb + koff + h * KH * 64;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) wf[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + ks * 64));
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < KH; ++ks) wf[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + ks * 64));
+    };
+    auto half_mma = [&](const u32x4 (&wf)[KH], int h, f32x4 acc) {
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) acc = mfma16(xa[ks], wf[ks], acc);
+        for (int ks = 0; ks < KH; ++ks) acc = mfma16(xa[h * KH + ks], wf[ks], acc);
+        return acc;
+    };
+    auto part_store = [&](const f32x4 acc, int buf) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) s_part[buf][wave][r * 64 + lane] = acc[r];
+    };
+    // One pass over a list of tiles: D = X_slice * W_slice^T partial over this wave's k-slice.  The
+    // two halves of the next tile are requested while the current tile is multiplied and reduced;
+    // every path keeps a fixed number of loads in flight.
+    auto tile_pass = [&](const char *w, int ntiles, auto row_of, auto reduce) {
+        u32x4 wa[KH], wb[KH];
+        if (ntiles > 0) {
+            half_load(wa, w, row_of(0), 0);
+            half_load(wb, w, row_of(0), 1);
+        }
+        for (int i = 0; i < ntiles; ++i) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            if (i + 1 < ntiles) {
+                const int nr = row_of(i + 1);
+                acc = half_mma(wa, 0, acc);
+                half_load(wa, w, nr, 0);
+                acc = half_mma(wb, 1, acc);
+                half_load(wb, w, nr, 1);
+            } else {
+                acc = half_mma(wa, 0, acc);
+                acc = half_mma(wb, 1, acc);
+            }
+            part_store(acc, i & 1);
+            __syncthreads();
+            reduce(i);
+        }
     };
     // element (r, ln) of the 16x16 tile: token m = 4*(ln/16) + r, neuron ln%16; waves summed in order
     auto tile_sum = [&](int buf, int e) {
@@ -95,15 +125,11 @@ k_bat_gateup(const BatParams p)
         for (int w = 0; w < 8; ++w) s += s_part[buf][w][e];
         return s;
     };
-
-    // ---------------------------------------------------------------- gate tiles
-    for (int i = 0; i < ni; ++i) {
-        const int t = blk + P * i;
-        tile_partial(p.wg, min(16 * t + n, F - 1), i & 1);
-        __syncthreads();
+    auto gate_row = [&](int i) { return min(16 * (blk + P * i) + n, F - 1); };
+    auto gate_reduce = [&](int i) {
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
-            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = 16 * t + nn;
+            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = 16 * (blk + P * i) + nn;
             const float a = silu_f32(tile_sum(i & 1, tid));
             const bool valid = m < B && j < F;
             const bool keep = valid && (DENSE ? true : (fabsf(a) >= p.tau[m]));
@@ -111,7 +137,10 @@ k_bat_gateup(const BatParams p)
             if (keep) atomicOr(&s_km[i * 16 + nn], 1 << m);
             if (p.keep && valid) p.keep[(size_t)m * F + j] = keep ? 1 : 0;
         }
-    }
+    };
+
+    // ---------------------------------------------------------------- gate tiles
+    tile_pass(p.wg, ni, gate_row, gate_reduce);
     __syncthreads();
 
     // ---------------------------------------------------------------- union compaction (every wave)
@@ -119,18 +148,19 @@ k_bat_gateup(const BatParams p)
     const unsigned long long bal = __ballot(mine);
     const int ku = __popcll(bal);
     if (mine) s_ul[__popcll(bal & ((1ull << lane) - 1ull))] = lane;
-    if (wave == 0) {
-        if (mine) p.ulist[blk * 64 + __popcll(bal & ((1ull << lane) - 1ull))] = 16 * (blk + P * (lane >> 4)) + (lane & 15);
-        if (lane == 0) p.ucnt[blk] = ku;
+    if (wave == 0 && lane < ni * 16) {                      // union flag of every owned neuron, for kernel B
+        const int j = 16 * (blk + P * (lane >> 4)) + (lane & 15);
+        if (j < F) p.uflag[j] = mine ? 1 : 0;
     }
 
     // ---------------------------------------------------------------- up tiles over the union list
     const int nu = (ku + 15) / 16;
-    for (int u = 0; u < nu; ++u) {
+    auto up_row = [&](int u) {
         const int e = 16 * u + n;
         const int li = s_ul[e < ku ? e : 0];
-        tile_partial(p.wu, 16 * (blk + P * (li >> 4)) + (li & 15), u & 1);
-        __syncthreads();
+        return 16 * (blk + P * (li >> 4)) + (li & 15);
+    };
+    auto up_reduce = [&](int u) {
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
             const int m = 4 * (ln >> 4) + r, nn = ln & 15;
@@ -143,7 +173,8 @@ k_bat_gateup(const BatParams p)
                 p.hbuf[(size_t)m * F + j] = keep ? s_a[l2 >> 4][m][l2 & 15] * usum : 0.0f;
             }
         }
-    }
+    };
+    tile_pass(p.wu, nu, up_row, up_reduce);
 }
 
 constexpr int DN_COLS = 256;                    // columns per workgroup in kernel B
@@ -168,26 +199,28 @@ k_bat_down(const BatParams p)
     const size_t rowb = (size_t)d * 2;
     const int col0 = cg * DN_COLS;
 
-    // ---- this row group's contiguous range of the compacted union list (workgroup-major order)
-    const int cnt = tid < p.P ? p.ucnt[tid] : 0;
-    int inc = cnt;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
-    }
-    if (lane == 63) s_scan[wave] = inc;
+    // ---- this row group's neurons [jlo, jhi): kept ones compacted in ascending order (ballot + scan)
+    const int jlo = (int)((long long)rg * F / p.RG), jhi = (int)((long long)(rg + 1) * F / p.RG);
+    if (tid == 0) s_rng[0] = 0;
     __syncthreads();
-    int base = 0, K = 0;
-    for (int w = 0; w < 8; ++w) {
-        if (w < wave) base += s_scan[w];
-        K += s_scan[w];
+    for (int j0 = jlo; j0 < jhi; j0 += 512) {
+        const int j = j0 + tid;
+        const bool k = j < jhi && p.uflag[j] != 0;
+        const unsigned long long bal = __ballot(k);
+        if (lane == 0) s_scan[wave] = __popcll(bal);
+        __syncthreads();
+        int off = s_rng[0];
+        for (int w = 0; w < wave; ++w) off += s_scan[w];
+        if (k) s_rows[off + __popcll(bal & ((1ull << lane) - 1ull))] = j;
+        __syncthreads();
+        if (tid == 0) {
+            int t = s_rng[0];
+            for (int w = 0; w < 8; ++w) t += s_scan[w];
+            s_rng[0] = t;
+        }
+        __syncthreads();
     }
-    const int pre = base + inc - cnt;
-    const int lo = (int)((long long)rg * K / p.RG), hi = (int)((long long)(rg + 1) * K / p.RG);
-    const int nrows = hi - lo;                                          // <= DN_MAX_ROWS (host check on F)
-    for (int r = max(lo, pre); r < min(hi, pre + cnt); ++r) s_rows[r - lo] = p.ulist[tid * 64 + (r - pre)];
-    __syncthreads();
+    const int nrows = s_rng[0];                                         // <= DN_MAX_ROWS (host check on F)
 
     f32x4 acc[DN_COLS / 16];
 #pragma unroll
@@ -196,54 +229,84 @@ k_bat_down(const BatParams p)
     const int n = lane & 15, q = lane >> 4;
     unsigned char *tile = s_tile + wave * DN_TILE_BYTES;
     const int nkb = (nrows + 31) / 32;
-    for (int kb = wave; kb < nkb; kb += 8) {
-        // A-fragments: h[token n][8 consecutive list entries], split into bf16 hi + lo
-        u32x4 ahi, alo;
-        {
-            unsigned int hi16[8], lo16[8];
+    static_assert(DN_COLS == 2 * DN_SUB, "two staging passes per block of neurons");
+
+    // h[token n][8 consecutive list entries] of block kb (raw fp32, converted when used)
+    auto h_load = [&](float (&hv)[8], int kb) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int e = 32 * kb + 8 * q + i;
-                const float hv = (e < nrows && n < B) ? p.hbuf[(size_t)n * F + s_rows[e]] : 0.0f;
-                hi16[i] = f32_to_bf16_bits(hv);
-                lo16[i] = f32_to_bf16_bits(hv - __uint_as_float(hi16[i] << 16));
-            }
-            ahi = u32x4{hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
-            alo = u32x4{lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
+        for (int i = 0; i < 8; ++i) {
+            const int e = 32 * kb + 8 * q + i;
+            hv[i] = (e < nrows && n < B) ? p.hbuf[(size_t)n * F + s_rows[e]] : 0.0f;
         }
+    };
+    // W_down[32 list entries][128 columns]: half-waves read 256-byte row pieces
+    auto w_load = [&](u32x4 (&wv)[8], int kb, int sub) {
 #pragma unroll
-        for (int sub = 0; sub < DN_COLS / DN_SUB; ++sub) {
-            // stage W_down[32 list entries][128 columns]: lane pair halves read 256-byte row pieces
-            u32x4 wv[8];
+        for (int ii = 0; ii < 8; ++ii) {
+            const int c = lane + 64 * ii, row = c >> 4, cc = c & 15;
+            const int e = 32 * kb + row;
+            const int col = col0 + sub * DN_SUB + 8 * cc;
+            // rows past the list repeat the last row (their h is zero); columns past d cannot
+            // occur for the supported widths (d is a multiple of 256)
+            const int er = e < nrows ? e : nrows - 1;
+            wv[ii] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.wd + (size_t)s_rows[er] * rowb + (size_t)col * 2));
+        }
+    };
+    auto process = [&](const u32x4 (&wv)[8], const u32x4 ahi, const u32x4 alo, int sub) {
 #pragma unroll
-            for (int ii = 0; ii < 8; ++ii) {
-                const int c = lane + 64 * ii, row = c >> 4, cc = c & 15;
-                const int e = 32 * kb + row;
-                const int col = col0 + sub * DN_SUB + 8 * cc;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (e < nrows && col < d)
-                    v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.wd + (size_t)s_rows[e] * rowb + (size_t)col * 2));
-                wv[ii] = v;
-            }
+        for (int ii = 0; ii < 8; ++ii) {
+            const int c = lane + 64 * ii, row = c >> 4, cc = c & 15;
+            *reinterpret_cast<u32x4 *>(tile + row * DN_PITCH + cc * 16) = wv[ii];
+        }
+        // K-major B-fragments by transpose reads: in each 16-lane group lane t = 4r + c4 supplies
+        // row 8q + r, columns 4*c4 .. 4*c4+3 and receives column t of rows 8q .. 8q+3
+        const int r = (lane & 15) >> 2, c4 = lane & 3;
 #pragma unroll
-            for (int ii = 0; ii < 8; ++ii) {
-                const int c = lane + 64 * ii, row = c >> 4, cc = c & 15;
-                *reinterpret_cast<u32x4 *>(tile + row * DN_PITCH + cc * 16) = wv[ii];
-            }
-            // K-major B-fragments by transpose reads: in each 16-lane group lane t = 4r + c4 supplies
-            // row 8q + r, columns 4*c4 .. 4*c4+3 and receives column t of rows 8q .. 8q+3
-            const int r = (lane & 15) >> 2, c4 = lane & 3;
+        for (int t = 0; t < DN_SUB / 16; ++t) {
+            const unsigned char *src = tile + (8 * q + r) * DN_PITCH + (t * 16 + 4 * c4) * 2;
+            const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)src);
+            const s16x4 b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(src + 4 * DN_PITCH));
+            const uint2 u0 = __builtin_bit_cast(uint2, b0), u1 = __builtin_bit_cast(uint2, b1);
+            const u32x4 bf = {u0.x, u0.y, u1.x, u1.y};
+            const int ti = sub * (DN_SUB / 16) + t;
+            acc[ti] = mfma16(ahi, bf, acc[ti]);
+            acc[ti] = mfma16(alo, bf, acc[ti]);
+        }
+    };
+    auto split_h = [&](const float (&hv)[8], u32x4 &ahi, u32x4 &alo) {
+        unsigned int hi16[8], lo16[8];
 #pragma unroll
-            for (int t = 0; t < DN_SUB / 16; ++t) {
-                const unsigned char *src = tile + (8 * q + r) * DN_PITCH + (t * 16 + 4 * c4) * 2;
-                const s16x4 b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)src);
-                const s16x4 b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(src + 4 * DN_PITCH));
-                const uint2 u0 = __builtin_bit_cast(uint2, b0), u1 = __builtin_bit_cast(uint2, b1);
-                const u32x4 bf = {u0.x, u0.y, u1.x, u1.y};
-                const int ti = sub * (DN_SUB / 16) + t;
-                acc[ti] = mfma16(ahi, bf, acc[ti]);
-                acc[ti] = mfma16(alo, bf, acc[ti]);
-            }
+        for (int i = 0; i < 8; ++i) {
+            hi16[i] = f32_to_bf16_bits(hv[i]);
+            lo16[i] = f32_to_bf16_bits(hv[i] - __uint_as_float(hi16[i] << 16));
+        }
+        ahi = u32x4{hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
+        alo = u32x4{lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
+    };
+
+    // both halves of a block are requested up front; the next block's first half goes out
+    // before the current second half is consumed
+    u32x4 wA[8], wB[8];
+    float hv[8], hn[8];
+    if (wave < nkb) {
+        h_load(hv, wave);
+        w_load(wA, wave, 0);
+        w_load(wB, wave, 1);
+    }
+    for (int kb = wave; kb < nkb; kb += 8) {
+        u32x4 ahi, alo;
+        split_h(hv, ahi, alo);
+        if (kb + 8 < nkb) {
+            process(wA, ahi, alo, 0);
+            h_load(hn, kb + 8);
+            w_load(wA, kb + 8, 0);
+            process(wB, ahi, alo, 1);
+            w_load(wB, kb + 8, 1);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) hv[i] = hn[i];
+        } else {
+            process(wA, ahi, alo, 0);
+            process(wB, ahi, alo, 1);
         }
     }
 
@@ -285,7 +348,7 @@ k_bat_down(const BatParams p)
 
 size_t clada_ws_decode_batched(int32_t d_ff)
 {
-    return align_up(sizeof(float) * 16 * (size_t)d_ff, 256) + align_up(sizeof(int) * 65 * COOP_MAX_WGS, 256);
+    return align_up(sizeof(float) * 16 * (size_t)d_ff, 256) + align_up((size_t)d_ff, 256);
 }
 
 // Returns CLADA_OK when the batched MFMA path ran, CLADA_ERR_SHAPE (without touching ctx->err) when
@@ -305,14 +368,13 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     int RG = P / CG;
     if (RG < 1) RG = 1;
     if (RG > 16) RG = 16;
-    if ((F + RG - 1) / RG + 64 > DN_MAX_ROWS) return CLADA_OK;
+    if ((F + RG - 1) / RG + 1 > DN_MAX_ROWS) return CLADA_OK;
 
     BatParams p;
     p.wg = (const char *)layer->w_gate; p.wu = (const char *)layer->w_up; p.wd = (const char *)layer->w_down;
     p.x = (const char *)x; p.tau = tau;
     p.hbuf = reinterpret_cast<float *>(scratch);
-    p.ulist = reinterpret_cast<int *>(scratch + align_up(sizeof(float) * 16 * (size_t)F, 256));
-    p.ucnt = p.ulist + 64 * COOP_MAX_WGS;
+    p.uflag = reinterpret_cast<unsigned char *>(scratch + align_up(sizeof(float) * 16 * (size_t)F, 256));
     p.keep = keep; p.partial = partial;
     p.d = d; p.F = F; p.B = B; p.P = P; p.RG = RG; p.CG = CG;
 
