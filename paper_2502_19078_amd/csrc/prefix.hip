@@ -23,11 +23,13 @@ namespace {
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
-constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int BM = 128, BN = 128;
+// k-tile depth: 64 for bf16 (half as many barriers per flop), 32 for fp32 (LDS budget)
+template <int ES> constexpr int BKV = (ES == 2) ? 64 : 32;
 
 template <int ES> struct Tile {
-    static constexpr int ROW = BK * ES + 16;            // padded LDS row stride, bytes
-    static constexpr int CHUNKS = BK * ES / 16;         // 16-byte chunks per tile row
+    static constexpr int ROW = BKV<ES> * ES + 16;       // padded LDS row stride, bytes
+    static constexpr int CHUNKS = BKV<ES> * ES / 16;    // 16-byte chunks per tile row
     static constexpr int PER_THREAD = BM * CHUNKS / 256; // chunks each thread moves per tile
 };
 
@@ -40,7 +42,7 @@ __device__ __forceinline__ void mma_tile(const char *sa, const char *const (&sb)
     const int r = lane & 31, q = lane >> 5;
     if (ES == 2) {
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
+        for (int ks = 0; ks < BKV<ES> / 16; ++ks) {
             bf16x8 a[2];
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
@@ -57,7 +59,7 @@ __device__ __forceinline__ void mma_tile(const char *sa, const char *const (&sb)
         }
     } else {
 #pragma unroll
-        for (int ks = 0; ks < BK / 2; ++ks) {
+        for (int ks = 0; ks < BKV<ES> / 2; ++ks) {
             float a[2];
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
@@ -92,7 +94,7 @@ struct GateUpParams {
     float *part;        // [n_tm][4][F]  partial aggregates (sum|a|, sum a^2, max|a|, sum h^2)
     float *pool;        // [T][F] or nullptr
     char *hbuf;         // [T][Fp] layer dtype (Fp = F rounded up to BK, zero past F) or nullptr
-    int Fp;
+    int Fp;             // F rounded up to a multiple of 64
 };
 
 template <int ES>
@@ -128,7 +130,7 @@ k_prefix_gateup(const GateUpParams p)
 #pragma unroll
         for (int i = 0; i < PT; ++i) {
             const int c = tid + i * 256, row = c / CH, ch = c % CH;
-            const int kbyte = kt * BK * ES + ch * 16;
+            const int kbyte = kt * BKV<ES> * ES + ch * 16;
             const bool kin = (size_t)kbyte < rowbytes;
             const int t = tm * BM + row, j = tn * BN + row;
             u32x4 z = {0u, 0u, 0u, 0u};
@@ -137,7 +139,7 @@ k_prefix_gateup(const GateUpParams p)
             ru[i] = (kin && j < p.F) ? *reinterpret_cast<const u32x4 *>(p.wu + (size_t)j * rowbytes + kbyte) : z;
         }
     };
-    const int nk = (p.d + BK - 1) / BK;
+    const int nk = (p.d + BKV<ES> - 1) / BKV<ES>;
     load_tile(0);
     for (int kt = 0; kt < nk; ++kt) {
         __syncthreads();
@@ -242,13 +244,13 @@ k_prefix_down(const DownParams p)
 
     // B tile in global memory: BK rows (neurons) x BN columns -> BK * BN*ES/16 chunks
     constexpr int BCH = BN * ES / 16;                  // chunks per neuron row of the tile
-    constexpr int BPT = BK * BCH / 256;
+    constexpr int BPT = BKV<ES> * BCH / 256;
     u32x4 ra[PT], rb[BPT];
     auto load_tile = [&](int kt) {
 #pragma unroll
         for (int i = 0; i < PT; ++i) {
             const int c = tid + i * 256, row = c / CH, ch = c % CH;
-            const size_t kbyte = (size_t)kt * BK * ES + ch * 16;
+            const size_t kbyte = (size_t)kt * BKV<ES> * ES + ch * 16;
             const int t = tm * BM + row;
             u32x4 z = {0u, 0u, 0u, 0u};
             // rows of h are padded to a multiple of BK elements, zero-filled past F
@@ -257,13 +259,13 @@ k_prefix_down(const DownParams p)
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
             const int c = tid + i * 256, k = c / BCH, ch = c % BCH;
-            const int j = kt * BK + k;
+            const int j = kt * BKV<ES> + k;
             const size_t nbyte = (size_t)tn * BN * ES + ch * 16;
             u32x4 z = {0u, 0u, 0u, 0u};
             rb[i] = (j < p.F && nbyte < wrow) ? *reinterpret_cast<const u32x4 *>(p.wd + (size_t)j * wrow + nbyte) : z;
         }
     };
-    const int nk = (p.F + BK - 1) / BK;
+    const int nk = (p.F + BKV<ES> - 1) / BKV<ES>;
     load_tile(0);
     for (int kt = 0; kt < nk; ++kt) {
         __syncthreads();
@@ -302,6 +304,109 @@ k_prefix_down(const DownParams p)
                     if (ES == 4) reinterpret_cast<float *>(p.y)[(size_t)t * p.d + col] = v;
                     else reinterpret_cast<unsigned short *>(p.y)[(size_t)t * p.d + col] = (unsigned short)f32_to_bf16_bits(v);
                 }
+            }
+    }
+}
+
+// bf16 down projection Y = H W_down with a 64-deep k-tile: the W_down tile stays row-major
+// ([k][n], as it lies in memory) in LDS and the K-major MFMA B-fragments come from
+// ds_read_b64_tr_b16 transpose reads (in each 16-lane group lane t = 4r + c4 supplies row
+// k0 + r, columns 4*c4..4*c4+3 and receives column t of rows k0..k0+3).
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+constexpr int DBK = 64;
+constexpr int DA_PITCH = DBK * 2 + 16;          // h tile row pitch (bytes)
+constexpr int DB_PITCH = BN * 2 + 32;           // W_down tile row pitch: 4 rows of a transpose read hit distinct banks
+
+__global__ void __launch_bounds__(256)
+k_prefix_down_bf16(const DownParams p)
+{
+    __shared__ __align__(16) char s_a[BM * DA_PITCH];
+    __shared__ __align__(16) char s_b[DBK * DB_PITCH];
+
+    const int total = p.n_tm * p.n_tn;
+    const int tile = remap_block(blockIdx.x, total);
+    if (tile >= total) return;
+    const int tm = tile % p.n_tm, tn = tile / p.n_tm;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const size_t hrow = (size_t)p.Fp * 2, wrow = (size_t)p.d * 2;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.0f;
+
+    u32x4 ra[4], rb[4];
+    auto load_tile = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + i * 256;
+            u32x4 z = {0u, 0u, 0u, 0u};
+            {   // h tile: 128 rows x 8 chunks
+                const int row = c >> 3, ch = c & 7;
+                const size_t kbyte = (size_t)kt * DBK * 2 + ch * 16;
+                const int t = tm * BM + row;
+                ra[i] = (t < p.T && kbyte < hrow) ? *reinterpret_cast<const u32x4 *>(p.h + (size_t)t * hrow + kbyte) : z;
+            }
+            {   // W_down tile: 64 rows x 16 chunks
+                const int k = c >> 4, ch = c & 15;
+                const int j = kt * DBK + k;
+                const size_t nbyte = (size_t)tn * BN * 2 + ch * 16;
+                rb[i] = (j < p.F && nbyte < wrow) ? *reinterpret_cast<const u32x4 *>(p.wd + (size_t)j * wrow + nbyte) : z;
+            }
+        }
+    };
+    const int nk = (p.F + DBK - 1) / DBK;
+    const int r32 = lane & 31, q = lane >> 5;
+    const int g = lane >> 4, t16 = lane & 15;
+    load_tile(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = tid + i * 256;
+            *reinterpret_cast<u32x4 *>(s_a + (c >> 3) * DA_PITCH + (c & 7) * 16) = ra[i];
+            *reinterpret_cast<u32x4 *>(s_b + (c >> 4) * DB_PITCH + (c & 15) * 16) = rb[i];
+        }
+        __syncthreads();
+        if (kt + 1 < nk) load_tile(kt + 1);
+#pragma unroll
+        for (int ks = 0; ks < DBK / 16; ++ks) {
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+                a[mb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                            s_a + (wm * 64 + mb * 32 + r32) * DA_PITCH + (ks * 16 + q * 8) * 2));
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const char *src = s_b + (ks * 16 + 8 * (g >> 1) + (t16 >> 2)) * DB_PITCH +
+                                  (wn * 64 + nb * 32 + 16 * (g & 1) + 4 * (t16 & 3)) * 2;
+                const s16x4_t b0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3))) *)src);
+                const s16x4_t b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3))) *)(src + 4 * DB_PITCH));
+                const uint2 u0 = __builtin_bit_cast(uint2, b0), u1 = __builtin_bit_cast(uint2, b1);
+                b[nb] = __builtin_bit_cast(bf16x8, u32x4{u0.x, u0.y, u1.x, u1.y});
+            }
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], b[nb], acc[mb][nb], 0, 0, 0);
+        }
+    }
+    const int n = lane & 31;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int col = tn * BN + wn * 64 + nb * 32 + n;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int t = tm * BM + wm * 64 + mb * 32 + acc_row(r, lane);
+                if (t < p.T && col < p.d)
+                    reinterpret_cast<unsigned short *>(p.y)[(size_t)t * p.d + col] = (unsigned short)f32_to_bf16_bits(acc[mb][nb][r]);
             }
     }
 }
@@ -353,7 +458,7 @@ size_t clada_ws_prefix(int32_t d, int32_t d_ff, int32_t T, bool want_y)
     if (T <= 0) return 0;
     const size_t n_tm = (size_t)(T + BM - 1) / BM;
     size_t need = align_up(sizeof(float) * 4 * n_tm * d_ff, 256);
-    if (want_y) need += align_up((size_t)T * align_up((size_t)d_ff, BK) * 4, 256);
+    if (want_y) need += align_up((size_t)T * align_up((size_t)d_ff, 64) * 4, 256);
     (void)d;
     return need;
 }
@@ -383,7 +488,7 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
     g.part = reinterpret_cast<float *>(ws);
     g.pool = out->abs_act_pool;
     g.hbuf = y ? ws + align_up(sizeof(float) * 4 * (size_t)n_tm * F, 256) : nullptr;
-    g.Fp = (int)align_up((size_t)F, BK);
+    g.Fp = (int)align_up((size_t)F, 64);
     const int total = n_tm * n_tn;
     const int grid = (total + 7) / 8 * 8;
     if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
@@ -395,7 +500,7 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
         q.T = T; q.d = d; q.F = F; q.Fp = g.Fp; q.n_tm = n_tm; q.n_tn = (d + BN - 1) / BN;
         const int tot2 = q.n_tm * q.n_tn, grid2 = (tot2 + 7) / 8 * 8;
         if (es == 4) hipLaunchKernelGGL(k_prefix_down<4>, dim3(grid2), dim3(256), 0, stream, q);
-        else         hipLaunchKernelGGL(k_prefix_down<2>, dim3(grid2), dim3(256), 0, stream, q);
+        else         hipLaunchKernelGGL(k_prefix_down_bf16, dim3(grid2), dim3(256), 0, stream, q);
         CLADA_CHECK_HIP(ctx, hipGetLastError());
     }
     if (out->sum_abs_act || out->sum_sq_act || out->max_abs_act || out->sum_sq_h || out->A) {
