@@ -160,11 +160,12 @@ clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer *layer, co
                                     int32_t B, void *y, void *hip_stream);
 
 /* Measurement helpers (no part of the method).  clada_diag_stream_read reads
- * `bytes` of device memory once with 16-byte loads from blocks_per_cu*CUs
- * workgroups and discards them: the practical HBM read ceiling the decode
- * kernels are compared with.  clada_diag_copy copies `bytes` from src to dst:
- * the known-size transfer the profiler's fetch/write counters are scaled by.
- * Pointers and sizes must be multiples of 16 bytes. */
+ * `bytes` (a multiple of 8192) of device memory once, in the decode kernels'
+ * access pattern (each wave streams whole 8 KiB rows with non-temporal 16-byte
+ * loads; blocks_per_cu in [1,4] workgroups of 8 waves per compute unit) and
+ * discards them: the practical HBM read ceiling.  clada_diag_copy copies `bytes`
+ * (a multiple of 16) from src to dst: the known-size transfer the profiler's
+ * fetch/write counters are scaled by.  Pointers must be 16-byte aligned. */
 clada_status clada_diag_stream_read(clada_ctx *ctx, const void *src, size_t bytes,
                                     int32_t blocks_per_cu, void *hip_stream);
 clada_status clada_diag_copy(clada_ctx *ctx, const void *src, void *dst, size_t bytes,

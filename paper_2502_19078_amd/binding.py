@@ -230,7 +230,7 @@ def dense_ffn_decode(ctx: Context, layer: Layer, x: torch.Tensor, y: torch.Tenso
     return y
 
 
-def diag_stream_read(ctx: Context, src: torch.Tensor, blocks_per_cu: int = 8):
+def diag_stream_read(ctx: Context, src: torch.Tensor, blocks_per_cu: int = 1):
     ctx.check(ctx._lib.clada_diag_stream_read(ctx._h, _ptr(src), src.numel() * src.element_size(),
                                               blocks_per_cu, _stream(src)))
 
