@@ -33,12 +33,16 @@ __global__ void __launch_bounds__(256) k_calib_init(CalibState *st, unsigned lon
     }
 }
 
+// The magnitudes crowd into a few dozen bins (pass 0 sees mostly exponent bits), so every wave
+// keeps a private LDS histogram: same-address atomic traffic drops by the number of waves.
+constexpr int HIST_COPIES = 4;
 __global__ void __launch_bounds__(256)
 k_calib_hist(const float *__restrict__ pool, long long n, CalibState *st, int pass)
 {
-    __shared__ unsigned int s_hist[NBINS];
-    for (int i = threadIdx.x; i < NBINS; i += blockDim.x) s_hist[i] = 0u;
+    __shared__ unsigned int s_hist[HIST_COPIES][NBINS];
+    for (int i = threadIdx.x; i < HIST_COPIES * NBINS; i += blockDim.x) (&s_hist[0][0])[i] = 0u;
     __syncthreads();
+    unsigned int *mine = s_hist[(threadIdx.x >> 6) % HIST_COPIES];
     const unsigned int prefix = st->prefix, pmask = st->prefix_mask;
     const int shift = c_shift[pass];
     const unsigned int dmask = (1u << c_bits[pass]) - 1u;
@@ -50,18 +54,22 @@ k_calib_hist(const float *__restrict__ pool, long long n, CalibState *st, int pa
         const unsigned int u[4] = {v.x & 0x7fffffffu, v.y & 0x7fffffffu, v.z & 0x7fffffffu, v.w & 0x7fffffffu};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if ((u[e] & pmask) == prefix) atomicAdd(&s_hist[(u[e] >> shift) & dmask], 1u);
+            if ((u[e] & pmask) == prefix) atomicAdd(&mine[(u[e] >> shift) & dmask], 1u);
     }
     if (blockIdx.x == 0) {
         const unsigned int *p1 = reinterpret_cast<const unsigned int *>(pool);
         for (long long i = (n4 << 2) + threadIdx.x; i < n; i += blockDim.x) {
             const unsigned int u = p1[i] & 0x7fffffffu;
-            if ((u & pmask) == prefix) atomicAdd(&s_hist[(u >> shift) & dmask], 1u);
+            if ((u & pmask) == prefix) atomicAdd(&mine[(u >> shift) & dmask], 1u);
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < NBINS; i += blockDim.x)
-        if (s_hist[i]) atomicAdd(&st->hist[pass][i], (unsigned long long)s_hist[i]);
+    for (int i = threadIdx.x; i < NBINS; i += blockDim.x) {
+        unsigned int c = 0u;
+#pragma unroll
+        for (int h = 0; h < HIST_COPIES; ++h) c += s_hist[h][i];
+        if (c) atomicAdd(&st->hist[pass][i], (unsigned long long)c);
+    }
 }
 
 // Pick the bin that holds rank k, descend into it.

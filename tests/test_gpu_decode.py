@@ -255,3 +255,23 @@ def test_full_size_other_configurations(clada, cfg_name, layer_id):
                           f"{cfg_name} layer {layer_id}")
     if B > 1:       # independent tokens: the union is nearly everything, each row keeps its own sparsity
         assert cnt[0] > 0.95 * F and np.all(cnt[1:] < 0.75 * F)
+
+
+def test_batched_path_bit_reproducible_and_matches_generic(clada):
+    """The MFMA batched path (2 <= B <= 16, bf16): identical bits run to run, same masks as the
+    generic per-token kernels, outputs within tolerance of them."""
+    cfg, w, x = _case("c3", 11, 4096, 3000, 8)
+    tau = _tau_for(w, x, 0.45)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 3000, 8, 0, 0))
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
+    runs = []
+    for batched in (1, 1, 0):
+        ctx.set_option("decode.batched", batched)
+        y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, td, want_lists=True)
+        torch.cuda.synchronize()
+        runs.append((y.clone(), idx.cpu().numpy(), cnt.cpu().numpy(), bits.cpu().numpy()))
+    assert torch.equal(runs[0][0], runs[1][0])
+    for a, b in zip(runs[0][1:], runs[2][1:]):
+        assert np.array_equal(a, b)
+    assert_close_y(to_np(runs[0][0]), to_np(runs[2][0]), TOL_Y["bf16"], "batched vs generic")
