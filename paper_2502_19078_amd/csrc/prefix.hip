@@ -97,6 +97,67 @@ struct GateUpParams {
     int Fp;             // F rounded up to a multiple of 64
 };
 
+// Epilogue of the gate/up GEMM on the accumulators (shared by the fp32 and bf16 kernels):
+// a = SiLU(C_g), h = a*C_u, per-neuron partial sums over the tile's tokens, |a| pool, h store.
+template <int ES>
+__device__ __forceinline__ void gateup_epilogue(const f32x16 (&acc)[2][2][2], const GateUpParams &p, int tm, int tn,
+                                                int wm, int wn, int lane, int tid, float (&s_stat)[2][4][BN])
+{
+    // ------------------------------------------------------------------ epilogue
+    const int n = lane & 31;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int jl = wn * 64 + nb * 32 + n;          // neuron inside the tile
+        const int j = tn * BN + jl;
+        float s_abs = 0.f, s_sq = 0.f, mx = 0.f, s_h2 = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int t = tm * BM + wm * 64 + mb * 32 + acc_row(r, lane);
+                const float a = silu_f32(acc[0][mb][nb][r]);
+                const float h = a * acc[1][mb][nb][r];
+                if (t < p.T && j < p.F) {
+                    const float aa = fabsf(a);
+                    s_abs += aa;
+                    s_sq = fmaf(a, a, s_sq);
+                    mx = (aa > mx || aa != aa) ? aa : mx;
+                    s_h2 = fmaf(h, h, s_h2);
+                    if (p.pool) p.pool[(size_t)t * p.F + j] = aa;
+                }
+                if (p.hbuf && t < p.T && j < p.Fp) {
+                    const float hv = j < p.F ? h : 0.0f;
+                    if (ES == 4) reinterpret_cast<float *>(p.hbuf)[(size_t)t * p.Fp + j] = hv;
+                    else reinterpret_cast<unsigned short *>(p.hbuf)[(size_t)t * p.Fp + j] = (unsigned short)f32_to_bf16_bits(hv);
+                }
+            }
+        // lanes l and l^32 hold the same neuron
+        s_abs += __shfl_xor(s_abs, 32);
+        s_sq += __shfl_xor(s_sq, 32);
+        s_h2 += __shfl_xor(s_h2, 32);
+        const float mo = __shfl_xor(mx, 32);
+        mx = (mo > mx || mo != mo) ? mo : mx;
+        if (lane < 32) {
+            s_stat[wm][0][jl] = s_abs;
+            s_stat[wm][1][jl] = s_sq;
+            s_stat[wm][2][jl] = mx;
+            s_stat[wm][3][jl] = s_h2;
+        }
+    }
+    __syncthreads();
+    if (tid < BN) {
+        const int j = tn * BN + tid;
+        if (j < p.F) {
+            float *dst = p.part + (size_t)tm * 4 * p.F + j;
+            dst[0] = s_stat[0][0][tid] + s_stat[1][0][tid];
+            dst[(size_t)p.F] = s_stat[0][1][tid] + s_stat[1][1][tid];
+            const float m0 = s_stat[0][2][tid], m1 = s_stat[1][2][tid];
+            dst[2 * (size_t)p.F] = (m1 > m0 || m1 != m1) ? m1 : m0;
+            dst[3 * (size_t)p.F] = s_stat[0][3][tid] + s_stat[1][3][tid];
+        }
+    }
+}
+
 template <int ES>
 __global__ void __launch_bounds__(256)
 k_prefix_gateup(const GateUpParams p)
@@ -156,59 +217,125 @@ k_prefix_gateup(const GateUpParams p)
         mma_tile<ES, 2>(s_a + wm * 64 * ROW, sb, acc, lane);
     }
 
-    // ------------------------------------------------------------------ epilogue
-    const int n = lane & 31;
+    gateup_epilogue<ES>(acc, p, tm, tn, wm, wn, lane, tid, s_stat);
+}
+
+// bf16 gate/up GEMM with direct-to-LDS loads and a three-stage pipeline: global_load_lds_dwordx4
+// writes a wave's 64 x 16 bytes straight into LDS (no staging registers), two k-tiles are in
+// flight while the third is multiplied, one raw barrier per k-tile.  A tile row is 128 bytes (64
+// bf16), so rows are stored XOR-swizzled (16-byte chunk c of row r sits at position c ^ (r & 7)),
+// done on the global-address side because the LDS side of the transfer is fixed to base + lane*16.
+// Each stage is its own __shared__ array so the compiler can tell the stages apart and does not
+// wait for in-flight transfers into the other stages before reading this one.  Needs d % 64 == 0.
+constexpr int GU_TILE = 128 * 128;     // bytes of one operand tile: 128 rows x 64 bf16
+
+__device__ __forceinline__ void lds_dma16(const char *gsrc, char *ldst)
+{
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)gsrc,
+                                     (void __attribute__((address_space(3))) *)ldst, 16, 0, 0);
+}
+
+__global__ void __launch_bounds__(256)
+k_prefix_gateup_bf16(const GateUpParams p)
+{
+    __shared__ __align__(16) char s_st0[3 * GU_TILE];
+    __shared__ __align__(16) char s_st1[3 * GU_TILE];
+    __shared__ __align__(16) char s_st2[3 * GU_TILE];
+    __shared__ float s_stat[2][4][BN];
+
+    const int total = p.n_tm * p.n_tn;
+    const int tile = remap_block(blockIdx.x, total);
+    if (tile >= total) return;
+    const int tm = tile % p.n_tm, tn = tile / p.n_tm;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const size_t rowbytes = (size_t)p.d * 2;
+
+    f32x16 acc[2][2][2];
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const int jl = wn * 64 + nb * 32 + n;          // neuron inside the tile
-        const int j = tn * BN + jl;
-        float s_abs = 0.f, s_sq = 0.f, mx = 0.f, s_h2 = 0.f;
+    for (int w = 0; w < 2; ++w)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int t = tm * BM + wm * 64 + mb * 32 + acc_row(r, lane);
-                const float a = silu_f32(acc[0][mb][nb][r]);
-                const float h = a * acc[1][mb][nb][r];
-                if (t < p.T && j < p.F) {
-                    const float aa = fabsf(a);
-                    s_abs += aa;
-                    s_sq = fmaf(a, a, s_sq);
-                    mx = (aa > mx || aa != aa) ? aa : mx;
-                    s_h2 = fmaf(h, h, s_h2);
-                    if (p.pool) p.pool[(size_t)t * p.F + j] = aa;
-                }
-                if (p.hbuf && t < p.T && j < p.Fp) {
-                    const float hv = j < p.F ? h : 0.0f;
-                    if (ES == 4) reinterpret_cast<float *>(p.hbuf)[(size_t)t * p.Fp + j] = hv;
-                    else reinterpret_cast<unsigned short *>(p.hbuf)[(size_t)t * p.Fp + j] = (unsigned short)f32_to_bf16_bits(hv);
-                }
-            }
-        // lanes l and l^32 hold the same neuron
-        s_abs += __shfl_xor(s_abs, 32);
-        s_sq += __shfl_xor(s_sq, 32);
-        s_h2 += __shfl_xor(s_h2, 32);
-        const float mo = __shfl_xor(mx, 32);
-        mx = (mo > mx || mo != mo) ? mo : mx;
-        if (lane < 32) {
-            s_stat[wm][0][jl] = s_abs;
-            s_stat[wm][1][jl] = s_sq;
-            s_stat[wm][2][jl] = mx;
-            s_stat[wm][3][jl] = s_h2;
-        }
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[w][mb][nb][r] = 0.0f;
+
+    // a wave moves 8-row pieces (1 KiB) of each operand tile: lane = (row lr, LDS position lp)
+    const int lr = lane >> 3, lp = lane & 7;
+    const char *gx[4], *gg[4], *gu[4];
+#pragma unroll
+    for (int c4 = 0; c4 < 4; ++c4) {
+        const int row = 8 * (wave + 4 * c4) + lr;           // rows past T / F repeat the last valid row;
+        const int t = min(tm * BM + row, p.T - 1);          // their products land in discarded outputs
+        const int j = min(tn * BN + row, p.F - 1);
+        const int koff = (lp ^ lr) * 16;
+        gx[c4] = p.x + (size_t)t * rowbytes + koff;
+        gg[c4] = p.wg + (size_t)j * rowbytes + koff;
+        gu[c4] = p.wu + (size_t)j * rowbytes + koff;
     }
-    __syncthreads();
-    if (tid < BN) {
-        const int j = tn * BN + tid;
-        if (j < p.F) {
-            float *dst = p.part + (size_t)tm * 4 * p.F + j;
-            dst[0] = s_stat[0][0][tid] + s_stat[1][0][tid];
-            dst[(size_t)p.F] = s_stat[0][1][tid] + s_stat[1][1][tid];
-            const float m0 = s_stat[0][2][tid], m1 = s_stat[1][2][tid];
-            dst[2 * (size_t)p.F] = (m1 > m0 || m1 != m1) ? m1 : m0;
-            dst[3 * (size_t)p.F] = s_stat[0][3][tid] + s_stat[1][3][tid];
+    auto issue = [&](char *st, int kt) {
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) {
+            char *dst = st + (wave + 4 * c4) * 1024;
+            lds_dma16(gx[c4] + (size_t)kt * 128, dst);
+            lds_dma16(gg[c4] + (size_t)kt * 128, dst + GU_TILE);
+            lds_dma16(gu[c4] + (size_t)kt * 128, dst + 2 * GU_TILE);
         }
+    };
+    // Fragment reads are issued as inline assembly: for an LDS read the compiler cannot prove
+    // distinct from an in-flight direct-to-LDS transfer it inserts vmcnt(0), which would serialise
+    // the pipeline; the hand-placed vmcnt above already orders the transfers of the stage read here.
+    const int r32 = lane & 31, q = lane >> 5, sw = r32 & 7;
+    const unsigned int a_off = (unsigned int)((wm * 64 + r32) * 128);
+    const unsigned int b_off = (unsigned int)(GU_TILE + (wn * 64 + r32) * 128);
+    auto compute = [&](const char *st) {
+        const unsigned int base = (unsigned int)(size_t)(const __attribute__((address_space(3))) char *)st;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const unsigned int pos = (unsigned int)(((2 * ks + q) ^ sw) * 16);
+            const unsigned int pa = base + a_off + pos, pb = base + b_off + pos;
+            u32x4 a0, a1, g0, g1, u0, u1;
+            asm volatile("ds_read_b128 %0, %6\n\t"
+                         "ds_read_b128 %1, %6 offset:4096\n\t"
+                         "ds_read_b128 %2, %7\n\t"
+                         "ds_read_b128 %3, %7 offset:4096\n\t"
+                         "ds_read_b128 %4, %7 offset:16384\n\t"
+                         "ds_read_b128 %5, %7 offset:20480\n\t"
+                         "s_waitcnt lgkmcnt(0)"
+                         : "=&v"(a0), "=&v"(a1), "=&v"(g0), "=&v"(g1), "=&v"(u0), "=&v"(u1)
+                         : "v"(pa), "v"(pb));
+            const bf16x8 fa[2] = {__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, a1)};
+            const bf16x8 fb[2][2] = {{__builtin_bit_cast(bf16x8, g0), __builtin_bit_cast(bf16x8, g1)},
+                                     {__builtin_bit_cast(bf16x8, u0), __builtin_bit_cast(bf16x8, u1)}};
+#pragma unroll
+            for (int w = 0; w < 2; ++w)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+                        acc[w][mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mb], fb[w][nb], acc[w][mb][nb], 0, 0, 0);
+        }
+    };
+    const int nk = p.d / 64;
+    // wait until this wave's transfers of tile k have landed (the 12 of tile k+1 may stay in
+    // flight), meet the other waves, refill the stage consumed one step ago, multiply
+    auto step = [&](int k, const char *cur, char *nxt) {
+        if (k + 1 < nk) __builtin_amdgcn_s_waitcnt(0x0F7C);     // vmcnt(12)
+        else            __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        if (k + 2 < nk) issue(nxt, k + 2);
+        compute(cur);
+    };
+    issue(s_st0, 0);
+    if (nk > 1) issue(s_st1, 1);
+    for (int kt = 0; kt < nk; kt += 3) {
+        step(kt, s_st0, s_st2);
+        if (kt + 1 < nk) step(kt + 1, s_st1, s_st0);
+        if (kt + 2 < nk) step(kt + 2, s_st2, s_st1);
     }
+    gateup_epilogue<2>(acc, p, tm, tn, wm, wn, lane, tid, s_stat);
 }
 
 struct DownParams {
@@ -492,6 +619,7 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
     const int total = n_tm * n_tn;
     const int grid = (total + 7) / 8 * 8;
     if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
+    else if (d % 64 == 0) hipLaunchKernelGGL(k_prefix_gateup_bf16, dim3(grid), dim3(256), 0, stream, g);
     else         hipLaunchKernelGGL(k_prefix_gateup<2>, dim3(grid), dim3(256), 0, stream, g);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     if (y) {
