@@ -70,7 +70,10 @@ const char *clada_last_error(const clada_ctx *ctx);
  * cross-workgroup load balancing [default], 2 = split-d kernel without balancing,
  * 0 = the generic kernels used for batch > 1), "decode.own_first" (1..14, neurons a
  * workgroup keeps for itself before the balanced hand-over; 0 = default),
- * "decode.wgs_per_cu" (1 or 2 workgroups per compute unit for the generic kernel).
+ * "decode.wgs_per_cu" (1 or 2 workgroups per compute unit for the generic kernel),
+ * "decode.batched" (1 = matrix-core kernels for bf16 batches 2..16 [default], 0 = the
+ * generic kernels), "diag.kernel_events" (1 = every decode call also records HIP
+ * events around its kernels for clada_diag_kernel_times; default 0).
  * Unknown names or out-of-range values give CLADA_ERR_VALUE and change nothing. */
 clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);
 
@@ -166,6 +169,12 @@ clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer *layer, co
  * discards them: the practical HBM read ceiling.  clada_diag_copy copies `bytes`
  * (a multiple of 16) from src to dst: the known-size transfer the profiler's
  * fetch/write counters are scaled by.  Pointers must be 16-byte aligned. */
+/* With option "diag.kernel_events" = 1 a decode call attaches HIP events to its
+ * kernels on the call's own stream.  This call waits for the last decode call of
+ * the context to finish and returns, in microseconds, the main kernel's own
+ * start-to-stop time (main_us) and the final-reduction kernel's (finalize_us; 0
+ * for the batched path, whose kernels are timed as one span).  Host pointers. */
+clada_status clada_diag_kernel_times(clada_ctx *ctx, float *main_us, float *finalize_us);
 clada_status clada_diag_stream_read(clada_ctx *ctx, const void *src, size_t bytes,
                                     int32_t blocks_per_cu, void *hip_stream);
 clada_status clada_diag_copy(clada_ctx *ctx, const void *src, void *dst, size_t bytes,

@@ -69,7 +69,8 @@ def load_library() -> C.CDLL:
     lib.clada_dense_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp]
     lib.clada_diag_stream_read.argtypes = [vp, vp, C.c_size_t, i32, vp]
     lib.clada_diag_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
-    for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
+    lib.clada_diag_kernel_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
                  "clada_cognitive_signals", "clada_threshold", "clada_sparse_ffn_decode",
                  "clada_dense_ffn_decode"):
         getattr(lib, name).restype = C.c_int
@@ -239,3 +240,10 @@ def diag_copy(ctx: Context, src: torch.Tensor, dst: torch.Tensor):
     assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
     ctx.check(ctx._lib.clada_diag_copy(ctx._h, _ptr(src), _ptr(dst), src.numel() * src.element_size(),
                                        _stream(src)))
+
+
+def diag_kernel_times(ctx: Context):
+    """(main_us, finalize_us) of the context's last decode call; needs option diag.kernel_events = 1."""
+    a, b = C.c_float(), C.c_float()
+    ctx.check(ctx._lib.clada_diag_kernel_times(ctx._h, C.byref(a), C.byref(b)))
+    return a.value, b.value

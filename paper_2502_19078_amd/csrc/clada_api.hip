@@ -57,6 +57,8 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->opt_decode_b1 = 1;
     ctx->opt_decode_batched = 1;
     ctx->opt_decode_own_first = 0;
+    ctx->opt_diag_events = 0;
+    ctx->ev[0] = ctx->ev[1] = ctx->ev[2] = ctx->ev[3] = nullptr;
     ctx->err[0] = 0;
     if (workspace_bytes > 0) {
         hipError_t e = hipSetDevice(device_id);
@@ -82,6 +84,8 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
 void clada_destroy(clada_ctx *ctx)
 {
     if (!ctx) return;
+    for (int i = 0; i < 4; ++i)
+        if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
     if (ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
 }
@@ -126,7 +130,28 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
         ctx->opt_decode_own_first = value;
         return CLADA_OK;
     }
+    if (!strcmp(name, "diag.kernel_events")) {
+        if (value < 0 || value > 1) return clada_fail(ctx, CLADA_ERR_VALUE, "diag.kernel_events=%d outside [0,1]", value);
+        if (value && !ctx->ws) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "diag.kernel_events needs a context with a workspace");
+        for (int i = 0; value && i < 4; ++i)
+            if (!ctx->ev[i]) CLADA_CHECK_HIP(ctx, hipEventCreate(&ctx->ev[i]));
+        ctx->opt_diag_events = value;
+        return CLADA_OK;
+    }
     return clada_fail(ctx, CLADA_ERR_VALUE, "unknown option '%s'", name);
+}
+
+clada_status clada_diag_kernel_times(clada_ctx *ctx, float *main_us, float *finalize_us)
+{
+    if (!ctx || !main_us || !finalize_us) return clada_fail(ctx, CLADA_ERR_NULL, "ctx or an output is NULL");
+    if (!ctx->opt_diag_events) return clada_fail(ctx, CLADA_ERR_VALUE, "diag.kernel_events is off");
+    CLADA_CHECK_HIP(ctx, hipEventSynchronize(ctx->ev[3]));
+    float a = 0.0f, b = 0.0f;
+    CLADA_CHECK_HIP(ctx, hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
+    CLADA_CHECK_HIP(ctx, hipEventElapsedTime(&b, ctx->ev[2], ctx->ev[3]));
+    *main_us = a * 1e3f;
+    *finalize_us = b * 1e3f;
+    return CLADA_OK;
 }
 
 size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int32_t V)

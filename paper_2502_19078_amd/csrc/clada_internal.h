@@ -16,6 +16,8 @@ struct clada_ctx {
     int opt_decode_b1;           // batch-1 split-d kernel: 0 off (generic kernels), 1 with balancing, 2 without
     int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
     int opt_decode_batched;      // 1: MFMA path for 2 <= B <= 16 (bf16), 0: generic kernels
+    int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)
+    hipEvent_t ev[4];            // start/stop of the main decode kernel, start/stop of the final reduction
     char err[512];
 };
 

@@ -19,6 +19,8 @@
 //                  results are bit-reproducible.
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "clada_internal.h"
 
 namespace {
@@ -263,9 +265,15 @@ k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict
     }
 }
 
-void launch_finalize(int es, const float *partial, int P, int B, int d, char *y, unsigned int *epoch, hipStream_t stream)
+void launch_finalize(int es, const float *partial, int P, int B, int d, char *y, unsigned int *epoch, hipStream_t stream,
+                     hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr)
 {
     const dim3 grid((d + 31) / 32, B);
+    if (ev_start) {
+        if (es == 4) hipExtLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch);
+        else         hipExtLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch);
+        return;
+    }
     if (es == 4) hipLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, partial, P, d, y, epoch);
     else         hipLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, partial, P, d, y, epoch);
 }
@@ -734,7 +742,9 @@ hipError_t launch_b1_variant(clada_ctx *ctx, const B1Params &p, int P, hipStream
         }
         if ((long long)occ * ctx->num_cu < P) return hipErrorNotSupported;
     }
-    hipLaunchKernelGGL(kern, dim3(P), dim3(512), 0, st, p);
+    // with the diagnostic option on, the two events take the kernel's own start and stop times
+    if (ctx->opt_diag_events) hipExtLaunchKernelGGL(kern, dim3(P), dim3(512), 0, st, ctx->ev[0], ctx->ev[1], 0, p);
+    else hipLaunchKernelGGL(kern, dim3(P), dim3(512), 0, st, p);
     return hipGetLastError();
 }
 
@@ -818,7 +828,8 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
                 if (eb == hipErrorNotSupported) balance = false;      // not co-resident: plain split-d
             }
             CLADA_CHECK_HIP(ctx, eb);
-            launch_finalize(es, p.partial, Pb, 1, d, (char *)y, balance ? epoch : nullptr, stream);
+            launch_finalize(es, p.partial, Pb, 1, d, (char *)y, balance ? epoch : nullptr, stream,
+                            ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3]);
             CLADA_CHECK_HIP(ctx, hipGetLastError());
             if (lists) {
                 hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
@@ -832,9 +843,15 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
         unsigned char *keep_region = reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256));
         char *scratch = reinterpret_cast<char *>(keep_region) + align_up((size_t)B * F, 256);
         bool ran = false;
+        if (ctx->opt_diag_events) CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[0], stream));
         st = clada_decode_batched(ctx, layer, x, B, tau, y, p.keep, p.partial, scratch, dense, stream, &ran);
         if (st != CLADA_OK) return st;
         if (ran) {
+            if (ctx->opt_diag_events) {     // the batched path's final reduction is not timed apart
+                CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[1], stream));
+                CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[2], stream));
+                CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[3], stream));
+            }
             if (lists) {
                 hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
                 CLADA_CHECK_HIP(ctx, hipGetLastError());
@@ -842,6 +859,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             return CLADA_OK;
         }
     }
+    if (ctx->opt_diag_events) CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[0], stream));
 #define CLADA_DECODE_CASE(ES_, NCH_, NW_, GB_, UB_)                                        \
     if (es == ES_ && nch <= NCH_ && e == hipErrorInvalidValue)                             \
         e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, dense, stream);
@@ -859,7 +877,9 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
 #undef CLADA_DECODE_CASE
     CLADA_CHECK_HIP(ctx, e);
 
-    launch_finalize(es, p.partial, P, B, d, (char *)y, nullptr, stream);
+    if (ctx->opt_diag_events) CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[1], stream));
+    launch_finalize(es, p.partial, P, B, d, (char *)y, nullptr, stream,
+                    ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3]);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     if (lists) {
         hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);

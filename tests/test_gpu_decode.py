@@ -275,3 +275,23 @@ def test_batched_path_bit_reproducible_and_matches_generic(clada):
     for a, b in zip(runs[0][1:], runs[2][1:]):
         assert np.array_equal(a, b)
     assert_close_y(to_np(runs[0][0]), to_np(runs[2][0]), TOL_Y["bf16"], "batched vs generic")
+
+
+@pytest.mark.parametrize("B", [1, 3])
+def test_kernel_event_timing_does_not_change_results(clada, B):
+    """diag.kernel_events attaches HIP events to the kernels: same bits out, positive durations back."""
+    from paper_2502_19078_amd import binding
+    cfg, w, x = _case("c1", 5, 512, 1376, B)
+    tau = _tau_for(w, x, 0.4)
+    ctx = clada.Context(0, clada.workspace_bytes(512, 1376, B, 0, 0))
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
+    y0 = clada.sparse_ffn_decode(ctx, layer, xd, td)[0].clone()
+    ctx.set_option("diag.kernel_events", 1)
+    y1 = clada.sparse_ffn_decode(ctx, layer, xd, td)[0].clone()
+    main_us, fin_us = binding.diag_kernel_times(ctx)
+    ctx.set_option("diag.kernel_events", 0)
+    assert torch.equal(y0, y1)
+    assert 0.0 < main_us < 1e5 and 0.0 < fin_us < 1e5
+    with pytest.raises(binding.CladaError):
+        binding.diag_kernel_times(ctx)
