@@ -183,3 +183,30 @@ def dense_decode(w_gate, w_up, w_down, x):
     rc = _load().clada_oracle_dense_decode(pg, pu, pd, d, F, px, B, py)
     assert rc == 0, rc
     return y
+
+
+def cett(w_gate, w_up, w_down, x, eps):
+    """Per-token CETT of the validation tokens x [T][d] at cut threshold eps, and its mean."""
+    keep, (pg, pu, pd), d, F = _weights(w_gate, w_up, w_down)
+    xx, px = _f32(x)
+    T = xx.shape[0]
+    assert xx.shape == (T, d)
+    out, po = _out((T,))
+    mean = C.c_double()
+    rc = _load().clada_oracle_cett(pg, pu, pd, d, F, px, T, C.c_double(float(eps)), po, C.byref(mean))
+    assert rc == 0, rc
+    return out, mean.value
+
+
+def cett_search(w_gate, w_up, w_down, x, bound=0.2):
+    """(tau_base, mean CETT at tau_base, rc): the largest eps whose mean CETT over x [T][d] is <= bound.
+    rc 0 = attained at a pooled magnitude, 3 = unbounded (tau = inf), 4 = nothing feasible."""
+    keep, (pg, pu, pd), d, F = _weights(w_gate, w_up, w_down)
+    xx, px = _f32(x)
+    T = xx.shape[0]
+    assert xx.shape == (T, d)
+    tau, mean = C.c_double(), C.c_double()
+    rc = _load().clada_oracle_cett_search(pg, pu, pd, d, F, px, T, C.c_double(float(bound)),
+                                          C.byref(tau), C.byref(mean))
+    assert rc in (0, 3, 4), rc
+    return tau.value, mean.value, rc

@@ -72,3 +72,28 @@ def softmax_signals(z, tok):
     p = [v / Z for v in e]
     H = -sum(q * math.log(q) for q in p if q > 0.0)
     return -math.log(p[tok]), H
+
+
+def cett_token(w_gate, w_up, w_down, x, eps):
+    """CETT of one token: norm of the summed contributions of the neurons with |a| < eps over the
+    norm of the dense output (0 when the dense output is zero)."""
+    terms = neuron_terms(w_gate, w_up, x)
+    cut = [j for j, (a, _, _) in enumerate(terms) if abs(a) < eps]
+    yc = ffn_for_subset(w_gate, w_up, w_down, x, cut)
+    yf = ffn_for_subset(w_gate, w_up, w_down, x, range(len(w_gate)))
+    nf = math.sqrt(sum(v * v for v in yf))
+    return math.sqrt(sum(v * v for v in yc)) / nf if nf > 0.0 else 0.0
+
+
+def cett_argmax(w_gate, w_up, w_down, X, bound):
+    """Largest feasible cut threshold by trying every candidate: each pooled magnitude, and one
+    value above them all (returned as inf when even that is feasible); None if none is."""
+    mags = sorted({abs(a) for x in X for (a, _, _) in neuron_terms(w_gate, w_up, x)})
+    best = None
+    for eps in mags + [2.0 * mags[-1] + 1.0]:
+        m = sum(cett_token(w_gate, w_up, w_down, x, eps) for x in X) / len(X)
+        if m <= bound:
+            best = eps
+    if best is not None and best > mags[-1]:
+        return math.inf
+    return best

@@ -21,7 +21,10 @@
  * Pins (see tests/test_oracle_*.py): library fp64 matmul, scalar hand cases,
  * tau=0 => dense, tau=+inf => zero, pure-Python brute force on 8-neuron toys,
  * closed forms for entropy/surprisal, the printed lambda/gamma factor table,
- * numpy.partition order statistics.  No function here is "parity unpinned".
+ * numpy.partition order statistics; for the CETT evaluation and search a
+ * hand-worked three-neuron example, brute force over every candidate threshold,
+ * dense-minus-sparse decode outputs, the closed form for orthogonal output rows
+ * and a constructed non-monotone case.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -355,4 +358,158 @@ int clada_oracle_dense_decode(const float *w_gate, const float *w_up,
     if (!w_gate || !w_up || !w_down || !x || !y || d <= 0 || d_ff <= 0 || B < 0) return 1;
     ffn_given_mask(w_gate, w_up, w_down, d, d_ff, x, B, NULL, NULL, y);
     return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Cumulative error of tail truncation (section 3.2.2, base-threshold equation).
+ *
+ *   CETT(x; eps) = || sum_{j in S_cut(x; eps)} n_j(x) ||_2 / || MLP(x) ||_2
+ *
+ * read with n_j(x) = h_j(x) W_down[j,:] (neuron j's contribution to the output,
+ * h_j = SiLU(W_gate[j,:].x) (W_up[j,:].x)), MLP(x) = sum over all j of n_j(x),
+ * and S_cut(x; eps) = { j : |a_j(x)| < eps }: the magnitude and the strict cut
+ * rule are those of the decode step, so that the eps found here is directly the
+ * tau_base the decode step compares with.  A token whose dense output is
+ * exactly zero has nothing to lose and gets CETT = 0.  A NaN magnitude is never
+ * below eps, so such a neuron is never in the cut set.
+ * cett [T] per token; *mean = (1/T) sum_t cett[t] (t ascending), the estimate
+ * of the expectation over the validation tokens.
+ * ---------------------------------------------------------------------- */
+int clada_oracle_cett(const float *w_gate, const float *w_up, const float *w_down,
+                      int d, int d_ff, const float *x, int T, double eps,
+                      double *cett, double *mean)
+{
+    if (!w_gate || !w_up || !w_down || !x || !cett || d <= 0 || d_ff <= 0 || T <= 0) return 1;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const float *xt = x + (size_t)t * d;
+        double *cut = (double *)calloc((size_t)d, sizeof(double));
+        double *full = (double *)calloc((size_t)d, sizeof(double));
+        if (!cut || !full) { bad = 1; free(cut); free(full); continue; }
+        for (int j = 0; j < d_ff; ++j) {
+            double a = silu(dot_fd(w_gate + (size_t)j * d, xt, d));
+            double u = dot_fd(w_up + (size_t)j * d, xt, d);
+            double h = a * u;
+            const float *wd = w_down + (size_t)j * d;
+            int is_cut = fabs(a) < eps;
+            for (int i = 0; i < d; ++i) {
+                double n = h * (double)wd[i];
+                full[i] += n;
+                if (is_cut) cut[i] += n;
+            }
+        }
+        double nc = 0.0, nf = 0.0;
+        for (int i = 0; i < d; ++i) { nc += cut[i] * cut[i]; nf += full[i] * full[i]; }
+        cett[t] = nf > 0.0 ? sqrt(nc) / sqrt(nf) : 0.0;
+        free(cut);
+        free(full);
+    }
+    if (bad) return 2;
+    if (mean) {
+        double s = 0.0;
+        for (int t = 0; t < T; ++t) s += cett[t];
+        *mean = s / (double)T;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Layer-wise base threshold (section 3.2.2):
+ *     tau_base = max eps  subject to  mean_t CETT(x_t; eps) <= bound
+ * over the validation tokens x [T][d] (bound = 0.2 in the paper).
+ *
+ * The cut sets change only when eps passes one of the T*d_ff magnitudes
+ * |a_tj|, and every eps in (v, v'] between two neighbouring magnitudes cuts
+ * what eps = v' cuts.  So if any eps is feasible, the largest feasible one is
+ * either a magnitude or unbounded.  The function visits every distinct
+ * magnitude v in ascending order, keeps per token the running cut sum
+ * c_t = sum_{|a_tj| < v} n_j(x_t), and records the last v whose mean is within
+ * the bound.  Nothing is assumed about monotonicity: the norm of a sum can
+ * shrink when a term is added, so every candidate is checked.
+ *
+ * Outputs: *tau = that magnitude, *mean_at_tau = the mean CETT there.
+ * Returns 0 on success, 3 if the all-cut mean (eps above every magnitude) is
+ * still within the bound (then the maximum is unbounded; *tau = +inf), 4 if no
+ * magnitude is feasible (cannot happen for bound >= 0, since the smallest
+ * magnitude cuts nothing).
+ * ---------------------------------------------------------------------- */
+typedef struct { double v; int t, j; } cett_event;
+
+static int cmp_event(const void *a, const void *b)
+{
+    const cett_event *x = (const cett_event *)a, *y = (const cett_event *)b;
+    if (x->v != y->v) return (x->v > y->v) - (x->v < y->v);
+    if (x->t != y->t) return (x->t > y->t) - (x->t < y->t);
+    return (x->j > y->j) - (x->j < y->j);
+}
+
+int clada_oracle_cett_search(const float *w_gate, const float *w_up, const float *w_down,
+                             int d, int d_ff, const float *x, int T, double bound,
+                             double *tau, double *mean_at_tau)
+{
+    if (!w_gate || !w_up || !w_down || !x || !tau || d <= 0 || d_ff <= 0 || T <= 0) return 1;
+    size_t N = (size_t)T * (size_t)d_ff;
+    double *h = (double *)malloc(sizeof(double) * N);
+    cett_event *ev = (cett_event *)malloc(sizeof(cett_event) * N);
+    double *c = (double *)calloc((size_t)T * (size_t)d, sizeof(double));
+    double *den = (double *)malloc(sizeof(double) * (size_t)T);
+    double *cur = (double *)calloc((size_t)T, sizeof(double));
+    if (!h || !ev || !c || !den || !cur) { free(h); free(ev); free(c); free(den); free(cur); return 2; }
+
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const float *xt = x + (size_t)t * d;
+        double *full = c + (size_t)t * d;                 /* borrowed as the dense sum, cleared below */
+        for (int j = 0; j < d_ff; ++j) {
+            double a = silu(dot_fd(w_gate + (size_t)j * d, xt, d));
+            double u = dot_fd(w_up + (size_t)j * d, xt, d);
+            double hv = a * u;
+            h[(size_t)t * d_ff + j] = hv;
+            cett_event e = { fabs(a), t, j };
+            ev[(size_t)t * d_ff + j] = e;
+            const float *wd = w_down + (size_t)j * d;
+            for (int i = 0; i < d; ++i) full[i] += hv * (double)wd[i];
+        }
+        double nf = 0.0;
+        for (int i = 0; i < d; ++i) { nf += full[i] * full[i]; full[i] = 0.0; }
+        den[t] = sqrt(nf);
+    }
+    /* NaN magnitudes are never cut: move them out of the visited range */
+    size_t n_ev = 0;
+    for (size_t k = 0; k < N; ++k)
+        if (ev[k].v == ev[k].v) ev[n_ev++] = ev[k];
+    qsort(ev, n_ev, sizeof(cett_event), cmp_event);
+
+    int found = 0;
+    double best = 0.0, best_mean = 0.0;
+    size_t k = 0;
+    while (k < n_ev) {
+        double v = ev[k].v;
+        double s = 0.0;
+        for (int t = 0; t < T; ++t) s += cur[t];
+        double m = s / (double)T;
+        if (m <= bound) { found = 1; best = v; best_mean = m; }
+        /* every magnitude equal to v joins the cut sets of all larger eps */
+        while (k < n_ev && ev[k].v == v) {
+            int t = ev[k].t, j = ev[k].j;
+            double hv = h[(size_t)t * d_ff + j];
+            const float *wd = w_down + (size_t)j * d;
+            double *ct = c + (size_t)t * d;
+            double nc = 0.0;
+            for (int i = 0; i < d; ++i) { ct[i] += hv * (double)wd[i]; nc += ct[i] * ct[i]; }
+            cur[t] = den[t] > 0.0 ? sqrt(nc) / den[t] : 0.0;
+            ++k;
+        }
+    }
+    double s = 0.0;
+    for (int t = 0; t < T; ++t) s += cur[t];
+    double all_cut = s / (double)T;
+    int rc = 0;
+    if (all_cut <= bound) { rc = 3; best = INFINITY; best_mean = all_cut; }
+    else if (!found) rc = 4;
+    *tau = best;
+    if (mean_at_tau) *mean_at_tau = best_mean;
+    free(h); free(ev); free(c); free(den); free(cur);
+    return rc;
 }
