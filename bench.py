@@ -116,6 +116,17 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     prefill_layer_ms = e0.elapsed_time(e1)
+    # the paper's own calibration (error-bounded search, bound 0.2) on the same prefix, for comparison
+    clada.threshold_search_cett(ctx, layers[L - 1], Xp, 0.2)
+    e0.record()
+    tau_cett, mean_cett = clada.threshold_search_cett(ctx, layers[L - 1], Xp, 0.2)
+    e1.record()
+    torch.cuda.synchronize()
+    cett_ms = e0.elapsed_time(e1)
+    cett_info = {"layer_ms_gpu": round(cett_ms, 3), "bound": 0.2, "tau_base": round(float(tau_cett.item()), 5),
+                 "mean_cett": round(float(mean_cett.item()), 5),
+                 "sparsity_on_prefix": round(float((st.abs_act_pool < tau_cett).float().mean().item()), 4),
+                 "percentile_tau_base": round(float(tau_base[L - 1].item()), 5)}
     del st, Xp
 
     lam = torch.full((L,), 0.80, dtype=torch.float32, device=dev)     # printed coefficients
@@ -317,7 +328,8 @@ def main():
         "dense_step_gbs": round(bytes_dense * L / (ms_dense * 1e-3) / 1e9, 1),
         "stream_read_ceiling_gbs": round(ceil_gbs, 1),   # whole-row streaming of one 90 MB matrix per launch, launch gaps included
         "prefill": {"layer_ms_gpu": round(prefill_layer_ms, 3), "stack_wall_ms_incl_h2d": round(prefill_wall_ms, 1),
-                    "tflops_layer": round(6.0 * T * d * F / (prefill_layer_ms * 1e-3) / 1e12, 1)},
+                    "tflops_layer": round(6.0 * T * d * F / (prefill_layer_ms * 1e-3) / 1e12, 1),
+                    "cett_search": cett_info},
         "roofline": {"bound": "hbm", "kernel": main_kernel,
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),

@@ -78,7 +78,7 @@ const char *clada_last_error(const clada_ctx *ctx);
 clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);
 
 /* Upper bound of the workspace any call needs for these sizes.  Pass 0 for a
- * size whose call will not be used (T for prefix_stats/calibrate, V for
+ * size whose call will not be used (T for prefix_stats/calibrate/the CETT calls, V for
  * cognitive_signals, B for the decode calls). */
 size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int32_t V);
 
@@ -118,6 +118,31 @@ clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *layer, const 
 clada_status clada_threshold_calibrate(clada_ctx *ctx, const float *abs_act_pool, int64_t n,
                                        float target_sparsity, float *tau_base_out,
                                        void *hip_stream);
+
+/* Error-bounded base threshold (section 3.2.2, base-threshold equation):
+ *   tau_base = max eps  subject to  mean_t CETT(x_t; eps) <= bound   (the paper uses 0.2),
+ *   CETT(x; eps) = || sum_{j : |a_j(x)| < eps} h_j(x) W_down[j,:] ||_2 / || MLP(x) ||_2
+ * over the validation tokens x_val [T][d] (layer dtype), with a, h as in
+ * clada_prefix_stats; the cut rule (strict '<' on |SiLU(gate)|, NaN never cut)
+ * is the decode call's, so the result feeds clada_threshold directly.  A token
+ * whose dense output is zero counts as CETT = 0.
+ * The search bisects the bit pattern of eps between 0 (cuts nothing) and +inf
+ * (cuts everything) with the bracket on the device: n_probes in [1,31] probes,
+ * each one masked down projection; 31 resolve the float exactly, fewer return
+ * the lower, feasible end of the remaining bracket.  Where the mean is not
+ * monotone in eps at the scale of single neurons the result is a boundary of
+ * the feasible set, not necessarily its last one.  bound in [0,1).
+ * Outputs (device): tau_base_out [1]; mean_cett_out [1] = the mean at
+ * tau_base_out, or NULL.  bf16 layers round h to bf16 before the projections. */
+clada_status clada_threshold_search_cett(clada_ctx *ctx, const clada_layer *layer, const void *x_val,
+                                         int32_t T, float bound, int32_t n_probes,
+                                         float *tau_base_out, float *mean_cett_out, void *hip_stream);
+
+/* The quantity the search bounds, at one given eps (host scalar; +inf allowed,
+ * NaN is CLADA_ERR_VALUE): cett_out [T] per validation token and/or mean_out [1]
+ * (device; one of them may be NULL). */
+clada_status clada_cett_eval(clada_ctx *ctx, const clada_layer *layer, const void *x_val, int32_t T,
+                             float eps, float *cett_out, float *mean_out, void *hip_stream);
 
 /* Cognitive-load signals (section 2.3.1, surprisal and entropy equations), per
  * row b of logits [B][V] (fp32 or bf16), natural log:

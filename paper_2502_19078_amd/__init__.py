@@ -9,4 +9,4 @@ library is not built.
 from .binding import (Context, Layer, PrefixStats, CladaError, cognitive_signals,  # noqa: F401
                       dense_ffn_decode, lib_path, load_library, prefix_stats,
                       sparse_ffn_decode, threshold, threshold_calibrate,
-                      workspace_bytes)
+                      threshold_search_cett, cett_eval, workspace_bytes)

@@ -69,8 +69,11 @@ def load_library() -> C.CDLL:
     lib.clada_dense_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp]
     lib.clada_diag_stream_read.argtypes = [vp, vp, C.c_size_t, i32, vp]
     lib.clada_diag_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
+    lib.clada_threshold_search_cett.argtypes = [vp, C.POINTER(_CLayer), vp, i32, C.c_float, i32, vp, vp, vp]
+    lib.clada_cett_eval.argtypes = [vp, C.POINTER(_CLayer), vp, i32, C.c_float, vp, vp, vp]
     lib.clada_diag_kernel_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
-    for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
+    for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times",
+                 "clada_threshold_search_cett", "clada_cett_eval", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
                  "clada_cognitive_signals", "clada_threshold", "clada_sparse_ffn_decode",
                  "clada_dense_ffn_decode"):
         getattr(lib, name).restype = C.c_int
@@ -174,6 +177,32 @@ def threshold_calibrate(ctx: Context, abs_act_pool: torch.Tensor, target_sparsit
     ctx.check(ctx._lib.clada_threshold_calibrate(ctx._h, _ptr(p), p.numel(), float(target_sparsity),
                                                  _ptr(out), _stream(p)))
     return out
+
+
+def threshold_search_cett(ctx: Context, layer: Layer, x_val: torch.Tensor, bound: float = 0.2,
+                          n_probes: int = 31, out: torch.Tensor | None = None):
+    """(tau_base [1], mean CETT at tau_base [1]) of the error-bounded base-threshold search."""
+    cl = layer.c_struct()
+    T = x_val.shape[0]
+    assert x_val.is_cuda and x_val.is_contiguous() and x_val.shape == (T, cl.d) and x_val.dtype == layer.w_gate.dtype
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=x_val.device)
+    mean = torch.empty(1, dtype=torch.float32, device=x_val.device)
+    ctx.check(ctx._lib.clada_threshold_search_cett(ctx._h, C.byref(cl), _ptr(x_val), T, float(bound), int(n_probes),
+                                                   _ptr(out), _ptr(mean), _stream(x_val)))
+    return out, mean
+
+
+def cett_eval(ctx: Context, layer: Layer, x_val: torch.Tensor, eps: float):
+    """(per-token CETT [T], mean [1]) at cut threshold eps."""
+    cl = layer.c_struct()
+    T = x_val.shape[0]
+    assert x_val.is_cuda and x_val.is_contiguous() and x_val.shape == (T, cl.d) and x_val.dtype == layer.w_gate.dtype
+    c = torch.empty(T, dtype=torch.float32, device=x_val.device)
+    mean = torch.empty(1, dtype=torch.float32, device=x_val.device)
+    ctx.check(ctx._lib.clada_cett_eval(ctx._h, C.byref(cl), _ptr(x_val), T, float(eps), _ptr(c), _ptr(mean),
+                                       _stream(x_val)))
+    return c, mean
 
 
 def cognitive_signals(ctx: Context, logits: torch.Tensor, token_ids: torch.Tensor):

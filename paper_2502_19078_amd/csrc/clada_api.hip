@@ -161,6 +161,7 @@ size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int3
     if (B > 0 && V > 0 && (n = clada_ws_signals(B, V)) > need) need = n;
     if (d > 0 && d_ff > 0 && T > 0 && (n = clada_ws_prefix(d, d_ff, T, true)) > need) need = n;
     if (T > 0 && (n = clada_ws_calibrate()) > need) need = n;
+    if (d > 0 && d_ff > 0 && T > 0 && (n = clada_ws_cett(d, d_ff, T)) > need) need = n;
     return need + 256;
 }
 

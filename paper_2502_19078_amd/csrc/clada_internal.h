@@ -64,6 +64,15 @@ size_t clada_ws_decode(int32_t d, int32_t d_ff, int32_t B);
 size_t clada_ws_signals(int32_t B, int32_t V);
 size_t clada_ws_prefix(int32_t d, int32_t d_ff, int32_t T, bool want_y);
 size_t clada_ws_calibrate(void);
+size_t clada_ws_cett(int32_t d, int32_t d_ff, int32_t T);
+
+// Prefill GEMMs shared by the prefix statistics and the CETT search (128 x 128 output tiles).
+int clada_prefix_token_tiles(int T);
+int clada_prefix_col_tiles(int d);
+hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, float *part, float *pool,
+                               char *hbuf, hipStream_t stream);
+hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, char *y, float *rowsq,
+                             hipStream_t stream);
 
 #ifdef __HIPCC__
 // ---------------------------------------------------------------- device helpers

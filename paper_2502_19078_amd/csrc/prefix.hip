@@ -340,9 +340,34 @@ k_prefix_gateup_bf16(const GateUpParams p)
 
 struct DownParams {
     const char *h, *wd;
-    char *y;
+    char *y;                       // [T][d] layer dtype, or nullptr
+    float *rowsq;                  // [n_tn][T] per column-tile sums of squares of the fp32 rows, or nullptr
     int T, d, F, Fp, n_tm, n_tn;   // Fp = F rounded up to a multiple of BK (row stride of h)
 };
+
+// Row sums of squares of a 128 x 128 output tile held in the accumulators of four waves (2 x 2
+// blocks of 32 x 32 each): 32-lane butterfly per row, then the two column halves in fixed order.
+__device__ __forceinline__ void down_rowsq(const f32x16 (&acc)[2][2], const DownParams &p, int tm, int tn, int wm,
+                                           int wn, int lane, int tid, float (&s_rs)[2][BM])
+{
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float v = fmaf(acc[mb][0][r], acc[mb][0][r], acc[mb][1][r] * acc[mb][1][r]);
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 8);
+            v += __shfl_xor(v, 4);
+            v += __shfl_xor(v, 2);
+            v += __shfl_xor(v, 1);
+            if ((lane & 31) == 0) s_rs[wn][wm * 64 + mb * 32 + acc_row(r, lane)] = v;
+        }
+    __syncthreads();
+    if (tid < BM) {
+        const int t = tm * BM + tid;
+        if (t < p.T) p.rowsq[(size_t)tn * p.T + t] = s_rs[0][tid] + s_rs[1][tid];
+    }
+}
 
 template <int ES>
 __global__ void __launch_bounds__(256)
@@ -352,6 +377,7 @@ k_prefix_down(const DownParams p)
     constexpr int VEC = 16 / ES;
     __shared__ __align__(16) char s_a[BM * ROW];
     __shared__ __align__(16) char s_b[BN * ROW];      // [n][k]: W_down tile transposed
+    __shared__ float s_rs[2][BM];
 
     const int total = p.n_tm * p.n_tn;
     const int tile = remap_block(blockIdx.x, total);
@@ -417,6 +443,8 @@ k_prefix_down(const DownParams p)
         const char *const sb[1] = {s_b + wn * 64 * ROW};
         mma_tile<ES, 1>(s_a + wm * 64 * ROW, sb, acc, lane);
     }
+    if (p.rowsq) down_rowsq(acc[0], p, tm, tn, wm, wn, lane, tid, s_rs);
+    if (!p.y) return;
     const int n = lane & 31;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
@@ -449,6 +477,7 @@ k_prefix_down_bf16(const DownParams p)
 {
     __shared__ __align__(16) char s_a[BM * DA_PITCH];
     __shared__ __align__(16) char s_b[DBK * DB_PITCH];
+    __shared__ float s_rs[2][BM];
 
     const int total = p.n_tm * p.n_tn;
     const int tile = remap_block(blockIdx.x, total);
@@ -523,6 +552,8 @@ k_prefix_down_bf16(const DownParams p)
                     acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], b[nb], acc[mb][nb], 0, 0, 0);
         }
     }
+    if (p.rowsq) down_rowsq(acc, p, tm, tn, wm, wn, lane, tid, s_rs);
+    if (!p.y) return;
     const int n = lane & 31;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
@@ -590,6 +621,45 @@ size_t clada_ws_prefix(int32_t d, int32_t d_ff, int32_t T, bool want_y)
     return need;
 }
 
+int clada_prefix_token_tiles(int T) { return (T + BM - 1) / BM; }
+int clada_prefix_col_tiles(int d) { return (d + BN - 1) / BN; }
+
+// Gate/up GEMM with the fused activation epilogue: part [n_tm][4][F] per-neuron partial
+// aggregates (always written), pool [T][F] |a| or nullptr, hbuf [T][Fp] h in the layer dtype or
+// nullptr (Fp = F rounded up to 64, zero past F).
+hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, float *part, float *pool,
+                               char *hbuf, hipStream_t stream)
+{
+    const int d = layer->d, F = layer->d_ff, es = (int)dtype_size(layer->dtype);
+    GateUpParams g;
+    g.x = (const char *)x; g.wg = (const char *)layer->w_gate; g.wu = (const char *)layer->w_up;
+    g.T = T; g.d = d; g.F = F; g.n_tm = (T + BM - 1) / BM; g.n_tn = (F + BN - 1) / BN;
+    g.part = part; g.pool = pool; g.hbuf = hbuf;
+    g.Fp = (int)align_up((size_t)F, 64);
+    const int total = g.n_tm * g.n_tn;
+    const int grid = (total + 7) / 8 * 8;
+    if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
+    else if (d % 64 == 0) hipLaunchKernelGGL(k_prefix_gateup_bf16, dim3(grid), dim3(256), 0, stream, g);
+    else         hipLaunchKernelGGL(k_prefix_gateup<2>, dim3(grid), dim3(256), 0, stream, g);
+    return hipGetLastError();
+}
+
+// Down projection of h [T][Fp]: y [T][d] in the layer dtype and/or rowsq [col tiles][T], the
+// per-column-tile sums of squares of the fp32 output rows (either may be nullptr).
+hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, char *y, float *rowsq,
+                             hipStream_t stream)
+{
+    const int d = layer->d, F = layer->d_ff, es = (int)dtype_size(layer->dtype);
+    DownParams q;
+    q.h = h; q.wd = (const char *)layer->w_down; q.y = y; q.rowsq = rowsq;
+    q.T = T; q.d = d; q.F = F; q.Fp = (int)align_up((size_t)F, 64);
+    q.n_tm = (T + BM - 1) / BM; q.n_tn = (d + BN - 1) / BN;
+    const int tot = q.n_tm * q.n_tn, grid = (tot + 7) / 8 * 8;
+    if (es == 4) hipLaunchKernelGGL(k_prefix_down<4>, dim3(grid), dim3(256), 0, stream, q);
+    else         hipLaunchKernelGGL(k_prefix_down_bf16, dim3(grid), dim3(256), 0, stream, q);
+    return hipGetLastError();
+}
+
 extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *layer, const void *x,
                                            int32_t T, void *y, const clada_prefix_out *out,
                                            void *hip_stream)
@@ -605,37 +675,19 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
     if (ctx->ws_bytes < need)
         return clada_fail(ctx, CLADA_ERR_WORKSPACE, "workspace %zu < %zu bytes needed", ctx->ws_bytes, need);
     const int es = (int)dtype_size(layer->dtype);
-    const int n_tm = (T + BM - 1) / BM, n_tn = (F + BN - 1) / BN;
+    const int n_tm = (T + BM - 1) / BM;
     char *ws = ctx->ws + CLADA_WS_HEADER;
     hipStream_t stream = (hipStream_t)hip_stream;
 
-    GateUpParams g;
-    g.x = (const char *)x; g.wg = (const char *)layer->w_gate; g.wu = (const char *)layer->w_up;
-    g.T = T; g.d = d; g.F = F; g.n_tm = n_tm; g.n_tn = n_tn;
-    g.part = reinterpret_cast<float *>(ws);
-    g.pool = out->abs_act_pool;
-    g.hbuf = y ? ws + align_up(sizeof(float) * 4 * (size_t)n_tm * F, 256) : nullptr;
-    g.Fp = (int)align_up((size_t)F, 64);
-    const int total = n_tm * n_tn;
-    const int grid = (total + 7) / 8 * 8;
-    if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
-    else if (d % 64 == 0) hipLaunchKernelGGL(k_prefix_gateup_bf16, dim3(grid), dim3(256), 0, stream, g);
-    else         hipLaunchKernelGGL(k_prefix_gateup<2>, dim3(grid), dim3(256), 0, stream, g);
-    CLADA_CHECK_HIP(ctx, hipGetLastError());
-    if (y) {
-        DownParams q;
-        q.h = g.hbuf; q.wd = (const char *)layer->w_down; q.y = (char *)y;
-        q.T = T; q.d = d; q.F = F; q.Fp = g.Fp; q.n_tm = n_tm; q.n_tn = (d + BN - 1) / BN;
-        const int tot2 = q.n_tm * q.n_tn, grid2 = (tot2 + 7) / 8 * 8;
-        if (es == 4) hipLaunchKernelGGL(k_prefix_down<4>, dim3(grid2), dim3(256), 0, stream, q);
-        else         hipLaunchKernelGGL(k_prefix_down_bf16, dim3(grid2), dim3(256), 0, stream, q);
-        CLADA_CHECK_HIP(ctx, hipGetLastError());
-    }
+    float *part = reinterpret_cast<float *>(ws);
+    char *hbuf = y ? ws + align_up(sizeof(float) * 4 * (size_t)n_tm * F, 256) : nullptr;
+    CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, part, out->abs_act_pool, hbuf, stream));
+    if (y) CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, hbuf, T, (char *)y, nullptr, stream));
     if (out->sum_abs_act || out->sum_sq_act || out->max_abs_act || out->sum_sq_h || out->A) {
         if (es == 4) hipLaunchKernelGGL(k_prefix_reduce<4>, dim3((F + 3) / 4), dim3(256), 0, stream,
-                                        (const char *)layer->w_down, d, F, g.part, n_tm, *out);
+                                        (const char *)layer->w_down, d, F, part, n_tm, *out);
         else         hipLaunchKernelGGL(k_prefix_reduce<2>, dim3((F + 3) / 4), dim3(256), 0, stream,
-                                        (const char *)layer->w_down, d, F, g.part, n_tm, *out);
+                                        (const char *)layer->w_down, d, F, part, n_tm, *out);
         CLADA_CHECK_HIP(ctx, hipGetLastError());
     }
     return CLADA_OK;
