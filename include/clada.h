@@ -187,6 +187,36 @@ clada_status clada_sparse_ffn_decode(clada_ctx *ctx, const clada_layer *layer, c
 clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
                                     int32_t B, void *y, void *hip_stream);
 
+/* Prefix-static masks.  The generation phase of the algorithm "CLADA Inference"
+ * says the masks are regenerated "by thresholding A": read literally, the
+ * prefill magnitudes A_j (clada_prefix_out.A, neuron-activation equation of
+ * section 3.2.1) are compared with tau_final, so a layer has one mask per
+ * indicator pattern and the gate rows of cut neurons are never read.
+ *   clada_static_mask_threshold: active_idx = ascending { j : A[j] >= tau_final[0] }
+ *     (cut iff strictly below; NaN is cut), n_active[0] = its size.
+ *   clada_static_mask_topk: the k neurons with the largest score (hard top-k on a
+ *     prefix aggregate, how section 4 characterises the Griffin baseline); equal
+ *     scores go to the lower index, NaN ranks below every number; ascending
+ *     indices, n_active[0] = k.  0 <= k <= d_ff.
+ * A / score [d_ff] fp32, tau_final [1] fp32, active_idx [d_ff] int32 (entries past
+ * the count untouched), n_active [1] int32: all device. */
+clada_status clada_static_mask_threshold(clada_ctx *ctx, const float *A, int32_t d_ff,
+                                         const float *tau_final, int32_t *active_idx,
+                                         int32_t *n_active, void *hip_stream);
+clada_status clada_static_mask_topk(clada_ctx *ctx, const float *score, int32_t d_ff, int32_t k,
+                                    int32_t *active_idx, int32_t *n_active, void *hip_stream);
+
+/* Sparse SwiGLU FFN over a given neuron list (the sparse forward pass of the
+ * algorithm "CLADA Inference" with a mask that does not depend on the token):
+ *   y_b = sum_{j in active_idx[0..n_active[0])} SiLU(W_gate[j,:] . x_b) (W_up[j,:] . x_b) W_down[j,:]
+ * for every token b of x [B][d].  Only the listed neurons' rows of the three
+ * matrices are read.  active_idx ascending int32 in [0,d_ff), n_active [1] int32,
+ * both device (e.g. straight from the two calls above, or from
+ * clada_sparse_ffn_decode).  Bit-reproducible from run to run. */
+clada_status clada_static_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
+                                     int32_t B, const int32_t *active_idx, const int32_t *n_active,
+                                     void *y, void *hip_stream);
+
 /* Measurement helpers (no part of the method).  clada_diag_stream_read reads
  * `bytes` (a multiple of 8192) of device memory once, in the decode kernels'
  * access pattern (each wave streams whole 8 KiB rows with non-temporal 16-byte

@@ -210,3 +210,27 @@ def cett_search(w_gate, w_up, w_down, x, bound=0.2):
                                           C.byref(tau), C.byref(mean))
     assert rc in (0, 3, 4), rc
     return tau.value, mean.value, rc
+
+
+def static_mask_threshold(A, tau):
+    """(mask bool [F], ascending idx) of the neurons with A_j >= tau."""
+    a, pa = _f64(np.ravel(A))
+    F = a.size
+    mask, pm = _out((F,), np.uint8)
+    idx, pi = _out((F,), np.int32)
+    n = C.c_int32()
+    rc = _load().clada_oracle_static_mask_threshold(pa, F, C.c_double(float(tau)), pm, pi, C.byref(n))
+    assert rc == 0, rc
+    return mask.astype(bool), idx[: n.value].copy()
+
+
+def static_mask_topk(score, k):
+    """(mask bool [F], ascending idx) of the k largest scores (ties to the lower index, NaN last)."""
+    a, pa = _f64(np.ravel(score))
+    F = a.size
+    mask, pm = _out((F,), np.uint8)
+    idx, pi = _out((F,), np.int32)
+    n = C.c_int32()
+    rc = _load().clada_oracle_static_mask_topk(pa, F, int(k), pm, pi, C.byref(n))
+    assert rc == 0, rc
+    return mask.astype(bool), idx[: n.value].copy()

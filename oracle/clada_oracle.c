@@ -513,3 +513,61 @@ int clada_oracle_cett_search(const float *w_gate, const float *w_up, const float
     free(h); free(ev); free(c); free(den); free(cur);
     return rc;
 }
+
+/* ------------------------------------------------------------------------
+ * Prefix-static masks.
+ *
+ * (i) The generation-phase line "regenerate the masks by thresholding A" of the
+ * algorithm "CLADA Inference" read literally: the prefill magnitudes A_j of the
+ * neuron-activation equation (section 3.2.1) are compared with tau_final;
+ * keep iff A_j >= tau (cut iff strictly below, as in the cut set of the
+ * base-threshold equation; NaN is cut).
+ * (ii) A hard top-k on a per-neuron prefix score, the way section 4 describes
+ * the Griffin baseline: the k neurons with the largest score; equal scores go
+ * to the lower index; NaN ranks below every number.
+ * Outputs: mask [d_ff] 0/1 (may be NULL), idx ascending (may be NULL), *n.
+ * ---------------------------------------------------------------------- */
+int clada_oracle_static_mask_threshold(const double *A, int d_ff, double tau,
+                                       uint8_t *mask, int32_t *idx, int32_t *n)
+{
+    if (!A || !n || d_ff <= 0) return 1;
+    int32_t c = 0;
+    for (int j = 0; j < d_ff; ++j) {
+        int keep = A[j] >= tau;
+        if (mask) mask[j] = (uint8_t)keep;
+        if (keep) { if (idx) idx[c] = j; ++c; }
+    }
+    *n = c;
+    return 0;
+}
+
+typedef struct { double s; int j; } score_item;
+
+static int cmp_score_desc(const void *a, const void *b)
+{
+    const score_item *x = (const score_item *)a, *y = (const score_item *)b;
+    int xn = x->s != x->s, yn = y->s != y->s;
+    if (xn != yn) return xn - yn;                       /* numbers before NaN */
+    if (!xn && x->s != y->s) return (x->s < y->s) - (x->s > y->s);   /* larger first */
+    return (x->j > y->j) - (x->j < y->j);               /* then lower index first */
+}
+
+int clada_oracle_static_mask_topk(const double *score, int d_ff, int k,
+                                  uint8_t *mask, int32_t *idx, int32_t *n)
+{
+    if (!score || !n || d_ff <= 0 || k < 0 || k > d_ff) return 1;
+    score_item *it = (score_item *)malloc(sizeof(score_item) * (size_t)d_ff);
+    uint8_t *m = (uint8_t *)calloc((size_t)d_ff, 1);
+    if (!it || !m) { free(it); free(m); return 2; }
+    for (int j = 0; j < d_ff; ++j) { it[j].s = score[j]; it[j].j = j; }
+    qsort(it, (size_t)d_ff, sizeof(score_item), cmp_score_desc);
+    for (int r = 0; r < k; ++r) m[it[r].j] = 1;
+    int32_t c = 0;
+    for (int j = 0; j < d_ff; ++j)
+        if (m[j]) { if (idx) idx[c] = j; ++c; }
+    if (mask) memcpy(mask, m, (size_t)d_ff);
+    *n = c;
+    free(it);
+    free(m);
+    return 0;
+}

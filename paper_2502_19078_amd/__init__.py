@@ -9,4 +9,5 @@ library is not built.
 from .binding import (Context, Layer, PrefixStats, CladaError, cognitive_signals,  # noqa: F401
                       dense_ffn_decode, lib_path, load_library, prefix_stats,
                       sparse_ffn_decode, threshold, threshold_calibrate,
-                      threshold_search_cett, cett_eval, workspace_bytes)
+                      threshold_search_cett, cett_eval, static_mask_threshold,
+                      static_mask_topk, static_ffn_decode, workspace_bytes)

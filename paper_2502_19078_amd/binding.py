@@ -71,9 +71,13 @@ def load_library() -> C.CDLL:
     lib.clada_diag_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
     lib.clada_threshold_search_cett.argtypes = [vp, C.POINTER(_CLayer), vp, i32, C.c_float, i32, vp, vp, vp]
     lib.clada_cett_eval.argtypes = [vp, C.POINTER(_CLayer), vp, i32, C.c_float, vp, vp, vp]
+    lib.clada_static_mask_threshold.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    lib.clada_static_mask_topk.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    lib.clada_static_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp, vp, vp]
     lib.clada_diag_kernel_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times",
-                 "clada_threshold_search_cett", "clada_cett_eval", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
+                 "clada_threshold_search_cett", "clada_cett_eval", "clada_static_mask_threshold",
+                 "clada_static_mask_topk", "clada_static_ffn_decode", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
                  "clada_cognitive_signals", "clada_threshold", "clada_sparse_ffn_decode",
                  "clada_dense_ffn_decode"):
         getattr(lib, name).restype = C.c_int
@@ -257,6 +261,41 @@ def dense_ffn_decode(ctx: Context, layer: Layer, x: torch.Tensor, y: torch.Tenso
     if y is None:
         y = torch.empty_like(x)
     ctx.check(ctx._lib.clada_dense_ffn_decode(ctx._h, C.byref(cl), _ptr(x), B, _ptr(y), _stream(x)))
+    return y
+
+
+def static_mask_threshold(ctx: Context, A: torch.Tensor, tau_final: torch.Tensor):
+    """(active_idx [F] int32, n_active [1] int32): ascending neurons with A_j >= tau_final[0]."""
+    assert A.is_cuda and A.dtype == torch.float32 and A.is_contiguous()
+    assert tau_final.is_cuda and tau_final.dtype == torch.float32 and tau_final.numel() >= 1
+    idx = torch.empty(A.numel(), dtype=torch.int32, device=A.device)
+    n = torch.empty(1, dtype=torch.int32, device=A.device)
+    ctx.check(ctx._lib.clada_static_mask_threshold(ctx._h, _ptr(A), A.numel(), _ptr(tau_final), _ptr(idx), _ptr(n),
+                                                   _stream(A)))
+    return idx, n
+
+
+def static_mask_topk(ctx: Context, score: torch.Tensor, k: int):
+    """(active_idx [F] int32, n_active [1] int32): ascending indices of the k largest scores."""
+    assert score.is_cuda and score.dtype == torch.float32 and score.is_contiguous()
+    idx = torch.empty(score.numel(), dtype=torch.int32, device=score.device)
+    n = torch.empty(1, dtype=torch.int32, device=score.device)
+    ctx.check(ctx._lib.clada_static_mask_topk(ctx._h, _ptr(score), score.numel(), int(k), _ptr(idx), _ptr(n),
+                                              _stream(score)))
+    return idx, n
+
+
+def static_ffn_decode(ctx: Context, layer: Layer, x: torch.Tensor, active_idx: torch.Tensor,
+                      n_active: torch.Tensor, y: torch.Tensor | None = None) -> torch.Tensor:
+    cl = layer.c_struct()
+    B = x.shape[0]
+    assert x.is_cuda and x.is_contiguous() and x.shape == (B, cl.d) and x.dtype == layer.w_gate.dtype
+    assert active_idx.is_cuda and active_idx.dtype == torch.int32 and active_idx.is_contiguous()
+    assert n_active.is_cuda and n_active.dtype == torch.int32 and n_active.numel() >= 1
+    if y is None:
+        y = torch.empty_like(x)
+    ctx.check(ctx._lib.clada_static_ffn_decode(ctx._h, C.byref(cl), _ptr(x), B, _ptr(active_idx), _ptr(n_active),
+                                               _ptr(y), _stream(x)))
     return y
 
 

@@ -31,6 +31,8 @@ struct DecodeParams {
     const float *tau;           // [B] (unused when DENSE)
     float *partial;             // [P][B][d]
     unsigned char *keep;        // [B][F] or nullptr
+    const int *idx;             // LIST: neuron indices to run (ascending), device
+    const int *n_list;          // LIST: their count, device
     int d, F, ni_max;
 };
 
@@ -41,11 +43,13 @@ __device__ __forceinline__ u32x4 ld_stream16(const char *p)
 
 // ES = element size (2: bf16, 4: fp32); NCH = 16-byte chunks per lane per row;
 // NW = waves per workgroup; GB / UB = rows in flight per wave in the gate /
-// up-down phase.
-template <int ES, int NCH, int NW, int GB, int UB, bool DENSE>
+// up-down phase.  LIST (with DENSE): the neurons are entries blk, blk+P, ... of a caller-supplied
+// index list instead of rows blk, blk+P, ... of the matrices; every listed neuron is kept.
+template <int ES, int NCH, int NW, int GB, int UB, bool DENSE, bool LIST = false>
 __global__ void __launch_bounds__(NW * 64)
 k_ffn_decode(const DecodeParams p)
 {
+    static_assert(!LIST || DENSE, "a list run keeps every listed neuron");
     constexpr int VEC = 16 / ES;
     extern __shared__ __align__(16) unsigned char smem[];
     float *s_a = reinterpret_cast<float *>(smem);
@@ -58,7 +62,13 @@ k_ffn_decode(const DecodeParams p)
     const int blk = blockIdx.x, P = gridDim.x, b = blockIdx.y;
     const int d = p.d, F = p.F;
     const size_t rowbytes = (size_t)d * ES;
-    const int ni = blk < F ? (F - blk + P - 1) / P : 0;
+    int n_src = F;
+    if (LIST) n_src = min(max(p.n_list[0], 0), F);
+    const int ni = blk < n_src ? (n_src - blk + P - 1) / P : 0;
+    auto neuron = [&](int i) -> size_t {
+        if (LIST) return (size_t)min(max(p.idx[blk + (size_t)P * i], 0), F - 1);
+        return blk + (size_t)P * i;
+    };
 
     bool ok[NCH];
     int coff[NCH];
@@ -80,7 +90,7 @@ k_ffn_decode(const DecodeParams p)
 #pragma unroll
         for (int r = 0; r < GB; ++r) {
             const bool rv = i0 + r < ni;
-            const char *row = p.wg + (size_t)(blk + (size_t)P * (rv ? i0 + r : i0)) * rowbytes;
+            const char *row = p.wg + neuron(rv ? i0 + r : i0) * rowbytes;
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 u32x4 v = {0u, 0u, 0u, 0u};
@@ -105,7 +115,7 @@ k_ffn_decode(const DecodeParams p)
             if (lane == 0 && i < ni) {
                 s_a[i] = a;
                 s_flag[i] = keep ? 1 : 0;
-                if (p.keep) p.keep[(size_t)b * F + blk + (size_t)P * i] = keep ? 1 : 0;
+                if (p.keep) p.keep[(size_t)b * F + neuron(i)] = keep ? 1 : 0;
             }
         }
     }
@@ -142,7 +152,7 @@ k_ffn_decode(const DecodeParams p)
             const bool rv = t < cnt;
             const int i = rv ? s_list[t] : 0;
             av[r] = rv ? s_a[i] : 0.0f;
-            const size_t off = (size_t)(blk + (size_t)P * i) * rowbytes;
+            const size_t off = neuron(i) * rowbytes;
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 u32x4 u = {0u, 0u, 0u, 0u}, w = {0u, 0u, 0u, 0u};
@@ -757,12 +767,13 @@ hipError_t launch_b1(clada_ctx *ctx, const B1Params &p, int P, bool dense, bool 
 }
 
 template <int ES, int NCH, int NW, int GB, int UB>
-hipError_t launch_decode(const DecodeParams &p, int P, int B, bool dense, hipStream_t st)
+hipError_t launch_decode(const DecodeParams &p, int P, int B, bool dense, hipStream_t st, bool list = false)
 {
     constexpr int VEC = 16 / ES;
     const size_t lds = align_up(sizeof(int) * (3 * (size_t)p.ni_max + 4), 16) +
                        sizeof(float) * (size_t)(NW / 2) * NCH * 64 * VEC;
-    auto kern = dense ? k_ffn_decode<ES, NCH, NW, GB, UB, true> : k_ffn_decode<ES, NCH, NW, GB, UB, false>;
+    auto kern = list ? k_ffn_decode<ES, NCH, NW, GB, UB, true, true>
+                     : dense ? k_ffn_decode<ES, NCH, NW, GB, UB, true> : k_ffn_decode<ES, NCH, NW, GB, UB, false>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -798,6 +809,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     p.x = (const char *)x; p.tau = tau;
     p.partial = reinterpret_cast<float *>(ws);
     p.keep = lists ? reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256)) : nullptr;
+    p.idx = nullptr; p.n_list = nullptr;
     p.d = d; p.F = F; p.ni_max = (F + P - 1) / P;
     hipStream_t stream = (hipStream_t)hip_stream;
 
@@ -888,7 +900,63 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     return CLADA_OK;
 }
 
+// Decode over a caller-supplied neuron list (prefix-static masks): gate, up and down rows of the
+// listed neurons only.
+clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const void *x, int32_t B,
+                             const int32_t *idx, const int32_t *n_active, void *y, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    clada_status st = clada_check_layer(ctx, layer);
+    if (st != CLADA_OK) return st;
+    if (!x || !y || !idx || !n_active) return clada_fail(ctx, CLADA_ERR_NULL, "x, y, active_idx or n_active is NULL");
+    if (B < 1 || B > CLADA_MAX_BATCH) return clada_fail(ctx, CLADA_ERR_SHAPE, "B=%d outside [1,%d]", B, CLADA_MAX_BATCH);
+    if (!aligned16(x) || !aligned16(y)) return clada_fail(ctx, CLADA_ERR_ALIGN, "x and y must be 16-byte aligned");
+    const int d = layer->d, F = layer->d_ff;
+    const size_t need = CLADA_WS_HEADER + clada_ws_decode(d, F, B);
+    if (ctx->ws_bytes < need)
+        return clada_fail(ctx, CLADA_ERR_WORKSPACE, "workspace %zu < %zu bytes needed", ctx->ws_bytes, need);
+    const int es = (int)dtype_size(layer->dtype);
+    int P = ctx->num_cu * ctx->opt_decode_wgs_per_cu;
+    if (P > F) P = F;
+    if (P > CLADA_MAX_DECODE_WGS) P = CLADA_MAX_DECODE_WGS;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    DecodeParams p;
+    p.wg = (const char *)layer->w_gate; p.wu = (const char *)layer->w_up; p.wd = (const char *)layer->w_down;
+    p.x = (const char *)x; p.tau = nullptr;
+    p.partial = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
+    p.keep = nullptr; p.idx = idx; p.n_list = n_active;
+    p.d = d; p.F = F; p.ni_max = (F + P - 1) / P;
+    const int nch = (d * es + 1023) / 1024;
+    hipError_t e = hipErrorInvalidValue;
+#define CLADA_LIST_CASE(ES_, NCH_, NW_, GB_, UB_)                                          \
+    if (es == ES_ && nch <= NCH_ && e == hipErrorInvalidValue)                             \
+        e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, true, stream, true);
+    CLADA_LIST_CASE(2, 1, 8, 2, 2)
+    CLADA_LIST_CASE(2, 2, 8, 2, 2)
+    CLADA_LIST_CASE(2, 4, 8, 2, 2)
+    CLADA_LIST_CASE(2, 8, 8, 1, 1)
+    CLADA_LIST_CASE(2, 10, 8, 1, 1)
+    CLADA_LIST_CASE(2, 16, 8, 1, 1)
+    CLADA_LIST_CASE(4, 1, 8, 2, 2)
+    CLADA_LIST_CASE(4, 2, 8, 2, 2)
+    CLADA_LIST_CASE(4, 4, 8, 2, 2)
+    CLADA_LIST_CASE(4, 8, 8, 1, 1)
+    CLADA_LIST_CASE(4, 16, 8, 1, 1)
+#undef CLADA_LIST_CASE
+    CLADA_CHECK_HIP(ctx, e);
+    launch_finalize(es, p.partial, P, B, d, (char *)y, nullptr, stream);
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    return CLADA_OK;
+}
+
 }  // namespace
+
+extern "C" clada_status clada_static_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
+                                                int32_t B, const int32_t *active_idx, const int32_t *n_active,
+                                                void *y, void *hip_stream)
+{
+    return run_list_decode(ctx, layer, x, B, active_idx, n_active, y, hip_stream);
+}
 
 void clada_launch_finalize(int es, const float *partial, int P, int B, int d, char *y, hipStream_t stream)
 {
