@@ -56,6 +56,9 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
                                   const float *tau, void *y, unsigned char *keep, float *partial,
                                   char *scratch, bool dense, hipStream_t stream, bool *ran);
 size_t clada_ws_decode_batched(int32_t d_ff);
+// Batch-1 decode over a neuron list with the streaming kernel, when the shape fits it (*ran).
+hipError_t clada_decode_list_b1(clada_ctx *ctx, const clada_layer *layer, const void *x, const int32_t *idx,
+                                const int32_t *n_active, float *partial, int *P_out, hipStream_t stream, bool *ran);
 // Fixed-order sum of P partial y's [P][B][d] (fp32) into y (element size es).
 void clada_launch_finalize(int es, const float *partial, int P, int B, int d, char *y, hipStream_t stream);
 
@@ -91,6 +94,33 @@ __device__ __forceinline__ void unpack_row16(const u32x4 v, float (&f)[4])
 {
     f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
     f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+}
+
+// 16-byte streaming load of weights that are read once (non-temporal: does not displace x and
+// the partial sums in the caches).
+__device__ __forceinline__ u32x4 ld_stream16(const char *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+// fp32 += bf16 pair . bf16 pair (exact products, fp32 accumulate).  The operands go through
+// plain scalars: bit-casting a vector element expression directly was seen to pick lane 0.
+__device__ __forceinline__ float dot2_bf16(unsigned int a, unsigned int b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
+template <int ES>
+__device__ __forceinline__ float dot16(const u32x4 w, const u32x4 x, float acc)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const unsigned int wk = w[k], xk = x[k];
+        acc = ES == 2 ? dot2_bf16(wk, xk, acc) : fmaf(__uint_as_float(wk), __uint_as_float(xk), acc);
+    }
+    return acc;
 }
 
 // fp32 -> bf16 bits, round to nearest even (NaN stays NaN).

@@ -36,10 +36,6 @@ struct DecodeParams {
     int d, F, ni_max;
 };
 
-__device__ __forceinline__ u32x4 ld_stream16(const char *p)
-{
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-}
 
 // ES = element size (2: bf16, 4: fp32); NCH = 16-byte chunks per lane per row;
 // NW = waves per workgroup; GB / UB = rows in flight per wave in the gate /
@@ -387,26 +383,6 @@ struct B1Params {
                                 // (read at kernel start, so graph replays stay correct)
     int d, F, K0;
 };
-
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-
-// fp32 += bf16 pair . bf16 pair (exact products, fp32 accumulate).  The operands go through
-// plain scalars: bit-casting a vector element expression directly was seen to pick lane 0.
-__device__ __forceinline__ float dot2_bf16(unsigned int a, unsigned int b, float acc)
-{
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
-}
-
-template <int ES>
-__device__ __forceinline__ float dot16(const u32x4 w, const u32x4 x, float acc)
-{
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const unsigned int wk = w[k], xk = x[k];
-        acc = ES == 2 ? dot2_bf16(wk, xk, acc) : fmaf(__uint_as_float(wk), __uint_as_float(xk), acc);
-    }
-    return acc;
-}
 
 // Exclusive prefix sum over the 64 lanes of a wave (no barrier); *total gets the wave sum.
 __device__ __forceinline__ int wave_excl_scan(int v, int lane, int *total)
@@ -927,6 +903,16 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
     p.keep = nullptr; p.idx = idx; p.n_list = n_active;
     p.d = d; p.F = F; p.ni_max = (F + P - 1) / P;
     const int nch = (d * es + 1023) / 1024;
+    if (B == 1 && ctx->opt_decode_b1 >= 1) {          // streaming kernel for whole-KiB rows
+        bool ran = false;
+        int Pl = 0;
+        CLADA_CHECK_HIP(ctx, clada_decode_list_b1(ctx, layer, x, idx, n_active, p.partial, &Pl, stream, &ran));
+        if (ran) {
+            launch_finalize(es, p.partial, Pl, 1, d, (char *)y, nullptr, stream);
+            CLADA_CHECK_HIP(ctx, hipGetLastError());
+            return CLADA_OK;
+        }
+    }
     hipError_t e = hipErrorInvalidValue;
 #define CLADA_LIST_CASE(ES_, NCH_, NW_, GB_, UB_)                                          \
     if (es == ES_ && nch <= NCH_ && e == hipErrorInvalidValue)                             \

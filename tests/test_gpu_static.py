@@ -66,6 +66,8 @@ CASES = [
     ("c2", 4096, 640, 1),        # config 2's row length, whole-KiB rows
     ("c2", 72, 129, 4),
     ("c5", 5120, 512, 2),
+    ("c5", 5120, 700, 1),        # 10 KiB rows: the unpipelined variant of the list kernel
+    ("c1", 512, 4100, 1),        # fp32, 2 KiB rows, 16 entries per workgroup and a ragged tail
 ]
 
 
@@ -137,6 +139,30 @@ def test_prefix_static_chain(clada, mode):
     ref = oracle.decode_given_mask(*w, x, keep_gpu[None, :])
     assert_close_y(to_np(y), ref, TOL_Y[cfg.dtype], "chain output")
     assert 0.3 * F < cnt < 0.8 * F
+
+
+@pytest.mark.parametrize("cfg_name", ["c2", "c4", "c5"])
+def test_list_decode_full_size_layers(clada, cfg_name):
+    """Full layer shapes at batch 1, list = hard top-k at the configuration's target sparsity."""
+    cfg = synth.CONFIGS[cfg_name]
+    d, F = cfg.d, cfg.d_ff
+    w = synth.layer_weights(cfg, 0, 7)
+    x = synth.decode_hidden(cfg, 0, 7, 0, B=1)
+    ctx = _ctx(clada, d, F, 1)
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd = to_dev(x, cfg.dtype)
+    score = np.abs(np.random.default_rng(5).standard_normal(F)).astype(np.float32)
+    k = int(round((1 - 0.45) * F))
+    idx, n = clada.static_mask_topk(ctx, torch.from_numpy(score).to(DEV), k)
+    y = clada.static_ffn_decode(ctx, layer, xd, idx, n)
+    ctx.set_option("decode.b1", 0)                       # the generic list kernels on the same list
+    y_gen = clada.static_ffn_decode(ctx, layer, xd, idx, n)
+    torch.cuda.synchronize()
+    keep = oracle.static_mask_topk(score, k)[0]
+    assert np.array_equal(np.flatnonzero(keep), idx.cpu().numpy()[:k])
+    ref = oracle.decode_given_mask(*w, x, keep[None, :])
+    assert_close_y(to_np(y), ref, TOL_Y[cfg.dtype], "list kernel")
+    assert_close_y(to_np(y_gen), ref, TOL_Y[cfg.dtype], "generic list kernel")
 
 
 def test_list_decode_accepts_the_dynamic_calls_lists(clada):
