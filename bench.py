@@ -36,6 +36,11 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
+    ap.add_argument("--q", type=float, default=0.0, help="override the configuration's target sparsity")
+    ap.add_argument("--batch", type=int, default=0, help="override the configuration's decode batch")
+    ap.add_argument("--shared-frac", type=float, default=0.0,
+                    help="c in [0,1]: decode tokens of a batch share a component, x_b = sqrt(c) x_shared + sqrt(1-c) x_b'")
+    ap.add_argument("--temperature", type=float, default=1.0, help="divide the Zipf logits by this (peaked < 1 < flat)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run only a short fixed call sequence (for rocprofv3 --pmc counter runs) and exit")
     args = ap.parse_args()
@@ -54,6 +59,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS[args.config]
+    if args.q or args.batch:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, q=args.q or cfg.q, B=args.batch or cfg.B)
     if args.pmc_probe:
         return pmc_probe(cfg, args, clada, binding, synth, torch, dev)
     L = args.layers or cfg.L
@@ -86,9 +94,11 @@ def main():
             if cfg.dtype == "bf16":
                 ts = [t.view(torch.bfloat16) for t in ts]
             layers[l] = clada.Layer(*ts)
-    x_host = np.stack([np.stack([synth.decode_hidden(cfg, args.seed, l, s) for l in range(L)]) for s in range(nsteps)])
+    x_host = np.stack([np.stack([synth.decode_hidden(cfg, args.seed, l, s, shared_frac=args.shared_frac)
+                                 for l in range(L)]) for s in range(nsteps)])
     x_all = to_dev(x_host.reshape(nsteps, L, B, d))                       # [step][layer][B][d]
-    z_host = np.stack([synth.logits(cfg, args.seed, s)[0] for s in range(nsteps)])   # [step][B][V]
+    z_host = np.stack([synth.logits(cfg, args.seed, s, temperature=args.temperature)[0]
+                       for s in range(nsteps)])                              # [step][B][V]
     tok_host = np.stack([synth.draw_tokens(cfg, args.seed, s, z_host[s]) for s in range(nsteps)])
     z_all = torch.from_numpy(z_host).to(dev)
     tok_all = torch.from_numpy(tok_host).to(dev)
@@ -305,6 +315,7 @@ def main():
                                f"decode batch {B}, prefix {T}, V={V}, target sparsity {cfg.q}",
                    "weights": f"N(0, std {cfg.w_std:g})", "hidden": "N(0,1)",
                    "lambda": 0.80, "gamma": 0.12, "tau_s": round(tau_s, 4), "tau_H": round(tau_H, 4),
+                   "shared_frac": args.shared_frac, "temperature": args.temperature,
                    "graph": not args.no_graph, "options": args.option},
         "sparsity_per_token": round(float(rho_token), 4),
         "sparsity_union": round(float(rho_union), 4),

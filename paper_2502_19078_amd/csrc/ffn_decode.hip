@@ -805,7 +805,9 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             b.epoch = epoch;
             b.d = d; b.F = F;
             b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
-            bool balance = !dense && ctx->opt_decode_b1 == 1 && ni_b <= 56;
+            // balancing pays for 8 KiB rows; with 10 KiB rows the balanced variant runs out of registers and
+            // was measured slower (57 vs 51 us per 13B-shape layer at 45 % sparsity) than the plain split
+            bool balance = !dense && ctx->opt_decode_b1 == 1 && ni_b <= 56 && nch != 10;
             hipError_t eb = hipErrorNotSupported;
             for (int attempt = 0; attempt < 2 && eb == hipErrorNotSupported; ++attempt) {
                 if (es == 2 && nch == 8) eb = launch_b1<2, 8, 16>(ctx, b, Pb, dense, balance, stream);

@@ -5,10 +5,11 @@
 // 16-wide M dimension.  Weights are still read once, and only for neurons kept by at least
 // one token (the union); every output row uses its own mask.
 //
-//   kernel A (gate + up -> h): workgroup p owns the 16-neuron tiles p, p+P, ...  Its 8 waves
+//   kernel A (gate + up -> h): workgroup p owns a contiguous run of neurons (whole octets, dealt
+//     out evenly), taken 16 at a time.  Its 8 waves
 //     split the d (= K) dimension: wave w keeps its slice of x as MFMA A-fragments in registers
 //     for the whole kernel and streams its slice of the 16 weight rows as B-fragments (lane =
-//     (neuron, 16-byte k-group): a row's 64 bytes per instruction, the row's whole slice over
+//     (neuron, k-group): 128 contiguous bytes of a row per pair of instructions, the row's whole slice over
 //     the k loop).  The 8 partial 16x16 tiles are summed through LDS in fixed order; SiLU, the
 //     per-token fp32 compare and the per-neuron 16-bit keep masks follow.  A ballot compacts
 //     the workgroup's union-kept neurons; the same MFMA loop over W_up rows gathered through
@@ -16,7 +17,9 @@
 //     one union flag per neuron.
 //   kernel B (down): 2-D split -- column groups of 256 x row groups (a fixed range of neuron
 //     indices each, its kept neurons compacted from the union flags by ballot + scan), so only
-//     R partial y's exist instead of one per workgroup.  W_down rows arrive as 512-byte segments, are staged per wave in LDS and read
+//     R partial y's exist instead of one per workgroup.  Work is dealt to the waves in units of 32
+//     neurons x 128 columns (wave w: column half w & 1, neuron blocks w >> 1, + 4, ...).  W_down
+//     rows arrive as 256-byte segments, are staged per wave in LDS and read
 //     back K-major with ds_read_b64_tr_b16 as MFMA B-fragments; h is split into bf16 hi + lo
 //     A-fragments (two MFMAs), so the down projection keeps ~fp32 accuracy of h.
 //   kernel C: k_ffn_finalize adds the R partials in fixed order.
@@ -61,9 +64,29 @@ k_bat_gateup(const BatParams p)
     const int blk = blockIdx.x, P = gridDim.x;
     const int d = p.d, F = p.F, B = p.B;
     const size_t rowb = (size_t)d * 2;
-    const int koff = (wave * KSTEPS * 32 + 8 * q) * 2;      // byte offset of this lane's first k-group
-    const int nt = (F + 15) / 16;
-    const int ni = blk < nt ? (nt - blk + P - 1) / P : 0;   // <= MAX_TILES
+    // This wave's k-slice of every row is SLICE bytes, taken in NPART parts of PB <= 1024 bytes.  A
+    // load instruction reads one row's part as one contiguous piece (lane l: bytes 16 l ..; measured
+    // 6.6 TB/s, against 5.6 TB/s for 16 rows x 64 bytes per instruction, which is what the MFMA
+    // operand layout would ask for).  The wave then turns 16 such rows into B-fragments through its
+    // private LDS tile: row r is written contiguously at r * PITCH, and lane (neuron n, k-group q)
+    // reads chunk q * SP + ks of row n for k-step ks.  The order of k within the slice is free as
+    // long as x uses the same one.  PITCH = PB + 16 keeps both directions free of bank conflicts.
+    constexpr int SLICE = KSTEPS * 64;
+    constexpr int NPART = SLICE > 1024 ? 2 : 1;
+    constexpr int PB = SLICE / NPART, SP = PB / 64, PITCH = PB + 16;
+    static_assert(PB % 64 == 0 && PB <= 1024 && NPART * SP == KSTEPS, "slice split");
+    __shared__ __align__(16) char s_stage[8 * 16 * PITCH];
+    char *stage = s_stage + wave * 16 * PITCH;
+    const bool ld_on = lane < PB / 16;
+    const int koff = wave * SLICE;
+    // Neurons are dealt out in contiguous runs of whole octets: workgroup q owns octets
+    // [q no / P, (q+1) no / P), at most 64 neurons, so every workgroup streams the same number of
+    // rows to within 8 (16-neuron granularity would leave an eighth of the chip idle at the end).
+    const int no = (F + 7) / 8;
+    const int j_lo = 8 * (int)((long long)blk * no / P);
+    const int j_hi = min(8 * (int)((long long)(blk + 1) * no / P), F);
+    const int nown = j_hi - j_lo;                           // <= 64
+    const int ni = (nown + 15) / 16;                        // <= MAX_TILES
 
     if (tid < MAX_TILES * 16) s_km[tid] = 0;
     // this wave's slice of x as A-fragments: lane = (token n, k-group q)
@@ -71,21 +94,41 @@ k_bat_gateup(const BatParams p)
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
         u32x4 v = {0u, 0u, 0u, 0u};
-        if (n < B) v = *reinterpret_cast<const u32x4 *>(p.x + (size_t)n * rowb + koff + ks * 64);
+        if (n < B) v = *reinterpret_cast<const u32x4 *>(p.x + (size_t)n * rowb + koff + (ks / SP) * PB + (q * SP + ks % SP) * 16);
         xa[ks] = v;
     }
     __syncthreads();
 
-    // B-fragments of 16 weight rows (one per lane n): half h of this wave's k-slice
-    constexpr int KH = KSTEPS / 2;
-    auto half_load = [&](u32x4 (&wf)[KH], const char *w, int row, int h) {
-        const char *src = w + (size_t)row * rowb + koff + h * KH * 64;
+    // eight rows (half a tile) of one part: one load instruction per row; a row that does not
+    // exist (row < 0) loads nothing and contributes zeros
+    auto rows_load = [&](u32x4 (&wr)[8], const char *w, auto row_of, int unit, int half) {
+        const int tile = unit / NPART, part = unit % NPART;
 #pragma unroll
-        for (int ks = 0; ks < KH; ++ks) wf[ks] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + ks * 64));
+        for (int r = 0; r < 8; ++r) {
+            const int row = row_of(tile, 8 * half + r);
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (row >= 0 && ld_on)
+                v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w + (size_t)row * rowb + koff + part * PB + lane * 16));
+            wr[r] = v;
+        }
     };
-    auto half_mma = [&](const u32x4 (&wf)[KH], int h, f32x4 acc) {
+    auto stage_write = [&](const u32x4 (&wr)[8], int half) {
 #pragma unroll
-        for (int ks = 0; ks < KH; ++ks) acc = mfma16(xa[h * KH + ks], wf[ks], acc);
+        for (int r = 0; r < 8; ++r)
+            if (ld_on) *reinterpret_cast<u32x4 *>(stage + (8 * half + r) * PITCH + lane * 16) = wr[r];
+    };
+    // lanes of this wave exchange data through the tile: order the LDS traffic within the wave
+    auto wave_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto part_mma = [&](int part, f32x4 acc) {
+#pragma unroll
+        for (int ks = 0; ks < SP; ++ks) {
+            const u32x4 frag = *reinterpret_cast<const u32x4 *>(stage + n * PITCH + (q * SP + ks) * 16);
+            acc = mfma16(xa[part * SP + ks], frag, acc);
+        }
         return acc;
     };
     auto part_store = [&](const f32x4 acc, int buf) {
@@ -93,25 +136,32 @@ k_bat_gateup(const BatParams p)
         for (int r = 0; r < 4; ++r) s_part[buf][wave][r * 64 + lane] = acc[r];
     };
     // One pass over a list of tiles: D = X_slice * W_slice^T partial over this wave's k-slice.  The
-    // two halves of the next tile are requested while the current tile is multiplied and reduced;
-    // every path keeps a fixed number of loads in flight.
+    // rows of the next part are requested as soon as the current ones sit in LDS; every path keeps
+    // a fixed number of loads in flight.
     auto tile_pass = [&](const char *w, int ntiles, auto row_of, auto reduce) {
-        u32x4 wa[KH], wb[KH];
-        if (ntiles > 0) {
-            half_load(wa, w, row_of(0), 0);
-            half_load(wb, w, row_of(0), 1);
+        u32x4 wa[8], wb[8];
+        const int nunits = ntiles * NPART;
+        if (nunits > 0) {
+            rows_load(wa, w, row_of, 0, 0);
+            rows_load(wb, w, row_of, 0, 1);
         }
         for (int i = 0; i < ntiles; ++i) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            if (i + 1 < ntiles) {
-                const int nr = row_of(i + 1);
-                acc = half_mma(wa, 0, acc);
-                half_load(wa, w, nr, 0);
-                acc = half_mma(wb, 1, acc);
-                half_load(wb, w, nr, 1);
-            } else {
-                acc = half_mma(wa, 0, acc);
-                acc = half_mma(wb, 1, acc);
+#pragma unroll
+            for (int part = 0; part < NPART; ++part) {        // unrolled: x fragments stay in registers
+                const int u = i * NPART + part;
+                wave_sync();                                  // the previous part's fragment reads are done
+                if (u + 1 < nunits) {
+                    stage_write(wa, 0);
+                    rows_load(wa, w, row_of, u + 1, 0);
+                    stage_write(wb, 1);
+                    rows_load(wb, w, row_of, u + 1, 1);
+                } else {
+                    stage_write(wa, 0);
+                    stage_write(wb, 1);
+                }
+                wave_sync();
+                acc = part_mma(part, acc);
             }
             part_store(acc, i & 1);
             __syncthreads();
@@ -125,13 +175,13 @@ k_bat_gateup(const BatParams p)
         for (int w = 0; w < 8; ++w) s += s_part[buf][w][e];
         return s;
     };
-    auto gate_row = [&](int i) { return min(16 * (blk + P * i) + n, F - 1); };
+    auto gate_row = [&](int i, int rr) { return 16 * i + rr < nown ? j_lo + 16 * i + rr : -1; };
     auto gate_reduce = [&](int i) {
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
-            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = 16 * (blk + P * i) + nn;
+            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = j_lo + 16 * i + nn;
             const float a = silu_f32(tile_sum(i & 1, tid));
-            const bool valid = m < B && j < F;
+            const bool valid = m < B && j < j_hi;
             const bool keep = valid && (DENSE ? true : (fabsf(a) >= p.tau[m]));
             s_a[i][m][nn] = a;
             if (keep) atomicOr(&s_km[i * 16 + nn], 1 << m);
@@ -144,21 +194,17 @@ k_bat_gateup(const BatParams p)
     __syncthreads();
 
     // ---------------------------------------------------------------- union compaction (every wave)
-    const bool mine = lane < ni * 16 && s_km[lane] != 0;
+    const bool mine = lane < nown && s_km[lane] != 0;
     const unsigned long long bal = __ballot(mine);
     const int ku = __popcll(bal);
     if (mine) s_ul[__popcll(bal & ((1ull << lane) - 1ull))] = lane;
-    if (wave == 0 && lane < ni * 16) {                      // union flag of every owned neuron, for kernel B
-        const int j = 16 * (blk + P * (lane >> 4)) + (lane & 15);
-        if (j < F) p.uflag[j] = mine ? 1 : 0;
-    }
+    if (wave == 0 && lane < nown) p.uflag[j_lo + lane] = mine ? 1 : 0;   // union flag of every owned neuron, for kernel B
 
     // ---------------------------------------------------------------- up tiles over the union list
     const int nu = (ku + 15) / 16;
-    auto up_row = [&](int u) {
-        const int e = 16 * u + n;
-        const int li = s_ul[e < ku ? e : 0];
-        return 16 * (blk + P * (li >> 4)) + (li & 15);
+    auto up_row = [&](int u, int rr) {
+        const int e = 16 * u + rr;
+        return e < ku ? j_lo + s_ul[e] : -1;
     };
     auto up_reduce = [&](int u) {
         if (tid < 256) {
@@ -167,7 +213,7 @@ k_bat_gateup(const BatParams p)
             const int e2 = 16 * u + nn;
             if (e2 < ku) {
                 const int l2 = s_ul[e2];
-                const int j = 16 * (blk + P * (l2 >> 4)) + (l2 & 15);
+                const int j = j_lo + l2;
                 const float usum = tile_sum(u & 1, tid);
                 const bool keep = (s_km[l2] >> m) & 1;
                 p.hbuf[(size_t)m * F + j] = keep ? s_a[l2 >> 4][m][l2 & 15] * usum : 0.0f;
@@ -222,9 +268,13 @@ k_bat_down(const BatParams p)
     }
     const int nrows = s_rng[0];                                         // <= DN_MAX_ROWS (host check on F)
 
-    f32x4 acc[DN_COLS / 16];
+    // Wave w works on column half sub = w & 1 of the workgroup's 256 columns and on the 32-neuron
+    // blocks rw, rw + 4, ... (rw = w >> 1): units of 32 rows x 128 columns dealt round-robin, so the
+    // eight waves differ by at most one unit.
+    const int sub = wave & 1, rw = wave >> 1;
+    f32x4 acc[DN_SUB / 16];
 #pragma unroll
-    for (int t = 0; t < DN_COLS / 16; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < DN_SUB / 16; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int n = lane & 15, q = lane >> 4;
     unsigned char *tile = s_tile + wave * DN_TILE_BYTES;
@@ -240,7 +290,7 @@ k_bat_down(const BatParams p)
         }
     };
     // W_down[32 list entries][128 columns]: half-waves read 256-byte row pieces
-    auto w_load = [&](u32x4 (&wv)[8], int kb, int sub) {
+    auto w_load = [&](u32x4 (&wv)[8], int kb) {
 #pragma unroll
         for (int ii = 0; ii < 8; ++ii) {
             const int c = lane + 64 * ii, row = c >> 4, cc = c & 15;
@@ -252,7 +302,7 @@ k_bat_down(const BatParams p)
             wv[ii] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p.wd + (size_t)s_rows[er] * rowb + (size_t)col * 2));
         }
     };
-    auto process = [&](const u32x4 (&wv)[8], const u32x4 ahi, const u32x4 alo, int sub) {
+    auto process = [&](const u32x4 (&wv)[8], const u32x4 ahi, const u32x4 alo) {
 #pragma unroll
         for (int ii = 0; ii < 8; ++ii) {
             const int c = lane + 64 * ii, row = c >> 4, cc = c & 15;
@@ -268,9 +318,8 @@ k_bat_down(const BatParams p)
             const s16x4 b1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(src + 4 * DN_PITCH));
             const uint2 u0 = __builtin_bit_cast(uint2, b0), u1 = __builtin_bit_cast(uint2, b1);
             const u32x4 bf = {u0.x, u0.y, u1.x, u1.y};
-            const int ti = sub * (DN_SUB / 16) + t;
-            acc[ti] = mfma16(ahi, bf, acc[ti]);
-            acc[ti] = mfma16(alo, bf, acc[ti]);
+            acc[t] = mfma16(ahi, bf, acc[t]);
+            acc[t] = mfma16(alo, bf, acc[t]);
         }
     };
     auto split_h = [&](const float (&hv)[8], u32x4 &ahi, u32x4 &alo) {
@@ -284,61 +333,65 @@ k_bat_down(const BatParams p)
         alo = u32x4{lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
     };
 
-    // both halves of a block are requested up front; the next block's first half goes out
-    // before the current second half is consumed
+    // the next unit's rows are requested before the current unit is consumed
     u32x4 wA[8], wB[8];
-    float hv[8], hn[8];
-    if (wave < nkb) {
-        h_load(hv, wave);
-        w_load(wA, wave, 0);
-        w_load(wB, wave, 1);
+    float hA[8], hB[8];
+    if (rw < nkb) {
+        h_load(hA, rw);
+        w_load(wA, rw);
     }
-    for (int kb = wave; kb < nkb; kb += 8) {
+    for (int kb = rw; kb < nkb; kb += 8) {
         u32x4 ahi, alo;
-        split_h(hv, ahi, alo);
-        if (kb + 8 < nkb) {
-            process(wA, ahi, alo, 0);
-            h_load(hn, kb + 8);
-            w_load(wA, kb + 8, 0);
-            process(wB, ahi, alo, 1);
-            w_load(wB, kb + 8, 1);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) hv[i] = hn[i];
+        if (kb + 4 < nkb) {
+            h_load(hB, kb + 4);
+            w_load(wB, kb + 4);
+            split_h(hA, ahi, alo);
+            process(wA, ahi, alo);
+            if (kb + 8 < nkb) {
+                h_load(hA, kb + 8);
+                w_load(wA, kb + 8);
+                split_h(hB, ahi, alo);
+                process(wB, ahi, alo);
+            } else {
+                split_h(hB, ahi, alo);
+                process(wB, ahi, alo);
+            }
         } else {
-            process(wA, ahi, alo, 0);
-            process(wB, ahi, alo, 1);
+            split_h(hA, ahi, alo);
+            process(wA, ahi, alo);
         }
     }
 
-    // ---- fixed-order fold of the waves' accumulators through LDS, then the partial y of this row group
+    // ---- fixed-order fold of the four row-waves of each column half through LDS, then the partial
+    // y of this row group
     __syncthreads();
-    float *s_red = reinterpret_cast<float *>(s_tile);                   // [4][16 tiles][4][64]
-    constexpr int ACC_FLOATS = (DN_COLS / 16) * 4 * 64;
+    float *s_red = reinterpret_cast<float *>(s_tile);                   // [2 halves][2][8 tiles][4][64]
+    constexpr int ACC_FLOATS = (DN_SUB / 16) * 4 * 64;
 #pragma unroll
-    for (int s = 4; s >= 1; s >>= 1) {
-        if (wave >= s && wave < 2 * s) {
-            float *dst = s_red + (size_t)(wave - s) * ACC_FLOATS;
+    for (int s2 = 2; s2 >= 1; s2 >>= 1) {
+        if (rw >= s2 && rw < 2 * s2) {
+            float *dst = s_red + (size_t)(sub * 2 + (rw - s2)) * ACC_FLOATS;
 #pragma unroll
-            for (int t = 0; t < DN_COLS / 16; ++t)
+            for (int t = 0; t < DN_SUB / 16; ++t)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) dst[(t * 4 + r) * 64 + lane] = acc[t][r];
         }
         __syncthreads();
-        if (wave < s) {
-            const float *src = s_red + (size_t)wave * ACC_FLOATS;
+        if (rw < s2) {
+            const float *src = s_red + (size_t)(sub * 2 + rw) * ACC_FLOATS;
 #pragma unroll
-            for (int t = 0; t < DN_COLS / 16; ++t)
+            for (int t = 0; t < DN_SUB / 16; ++t)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[t][r] += src[(t * 4 + r) * 64 + lane];
         }
         __syncthreads();
     }
-    if (wave == 0) {
+    if (rw == 0) {
 #pragma unroll
-        for (int t = 0; t < DN_COLS / 16; ++t)
+        for (int t = 0; t < DN_SUB / 16; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int m = 4 * q + r, col = col0 + t * 16 + n;
+                const int m = 4 * q + r, col = col0 + sub * DN_SUB + t * 16 + n;
                 if (m < B && col < d) p.partial[((size_t)rg * B + m) * d + col] = acc[t][r];
             }
     }
@@ -362,8 +415,8 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     if (layer->dtype != CLADA_BF16 || B < 2 || B > 16) return CLADA_OK;
     if (d % 256 != 0 || (d != 4096 && d != 5120 && d != 1024 && d != 2048)) return CLADA_OK;
     const int P = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
-    const int nt = (F + 15) / 16;
-    if ((nt + P - 1) / P > MAX_TILES) return CLADA_OK;
+    const int no = (F + 7) / 8;
+    if ((no + P - 1) / P > 2 * MAX_TILES) return CLADA_OK;      // at most 64 neurons per workgroup
     const int CG = (d + DN_COLS - 1) / DN_COLS;
     int RG = P / CG;
     if (RG < 1) RG = 1;
