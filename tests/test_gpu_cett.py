@@ -162,3 +162,28 @@ def test_cett_search_full_size_7b_layer(clada):
     assert m_at <= 0.2 * (1 + TOL_CETT["bf16"]) and m_above > 0.2 * (1 - TOL_CETT["bf16"])
     assert mean == pytest.approx(m_at, rel=TOL_CETT["bf16"])
     assert 0.19 < m_at <= 0.2002
+
+
+def test_cett_search_graph_replay_matches_eager(clada):
+    """The bracket lives on the device and every probe reads it there: the whole search can be
+    captured once and replayed; each replay must give the eager bits."""
+    cfg, w, X, ctx, layer, Xd = _setup(clada, "c2", 512, 640, 200)
+    tau_e, mean_e = clada.threshold_search_cett(ctx, layer, Xd, 0.2)
+    torch.cuda.synchronize()
+    tau_e, mean_e = tau_e.clone(), mean_e.clone()
+    out = torch.zeros(1, dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        clada.threshold_search_cett(ctx, layer, Xd, 0.2, out=out)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        clada.threshold_search_cett(ctx, layer, Xd, 0.2, out=out)
+    for _ in range(3):
+        out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, tau_e)
+        again = clada.threshold_search_cett(ctx, layer, Xd, 0.2)[0]      # eager call between replays
+        torch.cuda.synchronize()
+        assert torch.equal(again, tau_e)

@@ -191,3 +191,49 @@ def test_static_argument_errors(clada):
         clada.static_mask_topk(ctx, s, 97)
     with pytest.raises(CladaError):
         clada.static_mask_topk(ctx, s, -1)
+
+
+def test_static_chain_graph_replay_matches_eager(clada):
+    """Mask builder + list decode captured together; the list and its count stay on the device."""
+    cfg = synth.CONFIGS["c2"]
+    d, F = 4096, 2048
+    w = synth.layer_weights(cfg, 8, 0, d=d, d_ff=F)
+    x = synth.decode_hidden(cfg, 8, 0, 0, B=1, d=d)
+    ctx = _ctx(clada, d, F, 1)
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd = to_dev(x, cfg.dtype)
+    score = torch.rand(F, device=DEV)
+    tau = torch.tensor([0.4], dtype=torch.float32, device=DEV)
+    idx, n = clada.static_mask_threshold(ctx, score, tau)
+    y_e = clada.static_ffn_decode(ctx, layer, xd, idx, n).clone()
+    torch.cuda.synchronize()
+    lib, h = ctx._lib, ctx._h
+    import ctypes as C
+    cl = layer.c_struct()
+    idx_g = torch.zeros(F, dtype=torch.int32, device=DEV)
+    n_g = torch.zeros(1, dtype=torch.int32, device=DEV)
+    y_g = torch.empty_like(y_e)
+    side = torch.cuda.Stream()
+
+    def body():
+        sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        ctx.check(lib.clada_static_mask_threshold(h, score.data_ptr(), F, tau.data_ptr(), idx_g.data_ptr(),
+                                                  n_g.data_ptr(), sp))
+        ctx.check(lib.clada_static_ffn_decode(h, C.byref(cl), xd.data_ptr(), 1, idx_g.data_ptr(), n_g.data_ptr(),
+                                              y_g.data_ptr(), sp))
+
+    with torch.cuda.stream(side):
+        body()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        body()
+    for _ in range(3):
+        y_g.zero_()
+        n_g.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert int(n_g.item()) == int(n.item()) and torch.equal(y_g, y_e)
+        y2 = clada.static_ffn_decode(ctx, layer, xd, idx, n)
+        torch.cuda.synchronize()
+        assert torch.equal(y2, y_e)
