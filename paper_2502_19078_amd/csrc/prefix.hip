@@ -223,7 +223,8 @@ k_prefix_gateup(const GateUpParams p)
 // bf16 gate/up GEMM with direct-to-LDS loads and a three-stage pipeline: global_load_lds_dwordx4
 // writes a wave's 64 x 16 bytes straight into LDS (no staging registers), two k-tiles are in
 // flight while the third is multiplied, one raw barrier per k-tile.  A tile row is 128 bytes (64
-// bf16), so rows are stored XOR-swizzled (16-byte chunk c of row r sits at position c ^ (r & 7)),
+// bf16), so rows are stored XOR-swizzled (16-byte chunk c of row r sits at position
+// c ^ ((r >> 1) & 7): 16 consecutive rows read the same chunk from 16 different bank groups),
 // done on the global-address side because the LDS side of the transfer is fixed to base + lane*16.
 // Each stage is its own __shared__ array so the compiler can tell the stages apart and does not
 // wait for in-flight transfers into the other stages before reading this one.  Needs d % 64 == 0.
@@ -243,10 +244,24 @@ k_prefix_gateup_bf16(const GateUpParams p)
     __shared__ __align__(16) char s_st2[3 * GU_TILE];
     __shared__ float s_stat[2][4][BN];
 
-    const int total = p.n_tm * p.n_tn;
-    const int tile = remap_block(blockIdx.x, total);
-    if (tile >= total) return;
-    const int tm = tile % p.n_tm, tn = tile / p.n_tm;
+    // Tile order inside an XCD's run: with at least 8 token tiles, blocks of 8 token tiles x 4
+    // neuron tiles, so the 32 workgroups that share an L2 at any time re-use each X slice four
+    // times and each weight slice eight times (token tile fastest would re-use only the weights).
+    int tm, tn;
+    if (p.n_tm % 8 == 0) {
+        const int tn_pad = (p.n_tn + 3) / 4 * 4;
+        const int o = remap_block(blockIdx.x, p.n_tm * tn_pad);
+        const int sb = o >> 5, w = o & 31, tmb = p.n_tm >> 3;
+        tm = (sb % tmb) * 8 + (w & 7);
+        tn = (sb / tmb) * 4 + (w >> 3);
+        if (tn >= p.n_tn) return;
+    } else {
+        const int total = p.n_tm * p.n_tn;
+        const int tile = remap_block(blockIdx.x, total);
+        if (tile >= total) return;
+        tm = tile % p.n_tm;
+        tn = tile / p.n_tm;
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
@@ -270,11 +285,15 @@ k_prefix_gateup_bf16(const GateUpParams p)
         const int row = 8 * (wave + 4 * c4) + lr;           // rows past T / F repeat the last valid row;
         const int t = min(tm * BM + row, p.T - 1);          // their products land in discarded outputs
         const int j = min(tn * BN + row, p.F - 1);
-        const int koff = (lp ^ lr) * 16;
+        const int koff = (lp ^ (4 * (wave & 1) + (lr >> 1))) * 16;      // position lp holds chunk lp ^ ((row >> 1) & 7)
         gx[c4] = p.x + (size_t)t * rowbytes + koff;
         gg[c4] = p.wg + (size_t)j * rowbytes + koff;
         gu[c4] = p.wu + (size_t)j * rowbytes + koff;
     }
+    // (Every tile walks k in the same order on purpose: workgroups in step share their X and weight
+    // slices in L2.  Starting each tile at its own k, to spread the memory channels that rows a
+    // power of two apart map to, was measured 12 % slower.)
+    const int nk = p.d / 64;
     auto issue = [&](char *st, int kt) {
 #pragma unroll
         for (int c4 = 0; c4 < 4; ++c4) {
@@ -287,38 +306,58 @@ k_prefix_gateup_bf16(const GateUpParams p)
     // Fragment reads are issued as inline assembly: for an LDS read the compiler cannot prove
     // distinct from an in-flight direct-to-LDS transfer it inserts vmcnt(0), which would serialise
     // the pipeline; the hand-placed vmcnt above already orders the transfers of the stage read here.
-    const int r32 = lane & 31, q = lane >> 5, sw = r32 & 7;
+    const int r32 = lane & 31, q = lane >> 5, sw = (r32 >> 1) & 7;
     const unsigned int a_off = (unsigned int)((wm * 64 + r32) * 128);
     const unsigned int b_off = (unsigned int)(GU_TILE + (wn * 64 + r32) * 128);
+    // The reads of k-step ks+1 are in flight while the MFMAs of k-step ks run: LDS returns data in
+    // order, so waiting for lgkmcnt <= 6 means the older set of six has landed.
     auto compute = [&](const char *st) {
         const unsigned int base = (unsigned int)(size_t)(const __attribute__((address_space(3))) char *)st;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const unsigned int pos = (unsigned int)(((2 * ks + q) ^ sw) * 16);
-            const unsigned int pa = base + a_off + pos, pb = base + b_off + pos;
-            u32x4 a0, a1, g0, g1, u0, u1;
-            asm volatile("ds_read_b128 %0, %6\n\t"
-                         "ds_read_b128 %1, %6 offset:4096\n\t"
-                         "ds_read_b128 %2, %7\n\t"
-                         "ds_read_b128 %3, %7 offset:4096\n\t"
-                         "ds_read_b128 %4, %7 offset:16384\n\t"
-                         "ds_read_b128 %5, %7 offset:20480\n\t"
-                         "s_waitcnt lgkmcnt(0)"
-                         : "=&v"(a0), "=&v"(a1), "=&v"(g0), "=&v"(g1), "=&v"(u0), "=&v"(u1)
-                         : "v"(pa), "v"(pb));
-            const bf16x8 fa[2] = {__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, a1)};
-            const bf16x8 fb[2][2] = {{__builtin_bit_cast(bf16x8, g0), __builtin_bit_cast(bf16x8, g1)},
-                                     {__builtin_bit_cast(bf16x8, u0), __builtin_bit_cast(bf16x8, u1)}};
-#pragma unroll
-            for (int w = 0; w < 2; ++w)
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
-                        acc[w][mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mb], fb[w][nb], acc[w][mb][nb], 0, 0, 0);
+        u32x4 fr[2][6];
+#define GU_READ6(S, KS)                                                                                   \
+        {                                                                                                 \
+            const unsigned int pos = (unsigned int)(((2 * (KS) + q) ^ sw) * 16);                          \
+            const unsigned int pa = base + a_off + pos, pb = base + b_off + pos;                          \
+            asm volatile("ds_read_b128 %0, %6\n\t"                                                        \
+                         "ds_read_b128 %1, %6 offset:4096\n\t"                                            \
+                         "ds_read_b128 %2, %7\n\t"                                                        \
+                         "ds_read_b128 %3, %7 offset:4096\n\t"                                            \
+                         "ds_read_b128 %4, %7 offset:16384\n\t"                                           \
+                         "ds_read_b128 %5, %7 offset:20480"                                                \
+                         : "=&v"(fr[S][0]), "=&v"(fr[S][1]), "=&v"(fr[S][2]), "=&v"(fr[S][3]),            \
+                           "=&v"(fr[S][4]), "=&v"(fr[S][5])                                               \
+                         : "v"(pa), "v"(pb));                                                             \
         }
+#define GU_WAIT(S, CNT)                                                                                   \
+        asm volatile("s_waitcnt lgkmcnt(" #CNT ")"                                                        \
+                     : "+v"(fr[S][0]), "+v"(fr[S][1]), "+v"(fr[S][2]), "+v"(fr[S][3]), "+v"(fr[S][4]),    \
+                       "+v"(fr[S][5]));
+#define GU_MMA(S)                                                                                         \
+        {                                                                                                 \
+            const bf16x8 fa[2] = {__builtin_bit_cast(bf16x8, fr[S][0]), __builtin_bit_cast(bf16x8, fr[S][1])}; \
+            const bf16x8 fb[2][2] = {{__builtin_bit_cast(bf16x8, fr[S][2]), __builtin_bit_cast(bf16x8, fr[S][3])}, \
+                                     {__builtin_bit_cast(bf16x8, fr[S][4]), __builtin_bit_cast(bf16x8, fr[S][5])}}; \
+            _Pragma("unroll") for (int w = 0; w < 2; ++w)                                                 \
+            _Pragma("unroll") for (int nb = 0; nb < 2; ++nb)                                              \
+            _Pragma("unroll") for (int mb = 0; mb < 2; ++mb)                                              \
+                acc[w][mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mb], fb[w][nb], acc[w][mb][nb], 0, 0, 0); \
+        }
+        GU_READ6(0, 0)
+        GU_READ6(1, 1)
+        GU_WAIT(0, 6)
+        GU_MMA(0)
+        GU_READ6(0, 2)
+        GU_WAIT(1, 6)
+        GU_MMA(1)
+        GU_READ6(1, 3)
+        GU_WAIT(0, 6)
+        GU_MMA(0)
+        GU_WAIT(1, 0)
+        GU_MMA(1)
+#undef GU_READ6
+#undef GU_WAIT
+#undef GU_MMA
     };
-    const int nk = p.d / 64;
     // wait until this wave's transfers of tile k have landed (the 12 of tile k+1 may stay in
     // flight), meet the other waves, refill the stage consumed one step ago, multiply
     auto step = [&](int k, const char *cur, char *nxt) {
@@ -638,8 +677,9 @@ hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, f
     g.Fp = (int)align_up((size_t)F, 64);
     const int total = g.n_tm * g.n_tn;
     const int grid = (total + 7) / 8 * 8;
+    const int total_blk = g.n_tm % 8 == 0 ? g.n_tm * ((g.n_tn + 3) / 4 * 4) : total;   // the bf16 kernel's padded tile order
     if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
-    else if (d % 64 == 0) hipLaunchKernelGGL(k_prefix_gateup_bf16, dim3(grid), dim3(256), 0, stream, g);
+    else if (d % 64 == 0) hipLaunchKernelGGL(k_prefix_gateup_bf16, dim3((total_blk + 7) / 8 * 8), dim3(256), 0, stream, g);
     else         hipLaunchKernelGGL(k_prefix_gateup<2>, dim3(grid), dim3(256), 0, stream, g);
     return hipGetLastError();
 }

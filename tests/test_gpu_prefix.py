@@ -28,6 +28,8 @@ def _rel(a, b):
     ("c2", 1024, 1000, 300),     # bf16 MFMA, ragged tiles
     ("c2", 4096, 384, 512),      # bf16, real K and prefix length of config 2, three neuron tiles
     ("c2", 72, 129, 257),
+    ("c2", 512, 700, 1024),      # 8 token tiles: the blocked tile order, 6 neuron tiles padded to 8
+    ("c2", 256, 384, 2000),      # 16 token tiles (last one ragged), 3 neuron tiles
 ])
 def test_prefix_stats_parity(clada, cfg_name, d, F, T):
     cfg = synth.CONFIGS[cfg_name]
