@@ -234,3 +234,38 @@ def static_mask_topk(score, k):
     rc = _load().clada_oracle_static_mask_topk(pa, F, int(k), pm, pi, C.byref(n))
     assert rc == 0, rc
     return mask.astype(bool), idx[: n.value].copy()
+
+
+def relu_decode(w_in, b_in, w_out, b_out, x, tau=None, mask=None):
+    """Non-gated ReLU FFN (OPT family): a = relu(W_in x + b_in), y = sum_kept a W_out[j,:] + b_out.
+    tau [B] -> keep iff a >= tau; mask [B][F] -> as given; neither -> dense.  Returns a dict like
+    sparse_decode."""
+    wi, pi = _f32(w_in)
+    wo, po = _f32(w_out)
+    F, d = wi.shape
+    assert wo.shape == (F, d)
+    xx, px = _f32(np.atleast_2d(x))
+    B = xx.shape[0]
+    bi = bo = None
+    pbi = pbo = None
+    if b_in is not None:
+        bi, pbi = _f32(b_in)
+        assert bi.shape == (F,)
+    if b_out is not None:
+        bo, pbo = _f32(b_out)
+        assert bo.shape == (d,)
+    pt = pm = None
+    if tau is not None:
+        t, pt = _f64(np.broadcast_to(np.asarray(tau, np.float64), (B,)))
+    elif mask is not None:
+        mm = np.ascontiguousarray(np.atleast_2d(mask), dtype=np.uint8)
+        assert mm.shape == (B, F)
+        pm = mm.ctypes.data_as(C.POINTER(C.c_uint8))
+    y, py = _out((B, d))
+    act, pa = _out((B, F))
+    mo, pmo = _out((B, F), np.uint8)
+    idx, pidx = _out((F,), np.int32)
+    na, pna = _out((1 + B,), np.int32)
+    rc = _load().clada_oracle_relu_decode(pi, pbi, po, pbo, d, F, px, B, pt, pm, py, pa, pmo, pidx, pna)
+    assert rc == 0, rc
+    return {"y": y, "act": act, "mask": mo.astype(bool), "active_idx": idx[: na[0]].copy(), "n_active": na}

@@ -24,7 +24,10 @@
  * numpy.partition order statistics; for the CETT evaluation and search a
  * hand-worked three-neuron example, brute force over every candidate threshold,
  * dense-minus-sparse decode outputs, the closed form for orthogonal output rows
- * and a constructed non-monotone case.  No function here is "parity unpinned".
+ * and a constructed non-monotone case; for the static masks hand cases with
+ * ties / NaN / signed zeros and numpy's lexsort / partition; for the non-gated
+ * ReLU FFN a hand case and numpy fp64 matmul.  No function here is "parity
+ * unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -568,6 +571,70 @@ int clada_oracle_static_mask_topk(const double *score, int d_ff, int k,
     if (mask) memcpy(mask, m, (size_t)d_ff);
     *n = c;
     free(it);
+    free(m);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Non-gated ReLU FFN (the OPT models of the experimental set-up): the
+ * neuron-activation equation of section 3.2.1 without the V_in factor and with
+ * sigma = ReLU, biases as in those models:
+ *   a_bj = max(0, W_in[j,:] . x_b + b_in[j])
+ *   keep_bj = a_bj >= tau_b            (the decode step's cut rule; a >= 0)
+ *   y_b = sum_{j kept} a_bj W_out[j,:] + b_out
+ * W_in, W_out neuron-major [d_ff][d]; b_in [d_ff], b_out [d] may be NULL (zero).
+ * Kept set: tau != NULL -> by threshold; else mask_in != NULL -> as given;
+ * else every neuron (dense twin).  Optional outputs as in the gated decode.
+ * ---------------------------------------------------------------------- */
+int clada_oracle_relu_decode(const float *w_in, const float *b_in, const float *w_out,
+                             const float *b_out, int d, int d_ff, const float *x, int B,
+                             const double *tau, const uint8_t *mask_in, double *y,
+                             double *act, uint8_t *mask, int32_t *active_idx,
+                             int32_t *n_active)
+{
+    if (!w_in || !w_out || !x || !y || d <= 0 || d_ff <= 0 || B < 0) return 1;
+    size_t n = (size_t)(B > 0 ? B : 1) * (size_t)d_ff;
+    double *a = (double *)malloc(sizeof(double) * n);
+    uint8_t *m = (uint8_t *)malloc(n);
+    if (!a || !m) { free(a); free(m); return 2; }
+    for (int b = 0; b < B; ++b) {
+        const float *xb = x + (size_t)b * d;
+#pragma omp parallel for schedule(static)
+        for (int j = 0; j < d_ff; ++j) {
+            double g = dot_fd(w_in + (size_t)j * d, xb, d) + (b_in ? (double)b_in[j] : 0.0);
+            double v = g > 0.0 ? g : (g != g ? g : 0.0);          /* NaN stays NaN */
+            a[(size_t)b * d_ff + j] = v;
+            int keep = tau ? (v >= tau[b]) : (mask_in ? mask_in[(size_t)b * d_ff + j] != 0 : 1);
+            m[(size_t)b * d_ff + j] = (uint8_t)keep;
+        }
+        double *yb = y + (size_t)b * d;
+#pragma omp parallel for schedule(static)
+        for (int i = 0; i < d; ++i) {
+            double s = 0.0;
+            for (int j = 0; j < d_ff; ++j)
+                if (m[(size_t)b * d_ff + j]) s += a[(size_t)b * d_ff + j] * (double)w_out[(size_t)j * d + i];
+            yb[i] = s + (b_out ? (double)b_out[i] : 0.0);
+        }
+    }
+    if (n_active || active_idx) {
+        int32_t nu = 0;
+        for (int j = 0; j < d_ff; ++j) {
+            int any = 0;
+            for (int b = 0; b < B; ++b) any |= m[(size_t)b * d_ff + j];
+            if (any) { if (active_idx) active_idx[nu] = j; ++nu; }
+        }
+        if (n_active) {
+            n_active[0] = nu;
+            for (int b = 0; b < B; ++b) {
+                int32_t c = 0;
+                for (int j = 0; j < d_ff; ++j) c += m[(size_t)b * d_ff + j];
+                n_active[1 + b] = c;
+            }
+        }
+    }
+    if (act) memcpy(act, a, sizeof(double) * (size_t)B * d_ff);
+    if (mask) memcpy(mask, m, (size_t)B * d_ff);
+    free(a);
     free(m);
     return 0;
 }

@@ -1,0 +1,65 @@
+"""Pins of the oracle's non-gated ReLU FFN (OPT family) -- CPU only."""
+import numpy as np
+import pytest
+
+import oracle
+
+
+def _toy(seed, d, F, B):
+    rng = np.random.default_rng(seed)
+    wi = (rng.standard_normal((F, d)) * 0.3).astype(np.float32)
+    wo = (rng.standard_normal((F, d)) * 0.3).astype(np.float32)
+    bi = (rng.standard_normal(F) * 0.2).astype(np.float32)
+    bo = (rng.standard_normal(d) * 0.2).astype(np.float32)
+    x = rng.standard_normal((B, d)).astype(np.float32)
+    return wi, bi, wo, bo, x
+
+
+def test_hand_case():
+    # x = (1, 2); neuron 0: 1*1 + 0*2 + 0.5 = 1.5 -> 1.5; neuron 1: -1 - 2 + 1 = -2 -> 0; neuron 2: 0.5*2 - 0.25 = 0.75
+    wi = np.array([[1, 0], [-1, -1], [0, 0.5]], np.float32)
+    bi = np.array([0.5, 1.0, -0.25], np.float32)
+    wo = np.array([[1, 1], [5, 5], [2, -2]], np.float32)
+    bo = np.array([0.125, -0.125], np.float32)
+    x = np.array([[1, 2]], np.float32)
+    r = oracle.relu_decode(wi, bi, wo, bo, x)
+    assert r["act"][0].tolist() == [1.5, 0.0, 0.75]
+    assert r["y"][0].tolist() == [1.5 + 1.5 + 0.125, 1.5 - 1.5 - 0.125]
+    r = oracle.relu_decode(wi, bi, wo, bo, x, tau=[0.75])          # tie kept
+    assert r["active_idx"].tolist() == [0, 2]
+    r = oracle.relu_decode(wi, bi, wo, bo, x, tau=[0.7500001])
+    assert r["active_idx"].tolist() == [0] and r["y"][0].tolist() == [1.5 + 0.125, 1.5 - 0.125]
+    r = oracle.relu_decode(wi, bi, wo, bo, x, tau=[0.0])           # zero activations are kept at tau = 0
+    assert r["active_idx"].tolist() == [0, 1, 2] and r["n_active"].tolist() == [3, 3]
+    r = oracle.relu_decode(wi, bi, wo, bo, x, tau=[np.inf])
+    assert r["active_idx"].tolist() == [] and r["y"][0].tolist() == [0.125, -0.125]
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_matches_numpy(seed):
+    wi, bi, wo, bo, x = _toy(seed, 40, 96, 3)
+    a = np.maximum(x.astype(np.float64) @ wi.astype(np.float64).T + bi, 0.0)
+    r = oracle.relu_decode(wi, bi, wo, bo, x)
+    np.testing.assert_allclose(r["act"], a, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(r["y"], a @ wo.astype(np.float64) + bo, rtol=1e-12, atol=1e-13)
+    tau = np.array([0.1, 0.3, 0.0])
+    keep = a >= tau[:, None]
+    r = oracle.relu_decode(wi, bi, wo, bo, x, tau=tau)
+    assert np.array_equal(r["mask"], keep)
+    np.testing.assert_allclose(r["y"], (a * keep) @ wo.astype(np.float64) + bo, rtol=1e-12, atol=1e-13)
+    assert r["n_active"].tolist() == [int(keep.any(0).sum())] + keep.sum(1).tolist()
+    assert r["active_idx"].tolist() == np.flatnonzero(keep.any(0)).tolist()
+    # a given mask reproduces the thresholded result; no biases = zero biases
+    r2 = oracle.relu_decode(wi, bi, wo, bo, x, mask=keep)
+    assert np.array_equal(r2["y"], r["y"])
+    r3 = oracle.relu_decode(wi, None, wo, None, x)
+    a0 = np.maximum(x.astype(np.float64) @ wi.astype(np.float64).T, 0.0)
+    np.testing.assert_allclose(r3["y"], a0 @ wo.astype(np.float64), rtol=1e-12, atol=1e-13)
+
+
+def test_tau_zero_is_dense_and_rows_are_independent():
+    wi, bi, wo, bo, x = _toy(5, 24, 50, 4)
+    dense = oracle.relu_decode(wi, bi, wo, bo, x)["y"]
+    assert np.array_equal(oracle.relu_decode(wi, bi, wo, bo, x, tau=np.zeros(4))["y"], dense)
+    for b in range(4):
+        assert np.array_equal(oracle.relu_decode(wi, bi, wo, bo, x[b:b + 1])["y"][0], dense[b])
