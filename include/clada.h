@@ -82,10 +82,25 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);
  * cognitive_signals, B for the decode calls). */
 size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int32_t V);
 
+/* FFN family.  CLADA_FFN_SWIGLU (0, the default of a zeroed struct): the gated
+ * SiLU FFN of the LLaMA / Mistral models, sigma = SiLU in the neuron-activation
+ * equation of section 3.2.1.  CLADA_FFN_RELU: the non-gated FFN of the OPT models
+ * the paper also evaluates -- no V_in factor, sigma = ReLU, biases:
+ *   a_bj = max(0, W_in[j,:] . x_b + b_in[j]),  keep_bj = a_bj >= tau_final[b],
+ *   y_b = sum_{j kept} a_bj W_out[j,:] + b_out.
+ * For it w_gate holds W_in [d_ff][d], w_down holds W_out neuron-major [d_ff][d]
+ * (HF fc2.weight transposed), w_up is ignored; b_in [d_ff] and b_out [d] are fp32
+ * device arrays or NULL (zero).  Supported by clada_sparse_ffn_decode,
+ * clada_dense_ffn_decode and clada_static_ffn_decode; the prefill and CETT calls
+ * return CLADA_ERR_VALUE for it. */
+typedef enum { CLADA_FFN_SWIGLU = 0, CLADA_FFN_RELU = 1 } clada_ffn_kind;
+
 typedef struct {
     const void *w_gate, *w_up, *w_down; /* device, each [d_ff][d] neuron-major */
     int32_t d, d_ff;
     clada_dtype dtype;
+    clada_ffn_kind kind;
+    const float *b_in, *b_out;          /* CLADA_FFN_RELU only */
 } clada_layer;
 
 typedef struct {            /* device outputs, caller-allocated; any may be NULL to skip */

@@ -269,3 +269,27 @@ def relu_decode(w_in, b_in, w_out, b_out, x, tau=None, mask=None):
     rc = _load().clada_oracle_relu_decode(pi, pbi, po, pbo, d, F, px, B, pt, pm, py, pa, pmo, pidx, pna)
     assert rc == 0, rc
     return {"y": y, "act": act, "mask": mo.astype(bool), "active_idx": idx[: na[0]].copy(), "n_active": na}
+
+
+def relu_prefix_stats(w_in, b_in, w_out, b_out, x, want_y=True, want_pool=True):
+    """Prefill aggregates of the non-gated ReLU FFN over the prefix x [T][d] (dict like prefix_stats)."""
+    wi, pi = _f32(w_in)
+    wo, po = _f32(w_out)
+    F, d = wi.shape
+    xx, px = _f32(x)
+    T = xx.shape[0]
+    pbi = pbo = None
+    if b_in is not None:
+        bi, pbi = _f32(b_in)
+    if b_out is not None:
+        bo, pbo = _f32(b_out)
+    y, py = _out((T, d)) if want_y else (None, None)
+    pool, pp = _out((T, F)) if want_pool else (None, None)
+    names = ("sum_abs_act", "sum_sq_act", "max_abs_act", "sum_sq_h", "A")
+    outs = [_out((F,)) for _ in names]
+    rc = _load().clada_oracle_relu_prefix_stats(pi, pbi, po, pbo, d, F, px, T, py, *[o[1] for o in outs], pp)
+    assert rc == 0, rc
+    res = {n: o[0] for n, o in zip(names, outs)}
+    res["y"] = y
+    res["abs_act_pool"] = pool
+    return res

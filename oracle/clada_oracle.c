@@ -638,3 +638,54 @@ int clada_oracle_relu_decode(const float *w_in, const float *b_in, const float *
     free(m);
     return 0;
 }
+
+/* Prefill statistics of the non-gated ReLU FFN: the aggregates of
+ * clada_oracle_prefix_stats with a_tj = max(0, W_in[j,:].x_t + b_in[j]), h_tj = a_tj,
+ * Y[t,:] = sum_j h_tj W_out[j,:] + b_out. */
+int clada_oracle_relu_prefix_stats(const float *w_in, const float *b_in, const float *w_out,
+                                   const float *b_out, int d, int d_ff, const float *x, int T,
+                                   double *y, double *sum_abs_act, double *sum_sq_act,
+                                   double *max_abs_act, double *sum_sq_h, double *A, double *pool)
+{
+    if (!w_in || !w_out || !x || d <= 0 || d_ff <= 0 || T < 0) return 1;
+    double *h = NULL;
+    if (y) {
+        h = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * (size_t)d_ff);
+        if (!h) return 2;
+    }
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < d_ff; ++j) {
+        double s_abs = 0.0, s_sq = 0.0, mx = 0.0, wn2 = 0.0;
+        for (int t = 0; t < T; ++t) {
+            double g = dot_fd(w_in + (size_t)j * d, x + (size_t)t * d, d) + (b_in ? (double)b_in[j] : 0.0);
+            double a = g > 0.0 ? g : (g != g ? g : 0.0);
+            s_abs += a;
+            s_sq += a * a;
+            if (a != a) mx = a;
+            else if (mx == mx && a > mx) mx = a;
+            if (pool) pool[(size_t)t * d_ff + j] = a;
+            if (h) h[(size_t)t * d_ff + j] = a;
+        }
+        for (int i = 0; i < d; ++i) wn2 += (double)w_out[(size_t)j * d + i] * (double)w_out[(size_t)j * d + i];
+        if (sum_abs_act) sum_abs_act[j] = s_abs;
+        if (sum_sq_act) sum_sq_act[j] = s_sq;
+        if (max_abs_act) max_abs_act[j] = mx;
+        if (sum_sq_h) sum_sq_h[j] = s_sq;
+        if (A) A[j] = sqrt(s_sq) * sqrt(wn2);
+    }
+    if (y) {
+#pragma omp parallel for schedule(static)
+        for (int t = 0; t < T; ++t) {
+            double *yt = y + (size_t)t * d;
+            for (int i = 0; i < d; ++i) yt[i] = 0.0;
+            for (int j = 0; j < d_ff; ++j) {
+                double hv = h[(size_t)t * d_ff + j];
+                for (int i = 0; i < d; ++i) yt[i] += hv * (double)w_out[(size_t)j * d + i];
+            }
+            if (b_out)
+                for (int i = 0; i < d; ++i) yt[i] += (double)b_out[i];
+        }
+        free(h);
+    }
+    return 0;
+}

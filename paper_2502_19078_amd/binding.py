@@ -27,9 +27,13 @@ class CladaError(RuntimeError):
         super().__init__(f"{name}: {text}")
 
 
+SWIGLU, RELU = 0, 1      # clada_ffn_kind
+
+
 class _CLayer(C.Structure):
     _fields_ = [("w_gate", C.c_void_p), ("w_up", C.c_void_p), ("w_down", C.c_void_p),
-                ("d", C.c_int32), ("d_ff", C.c_int32), ("dtype", C.c_int)]
+                ("d", C.c_int32), ("d_ff", C.c_int32), ("dtype", C.c_int), ("kind", C.c_int),
+                ("b_in", C.c_void_p), ("b_out", C.c_void_p)]
 
 
 class _CPrefixOut(C.Structure):
@@ -134,17 +138,27 @@ class Context:
 
 @dataclass
 class Layer:
-    """Neuron-major weights of one FFN layer, each [d_ff][d] on the GPU."""
+    """Neuron-major weights of one FFN layer, each [d_ff][d] on the GPU.  kind = SWIGLU (gated SiLU:
+    w_gate, w_up, w_down) or RELU (non-gated, OPT family: w_gate = W_in, w_up = None, w_down = W_out
+    neuron-major, optional fp32 biases b_in [d_ff], b_out [d])."""
     w_gate: torch.Tensor
-    w_up: torch.Tensor
+    w_up: torch.Tensor | None
     w_down: torch.Tensor
+    kind: int = 0
+    b_in: torch.Tensor | None = None
+    b_out: torch.Tensor | None = None
 
     def c_struct(self) -> _CLayer:
         F, d = self.w_gate.shape
-        for w in (self.w_gate, self.w_up, self.w_down):
+        ws = (self.w_gate, self.w_down) if self.kind == RELU else (self.w_gate, self.w_up, self.w_down)
+        for w in ws:
             assert w.is_cuda and w.is_contiguous() and tuple(w.shape) == (F, d) and w.dtype == self.w_gate.dtype
-        return _CLayer(self.w_gate.data_ptr(), self.w_up.data_ptr(), self.w_down.data_ptr(), d, F,
-                       _dtype_code(self.w_gate))
+        for b, n in ((self.b_in, F), (self.b_out, d)):
+            assert b is None or (b.is_cuda and b.is_contiguous() and b.dtype == torch.float32 and b.numel() == n)
+        return _CLayer(self.w_gate.data_ptr(), None if self.w_up is None else self.w_up.data_ptr(),
+                       self.w_down.data_ptr(), d, F, _dtype_code(self.w_gate), self.kind,
+                       None if self.b_in is None else self.b_in.data_ptr(),
+                       None if self.b_out is None else self.b_out.data_ptr())
 
 
 @dataclass

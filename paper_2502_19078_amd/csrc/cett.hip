@@ -157,6 +157,7 @@ clada_status check_common(clada_ctx *ctx, const clada_layer *layer, const void *
 {
     if (!ctx) return CLADA_ERR_NULL;
     clada_status st = clada_check_layer(ctx, layer);
+    if (st == CLADA_OK) st = clada_require_swiglu(ctx, layer, "the CETT calls");
     if (st != CLADA_OK) return st;
     if (!x) return clada_fail(ctx, CLADA_ERR_NULL, "x_val is NULL");
     if (T < 1 || T > (1 << 20)) return clada_fail(ctx, CLADA_ERR_SHAPE, "T=%d outside [1,2^20]", T);

@@ -22,7 +22,9 @@ clada_status clada_fail(clada_ctx *ctx, clada_status s, const char *fmt, ...)
 clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer)
 {
     if (!layer) return clada_fail(ctx, CLADA_ERR_NULL, "layer is NULL");
-    if (!layer->w_gate || !layer->w_up || !layer->w_down)
+    if (layer->kind != CLADA_FFN_SWIGLU && layer->kind != CLADA_FFN_RELU)
+        return clada_fail(ctx, CLADA_ERR_VALUE, "unknown FFN kind %d", (int)layer->kind);
+    if (!layer->w_gate || !layer->w_down || (layer->kind == CLADA_FFN_SWIGLU && !layer->w_up))
         return clada_fail(ctx, CLADA_ERR_NULL, "a weight pointer is NULL");
     if (layer->dtype != CLADA_F32 && layer->dtype != CLADA_BF16)
         return clada_fail(ctx, CLADA_ERR_DTYPE, "unknown dtype %d", (int)layer->dtype);
@@ -35,8 +37,18 @@ clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer)
         return clada_fail(ctx, CLADA_ERR_SHAPE, "row of %zu bytes is not a multiple of 16", rowbytes);
     if (rowbytes > 16384)
         return clada_fail(ctx, CLADA_ERR_SHAPE, "row of %zu bytes exceeds 16384", rowbytes);
-    if (!aligned16(layer->w_gate) || !aligned16(layer->w_up) || !aligned16(layer->w_down))
+    if (!aligned16(layer->w_gate) || !aligned16(layer->w_down) ||
+        (layer->kind == CLADA_FFN_SWIGLU && !aligned16(layer->w_up)))
         return clada_fail(ctx, CLADA_ERR_ALIGN, "weight pointers must be 16-byte aligned");
+    if (layer->kind == CLADA_FFN_RELU && ((((uintptr_t)layer->b_in) & 3u) || !aligned16(layer->b_out)))
+        return clada_fail(ctx, CLADA_ERR_ALIGN, "b_in must be 4-byte and b_out 16-byte aligned");
+    return CLADA_OK;
+}
+
+clada_status clada_require_swiglu(clada_ctx *ctx, const clada_layer *layer, const char *call)
+{
+    if (layer->kind != CLADA_FFN_SWIGLU)
+        return clada_fail(ctx, CLADA_ERR_VALUE, "%s supports the gated SiLU FFN only", call);
     return CLADA_OK;
 }
 

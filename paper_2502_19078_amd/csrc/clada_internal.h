@@ -50,6 +50,7 @@ static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; 
 
 // Validation shared by the FFN calls.
 clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer);
+clada_status clada_require_swiglu(clada_ctx *ctx, const clada_layer *layer, const char *call);
 
 // Batched (B >= 2, bf16) MFMA decode path; *ran tells whether the shape was eligible and it ran.
 clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, const void *x, int32_t B,
@@ -60,7 +61,8 @@ size_t clada_ws_decode_batched(int32_t d_ff);
 hipError_t clada_decode_list_b1(clada_ctx *ctx, const clada_layer *layer, const void *x, const int32_t *idx,
                                 const int32_t *n_active, float *partial, int *P_out, hipStream_t stream, bool *ran);
 // Fixed-order sum of P partial y's [P][B][d] (fp32) into y (element size es).
-void clada_launch_finalize(int es, const float *partial, int P, int B, int d, char *y, hipStream_t stream);
+void clada_launch_finalize(int es, const float *partial, int P, int B, int d, char *y, hipStream_t stream,
+                           const float *bias = nullptr);
 
 // Workspace needs of the individual calls (bytes beyond the header).
 size_t clada_ws_decode(int32_t d, int32_t d_ff, int32_t B);

@@ -33,15 +33,27 @@ struct DecodeParams {
     unsigned char *keep;        // [B][F] or nullptr
     const int *idx;             // LIST: neuron indices to run (ascending), device
     const int *n_list;          // LIST: their count, device
+    const float *b_in;          // RELU: input bias [F] or nullptr
     int d, F, ni_max;
 };
+
+// Activation of the two FFN families: SiLU(g) for the gated FFN; for the non-gated one
+// max(0, g + bias) (a NaN pre-activation stays NaN).
+template <bool RELU>
+__device__ __forceinline__ float ffn_act(float g, const float *b_in, size_t j)
+{
+    if (!RELU) return silu_f32(g);
+    if (b_in) g += b_in[j];
+    return g > 0.0f ? g : (g != g ? g : 0.0f);
+}
 
 
 // ES = element size (2: bf16, 4: fp32); NCH = 16-byte chunks per lane per row;
 // NW = waves per workgroup; GB / UB = rows in flight per wave in the gate /
 // up-down phase.  LIST (with DENSE): the neurons are entries blk, blk+P, ... of a caller-supplied
 // index list instead of rows blk, blk+P, ... of the matrices; every listed neuron is kept.
-template <int ES, int NCH, int NW, int GB, int UB, bool DENSE, bool LIST = false>
+// RELU: the non-gated family (no W_up pass, h = a).
+template <int ES, int NCH, int NW, int GB, int UB, bool DENSE, bool LIST = false, bool RELU = false>
 __global__ void __launch_bounds__(NW * 64)
 k_ffn_decode(const DecodeParams p)
 {
@@ -105,9 +117,9 @@ k_ffn_decode(const DecodeParams p)
                 for (int e = 0; e < VEC; ++e) s = fmaf(w[e], xr[c][e], s);
             }
             s = wave_sum(s);
-            const float a = silu_f32(s);
-            const bool keep = DENSE ? true : (fabsf(a) >= tau);
             const int i = i0 + r;
+            const float a = ffn_act<RELU>(s, p.b_in, neuron(i < ni ? i : i0));
+            const bool keep = DENSE ? true : (fabsf(a) >= tau);
             if (lane == 0 && i < ni) {
                 s_a[i] = a;
                 s_flag[i] = keep ? 1 : 0;
@@ -153,7 +165,7 @@ k_ffn_decode(const DecodeParams p)
             for (int c = 0; c < NCH; ++c) {
                 u32x4 u = {0u, 0u, 0u, 0u}, w = {0u, 0u, 0u, 0u};
                 if (rv && ok[c]) {
-                    u = ld_stream16(p.wu + off + coff[c]);
+                    if (!RELU) u = ld_stream16(p.wu + off + coff[c]);
                     w = ld_stream16(p.wd + off + coff[c]);
                 }
                 ub[r][c] = u;
@@ -170,7 +182,7 @@ k_ffn_decode(const DecodeParams p)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) s = fmaf(w[e], xr[c][e], s);
             }
-            const float h = av[r] * wave_sum(s);
+            const float h = RELU ? av[r] : av[r] * wave_sum(s);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 float w[VEC];
@@ -224,7 +236,8 @@ k_ffn_decode(const DecodeParams p)
 // folded by a fixed tree; one rounding to the output dtype.
 template <int ES>
 __global__ void __launch_bounds__(256)
-k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict__ y, unsigned int *epoch)
+k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict__ y, unsigned int *epoch,
+               const float *__restrict__ bias)
 {
     if (epoch && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *epoch += 1u;   // cooperative call counter
     __shared__ float4 s_sum[32][8];
@@ -260,6 +273,10 @@ k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict
         __syncthreads();
     }
     if (sl == 0 && col < d) {
+        if (bias) {                                     // output bias of the non-gated family
+            const float4 bv = *reinterpret_cast<const float4 *>(bias + col);
+            s.x += bv.x; s.y += bv.y; s.z += bv.z; s.w += bv.w;
+        }
         if (ES == 4) {
             *reinterpret_cast<float4 *>(y + ((size_t)b * d + col) * 4) = s;
         } else {
@@ -272,16 +289,16 @@ k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict
 }
 
 void launch_finalize(int es, const float *partial, int P, int B, int d, char *y, unsigned int *epoch, hipStream_t stream,
-                     hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr)
+                     hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, const float *bias = nullptr)
 {
     const dim3 grid((d + 31) / 32, B);
     if (ev_start) {
-        if (es == 4) hipExtLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch);
-        else         hipExtLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch);
+        if (es == 4) hipExtLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias);
+        else         hipExtLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias);
         return;
     }
-    if (es == 4) hipLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, partial, P, d, y, epoch);
-    else         hipLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, partial, P, d, y, epoch);
+    if (es == 4) hipLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, partial, P, d, y, epoch, bias);
+    else         hipLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, partial, P, d, y, epoch, bias);
 }
 
 // Ascending union index list, counts and per-token bit masks from the keep
@@ -381,6 +398,7 @@ struct B1Params {
     float *apub;                // [P][64] published activations
     const unsigned int *epoch;  // device-side counter of balanced calls, advanced by k_ffn_finalize
                                 // (read at kernel start, so graph replays stay correct)
+    const float *b_in;          // RELU: input bias [F] or nullptr
     int d, F, K0;
 };
 
@@ -409,7 +427,8 @@ __device__ __forceinline__ int wave_excl_scan(int v, int lane, int *total)
 // write-through partials, "done" tags, every workgroup adding its d/P columns -- was measured
 // 7 us slower than the separate k_ffn_finalize launch: each agent-scope round trip costs ~3 us
 // here.  For the same reason balancing only pays when chunk 0 is long enough to hide two hops.)
-template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL>
+// RELU: the non-gated family -- no W_up rows at all, h is the activation itself.
+template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL, bool RELU = false>
 __global__ void __launch_bounds__(NW * 64)
 k_ffn_decode_b1(const B1Params p)
 {
@@ -457,7 +476,7 @@ k_ffn_decode_b1(const B1Params p)
 #pragma unroll
         for (int c = 0; c < NCH; ++c) s = dot16<ES>(buf[c], xr[c], s);
         s = wave_sum(s);
-        const float a = silu_f32(s);
+        const float a = ffn_act<RELU>(s, p.b_in, (size_t)(blk + P * i));
         const bool keep = DENSE ? true : (fabsf(a) >= tau);
         if (lane == 0) {
             s_a[i] = a;
@@ -540,15 +559,18 @@ k_ffn_decode_b1(const B1Params p)
             const int j = local ? blk + P * rows[e] : rows[e];
             if (local) av[r] = s_a[rows[e]];
             else av[r] = __hip_atomic_load(p.apub + aidx[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            load_row(up[r], p.wu, j);
+            if (!RELU) load_row(up[r], p.wu, j);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            float s0 = 0.0f;
+            float s0 = 1.0f;
+            if (!RELU) {
+                s0 = 0.0f;
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xr[c], s0);
-            s0 = wave_sum(s0);
-            if (lane == 0) hs[first + r * stride] = av[r] * s0;
+                for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xr[c], s0);
+                s0 = wave_sum(s0);
+            }
+            if (lane == 0) hs[first + r * stride] = RELU ? av[r] : av[r] * s0;
         }
     };
 
@@ -651,17 +673,20 @@ k_ffn_decode_b1(const B1Params p)
                 if (r < nup) {
                     const int e = wave + r * NW;
                     av[r] = __hip_atomic_load(p.apub + s_l2a[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    load_row(up[r], p.wu, s_l2row[e]);
+                    if (!RELU) load_row(up[r], p.wu, s_l2row[e]);
                 }
             down_fma(std::integral_constant<int, K0MAX>{}, dn0, s_h[0], own);
 #pragma unroll
             for (int r = 0; r < UPB; ++r)
                 if (r < nup) {
-                    float s0 = 0.0f;
+                    float s0 = 1.0f;
+                    if (!RELU) {
+                        s0 = 0.0f;
 #pragma unroll
-                    for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xr[c], s0);
-                    s0 = wave_sum(s0);
-                    if (lane == 0) s_h[1][wave + r * NW] = av[r] * s0;
+                        for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xr[c], s0);
+                        s0 = wave_sum(s0);
+                    }
+                    if (lane == 0) s_h[1][wave + r * NW] = RELU ? av[r] : av[r] * s0;
                 }
             B1_STAMP(3);
             __syncthreads();
@@ -714,10 +739,10 @@ k_ffn_decode_b1(const B1Params p)
     B1_STAMP(6);
 }
 
-template <int ES, int NCH, int DCH, bool DENSE, bool BAL>
+template <int ES, int NCH, int DCH, bool DENSE, bool BAL, bool RELU = false>
 hipError_t launch_b1_variant(clada_ctx *ctx, const B1Params &p, int P, hipStream_t st)
 {
-    auto kern = k_ffn_decode_b1<ES, NCH, 8, DCH, DENSE, BAL>;
+    auto kern = k_ffn_decode_b1<ES, NCH, 8, DCH, DENSE, BAL, RELU>;
     if (BAL) {          // spinning on other workgroups' records needs every workgroup resident at once
         static int occ = -1;
         if (occ < 0) {
@@ -734,22 +759,24 @@ hipError_t launch_b1_variant(clada_ctx *ctx, const B1Params &p, int P, hipStream
     return hipGetLastError();
 }
 
-template <int ES, int NCH, int DCH>
+template <int ES, int NCH, int DCH, bool RELU = false>
 hipError_t launch_b1(clada_ctx *ctx, const B1Params &p, int P, bool dense, bool balance, hipStream_t st)
 {
-    if (dense) return launch_b1_variant<ES, NCH, DCH, true, false>(ctx, p, P, st);
-    if (balance) return launch_b1_variant<ES, NCH, DCH, false, true>(ctx, p, P, st);
-    return launch_b1_variant<ES, NCH, DCH, false, false>(ctx, p, P, st);
+    if (dense) return launch_b1_variant<ES, NCH, DCH, true, false, RELU>(ctx, p, P, st);
+    if (balance) return launch_b1_variant<ES, NCH, DCH, false, true, RELU>(ctx, p, P, st);
+    return launch_b1_variant<ES, NCH, DCH, false, false, RELU>(ctx, p, P, st);
 }
 
 template <int ES, int NCH, int NW, int GB, int UB>
-hipError_t launch_decode(const DecodeParams &p, int P, int B, bool dense, hipStream_t st, bool list = false)
+hipError_t launch_decode(const DecodeParams &p, int P, int B, bool dense, hipStream_t st, bool list = false,
+                         bool relu = false)
 {
     constexpr int VEC = 16 / ES;
     const size_t lds = align_up(sizeof(int) * (3 * (size_t)p.ni_max + 4), 16) +
                        sizeof(float) * (size_t)(NW / 2) * NCH * 64 * VEC;
-    auto kern = list ? k_ffn_decode<ES, NCH, NW, GB, UB, true, true>
-                     : dense ? k_ffn_decode<ES, NCH, NW, GB, UB, true> : k_ffn_decode<ES, NCH, NW, GB, UB, false>;
+    auto kern = list ? (relu ? k_ffn_decode<ES, NCH, NW, GB, UB, true, true, true> : k_ffn_decode<ES, NCH, NW, GB, UB, true, true>)
+                : relu ? (dense ? k_ffn_decode<ES, NCH, NW, GB, UB, true, false, true> : k_ffn_decode<ES, NCH, NW, GB, UB, false, false, true>)
+                : dense ? k_ffn_decode<ES, NCH, NW, GB, UB, true> : k_ffn_decode<ES, NCH, NW, GB, UB, false>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -785,15 +812,21 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     p.x = (const char *)x; p.tau = tau;
     p.partial = reinterpret_cast<float *>(ws);
     p.keep = lists ? reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256)) : nullptr;
-    p.idx = nullptr; p.n_list = nullptr;
+    p.idx = nullptr; p.n_list = nullptr; p.b_in = nullptr;
     p.d = d; p.F = F; p.ni_max = (F + P - 1) / P;
     hipStream_t stream = (hipStream_t)hip_stream;
 
     const int nch = (d * es + 1023) / 1024;
     hipError_t e = hipErrorInvalidValue;
 
+    const bool relu = layer->kind == CLADA_FFN_RELU;
+    p.b_in = relu ? layer->b_in : nullptr;
+    const float *b_out = relu ? layer->b_out : nullptr;
+
     // ---- split-d path (decode batch 1, whole-KiB rows, <= 64 neurons per workgroup)
-    if (ctx->opt_decode_b1 >= 1 && B == 1 && (d * es) % 1024 == 0 && (nch == 2 || nch == 8 || nch == 10)) {
+    const bool b1_shape = relu ? (es == 2 && (nch == 2 || nch == 5 || nch == 8 || nch == 10))
+                               : (nch == 2 || nch == 8 || nch == 10 || (es == 2 && (nch == 4 || nch == 5)));
+    if (ctx->opt_decode_b1 >= 1 && B == 1 && (d * es) % 1024 == 0 && b1_shape) {
         const int Pb = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
         const int ni_b = (F + Pb - 1) / Pb;
         if (F >= Pb && ni_b <= 64) {
@@ -803,15 +836,24 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             b.apub = reinterpret_cast<float *>(ctx->ws + COOP_APUB);
             unsigned int *epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
             b.epoch = epoch;
+            b.b_in = p.b_in;
             b.d = d; b.F = F;
             b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
             // balancing pays for 8 KiB rows; with 10 KiB rows the balanced variant runs out of registers and
             // was measured slower (57 vs 51 us per 13B-shape layer at 45 % sparsity) than the plain split
-            bool balance = !dense && ctx->opt_decode_b1 == 1 && ni_b <= 56 && nch != 10;
+            bool balance = !dense && ctx->opt_decode_b1 == 1 && ni_b <= 56 && (nch != 10 || relu);
             hipError_t eb = hipErrorNotSupported;
             for (int attempt = 0; attempt < 2 && eb == hipErrorNotSupported; ++attempt) {
-                if (es == 2 && nch == 8) eb = launch_b1<2, 8, 16>(ctx, b, Pb, dense, balance, stream);
+                if (relu) {
+                    if (nch == 8) eb = launch_b1<2, 8, 16, true>(ctx, b, Pb, dense, balance, stream);
+                    else if (nch == 10) eb = launch_b1<2, 10, 8, true>(ctx, b, Pb, dense, balance, stream);
+                    else if (nch == 5) eb = launch_b1<2, 5, 16, true>(ctx, b, Pb, dense, balance, stream);
+                    else eb = launch_b1<2, 2, 16, true>(ctx, b, Pb, dense, balance, stream);
+                }
+                else if (es == 2 && nch == 8) eb = launch_b1<2, 8, 16>(ctx, b, Pb, dense, balance, stream);
                 else if (es == 2 && nch == 10) eb = launch_b1<2, 10, 8>(ctx, b, Pb, dense, balance, stream);
+                else if (es == 2 && nch == 5) eb = launch_b1<2, 5, 16>(ctx, b, Pb, dense, balance, stream);
+                else if (es == 2 && nch == 4) eb = launch_b1<2, 4, 16>(ctx, b, Pb, dense, balance, stream);
                 else if (es == 2 && nch == 2) eb = launch_b1<2, 2, 16>(ctx, b, Pb, dense, balance, stream);
                 else if (es == 4 && nch == 2) eb = launch_b1<4, 2, 16>(ctx, b, Pb, dense, balance, stream);
                 else if (es == 4 && nch == 8) eb = launch_b1<4, 8, 16>(ctx, b, Pb, dense, balance, stream);
@@ -819,7 +861,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             }
             CLADA_CHECK_HIP(ctx, eb);
             launch_finalize(es, p.partial, Pb, 1, d, (char *)y, balance ? epoch : nullptr, stream,
-                            ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3]);
+                            ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3], b_out);
             CLADA_CHECK_HIP(ctx, hipGetLastError());
             if (lists) {
                 hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
@@ -829,7 +871,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
         }
     }
     // ---- batched MFMA path (2 <= B <= 16, bf16, supported widths)
-    if (B >= 2 && ctx->opt_decode_batched) {
+    if (B >= 2 && ctx->opt_decode_batched && !relu) {
         unsigned char *keep_region = reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256));
         char *scratch = reinterpret_cast<char *>(keep_region) + align_up((size_t)B * F, 256);
         bool ran = false;
@@ -852,7 +894,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     if (ctx->opt_diag_events) CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[0], stream));
 #define CLADA_DECODE_CASE(ES_, NCH_, NW_, GB_, UB_)                                        \
     if (es == ES_ && nch <= NCH_ && e == hipErrorInvalidValue)                             \
-        e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, dense, stream);
+        e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, dense, stream, false, relu);
     CLADA_DECODE_CASE(2, 1, 8, 2, 2)
     CLADA_DECODE_CASE(2, 2, 8, 2, 2)
     CLADA_DECODE_CASE(2, 4, 8, 2, 2)
@@ -869,7 +911,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
 
     if (ctx->opt_diag_events) CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[1], stream));
     launch_finalize(es, p.partial, P, B, d, (char *)y, nullptr, stream,
-                    ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3]);
+                    ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3], b_out);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     if (lists) {
         hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);
@@ -904,8 +946,11 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
     p.partial = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
     p.keep = nullptr; p.idx = idx; p.n_list = n_active;
     p.d = d; p.F = F; p.ni_max = (F + P - 1) / P;
+    const bool relu = layer->kind == CLADA_FFN_RELU;
+    p.b_in = relu ? layer->b_in : nullptr;
+    const float *b_out = relu ? layer->b_out : nullptr;
     const int nch = (d * es + 1023) / 1024;
-    if (B == 1 && ctx->opt_decode_b1 >= 1) {          // streaming kernel for whole-KiB rows
+    if (B == 1 && ctx->opt_decode_b1 >= 1 && !relu) {  // streaming kernel for whole-KiB rows
         bool ran = false;
         int Pl = 0;
         CLADA_CHECK_HIP(ctx, clada_decode_list_b1(ctx, layer, x, idx, n_active, p.partial, &Pl, stream, &ran));
@@ -918,7 +963,7 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
     hipError_t e = hipErrorInvalidValue;
 #define CLADA_LIST_CASE(ES_, NCH_, NW_, GB_, UB_)                                          \
     if (es == ES_ && nch <= NCH_ && e == hipErrorInvalidValue)                             \
-        e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, true, stream, true);
+        e = launch_decode<ES_, NCH_, NW_, GB_, UB_>(p, P, B, true, stream, true, relu);
     CLADA_LIST_CASE(2, 1, 8, 2, 2)
     CLADA_LIST_CASE(2, 2, 8, 2, 2)
     CLADA_LIST_CASE(2, 4, 8, 2, 2)
@@ -932,7 +977,7 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
     CLADA_LIST_CASE(4, 16, 8, 1, 1)
 #undef CLADA_LIST_CASE
     CLADA_CHECK_HIP(ctx, e);
-    launch_finalize(es, p.partial, P, B, d, (char *)y, nullptr, stream);
+    launch_finalize(es, p.partial, P, B, d, (char *)y, nullptr, stream, nullptr, nullptr, b_out);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     return CLADA_OK;
 }
@@ -946,9 +991,10 @@ extern "C" clada_status clada_static_ffn_decode(clada_ctx *ctx, const clada_laye
     return run_list_decode(ctx, layer, x, B, active_idx, n_active, y, hip_stream);
 }
 
-void clada_launch_finalize(int es, const float *partial, int P, int B, int d, char *y, hipStream_t stream)
+void clada_launch_finalize(int es, const float *partial, int P, int B, int d, char *y, hipStream_t stream,
+                           const float *bias)
 {
-    launch_finalize(es, partial, P, B, d, y, nullptr, stream);
+    launch_finalize(es, partial, P, B, d, y, nullptr, stream, nullptr, nullptr, bias);
 }
 
 size_t clada_ws_decode(int32_t d, int32_t d_ff, int32_t B)

@@ -706,6 +706,7 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
 {
     if (!ctx) return CLADA_ERR_NULL;
     clada_status st = clada_check_layer(ctx, layer);
+    if (st == CLADA_OK) st = clada_require_swiglu(ctx, layer, "clada_prefix_stats");
     if (st != CLADA_OK) return st;
     if (!x || !out) return clada_fail(ctx, CLADA_ERR_NULL, "x or out is NULL");
     if (T < 1 || T > (1 << 20)) return clada_fail(ctx, CLADA_ERR_SHAPE, "T=%d outside [1,2^20]", T);

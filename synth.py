@@ -19,7 +19,7 @@ from dataclasses import dataclass
 import numpy as np
 
 # tensor-kind tags for the stream keys
-_W_GATE, _W_UP, _W_DOWN, _PREFIX, _HIDDEN, _LOGITS, _TOKENS, _PERM = range(8)
+_W_GATE, _W_UP, _W_DOWN, _PREFIX, _HIDDEN, _LOGITS, _TOKENS, _PERM, _BIAS = range(9)
 
 
 @dataclass(frozen=True)
@@ -51,6 +51,10 @@ CONFIGS = {
     "c4": Config(4, "llama3-8b", 32, 4096, 14336, "bf16", 0.02, 1, 4096, 128256, 0.45, "zipf", 256),
     # LLaMA2-13B FFN shape, decode batch 16
     "c5": Config(5, "llama2-13b", 40, 5120, 13824, "bf16", 0.02, 16, 2048, 32000, 0.45, "zipf", 16),
+    # non-gated ReLU FFN shapes of the OPT models the paper also evaluates (not in the benchmark
+    # list; the target sparsity sits above the 50 % of exact zeros a ReLU produces by itself)
+    "o27": Config(6, "opt-2.7b", 32, 2560, 10240, "bf16", 0.02, 1, 512, 50272, 0.70, "zipf", 64),
+    "o350": Config(7, "opt-350m", 24, 1024, 4096, "bf16", 0.02, 1, 512, 50272, 0.70, "zipf", 64),
 }
 
 
@@ -89,6 +93,19 @@ def layer_weights(cfg: Config, seed: int, layer: int, d: int | None = None, d_ff
     F = d_ff or cfg.d_ff
     return tuple(_normal(_rng(seed, cfg.cid, k, layer), (F, d), cfg.w_std, cfg.dtype)
                  for k in (_W_GATE, _W_UP, _W_DOWN))
+
+
+def relu_layer(cfg: Config, seed: int, layer: int, d: int | None = None, d_ff: int | None = None):
+    """(w_in, b_in, w_out, b_out) of a non-gated ReLU FFN: weights [d_ff][d] neuron-major in the
+    storage dtype, biases fp32 ~ N(0, w_std)."""
+    d = d or cfg.d
+    F = d_ff or cfg.d_ff
+    w_in = _normal(_rng(seed, cfg.cid, _W_GATE, layer), (F, d), cfg.w_std, cfg.dtype)
+    w_out = _normal(_rng(seed, cfg.cid, _W_DOWN, layer), (F, d), cfg.w_std, cfg.dtype)
+    rb = _rng(seed, cfg.cid, _BIAS, layer)
+    b_in = (rb.standard_normal(F, dtype=np.float32) * np.float32(cfg.w_std)).astype(np.float32)
+    b_out = (rb.standard_normal(d, dtype=np.float32) * np.float32(cfg.w_std)).astype(np.float32)
+    return w_in, b_in, w_out, b_out
 
 
 def prefix_hidden(cfg: Config, seed: int, layer: int, T: int | None = None, d: int | None = None):

@@ -1,0 +1,124 @@
+"""GPU parity: the non-gated ReLU FFN family (OPT shapes) through the decode calls."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import BAND, DEV, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def clada():
+    import paper_2502_19078_amd as m
+    m.load_library()
+    return m
+
+
+def _layer(clada, cfg, w, biases=True):
+    from paper_2502_19078_amd import binding
+    w_in, b_in, w_out, b_out = w
+    return clada.Layer(to_dev(w_in, cfg.dtype), None, to_dev(w_out, cfg.dtype), kind=binding.RELU,
+                       b_in=torch.from_numpy(b_in).to(DEV) if biases else None,
+                       b_out=torch.from_numpy(b_out).to(DEV) if biases else None)
+
+
+CASES = [
+    ("o350", 1024, 4096, 1),     # OPT-350M shape: 2 KiB rows, batch-1 kernel
+    ("o27", 2560, 10240, 1),     # OPT-2.7B shape: 5 KiB rows, batch-1 kernel with balancing
+    ("o27", 2560, 1000, 1),      # ragged neuron count, fewer neurons than the balanced kernel wants
+    ("o27", 2560, 640, 4),       # batch > 1: generic kernel, per-token thresholds
+    ("c1", 96, 200, 3),          # fp32, odd row length: generic kernel
+    ("o27", 4096, 1024, 1),      # 8 KiB rows (OPT-6.7B width)
+    ("o27", 5120, 768, 1),       # 10 KiB rows (OPT-13B width)
+]
+
+
+@pytest.mark.parametrize("cfg_name,d,F,B", CASES)
+@pytest.mark.parametrize("biases", [True, False])
+def test_relu_sparse_and_dense_parity(clada, cfg_name, d, F, B, biases):
+    cfg = synth.CONFIGS[cfg_name]
+    w = synth.relu_layer(cfg, 2, 3, d=d, d_ff=F)
+    x = synth.decode_hidden(cfg, 2, 3, 0, B=B, d=d)
+    wb = w if biases else (w[0], None, w[2], None)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, B, 0, 0))
+    layer = _layer(clada, cfg, w, biases)
+    xd = to_dev(x, cfg.dtype)
+    act = oracle.relu_decode(*wb, x)["act"]
+    for q in (0.0, 0.7, 0.9):
+        tau = np.quantile(act, q, axis=1).astype(np.float32)
+        if q == 0.7:
+            tau = np.maximum(tau, np.float32(1e-6))               # above the exact zeros
+        y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, torch.from_numpy(tau).to(DEV), want_lists=True)
+        torch.cuda.synchronize()
+        ref = oracle.relu_decode(*wb, x, tau=tau.astype(np.float64))
+        mask_gpu = unpack_bits(bits, F)
+        diff = mask_gpu != ref["mask"]
+        band = np.abs(ref["act"] - tau[:, None]) <= BAND * np.maximum(tau[:, None], 1e-30)
+        assert not (diff & ~band).any(), f"q={q}: mask differs outside the band"
+        ref_y = oracle.relu_decode(*wb, x, mask=mask_gpu)["y"]
+        assert_close_y(to_np(y), ref_y, TOL_Y[cfg.dtype], f"relu sparse q={q}")
+        union = np.flatnonzero(mask_gpu.any(0))
+        c = cnt.cpu().numpy()
+        assert c[0] == union.size and np.array_equal(idx.cpu().numpy()[: c[0]], union)
+        assert np.array_equal(c[1:], mask_gpu.sum(1))
+    yd = clada.dense_ffn_decode(ctx, layer, xd)
+    torch.cuda.synchronize()
+    assert_close_y(to_np(yd), oracle.relu_decode(*wb, x)["y"], TOL_Y[cfg.dtype], "relu dense twin")
+    # tau = +inf keeps nothing: the output is the output bias
+    y_inf = clada.sparse_ffn_decode(ctx, layer, xd, torch.full((B,), float("inf"), device=DEV))
+    want = np.broadcast_to(w[3] if biases else np.zeros(d, np.float32), (B, d))
+    assert_close_y(to_np(y_inf), want.astype(np.float64), TOL_Y[cfg.dtype] if biases else 0.0, "tau=inf")
+
+
+def test_relu_tau_zero_equals_dense_and_small_tau_drops_only_zeros(clada):
+    cfg = synth.CONFIGS["o27"]
+    d, F = 2560, 10240
+    w = synth.relu_layer(cfg, 0, 0)
+    x = synth.decode_hidden(cfg, 0, 0, 0, B=1)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, 0, 0))
+    layer = _layer(clada, cfg, w)
+    xd = to_dev(x, cfg.dtype)
+    y0, _, c0, _ = clada.sparse_ffn_decode(ctx, layer, xd, torch.zeros(1, device=DEV), want_lists=True)
+    y0 = y0.clone()
+    yt, _, ct, _ = clada.sparse_ffn_decode(ctx, layer, xd, torch.full((1,), 1e-30, device=DEV), want_lists=True)
+    yd = clada.dense_ffn_decode(ctx, layer, xd)
+    torch.cuda.synchronize()
+    assert int(c0[0]) == F                                   # a >= 0 always: tau = 0 keeps every neuron
+    assert 0.3 * F < int(ct[0]) < 0.7 * F                    # the exact zeros of the ReLU are gone
+    # dropping exact zeros changes nothing but the summation order
+    assert_close_y(to_np(yt), to_np(y0), 2e-2, "zeros dropped")
+    assert_close_y(to_np(y0), to_np(yd), 2e-2, "tau=0 vs dense twin")
+
+
+def test_relu_static_list_decode(clada):
+    cfg = synth.CONFIGS["o27"]
+    d, F, B = 2560, 900, 2
+    w = synth.relu_layer(cfg, 1, 1, d=d, d_ff=F)
+    x = synth.decode_hidden(cfg, 1, 1, 0, B=B, d=d)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, B, 0, 0))
+    layer = _layer(clada, cfg, w)
+    keep = np.random.default_rng(3).random(F) < 0.4
+    idx = torch.zeros(F, dtype=torch.int32, device=DEV)
+    ii = np.flatnonzero(keep).astype(np.int32)
+    idx[: ii.size] = torch.from_numpy(ii).to(DEV)
+    n = torch.tensor([ii.size], dtype=torch.int32, device=DEV)
+    y = clada.static_ffn_decode(ctx, layer, to_dev(x, cfg.dtype), idx, n)
+    torch.cuda.synchronize()
+    ref = oracle.relu_decode(*w, x, mask=np.broadcast_to(keep, (B, F)))["y"]
+    assert_close_y(to_np(y), ref, TOL_Y[cfg.dtype], "relu list decode")
+
+
+def test_relu_rejected_by_prefill_calls(clada):
+    from paper_2502_19078_amd.binding import CladaError
+    cfg = synth.CONFIGS["o27"]
+    w = synth.relu_layer(cfg, 1, 1, d=256, d_ff=128)
+    ctx = clada.Context(0, clada.workspace_bytes(256, 128, 1, 64, 0))
+    layer = _layer(clada, cfg, w)
+    X = to_dev(synth.prefix_hidden(cfg, 1, 1, T=64, d=256), cfg.dtype)
+    with pytest.raises(CladaError):
+        clada.prefix_stats(ctx, layer, X)
+    with pytest.raises(CladaError):
+        clada.threshold_search_cett(ctx, layer, X)

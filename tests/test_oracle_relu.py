@@ -63,3 +63,17 @@ def test_tau_zero_is_dense_and_rows_are_independent():
     assert np.array_equal(oracle.relu_decode(wi, bi, wo, bo, x, tau=np.zeros(4))["y"], dense)
     for b in range(4):
         assert np.array_equal(oracle.relu_decode(wi, bi, wo, bo, x[b:b + 1])["y"][0], dense[b])
+
+
+def test_prefix_stats_match_numpy_and_the_decode_function():
+    wi, bi, wo, bo, x = _toy(9, 32, 70, 11)
+    r = oracle.relu_prefix_stats(wi, bi, wo, bo, x)
+    a = np.maximum(x.astype(np.float64) @ wi.astype(np.float64).T + bi, 0.0)
+    np.testing.assert_allclose(r["abs_act_pool"], a, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(r["sum_abs_act"], a.sum(0), rtol=1e-12)
+    np.testing.assert_allclose(r["sum_sq_act"], (a * a).sum(0), rtol=1e-12)
+    np.testing.assert_allclose(r["sum_sq_h"], (a * a).sum(0), rtol=1e-12)
+    np.testing.assert_allclose(r["max_abs_act"], a.max(0), rtol=1e-13)
+    np.testing.assert_allclose(r["A"], np.sqrt((a * a).sum(0)) * np.linalg.norm(wo.astype(np.float64), axis=1), rtol=1e-12)
+    # the prefill output is the dense decode of every prefix token
+    np.testing.assert_allclose(r["y"], oracle.relu_decode(wi, bi, wo, bo, x)["y"], rtol=1e-12, atol=1e-13)
