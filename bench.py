@@ -69,6 +69,8 @@ def main():
     K, W = args.steps, args.warmup
     nsteps = K + W
     es = 2 if cfg.dtype == "bf16" else 4
+    relu = cfg.name.startswith("opt")           # non-gated ReLU FFN family: two matrices + biases
+    nmat = 2 if relu else 3                     # matrices a dense call reads
     tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     t_setup = time.time()
 
@@ -82,18 +84,28 @@ def main():
     host_w = {}
 
     def make_layer(l):
-        w = synth.layer_weights(cfg, args.seed, l)
-        if l < n_host:
-            host_w[l] = w
-        return l, [synth.bf16_bits(a).view(np.int16) if cfg.dtype == "bf16" else a for a in w]
+        if relu:
+            w_in, b_in, w_out, b_out = synth.relu_layer(cfg, args.seed, l)
+            if l < n_host:
+                host_w[l] = (w_in, b_in, w_out, b_out)
+            w, biases = (w_in, w_out), (b_in, b_out)
+        else:
+            w, biases = synth.layer_weights(cfg, args.seed, l), None
+            if l < n_host:
+                host_w[l] = w
+        return l, [synth.bf16_bits(a).view(np.int16) if cfg.dtype == "bf16" else a for a in w], biases
 
     layers = [None] * L
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
-        for l, arrs in ex.map(make_layer, range(L)):
+        for l, arrs, biases in ex.map(make_layer, range(L)):
             ts = [torch.from_numpy(a).to(dev) for a in arrs]
             if cfg.dtype == "bf16":
                 ts = [t.view(torch.bfloat16) for t in ts]
-            layers[l] = clada.Layer(*ts)
+            if relu:
+                layers[l] = clada.Layer(ts[0], None, ts[1], kind=binding.RELU,
+                                        b_in=torch.from_numpy(biases[0]).to(dev), b_out=torch.from_numpy(biases[1]).to(dev))
+            else:
+                layers[l] = clada.Layer(*ts)
     x_host = np.stack([np.stack([synth.decode_hidden(cfg, args.seed, l, s, shared_frac=args.shared_frac)
                                  for l in range(L)]) for s in range(nsteps)])
     x_all = to_dev(x_host.reshape(nsteps, L, B, d))                       # [step][layer][B][d]
@@ -127,16 +139,18 @@ def main():
     torch.cuda.synchronize()
     prefill_layer_ms = e0.elapsed_time(e1)
     # the paper's own calibration (error-bounded search, bound 0.2) on the same prefix, for comparison
-    clada.threshold_search_cett(ctx, layers[L - 1], Xp, 0.2)
-    e0.record()
-    tau_cett, mean_cett = clada.threshold_search_cett(ctx, layers[L - 1], Xp, 0.2)
-    e1.record()
-    torch.cuda.synchronize()
-    cett_ms = e0.elapsed_time(e1)
-    cett_info = {"layer_ms_gpu": round(cett_ms, 3), "bound": 0.2, "tau_base": round(float(tau_cett.item()), 5),
-                 "mean_cett": round(float(mean_cett.item()), 5),
-                 "sparsity_on_prefix": round(float((st.abs_act_pool < tau_cett).float().mean().item()), 4),
-                 "percentile_tau_base": round(float(tau_base[L - 1].item()), 5)}
+    cett_info = None
+    if not relu:
+        clada.threshold_search_cett(ctx, layers[L - 1], Xp, 0.2)
+        e0.record()
+        tau_cett, mean_cett = clada.threshold_search_cett(ctx, layers[L - 1], Xp, 0.2)
+        e1.record()
+        torch.cuda.synchronize()
+        cett_ms = e0.elapsed_time(e1)
+        cett_info = {"layer_ms_gpu": round(cett_ms, 3), "bound": 0.2, "tau_base": round(float(tau_cett.item()), 5),
+                     "mean_cett": round(float(mean_cett.item()), 5),
+                     "sparsity_on_prefix": round(float((st.abs_act_pool < tau_cett).float().mean().item()), 4),
+                     "percentile_tau_base": round(float(tau_base[L - 1].item()), 5)}
     del st, Xp
 
     lam = torch.full((L,), 0.80, dtype=torch.float32, device=dev)     # printed coefficients
@@ -235,7 +249,7 @@ def main():
         cnt_np = cnt.cpu().numpy()
         n_union = cnt_np[:, :, 0].astype(np.float64).mean()
         res = {"ms": ms, "rho_union": 1.0 - n_union / F, "rho_token": 1.0 - cnt_np[:, :, 1:].mean() / F,
-               "bytes_layer": (F + 2.0 * n_union) * d * es}
+               "bytes_layer": (F + (nmat - 1.0) * n_union) * d * es}
         nprobe = min(K, 8)                                           # events around every per-layer call
         evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
                for _ in range(nprobe)]
@@ -275,7 +289,7 @@ def main():
         ctx.set_option("diag.kernel_events", 0)
         res["main_us"], res["finalize_us"] = float(np.mean(main_us)), float(np.mean(fin_us))
         # algorithmic bytes of exactly the probed calls (the first nprobe timed steps)
-        res["bytes_probe"] = (F + 2.0 * cnt_np[:nprobe, :, 0].astype(np.float64).mean()) * d * es
+        res["bytes_probe"] = (F + (nmat - 1.0) * cnt_np[:nprobe, :, 0].astype(np.float64).mean()) * d * es
         return res
 
     nat = measure_regime(tau_s, tau_H)            # the method as defined: thresholds follow the signals
@@ -284,7 +298,8 @@ def main():
     ms_sparse, rho_union, rho_token = nat["ms"], nat["rho_union"], nat["rho_token"]
     bytes_layer, call_us = nat["bytes_layer"], nat["call_us"]
     bytes_probe, main_us = nat["bytes_probe"], nat["main_us"]
-    bytes_dense = 3.0 * F * d * es
+    bytes_dense = float(nmat) * F * d * es
+    ideal = lambda rho: nmat / (nmat - (nmat - 1.0) * rho)      # dense bytes / sparse bytes
     step_us_per_layer = ms_sparse * 1e3 / L
 
     # stream-read ceiling on the same weights
@@ -299,7 +314,8 @@ def main():
     torch.cuda.synchronize()
     ceil_gbs = min(L, 8) * F * d * es / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
-    main_kernel = ("k_ffn_decode_b1 (gate rows dense + up/down rows of kept neurons)" if B == 1
+    main_kernel = ("k_ffn_decode_b1 (input rows dense + output rows of kept neurons)" if B == 1 and relu
+                   else "k_ffn_decode_b1 (gate rows dense + up/down rows of kept neurons)" if B == 1
                    else "k_bat_gateup + k_bat_down (batched decode, timed as one)")
     achieved = bytes_probe / (main_us * 1e-6) / 1e9          # dominant kernel alone
     achieved_call = bytes_probe / (call_us * 1e-6) / 1e9     # whole call: main kernel + final reduction + launch gap
@@ -321,13 +337,13 @@ def main():
         "sparsity_union": round(float(rho_union), 4),
         "dense_ms_per_step": round(ms_dense, 4),
         "speedup_vs_dense": round(ms_dense / ms_sparse, 4),
-        "ideal_speedup": round(3.0 / (3.0 - 2.0 * rho_union), 4),
+        "ideal_speedup": round(ideal(rho_union), 4),
         "regime": "natural: tau_s, tau_H = medians of the run's own surprisal/entropy streams",
         "regime_indicators_off": {
             "ms_per_step": round(off["ms"], 4), "tokens_per_s": round(B * 1e3 / off["ms"], 2),
             "sparsity_union": round(float(off["rho_union"]), 4),
             "speedup_vs_dense": round(ms_dense / off["ms"], 4),
-            "ideal_speedup": round(3.0 / (3.0 - 2.0 * off["rho_union"]), 4),
+            "ideal_speedup": round(ideal(off["rho_union"]), 4),
             "bytes_per_launch": round(off["bytes_probe"]),
             "kernel_us": round(off["main_us"], 2), "finalize_us": round(off["finalize_us"], 2),
             "call_us": round(off["call_us"], 2),
@@ -339,7 +355,7 @@ def main():
         "dense_step_gbs": round(bytes_dense * L / (ms_dense * 1e-3) / 1e9, 1),
         "stream_read_ceiling_gbs": round(ceil_gbs, 1),   # whole-row streaming of one 90 MB matrix per launch, launch gaps included
         "prefill": {"layer_ms_gpu": round(prefill_layer_ms, 3), "stack_wall_ms_incl_h2d": round(prefill_wall_ms, 1),
-                    "tflops_layer": round(6.0 * T * d * F / (prefill_layer_ms * 1e-3) / 1e12, 1),
+                    "tflops_layer": round(2.0 * nmat * T * d * F / (prefill_layer_ms * 1e-3) / 1e12, 1),
                     "cett_search": cett_info},
         "roofline": {"bound": "hbm", "kernel": main_kernel,
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -362,7 +378,10 @@ def main():
         for s in range(W, W + K):
             for l in range(n_host):
                 t0 = time.perf_counter()
-                oracle.sparse_decode(*host_w[l], x_host[s, l], tf[l])
+                if relu:
+                    oracle.relu_decode(*host_w[l], x_host[s, l], tau=tf[l])
+                else:
+                    oracle.sparse_decode(*host_w[l], x_host[s, l], tf[l])
                 t_used += time.perf_counter() - t0
                 n_done += 1
             if t_used > budget:

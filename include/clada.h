@@ -66,9 +66,10 @@ const char *clada_status_str(clada_status s);
 const char *clada_last_error(const clada_ctx *ctx);
 
 /* Launch-shape tuning knobs; results never depend on them beyond fp32 summation
- * order.  Names: "decode.b1" (batch-1 decode kernel: 1 = split-d kernel with
- * cross-workgroup load balancing [default], 2 = split-d kernel without balancing,
- * 0 = the generic kernels used for batch > 1), "decode.own_first" (1..14, neurons a
+ * order.  Names: "decode.b1" (batch-1 decode kernel: 1 = split-d kernel, with
+ * cross-workgroup load balancing where the layer is large enough for it to pay
+ * [default], 2 = split-d kernel without balancing, 3 = with balancing whenever
+ * the launch allows it, 0 = the generic kernels), "decode.own_first" (1..14, neurons a
  * workgroup keeps for itself before the balanced hand-over; 0 = default),
  * "decode.wgs_per_cu" (1 or 2 workgroups per compute unit for the generic kernel),
  * "decode.batched" (1 = matrix-core kernels for bf16 batches 2..16 [default], 0 = the
@@ -90,9 +91,8 @@ size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int3
  *   y_b = sum_{j kept} a_bj W_out[j,:] + b_out.
  * For it w_gate holds W_in [d_ff][d], w_down holds W_out neuron-major [d_ff][d]
  * (HF fc2.weight transposed), w_up is ignored; b_in [d_ff] and b_out [d] are fp32
- * device arrays or NULL (zero).  Supported by clada_sparse_ffn_decode,
- * clada_dense_ffn_decode and clada_static_ffn_decode; the prefill and CETT calls
- * return CLADA_ERR_VALUE for it. */
+ * device arrays or NULL (zero).  Supported by clada_prefix_stats (h = a), the decode
+ * calls and clada_static_ffn_decode; the CETT calls return CLADA_ERR_VALUE for it. */
 typedef enum { CLADA_FFN_SWIGLU = 0, CLADA_FFN_RELU = 1 } clada_ffn_kind;
 
 typedef struct {

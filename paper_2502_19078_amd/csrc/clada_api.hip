@@ -128,7 +128,7 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
         return CLADA_OK;
     }
     if (!strcmp(name, "decode.b1")) {
-        if (value < 0 || value > 2) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.b1=%d outside [0,2]", value);
+        if (value < 0 || value > 3) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.b1=%d outside [0,3]", value);
         ctx->opt_decode_b1 = value;
         return CLADA_OK;
     }

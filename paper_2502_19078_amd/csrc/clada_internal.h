@@ -13,7 +13,7 @@ struct clada_ctx {
     size_t ws_bytes;
     char *ws;            // device workspace, 256-byte aligned; first CLADA_WS_HEADER bytes = counters
     int opt_decode_wgs_per_cu;   // launch shape of the decode kernel (clada_set_option)
-    int opt_decode_b1;           // batch-1 split-d kernel: 0 off (generic kernels), 1 with balancing, 2 without
+    int opt_decode_b1;           // batch-1 split-d kernel: 0 off (generic kernels), 1 balancing where it pays, 2 never, 3 always
     int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
     int opt_decode_batched;      // 1: MFMA path for 2 <= B <= 16 (bf16), 0: generic kernels
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)

@@ -839,9 +839,14 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             b.b_in = p.b_in;
             b.d = d; b.F = F;
             b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
-            // balancing pays for 8 KiB rows; with 10 KiB rows the balanced variant runs out of registers and
-            // was measured slower (57 vs 51 us per 13B-shape layer at 45 % sparsity) than the plain split
-            bool balance = !dense && ctx->opt_decode_b1 == 1 && ni_b <= 56 && (nch != 10 || relu);
+            // Balancing pays when the kept-row phase is long enough to hide the mask exchange behind the
+            // workgroup's own first chunk: measured faster on the 7B/8B shapes (90-117 MB per matrix), slower
+            // on 52 MB ReLU layers (17.0 vs 14.1 us) and on 8 MB ones (10.0 vs 6.4 us).  With 10 KiB gated rows
+            // the balanced variant also runs out of registers (57 vs 51 us per 13B-shape layer).
+            const double phase2_bytes = (relu ? 1.0 : 2.0) * (double)F * d * es;
+            bool balance = !dense && ni_b <= 56 &&
+                           (ctx->opt_decode_b1 == 3 ||
+                            (ctx->opt_decode_b1 == 1 && phase2_bytes >= 128e6 && (nch != 10 || relu)));
             hipError_t eb = hipErrorNotSupported;
             for (int attempt = 0; attempt < 2 && eb == hipErrorNotSupported; ++attempt) {
                 if (relu) {

@@ -95,6 +95,8 @@ struct GateUpParams {
     float *pool;        // [T][F] or nullptr
     char *hbuf;         // [T][Fp] layer dtype (Fp = F rounded up to BK, zero past F) or nullptr
     int Fp;             // F rounded up to a multiple of 64
+    const float *b_in;  // non-gated family: input bias [F] or nullptr
+    int relu;           // non-gated family: a = max(0, C_g + b_in), h = a (wu then aliases wg and C_u is ignored)
 };
 
 // Epilogue of the gate/up GEMM on the accumulators (shared by the fp32 and bf16 kernels):
@@ -115,8 +117,15 @@ __device__ __forceinline__ void gateup_epilogue(const f32x16 (&acc)[2][2][2], co
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int t = tm * BM + wm * 64 + mb * 32 + acc_row(r, lane);
-                const float a = silu_f32(acc[0][mb][nb][r]);
-                const float h = a * acc[1][mb][nb][r];
+                float a, h;
+                if (p.relu) {
+                    const float g = acc[0][mb][nb][r] + ((p.b_in && j < p.F) ? p.b_in[j] : 0.0f);
+                    a = g > 0.0f ? g : (g != g ? g : 0.0f);
+                    h = a;
+                } else {
+                    a = silu_f32(acc[0][mb][nb][r]);
+                    h = a * acc[1][mb][nb][r];
+                }
                 if (t < p.T && j < p.F) {
                     const float aa = fabsf(a);
                     s_abs += aa;
@@ -380,6 +389,7 @@ k_prefix_gateup_bf16(const GateUpParams p)
 struct DownParams {
     const char *h, *wd;
     char *y;                       // [T][d] layer dtype, or nullptr
+    const float *bias;             // output bias [d] of the non-gated family, or nullptr
     float *rowsq;                  // [n_tn][T] per column-tile sums of squares of the fp32 rows, or nullptr
     int T, d, F, Fp, n_tm, n_tn;   // Fp = F rounded up to a multiple of BK (row stride of h)
 };
@@ -494,7 +504,7 @@ k_prefix_down(const DownParams p)
             for (int r = 0; r < 16; ++r) {
                 const int t = tm * BM + wm * 64 + mb * 32 + acc_row(r, lane);
                 if (t < p.T && col < p.d) {
-                    const float v = acc[0][mb][nb][r];
+                    const float v = acc[0][mb][nb][r] + (p.bias ? p.bias[col] : 0.0f);
                     if (ES == 4) reinterpret_cast<float *>(p.y)[(size_t)t * p.d + col] = v;
                     else reinterpret_cast<unsigned short *>(p.y)[(size_t)t * p.d + col] = (unsigned short)f32_to_bf16_bits(v);
                 }
@@ -603,7 +613,8 @@ k_prefix_down_bf16(const DownParams p)
             for (int r = 0; r < 16; ++r) {
                 const int t = tm * BM + wm * 64 + mb * 32 + acc_row(r, lane);
                 if (t < p.T && col < p.d)
-                    reinterpret_cast<unsigned short *>(p.y)[(size_t)t * p.d + col] = (unsigned short)f32_to_bf16_bits(acc[mb][nb][r]);
+                    reinterpret_cast<unsigned short *>(p.y)[(size_t)t * p.d + col] =
+                        (unsigned short)f32_to_bf16_bits(acc[mb][nb][r] + (p.bias ? p.bias[col] : 0.0f));
             }
     }
 }
@@ -671,7 +682,10 @@ hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, f
 {
     const int d = layer->d, F = layer->d_ff, es = (int)dtype_size(layer->dtype);
     GateUpParams g;
-    g.x = (const char *)x; g.wg = (const char *)layer->w_gate; g.wu = (const char *)layer->w_up;
+    const bool relu = layer->kind == CLADA_FFN_RELU;
+    g.x = (const char *)x; g.wg = (const char *)layer->w_gate;
+    g.wu = (const char *)(relu ? layer->w_gate : layer->w_up);
+    g.relu = relu ? 1 : 0; g.b_in = relu ? layer->b_in : nullptr;
     g.T = T; g.d = d; g.F = F; g.n_tm = (T + BM - 1) / BM; g.n_tn = (F + BN - 1) / BN;
     g.part = part; g.pool = pool; g.hbuf = hbuf;
     g.Fp = (int)align_up((size_t)F, 64);
@@ -692,6 +706,7 @@ hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, cha
     const int d = layer->d, F = layer->d_ff, es = (int)dtype_size(layer->dtype);
     DownParams q;
     q.h = h; q.wd = (const char *)layer->w_down; q.y = y; q.rowsq = rowsq;
+    q.bias = (layer->kind == CLADA_FFN_RELU && y) ? layer->b_out : nullptr;
     q.T = T; q.d = d; q.F = F; q.Fp = (int)align_up((size_t)F, 64);
     q.n_tm = (T + BM - 1) / BM; q.n_tn = (d + BN - 1) / BN;
     const int tot = q.n_tm * q.n_tn, grid = (tot + 7) / 8 * 8;
@@ -706,7 +721,6 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
 {
     if (!ctx) return CLADA_ERR_NULL;
     clada_status st = clada_check_layer(ctx, layer);
-    if (st == CLADA_OK) st = clada_require_swiglu(ctx, layer, "clada_prefix_stats");
     if (st != CLADA_OK) return st;
     if (!x || !out) return clada_fail(ctx, CLADA_ERR_NULL, "x or out is NULL");
     if (T < 1 || T > (1 << 20)) return clada_fail(ctx, CLADA_ERR_SHAPE, "T=%d outside [1,2^20]", T);

@@ -176,7 +176,7 @@ def test_batch1_and_generic_paths_agree(clada):
         layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
         xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
         outs = {}
-        for coop in (2, 1, 0):
+        for coop in (3, 2, 1, 0):                       # balanced, plain, automatic choice, generic kernels
             ctx.set_option("decode.b1", coop)
             y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, td, want_lists=True)
             yd = clada.dense_ffn_decode(ctx, layer, xd)
@@ -184,7 +184,7 @@ def test_batch1_and_generic_paths_agree(clada):
             outs[coop] = (to_np(y), idx.cpu().numpy(), cnt.cpu().numpy(), to_np(yd))
             _check_against_oracle(cfg, w, x, tau, y, idx.cpu().numpy(), cnt.cpu().numpy(), unpack_bits(bits, F),
                                   f"{cfg_name} coop={coop}")
-        for c in (1, 2):
+        for c in (1, 2, 3):
             assert np.array_equal(outs[c][1], outs[0][1]) and np.array_equal(outs[c][2], outs[0][2])
             assert_close_y(outs[c][0], outs[0][0], TOL_Y[cfg.dtype], "batch-1 path vs generic")
             assert_close_y(outs[c][3], outs[0][3], TOL_Y[cfg.dtype], "dense batch-1 path vs generic")
@@ -196,6 +196,7 @@ def test_balancing_any_own_first(clada, own_first):
     including very sparse and fully dense masks."""
     cfg, w, x = _case("c2", 8, 4096, 11008, 1)
     ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+    ctx.set_option("decode.b1", 3)
     ctx.set_option("decode.own_first", own_first)
     layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
     xd = to_dev(x, cfg.dtype)

@@ -37,13 +37,14 @@ CASES = [
 
 
 @pytest.mark.parametrize("cfg_name,d,F,B", CASES)
-@pytest.mark.parametrize("biases", [True, False])
-def test_relu_sparse_and_dense_parity(clada, cfg_name, d, F, B, biases):
+@pytest.mark.parametrize("biases,b1", [(True, 1), (False, 1), (True, 3)])
+def test_relu_sparse_and_dense_parity(clada, cfg_name, d, F, B, biases, b1):
     cfg = synth.CONFIGS[cfg_name]
     w = synth.relu_layer(cfg, 2, 3, d=d, d_ff=F)
     x = synth.decode_hidden(cfg, 2, 3, 0, B=B, d=d)
     wb = w if biases else (w[0], None, w[2], None)
     ctx = clada.Context(0, clada.workspace_bytes(d, F, B, 0, 0))
+    ctx.set_option("decode.b1", b1)                      # 3: the balanced batch-1 kernel wherever it can run
     layer = _layer(clada, cfg, w, biases)
     xd = to_dev(x, cfg.dtype)
     act = oracle.relu_decode(*wb, x)["act"]
@@ -111,7 +112,27 @@ def test_relu_static_list_decode(clada):
     assert_close_y(to_np(y), ref, TOL_Y[cfg.dtype], "relu list decode")
 
 
-def test_relu_rejected_by_prefill_calls(clada):
+@pytest.mark.parametrize("cfg_name,d,F,T", [("o27", 2560, 700, 300), ("o350", 1024, 4096, 512), ("c1", 96, 200, 130)])
+def test_relu_prefix_stats_parity_and_calibration(clada, cfg_name, d, F, T):
+    cfg = synth.CONFIGS[cfg_name]
+    w = synth.relu_layer(cfg, 5, 2, d=d, d_ff=F)
+    X = synth.prefix_hidden(cfg, 5, 2, T=T, d=d)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 0, T, 0))
+    layer = _layer(clada, cfg, w)
+    st = clada.prefix_stats(ctx, layer, to_dev(X, cfg.dtype))
+    torch.cuda.synchronize()
+    ref = oracle.relu_prefix_stats(*w, X)
+    np.testing.assert_allclose(to_np(st.abs_act_pool), ref["abs_act_pool"], rtol=1e-4, atol=2e-6)
+    for name in ("sum_abs_act", "sum_sq_act", "max_abs_act", "sum_sq_h", "A"):
+        np.testing.assert_allclose(to_np(getattr(st, name)), ref[name], rtol=3e-5, atol=1e-6, err_msg=name)
+    assert_close_y(to_np(st.y), ref["y"], TOL_Y[cfg.dtype], "relu prefill y")
+    tau = clada.threshold_calibrate(ctx, st.abs_act_pool, cfg.q if cfg_name != "c1" else 0.7)
+    torch.cuda.synchronize()
+    assert float(tau.item()) == oracle.calibrate(to_np(st.abs_act_pool), cfg.q if cfg_name != "c1" else 0.7)
+    assert float(tau.item()) > 0.0                      # above the ReLU's own zeros
+
+
+def test_relu_rejected_by_the_cett_calls(clada):
     from paper_2502_19078_amd.binding import CladaError
     cfg = synth.CONFIGS["o27"]
     w = synth.relu_layer(cfg, 1, 1, d=256, d_ff=128)
@@ -119,6 +140,6 @@ def test_relu_rejected_by_prefill_calls(clada):
     layer = _layer(clada, cfg, w)
     X = to_dev(synth.prefix_hidden(cfg, 1, 1, T=64, d=256), cfg.dtype)
     with pytest.raises(CladaError):
-        clada.prefix_stats(ctx, layer, X)
-    with pytest.raises(CladaError):
         clada.threshold_search_cett(ctx, layer, X)
+    with pytest.raises(CladaError):
+        clada.cett_eval(ctx, layer, X, 0.1)
