@@ -221,6 +221,18 @@ clada_status clada_static_mask_threshold(clada_ctx *ctx, const float *A, int32_t
 clada_status clada_static_mask_topk(clada_ctx *ctx, const float *score, int32_t d_ff, int32_t k,
                                     int32_t *active_idx, int32_t *n_active, void *hip_stream);
 
+/* Packed mask storage (the paper's limitations name the memory that stored masks
+ * take; its future work asks for a sparse encoding): a mask over d_ff neurons as
+ * ceil(d_ff/32) words, bit j%32 of word j/32 set iff neuron j is kept -- the layout
+ * of clada_sparse_ffn_decode's mask_bits, d_ff/8 bytes against 4 bytes per kept
+ * neuron for a list.  clada_mask_pack builds the words from an ascending list
+ * (active_idx, n_active[0]); clada_mask_unpack rebuilds the ascending list and its
+ * count (bits past d_ff are ignored).  Both exact; all arrays device. */
+clada_status clada_mask_pack(clada_ctx *ctx, const int32_t *active_idx, const int32_t *n_active,
+                             int32_t d_ff, uint32_t *mask_bits, void *hip_stream);
+clada_status clada_mask_unpack(clada_ctx *ctx, const uint32_t *mask_bits, int32_t d_ff,
+                               int32_t *active_idx, int32_t *n_active, void *hip_stream);
+
 /* Sparse SwiGLU FFN over a given neuron list (the sparse forward pass of the
  * algorithm "CLADA Inference" with a mask that does not depend on the token):
  *   y_b = sum_{j in active_idx[0..n_active[0])} SiLU(W_gate[j,:] . x_b) (W_up[j,:] . x_b) W_down[j,:]

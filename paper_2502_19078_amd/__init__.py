@@ -10,4 +10,5 @@ from .binding import (Context, Layer, PrefixStats, CladaError, cognitive_signals
                       dense_ffn_decode, lib_path, load_library, prefix_stats,
                       sparse_ffn_decode, threshold, threshold_calibrate,
                       threshold_search_cett, cett_eval, static_mask_threshold,
-                      static_mask_topk, static_ffn_decode, workspace_bytes)
+                      static_mask_topk, static_ffn_decode, mask_pack, mask_unpack,
+                      workspace_bytes)

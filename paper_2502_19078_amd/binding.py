@@ -78,10 +78,12 @@ def load_library() -> C.CDLL:
     lib.clada_static_mask_threshold.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     lib.clada_static_mask_topk.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.clada_static_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp, vp, vp]
+    lib.clada_mask_pack.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.clada_mask_unpack.argtypes = [vp, vp, i32, vp, vp, vp]
     lib.clada_diag_kernel_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times",
                  "clada_threshold_search_cett", "clada_cett_eval", "clada_static_mask_threshold",
-                 "clada_static_mask_topk", "clada_static_ffn_decode", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
+                 "clada_static_mask_topk", "clada_static_ffn_decode", "clada_mask_pack", "clada_mask_unpack", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
                  "clada_cognitive_signals", "clada_threshold", "clada_sparse_ffn_decode",
                  "clada_dense_ffn_decode"):
         getattr(lib, name).restype = C.c_int
@@ -296,6 +298,24 @@ def static_mask_topk(ctx: Context, score: torch.Tensor, k: int):
     n = torch.empty(1, dtype=torch.int32, device=score.device)
     ctx.check(ctx._lib.clada_static_mask_topk(ctx._h, _ptr(score), score.numel(), int(k), _ptr(idx), _ptr(n),
                                               _stream(score)))
+    return idx, n
+
+
+def mask_pack(ctx: Context, active_idx: torch.Tensor, n_active: torch.Tensor, d_ff: int) -> torch.Tensor:
+    """Ascending list -> packed bit mask [ceil(d_ff/32)] int32."""
+    assert active_idx.is_cuda and active_idx.dtype == torch.int32 and n_active.dtype == torch.int32
+    bits = torch.empty((d_ff + 31) // 32, dtype=torch.int32, device=active_idx.device)
+    ctx.check(ctx._lib.clada_mask_pack(ctx._h, _ptr(active_idx), _ptr(n_active), int(d_ff), _ptr(bits),
+                                       _stream(active_idx)))
+    return bits
+
+
+def mask_unpack(ctx: Context, mask_bits: torch.Tensor, d_ff: int):
+    """Packed bit mask -> (active_idx [d_ff] int32, n_active [1] int32)."""
+    assert mask_bits.is_cuda and mask_bits.dtype == torch.int32 and mask_bits.numel() >= (d_ff + 31) // 32
+    idx = torch.empty(d_ff, dtype=torch.int32, device=mask_bits.device)
+    n = torch.empty(1, dtype=torch.int32, device=mask_bits.device)
+    ctx.check(ctx._lib.clada_mask_unpack(ctx._h, _ptr(mask_bits), int(d_ff), _ptr(idx), _ptr(n), _stream(mask_bits)))
     return idx, n
 
 

@@ -237,3 +237,44 @@ def test_static_chain_graph_replay_matches_eager(clada):
         y2 = clada.static_ffn_decode(ctx, layer, xd, idx, n)
         torch.cuda.synchronize()
         assert torch.equal(y2, y_e)
+
+
+@pytest.mark.parametrize("F", [1, 31, 32, 33, 1000, 11008, 262144])
+def test_mask_pack_unpack_bit_exact(clada, F):
+    """Packed storage: the words are numpy's little-endian bit packing of the mask, the round trip is
+    the identity, and the dynamic call's own mask_bits unpack to its own list."""
+    rng = np.random.default_rng(F + 7)
+    keep = rng.random(F) < 0.55
+    ctx = _ctx(clada, 64, min(F, 4096), 1)
+    ii = np.flatnonzero(keep).astype(np.int32)
+    idx = torch.full((F,), -1, dtype=torch.int32, device=DEV)
+    idx[: ii.size] = torch.from_numpy(ii).to(DEV)
+    n = torch.tensor([ii.size], dtype=torch.int32, device=DEV)
+    bits = clada.mask_pack(ctx, idx, n, F)
+    torch.cuda.synchronize()
+    words = (F + 31) // 32
+    want = np.packbits(np.pad(keep, (0, words * 32 - F)), bitorder="little").view(np.uint32)
+    assert np.array_equal(bits.cpu().numpy().view(np.uint32), want)
+    idx2, n2 = clada.mask_unpack(ctx, bits, F)
+    torch.cuda.synchronize()
+    assert int(n2.item()) == ii.size and np.array_equal(idx2.cpu().numpy()[: ii.size], ii)
+    # garbage above d_ff in the last word is ignored
+    if F % 32:
+        bits[-1] |= torch.tensor(-1 << (F % 32), dtype=torch.int32, device=DEV)
+        idx3, n3 = clada.mask_unpack(ctx, bits, F)
+        assert int(n3.item()) == ii.size and np.array_equal(idx3.cpu().numpy()[: ii.size], ii)
+
+
+def test_dynamic_mask_bits_unpack_to_the_dynamic_list(clada):
+    cfg = synth.CONFIGS["c2"]
+    d, F = 1024, 3000
+    w = synth.layer_weights(cfg, 2, 0, d=d, d_ff=F)
+    x = synth.decode_hidden(cfg, 2, 0, 0, B=1, d=d)
+    ctx = _ctx(clada, d, F, 1)
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, to_dev(x, cfg.dtype),
+                                                torch.tensor([0.25], dtype=torch.float32, device=DEV), want_lists=True)
+    idx2, n2 = clada.mask_unpack(ctx, bits[0].contiguous(), F)
+    torch.cuda.synchronize()
+    k = int(cnt[0].item())
+    assert int(n2.item()) == k and torch.equal(idx2[:k], idx[:k])
