@@ -33,42 +33,55 @@ __global__ void __launch_bounds__(256) k_calib_init(CalibState *st, unsigned lon
     }
 }
 
-// The magnitudes crowd into a few dozen bins (pass 0 sees mostly exponent bits), so every wave
-// keeps a private LDS histogram: same-address atomic traffic drops by the number of waves.
-constexpr int HIST_COPIES = 4;
-__global__ void __launch_bounds__(256)
+// The magnitudes crowd into a few dozen bins (pass 0 sees mostly exponent bits), and LDS atomics
+// of a wave to one address are served one lane at a time.  The workgroup therefore keeps 16
+// histogram copies, chosen by lane % 16 (at most four lanes of a wave share an address), each
+// shifted by one bank so that the copies of one bin do not collide either; 128 KiB of LDS, one
+// workgroup of 1024 threads per compute unit, four 16-byte loads in flight per thread.
+constexpr int HIST_COPIES = 16;
+constexpr int HIST_PITCH = NBINS + 1;
+constexpr int CALIB_THREADS = 1024;
+__global__ void __launch_bounds__(CALIB_THREADS)
 k_calib_hist(const float *__restrict__ pool, long long n, CalibState *st, int pass)
 {
-    __shared__ unsigned int s_hist[HIST_COPIES][NBINS];
-    for (int i = threadIdx.x; i < HIST_COPIES * NBINS; i += blockDim.x) (&s_hist[0][0])[i] = 0u;
+    __shared__ unsigned int s_hist[HIST_COPIES * HIST_PITCH];
+    for (int i = threadIdx.x; i < HIST_COPIES * HIST_PITCH; i += CALIB_THREADS) s_hist[i] = 0u;
     __syncthreads();
-    unsigned int *mine = s_hist[(threadIdx.x >> 6) % HIST_COPIES];
+    unsigned int *mine = s_hist + (threadIdx.x & (HIST_COPIES - 1)) * HIST_PITCH;
     const unsigned int prefix = st->prefix, pmask = st->prefix_mask;
     const int shift = c_shift[pass];
     const unsigned int dmask = (1u << c_bits[pass]) - 1u;
     const long long n4 = n >> 2;
     const u32x4 *p4 = reinterpret_cast<const u32x4 *>(pool);
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        const u32x4 v = __builtin_nontemporal_load(p4 + i);
+    const long long stride = (long long)gridDim.x * CALIB_THREADS;
+    auto count = [&](const u32x4 v) {
         const unsigned int u[4] = {v.x & 0x7fffffffu, v.y & 0x7fffffffu, v.z & 0x7fffffffu, v.w & 0x7fffffffu};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             if ((u[e] & pmask) == prefix) atomicAdd(&mine[(u[e] >> shift) & dmask], 1u);
+    };
+    long long i = (long long)blockIdx.x * CALIB_THREADS + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        u32x4 v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = __builtin_nontemporal_load(p4 + i + r * stride);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) count(v[r]);
     }
+    for (; i < n4; i += stride) count(__builtin_nontemporal_load(p4 + i));
     if (blockIdx.x == 0) {
         const unsigned int *p1 = reinterpret_cast<const unsigned int *>(pool);
-        for (long long i = (n4 << 2) + threadIdx.x; i < n; i += blockDim.x) {
-            const unsigned int u = p1[i] & 0x7fffffffu;
+        for (long long t = (n4 << 2) + threadIdx.x; t < n; t += CALIB_THREADS) {
+            const unsigned int u = p1[t] & 0x7fffffffu;
             if ((u & pmask) == prefix) atomicAdd(&mine[(u >> shift) & dmask], 1u);
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < NBINS; i += blockDim.x) {
+    for (int b = threadIdx.x; b < NBINS; b += CALIB_THREADS) {
         unsigned int c = 0u;
 #pragma unroll
-        for (int h = 0; h < HIST_COPIES; ++h) c += s_hist[h][i];
-        if (c) atomicAdd(&st->hist[pass][i], (unsigned long long)c);
+        for (int h = 0; h < HIST_COPIES; ++h) c += s_hist[h * HIST_PITCH + b];
+        if (c) atomicAdd(&st->hist[pass][b], (unsigned long long)c);
     }
 }
 
@@ -132,11 +145,11 @@ extern "C" clada_status clada_threshold_calibrate(clada_ctx *ctx, const float *a
     hipStream_t stream = (hipStream_t)hip_stream;
     hipLaunchKernelGGL(k_calib_init, dim3((NPASS * NBINS + 255) / 256), dim3(256), 0, stream, st,
                        (unsigned long long)k);
-    long long want = ((n >> 2) + 255) / 256;
-    const int cap = ctx->num_cu * 8;
+    long long want = ((n >> 2) + 4 * CALIB_THREADS - 1) / (4 * CALIB_THREADS);
+    const int cap = ctx->num_cu;
     const int blocks = (int)(want < 1 ? 1 : (want > cap ? cap : want));
     for (int pass = 0; pass < NPASS; ++pass) {
-        hipLaunchKernelGGL(k_calib_hist, dim3(blocks), dim3(256), 0, stream, abs_act_pool, (long long)n, st, pass);
+        hipLaunchKernelGGL(k_calib_hist, dim3(blocks), dim3(CALIB_THREADS), 0, stream, abs_act_pool, (long long)n, st, pass);
         hipLaunchKernelGGL(k_calib_select, dim3(1), dim3(256), 0, stream, st, pass, tau_base_out);
     }
     CLADA_CHECK_HIP(ctx, hipGetLastError());
