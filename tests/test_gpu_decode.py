@@ -296,3 +296,31 @@ def test_kernel_event_timing_does_not_change_results(clada, B):
     assert 0.0 < main_us < 1e5 and 0.0 < fin_us < 1e5
     with pytest.raises(binding.CladaError):
         binding.diag_kernel_times(ctx)
+
+
+@pytest.mark.parametrize("cfg_name,d,F,B", [
+    ("c2", 256, 300, 64),        # the largest batch the ABI takes
+    ("c2", 1024, 520, 17),       # one past the matrix-core path's 16 tokens: generic kernels
+    ("c2", 8192, 300, 1),        # the longest bf16 row (16 KiB)
+    ("c1", 4096, 260, 2),        # the longest fp32 row (16 KiB)
+    ("c2", 4096, 255, 1),        # fewer neurons than workgroups
+    ("c2", 4096, 1, 1),          # a single neuron
+])
+def test_limits_of_batch_width_and_neuron_count(clada, cfg_name, d, F, B):
+    cfg, w, x = _case(cfg_name, 11, d, F, B)
+    tau = _tau_for(w, x, 0.45)
+    _, _, _, y, idx, cnt, mask = _run_sparse(clada, cfg, w, x, tau)
+    _check_against_oracle(cfg, w, x, tau, y, idx, cnt, mask, f"{cfg_name} d={d} F={F} B={B}")
+
+
+def test_sizes_beyond_the_limits_are_rejected(clada):
+    from paper_2502_19078_amd.binding import CladaError
+    cfg, w, x = _case("c2", 12, 256, 64, 1)
+    ctx = clada.Context(0, clada.workspace_bytes(256, 64, 64, 0, 0))
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xb = torch.zeros(65, 256, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(CladaError):
+        clada.sparse_ffn_decode(ctx, layer, xb, torch.zeros(65, device=DEV))
+    small = clada.Context(0, 1024)                       # workspace too small for the call
+    with pytest.raises(CladaError):
+        clada.sparse_ffn_decode(small, layer, to_dev(x, cfg.dtype), torch.zeros(1, device=DEV))
