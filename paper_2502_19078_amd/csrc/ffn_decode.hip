@@ -307,46 +307,68 @@ __global__ void __launch_bounds__(1024)
 k_ffn_lists(const unsigned char *__restrict__ keep, int B, int F, int32_t *__restrict__ active_idx,
             int32_t *__restrict__ n_active, uint32_t *__restrict__ mask_bits)
 {
-    __shared__ int s_wave_cnt[16];
+    // Thread t owns the 32-flag words [t*wpt, (t+1)*wpt): it packs each token's flags into mask
+    // words, ORs them into union words, and after one workgroup-wide exclusive scan of the union
+    // popcounts writes its neurons' indices in ascending order.
+    __shared__ int s_wave[16];
     __shared__ int s_tok_cnt[CLADA_MAX_BATCH];
-    __shared__ int s_base;
+    constexpr int MAXW = 8;                                   // words per thread: covers d_ff <= 262144
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int words = (F + 31) / 32;
+    const int wpt = (words + 1023) / 1024;
+    const int w0 = min(words, tid * wpt), w1 = min(words, w0 + wpt);
     if (tid < CLADA_MAX_BATCH) s_tok_cnt[tid] = 0;
-    if (tid == 0) s_base = 0;
     __syncthreads();
-    for (int base = 0; base < F; base += 1024) {
-        const int j = base + tid;
-        bool any = false;
-        for (int b = 0; b < B; ++b) {
-            const bool k = j < F && keep[(size_t)b * F + j] != 0;
-            any |= k;
-            const unsigned long long bal = __ballot(k);
-            if (lane == 0) {
-                if (bal) atomicAdd(&s_tok_cnt[b], __popcll(bal));
-                if (mask_bits) {
-                    const int w0 = (base + wave * 64) >> 5;
-                    if (w0 < words) mask_bits[(size_t)b * words + w0] = (uint32_t)bal;
-                    if (w0 + 1 < words) mask_bits[(size_t)b * words + w0 + 1] = (uint32_t)(bal >> 32);
-                }
+    unsigned int uni[MAXW];
+#pragma unroll
+    for (int i = 0; i < MAXW; ++i) uni[i] = 0u;
+    for (int b = 0; b < B; ++b) {
+        const unsigned char *row = keep + (size_t)b * F;
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < MAXW; ++i) {
+            const int w = w0 + i;
+            if (w < w1) {
+                unsigned int bits = 0u;
+                const int j0 = 32 * w, nj = min(32, F - j0);
+                for (int e = 0; e < nj; ++e) bits |= (row[j0 + e] != 0 ? 1u : 0u) << e;
+                if (mask_bits) mask_bits[(size_t)b * words + w] = bits;
+                uni[i] |= bits;
+                cnt += __popc(bits);
             }
         }
-        const unsigned long long ubal = __ballot(any);
-        if (lane == 0) s_wave_cnt[wave] = __popcll(ubal);
-        __syncthreads();
-        int off = s_base;
-        for (int w = 0; w < wave; ++w) off += s_wave_cnt[w];
-        if (any && active_idx) active_idx[off + __popcll(ubal & ((1ull << lane) - 1ull))] = j;
-        __syncthreads();
-        if (tid == 0) {
-            int t = s_base;
-            for (int w = 0; w < 16; ++w) t += s_wave_cnt[w];
-            s_base = t;
+        if (cnt) atomicAdd(&s_tok_cnt[b], cnt);
+    }
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < MAXW; ++i) c += __popc(uni[i]);
+    int inc = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    int base = 0, total = 0;
+    for (int w = 0; w < 16; ++w) {
+        const int v = s_wave[w];
+        if (w < wave) base += v;
+        total += v;
+    }
+    if (active_idx) {
+        int pos = base + inc - c;
+#pragma unroll
+        for (int i = 0; i < MAXW; ++i) {
+            unsigned int v = uni[i];
+            while (v) {
+                active_idx[pos++] = 32 * (w0 + i) + (__ffs(v) - 1);
+                v &= v - 1u;
+            }
         }
-        __syncthreads();
     }
     if (n_active) {
-        if (tid == 0) n_active[0] = s_base;
+        if (tid == 0) n_active[0] = total;
         if (tid < B) n_active[1 + tid] = s_tok_cnt[tid];
     }
 }
