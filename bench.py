@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--shared-frac", type=float, default=0.0,
                     help="c in [0,1]: decode tokens of a batch share a component, x_b = sqrt(c) x_shared + sqrt(1-c) x_b'")
     ap.add_argument("--temperature", type=float, default=1.0, help="divide the Zipf logits by this (peaked < 1 < flat)")
+    ap.add_argument("--tau-s", type=float, default=None, help="fix the surprisal threshold (default: median of the run's own stream)")
+    ap.add_argument("--tau-h", type=float, default=None, help="fix the entropy threshold (default: median of the run's own stream)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run only a short fixed call sequence (for rocprofv3 --pmc counter runs) and exit")
     args = ap.parse_args()
@@ -162,8 +164,9 @@ def main():
         a, b = clada.cognitive_signals(ctx, z_all[s], tok_all[s])
         s_all.append(a)
         h_all.append(b)
-    tau_s = float(torch.stack(s_all).median().item())
-    tau_H = float(torch.stack(h_all).median().item())
+    tau_s = float(torch.stack(s_all).median().item()) if args.tau_s is None else args.tau_s
+    tau_H = float(torch.stack(h_all).median().item()) if args.tau_h is None else args.tau_h
+    mean_s, mean_H = float(torch.stack(s_all).mean().item()), float(torch.stack(h_all).mean().item())
 
     # ---------------------------------------------------------------- one decode step
     x_cur = torch.empty(L, B, d, dtype=tdtype, device=dev)
@@ -332,6 +335,7 @@ def main():
                    "weights": f"N(0, std {cfg.w_std:g})", "hidden": "N(0,1)",
                    "lambda": 0.80, "gamma": 0.12, "tau_s": round(tau_s, 4), "tau_H": round(tau_H, 4),
                    "shared_frac": args.shared_frac, "temperature": args.temperature,
+                   "mean_surprisal": round(mean_s, 4), "mean_entropy": round(mean_H, 4),
                    "graph": not args.no_graph, "options": args.option},
         "sparsity_per_token": round(float(rho_token), 4),
         "sparsity_union": round(float(rho_union), 4),
