@@ -73,10 +73,21 @@ const char *clada_last_error(const clada_ctx *ctx);
  * workgroup keeps for itself before the balanced hand-over; 0 = default),
  * "decode.wgs_per_cu" (1 or 2 workgroups per compute unit for the generic kernel),
  * "decode.batched" (1 = matrix-core kernels for bf16 batches 2..16 [default], 0 = the
- * generic kernels), "diag.kernel_events" (1 = every decode call also records HIP
- * events around its kernels for clada_diag_kernel_times; default 0).
+ * generic kernels), "decode.spin_limit" (how often a balanced batch-1 kernel polls
+ * for the other workgroups' masks before it gives up; default 2^21, about two
+ * seconds; see clada_device_fault), "diag.kernel_events" (1 = every decode call also
+ * records HIP events around its kernels for clada_diag_kernel_times; default 0).
  * Unknown names or out-of-range values give CLADA_ERR_VALUE and change nothing. */
 clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);
+
+/* The balanced batch-1 decode kernel waits, inside the kernel, for the keep masks of
+ * all its workgroups.  They can only stay away while something else holds the
+ * compute units they need (two balanced calls overlapping from different streams
+ * or processes: use one stream at a time, or option "decode.b1" = 2).  The wait is
+ * bounded: past the limit the kernel gives up, the call's output and every later
+ * output of the context is NaN, and this call (which synchronises the device)
+ * reports *fault_out = 1.  A context that has faulted must be destroyed. */
+clada_status clada_device_fault(clada_ctx *ctx, int32_t *fault_out);
 
 /* Upper bound of the workspace any call needs for these sizes.  Pass 0 for a
  * size whose call will not be used (T for prefix_stats/calibrate/the CETT calls, V for

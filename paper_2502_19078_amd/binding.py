@@ -80,8 +80,9 @@ def load_library() -> C.CDLL:
     lib.clada_static_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp, vp, vp]
     lib.clada_mask_pack.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.clada_mask_unpack.argtypes = [vp, vp, i32, vp, vp, vp]
+    lib.clada_device_fault.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.clada_diag_kernel_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
-    for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times",
+    for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times", "clada_device_fault",
                  "clada_threshold_search_cett", "clada_cett_eval", "clada_static_mask_threshold",
                  "clada_static_mask_topk", "clada_static_ffn_decode", "clada_mask_pack", "clada_mask_unpack", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
                  "clada_cognitive_signals", "clada_threshold", "clada_sparse_ffn_decode",
@@ -133,6 +134,12 @@ class Context:
     def check(self, st: int):
         if st != 0:
             raise CladaError(st, self._lib.clada_last_error(self._h).decode())
+
+    def device_fault(self) -> bool:
+        """True once a balanced decode kernel of this context has given up its bounded wait."""
+        f = C.c_int32()
+        self.check(self._lib.clada_device_fault(self._h, C.byref(f)))
+        return f.value != 0
 
     def set_option(self, name: str, value: int):
         self.check(self._lib.clada_set_option(self._h, name.encode(), int(value)))

@@ -69,6 +69,7 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->opt_decode_b1 = 1;
     ctx->opt_decode_batched = 1;
     ctx->opt_decode_own_first = 0;
+    ctx->opt_decode_spin_limit = 1 << 21;
     ctx->opt_diag_events = 0;
     ctx->ev[0] = ctx->ev[1] = ctx->ev[2] = ctx->ev[3] = nullptr;
     ctx->err[0] = 0;
@@ -142,6 +143,11 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
         ctx->opt_decode_own_first = value;
         return CLADA_OK;
     }
+    if (!strcmp(name, "decode.spin_limit")) {
+        if (value < 0) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.spin_limit=%d is negative", value);
+        ctx->opt_decode_spin_limit = value;
+        return CLADA_OK;
+    }
     if (!strcmp(name, "diag.kernel_events")) {
         if (value < 0 || value > 1) return clada_fail(ctx, CLADA_ERR_VALUE, "diag.kernel_events=%d outside [0,1]", value);
         if (value && !ctx->ws) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "diag.kernel_events needs a context with a workspace");
@@ -151,6 +157,15 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
         return CLADA_OK;
     }
     return clada_fail(ctx, CLADA_ERR_VALUE, "unknown option '%s'", name);
+}
+
+clada_status clada_device_fault(clada_ctx *ctx, int32_t *fault_out)
+{
+    if (!ctx || !fault_out) return clada_fail(ctx, CLADA_ERR_NULL, "ctx or fault_out is NULL");
+    if (!ctx->ws) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "the context has no workspace (no device)");
+    CLADA_CHECK_HIP(ctx, hipDeviceSynchronize());
+    CLADA_CHECK_HIP(ctx, hipMemcpy(fault_out, ctx->ws + COOP_FAULT, sizeof(int32_t), hipMemcpyDeviceToHost));
+    return CLADA_OK;
 }
 
 clada_status clada_diag_kernel_times(clada_ctx *ctx, float *main_us, float *finalize_us)

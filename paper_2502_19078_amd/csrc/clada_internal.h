@@ -16,6 +16,7 @@ struct clada_ctx {
     int opt_decode_b1;           // batch-1 split-d kernel: 0 off (generic kernels), 1 balancing where it pays, 2 never, 3 always
     int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
     int opt_decode_batched;      // 1: MFMA path for 2 <= B <= 16 (bf16), 0: generic kernels
+    int opt_decode_spin_limit;   // polls a balanced batch-1 kernel makes before it gives up (see clada.h)
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)
     hipEvent_t ev[4];            // start/stop of the main decode kernel, start/stop of the final reduction
     char err[512];
@@ -30,7 +31,7 @@ struct clada_ctx {
 enum { CTR_SIGNALS = 0, CTR_DECODE = 64, CTR_PREFIX = 128, CTR_CALIB = 192 };  // int32 slots
 // Control words of the cooperative decode kernel inside the header (byte offsets).
 #define COOP_MAX_WGS 256
-enum { COOP_EPOCH = 1024, COOP_REC = 4096,
+enum { COOP_EPOCH = 1024, COOP_FAULT = 1088, COOP_REC = 4096,
        COOP_APUB = 8192 /* 256*64 floats = 64 KiB */ };
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

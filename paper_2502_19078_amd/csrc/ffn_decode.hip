@@ -237,7 +237,7 @@ k_ffn_decode(const DecodeParams p)
 template <int ES>
 __global__ void __launch_bounds__(256)
 k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict__ y, unsigned int *epoch,
-               const float *__restrict__ bias)
+               const float *__restrict__ bias, const int *__restrict__ fault)
 {
     if (epoch && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *epoch += 1u;   // cooperative call counter
     __shared__ float4 s_sum[32][8];
@@ -273,6 +273,7 @@ k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict
         __syncthreads();
     }
     if (sl == 0 && col < d) {
+        if (fault && *fault) s.x = s.y = s.z = s.w = __int_as_float(0x7fc00000);   // a balanced call gave up: no silent wrong sums
         if (bias) {                                     // output bias of the non-gated family
             const float4 bv = *reinterpret_cast<const float4 *>(bias + col);
             s.x += bv.x; s.y += bv.y; s.z += bv.z; s.w += bv.w;
@@ -289,16 +290,17 @@ k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict
 }
 
 void launch_finalize(int es, const float *partial, int P, int B, int d, char *y, unsigned int *epoch, hipStream_t stream,
-                     hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, const float *bias = nullptr)
+                     hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, const float *bias = nullptr,
+                     const int *fault = nullptr)
 {
     const dim3 grid((d + 31) / 32, B);
     if (ev_start) {
-        if (es == 4) hipExtLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias);
-        else         hipExtLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias);
+        if (es == 4) hipExtLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias, fault);
+        else         hipExtLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias, fault);
         return;
     }
-    if (es == 4) hipLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, partial, P, d, y, epoch, bias);
-    else         hipLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, partial, P, d, y, epoch, bias);
+    if (es == 4) hipLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, partial, P, d, y, epoch, bias, fault);
+    else         hipLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, partial, P, d, y, epoch, bias, fault);
 }
 
 // Ascending union index list, counts and per-token bit masks from the keep
@@ -421,6 +423,8 @@ struct B1Params {
     const unsigned int *epoch;  // device-side counter of balanced calls, advanced by k_ffn_finalize
                                 // (read at kernel start, so graph replays stay correct)
     const float *b_in;          // RELU: input bias [F] or nullptr
+    int *fault;                 // set to 1 when a balanced call gives up waiting for the other workgroups
+    int max_spins;              // polls of the other workgroups' records before giving up
     int d, F, K0;
 };
 
@@ -616,8 +620,13 @@ k_ffn_decode_b1(const B1Params p)
             else if (nup == 2) up_rows(std::integral_constant<int, 2>{}, s_list, nullptr, true, first, NW - 1, s_h[0]);
         } else {
             // wave 0: read all P masks (lane handles records 4*lane .. 4*lane+3), no barriers
+            // The wait is bounded: if the other workgroups' records do not arrive (they can only be
+            // missing while something else holds the compute units they need, e.g. a second balanced
+            // call overlapping from another stream), this workgroup gives up its share, raises the
+            // context's fault flag, and the final reduction turns the output into NaN.
             unsigned long long m[4];
-            for (;;) {
+            bool gave_up = false;
+            for (int spins = 0;; ++spins) {
                 bool ok = true;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -627,8 +636,15 @@ k_ffn_decode_b1(const B1Params p)
 #pragma unroll
                 for (int u = 0; u < 4; ++u) ok = ok && ((m[u] & (0xffull << 56)) == tag);
                 if (__ballot(ok) == ~0ull) break;
+                if (spins >= p.max_spins) { gave_up = true; break; }
                 __builtin_amdgcn_s_sleep(8);
             }
+            if (gave_up) {
+                if (lane == 0) {
+                    s_n2 = 0;
+                    __hip_atomic_store(p.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            } else {
             int kq[4], oq[4], sq[4], ksum = 0;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -677,6 +693,7 @@ k_ffn_decode_b1(const B1Params p)
                 }
             }
             if (lane == 0) s_n2 = hi - lo;
+            }
         }
         B1_STAMP(7);
         __syncthreads();
@@ -859,6 +876,8 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             unsigned int *epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
             b.epoch = epoch;
             b.b_in = p.b_in;
+            b.fault = reinterpret_cast<int *>(ctx->ws + COOP_FAULT);
+            b.max_spins = ctx->opt_decode_spin_limit;
             b.d = d; b.F = F;
             b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
             // Balancing pays when the kept-row phase is long enough to hide the mask exchange behind the
@@ -888,7 +907,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             }
             CLADA_CHECK_HIP(ctx, eb);
             launch_finalize(es, p.partial, Pb, 1, d, (char *)y, balance ? epoch : nullptr, stream,
-                            ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3], b_out);
+                            ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3], b_out, balance ? b.fault : nullptr);
             CLADA_CHECK_HIP(ctx, hipGetLastError());
             if (lists) {
                 hipLaunchKernelGGL(k_ffn_lists, dim3(1), dim3(1024), 0, stream, p.keep, B, F, active_idx, n_active, mask_bits);

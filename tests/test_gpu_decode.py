@@ -324,3 +324,26 @@ def test_sizes_beyond_the_limits_are_rejected(clada):
     small = clada.Context(0, 1024)                       # workspace too small for the call
     with pytest.raises(CladaError):
         clada.sparse_ffn_decode(small, layer, to_dev(x, cfg.dtype), torch.zeros(1, device=DEV))
+
+
+def test_bounded_wait_of_the_balanced_kernel_gives_up_cleanly(clada):
+    """The balanced kernel polls for the other workgroups' masks a bounded number of times.  With the
+    limit forced to zero from the host nearly every workgroup gives up at once: every kernel still runs
+    to its end, the output is NaN rather than a silent partial sum, and the context reports the fault."""
+    cfg, w, x = _case("c2", 13, 4096, 11008, 1)
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd = to_dev(x, cfg.dtype)
+    td = torch.from_numpy(_tau_for(w, x, 0.45)).to(DEV)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+    ctx.set_option("decode.b1", 3)
+    good = clada.sparse_ffn_decode(ctx, layer, xd, td).clone()
+    assert not ctx.device_fault() and torch.isfinite(good.float()).all()
+    ctx.set_option("decode.spin_limit", 0)
+    bad = clada.sparse_ffn_decode(ctx, layer, xd, td)
+    torch.cuda.synchronize()
+    assert ctx.device_fault() and torch.isnan(bad.float()).all()
+    fresh = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))      # a new context is clean
+    fresh.set_option("decode.b1", 3)
+    again = clada.sparse_ffn_decode(fresh, layer, xd, td)
+    torch.cuda.synchronize()
+    assert not fresh.device_fault() and torch.equal(again, good)
