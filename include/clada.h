@@ -72,7 +72,8 @@ const char *clada_last_error(const clada_ctx *ctx);
  * the launch allows it, 0 = the generic kernels), "decode.own_first" (1..14, neurons a
  * workgroup keeps for itself before the balanced hand-over; 0 = default),
  * "decode.wgs_per_cu" (1 or 2 workgroups per compute unit for the generic kernel),
- * "decode.batched" (1 = matrix-core kernels for bf16 batches 2..16 [default], 0 = the
+ * "decode.batched" (1 = matrix-core kernels for bf16 batches of 2 and more, 16 tokens
+ * per pass [default], 0 = the
  * generic kernels), "decode.spin_limit" (how often a balanced batch-1 kernel polls
  * for the other workgroups' masks before it gives up; default 2^21, about two
  * seconds; see clada_device_fault), "diag.kernel_events" (1 = every decode call also

@@ -916,15 +916,31 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             return CLADA_OK;
         }
     }
-    // ---- batched MFMA path (2 <= B <= 16, bf16, supported widths)
+    // ---- batched MFMA path (bf16, supported widths): up to 16 tokens per pass; larger batches run
+    // as ceil(B/16) passes of near-equal size, each re-reading the weights of its own union
     if (B >= 2 && ctx->opt_decode_batched && !relu) {
         unsigned char *keep_region = reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256));
         char *scratch = reinterpret_cast<char *>(keep_region) + align_up((size_t)B * F, 256);
-        bool ran = false;
+        const int n_groups = (B + 15) / 16, per_group = (B + n_groups - 1) / n_groups;     // per_group >= 2 whenever B >= 2
+        bool ran_all = false;
         if (ctx->opt_diag_events) CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[0], stream));
-        st = clada_decode_batched(ctx, layer, x, B, tau, y, p.keep, p.partial, scratch, dense, stream, &ran);
-        if (st != CLADA_OK) return st;
-        if (ran) {
+        for (int g0 = 0; g0 < B; g0 += per_group) {
+            const int Bg = (B - g0 < per_group) ? B - g0 : per_group;
+            bool ran = false;
+            if (Bg >= 2)
+                st = clada_decode_batched(ctx, layer, (const char *)x + (size_t)g0 * d * es, Bg, tau ? tau + g0 : nullptr,
+                                          (char *)y + (size_t)g0 * d * es, p.keep ? p.keep + (size_t)g0 * F : nullptr,
+                                          p.partial, scratch, dense, stream, &ran);
+            if (st != CLADA_OK) return st;
+            if (!ran) {
+                // not eligible (decided by dtype and shape before anything is launched, so by the first
+                // group) or a one-token remainder: the generic kernels below redo the whole batch
+                ran_all = false;
+                break;
+            }
+            ran_all = true;
+        }
+        if (ran_all) {
             if (ctx->opt_diag_events) {     // the batched path's final reduction is not timed apart
                 CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[1], stream));
                 CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev[2], stream));

@@ -300,7 +300,9 @@ def test_kernel_event_timing_does_not_change_results(clada, B):
 
 @pytest.mark.parametrize("cfg_name,d,F,B", [
     ("c2", 256, 300, 64),        # the largest batch the ABI takes
-    ("c2", 1024, 520, 17),       # one past the matrix-core path's 16 tokens: generic kernels
+    ("c2", 1024, 520, 17),       # one past 16 tokens: two passes (9 + 8) of the matrix-core path
+    ("c2", 2048, 700, 40),       # three passes (14 + 14 + 12)
+    ("c2", 1024, 333, 64),       # the largest batch on the matrix-core path: four passes of 16
     ("c2", 8192, 300, 1),        # the longest bf16 row (16 KiB)
     ("c1", 4096, 260, 2),        # the longest fp32 row (16 KiB)
     ("c2", 4096, 255, 1),        # fewer neurons than workgroups
