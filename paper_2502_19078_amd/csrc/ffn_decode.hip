@@ -627,6 +627,7 @@ k_ffn_decode_b1(const B1Params p)
             unsigned long long m[4];
             bool gave_up = false;
             for (int spins = 0;; ++spins) {
+                if (spins >= p.max_spins) { gave_up = true; break; }
                 bool ok = true;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -636,7 +637,6 @@ k_ffn_decode_b1(const B1Params p)
 #pragma unroll
                 for (int u = 0; u < 4; ++u) ok = ok && ((m[u] & (0xffull << 56)) == tag);
                 if (__ballot(ok) == ~0ull) break;
-                if (spins >= p.max_spins) { gave_up = true; break; }
                 __builtin_amdgcn_s_sleep(8);
             }
             if (gave_up) {

@@ -82,13 +82,12 @@ k_bat_gateup(const BatParams p)
     // Neurons are dealt out in contiguous runs of whole octets: workgroup q owns octets
     // [q no / P, (q+1) no / P), at most 64 neurons, so every workgroup streams the same number of
     // rows to within 8 (16-neuron granularity would leave an eighth of the chip idle at the end).
+    // A run longer than 64 neurons (d_ff above 16384) is worked off in rounds of 64: one ballot
+    // compacts a round's kept neurons.
     const int no = (F + 7) / 8;
-    const int j_lo = 8 * (int)((long long)blk * no / P);
-    const int j_hi = min(8 * (int)((long long)(blk + 1) * no / P), F);
-    const int nown = j_hi - j_lo;                           // <= 64
-    const int ni = (nown + 15) / 16;                        // <= MAX_TILES
+    const int j_lo_all = 8 * (int)((long long)blk * no / P);
+    const int j_hi_all = min(8 * (int)((long long)(blk + 1) * no / P), F);
 
-    if (tid < MAX_TILES * 16) s_km[tid] = 0;
     // this wave's slice of x as A-fragments: lane = (token n, k-group q)
     u32x4 xa[KSTEPS];
 #pragma unroll
@@ -175,6 +174,13 @@ k_bat_gateup(const BatParams p)
         for (int w = 0; w < 8; ++w) s += s_part[buf][w][e];
         return s;
     };
+    for (int j_lo = j_lo_all; j_lo < j_hi_all; j_lo += 16 * MAX_TILES) {
+    const int j_hi = min(j_lo + 16 * MAX_TILES, j_hi_all);
+    const int nown = j_hi - j_lo;                           // <= 64
+    const int ni = (nown + 15) / 16;                        // <= MAX_TILES
+    __syncthreads();                                        // the previous round is done with s_km, s_a, s_ul
+    if (tid < MAX_TILES * 16) s_km[tid] = 0;
+    __syncthreads();
     auto gate_row = [&](int i, int rr) { return 16 * i + rr < nown ? j_lo + 16 * i + rr : -1; };
     auto gate_reduce = [&](int i) {
         if (tid < 256) {
@@ -221,6 +227,7 @@ k_bat_gateup(const BatParams p)
         }
     };
     tile_pass(p.wu, nu, up_row, up_reduce);
+    }   // rounds
 }
 
 constexpr int DN_COLS = 256;                    // columns per workgroup in kernel B
@@ -413,14 +420,16 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     *ran = false;
     const int d = layer->d, F = layer->d_ff;
     if (layer->dtype != CLADA_BF16 || B < 2 || B > 16) return CLADA_OK;
-    if (d % 256 != 0 || (d != 4096 && d != 5120 && d != 1024 && d != 2048)) return CLADA_OK;
+    const int ksteps = d / 256;                                  // 8 waves x ksteps x 32 = d
+    if (d % 256 != 0 || !(ksteps == 4 || ksteps == 8 || ksteps == 10 || ksteps == 12 || ksteps == 16 || ksteps == 20 ||
+                          ksteps == 24 || ksteps == 32))
+        return CLADA_OK;
     const int P = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
-    const int no = (F + 7) / 8;
-    if ((no + P - 1) / P > 2 * MAX_TILES) return CLADA_OK;      // at most 64 neurons per workgroup
     const int CG = (d + DN_COLS - 1) / DN_COLS;
     int RG = P / CG;
     if (RG < 1) RG = 1;
     if (RG > 16) RG = 16;
+    while ((F + RG - 1) / RG + 1 > DN_MAX_ROWS && RG < 64) RG *= 2;     // wide layers: more, smaller row groups
     if ((F + RG - 1) / RG + 1 > DN_MAX_ROWS) return CLADA_OK;
 
     BatParams p;
@@ -436,7 +445,8 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
         if (dense) hipLaunchKernelGGL((k_bat_gateup<KS, true>), dim3(P), dim3(512), 0, stream, p);    \
         else       hipLaunchKernelGGL((k_bat_gateup<KS, false>), dim3(P), dim3(512), 0, stream, p);   \
     }
-    CLADA_BAT_CASE(4) CLADA_BAT_CASE(8) CLADA_BAT_CASE(16) CLADA_BAT_CASE(20)
+    CLADA_BAT_CASE(4) CLADA_BAT_CASE(8) CLADA_BAT_CASE(10) CLADA_BAT_CASE(12) CLADA_BAT_CASE(16) CLADA_BAT_CASE(20)
+    CLADA_BAT_CASE(24) CLADA_BAT_CASE(32)
 #undef CLADA_BAT_CASE
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     const size_t lds = 8 * (size_t)DN_TILE_BYTES + sizeof(int) * DN_MAX_ROWS;
