@@ -173,7 +173,7 @@ clada_status begin(clada_ctx *ctx, const clada_layer *layer, const void *x, int 
                    float eps, hipStream_t stream)
 {
     const int n_tn = clada_prefix_col_tiles(layer->d);
-    CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, w.part, w.pool, w.h, stream));
+    CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, w.part, w.pool, w.h, ctx->opt_prefix_tile, stream));
     CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.h, T, nullptr, w.rowsq_den, stream));
     hipLaunchKernelGGL(k_cett_begin, dim3((T + 255) / 256), dim3(256), 0, stream, w.state, w.rowsq_den, n_tn, T,
                        w.den, search, eps);

@@ -70,6 +70,7 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->opt_decode_batched = 1;
     ctx->opt_decode_own_first = 0;
     ctx->opt_decode_spin_limit = 1 << 21;
+    ctx->opt_prefix_tile = 0;
     ctx->opt_diag_events = 0;
     ctx->ev[0] = ctx->ev[1] = ctx->ev[2] = ctx->ev[3] = nullptr;
     ctx->err[0] = 0;
@@ -146,6 +147,11 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
     if (!strcmp(name, "decode.spin_limit")) {
         if (value < 0) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.spin_limit=%d is negative", value);
         ctx->opt_decode_spin_limit = value;
+        return CLADA_OK;
+    }
+    if (!strcmp(name, "prefix.tile")) {
+        if (value < 0 || value > 2) return clada_fail(ctx, CLADA_ERR_VALUE, "prefix.tile=%d outside [0,2]", value);
+        ctx->opt_prefix_tile = value;
         return CLADA_OK;
     }
     if (!strcmp(name, "diag.kernel_events")) {

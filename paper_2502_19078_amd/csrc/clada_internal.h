@@ -17,6 +17,7 @@ struct clada_ctx {
     int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
     int opt_decode_batched;      // 1: MFMA path for 2 <= B <= 16 (bf16), 0: generic kernels
     int opt_decode_spin_limit;   // polls a balanced batch-1 kernel makes before it gives up (see clada.h)
+    int opt_prefix_tile;         // gate/up prefill GEMM: 0 choose by T, 1 = 128-token tiles, 2 = 256-token tiles
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)
     hipEvent_t ev[4];            // start/stop of the main decode kernel, start/stop of the final reduction
     char err[512];
@@ -76,7 +77,7 @@ size_t clada_ws_cett(int32_t d, int32_t d_ff, int32_t T);
 int clada_prefix_token_tiles(int T);
 int clada_prefix_col_tiles(int d);
 hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, float *part, float *pool,
-                               char *hbuf, hipStream_t stream);
+                               char *hbuf, int tile_mode, hipStream_t stream);
 hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, char *y, float *rowsq,
                              hipStream_t stream);
 

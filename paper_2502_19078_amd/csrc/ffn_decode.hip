@@ -326,6 +326,7 @@ k_ffn_lists(const unsigned char *__restrict__ keep, int B, int F, int32_t *__res
     for (int i = 0; i < MAXW; ++i) uni[i] = 0u;
     for (int b = 0; b < B; ++b) {
         const unsigned char *row = keep + (size_t)b * F;
+        const bool row_al4 = (reinterpret_cast<size_t>(row) & 3) == 0;
         int cnt = 0;
 #pragma unroll
         for (int i = 0; i < MAXW; ++i) {
@@ -333,7 +334,19 @@ k_ffn_lists(const unsigned char *__restrict__ keep, int B, int F, int32_t *__res
             if (w < w1) {
                 unsigned int bits = 0u;
                 const int j0 = 32 * w, nj = min(32, F - j0);
-                for (int e = 0; e < nj; ++e) bits |= (row[j0 + e] != 0 ? 1u : 0u) << e;
+                if (nj == 32 && row_al4) {
+                    // four flags per 32-bit load: high bit of every non-zero byte, gathered into a nibble
+                    // by a multiplication whose sixteen partial products all land on different bits
+                    const unsigned int *r4 = reinterpret_cast<const unsigned int *>(row + j0);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const unsigned int v = r4[e];
+                        const unsigned int nz = ((((v & 0x7f7f7f7fu) + 0x7f7f7f7fu) | v) & 0x80808080u) >> 7;
+                        bits |= ((nz * 0x01020408u) >> 24) << (4 * e);
+                    }
+                } else {
+                    for (int e = 0; e < nj; ++e) bits |= (row[j0 + e] != 0 ? 1u : 0u) << e;
+                }
                 if (mask_bits) mask_bits[(size_t)b * words + w] = bits;
                 uni[i] |= bits;
                 cnt += __popc(bits);

@@ -16,6 +16,8 @@
 // XCD's L2 while the token tiles stream past it).
 #include <math.h>
 
+#include <type_traits>
+
 #include "clada_internal.h"
 
 namespace {
@@ -386,6 +388,269 @@ k_prefix_gateup_bf16(const GateUpParams p)
     gateup_epilogue<2>(acc, p, tm, tn, wm, wn, lane, tid, s_stat);
 }
 
+// Epilogue of the 256-token kernel for one wave: 128 tokens (rows tm128*128 ..) x 64 neurons, gate
+// accumulators acc[0], up accumulators acc[1].  FULL = the whole block lies inside [T] x [F], so no
+// element needs a bounds check.  Writes the per-neuron partial sums of these 128 tokens.
+template <bool FULL>
+__device__ __forceinline__ void wide_epilogue(const f32x16 (&acc)[2][4][2], const GateUpParams &p, int tm128, int tn,
+                                              int wn, int lane)
+{
+    const int n = lane & 31;
+    const int t0 = tm128 * 128 + 4 * (lane >> 5);          // row of accumulator register 0 of block mb = 0
+    const size_t F1 = (size_t)p.F, Fp1 = (size_t)p.Fp;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int j = tn * BN + wn * 64 + nb * 32 + n;
+        const bool jok = FULL || j < p.F;
+        const float bj = (p.relu && p.b_in && jok) ? p.b_in[j] : 0.0f;
+        float s_abs = 0.f, s_sq = 0.f, mx = 0.f, s_h2 = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            float aa[16], hh[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float a, h;
+                if (p.relu) {
+                    const float g = acc[0][mb][nb][r] + bj;
+                    a = g > 0.0f ? g : (g != g ? g : 0.0f);
+                    h = a;
+                } else {
+                    a = silu_f32(acc[0][mb][nb][r]);
+                    h = a * acc[1][mb][nb][r];
+                }
+                aa[r] = fabsf(a);
+                hh[r] = h;
+                const int t = t0 + mb * 32 + 8 * (r >> 2) + (r & 3);
+                if (FULL || (t < p.T && jok)) {
+                    s_abs += aa[r];
+                    s_sq = fmaf(a, a, s_sq);
+                    mx = (aa[r] > mx || aa[r] != aa[r]) ? aa[r] : mx;
+                    s_h2 = fmaf(h, h, s_h2);
+                }
+            }
+            if (p.pool) {
+                float *dst = p.pool + (size_t)(t0 + mb * 32) * F1 + j;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + (r & 3);
+                    if (FULL || (t0 + mb * 32 + row < p.T && jok)) dst[row * F1] = aa[r];
+                }
+            }
+            if (p.hbuf) {
+                unsigned short *dst = reinterpret_cast<unsigned short *>(p.hbuf) + (size_t)(t0 + mb * 32) * Fp1 + j;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 8 * (r >> 2) + (r & 3);
+                    if (FULL || (t0 + mb * 32 + row < p.T && j < p.Fp))
+                        dst[row * Fp1] = (unsigned short)f32_to_bf16_bits(jok ? hh[r] : 0.0f);
+                }
+            }
+        }
+        // lanes l and l^32 hold the same neuron
+        s_abs += __shfl_xor(s_abs, 32);
+        s_sq += __shfl_xor(s_sq, 32);
+        s_h2 += __shfl_xor(s_h2, 32);
+        const float mo = __shfl_xor(mx, 32);
+        mx = (mo > mx || mo != mo) ? mo : mx;
+        if (lane < 32 && jok && tm128 < p.n_tm) {
+            float *dst = p.part + (size_t)tm128 * 4 * F1 + j;
+            dst[0] = s_abs;
+            dst[F1] = s_sq;
+            dst[2 * F1] = mx;
+            dst[3 * F1] = s_h2;
+        }
+    }
+}
+
+// The same GEMM with a 256-token x 128-neuron workgroup tile: four waves of 128 x (64 gate + 64 up)
+// outputs, all 256 accumulator registers of a lane in use.  The 128 x 128 kernel above moves
+// 144 KiB through LDS (fragment reads plus the transfers' writes) per 1024 clocks of MFMA issue,
+// more than LDS delivers; a wave tile twice as tall needs a third less of both per flop.  k-tiles
+// are 32 deep (64-byte rows, chunk c of row r at position c ^ ((r >> 2) & 3)) so that four stages
+// of 32 KiB fit: at the barrier that certifies k-tile k+1 (placed between the two k-steps of
+// k-tile k, so the first fragment reads of k+1 run under the MFMAs of k) k-tile k+2 is in flight
+// and k+3 is issued into the stage k-1 has left.  Per-neuron partial sums are written per 128-token
+// half (one wave row each), i.e. in the layout of the 128-row kernel.
+constexpr int GW_STAGE = 32 * 1024;    // X 256 x 64 B | gate 128 x 64 B | up 128 x 64 B
+constexpr int GW_G = 16 * 1024, GW_U = 24 * 1024;
+
+__global__ void __launch_bounds__(256)
+k_prefix_gateup_bf16_wide(const GateUpParams p)
+{
+    __shared__ __align__(16) char s_w[4 * GW_STAGE];
+
+    const int n_tmw = (p.T + 255) / 256;
+    int tm, tn;
+    if (n_tmw % 8 == 0) {                                   // 8 token tiles x 4 neuron tiles per XCD at a time
+        const int tn_pad = (p.n_tn + 3) / 4 * 4;
+        const int o = remap_block(blockIdx.x, n_tmw * tn_pad);
+        const int sb = o >> 5, w = o & 31, tmb = n_tmw >> 3;
+        tm = (sb % tmb) * 8 + (w & 7);
+        tn = (sb / tmb) * 4 + (w >> 3);
+        if (tn >= p.n_tn) return;
+    } else {
+        const int total = n_tmw * p.n_tn;
+        const int tile = remap_block(blockIdx.x, total);
+        if (tile >= total) return;
+        tm = tile % n_tmw;
+        tn = tile / n_tmw;
+    }
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const size_t rowbytes = (size_t)p.d * 2;
+
+    f32x16 acc[2][4][2];
+#pragma unroll
+    for (int w = 0; w < 2; ++w)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[w][mb][nb][r] = 0.0f;
+
+    // a wave moves 16-row pieces (1 KiB): lane = (row lane >> 2, LDS position lane & 3)
+    const int lr = lane >> 2;
+    const int koff = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;
+    const char *gx[4], *gg[2], *gu[2];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {                           // rows past T / F repeat the last valid row;
+        const int t = min(tm * 256 + 16 * (wave + 4 * c) + lr, p.T - 1);   // their products land in discarded outputs
+        gx[c] = p.x + (size_t)t * rowbytes + koff;
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int j = min(tn * BN + 16 * (wave + 4 * c) + lr, p.F - 1);
+        gg[c] = p.wg + (size_t)j * rowbytes + koff;
+        gu[c] = p.wu + (size_t)j * rowbytes + koff;
+    }
+    const int nk = p.d / 32;
+    // transfer i (0..7) of this wave for k-tile kt: four X pieces, two gate, two up
+    auto dma_one = [&](auto ic, char *st, int kt) {
+        constexpr int i = decltype(ic)::value;
+        if (i < 4) lds_dma16(gx[i] + (size_t)kt * 64, st + (wave + 4 * i) * 1024);
+        else if (i < 6) lds_dma16(gg[i - 4] + (size_t)kt * 64, st + GW_G + (wave + 4 * (i - 4)) * 1024);
+        else lds_dma16(gu[i - 6] + (size_t)kt * 64, st + GW_U + (wave + 4 * (i - 6)) * 1024);
+    };
+    auto issue = [&](char *st, int kt) {
+        dma_one(std::integral_constant<int, 0>{}, st, kt); dma_one(std::integral_constant<int, 1>{}, st, kt);
+        dma_one(std::integral_constant<int, 2>{}, st, kt); dma_one(std::integral_constant<int, 3>{}, st, kt);
+        dma_one(std::integral_constant<int, 4>{}, st, kt); dma_one(std::integral_constant<int, 5>{}, st, kt);
+        dma_one(std::integral_constant<int, 6>{}, st, kt); dma_one(std::integral_constant<int, 7>{}, st, kt);
+    };
+    const int r32 = lane & 31, q = lane >> 5, sw = (r32 >> 2) & 3;
+    const unsigned int lds0 = (unsigned int)(size_t)(const __attribute__((address_space(3))) char *)s_w;
+    const unsigned int a_off = lds0 + (unsigned int)((wm * 128 + r32) * 64);
+    const unsigned int b_off = lds0 + (unsigned int)(GW_G + (wn * 64 + r32) * 64);
+    u32x4 fr[2][8];         // two fragment sets: 0..3 = X rows mb*32.., 4,5 = gate nb, 6,7 = up nb
+    // Fragment reads are inline assembly: for an LDS read the compiler cannot prove distinct from an
+    // in-flight direct-to-LDS transfer it inserts vmcnt(0), which would serialise the pipeline; the
+    // hand-placed vmcnt + barrier already order the transfers of the stage read here.
+#define GW_RD(S, I, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(fr[S][I]) : "v"(ADDR));
+#define GW_WAIT(S)                                                                                        \
+    asm volatile("s_waitcnt lgkmcnt(0)"                                                                   \
+                 : "+v"(fr[S][0]), "+v"(fr[S][1]), "+v"(fr[S][2]), "+v"(fr[S][3]), "+v"(fr[S][4]),        \
+                   "+v"(fr[S][5]), "+v"(fr[S][6]), "+v"(fr[S][7]));
+    // MFMA I (0..15) of a k-step: B fragment I / 4 (gate 0, gate 1, up 0, up 1) against X row block I % 4
+#define GW_MMA1(S, I)                                                                                     \
+    {                                                                                                     \
+        constexpr int bi = (I) >> 2, w = bi >> 1, nb = bi & 1, mb = (I) & 3;                              \
+        acc[w][mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                         \
+            __builtin_bit_cast(bf16x8, fr[S][mb]), __builtin_bit_cast(bf16x8, fr[S][4 + bi]), acc[w][mb][nb], 0, 0, 0); \
+    }
+#define GW_MMA8(S, I0)                                                                                    \
+    GW_MMA1(S, I0) GW_MMA1(S, I0 + 1) GW_MMA1(S, I0 + 2) GW_MMA1(S, I0 + 3)                               \
+    GW_MMA1(S, I0 + 4) GW_MMA1(S, I0 + 5) GW_MMA1(S, I0 + 6) GW_MMA1(S, I0 + 7)
+    // all eight reads of k-step ks of the stage at byte offset so (no MFMAs in between)
+    auto read_all = [&](auto sc, u32x4 (&fr)[2][8], unsigned int so, int ks) {
+        constexpr int S = decltype(sc)::value;
+        const unsigned int pos = (unsigned int)(((2 * ks + q) ^ sw) * 16);
+        const unsigned int pa = a_off + so + pos, pb = b_off + so + pos;
+        GW_RD(S, 0, pa, 0) GW_RD(S, 1, pa, 2048) GW_RD(S, 2, pa, 4096) GW_RD(S, 3, pa, 6144)
+        GW_RD(S, 4, pb, 0) GW_RD(S, 5, pb, 2048) GW_RD(S, 6, pb, 8192) GW_RD(S, 7, pb, 10240)
+    };
+    // One k-tile.  All four waves run in step, so whatever they issue in a burst queues up behind the
+    // same LDS and the same texture unit while the matrix cores wait: fragment reads and transfers are
+    // dealt out one at a time between MFMAs (sched_barrier keeps the compiler from regrouping), the
+    // reads in the first half of each k-step so that the last one has eight MFMAs to land.
+    //   first half : MFMAs of k-step 0 (set 0), reads of k-step 1 into set 1
+    //   barrier    : k-tile k+1 has landed for every wave, k-tile k-1 is no longer read
+    //   second half: MFMAs of k-step 1 (set 1), reads of k-step 0 of k-tile k+1 into set 0, then the
+    //                transfers of k-tile k+3 into the stage of k-1
+    auto ktile = [&](auto dmac, auto vmc, u32x4 (&fr)[2][8], f32x16 (&acc)[2][4][2], int k) {
+        constexpr bool DMA = decltype(dmac)::value;
+        constexpr int VM = decltype(vmc)::value;
+        const unsigned int cur = (unsigned int)((k & 3) * GW_STAGE), nxt = (unsigned int)(((k + 1) & 3) * GW_STAGE);
+        char *rf = s_w + ((k + 3) & 3) * GW_STAGE;
+#define GW_SB __builtin_amdgcn_sched_barrier(0);
+        {
+            const unsigned int pos = (unsigned int)(((2 + q) ^ sw) * 16);
+            const unsigned int pa = a_off + cur + pos, pb = b_off + cur + pos;
+            GW_WAIT(0)
+            GW_RD(1, 0, pa, 0)      GW_MMA1(0, 0) GW_SB
+            GW_RD(1, 1, pa, 2048)   GW_MMA1(0, 1) GW_SB
+            GW_RD(1, 2, pa, 4096)   GW_MMA1(0, 2) GW_SB
+            GW_RD(1, 3, pa, 6144)   GW_MMA1(0, 3) GW_SB
+            GW_RD(1, 4, pb, 0)      GW_MMA1(0, 4) GW_SB
+            GW_RD(1, 5, pb, 2048)   GW_MMA1(0, 5) GW_SB
+            GW_RD(1, 6, pb, 8192)   GW_MMA1(0, 6) GW_SB
+            GW_RD(1, 7, pb, 10240)  GW_MMA1(0, 7) GW_SB
+            GW_MMA8(0, 8) GW_SB
+        }
+        if (VM == 8) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8): k-tile k+1 landed, k+2 may fly
+        else         __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();
+        {
+            const unsigned int pos = (unsigned int)((q ^ sw) * 16);
+            const unsigned int pa = a_off + nxt + pos, pb = b_off + nxt + pos;
+            GW_WAIT(1)
+            GW_RD(0, 0, pa, 0)      GW_MMA1(1, 0) GW_SB
+            GW_RD(0, 1, pa, 2048)   GW_MMA1(1, 1) GW_SB
+            GW_RD(0, 2, pa, 4096)   GW_MMA1(1, 2) GW_SB
+            GW_RD(0, 3, pa, 6144)   GW_MMA1(1, 3) GW_SB
+            GW_RD(0, 4, pb, 0)      GW_MMA1(1, 4) GW_SB
+            GW_RD(0, 5, pb, 2048)   GW_MMA1(1, 5) GW_SB
+            GW_RD(0, 6, pb, 8192)   GW_MMA1(1, 6) GW_SB
+            GW_RD(0, 7, pb, 10240)  GW_MMA1(1, 7) GW_SB
+#define GW_STEP(I)                                                                                        \
+            if (DMA) dma_one(std::integral_constant<int, I>{}, rf, k + 3);                                \
+            GW_MMA1(1, 8 + I) GW_SB
+            GW_STEP(0) GW_STEP(1) GW_STEP(2) GW_STEP(3) GW_STEP(4) GW_STEP(5) GW_STEP(6) GW_STEP(7)
+#undef GW_STEP
+        }
+#undef GW_SB
+    };
+    using T_ = std::true_type; using F_ = std::false_type;
+    issue(s_w, 0);
+    issue(s_w + GW_STAGE, 1);                               // d >= 64: at least two k-tiles
+    if (nk > 2) issue(s_w + 2 * GW_STAGE, 2);
+    if (nk > 2) __builtin_amdgcn_s_waitcnt(0x4F70);         // vmcnt(16): k-tile 0 of this wave has landed
+    else        __builtin_amdgcn_s_waitcnt(0x0F78);         // vmcnt(8)
+    __builtin_amdgcn_s_barrier();
+    read_all(std::integral_constant<int, 0>{}, fr, 0u, 0);
+    for (int k = 0; k < nk - 3; ++k) ktile(T_{}, std::integral_constant<int, 8>{}, fr, acc, k);
+    if (nk >= 3) ktile(F_{}, std::integral_constant<int, 8>{}, fr, acc, nk - 3);
+    ktile(F_{}, std::integral_constant<int, 0>{}, fr, acc, nk - 2);
+    {   // last k-tile: nothing left to fetch
+        const unsigned int so = (unsigned int)(((nk - 1) & 3) * GW_STAGE);
+        read_all(std::integral_constant<int, 1>{}, fr, so, 1);
+        GW_WAIT(0)
+        GW_MMA8(0, 0) GW_MMA8(0, 8)
+        GW_WAIT(1)
+        GW_MMA8(1, 0) GW_MMA8(1, 8)
+    }
+#undef GW_RD
+#undef GW_WAIT
+#undef GW_MMA1
+#undef GW_MMA8
+
+    // ------------------------------------------------------------------ epilogue: this wave's 128 tokens x 64 neurons
+    const int tm128 = 2 * tm + wm;
+    if (tm128 * 128 + 128 <= p.T && tn * BN + BN <= p.F) wide_epilogue<true>(acc, p, tm128, tn, wn, lane);
+    else wide_epilogue<false>(acc, p, tm128, tn, wn, lane);
+}
+
 struct DownParams {
     const char *h, *wd;
     char *y;                       // [T][d] layer dtype, or nullptr
@@ -678,7 +943,7 @@ int clada_prefix_col_tiles(int d) { return (d + BN - 1) / BN; }
 // aggregates (always written), pool [T][F] |a| or nullptr, hbuf [T][Fp] h in the layer dtype or
 // nullptr (Fp = F rounded up to 64, zero past F).
 hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, float *part, float *pool,
-                               char *hbuf, hipStream_t stream)
+                               char *hbuf, int tile_mode, hipStream_t stream)
 {
     const int d = layer->d, F = layer->d_ff, es = (int)dtype_size(layer->dtype);
     GateUpParams g;
@@ -692,7 +957,15 @@ hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, f
     const int total = g.n_tm * g.n_tn;
     const int grid = (total + 7) / 8 * 8;
     const int total_blk = g.n_tm % 8 == 0 ? g.n_tm * ((g.n_tn + 3) / 4 * 4) : total;   // the bf16 kernel's padded tile order
-    if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
+    // tile_mode: 0 = choose, 1 = 128-token tiles, 2 = 256-token tiles (bf16, d % 64 == 0 only)
+    const int n_tmw = (T + 255) / 256;
+    const bool wide_ok = es == 2 && d % 64 == 0;
+    const bool wide = wide_ok && (tile_mode == 2 || (tile_mode == 0 && T >= 1024));
+    if (wide) {
+        const int blocks = n_tmw % 8 == 0 ? n_tmw * ((g.n_tn + 3) / 4 * 4) : n_tmw * g.n_tn;
+        hipLaunchKernelGGL(k_prefix_gateup_bf16_wide, dim3((blocks + 7) / 8 * 8), dim3(256), 0, stream, g);
+    }
+    else if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
     else if (d % 64 == 0) hipLaunchKernelGGL(k_prefix_gateup_bf16, dim3((total_blk + 7) / 8 * 8), dim3(256), 0, stream, g);
     else         hipLaunchKernelGGL(k_prefix_gateup<2>, dim3(grid), dim3(256), 0, stream, g);
     return hipGetLastError();
@@ -736,7 +1009,7 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
 
     float *part = reinterpret_cast<float *>(ws);
     char *hbuf = y ? ws + align_up(sizeof(float) * 4 * (size_t)n_tm * F, 256) : nullptr;
-    CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, part, out->abs_act_pool, hbuf, stream));
+    CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, part, out->abs_act_pool, hbuf, ctx->opt_prefix_tile, stream));
     if (y) CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, hbuf, T, (char *)y, nullptr, stream));
     if (out->sum_abs_act || out->sum_sq_act || out->max_abs_act || out->sum_sq_h || out->A) {
         if (es == 4) hipLaunchKernelGGL(k_prefix_reduce<4>, dim3((F + 3) / 4), dim3(256), 0, stream,

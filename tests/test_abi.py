@@ -86,6 +86,8 @@ def test_validation_without_gpu(lib):
     assert lib.clada_set_option(h, b"decode.wgs_per_cu", 2) == 0
     assert lib.clada_set_option(h, b"decode.b1", 4) == 6
     assert lib.clada_set_option(h, b"decode.b1", 2) == 0
+    assert lib.clada_set_option(h, b"prefix.tile", 3) == 6
+    assert lib.clada_set_option(h, b"prefix.tile", 2) == 0
     lib.clada_destroy(h)
 
 

@@ -28,14 +28,22 @@ def _rel(a, b):
     ("c2", 1024, 1000, 300),     # bf16 MFMA, ragged tiles
     ("c2", 4096, 384, 512),      # bf16, real K and prefix length of config 2, three neuron tiles
     ("c2", 72, 129, 257),
+    ("c2", 64, 200, 300),        # two 32-deep k-tiles: shorter than the 256-token kernel's pipeline
+    ("c2", 192, 129, 513),       # six k-tiles; the last 256-token tile holds one token
+    ("c2", 320, 64, 129),        # ten k-tiles; second half of the only 256-token tile holds one token
     ("c2", 512, 700, 1024),      # 8 token tiles: the blocked tile order, 6 neuron tiles padded to 8
     ("c2", 256, 384, 2000),      # 16 token tiles (last one ragged), 3 neuron tiles
 ])
-def test_prefix_stats_parity(clada, cfg_name, d, F, T):
+@pytest.mark.parametrize("tile", [1, 2])
+def test_prefix_stats_parity(clada, cfg_name, d, F, T, tile):
+    """tile = workgroup tile of the bf16 gate/up GEMM (128 or 256 tokens); fp32 layers have one kernel."""
     cfg = synth.CONFIGS[cfg_name]
+    if tile == 2 and cfg.dtype != "bf16":
+        pytest.skip("the 256-token tile is a bf16 kernel")
     w = synth.layer_weights(cfg, 0, 1, d=d, d_ff=F)
     X = synth.prefix_hidden(cfg, 0, 1, T=T, d=d)
     ctx = clada.Context(0, clada.workspace_bytes(d, F, 0, T, 0))
+    ctx.set_option("prefix.tile", tile)
     layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
     st = clada.prefix_stats(ctx, layer, to_dev(X, cfg.dtype))
     torch.cuda.synchronize()

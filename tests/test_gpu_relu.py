@@ -112,12 +112,14 @@ def test_relu_static_list_decode(clada):
     assert_close_y(to_np(y), ref, TOL_Y[cfg.dtype], "relu list decode")
 
 
-@pytest.mark.parametrize("cfg_name,d,F,T", [("o27", 2560, 700, 300), ("o350", 1024, 4096, 512), ("c1", 96, 200, 130)])
-def test_relu_prefix_stats_parity_and_calibration(clada, cfg_name, d, F, T):
+@pytest.mark.parametrize("cfg_name,d,F,T,tile", [("o27", 2560, 700, 300, 1), ("o27", 2560, 700, 300, 2),
+                                                 ("o350", 1024, 4096, 512, 0), ("c1", 96, 200, 130, 0)])
+def test_relu_prefix_stats_parity_and_calibration(clada, cfg_name, d, F, T, tile):
     cfg = synth.CONFIGS[cfg_name]
     w = synth.relu_layer(cfg, 5, 2, d=d, d_ff=F)
     X = synth.prefix_hidden(cfg, 5, 2, T=T, d=d)
     ctx = clada.Context(0, clada.workspace_bytes(d, F, 0, T, 0))
+    ctx.set_option("prefix.tile", tile)
     layer = _layer(clada, cfg, w)
     st = clada.prefix_stats(ctx, layer, to_dev(X, cfg.dtype))
     torch.cuda.synchronize()
