@@ -78,7 +78,7 @@ const char *clada_last_error(const clada_ctx *ctx);
  * for the other workgroups' masks before it gives up; default 2^21, about two
  * seconds; 0 = give up without polling; see clada_device_fault), "prefix.tile" (workgroup
  * tile of the bf16 prefill gate/up GEMM: 1 = 128 tokens x 128 neurons, 2 = 256 x 128,
- * 0 = 256 x 128 from 1024 prefix tokens on [default]), "diag.kernel_events" (1 = every decode call also
+ * 0 = 256 x 128 for more than 128 prefix tokens [default]), "diag.kernel_events" (1 = every decode call also
  * records HIP events around its kernels for clada_diag_kernel_times; default 0).
  * Unknown names or out-of-range values give CLADA_ERR_VALUE and change nothing. */
 clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);

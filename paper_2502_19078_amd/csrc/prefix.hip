@@ -79,6 +79,13 @@ __device__ __forceinline__ void mma_tile(const char *sa, const char *const (&sb)
     }
 }
 
+// SiLU of the prefill epilogues: hardware exp2 and reciprocal (a few ulp), a third of the instructions
+// of the division form; +-inf and NaN behave as in g / (1 + exp(-g)).
+__device__ __forceinline__ float silu_prefill(float g)
+{
+    return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * g));
+}
+
 // Row of accumulator register r of a 32x32 MFMA block held by `lane`.
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
@@ -125,7 +132,7 @@ __device__ __forceinline__ void gateup_epilogue(const f32x16 (&acc)[2][2][2], co
                     a = g > 0.0f ? g : (g != g ? g : 0.0f);
                     h = a;
                 } else {
-                    a = silu_f32(acc[0][mb][nb][r]);
+                    a = silu_prefill(acc[0][mb][nb][r]);
                     h = a * acc[1][mb][nb][r];
                 }
                 if (t < p.T && j < p.F) {
@@ -415,7 +422,7 @@ __device__ __forceinline__ void wide_epilogue(const f32x16 (&acc)[2][4][2], cons
                     a = g > 0.0f ? g : (g != g ? g : 0.0f);
                     h = a;
                 } else {
-                    a = silu_f32(acc[0][mb][nb][r]);
+                    a = silu_prefill(acc[0][mb][nb][r]);
                     h = a * acc[1][mb][nb][r];
                 }
                 aa[r] = fabsf(a);
@@ -572,66 +579,83 @@ k_prefix_gateup_bf16_wide(const GateUpParams p)
     };
     // One k-tile.  All four waves run in step, so whatever they issue in a burst queues up behind the
     // same LDS and the same texture unit while the matrix cores wait: fragment reads and transfers are
-    // dealt out one at a time between MFMAs (sched_barrier keeps the compiler from regrouping), the
-    // reads in the first half of each k-step so that the last one has eight MFMAs to land.
-    //   first half : MFMAs of k-step 0 (set 0), reads of k-step 1 into set 1
-    //   barrier    : k-tile k+1 has landed for every wave, k-tile k-1 is no longer read
-    //   second half: MFMAs of k-step 1 (set 1), reads of k-step 0 of k-tile k+1 into set 0, then the
-    //                transfers of k-tile k+3 into the stage of k-1
-    auto ktile = [&](auto dmac, auto vmc, u32x4 (&fr)[2][8], f32x16 (&acc)[2][4][2], int k) {
-        constexpr bool DMA = decltype(dmac)::value;
+    // dealt out one at a time between MFMAs (sched_barrier keeps the compiler from regrouping) -- the
+    // reads in the first half of each k-step so that the last one has eight MFMAs to land, the
+    // transfers one per MFMA slot over the whole workgroup (wave w takes slots 4i + w).
+    //   first half : MFMAs of k-step 0 (set 0), reads of k-step 1 into set 1, second half of the
+    //                transfers of k-tile k+3
+    //   barrier    : k-tile k+1 has landed for every wave and k-tile k is no longer read
+    //   second half: MFMAs of k-step 1 (set 1), reads of k-step 0 of k-tile k+1 into set 0, first half
+    //                of the transfers of k-tile k+4 into the stage of k
+    auto ktile = [&](auto dac, auto dbc, auto vmc, u32x4 (&fr)[2][8], f32x16 (&acc)[2][4][2], int k) {
+        constexpr bool DA = decltype(dac)::value, DB = decltype(dbc)::value;
         constexpr int VM = decltype(vmc)::value;
         const unsigned int cur = (unsigned int)((k & 3) * GW_STAGE), nxt = (unsigned int)(((k + 1) & 3) * GW_STAGE);
-        char *rf = s_w + ((k + 3) & 3) * GW_STAGE;
+        char *sta = s_w + ((k + 3) & 3) * GW_STAGE, *stb = s_w + (k & 3) * GW_STAGE;
 #define GW_SB __builtin_amdgcn_sched_barrier(0);
+#define GW_SLOT_A(SL)                                                                                     \
+        if (DA && ((SL) & 3) == wave) dma_one(std::integral_constant<int, 4 + (SL) / 4>{}, sta, k + 3);   \
+        GW_MMA1(0, SL) GW_SB
+#define GW_SLOT_B(SL)                                                                                     \
+        if (DB && ((SL) & 3) == wave) dma_one(std::integral_constant<int, (SL) / 4>{}, stb, k + 4);       \
+        GW_MMA1(1, SL) GW_SB
         {
             const unsigned int pos = (unsigned int)(((2 + q) ^ sw) * 16);
             const unsigned int pa = a_off + cur + pos, pb = b_off + cur + pos;
             GW_WAIT(0)
-            GW_RD(1, 0, pa, 0)      GW_MMA1(0, 0) GW_SB
-            GW_RD(1, 1, pa, 2048)   GW_MMA1(0, 1) GW_SB
-            GW_RD(1, 2, pa, 4096)   GW_MMA1(0, 2) GW_SB
-            GW_RD(1, 3, pa, 6144)   GW_MMA1(0, 3) GW_SB
-            GW_RD(1, 4, pb, 0)      GW_MMA1(0, 4) GW_SB
-            GW_RD(1, 5, pb, 2048)   GW_MMA1(0, 5) GW_SB
-            GW_RD(1, 6, pb, 8192)   GW_MMA1(0, 6) GW_SB
-            GW_RD(1, 7, pb, 10240)  GW_MMA1(0, 7) GW_SB
-            GW_MMA8(0, 8) GW_SB
+            GW_RD(1, 0, pa, 0)      GW_SLOT_A(0)
+            GW_RD(1, 1, pa, 2048)   GW_SLOT_A(1)
+            GW_RD(1, 2, pa, 4096)   GW_SLOT_A(2)
+            GW_RD(1, 3, pa, 6144)   GW_SLOT_A(3)
+            GW_RD(1, 4, pb, 0)      GW_SLOT_A(4)
+            GW_RD(1, 5, pb, 2048)   GW_SLOT_A(5)
+            GW_RD(1, 6, pb, 8192)   GW_SLOT_A(6)
+            GW_RD(1, 7, pb, 10240)  GW_SLOT_A(7)
+            GW_SLOT_A(8) GW_SLOT_A(9) GW_SLOT_A(10) GW_SLOT_A(11)
+            GW_SLOT_A(12) GW_SLOT_A(13) GW_SLOT_A(14) GW_SLOT_A(15)
+            GW_WAIT(1)                                      // every read of k-tile k is complete before the barrier
         }
-        if (VM == 8) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8): k-tile k+1 landed, k+2 may fly
-        else         __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (VM == 16)     __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): k-tile k+1 landed, k+2 and k+3 may fly
+        else if (VM == 8) __builtin_amdgcn_s_waitcnt(0x0F78);
+        else              __builtin_amdgcn_s_waitcnt(0x0F70);
         __builtin_amdgcn_s_barrier();
         {
             const unsigned int pos = (unsigned int)((q ^ sw) * 16);
             const unsigned int pa = a_off + nxt + pos, pb = b_off + nxt + pos;
-            GW_WAIT(1)
-            GW_RD(0, 0, pa, 0)      GW_MMA1(1, 0) GW_SB
-            GW_RD(0, 1, pa, 2048)   GW_MMA1(1, 1) GW_SB
-            GW_RD(0, 2, pa, 4096)   GW_MMA1(1, 2) GW_SB
-            GW_RD(0, 3, pa, 6144)   GW_MMA1(1, 3) GW_SB
-            GW_RD(0, 4, pb, 0)      GW_MMA1(1, 4) GW_SB
-            GW_RD(0, 5, pb, 2048)   GW_MMA1(1, 5) GW_SB
-            GW_RD(0, 6, pb, 8192)   GW_MMA1(1, 6) GW_SB
-            GW_RD(0, 7, pb, 10240)  GW_MMA1(1, 7) GW_SB
-#define GW_STEP(I)                                                                                        \
-            if (DMA) dma_one(std::integral_constant<int, I>{}, rf, k + 3);                                \
-            GW_MMA1(1, 8 + I) GW_SB
-            GW_STEP(0) GW_STEP(1) GW_STEP(2) GW_STEP(3) GW_STEP(4) GW_STEP(5) GW_STEP(6) GW_STEP(7)
-#undef GW_STEP
+            GW_RD(0, 0, pa, 0)      GW_SLOT_B(0)
+            GW_RD(0, 1, pa, 2048)   GW_SLOT_B(1)
+            GW_RD(0, 2, pa, 4096)   GW_SLOT_B(2)
+            GW_RD(0, 3, pa, 6144)   GW_SLOT_B(3)
+            GW_RD(0, 4, pb, 0)      GW_SLOT_B(4)
+            GW_RD(0, 5, pb, 2048)   GW_SLOT_B(5)
+            GW_RD(0, 6, pb, 8192)   GW_SLOT_B(6)
+            GW_RD(0, 7, pb, 10240)  GW_SLOT_B(7)
+            GW_SLOT_B(8) GW_SLOT_B(9) GW_SLOT_B(10) GW_SLOT_B(11)
+            GW_SLOT_B(12) GW_SLOT_B(13) GW_SLOT_B(14) GW_SLOT_B(15)
         }
+#undef GW_SLOT_A
+#undef GW_SLOT_B
 #undef GW_SB
     };
     using T_ = std::true_type; using F_ = std::false_type;
     issue(s_w, 0);
     issue(s_w + GW_STAGE, 1);                               // d >= 64: at least two k-tiles
     if (nk > 2) issue(s_w + 2 * GW_STAGE, 2);
-    if (nk > 2) __builtin_amdgcn_s_waitcnt(0x4F70);         // vmcnt(16): k-tile 0 of this wave has landed
-    else        __builtin_amdgcn_s_waitcnt(0x0F78);         // vmcnt(8)
+    if (nk > 3) {                                           // first half of k-tile 3; the loop sends the second
+        dma_one(std::integral_constant<int, 0>{}, s_w + 3 * GW_STAGE, 3); dma_one(std::integral_constant<int, 1>{}, s_w + 3 * GW_STAGE, 3);
+        dma_one(std::integral_constant<int, 2>{}, s_w + 3 * GW_STAGE, 3); dma_one(std::integral_constant<int, 3>{}, s_w + 3 * GW_STAGE, 3);
+    }
+    // k-tile 0 of this wave has landed: the transfers issued after it may stay in flight
+    if (nk > 3)      __builtin_amdgcn_s_waitcnt(0x4F74);    // vmcnt(20)
+    else if (nk > 2) __builtin_amdgcn_s_waitcnt(0x4F70);    // vmcnt(16)
+    else             __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8)
     __builtin_amdgcn_s_barrier();
     read_all(std::integral_constant<int, 0>{}, fr, 0u, 0);
-    for (int k = 0; k < nk - 3; ++k) ktile(T_{}, std::integral_constant<int, 8>{}, fr, acc, k);
-    if (nk >= 3) ktile(F_{}, std::integral_constant<int, 8>{}, fr, acc, nk - 3);
-    ktile(F_{}, std::integral_constant<int, 0>{}, fr, acc, nk - 2);
+    using V16 = std::integral_constant<int, 16>; using V8 = std::integral_constant<int, 8>; using V0 = std::integral_constant<int, 0>;
+    for (int k = 0; k + 4 < nk; ++k) ktile(T_{}, T_{}, V16{}, fr, acc, k);
+    if (nk >= 4) ktile(T_{}, F_{}, V16{}, fr, acc, nk - 4);
+    if (nk >= 3) ktile(F_{}, F_{}, V8{}, fr, acc, nk - 3);
+    ktile(F_{}, F_{}, V0{}, fr, acc, nk - 2);
     {   // last k-tile: nothing left to fetch
         const unsigned int so = (unsigned int)(((nk - 1) & 3) * GW_STAGE);
         read_all(std::integral_constant<int, 1>{}, fr, so, 1);
@@ -960,7 +984,7 @@ hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, f
     // tile_mode: 0 = choose, 1 = 128-token tiles, 2 = 256-token tiles (bf16, d % 64 == 0 only)
     const int n_tmw = (T + 255) / 256;
     const bool wide_ok = es == 2 && d % 64 == 0;
-    const bool wide = wide_ok && (tile_mode == 2 || (tile_mode == 0 && T >= 1024));
+    const bool wide = wide_ok && (tile_mode == 2 || (tile_mode == 0 && T > 128));     // measured faster from T = 512 down
     if (wide) {
         const int blocks = n_tmw % 8 == 0 ? n_tmw * ((g.n_tn + 3) / 4 * 4) : n_tmw * g.n_tn;
         hipLaunchKernelGGL(k_prefix_gateup_bf16_wide, dim3((blocks + 7) / 8 * 8), dim3(256), 0, stream, g);

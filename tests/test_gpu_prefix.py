@@ -29,6 +29,7 @@ def _rel(a, b):
     ("c2", 4096, 384, 512),      # bf16, real K and prefix length of config 2, three neuron tiles
     ("c2", 72, 129, 257),
     ("c2", 64, 200, 300),        # two 32-deep k-tiles: shorter than the 256-token kernel's pipeline
+    ("c2", 128, 100, 257),       # four k-tiles: exactly the four LDS stages, no steady-state iteration
     ("c2", 192, 129, 513),       # six k-tiles; the last 256-token tile holds one token
     ("c2", 320, 64, 129),        # ten k-tiles; second half of the only 256-token tile holds one token
     ("c2", 512, 700, 1024),      # 8 token tiles: the blocked tile order, 6 neuron tiles padded to 8
