@@ -95,3 +95,35 @@ def test_calibrated_threshold_gives_target_decode_sparsity(clada):
     torch.cuda.synchronize()
     rho = 1.0 - cnt[1:].float().mean().item() / F
     assert abs(rho - cfg.q) < 0.03
+
+
+@pytest.mark.parametrize("cfg_name,layer_id", [("c4", 3), ("c2", 7)])
+def test_prefix_stats_full_size_layers_sampled(clada, cfg_name, layer_id):
+    """One full-size layer with the configuration's own prefix length (LLaMA-3-8B shape with 4096
+    tokens, LLaMA2-7B shape with 512), in the launch the benchmark times.  The oracle is too slow
+    for the whole prefill, so it checks what it can compute piece by piece: per-neuron aggregates
+    and pool columns of sampled neurons (each neuron's statistics depend on its own three weight
+    rows only), and the output rows of sampled tokens (the prefill output of a token is its dense
+    decode)."""
+    cfg = synth.CONFIGS[cfg_name]
+    d, F, T = cfg.d, cfg.d_ff, cfg.T
+    w = synth.layer_weights(cfg, 0, layer_id)
+    X = synth.prefix_hidden(cfg, 0, layer_id)
+    assert X.shape == (T, d)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 0, T, 0))
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    st = clada.prefix_stats(ctx, layer, to_dev(X, cfg.dtype))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    # neurons at tile borders of both kernels' tilings plus random ones
+    S = np.unique(np.concatenate([[0, 31, 32, 63, 64, 127, 128, F - 129, F - 128, F - 1],
+                                  rng.integers(0, F, 54)])).astype(np.int64)
+    ref = oracle.prefix_stats(w[0][S], w[1][S], w[2][S], X, want_y=False)
+    pool = to_np(st.abs_act_pool[:, torch.from_numpy(S).to(DEV)])
+    np.testing.assert_allclose(pool, ref["abs_act_pool"], rtol=1e-4, atol=1e-6)
+    for name in ("sum_abs_act", "sum_sq_act", "max_abs_act", "sum_sq_h", "A"):
+        np.testing.assert_allclose(to_np(getattr(st, name))[S], ref[name], rtol=2e-5, atol=1e-7, err_msg=name)
+    toks = np.unique(np.concatenate([[0, 127, 128, 255, 256, T - 1], rng.integers(0, T, 4)]))
+    y = to_np(st.y)
+    for t in toks:
+        assert_close_y(y[t:t + 1], oracle.dense_decode(*w, X[t:t + 1]), TOL_Y[cfg.dtype], f"prefill y, token {t}")
