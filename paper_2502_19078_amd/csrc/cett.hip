@@ -174,7 +174,7 @@ clada_status begin(clada_ctx *ctx, const clada_layer *layer, const void *x, int 
 {
     const int n_tn = clada_prefix_col_tiles(layer->d);
     CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, w.part, w.pool, w.h, ctx->opt_prefix_tile, stream));
-    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.h, T, nullptr, w.rowsq_den, stream));
+    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.h, T, nullptr, w.rowsq_den, ctx->opt_prefix_tile, stream));
     hipLaunchKernelGGL(k_cett_begin, dim3((T + 255) / 256), dim3(256), 0, stream, w.state, w.rowsq_den, n_tn, T,
                        w.den, search, eps);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
@@ -194,7 +194,7 @@ clada_status probe(clada_ctx *ctx, const clada_layer *layer, int T, const CettWs
     else
         hipLaunchKernelGGL(k_cett_mask<4>, dim3(grid), dim3(256), 0, stream, w.state, w.pool, w.h, w.hcut, T, F, Fp);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
-    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.hcut, T, nullptr, w.rowsq_num, stream));
+    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.hcut, T, nullptr, w.rowsq_num, ctx->opt_prefix_tile, stream));
     hipLaunchKernelGGL(k_cett_update, dim3(1), dim3(1024), 0, stream, w.state, w.rowsq_num, n_tn, T, w.den, bound,
                        search, cett_out, mean_out);
     CLADA_CHECK_HIP(ctx, hipGetLastError());

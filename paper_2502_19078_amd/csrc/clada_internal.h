@@ -79,7 +79,7 @@ int clada_prefix_col_tiles(int d);
 hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, float *part, float *pool,
                                char *hbuf, int tile_mode, hipStream_t stream);
 hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, char *y, float *rowsq,
-                             hipStream_t stream);
+                             int tile_mode, hipStream_t stream);
 
 #ifdef __HIPCC__
 // ---------------------------------------------------------------- device helpers

@@ -908,6 +908,229 @@ k_prefix_down_bf16(const DownParams p)
     }
 }
 
+// bf16 down projection with a 256-token x 256-column workgroup tile (four waves of 128 x 128, all
+// 256 accumulator registers of a lane), built like k_prefix_gateup_bf16_wide: four stages of 32-deep
+// k-tiles filled by direct-to-LDS transfers, reads and transfers dealt out between MFMAs, one
+// barrier per k-tile.  The h tile uses that kernel's layout.  The W_down tile stays row-major
+// ([k][256 columns], 512 bytes a row); a transfer of 1 KiB carries two rows.  A transposing read
+// takes, per pass, 64 bytes from each of four consecutive rows, so row k is placed such that its
+// bank offset is 64 (k & 3): odd rows are stored rotated by 64 bytes inside their 512 (the
+// rotation happens on the global-address side of the transfer), and every pair of rows is followed
+// by 128 bytes of padding.  Needs d % 256 == 0 and d_ff % 32 == 0 (no k-tile reaches past d_ff).
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+constexpr int DW_PAIR = 1024 + 128;                 // two W_down rows + padding
+constexpr int DW_B = 16 * 1024;                     // offset of the W_down tile in a stage
+constexpr int DW_STAGE = DW_B + 16 * DW_PAIR;       // 34816 bytes
+
+__global__ void __launch_bounds__(256)
+k_prefix_down_bf16_wide(const DownParams p)
+{
+    __shared__ __align__(16) char s_w[4 * DW_STAGE];
+
+    const int n_tmw = (p.T + 255) / 256, n_tnw = p.d / 256;
+    int tm, tn;
+    if (n_tmw % 8 == 0) {                                   // 8 token tiles x 4 column tiles per XCD at a time
+        const int tn_pad = (n_tnw + 3) / 4 * 4;
+        const int o = remap_block(blockIdx.x, n_tmw * tn_pad);
+        const int sb = o >> 5, w = o & 31, tmb = n_tmw >> 3;
+        tm = (sb % tmb) * 8 + (w & 7);
+        tn = (sb / tmb) * 4 + (w >> 3);
+        if (tn >= n_tnw) return;
+    } else {
+        const int total = n_tmw * n_tnw;
+        const int tile = remap_block(blockIdx.x, total);
+        if (tile >= total) return;
+        tm = tile % n_tmw;
+        tn = tile / n_tmw;
+    }
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const size_t hrow = (size_t)p.Fp * 2, wrow = (size_t)p.d * 2;
+
+    f32x16 acc[4][4];                                       // [token block mb][column block nb]
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.0f;
+
+    // transfers of a wave per k-tile: four 16-row pieces of the h tile, four row pairs of W_down
+    const char *gh[4], *gw[4];
+    {
+        const int lr = lane >> 2;
+        const int koff = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;
+        const int half = lane >> 5, cidx = ((lane & 31) - 4 * half) & 31;     // LDS position p of an odd row holds chunk p - 4
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int t = min(tm * 256 + 16 * (wave + 4 * c) + lr, p.T - 1);  // rows past T repeat the last one: discarded outputs
+            gh[c] = p.h + (size_t)t * hrow + koff;
+            gw[c] = p.wd + (size_t)(2 * (wave + 4 * c) + half) * wrow + (size_t)tn * 512 + cidx * 16;
+        }
+    }
+    const int nk = p.F / 32;                                // >= 1; d_ff % 32 == 0
+    auto dma_one = [&](auto ic, char *st, int kt) {
+        constexpr int i = decltype(ic)::value;
+        if (i < 4) lds_dma16(gh[i] + (size_t)kt * 64, st + (wave + 4 * i) * 1024);
+        else lds_dma16(gw[i - 4] + (size_t)kt * 32 * wrow, st + DW_B + (wave + 4 * (i - 4)) * DW_PAIR);
+    };
+    auto issue = [&](char *st, int kt) {
+        dma_one(std::integral_constant<int, 0>{}, st, kt); dma_one(std::integral_constant<int, 1>{}, st, kt);
+        dma_one(std::integral_constant<int, 2>{}, st, kt); dma_one(std::integral_constant<int, 3>{}, st, kt);
+        dma_one(std::integral_constant<int, 4>{}, st, kt); dma_one(std::integral_constant<int, 5>{}, st, kt);
+        dma_one(std::integral_constant<int, 6>{}, st, kt); dma_one(std::integral_constant<int, 7>{}, st, kt);
+    };
+    const unsigned int lds0 = (unsigned int)(size_t)(const __attribute__((address_space(3))) char *)s_w;
+    // A fragments: as in the gate/up kernel
+    const int r32 = lane & 31, q = lane >> 5, sw = (r32 >> 2) & 3;
+    const unsigned int a_off = lds0 + (unsigned int)((wm * 128 + r32) * 64);
+    // B fragments: in each 16-lane group lane t = 4r + c4 supplies row k0 + r, columns 4 c4 .. 4 c4 + 3,
+    // and receives column t of rows k0 .. k0 + 3; group g covers columns 16 (g & 1) .., k half g >> 1
+    const int t16 = lane & 15, g = lane >> 4, rr = t16 >> 2;
+    const unsigned int b_lane = lds0 + (unsigned int)(DW_B + (4 * (g >> 1) + (rr >> 1)) * DW_PAIR + (rr & 1) * 512);
+    unsigned int b_off[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+        b_off[nb] = b_lane + (unsigned int)((wn * 256 + nb * 64 + 32 * (g & 1) + 8 * (t16 & 3) + 64 * (rr & 1)) & 511);
+    u32x4 fa[2][4];                                         // two fragment sets
+    u32x2 fb[2][8];                                         // [set][2 nb + half]: rows k0..k0+3 and k0+4..k0+7
+#define DW_RDA(S, I, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(fa[S][I]) : "v"(ADDR));
+#define DW_RDB(S, I, ADDR, OFF) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:" #OFF : "=v"(fb[S][I]) : "v"(ADDR));
+#define DW_WAIT(S)                                                                                        \
+    asm volatile("s_waitcnt lgkmcnt(0)"                                                                   \
+                 : "+v"(fa[S][0]), "+v"(fa[S][1]), "+v"(fa[S][2]), "+v"(fa[S][3]), "+v"(fb[S][0]),        \
+                   "+v"(fb[S][1]), "+v"(fb[S][2]), "+v"(fb[S][3]), "+v"(fb[S][4]), "+v"(fb[S][5]),        \
+                   "+v"(fb[S][6]), "+v"(fb[S][7]));
+    // MFMA I (0..15) of a k-step: column block I / 4 against token block I % 4
+#define DW_MMA1(S, I)                                                                                     \
+    {                                                                                                     \
+        constexpr int nb = (I) >> 2, mb = (I) & 3;                                                        \
+        const u32x4 bv = {fb[S][2 * nb].x, fb[S][2 * nb].y, fb[S][2 * nb + 1].x, fb[S][2 * nb + 1].y};    \
+        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[S][mb]),      \
+                                                              __builtin_bit_cast(bf16x8, bv), acc[mb][nb], 0, 0, 0); \
+    }
+    // read I (0..11) of k-step KS from the stage at byte offset SO into set S: four A fragments, then
+    // the eight halves of the B fragments
+#define DW_RD(S, I, SO, KS)                                                                               \
+    {                                                                                                     \
+        if ((I) < 4) {                                                                                    \
+            const unsigned int pa = a_off + (SO) + (unsigned int)(((2 * (KS) + q) ^ sw) * 16);            \
+            if ((I) == 0) DW_RDA(S, 0, pa, 0) else if ((I) == 1) DW_RDA(S, 1, pa, 2048)                   \
+            else if ((I) == 2) DW_RDA(S, 2, pa, 4096) else DW_RDA(S, 3, pa, 6144)                         \
+        } else {                                                                                          \
+            const unsigned int pb = b_off[((I) - 4) >> 1] + (SO);                                         \
+            if ((KS) == 0) { if (((I) & 1) == 0) DW_RDB(S, (I) - 4, pb, 0) else DW_RDB(S, (I) - 4, pb, 2304) }       \
+            else           { if (((I) & 1) == 0) DW_RDB(S, (I) - 4, pb, 9216) else DW_RDB(S, (I) - 4, pb, 11520) }   \
+        }                                                                                                 \
+    }
+#define DW_SB __builtin_amdgcn_sched_barrier(0);
+    auto read_all = [&](auto sc, auto ksc, u32x4 (&fa)[2][4], u32x2 (&fb)[2][8], unsigned int so) {
+        constexpr int S = decltype(sc)::value, KS = decltype(ksc)::value;
+        DW_RD(S, 0, so, KS) DW_RD(S, 1, so, KS) DW_RD(S, 2, so, KS) DW_RD(S, 3, so, KS)
+        DW_RD(S, 4, so, KS) DW_RD(S, 5, so, KS) DW_RD(S, 6, so, KS) DW_RD(S, 7, so, KS)
+        DW_RD(S, 8, so, KS) DW_RD(S, 9, so, KS) DW_RD(S, 10, so, KS) DW_RD(S, 11, so, KS)
+    };
+    // one k-tile; the schedule is that of k_prefix_gateup_bf16_wide (twelve reads per k-step here)
+    auto ktile = [&](auto dac, auto dbc, auto vmc, u32x4 (&fa)[2][4], u32x2 (&fb)[2][8], f32x16 (&acc)[4][4], int k) {
+        constexpr bool DA = decltype(dac)::value, DB = decltype(dbc)::value;
+        constexpr int VM = decltype(vmc)::value;
+        const unsigned int cur = (unsigned int)((k & 3) * DW_STAGE), nxt = (unsigned int)(((k + 1) & 3) * DW_STAGE);
+        char *sta = s_w + ((k + 3) & 3) * DW_STAGE, *stb = s_w + (k & 3) * DW_STAGE;
+#define DW_SLOT_A(SL)                                                                                     \
+        if ((SL) < 12) DW_RD(1, SL, cur, 1)                                                               \
+        if (DA && ((SL) & 3) == wave) dma_one(std::integral_constant<int, 4 + (SL) / 4>{}, sta, k + 3);   \
+        DW_MMA1(0, SL) DW_SB
+#define DW_SLOT_B(SL)                                                                                     \
+        if ((SL) < 12) DW_RD(0, SL, nxt, 0)                                                               \
+        if (DB && ((SL) & 3) == wave) dma_one(std::integral_constant<int, (SL) / 4>{}, stb, k + 4);       \
+        DW_MMA1(1, SL) DW_SB
+        DW_WAIT(0)
+        DW_SLOT_A(0) DW_SLOT_A(1) DW_SLOT_A(2) DW_SLOT_A(3) DW_SLOT_A(4) DW_SLOT_A(5) DW_SLOT_A(6) DW_SLOT_A(7)
+        DW_SLOT_A(8) DW_SLOT_A(9) DW_SLOT_A(10) DW_SLOT_A(11) DW_SLOT_A(12) DW_SLOT_A(13) DW_SLOT_A(14) DW_SLOT_A(15)
+        DW_WAIT(1)                                          // every read of k-tile k is complete before the barrier
+        if (VM == 16)     __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16): k-tile k+1 landed, k+2 and k+3 may fly
+        else if (VM == 8) __builtin_amdgcn_s_waitcnt(0x0F78);
+        else              __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_barrier();
+        DW_SLOT_B(0) DW_SLOT_B(1) DW_SLOT_B(2) DW_SLOT_B(3) DW_SLOT_B(4) DW_SLOT_B(5) DW_SLOT_B(6) DW_SLOT_B(7)
+        DW_SLOT_B(8) DW_SLOT_B(9) DW_SLOT_B(10) DW_SLOT_B(11) DW_SLOT_B(12) DW_SLOT_B(13) DW_SLOT_B(14) DW_SLOT_B(15)
+#undef DW_SLOT_A
+#undef DW_SLOT_B
+    };
+    using T_ = std::true_type; using F_ = std::false_type;
+    using V16 = std::integral_constant<int, 16>; using V8 = std::integral_constant<int, 8>; using V0 = std::integral_constant<int, 0>;
+    issue(s_w, 0);
+    if (nk > 1) issue(s_w + DW_STAGE, 1);
+    if (nk > 2) issue(s_w + 2 * DW_STAGE, 2);
+    if (nk > 3) {                                           // first half of k-tile 3; the loop sends the second
+        dma_one(std::integral_constant<int, 0>{}, s_w + 3 * DW_STAGE, 3); dma_one(std::integral_constant<int, 1>{}, s_w + 3 * DW_STAGE, 3);
+        dma_one(std::integral_constant<int, 2>{}, s_w + 3 * DW_STAGE, 3); dma_one(std::integral_constant<int, 3>{}, s_w + 3 * DW_STAGE, 3);
+    }
+    if (nk > 3)      __builtin_amdgcn_s_waitcnt(0x4F74);    // vmcnt(20): k-tile 0 of this wave has landed
+    else if (nk > 2) __builtin_amdgcn_s_waitcnt(0x4F70);    // vmcnt(16)
+    else if (nk > 1) __builtin_amdgcn_s_waitcnt(0x0F78);    // vmcnt(8)
+    else             __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    read_all(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, fa, fb, 0u);
+    for (int k = 0; k + 4 < nk; ++k) ktile(T_{}, T_{}, V16{}, fa, fb, acc, k);
+    if (nk >= 4) ktile(T_{}, F_{}, V16{}, fa, fb, acc, nk - 4);
+    if (nk >= 3) ktile(F_{}, F_{}, V8{}, fa, fb, acc, nk - 3);
+    if (nk >= 2) ktile(F_{}, F_{}, V0{}, fa, fb, acc, nk - 2);
+    {   // last k-tile: nothing left to fetch
+        const unsigned int so = (unsigned int)(((nk - 1) & 3) * DW_STAGE);
+        read_all(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, fa, fb, so);
+        DW_WAIT(0)
+        DW_MMA1(0, 0) DW_MMA1(0, 1) DW_MMA1(0, 2) DW_MMA1(0, 3) DW_MMA1(0, 4) DW_MMA1(0, 5) DW_MMA1(0, 6) DW_MMA1(0, 7)
+        DW_MMA1(0, 8) DW_MMA1(0, 9) DW_MMA1(0, 10) DW_MMA1(0, 11) DW_MMA1(0, 12) DW_MMA1(0, 13) DW_MMA1(0, 14) DW_MMA1(0, 15)
+        DW_WAIT(1)
+        DW_MMA1(1, 0) DW_MMA1(1, 1) DW_MMA1(1, 2) DW_MMA1(1, 3) DW_MMA1(1, 4) DW_MMA1(1, 5) DW_MMA1(1, 6) DW_MMA1(1, 7)
+        DW_MMA1(1, 8) DW_MMA1(1, 9) DW_MMA1(1, 10) DW_MMA1(1, 11) DW_MMA1(1, 12) DW_MMA1(1, 13) DW_MMA1(1, 14) DW_MMA1(1, 15)
+    }
+#undef DW_RDA
+#undef DW_RDB
+#undef DW_WAIT
+#undef DW_MMA1
+#undef DW_RD
+#undef DW_SB
+
+    // ------------------------------------------------------------------ epilogue: 128 tokens x 128 columns of this wave
+    const int n = lane & 31;
+    const int t0 = tm * 256 + wm * 128 + 4 * (lane >> 5);
+    const int c0 = tn * 256 + wn * 128;                     // one 128-column tile of the row-norm buffer
+    if (p.rowsq) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float v = 0.0f;
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) v = fmaf(acc[mb][nb][r], acc[mb][nb][r], v);
+                v += __shfl_xor(v, 16);
+                v += __shfl_xor(v, 8);
+                v += __shfl_xor(v, 4);
+                v += __shfl_xor(v, 2);
+                v += __shfl_xor(v, 1);
+                const int t = t0 + mb * 32 + 8 * (r >> 2) + (r & 3);
+                if (n == 0 && t < p.T) p.rowsq[(size_t)(c0 >> 7) * p.T + t] = v;
+            }
+    }
+    if (!p.y) return;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        const int col = c0 + nb * 32 + n;
+        const float bv = p.bias ? p.bias[col] : 0.0f;
+        unsigned short *dst = reinterpret_cast<unsigned short *>(p.y) + (size_t)t0 * p.d + col;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = mb * 32 + 8 * (r >> 2) + (r & 3);
+                if (t0 + row < p.T) dst[(size_t)row * p.d] = (unsigned short)f32_to_bf16_bits(acc[mb][nb][r] + bv);
+            }
+    }
+}
+
 // One wave per neuron: ||W_down[j,:]||^2, then fold the token-tile partials in
 // ascending tile order and write the requested aggregates.
 template <int ES>
@@ -998,7 +1221,7 @@ hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, f
 // Down projection of h [T][Fp]: y [T][d] in the layer dtype and/or rowsq [col tiles][T], the
 // per-column-tile sums of squares of the fp32 output rows (either may be nullptr).
 hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, char *y, float *rowsq,
-                             hipStream_t stream)
+                             int tile_mode, hipStream_t stream)
 {
     const int d = layer->d, F = layer->d_ff, es = (int)dtype_size(layer->dtype);
     DownParams q;
@@ -1007,7 +1230,15 @@ hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, cha
     q.T = T; q.d = d; q.F = F; q.Fp = (int)align_up((size_t)F, 64);
     q.n_tm = (T + BM - 1) / BM; q.n_tn = (d + BN - 1) / BN;
     const int tot = q.n_tm * q.n_tn, grid = (tot + 7) / 8 * 8;
-    if (es == 4) hipLaunchKernelGGL(k_prefix_down<4>, dim3(grid), dim3(256), 0, stream, q);
+    // 256 x 256 tiles when they fill the chip at least once (tile_mode 2: whenever the shape allows)
+    const int n_tmw = (T + 255) / 256, n_tnw = d / 256;
+    const bool wide_ok = es == 2 && d % 256 == 0 && F % 32 == 0;
+    const bool wide = wide_ok && (tile_mode == 2 || (tile_mode == 0 && n_tmw * n_tnw >= 192));
+    if (wide) {
+        const int blocks = n_tmw % 8 == 0 ? n_tmw * ((n_tnw + 3) / 4 * 4) : n_tmw * n_tnw;
+        hipLaunchKernelGGL(k_prefix_down_bf16_wide, dim3((blocks + 7) / 8 * 8), dim3(256), 0, stream, q);
+    }
+    else if (es == 4) hipLaunchKernelGGL(k_prefix_down<4>, dim3(grid), dim3(256), 0, stream, q);
     else         hipLaunchKernelGGL(k_prefix_down_bf16, dim3(grid), dim3(256), 0, stream, q);
     return hipGetLastError();
 }
@@ -1034,7 +1265,7 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
     float *part = reinterpret_cast<float *>(ws);
     char *hbuf = y ? ws + align_up(sizeof(float) * 4 * (size_t)n_tm * F, 256) : nullptr;
     CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, part, out->abs_act_pool, hbuf, ctx->opt_prefix_tile, stream));
-    if (y) CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, hbuf, T, (char *)y, nullptr, stream));
+    if (y) CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, hbuf, T, (char *)y, nullptr, ctx->opt_prefix_tile, stream));
     if (out->sum_abs_act || out->sum_sq_act || out->max_abs_act || out->sum_sq_h || out->A) {
         if (es == 4) hipLaunchKernelGGL(k_prefix_reduce<4>, dim3((F + 3) / 4), dim3(256), 0, stream,
                                         (const char *)layer->w_down, d, F, part, n_tm, *out);

@@ -29,11 +29,12 @@ def clada():
     return m
 
 
-def _setup(clada, cfg_name, d, F, T, seed=0, layer_id=2):
+def _setup(clada, cfg_name, d, F, T, seed=0, layer_id=2, tile=0):
     cfg = synth.CONFIGS[cfg_name]
     w = synth.layer_weights(cfg, seed, layer_id, d=d, d_ff=F)
     X = synth.prefix_hidden(cfg, seed, layer_id, T=T, d=d)
     ctx = clada.Context(0, clada.workspace_bytes(d, F, 0, T, 0))
+    ctx.set_option("prefix.tile", tile)
     layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
     return cfg, w, X, ctx, layer, to_dev(X, cfg.dtype)
 
@@ -47,21 +48,24 @@ def _cett_given_cut(w, X, cut):
     return np.where(nd > 0, np.linalg.norm(y_cut, axis=1) / np.where(nd > 0, nd, 1.0), 0.0)
 
 
+# last entry: option prefix.tile (0 = the library's choice, 2 = the 256-row tiles of both prefill GEMMs)
 CASES = [
-    ("c1", 512, 1376, 64),       # config 1 as written (fp32)
-    ("c1", 96, 200, 130),        # ragged in every dimension
-    ("c1", 8, 5, 1),             # one token
-    ("c2", 1024, 1000, 300),     # bf16, ragged tiles
-    ("c2", 72, 129, 257),
+    ("c1", 512, 1376, 64, 0),    # config 1 as written (fp32)
+    ("c1", 96, 200, 130, 0),     # ragged in every dimension
+    ("c1", 8, 5, 1, 0),          # one token
+    ("c2", 1024, 1000, 300, 0),  # bf16, ragged tiles
+    ("c2", 72, 129, 257, 0),
+    ("c2", 512, 416, 300, 2),    # 256 x 256 down-projection tiles: 13 k-tiles of 32, d_ff not a multiple of 64
+    ("c2", 256, 64, 257, 2),     # two k-tiles; the second token tile holds one token
 ]
 
 
-@pytest.mark.parametrize("cfg_name,d,F,T", CASES)
-def test_cett_eval_parity(clada, cfg_name, d, F, T):
+@pytest.mark.parametrize("cfg_name,d,F,T,tile", CASES)
+def test_cett_eval_parity(clada, cfg_name, d, F, T, tile):
     """The device's cut set is read off the device's own |a| pool (the same kernel feeds the masking
     pass), validated against the oracle's inside the band around eps, and the oracle is evaluated on
     that set: a neuron within rounding of eps may fall on either side, everything else is fixed."""
-    cfg, w, X, ctx, layer, Xd = _setup(clada, cfg_name, d, F, T)
+    cfg, w, X, ctx, layer, Xd = _setup(clada, cfg_name, d, F, T, tile=tile)
     a_ref = oracle.prefix_stats(*w, X, want_y=False)["abs_act_pool"]
     pool_ref = np.sort(a_ref.ravel())
     pool_gpu = clada.prefix_stats(ctx, layer, Xd, want_y=False).abs_act_pool.cpu().numpy()
@@ -73,7 +77,9 @@ def test_cett_eval_parity(clada, cfg_name, d, F, T):
         cut_gpu = pool_gpu < np.float32(eps)
         cut_ref = a_ref < eps
         flips = cut_gpu != cut_ref
-        assert not (flips & (np.abs(a_ref - eps) > BAND * eps)).any(), "cut sets differ outside the band"
+        # the band is relative to eps; for the smallest pool value (q = 0, eps ~ 1e-7) the fp32 accumulation
+        # error of the pre-activation (~1e-8 absolute) is what decides, hence the absolute term
+        assert not (flips & (np.abs(a_ref - eps) > BAND * eps + 2e-7)).any(), "cut sets differ outside the band"
         ref = _cett_given_cut(w, X, cut_gpu)
         np.testing.assert_allclose(to_np(got), ref, rtol=tol, atol=1e-6, err_msg=f"q={q}")
         assert float(mean.item()) == pytest.approx(ref.mean(), rel=tol, abs=1e-6)
@@ -86,10 +92,10 @@ def test_cett_eval_parity(clada, cfg_name, d, F, T):
     np.testing.assert_allclose(to_np(got), 1.0, rtol=1e-6)
 
 
-@pytest.mark.parametrize("cfg_name,d,F,T", CASES)
+@pytest.mark.parametrize("cfg_name,d,F,T,tile", CASES)
 @pytest.mark.parametrize("bound", [0.2, 0.05])
-def test_cett_search_parity(clada, cfg_name, d, F, T, bound):
-    cfg, w, X, ctx, layer, Xd = _setup(clada, cfg_name, d, F, T)
+def test_cett_search_parity(clada, cfg_name, d, F, T, tile, bound):
+    cfg, w, X, ctx, layer, Xd = _setup(clada, cfg_name, d, F, T, tile=tile)
     tau_d, mean_d = clada.threshold_search_cett(ctx, layer, Xd, bound)
     torch.cuda.synchronize()
     tau, mean = float(tau_d.item()), float(mean_d.item())
