@@ -77,8 +77,8 @@ const char *clada_last_error(const clada_ctx *ctx);
  * generic kernels), "decode.spin_limit" (how often a balanced batch-1 kernel polls
  * for the other workgroups' masks before it gives up; default 2^21, about two
  * seconds; 0 = give up without polling; see clada_device_fault), "prefix.tile" (workgroup
- * tile of the bf16 prefill gate/up GEMM: 1 = 128 tokens x 128 neurons, 2 = 256 x 128,
- * 0 = 256 x 128 for more than 128 prefix tokens [default]), "diag.kernel_events" (1 = every decode call also
+ * tiles of the bf16 prefill GEMMs: 1 = 128 tokens, 2 = 256 tokens wherever the shape
+ * allows, 0 = chosen by shape [default]), "diag.kernel_events" (1 = every decode call also
  * records HIP events around its kernels for clada_diag_kernel_times; default 0).
  * Unknown names or out-of-range values give CLADA_ERR_VALUE and change nothing. */
 clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);
