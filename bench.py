@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--tau-h", type=float, default=None, help="fix the entropy threshold (default: median of the run's own stream)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run only a short fixed call sequence (for rocprofv3 --pmc counter runs) and exit")
+    ap.add_argument("--prefill-probe", action="store_true",
+                    help="run only the prefill of one layer, on the synthetic operands and on all-zero ones, and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (see DESIGN.md, sharding note)",
@@ -66,6 +68,8 @@ def main():
         cfg = dataclasses.replace(cfg, q=args.q or cfg.q, B=args.batch or cfg.B)
     if args.pmc_probe:
         return pmc_probe(cfg, args, clada, binding, synth, torch, dev)
+    if args.prefill_probe:
+        return prefill_probe(cfg, args, clada, synth, torch, dev)
     L = args.layers or cfg.L
     d, F, B, T, V = cfg.d, cfg.d_ff, cfg.B, cfg.T, cfg.V
     K, W = args.steps, args.warmup
@@ -442,6 +446,41 @@ def pmc_probe(cfg, args, clada, binding, synth, torch, dev):
         binding.diag_copy(ctx, src, dst)
     torch.cuda.synchronize()
     print(f"pmc-probe copy bytes {src.numel()}")
+
+
+def prefill_probe(cfg, args, clada, synth, torch, dev):
+    """Prefill of one layer of the configuration (gate/up and down GEMMs, aggregates, no calibration), three
+    timed repetitions on the seeded synthetic operands and three on all-zero operands of the same shape.
+    The zero run does the same instructions on operands that toggle no bits: the difference is what the
+    power limit costs the matrix-core kernels.  Prints one JSON line."""
+    d, F, T = cfg.d, cfg.d_ff, cfg.T
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 0, T, 0))
+    for opt in args.option:
+        k, v = opt.split("=")
+        ctx.set_option(k, int(v))
+
+    def to_dev(a):
+        if cfg.dtype == "bf16":
+            return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+
+    w = [to_dev(a) for a in synth.layer_weights(cfg, args.seed, 0)]
+    X = to_dev(synth.prefix_hidden(cfg, args.seed, 0))
+    out = {"workload": f"{args.config}: prefill of one layer, T={T}, d={d}, d_ff={F}, {cfg.dtype}", "reps": 3}
+    for name, ws, x in (("synthetic", w, X), ("zeros", [torch.zeros_like(a) for a in w], torch.zeros_like(X))):
+        layer = clada.Layer(*ws)
+        for want_y in (False, True):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for r in range(4):
+                if r == 1:
+                    e0.record()
+                clada.prefix_stats(ctx, layer, x, want_y=want_y, want_pool=True)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 3
+            flop = (6.0 if want_y else 4.0) * T * d * F
+            out[f"{name}_{'with_y' if want_y else 'without_y'}"] = {"ms": round(ms, 3), "tflops": round(flop / ms / 1e9, 1)}
+    print(json.dumps(out))
 
 
 def _traffic():
