@@ -34,6 +34,7 @@ def _rel(a, b):
     ("c2", 320, 64, 129),        # ten k-tiles; second half of the only 256-token tile holds one token
     ("c2", 512, 700, 1024),      # 8 token tiles: the blocked tile order, 6 neuron tiles padded to 8
     ("c2", 256, 384, 2000),      # 16 token tiles (last one ragged), 3 neuron tiles
+    ("c2", 64, 40, 1),           # bf16, one token: every row of a tile repeats it
     ("c2", 512, 32, 300),        # a single 32-deep k-tile in the 256 x 256 down projection
     ("c2", 768, 96, 520),        # three column tiles, three k-tiles
 ])
