@@ -61,6 +61,15 @@ def num_threads() -> int:
     return int(_load().clada_oracle_num_threads())
 
 
+SIGMAS = {"silu": 0, "gelu_tanh": 1}
+
+
+def _set_sigma(sigma):
+    """Select sigma of the gated FFN for the next call: "silu" (LLaMA / Mistral) or "gelu_tanh" (Gemma)."""
+    rc = _load().clada_oracle_set_sigma(SIGMAS[sigma])
+    assert rc == 0, rc
+
+
 def _weights(w_gate, w_up, w_down):
     wg, pg = _f32(w_gate)
     wu, pu = _f32(w_up)
@@ -70,7 +79,7 @@ def _weights(w_gate, w_up, w_down):
     return (wg, wu, wd), (pg, pu, pd), d, F
 
 
-def prefix_stats(w_gate, w_up, w_down, x, want_y=True, want_pool=True):
+def prefix_stats(w_gate, w_up, w_down, x, want_y=True, want_pool=True, sigma="silu"):
     """Dense FFN over the prefix x [T][d] and the per-neuron aggregates."""
     keep, (pg, pu, pd), d, F = _weights(w_gate, w_up, w_down)
     xx, px = _f32(x)
@@ -79,6 +88,7 @@ def prefix_stats(w_gate, w_up, w_down, x, want_y=True, want_pool=True):
     y, py = _out((T, d)) if want_y else (None, None)
     pool, pp = _out((T, F)) if want_pool else (None, None)
     outs = [_out((F,)) for _ in range(5)]
+    _set_sigma(sigma)
     rc = _load().clada_oracle_prefix_stats(pg, pu, pd, d, F, px, T, py,
                                            *[o[1] for o in outs], pp)
     assert rc == 0, rc
@@ -132,18 +142,19 @@ def threshold(tau_base, lam, gam, surprisal, entropy, tau_s, tau_H):
     return out
 
 
-def gate_act(w_gate, x):
+def gate_act(w_gate, x, sigma="silu"):
     wg, pg = _f32(w_gate)
     xx, px = _f32(np.atleast_2d(x))
     F, d = wg.shape
     B = xx.shape[0]
     act, pa = _out((B, F))
+    _set_sigma(sigma)
     rc = _load().clada_oracle_gate_act(pg, d, F, px, B, pa)
     assert rc == 0, rc
     return act
 
 
-def sparse_decode(w_gate, w_up, w_down, x, tau):
+def sparse_decode(w_gate, w_up, w_down, x, tau, sigma="silu"):
     """One layer's thresholded sparse FFN for x [B][d], tau [B]."""
     keep, (pg, pu, pd), d, F = _weights(w_gate, w_up, w_down)
     xx, px = _f32(np.atleast_2d(x))
@@ -156,36 +167,39 @@ def sparse_decode(w_gate, w_up, w_down, x, tau):
     mask, pm = _out((B, F), np.uint8)
     idx, pi = _out((F,), np.int32)
     na, pn = _out((1 + B,), np.int32)
+    _set_sigma(sigma)
     rc = _load().clada_oracle_sparse_decode(pg, pu, pd, d, F, px, B, pt, py, pa, pm, pi, pn)
     assert rc == 0, rc
     return {"y": y, "act": act, "mask": mask.astype(bool), "active_idx": idx[: na[0]].copy(),
             "n_active": na}
 
 
-def decode_given_mask(w_gate, w_up, w_down, x, mask):
+def decode_given_mask(w_gate, w_up, w_down, x, mask, sigma="silu"):
     keep, (pg, pu, pd), d, F = _weights(w_gate, w_up, w_down)
     xx, px = _f32(np.atleast_2d(x))
     B = xx.shape[0]
     m = np.ascontiguousarray(np.atleast_2d(mask), dtype=np.uint8)
     assert m.shape == (B, F)
     y, py = _out((B, d))
+    _set_sigma(sigma)
     rc = _load().clada_oracle_decode_given_mask(pg, pu, pd, d, F, px, B,
                                                 m.ctypes.data_as(C.POINTER(C.c_uint8)), py)
     assert rc == 0, rc
     return y
 
 
-def dense_decode(w_gate, w_up, w_down, x):
+def dense_decode(w_gate, w_up, w_down, x, sigma="silu"):
     keep, (pg, pu, pd), d, F = _weights(w_gate, w_up, w_down)
     xx, px = _f32(np.atleast_2d(x))
     B = xx.shape[0]
     y, py = _out((B, d))
+    _set_sigma(sigma)
     rc = _load().clada_oracle_dense_decode(pg, pu, pd, d, F, px, B, py)
     assert rc == 0, rc
     return y
 
 
-def cett(w_gate, w_up, w_down, x, eps):
+def cett(w_gate, w_up, w_down, x, eps, sigma="silu"):
     """Per-token CETT of the validation tokens x [T][d] at cut threshold eps, and its mean."""
     keep, (pg, pu, pd), d, F = _weights(w_gate, w_up, w_down)
     xx, px = _f32(x)
@@ -193,12 +207,13 @@ def cett(w_gate, w_up, w_down, x, eps):
     assert xx.shape == (T, d)
     out, po = _out((T,))
     mean = C.c_double()
+    _set_sigma(sigma)
     rc = _load().clada_oracle_cett(pg, pu, pd, d, F, px, T, C.c_double(float(eps)), po, C.byref(mean))
     assert rc == 0, rc
     return out, mean.value
 
 
-def cett_search(w_gate, w_up, w_down, x, bound=0.2):
+def cett_search(w_gate, w_up, w_down, x, bound=0.2, sigma="silu"):
     """(tau_base, mean CETT at tau_base, rc): the largest eps whose mean CETT over x [T][d] is <= bound.
     rc 0 = attained at a pooled magnitude, 3 = unbounded (tau = inf), 4 = nothing feasible."""
     keep, (pg, pu, pd), d, F = _weights(w_gate, w_up, w_down)
@@ -206,6 +221,7 @@ def cett_search(w_gate, w_up, w_down, x, bound=0.2):
     T = xx.shape[0]
     assert xx.shape == (T, d)
     tau, mean = C.c_double(), C.c_double()
+    _set_sigma(sigma)
     rc = _load().clada_oracle_cett_search(pg, pu, pd, d, F, px, T, C.c_double(float(bound)),
                                           C.byref(tau), C.byref(mean))
     assert rc in (0, 3, 4), rc

@@ -11,6 +11,11 @@ def silu(g):
     return g / (1.0 + math.exp(-g))
 
 
+def gelu_tanh(g):
+    """Tanh form of GELU, the gate activation of the Gemma model in the paper's experiments."""
+    return 0.5 * g * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (g + 0.044715 * g ** 3)))
+
+
 def dot(u, v):
     s = 0.0
     for a, b in zip(u, v):
@@ -18,20 +23,20 @@ def dot(u, v):
     return s
 
 
-def neuron_terms(w_gate, w_up, x):
+def neuron_terms(w_gate, w_up, x, sigma=silu):
     """(a_j, u_j, h_j) of every neuron for one token x."""
     out = []
     for wg, wu in zip(w_gate, w_up):
-        a = silu(dot(wg, x))
+        a = sigma(dot(wg, x))
         u = dot(wu, x)
         out.append((a, u, a * u))
     return out
 
 
-def ffn_for_subset(w_gate, w_up, w_down, x, subset):
+def ffn_for_subset(w_gate, w_up, w_down, x, subset, sigma=silu):
     """y = sum_{j in subset} h_j * W_down[j,:], j ascending."""
     d = len(x)
-    terms = neuron_terms(w_gate, w_up, x)
+    terms = neuron_terms(w_gate, w_up, x, sigma)
     y = [0.0] * d
     for j in sorted(subset):
         h = terms[j][2]
@@ -40,9 +45,9 @@ def ffn_for_subset(w_gate, w_up, w_down, x, subset):
     return y
 
 
-def kept_set(w_gate, x, tau):
-    """Neurons with |SiLU(gate)| >= tau (cut iff strictly below)."""
-    return [j for j, wg in enumerate(w_gate) if abs(silu(dot(wg, x))) >= tau]
+def kept_set(w_gate, x, tau, sigma=silu):
+    """Neurons with |sigma(gate)| >= tau (cut iff strictly below)."""
+    return [j for j, wg in enumerate(w_gate) if abs(sigma(dot(wg, x))) >= tau]
 
 
 def all_subset_outputs(w_gate, w_up, w_down, x):

@@ -41,6 +41,25 @@
  * FFNs: sigma(g) = g * sigmoid(g) = g / (1 + exp(-g)). */
 static double silu(double g) { return g / (1.0 + exp(-g)); }
 
+/* sigma of the GELU-gated FFN (the Gemma model of the paper's experiments), in the tanh
+ * form that model's public configuration names:
+ *   GELU(g) = g/2 * (1 + tanh(sqrt(2/pi) * (g + 0.044715 g^3))). */
+static double gelu_tanh(double g)
+{
+    return 0.5 * g * (1.0 + tanh(0.7978845608028654 * (g + 0.044715 * g * g * g)));
+}
+
+/* Which sigma the gated functions below use: 0 = SiLU (default), 1 = tanh-form GELU.
+ * Set by the Python wrapper before every call from its own `sigma` argument. */
+static int g_sigma = 0;
+int clada_oracle_set_sigma(int kind)
+{
+    if (kind != 0 && kind != 1) return 1;
+    g_sigma = kind;
+    return 0;
+}
+static double sigma_act(double g) { return g_sigma == 1 ? gelu_tanh(g) : silu(g); }
+
 static double dot_fd(const float *w, const float *x, int n)
 {
     double s = 0.0;
@@ -63,7 +82,7 @@ int clada_oracle_num_threads(void)
  * prefill phase.)
  *
  *   g_tj = W_gate[j,:] . X[t,:]      u_tj = W_up[j,:] . X[t,:]
- *   a_tj = SiLU(g_tj)                h_tj = a_tj * u_tj
+ *   a_tj = sigma(g_tj)               h_tj = a_tj * u_tj
  *   Y[t,:] = sum_j h_tj * W_down[j,:]
  *   sum_abs_act[j] = sum_t |a_tj|    sum_sq_act[j] = sum_t a_tj^2
  *   max_abs_act[j] = max_t |a_tj|    sum_sq_h[j]   = sum_t h_tj^2
@@ -94,7 +113,7 @@ int clada_oracle_prefix_stats(const float *w_gate, const float *w_up,
             const float *xt = x + (size_t)t * d;
             double g = dot_fd(wg, xt, d);
             double u = dot_fd(wu, xt, d);
-            double a = silu(g);
+            double a = sigma_act(g);
             double hv = a * u;
             double aa = fabs(a);
             s_abs += aa;
@@ -237,7 +256,7 @@ int clada_oracle_gate_act(const float *w_gate, int d, int d_ff, const float *x,
         const float *xb = x + (size_t)b * d;
 #pragma omp parallel for schedule(static)
         for (int j = 0; j < d_ff; ++j)
-            act[(size_t)b * d_ff + j] = silu(dot_fd(w_gate + (size_t)j * d, xb, d));
+            act[(size_t)b * d_ff + j] = sigma_act(dot_fd(w_gate + (size_t)j * d, xb, d));
     }
     return 0;
 }
@@ -260,7 +279,7 @@ static void ffn_given_mask(const float *w_gate, const float *w_up,
                 continue;
             }
             double a = act_in ? act_in[(size_t)b * d_ff + j]
-                              : silu(dot_fd(w_gate + (size_t)j * d, xb, d));
+                              : sigma_act(dot_fd(w_gate + (size_t)j * d, xb, d));
             double u = dot_fd(w_up + (size_t)j * d, xb, d);
             h[j] = a * u;
         }
@@ -391,7 +410,7 @@ int clada_oracle_cett(const float *w_gate, const float *w_up, const float *w_dow
         double *full = (double *)calloc((size_t)d, sizeof(double));
         if (!cut || !full) { bad = 1; free(cut); free(full); continue; }
         for (int j = 0; j < d_ff; ++j) {
-            double a = silu(dot_fd(w_gate + (size_t)j * d, xt, d));
+            double a = sigma_act(dot_fd(w_gate + (size_t)j * d, xt, d));
             double u = dot_fd(w_up + (size_t)j * d, xt, d);
             double h = a * u;
             const float *wd = w_down + (size_t)j * d;
@@ -465,7 +484,7 @@ int clada_oracle_cett_search(const float *w_gate, const float *w_up, const float
         const float *xt = x + (size_t)t * d;
         double *full = c + (size_t)t * d;                 /* borrowed as the dense sum, cleared below */
         for (int j = 0; j < d_ff; ++j) {
-            double a = silu(dot_fd(w_gate + (size_t)j * d, xt, d));
+            double a = sigma_act(dot_fd(w_gate + (size_t)j * d, xt, d));
             double u = dot_fd(w_up + (size_t)j * d, xt, d);
             double hv = a * u;
             h[(size_t)t * d_ff + j] = hv;

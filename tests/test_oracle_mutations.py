@@ -10,6 +10,7 @@ import pytest
 import oracle
 import test_oracle_cett as t_cett
 import test_oracle_ffn as t_ffn
+import test_oracle_geglu as t_geglu
 import test_oracle_relu as t_relu
 import test_oracle_signals as t_sig
 import test_oracle_static_mask as t_mask
@@ -51,6 +52,13 @@ MASK_PINS = [
     lambda: t_mask.test_threshold_matches_numpy(),
     lambda: t_mask.test_topk_hand_cases(),
     lambda: t_mask.test_topk_matches_numpy_and_python(0),
+]
+GEGLU_PINS = [
+    lambda: t_geglu.test_sigma_values_closed_forms(),
+    lambda: t_geglu.test_matches_library_gelu(0),
+    lambda: t_geglu.test_limits_and_brute_force_masks(),
+    lambda: t_geglu.test_cett_with_gelu_sigma(),
+    lambda: t_geglu.test_sigma_argument_does_not_leak_between_calls(),
 ]
 RELU_PINS = [
     lambda: t_relu.test_hand_case(),
@@ -114,6 +122,14 @@ MUTATIONS = [
      "double g = dot_fd(w_in + (size_t)j * d, xb, d);", RELU_PINS),
     ("ReLU FFN without the output bias",
      "            yb[i] = s + (b_out ? (double)b_out[i] : 0.0);", "            yb[i] = s;", RELU_PINS),
+    ("GELU's cubic coefficient off by a factor of ten",
+     "(g + 0.044715 * g * g * g)", "(g + 0.44715 * g * g * g)", GEGLU_PINS),
+    ("GELU without the factor one half",
+     "return 0.5 * g * (1.0 + tanh(", "return g * (1.0 + tanh(", GEGLU_PINS),
+    ("GELU with 1 - tanh",
+     "return 0.5 * g * (1.0 + tanh(", "return 0.5 * g * (1.0 - tanh(", GEGLU_PINS),
+    ("sigma selector ignored: SiLU whatever is asked for",
+     "return g_sigma == 1 ? gelu_tanh(g) : silu(g);", "return silu(g);", GEGLU_PINS),
     ("ReLU replaced by the identity",
      "            double v = g > 0.0 ? g : (g != g ? g : 0.0);          /* NaN stays NaN */", "            double v = g;", RELU_PINS),
 ]
@@ -151,6 +167,6 @@ def test_planted_mistake_is_caught(tmp_path, what, find, repl, pins):
 
 
 def test_unmutated_oracle_passes_every_pin_used_above():
-    for pins in (FFN_PINS, SIGNAL_PINS, CETT_PINS, MASK_PINS, RELU_PINS):
+    for pins in (FFN_PINS, SIGNAL_PINS, CETT_PINS, MASK_PINS, RELU_PINS, GEGLU_PINS):
         for pin in pins:
             pin()
