@@ -76,6 +76,7 @@ def main():
     nsteps = K + W
     es = 2 if cfg.dtype == "bf16" else 4
     relu = cfg.name.startswith("opt")           # non-gated ReLU FFN family: two matrices + biases
+    geglu = cfg.name.startswith("gemma")        # gated family with sigma = tanh-form GELU
     nmat = 2 if relu else 3                     # matrices a dense call reads
     tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     t_setup = time.time()
@@ -111,7 +112,7 @@ def main():
                 layers[l] = clada.Layer(ts[0], None, ts[1], kind=binding.RELU,
                                         b_in=torch.from_numpy(biases[0]).to(dev), b_out=torch.from_numpy(biases[1]).to(dev))
             else:
-                layers[l] = clada.Layer(*ts)
+                layers[l] = clada.Layer(*ts, kind=binding.GEGLU if geglu else binding.SWIGLU)
     x_host = np.stack([np.stack([synth.decode_hidden(cfg, args.seed, l, s, shared_frac=args.shared_frac)
                                  for l in range(L)]) for s in range(nsteps)])
     x_all = to_dev(x_host.reshape(nsteps, L, B, d))                       # [step][layer][B][d]
@@ -398,7 +399,7 @@ def main():
                 if relu:
                     oracle.relu_decode(*host_w[l], x_host[s, l], tau=tf[l])
                 else:
-                    oracle.sparse_decode(*host_w[l], x_host[s, l], tf[l])
+                    oracle.sparse_decode(*host_w[l], x_host[s, l], tf[l], sigma="gelu_tanh" if geglu else "silu")
                 t_used += time.perf_counter() - t0
                 n_done += 1
             if t_used > budget:

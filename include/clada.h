@@ -106,8 +106,12 @@ size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int3
  * For it w_gate holds W_in [d_ff][d], w_down holds W_out neuron-major [d_ff][d]
  * (HF fc2.weight transposed), w_up is ignored; b_in [d_ff] and b_out [d] are fp32
  * device arrays or NULL (zero).  Supported by clada_prefix_stats (h = a), the decode
- * calls and clada_static_ffn_decode; the CETT calls return CLADA_ERR_VALUE for it. */
-typedef enum { CLADA_FFN_SWIGLU = 0, CLADA_FFN_RELU = 1 } clada_ffn_kind;
+ * calls and clada_static_ffn_decode; the CETT calls return CLADA_ERR_VALUE for it.
+ * CLADA_FFN_GEGLU: the gated FFN of the Gemma model the paper also evaluates -- as
+ * CLADA_FFN_SWIGLU in every respect (three matrices, no biases, every entry point)
+ * except sigma = GELU in its tanh form,
+ *   sigma(g) = g/2 (1 + tanh(sqrt(2/pi) (g + 0.044715 g^3))). */
+typedef enum { CLADA_FFN_SWIGLU = 0, CLADA_FFN_RELU = 1, CLADA_FFN_GEGLU = 2 } clada_ffn_kind;
 
 typedef struct {
     const void *w_gate, *w_up, *w_down; /* device, each [d_ff][d] neuron-major */

@@ -27,7 +27,7 @@ class CladaError(RuntimeError):
         super().__init__(f"{name}: {text}")
 
 
-SWIGLU, RELU = 0, 1      # clada_ffn_kind
+SWIGLU, RELU, GEGLU = 0, 1, 2      # clada_ffn_kind
 
 
 class _CLayer(C.Structure):
@@ -147,7 +147,7 @@ class Context:
 
 @dataclass
 class Layer:
-    """Neuron-major weights of one FFN layer, each [d_ff][d] on the GPU.  kind = SWIGLU (gated SiLU:
+    """Neuron-major weights of one FFN layer, each [d_ff][d] on the GPU.  kind = SWIGLU or GEGLU (gated, sigma = SiLU or tanh-form GELU:
     w_gate, w_up, w_down) or RELU (non-gated, OPT family: w_gate = W_in, w_up = None, w_down = W_out
     neuron-major, optional fp32 biases b_in [d_ff], b_out [d])."""
     w_gate: torch.Tensor

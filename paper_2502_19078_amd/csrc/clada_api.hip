@@ -22,9 +22,9 @@ clada_status clada_fail(clada_ctx *ctx, clada_status s, const char *fmt, ...)
 clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer)
 {
     if (!layer) return clada_fail(ctx, CLADA_ERR_NULL, "layer is NULL");
-    if (layer->kind != CLADA_FFN_SWIGLU && layer->kind != CLADA_FFN_RELU)
+    if (layer->kind != CLADA_FFN_SWIGLU && layer->kind != CLADA_FFN_RELU && layer->kind != CLADA_FFN_GEGLU)
         return clada_fail(ctx, CLADA_ERR_VALUE, "unknown FFN kind %d", (int)layer->kind);
-    if (!layer->w_gate || !layer->w_down || (layer->kind == CLADA_FFN_SWIGLU && !layer->w_up))
+    if (!layer->w_gate || !layer->w_down || (layer->kind != CLADA_FFN_RELU && !layer->w_up))
         return clada_fail(ctx, CLADA_ERR_NULL, "a weight pointer is NULL");
     if (layer->dtype != CLADA_F32 && layer->dtype != CLADA_BF16)
         return clada_fail(ctx, CLADA_ERR_DTYPE, "unknown dtype %d", (int)layer->dtype);
@@ -38,7 +38,7 @@ clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer)
     if (rowbytes > 16384)
         return clada_fail(ctx, CLADA_ERR_SHAPE, "row of %zu bytes exceeds 16384", rowbytes);
     if (!aligned16(layer->w_gate) || !aligned16(layer->w_down) ||
-        (layer->kind == CLADA_FFN_SWIGLU && !aligned16(layer->w_up)))
+        (layer->kind != CLADA_FFN_RELU && !aligned16(layer->w_up)))
         return clada_fail(ctx, CLADA_ERR_ALIGN, "weight pointers must be 16-byte aligned");
     if (layer->kind == CLADA_FFN_RELU && ((((uintptr_t)layer->b_in) & 3u) || !aligned16(layer->b_out)))
         return clada_fail(ctx, CLADA_ERR_ALIGN, "b_in must be 4-byte and b_out 16-byte aligned");
@@ -47,8 +47,8 @@ clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer)
 
 clada_status clada_require_swiglu(clada_ctx *ctx, const clada_layer *layer, const char *call)
 {
-    if (layer->kind != CLADA_FFN_SWIGLU)
-        return clada_fail(ctx, CLADA_ERR_VALUE, "%s supports the gated SiLU FFN only", call);
+    if (layer->kind == CLADA_FFN_RELU)
+        return clada_fail(ctx, CLADA_ERR_VALUE, "%s supports the gated FFN families only", call);
     return CLADA_OK;
 }
 

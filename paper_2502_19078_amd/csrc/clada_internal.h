@@ -161,4 +161,15 @@ __device__ __forceinline__ float wave_max(float v)
 
 // SiLU(g) = g * sigmoid(g), fp32.
 __device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + expf(-g)); }
+
+// Tanh-form GELU, g/2 (1 + tanh(sqrt(2/pi) (g + 0.044715 g^3))), evaluated as g * sigmoid(2 u):
+// 1 + tanh(u) = 2 sigmoid(2u), so no tanh is needed and the +-inf limits come out as for SiLU.
+__device__ __forceinline__ float gelu_tanh_f32(float g)
+{
+    const float u2 = 1.5957691216057308f * fmaf(0.044715f * g, g * g, g);
+    return g / (1.0f + expf(-u2));
+}
+
+// sigma of the gated families: SiLU (LLaMA / Mistral) or tanh-form GELU (Gemma)
+__device__ __forceinline__ float gate_sigma_f32(float g, int gelu) { return gelu ? gelu_tanh_f32(g) : silu_f32(g); }
 #endif

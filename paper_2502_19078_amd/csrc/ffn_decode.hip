@@ -35,14 +35,15 @@ struct DecodeParams {
     const int *n_list;          // LIST: their count, device
     const float *b_in;          // RELU: input bias [F] or nullptr
     int d, F, ni_max;
+    int gelu;                   // gated family: sigma = tanh-form GELU instead of SiLU
 };
 
-// Activation of the two FFN families: SiLU(g) for the gated FFN; for the non-gated one
-// max(0, g + bias) (a NaN pre-activation stays NaN).
+// Activation of the FFN families: sigma(g) (SiLU or tanh-form GELU) for the gated FFN; for the
+// non-gated one max(0, g + bias) (a NaN pre-activation stays NaN).
 template <bool RELU>
-__device__ __forceinline__ float ffn_act(float g, const float *b_in, size_t j)
+__device__ __forceinline__ float ffn_act(float g, const float *b_in, size_t j, int gelu)
 {
-    if (!RELU) return silu_f32(g);
+    if (!RELU) return gate_sigma_f32(g, gelu);
     if (b_in) g += b_in[j];
     return g > 0.0f ? g : (g != g ? g : 0.0f);
 }
@@ -118,7 +119,7 @@ k_ffn_decode(const DecodeParams p)
             }
             s = wave_sum(s);
             const int i = i0 + r;
-            const float a = ffn_act<RELU>(s, p.b_in, neuron(i < ni ? i : i0));
+            const float a = ffn_act<RELU>(s, p.b_in, neuron(i < ni ? i : i0), p.gelu);
             const bool keep = DENSE ? true : (fabsf(a) >= tau);
             if (lane == 0 && i < ni) {
                 s_a[i] = a;
@@ -439,6 +440,7 @@ struct B1Params {
     int *fault;                 // set to 1 when a balanced call gives up waiting for the other workgroups
     int max_spins;              // polls of the other workgroups' records before giving up
     int d, F, K0;
+    int gelu;                   // gated family: sigma = tanh-form GELU instead of SiLU
 };
 
 // Exclusive prefix sum over the 64 lanes of a wave (no barrier); *total gets the wave sum.
@@ -515,7 +517,7 @@ k_ffn_decode_b1(const B1Params p)
 #pragma unroll
         for (int c = 0; c < NCH; ++c) s = dot16<ES>(buf[c], xr[c], s);
         s = wave_sum(s);
-        const float a = ffn_act<RELU>(s, p.b_in, (size_t)(blk + P * i));
+        const float a = ffn_act<RELU>(s, p.b_in, (size_t)(blk + P * i), p.gelu);
         const bool keep = DENSE ? true : (fabsf(a) >= tau);
         if (lane == 0) {
             s_a[i] = a;
@@ -865,6 +867,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     p.partial = reinterpret_cast<float *>(ws);
     p.keep = lists ? reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256)) : nullptr;
     p.idx = nullptr; p.n_list = nullptr; p.b_in = nullptr;
+    p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
     p.d = d; p.F = F; p.ni_max = (F + P - 1) / P;
     hipStream_t stream = (hipStream_t)hip_stream;
 
@@ -893,6 +896,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             b.max_spins = ctx->opt_decode_spin_limit;
             b.d = d; b.F = F;
             b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
+            b.gelu = p.gelu;
             // Balancing pays when the kept-row phase is long enough to hide the mask exchange behind the
             // workgroup's own first chunk: measured faster on the 7B/8B shapes (90-117 MB per matrix), slower
             // on 52 MB ReLU layers (17.0 vs 14.1 us) and on 8 MB ones (10.0 vs 6.4 us).  With 10 KiB gated rows
@@ -1021,6 +1025,7 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
     p.partial = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
     p.keep = nullptr; p.idx = idx; p.n_list = n_active;
     p.d = d; p.F = F; p.ni_max = (F + P - 1) / P;
+    p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
     const bool relu = layer->kind == CLADA_FFN_RELU;
     p.b_in = relu ? layer->b_in : nullptr;
     const float *b_out = relu ? layer->b_out : nullptr;

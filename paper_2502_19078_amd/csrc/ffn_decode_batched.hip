@@ -39,6 +39,7 @@ struct BatParams {
     unsigned char *keep;        // [B][F] or nullptr
     float *partial;             // [RG][B][d]
     int d, F, B, P, RG, CG;
+    int gelu;                   // sigma = tanh-form GELU instead of SiLU
 };
 
 __device__ __forceinline__ f32x4 mfma16(const u32x4 a, const u32x4 b, const f32x4 c)
@@ -186,7 +187,7 @@ k_bat_gateup(const BatParams p)
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
             const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = j_lo + 16 * i + nn;
-            const float a = silu_f32(tile_sum(i & 1, tid));
+            const float a = gate_sigma_f32(tile_sum(i & 1, tid), p.gelu);
             const bool valid = m < B && j < j_hi;
             const bool keep = valid && (DENSE ? true : (fabsf(a) >= p.tau[m]));
             s_a[i][m][nn] = a;
@@ -439,6 +440,7 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     p.uflag = reinterpret_cast<unsigned char *>(scratch + align_up(sizeof(float) * 16 * (size_t)F, 256));
     p.keep = keep; p.partial = partial;
     p.d = d; p.F = F; p.B = B; p.P = P; p.RG = RG; p.CG = CG;
+    p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
 
 #define CLADA_BAT_CASE(KS)                                                                            \
     if (d == 8 * 32 * KS) {                                                                            \

@@ -17,6 +17,7 @@ struct ListParams {
     const int *idx, *n_list;
     float *partial;             // [P][d]
     int d, F;
+    int gelu;                   // sigma = tanh-form GELU instead of SiLU
 };
 
 constexpr int LIST_MAXSEG = 1024;       // list entries per workgroup
@@ -70,7 +71,7 @@ k_ffn_decode_list(const ListParams p)
             }
         }
     };
-    // h = SiLU(gate . x) * (up . x) of this wave's neuron; x comes from LDS a chunk at a time
+    // h = sigma(gate . x) * (up . x) of this wave's neuron; x comes from LDS a chunk at a time
     auto neuron_h = [&](const u32x4 (&g)[NCH], const u32x4 (&u)[NCH]) {
         float sg = 0.0f, su = 0.0f;
 #pragma unroll
@@ -81,7 +82,7 @@ k_ffn_decode_list(const ListParams p)
         }
         sg = wave_sum(sg);
         su = wave_sum(su);
-        return silu_f32(sg) * su;
+        return gate_sigma_f32(sg, p.gelu) * su;
     };
     auto down_fma = [&](const u32x4 (&dn)[NW][SL], const float *hs, int nvalid) {
 #pragma unroll
@@ -201,6 +202,7 @@ hipError_t clada_decode_list_b1(clada_ctx *ctx, const clada_layer *layer, const 
     ListParams p;
     p.wg = (const char *)layer->w_gate; p.wu = (const char *)layer->w_up; p.wd = (const char *)layer->w_down;
     p.x = (const char *)x; p.idx = idx; p.n_list = n_active; p.partial = partial; p.d = d; p.F = F;
+    p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
     hipError_t e;
     if (es == 2 && nch == 8) e = launch_list<2, 8, true>(p, P, stream);
     else if (es == 2 && nch == 10) e = launch_list<2, 10, false>(p, P, stream);

@@ -86,6 +86,13 @@ __device__ __forceinline__ float silu_prefill(float g)
     return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * g));
 }
 
+// Tanh-form GELU the same way: g * sigmoid(2 sqrt(2/pi) (g + 0.044715 g^3)).
+__device__ __forceinline__ float gelu_prefill(float g)
+{
+    const float u2 = 1.5957691216057308f * fmaf(0.044715f * g, g * g, g);
+    return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * u2));
+}
+
 // Row of accumulator register r of a 32x32 MFMA block held by `lane`.
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
@@ -106,6 +113,7 @@ struct GateUpParams {
     int Fp;             // F rounded up to a multiple of 64
     const float *b_in;  // non-gated family: input bias [F] or nullptr
     int relu;           // non-gated family: a = max(0, C_g + b_in), h = a (wu then aliases wg and C_u is ignored)
+    int gelu;           // gated family: sigma = tanh-form GELU instead of SiLU
 };
 
 // Epilogue of the gate/up GEMM on the accumulators (shared by the fp32 and bf16 kernels):
@@ -132,7 +140,7 @@ __device__ __forceinline__ void gateup_epilogue(const f32x16 (&acc)[2][2][2], co
                     a = g > 0.0f ? g : (g != g ? g : 0.0f);
                     h = a;
                 } else {
-                    a = silu_prefill(acc[0][mb][nb][r]);
+                    a = p.gelu ? gelu_prefill(acc[0][mb][nb][r]) : silu_prefill(acc[0][mb][nb][r]);
                     h = a * acc[1][mb][nb][r];
                 }
                 if (t < p.T && j < p.F) {
@@ -422,7 +430,7 @@ __device__ __forceinline__ void wide_epilogue(const f32x16 (&acc)[2][4][2], cons
                     a = g > 0.0f ? g : (g != g ? g : 0.0f);
                     h = a;
                 } else {
-                    a = silu_prefill(acc[0][mb][nb][r]);
+                    a = p.gelu ? gelu_prefill(acc[0][mb][nb][r]) : silu_prefill(acc[0][mb][nb][r]);
                     h = a * acc[1][mb][nb][r];
                 }
                 aa[r] = fabsf(a);
@@ -1198,6 +1206,7 @@ hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, f
     g.x = (const char *)x; g.wg = (const char *)layer->w_gate;
     g.wu = (const char *)(relu ? layer->w_gate : layer->w_up);
     g.relu = relu ? 1 : 0; g.b_in = relu ? layer->b_in : nullptr;
+    g.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
     g.T = T; g.d = d; g.F = F; g.n_tm = (T + BM - 1) / BM; g.n_tn = (F + BN - 1) / BN;
     g.part = part; g.pool = pool; g.hbuf = hbuf;
     g.Fp = (int)align_up((size_t)F, 64);

@@ -55,6 +55,8 @@ CONFIGS = {
     # list; the target sparsity sits above the 50 % of exact zeros a ReLU produces by itself)
     "o27": Config(6, "opt-2.7b", 32, 2560, 10240, "bf16", 0.02, 1, 512, 50272, 0.70, "zipf", 64),
     "o350": Config(7, "opt-350m", 24, 1024, 4096, "bf16", 0.02, 1, 512, 50272, 0.70, "zipf", 64),
+    # GELU-gated FFN shape of the Gemma-2B model the paper also evaluates (not in the benchmark list)
+    "g2b": Config(8, "gemma-2b", 18, 2048, 16384, "bf16", 0.02, 1, 512, 256000, 0.45, "zipf", 64),
 }
 
 
