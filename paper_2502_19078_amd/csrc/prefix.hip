@@ -1139,8 +1139,8 @@ k_prefix_down_bf16_wide(const DownParams p)
     }
 }
 
-// One wave per neuron: ||W_down[j,:]||^2, then fold the token-tile partials in
-// ascending tile order and write the requested aggregates.
+// One wave per neuron: ||W_down[j,:]||^2, then fold the token-tile partials (fixed order)
+// and write the requested aggregates.
 template <int ES>
 __global__ void __launch_bounds__(256)
 k_prefix_reduce(const char *__restrict__ wd, int d, int F, const float *__restrict__ part, int n_tm,
@@ -1152,25 +1152,45 @@ k_prefix_reduce(const char *__restrict__ wd, int d, int F, const float *__restri
     if (j >= F) return;
     float wn2 = 0.0f;
     if (out.A) {
+        // the row in 16-byte chunks, lane l takes chunks l, l + 64, ...: eight loads in flight at a time
         const char *row = wd + (size_t)j * d * ES;
-        for (int col = lane * VEC; col < d; col += 64 * VEC) {
-            float w[VEC];
-            unpack_row16(*reinterpret_cast<const u32x4 *>(row + (size_t)col * ES), w);
+        const int nchunk = d * ES / 16;
+        for (int c0 = lane; c0 < nchunk; c0 += 8 * 64) {
+            u32x4 v[8];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) wn2 = fmaf(w[e], w[e], wn2);
+            for (int i = 0; i < 8; ++i)
+                v[i] = c0 + 64 * i < nchunk ? *reinterpret_cast<const u32x4 *>(row + (size_t)(c0 + 64 * i) * 16)
+                                            : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float w[VEC];
+                unpack_row16(v[i], w);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) wn2 = fmaf(w[e], w[e], wn2);
+            }
         }
         wn2 = wave_sum(wn2);
     }
+    // token-tile partials: lane l takes tiles l, l + 64, ... (all loads of a wave in flight together),
+    // then the lanes are folded in the fixed order of the wave reductions
+    float s_abs = 0.f, s_sq = 0.f, mx = 0.f, s_h2 = 0.f;
+    for (int tmi = lane; tmi < n_tm; tmi += 64) {
+        const float *src = part + (size_t)tmi * 4 * F + j;
+        s_abs += src[0];
+        s_sq += src[(size_t)F];
+        const float m = src[2 * (size_t)F];
+        mx = (m > mx || m != m) ? m : mx;
+        s_h2 += src[3 * (size_t)F];
+    }
+    s_abs = wave_sum(s_abs);
+    s_sq = wave_sum(s_sq);
+    s_h2 = wave_sum(s_h2);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const float m = __shfl_xor(mx, o);
+        mx = (m > mx || m != m) ? m : mx;                 // a NaN sticks
+    }
     if (lane == 0) {
-        float s_abs = 0.f, s_sq = 0.f, mx = 0.f, s_h2 = 0.f;
-        for (int tmi = 0; tmi < n_tm; ++tmi) {
-            const float *src = part + (size_t)tmi * 4 * F + j;
-            s_abs += src[0];
-            s_sq += src[(size_t)F];
-            const float m = src[2 * (size_t)F];
-            mx = (m > mx || m != m) ? m : mx;
-            s_h2 += src[3 * (size_t)F];
-        }
         if (out.sum_abs_act) out.sum_abs_act[j] = s_abs;
         if (out.sum_sq_act) out.sum_sq_act[j] = s_sq;
         if (out.max_abs_act) out.max_abs_act[j] = mx;
