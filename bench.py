@@ -49,7 +49,7 @@ def main():
                     help="run only the prefill of one layer, on the synthetic operands and on all-zero ones, and exit")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (see DESIGN.md, sharding note)",
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path would shard along d_ff, not built)",
               file=sys.stderr)
         sys.exit(2)
 
