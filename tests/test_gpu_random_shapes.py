@@ -1,0 +1,82 @@
+"""GPU parity on seeded random shapes: the host code picks among several kernels by row length, neuron
+count, batch, dtype and family; this walks that choice with shapes nobody tuned for."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import BAND, DEV, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def clada():
+    import paper_2502_19078_amd as m
+    m.load_library()
+    return m
+
+
+def _cases(n=36):
+    rng = np.random.default_rng(20250219)
+    widths = [512, 1024, 2048, 2560, 4096, 5120]             # whole-KiB bf16 rows: the batch-1 and batched kernels
+    out = []
+    for i in range(n):
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        if rng.random() < 0.55:
+            d = int(rng.choice(widths))
+        else:
+            d = int(rng.integers(1, 160)) * 8                # any row that is a multiple of 16 bytes
+        if dtype == "f32" and d * 4 > 16384:                 # the library's row limit is 16 KiB
+            d = 4096
+        F = int(rng.integers(1, 2600)) if rng.random() < 0.8 else int(rng.integers(2600, 9000))
+        B = int(rng.choice([1, 1, 1, 2, 3, 5, 8, 13, 16, 19]))
+        kind = str(rng.choice(["silu", "silu", "gelu_tanh", "relu"]))
+        q = float(rng.choice([0.0, 0.3, 0.45, 0.7, 0.9]))
+        out.append((i, dtype, d, F, B, kind, q))
+    return out
+
+
+@pytest.mark.parametrize("i,dtype,d,F,B,kind,q", _cases(), ids=lambda v: str(v))
+def test_random_shape_parity(clada, i, dtype, d, F, B, kind, q):
+    from paper_2502_19078_amd import binding
+    cfg = synth.CONFIGS["c2" if dtype == "bf16" else "c1"]
+    x = synth.decode_hidden(cfg, 7, i, 0, B=B, d=d)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, B, 0, 0))
+    xd = to_dev(x, dtype)
+    if kind == "relu":
+        w = synth.relu_layer(cfg, 7, i, d=d, d_ff=F)
+        layer = clada.Layer(to_dev(w[0], dtype), None, to_dev(w[2], dtype), kind=binding.RELU,
+                            b_in=torch.from_numpy(w[1]).to(DEV), b_out=torch.from_numpy(w[3]).to(DEV))
+        act = oracle.relu_decode(*w, x)["act"]
+        run = lambda tau=None, mask=None: oracle.relu_decode(*w, x, tau=tau, mask=mask)
+    else:
+        w = synth.layer_weights(cfg, 7, i, d=d, d_ff=F)
+        layer = clada.Layer(*[to_dev(a, dtype) for a in w], kind=binding.GEGLU if kind == "gelu_tanh" else binding.SWIGLU)
+        act = np.abs(oracle.gate_act(w[0], x, sigma=kind))
+        def run(tau=None, mask=None):
+            if mask is not None:
+                return {"y": oracle.decode_given_mask(*w, x, mask, sigma=kind)}
+            return oracle.sparse_decode(*w, x, tau, sigma=kind)
+    tau = np.quantile(act, q, axis=1).astype(np.float32) * np.resize(np.array([1.0, 1.8, 1.12], np.float32), B)
+    if kind == "relu" and q > 0:
+        tau = np.maximum(tau, np.float32(1e-6))
+    y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, torch.from_numpy(tau).to(DEV), want_lists=True)
+    torch.cuda.synchronize()
+    ref = run(tau=tau.astype(np.float64))
+    mask_gpu = unpack_bits(bits, F)
+    band = np.abs(np.abs(ref["act"]) - tau[:, None]) <= BAND * np.maximum(tau[:, None], 1e-30)
+    assert not ((mask_gpu != ref["mask"]) & ~band).any(), "mask differs outside the band"
+    assert_close_y(to_np(y), run(mask=mask_gpu)["y"], TOL_Y[dtype], "sparse")
+    union = np.flatnonzero(mask_gpu.any(0))
+    c = cnt.cpu().numpy()
+    assert c[0] == union.size and np.array_equal(idx.cpu().numpy()[: c[0]], union)
+    assert np.array_equal(c[1:], mask_gpu.sum(1))
+    yd = clada.dense_ffn_decode(ctx, layer, xd)
+    torch.cuda.synchronize()
+    assert_close_y(to_np(yd), run(mask=np.ones((B, F), bool))["y"], TOL_Y[dtype], "dense twin")
+    # the same union list through the static-list call (one mask for every token)
+    ys = clada.static_ffn_decode(ctx, layer, xd, idx, cnt[:1].contiguous())
+    torch.cuda.synchronize()
+    assert_close_y(to_np(ys), run(mask=np.broadcast_to(mask_gpu.any(0), (B, F)))["y"], TOL_Y[dtype], "static list")
