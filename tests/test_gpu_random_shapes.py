@@ -80,3 +80,41 @@ def test_random_shape_parity(clada, i, dtype, d, F, B, kind, q):
     ys = clada.static_ffn_decode(ctx, layer, xd, idx, cnt[:1].contiguous())
     torch.cuda.synchronize()
     assert_close_y(to_np(ys), run(mask=np.broadcast_to(mask_gpu.any(0), (B, F)))["y"], TOL_Y[dtype], "static list")
+
+
+def _prefix_cases(n=18):
+    rng = np.random.default_rng(502)
+    out = []
+    for i in range(n):
+        dtype = "bf16" if rng.random() < 0.75 else "f32"
+        d = int(rng.choice([64, 128, 256, 512, 768, 1024])) if rng.random() < 0.6 else int(rng.integers(1, 100)) * 8
+        F = int(rng.integers(1, 40)) * 32 if rng.random() < 0.5 else int(rng.integers(1, 1200))
+        T = int(rng.choice([1, 7, 128, 129, 255, 256, 257, 300, 513, 700]))
+        kind = str(rng.choice(["silu", "silu", "gelu_tanh", "relu"]))
+        tile = int(rng.choice([0, 1, 2, 2]))
+        out.append((i, dtype, d, F, T, kind, tile))
+    return out
+
+
+@pytest.mark.parametrize("i,dtype,d,F,T,kind,tile", _prefix_cases(), ids=lambda v: str(v))
+def test_random_shape_prefix_stats(clada, i, dtype, d, F, T, kind, tile):
+    from paper_2502_19078_amd import binding
+    cfg = synth.CONFIGS["c2" if dtype == "bf16" else "c1"]
+    X = synth.prefix_hidden(cfg, 9, i, T=T, d=d)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 0, T, 0))
+    ctx.set_option("prefix.tile", tile)
+    if kind == "relu":
+        w = synth.relu_layer(cfg, 9, i, d=d, d_ff=F)
+        layer = clada.Layer(to_dev(w[0], dtype), None, to_dev(w[2], dtype), kind=binding.RELU,
+                            b_in=torch.from_numpy(w[1]).to(DEV), b_out=torch.from_numpy(w[3]).to(DEV))
+        ref = oracle.relu_prefix_stats(*w, X)
+    else:
+        w = synth.layer_weights(cfg, 9, i, d=d, d_ff=F)
+        layer = clada.Layer(*[to_dev(a, dtype) for a in w], kind=binding.GEGLU if kind == "gelu_tanh" else binding.SWIGLU)
+        ref = oracle.prefix_stats(*w, X, sigma=kind)
+    st = clada.prefix_stats(ctx, layer, to_dev(X, dtype))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_np(st.abs_act_pool), ref["abs_act_pool"], rtol=1e-4, atol=2e-6)
+    for name in ("sum_abs_act", "sum_sq_act", "max_abs_act", "sum_sq_h", "A"):
+        np.testing.assert_allclose(to_np(getattr(st, name)), ref[name], rtol=3e-5, atol=1e-6, err_msg=name)
+    assert_close_y(to_np(st.y), ref["y"], TOL_Y[dtype], "prefill y")
