@@ -130,7 +130,7 @@ __global__ void k_cett_finish(const CettState *st, float *tau_out, float *mean_o
 }
 
 struct CettWs {
-    float *part, *pool, *rowsq_den, *rowsq_num, *den;
+    float *part, *pool, *rowsq_den, *rowsq_num, *den, *splitk;
     char *h, *hcut;
     CettState *state;
 };
@@ -150,6 +150,8 @@ CettWs carve(char *ws, int d, int F, int T)
     w.rowsq_num = reinterpret_cast<float *>(take(sizeof(float) * n_tn * T));
     w.den = reinterpret_cast<float *>(take(sizeof(float) * (size_t)T));
     w.state = reinterpret_cast<CettState *>(take(sizeof(CettState)));
+    const size_t sk = clada_ws_down_splitk(d, F, T);
+    w.splitk = sk ? reinterpret_cast<float *>(take(sk)) : nullptr;
     return w;
 }
 
@@ -174,7 +176,7 @@ clada_status begin(clada_ctx *ctx, const clada_layer *layer, const void *x, int 
 {
     const int n_tn = clada_prefix_col_tiles(layer->d);
     CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, w.part, w.pool, w.h, ctx->opt_prefix_tile, stream));
-    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.h, T, nullptr, w.rowsq_den, ctx->opt_prefix_tile, stream));
+    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.h, T, nullptr, w.rowsq_den, w.splitk, ctx->opt_prefix_tile, stream));
     hipLaunchKernelGGL(k_cett_begin, dim3((T + 255) / 256), dim3(256), 0, stream, w.state, w.rowsq_den, n_tn, T,
                        w.den, search, eps);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
@@ -194,7 +196,7 @@ clada_status probe(clada_ctx *ctx, const clada_layer *layer, int T, const CettWs
     else
         hipLaunchKernelGGL(k_cett_mask<4>, dim3(grid), dim3(256), 0, stream, w.state, w.pool, w.h, w.hcut, T, F, Fp);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
-    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.hcut, T, nullptr, w.rowsq_num, ctx->opt_prefix_tile, stream));
+    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.hcut, T, nullptr, w.rowsq_num, w.splitk, ctx->opt_prefix_tile, stream));
     hipLaunchKernelGGL(k_cett_update, dim3(1), dim3(1024), 0, stream, w.state, w.rowsq_num, n_tn, T, w.den, bound,
                        search, cett_out, mean_out);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
@@ -210,7 +212,7 @@ size_t clada_ws_cett(int32_t d, int32_t d_ff, int32_t T)
     const size_t Fp = align_up((size_t)d_ff, 64);
     return align_up(sizeof(float) * 4 * n_tm * d_ff, 256) + align_up(sizeof(float) * (size_t)T * d_ff, 256) +
            2 * align_up((size_t)T * Fp * 4, 256) + 2 * align_up(sizeof(float) * n_tn * T, 256) +
-           align_up(sizeof(float) * (size_t)T, 256) + 256;
+           align_up(sizeof(float) * (size_t)T, 256) + 256 + clada_ws_down_splitk(d, d_ff, T);
 }
 
 extern "C" clada_status clada_cett_eval(clada_ctx *ctx, const clada_layer *layer, const void *x_val, int32_t T,

@@ -79,7 +79,9 @@ int clada_prefix_col_tiles(int d);
 hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, float *part, float *pool,
                                char *hbuf, int tile_mode, hipStream_t stream);
 hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, char *y, float *rowsq,
-                             int tile_mode, hipStream_t stream);
+                             float *splitk_ws, int tile_mode, hipStream_t stream);
+int clada_prefix_down_splits(int d, int F, int T);
+size_t clada_ws_down_splitk(int d, int F, int T);
 
 #ifdef __HIPCC__
 // ---------------------------------------------------------------- device helpers

@@ -689,6 +689,8 @@ struct DownParams {
     const float *bias;             // output bias [d] of the non-gated family, or nullptr
     float *rowsq;                  // [n_tn][T] per column-tile sums of squares of the fp32 rows, or nullptr
     int T, d, F, Fp, n_tm, n_tn;   // Fp = F rounded up to a multiple of BK (row stride of h)
+    float *part_out;               // split-K (256 x 256 kernel): fp32 partial outputs [S][T][d] instead of y / rowsq
+    int S;                         // number of k ranges the neurons are split into (1 = no split)
 };
 
 // Row sums of squares of a 128 x 128 output tile held in the accumulators of four waves (2 x 2
@@ -936,8 +938,15 @@ k_prefix_down_bf16_wide(const DownParams p)
     __shared__ __align__(16) char s_w[4 * DW_STAGE];
 
     const int n_tmw = (p.T + 255) / 256, n_tnw = p.d / 256;
-    int tm, tn;
-    if (n_tmw % 8 == 0) {                                   // 8 token tiles x 4 column tiles per XCD at a time
+    int tm, tn, ks = 0;
+    if (p.S > 1) {                                          // split-K: the S parts of a tile sit side by side
+        const int total = n_tmw * n_tnw * p.S;
+        const int o = remap_block(blockIdx.x, total);
+        if (o >= total) return;
+        ks = o % p.S;
+        tm = (o / p.S) % n_tmw;
+        tn = (o / p.S) / n_tmw;
+    } else if (n_tmw % 8 == 0) {                            // 8 token tiles x 4 column tiles per XCD at a time
         const int tn_pad = (n_tnw + 3) / 4 * 4;
         const int o = remap_block(blockIdx.x, n_tmw * tn_pad);
         const int sb = o >> 5, w = o & 31, tmb = n_tmw >> 3;
@@ -977,7 +986,15 @@ k_prefix_down_bf16_wide(const DownParams p)
             gw[c] = p.wd + (size_t)(2 * (wave + 4 * c) + half) * wrow + (size_t)tn * 512 + cidx * 16;
         }
     }
-    const int nk = p.F / 32;                                // >= 1; d_ff % 32 == 0
+    // this workgroup's k-tiles [kt0, kt0 + nk) of the d_ff / 32 (d_ff % 32 == 0; the host keeps S <= d_ff / 32)
+    const int nk_all = p.F / 32;
+    const int kt0 = (int)((long long)ks * nk_all / p.S);
+    const int nk = (int)((long long)(ks + 1) * nk_all / p.S) - kt0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        gh[c] += (size_t)kt0 * 64;
+        gw[c] += (size_t)kt0 * 32 * wrow;
+    }
     auto dma_one = [&](auto ic, char *st, int kt) {
         constexpr int i = decltype(ic)::value;
         if (i < 4) lds_dma16(gh[i] + (size_t)kt * 64, st + (wave + 4 * i) * 1024);
@@ -1106,6 +1123,20 @@ k_prefix_down_bf16_wide(const DownParams p)
     const int n = lane & 31;
     const int t0 = tm * 256 + wm * 128 + 4 * (lane >> 5);
     const int c0 = tn * 256 + wn * 128;                     // one 128-column tile of the row-norm buffer
+    if (p.part_out) {                                       // split-K: fp32 partial sums, reduced by k_prefix_down_combine
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            float *dst = p.part_out + ((size_t)ks * p.T + t0) * p.d + c0 + nb * 32 + n;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = mb * 32 + 8 * (r >> 2) + (r & 3);
+                    if (t0 + row < p.T) dst[(size_t)row * p.d] = acc[mb][nb][r];
+                }
+        }
+        return;
+    }
     if (p.rowsq) {
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
@@ -1136,6 +1167,43 @@ k_prefix_down_bf16_wide(const DownParams p)
                 const int row = mb * 32 + 8 * (r >> 2) + (r & 3);
                 if (t0 + row < p.T) dst[(size_t)row * p.d] = (unsigned short)f32_to_bf16_bits(acc[mb][nb][r] + bv);
             }
+    }
+}
+
+// Sum of the S split-K partial outputs [S][T][d] in ascending order, then what the direct epilogue does:
+// y in bf16 (+ bias) and / or the per-row sums of squares of every 128-column tile.  A workgroup takes
+// 8 rows x 128 columns: thread = (row tid >> 5, four columns 4 (tid & 31) ..).
+__global__ void __launch_bounds__(256)
+k_prefix_down_combine(const float *__restrict__ part, int S, int T, int d, char *__restrict__ y,
+                      const float *__restrict__ bias, float *__restrict__ rowsq)
+{
+    const int t = blockIdx.x * 8 + (threadIdx.x >> 5);
+    const int col = blockIdx.y * 128 + 4 * (threadIdx.x & 31);
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (t < T) {
+        for (int k = 0; k < S; ++k) {
+            const float4 v = *reinterpret_cast<const float4 *>(part + ((size_t)k * T + t) * d + col);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+    }
+    if (rowsq) {
+        float v = fmaf(s.x, s.x, fmaf(s.y, s.y, fmaf(s.z, s.z, s.w * s.w)));
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 8);
+        v += __shfl_xor(v, 4);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 1);
+        if ((threadIdx.x & 31) == 0 && t < T) rowsq[(size_t)blockIdx.y * T + t] = v;
+    }
+    if (y && t < T) {
+        if (bias) {
+            const float4 b = *reinterpret_cast<const float4 *>(bias + col);
+            s.x += b.x; s.y += b.y; s.z += b.z; s.w += b.w;
+        }
+        uint2 o;
+        o.x = f32_to_bf16_bits(s.x) | (f32_to_bf16_bits(s.y) << 16);
+        o.y = f32_to_bf16_bits(s.z) | (f32_to_bf16_bits(s.w) << 16);
+        *reinterpret_cast<uint2 *>(y + ((size_t)t * d + col) * 2) = o;
     }
 }
 
@@ -1206,12 +1274,30 @@ size_t clada_ws_prefix(int32_t d, int32_t d_ff, int32_t T, bool want_y)
     if (T <= 0) return 0;
     const size_t n_tm = (size_t)(T + BM - 1) / BM;
     size_t need = align_up(sizeof(float) * 4 * n_tm * d_ff, 256);
-    if (want_y) need += align_up((size_t)T * align_up((size_t)d_ff, 64) * 4, 256);
-    (void)d;
+    if (want_y) need += align_up((size_t)T * align_up((size_t)d_ff, 64) * 4, 256) + clada_ws_down_splitk(d, d_ff, T);
     return need;
 }
 
 int clada_prefix_token_tiles(int T) { return (T + BM - 1) / BM; }
+
+// Split-K factor of the 256 x 256 down projection for a shape that leaves compute units idle
+// (fewer than 192 tiles): enough parts to reach about one workgroup per CU, every part at least
+// eight 32-deep k-tiles, at most 8.  1 = no split (the shape does not qualify or does not need it).
+int clada_prefix_down_splits(int d, int F, int T)
+{
+    if (T <= 0 || d % 256 != 0 || F % 32 != 0) return 1;
+    const int tiles = ((T + 255) / 256) * (d / 256);
+    if (tiles >= 192) return 1;
+    int S = 256 / tiles;
+    if (S > 8) S = 8;
+    if (S > F / 256) S = F / 256;
+    return S < 2 ? 1 : S;
+}
+size_t clada_ws_down_splitk(int d, int F, int T)
+{
+    const int S = clada_prefix_down_splits(d, F, T);
+    return S > 1 ? align_up(sizeof(float) * (size_t)S * T * d, 256) : 0;
+}
 int clada_prefix_col_tiles(int d) { return (d + BN - 1) / BN; }
 
 // Gate/up GEMM with the fused activation epilogue: part [n_tm][4][F] per-neuron partial
@@ -1250,7 +1336,7 @@ hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, f
 // Down projection of h [T][Fp]: y [T][d] in the layer dtype and/or rowsq [col tiles][T], the
 // per-column-tile sums of squares of the fp32 output rows (either may be nullptr).
 hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, char *y, float *rowsq,
-                             int tile_mode, hipStream_t stream)
+                             float *splitk_ws, int tile_mode, hipStream_t stream)
 {
     const int d = layer->d, F = layer->d_ff, es = (int)dtype_size(layer->dtype);
     DownParams q;
@@ -1259,11 +1345,22 @@ hipError_t clada_prefix_down(const clada_layer *layer, const char *h, int T, cha
     q.T = T; q.d = d; q.F = F; q.Fp = (int)align_up((size_t)F, 64);
     q.n_tm = (T + BM - 1) / BM; q.n_tn = (d + BN - 1) / BN;
     const int tot = q.n_tm * q.n_tn, grid = (tot + 7) / 8 * 8;
-    // 256 x 256 tiles when they fill the chip at least once (tile_mode 2: whenever the shape allows)
+    // 256 x 256 tiles (bf16, d % 256 == 0, d_ff % 32 == 0): directly when they fill the chip, split along
+    // d_ff into S parts with a combining pass when they would not (splitk_ws [S][T][d] fp32).
+    // tile_mode 1 = 128 x 128 tiles always.
     const int n_tmw = (T + 255) / 256, n_tnw = d / 256;
-    const bool wide_ok = es == 2 && d % 256 == 0 && F % 32 == 0;
-    const bool wide = wide_ok && (tile_mode == 2 || (tile_mode == 0 && n_tmw * n_tnw >= 192));
-    if (wide) {
+    const bool wide_ok = es == 2 && d % 256 == 0 && F % 32 == 0 && tile_mode != 1;
+    const int S = wide_ok && splitk_ws ? clada_prefix_down_splits(d, F, T) : 1;
+    q.part_out = nullptr; q.S = 1;
+    if (wide_ok && S > 1) {
+        q.part_out = splitk_ws; q.S = S;
+        hipLaunchKernelGGL(k_prefix_down_bf16_wide, dim3((n_tmw * n_tnw * S + 7) / 8 * 8), dim3(256), 0, stream, q);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_prefix_down_combine, dim3((T + 7) / 8, d / 128), dim3(256), 0, stream, splitk_ws, S, T, d,
+                           y, q.bias, rowsq);
+    }
+    else if (wide_ok && (tile_mode == 2 || n_tmw * n_tnw >= 192)) {
         const int blocks = n_tmw % 8 == 0 ? n_tmw * ((n_tnw + 3) / 4 * 4) : n_tmw * n_tnw;
         hipLaunchKernelGGL(k_prefix_down_bf16_wide, dim3((blocks + 7) / 8 * 8), dim3(256), 0, stream, q);
     }
@@ -1294,7 +1391,11 @@ extern "C" clada_status clada_prefix_stats(clada_ctx *ctx, const clada_layer *la
     float *part = reinterpret_cast<float *>(ws);
     char *hbuf = y ? ws + align_up(sizeof(float) * 4 * (size_t)n_tm * F, 256) : nullptr;
     CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, part, out->abs_act_pool, hbuf, ctx->opt_prefix_tile, stream));
-    if (y) CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, hbuf, T, (char *)y, nullptr, ctx->opt_prefix_tile, stream));
+    if (y) {
+        float *splitk = clada_ws_down_splitk(d, F, T)
+                            ? reinterpret_cast<float *>(hbuf + align_up((size_t)T * align_up((size_t)F, 64) * 4, 256)) : nullptr;
+        CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, hbuf, T, (char *)y, nullptr, splitk, ctx->opt_prefix_tile, stream));
+    }
     if (out->sum_abs_act || out->sum_sq_act || out->max_abs_act || out->sum_sq_h || out->A) {
         if (es == 4) hipLaunchKernelGGL(k_prefix_reduce<4>, dim3((F + 3) / 4), dim3(256), 0, stream,
                                         (const char *)layer->w_down, d, F, part, n_tm, *out);

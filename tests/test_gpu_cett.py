@@ -57,6 +57,7 @@ CASES = [
     ("c2", 72, 129, 257, 0),
     ("c2", 512, 416, 300, 2),    # 256 x 256 down-projection tiles: 13 k-tiles of 32, d_ff not a multiple of 64
     ("c2", 256, 64, 257, 2),     # two k-tiles; the second token tile holds one token
+    ("c2", 256, 768, 257, 0),    # down projection split three ways along d_ff, row norms from the combining pass
 ]
 
 

@@ -37,6 +37,8 @@ def _rel(a, b):
     ("c2", 64, 40, 1),           # bf16, one token: every row of a tile repeats it
     ("c2", 512, 32, 300),        # a single 32-deep k-tile in the 256 x 256 down projection
     ("c2", 768, 96, 520),        # three column tiles, three k-tiles
+    ("c2", 512, 1024, 300),      # few tiles, long d_ff: the down projection splits d_ff four ways
+    ("c2", 256, 800, 130),       # split three ways, 25 k-tiles (uneven parts)
 ])
 @pytest.mark.parametrize("tile", [1, 2])
 def test_prefix_stats_parity(clada, cfg_name, d, F, T, tile):
