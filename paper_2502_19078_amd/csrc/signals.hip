@@ -6,7 +6,7 @@
 // so that  lse = m + log Z,  entropy = log Z - T/Z,  surprisal = lse - z_tok.
 // Triples merge associatively (rescale by e^{m_i - m}); lanes merge by a fixed
 // butterfly, waves through LDS, blocks through the workspace with the last
-// arriving block of each row folding the block partials in ascending order, so
+// arriving block of each row folding the block partials in a fixed order, so
 // the result is bit-reproducible.
 #include <math.h>
 
@@ -109,17 +109,23 @@ k_signals(const char *__restrict__ logits, int V, const int32_t *__restrict__ to
     if (tid == 0) {
         Lse r = s_w[0];
         for (int w = 1; w < SIG_THREADS / 64; ++w) r = lse_merge(r, s_w[w]);
+        // agent-scope (write-through) stores, their acknowledgements, then the arrival count: the block that
+        // folds the partials may run on another XCD, and a release fence at that scope would write back the L2
         float *dst = part + ((size_t)b * nb + blockIdx.x) * 4;
-        dst[0] = r.m; dst[1] = r.Z; dst[2] = r.T; dst[3] = r.bad ? 1.0f : 0.0f;
-        __threadfence();
-        const int prev = atomicAdd(&counters[b], 1);
+        __hip_atomic_store(dst + 0, r.m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(dst + 1, r.Z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(dst + 2, r.T, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(dst + 3, r.bad ? 1.0f : 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        const int prev = __hip_atomic_fetch_add(&counters[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (prev == nb - 1);
     }
     __syncthreads();
-    if (s_last && tid == 0) {
-        __threadfence();
+    if (s_last && tid < 64) {
+        // last block of the row: lane l folds partials l, l + 64, ... in ascending order (all loads of the
+        // wave in flight together), then the lanes merge by the same fixed butterfly as above
         Lse r = lse_empty();
-        for (int q = 0; q < nb; ++q) {
+        for (int q = tid; q < nb; q += 64) {
             const float *src = part + ((size_t)b * nb + q) * 4;
             Lse t;
             t.m = __hip_atomic_load(src + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -128,19 +134,30 @@ k_signals(const char *__restrict__ logits, int V, const int32_t *__restrict__ to
             t.bad = __hip_atomic_load(src + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0.0f;
             r = lse_merge(r, t);
         }
-        counters[b] = 0;                        // ready for the next call
-        float H, s;
-        if (r.bad || !(r.Z > 0.0f)) {
-            H = NAN;
-            s = NAN;
-        } else {
-            const float logZ = logf(r.Z);
-            H = logZ - r.T / r.Z;
-            const int t = tok[b];
-            s = (t >= 0 && t < V) ? (r.m + logZ) - load_logit<ES>(row, t) : NAN;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            Lse other;
+            other.m = __shfl_xor(r.m, o);
+            other.Z = __shfl_xor(r.Z, o);
+            other.T = __shfl_xor(r.T, o);
+            other.bad = __shfl_xor(r.bad, o);
+            r = ((tid & o) == 0) ? lse_merge(r, other) : lse_merge(other, r);
         }
-        entropy[b] = H;
-        surprisal[b] = s;
+        if (tid == 0) {
+            __hip_atomic_store(&counters[b], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+            float H, s;
+            if (r.bad || !(r.Z > 0.0f)) {
+                H = NAN;
+                s = NAN;
+            } else {
+                const float logZ = logf(r.Z);
+                H = logZ - r.T / r.Z;
+                const int t = tok[b];
+                s = (t >= 0 && t < V) ? (r.m + logZ) - load_logit<ES>(row, t) : NAN;
+            }
+            entropy[b] = H;
+            surprisal[b] = s;
+        }
     }
 }
 
