@@ -544,8 +544,8 @@ k_prefix_gateup_bf16_wide(const GateUpParams p)
     // transfer i (0..7) of this wave for k-tile kt: four X pieces, two gate, two up
     auto dma_one = [&](auto ic, char *st, int kt) {
         constexpr int i = decltype(ic)::value;
-        if (i < 4) lds_dma16(gx[i] + (size_t)kt * 64, st + (wave + 4 * i) * 1024);
-        else if (i < 6) lds_dma16(gg[i - 4] + (size_t)kt * 64, st + GW_G + (wave + 4 * (i - 4)) * 1024);
+        if constexpr (i < 4) lds_dma16(gx[i] + (size_t)kt * 64, st + (wave + 4 * i) * 1024);
+        else if constexpr (i < 6) lds_dma16(gg[i - 4] + (size_t)kt * 64, st + GW_G + (wave + 4 * (i - 4)) * 1024);
         else lds_dma16(gu[i - 6] + (size_t)kt * 64, st + GW_U + (wave + 4 * (i - 6)) * 1024);
     };
     auto issue = [&](char *st, int kt) {
@@ -997,7 +997,7 @@ k_prefix_down_bf16_wide(const DownParams p)
     }
     auto dma_one = [&](auto ic, char *st, int kt) {
         constexpr int i = decltype(ic)::value;
-        if (i < 4) lds_dma16(gh[i] + (size_t)kt * 64, st + (wave + 4 * i) * 1024);
+        if constexpr (i < 4) lds_dma16(gh[i] + (size_t)kt * 64, st + (wave + 4 * i) * 1024);
         else lds_dma16(gw[i - 4] + (size_t)kt * 32 * wrow, st + DW_B + (wave + 4 * (i - 4)) * DW_PAIR);
     };
     auto issue = [&](char *st, int kt) {
@@ -1020,8 +1020,6 @@ k_prefix_down_bf16_wide(const DownParams p)
         b_off[nb] = b_lane + (unsigned int)((wn * 256 + nb * 64 + 32 * (g & 1) + 8 * (t16 & 3) + 64 * (rr & 1)) & 511);
     u32x4 fa[2][4];                                         // two fragment sets
     u32x2 fb[2][8];                                         // [set][2 nb + half]: rows k0..k0+3 and k0+4..k0+7
-#define DW_RDA(S, I, ADDR, OFF) asm volatile("ds_read_b128 %0, %1 offset:" #OFF : "=v"(fa[S][I]) : "v"(ADDR));
-#define DW_RDB(S, I, ADDR, OFF) asm volatile("ds_read_b64_tr_b16 %0, %1 offset:" #OFF : "=v"(fb[S][I]) : "v"(ADDR));
 #define DW_WAIT(S)                                                                                        \
     asm volatile("s_waitcnt lgkmcnt(0)"                                                                   \
                  : "+v"(fa[S][0]), "+v"(fa[S][1]), "+v"(fa[S][2]), "+v"(fa[S][3]), "+v"(fb[S][0]),        \
@@ -1035,20 +1033,24 @@ k_prefix_down_bf16_wide(const DownParams p)
         acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[S][mb]),      \
                                                               __builtin_bit_cast(bf16x8, bv), acc[mb][nb], 0, 0, 0); \
     }
-    // read I (0..11) of k-step KS from the stage at byte offset SO into set S: four A fragments, then
-    // the eight halves of the B fragments
-#define DW_RD(S, I, SO, KS)                                                                               \
-    {                                                                                                     \
-        if ((I) < 4) {                                                                                    \
-            const unsigned int pa = a_off + (SO) + (unsigned int)(((2 * (KS) + q) ^ sw) * 16);            \
-            if ((I) == 0) DW_RDA(S, 0, pa, 0) else if ((I) == 1) DW_RDA(S, 1, pa, 2048)                   \
-            else if ((I) == 2) DW_RDA(S, 2, pa, 4096) else DW_RDA(S, 3, pa, 6144)                         \
-        } else {                                                                                          \
-            const unsigned int pb = b_off[((I) - 4) >> 1] + (SO);                                         \
-            if ((KS) == 0) { if (((I) & 1) == 0) DW_RDB(S, (I) - 4, pb, 0) else DW_RDB(S, (I) - 4, pb, 2304) }       \
-            else           { if (((I) & 1) == 0) DW_RDB(S, (I) - 4, pb, 9216) else DW_RDB(S, (I) - 4, pb, 11520) }   \
-        }                                                                                                 \
-    }
+    // read I (0..11) of k-step KS from the stage at byte offset so into set S: four A fragments, then the
+    // eight halves of the B fragments (rows k0..k0+3 and k0+4..k0+7 of each 32-column block)
+    auto rd_one = [&](auto sc, auto ic, auto ksc, u32x4 (&fa)[2][4], u32x2 (&fb)[2][8], unsigned int so) {
+        constexpr int S = decltype(sc)::value, I = decltype(ic)::value, KS = decltype(ksc)::value;
+        if constexpr (I < 4) {
+            const unsigned int pa = a_off + so + (unsigned int)(((2 * KS + q) ^ sw) * 16);
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(fa[S][I]) : "v"(pa), "n"(I * 2048));
+        } else {
+            const unsigned int pb = b_off[(I - 4) >> 1] + so;
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(fb[S][I - 4]) : "v"(pb), "n"(KS * 9216 + (I & 1) * 2304));
+        }
+    };
+    // the same for MFMA slot SL of a k-step: slots 12..15 carry no read
+    auto rd_slot = [&](auto sc, auto slc, auto ksc, u32x4 (&fa)[2][4], u32x2 (&fb)[2][8], unsigned int so) {
+        if constexpr (decltype(slc)::value < 12) rd_one(sc, slc, ksc, fa, fb, so);
+    };
+#define DW_RD(S, I, SO, KS) rd_slot(std::integral_constant<int, S>{}, std::integral_constant<int, I>{},   \
+                                    std::integral_constant<int, KS>{}, fa, fb, SO);
 #define DW_SB __builtin_amdgcn_sched_barrier(0);
     auto read_all = [&](auto sc, auto ksc, u32x4 (&fa)[2][4], u32x2 (&fb)[2][8], unsigned int so) {
         constexpr int S = decltype(sc)::value, KS = decltype(ksc)::value;
@@ -1063,11 +1065,11 @@ k_prefix_down_bf16_wide(const DownParams p)
         const unsigned int cur = (unsigned int)((k & 3) * DW_STAGE), nxt = (unsigned int)(((k + 1) & 3) * DW_STAGE);
         char *sta = s_w + ((k + 3) & 3) * DW_STAGE, *stb = s_w + (k & 3) * DW_STAGE;
 #define DW_SLOT_A(SL)                                                                                     \
-        if ((SL) < 12) DW_RD(1, SL, cur, 1)                                                               \
+        DW_RD(1, SL, cur, 1)                                                                              \
         if (DA && ((SL) & 3) == wave) dma_one(std::integral_constant<int, 4 + (SL) / 4>{}, sta, k + 3);   \
         DW_MMA1(0, SL) DW_SB
 #define DW_SLOT_B(SL)                                                                                     \
-        if ((SL) < 12) DW_RD(0, SL, nxt, 0)                                                               \
+        DW_RD(0, SL, nxt, 0)                                                                              \
         if (DB && ((SL) & 3) == wave) dma_one(std::integral_constant<int, (SL) / 4>{}, stb, k + 4);       \
         DW_MMA1(1, SL) DW_SB
         DW_WAIT(0)
@@ -1112,8 +1114,6 @@ k_prefix_down_bf16_wide(const DownParams p)
         DW_MMA1(1, 0) DW_MMA1(1, 1) DW_MMA1(1, 2) DW_MMA1(1, 3) DW_MMA1(1, 4) DW_MMA1(1, 5) DW_MMA1(1, 6) DW_MMA1(1, 7)
         DW_MMA1(1, 8) DW_MMA1(1, 9) DW_MMA1(1, 10) DW_MMA1(1, 11) DW_MMA1(1, 12) DW_MMA1(1, 13) DW_MMA1(1, 14) DW_MMA1(1, 15)
     }
-#undef DW_RDA
-#undef DW_RDB
 #undef DW_WAIT
 #undef DW_MMA1
 #undef DW_RD
