@@ -1,6 +1,5 @@
 """Pins of the oracle's GELU-gated FFN (sigma = tanh-form GELU, the Gemma model of the paper's
 experiments) -- CPU only.  Every gated oracle function takes sigma="gelu_tanh"."""
-import math
 
 import numpy as np
 import pytest
