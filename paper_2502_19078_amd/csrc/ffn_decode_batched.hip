@@ -65,21 +65,31 @@ k_bat_gateup(const BatParams p)
     const int blk = blockIdx.x, P = gridDim.x;
     const int d = p.d, F = p.F, B = p.B;
     const size_t rowb = (size_t)d * 2;
-    // This wave's k-slice of every row is SLICE bytes, taken in NPART parts of PB <= 1024 bytes.  A
-    // load instruction reads one row's part as one contiguous piece (lane l: bytes 16 l ..; measured
-    // 6.6 TB/s, against 5.6 TB/s for 16 rows x 64 bytes per instruction, which is what the MFMA
-    // operand layout would ask for).  The wave then turns 16 such rows into B-fragments through its
-    // private LDS tile: row r is written contiguously at r * PITCH, and lane (neuron n, k-group q)
-    // reads chunk q * SP + ks of row n for k-step ks.  The order of k within the slice is free as
-    // long as x uses the same one.  PITCH = PB + 16 keeps both directions free of bank conflicts.
+    // This wave's k-slice of every row is SLICE bytes, taken in NPART parts of PB <= 1024 bytes.  The
+    // loads of eight rows' parts (8 PB bytes) are packed into NL = PB / 128 full instructions of
+    // 64 x 16 bytes: lane l of instruction i takes byte 1024 i + 16 l of the eight parts laid end
+    // to end, i.e. contiguous pieces of PB bytes (or the two ends of neighbouring rows) -- measured
+    // 6.6 TB/s for whole-KiB pieces against 5.6 TB/s for 16 rows x 64 bytes per instruction, which
+    // is what the MFMA operand layout would ask for.  The wave then turns 16 such rows into
+    // B-fragments through its private LDS tile: row r is written contiguously at r * PITCH, and lane
+    // (neuron n, k-group q) reads chunk q * SP + ks of row n for k-step ks.  The order of k within the
+    // slice is free as long as x uses the same one.  PITCH = PB + 16 keeps both directions free of
+    // bank conflicts.
     constexpr int SLICE = KSTEPS * 64;
     constexpr int NPART = SLICE > 1024 ? 2 : 1;
     constexpr int PB = SLICE / NPART, SP = PB / 64, PITCH = PB + 16;
-    static_assert(PB % 64 == 0 && PB <= 1024 && NPART * SP == KSTEPS, "slice split");
+    constexpr int NL = PB / 128;                            // load instructions per eight rows of a part
+    static_assert(PB % 128 == 0 && PB <= 1024 && NPART * SP == KSTEPS, "slice split");
     __shared__ __align__(16) char s_stage[8 * 16 * PITCH];
     char *stage = s_stage + wave * 16 * PITCH;
-    const bool ld_on = lane < PB / 16;
     const int koff = wave * SLICE;
+    int ld_row[NL], ld_col[NL];                             // (row within the eight, byte within the part) of this lane's piece
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int o = 1024 * i + 16 * lane;
+        ld_row[i] = o / PB;
+        ld_col[i] = o % PB;
+    }
     // Neurons are dealt out in contiguous runs of whole octets: workgroup q owns octets
     // [q no / P, (q+1) no / P), at most 64 neurons, so every workgroup streams the same number of
     // rows to within 8 (16-neuron granularity would leave an eighth of the chip idle at the end).
@@ -99,23 +109,23 @@ k_bat_gateup(const BatParams p)
     }
     __syncthreads();
 
-    // eight rows (half a tile) of one part: one load instruction per row; a row that does not
-    // exist (row < 0) loads nothing and contributes zeros
-    auto rows_load = [&](u32x4 (&wr)[8], const char *w, auto row_of, int unit, int half) {
+    // eight rows (half a tile) of one part; a row that does not exist (row < 0) loads nothing and
+    // contributes zeros
+    auto rows_load = [&](u32x4 (&wr)[NL], const char *w, auto row_of, int unit, int half) {
         const int tile = unit / NPART, part = unit % NPART;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int row = row_of(tile, 8 * half + r);
+        for (int i = 0; i < NL; ++i) {
+            const int row = row_of(tile, 8 * half + ld_row[i]);
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (row >= 0 && ld_on)
-                v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w + (size_t)row * rowb + koff + part * PB + lane * 16));
-            wr[r] = v;
+            if (row >= 0)
+                v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w + (size_t)row * rowb + koff + part * PB + ld_col[i]));
+            wr[i] = v;
         }
     };
-    auto stage_write = [&](const u32x4 (&wr)[8], int half) {
+    auto stage_write = [&](const u32x4 (&wr)[NL], int half) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
-            if (ld_on) *reinterpret_cast<u32x4 *>(stage + (8 * half + r) * PITCH + lane * 16) = wr[r];
+        for (int i = 0; i < NL; ++i)
+            *reinterpret_cast<u32x4 *>(stage + (8 * half + ld_row[i]) * PITCH + ld_col[i]) = wr[i];
     };
     // lanes of this wave exchange data through the tile: order the LDS traffic within the wave
     auto wave_sync = [&]() {
@@ -139,7 +149,7 @@ k_bat_gateup(const BatParams p)
     // rows of the next part are requested as soon as the current ones sit in LDS; every path keeps
     // a fixed number of loads in flight.
     auto tile_pass = [&](const char *w, int ntiles, auto row_of, auto reduce) {
-        u32x4 wa[8], wb[8];
+        u32x4 wa[NL], wb[NL];
         const int nunits = ntiles * NPART;
         if (nunits > 0) {
             rows_load(wa, w, row_of, 0, 0);
