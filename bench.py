@@ -224,14 +224,15 @@ def main():
         if args.no_graph:
             return lambda: step_body(dense, ts, th)
         load_inputs(0)
+        torch.cuda.synchronize()
         with torch.cuda.stream(side):
+            step_body(dense, ts, th)                    # eager once: first calls set kernel attributes
+            side.synchronize()
+            clada.graph_begin(ctx)                      # the library's own capture (clada_graph_*)
             step_body(dense, ts, th)
+            g = clada.graph_end(ctx)
         torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=side):
-            step_body(dense, ts, th)
-        torch.cuda.synchronize()
-        return g.replay
+        return g.launch                                 # replays on the current stream; the bound method keeps g alive
 
     def timed(run):
         for s in range(W):

@@ -262,6 +262,23 @@ clada_status clada_static_ffn_decode(clada_ctx *ctx, const clada_layer *layer, c
                                      int32_t B, const int32_t *active_idx, const int32_t *n_active,
                                      void *y, void *hip_stream);
 
+/* One decode step as a replayable HIP graph (the algorithm "CLADA Inference", generation
+ * phase, is the same short sequence of calls for every token: signals, thresholds, one
+ * sparse FFN per layer; captured once, a replay costs one launch instead of 2 L + 2).
+ * Between clada_graph_begin and clada_graph_end every call of this library on `hip_stream`
+ * (which must not be the default stream) is recorded instead of run; other work the caller
+ * enqueues on that stream is recorded too.  The graph holds the pointers the calls were
+ * given: replays read and write those same buffers, so the caller refreshes the inputs in
+ * place.  Run the same calls once eagerly before capturing (first calls set kernel
+ * attributes, which a capture must not contain); options that record events
+ * ("diag.kernel_events") must be off.  clada_graph_launch enqueues one replay on
+ * `hip_stream`.  The context must outlive the graph; one capture at a time per context. */
+typedef struct clada_graph clada_graph;
+clada_status clada_graph_begin(clada_ctx *ctx, void *hip_stream);
+clada_status clada_graph_end(clada_ctx *ctx, void *hip_stream, clada_graph **out);
+clada_status clada_graph_launch(clada_ctx *ctx, clada_graph *graph, void *hip_stream);
+void clada_graph_destroy(clada_graph *graph);
+
 /* Measurement helpers (no part of the method).  clada_diag_stream_read reads
  * `bytes` (a multiple of 8192) of device memory once, in the decode kernels'
  * access pattern (each wave streams whole 8 KiB rows with non-temporal 16-byte

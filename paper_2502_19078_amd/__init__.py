@@ -11,4 +11,4 @@ from .binding import (Context, Layer, PrefixStats, CladaError, cognitive_signals
                       sparse_ffn_decode, threshold, threshold_calibrate,
                       threshold_search_cett, cett_eval, static_mask_threshold,
                       static_mask_topk, static_ffn_decode, mask_pack, mask_unpack,
-                      workspace_bytes)
+                      workspace_bytes, Graph, graph_begin, graph_end)

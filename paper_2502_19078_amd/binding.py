@@ -81,6 +81,11 @@ def load_library() -> C.CDLL:
     lib.clada_mask_pack.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.clada_mask_unpack.argtypes = [vp, vp, i32, vp, vp, vp]
     lib.clada_device_fault.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.clada_graph_begin.argtypes = [vp, vp]
+    lib.clada_graph_end.argtypes = [vp, vp, C.POINTER(vp)]
+    lib.clada_graph_launch.argtypes = [vp, vp, vp]
+    lib.clada_graph_destroy.argtypes = [vp]
+    lib.clada_graph_destroy.restype = None
     lib.clada_diag_kernel_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times", "clada_device_fault",
                  "clada_threshold_search_cett", "clada_cett_eval", "clada_static_mask_threshold",
@@ -343,6 +348,33 @@ def static_ffn_decode(ctx: Context, layer: Layer, x: torch.Tensor, active_idx: t
 def diag_stream_read(ctx: Context, src: torch.Tensor, blocks_per_cu: int = 1):
     ctx.check(ctx._lib.clada_diag_stream_read(ctx._h, _ptr(src), src.numel() * src.element_size(),
                                               blocks_per_cu, _stream(src)))
+
+
+class Graph:
+    """One captured decode step (clada_graph_*).  The calls issued on torch's current stream between
+    graph_begin and graph_end are recorded; launch() replays them on the current stream."""
+
+    def __init__(self, ctx: Context, handle):
+        self._ctx, self._g = ctx, handle
+
+    def launch(self):
+        st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        self._ctx.check(self._ctx._lib.clada_graph_launch(self._ctx._h, self._g, st))
+
+    def __del__(self):
+        if getattr(self, "_g", None):
+            self._ctx._lib.clada_graph_destroy(self._g)
+            self._g = None
+
+
+def graph_begin(ctx: Context):
+    ctx.check(ctx._lib.clada_graph_begin(ctx._h, C.c_void_p(torch.cuda.current_stream().cuda_stream)))
+
+
+def graph_end(ctx: Context) -> Graph:
+    g = C.c_void_p()
+    ctx.check(ctx._lib.clada_graph_end(ctx._h, C.c_void_p(torch.cuda.current_stream().cuda_stream), C.byref(g)))
+    return Graph(ctx, g)
 
 
 def diag_copy(ctx: Context, src: torch.Tensor, dst: torch.Tensor):

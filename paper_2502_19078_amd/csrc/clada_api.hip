@@ -71,6 +71,7 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->opt_decode_own_first = 0;
     ctx->opt_decode_spin_limit = 1 << 21;
     ctx->opt_prefix_tile = 0;
+    ctx->capturing = 0;
     ctx->opt_diag_events = 0;
     ctx->ev[0] = ctx->ev[1] = ctx->ev[2] = ctx->ev[3] = nullptr;
     ctx->err[0] = 0;
@@ -196,6 +197,67 @@ size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int3
     if (T > 0 && (n = clada_ws_calibrate()) > need) need = n;
     if (d > 0 && d_ff > 0 && T > 0 && (n = clada_ws_cett(d, d_ff, T)) > need) need = n;
     return need + 256;
+}
+
+// ---- one decode step as a HIP graph: thin wrappers over stream capture, so that callers without a
+// framework's capture facility can replay the per-token call sequence.
+struct clada_graph {
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+clada_status clada_graph_begin(clada_ctx *ctx, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    if (!hip_stream) return clada_fail(ctx, CLADA_ERR_VALUE, "the default stream cannot be captured");
+    if (!ctx->ws) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "the context has no workspace (no device)");
+    if (ctx->opt_diag_events) return clada_fail(ctx, CLADA_ERR_VALUE, "switch diag.kernel_events off before capturing");
+    if (ctx->capturing) return clada_fail(ctx, CLADA_ERR_VALUE, "a capture is already open on this context");
+    CLADA_CHECK_HIP(ctx, hipStreamBeginCapture((hipStream_t)hip_stream, hipStreamCaptureModeRelaxed));
+    ctx->capturing = 1;
+    return CLADA_OK;
+}
+
+clada_status clada_graph_end(clada_ctx *ctx, void *hip_stream, clada_graph **out)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    if (!out) return clada_fail(ctx, CLADA_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (!ctx->capturing) return clada_fail(ctx, CLADA_ERR_VALUE, "no capture is open on this context");
+    ctx->capturing = 0;
+    hipGraph_t g = nullptr;
+    CLADA_CHECK_HIP(ctx, hipStreamEndCapture((hipStream_t)hip_stream, &g));
+    if (!g) return clada_fail(ctx, CLADA_ERR_HIP, "the capture produced no graph");
+    hipGraphExec_t ex = nullptr;
+    hipError_t e = hipGraphInstantiate(&ex, g, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        (void)hipGraphDestroy(g);
+        CLADA_CHECK_HIP(ctx, e);
+    }
+    clada_graph *r = new (std::nothrow) clada_graph{g, ex};
+    if (!r) {
+        (void)hipGraphExecDestroy(ex);
+        (void)hipGraphDestroy(g);
+        return clada_fail(ctx, CLADA_ERR_HIP, "out of host memory");
+    }
+    *out = r;
+    return CLADA_OK;
+}
+
+clada_status clada_graph_launch(clada_ctx *ctx, clada_graph *graph, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    if (!graph) return clada_fail(ctx, CLADA_ERR_NULL, "graph is NULL");
+    CLADA_CHECK_HIP(ctx, hipGraphLaunch(graph->exec, (hipStream_t)hip_stream));
+    return CLADA_OK;
+}
+
+void clada_graph_destroy(clada_graph *graph)
+{
+    if (!graph) return;
+    (void)hipGraphExecDestroy(graph->exec);
+    (void)hipGraphDestroy(graph->graph);
+    delete graph;
 }
 
 }  // extern "C"

@@ -20,6 +20,7 @@ struct clada_ctx {
     int opt_prefix_tile;         // gate/up prefill GEMM: 0 choose by T, 1 = 128-token tiles, 2 = 256-token tiles
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)
     hipEvent_t ev[4];            // start/stop of the main decode kernel, start/stop of the final reduction
+    int capturing;               // a clada_graph_begin is open
     char err[512];
 };
 
