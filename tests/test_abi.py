@@ -88,6 +88,14 @@ def test_validation_without_gpu(lib):
     assert lib.clada_set_option(h, b"decode.b1", 2) == 0
     assert lib.clada_set_option(h, b"prefix.tile", 3) == 6
     assert lib.clada_set_option(h, b"prefix.tile", 2) == 0
+    # graph helpers: validation only (a context without a device cannot capture)
+    g = C.c_void_p()
+    assert lib.clada_graph_begin(h, None) == 6                       # the default stream cannot be captured
+    assert lib.clada_graph_begin(h, vp(base)) == 5                   # no workspace, no device
+    assert lib.clada_graph_end(h, vp(base), C.byref(g)) == 6 and not g.value     # no capture open
+    assert lib.clada_graph_end(h, vp(base), None) == 1
+    assert lib.clada_graph_launch(h, None, None) == 1
+    lib.clada_graph_destroy(None)
     lib.clada_destroy(h)
 
 
