@@ -879,8 +879,10 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     const float *b_out = relu ? layer->b_out : nullptr;
 
     // ---- split-d path (decode batch 1, whole-KiB rows, <= 64 neurons per workgroup)
+    // (exactly the instantiations launched below: a shape admitted here without one would fail the call)
     const bool b1_shape = relu ? (es == 2 && (nch == 2 || nch == 5 || nch == 8 || nch == 10))
-                               : (nch == 2 || nch == 8 || nch == 10 || (es == 2 && (nch == 4 || nch == 5)));
+                          : es == 2 ? (nch == 2 || nch == 4 || nch == 5 || nch == 8 || nch == 10)
+                                    : (nch == 2 || nch == 8);
     if (ctx->opt_decode_b1 >= 1 && B == 1 && (d * es) % 1024 == 0 && b1_shape) {
         const int Pb = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
         const int ni_b = (F + Pb - 1) / Pb;

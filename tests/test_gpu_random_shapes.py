@@ -1,5 +1,7 @@
 """GPU parity on seeded random shapes: the host code picks among several kernels by row length, neuron
 count, batch, dtype and family; this walks that choice with shapes nobody tuned for."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -9,6 +11,7 @@ import synth
 from gpu_util import BAND, DEV, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
 
 pytestmark = pytest.mark.gpu
+SEED_SHIFT = int(os.environ.get("CLADA_TEST_SEED_SHIFT", "0"))      # other shape draws for a longer hunt
 
 
 @pytest.fixture(scope="module")
@@ -19,7 +22,7 @@ def clada():
 
 
 def _cases(n=36):
-    rng = np.random.default_rng(20250219)
+    rng = np.random.default_rng(20250219 + SEED_SHIFT)
     widths = [512, 1024, 2048, 2560, 4096, 5120]             # whole-KiB bf16 rows: the batch-1 and batched kernels
     out = []
     for i in range(n):
@@ -82,8 +85,15 @@ def test_random_shape_parity(clada, i, dtype, d, F, B, kind, q):
     assert_close_y(to_np(ys), run(mask=np.broadcast_to(mask_gpu.any(0), (B, F)))["y"], TOL_Y[dtype], "static list")
 
 
+@pytest.mark.parametrize("d,F", [(2560, 346), (1280, 900), (1024, 700)])
+def test_fp32_rows_without_a_batch1_instantiation_use_the_generic_kernel(clada, d, F):
+    """fp32 rows of 10, 5 and 4 KiB at batch 1: whole-KiB rows for which only the bf16 layers have a
+    split-d kernel (a shape draw of the hunt above found the 10 KiB one rejected with a HIP error)."""
+    test_random_shape_parity(clada, 100 + d // 256, "f32", d, F, 1, "silu", 0.45)
+
+
 def _prefix_cases(n=18):
-    rng = np.random.default_rng(502)
+    rng = np.random.default_rng(502 + SEED_SHIFT)
     out = []
     for i in range(n):
         dtype = "bf16" if rng.random() < 0.75 else "f32"
@@ -114,7 +124,10 @@ def test_random_shape_prefix_stats(clada, i, dtype, d, F, T, kind, tile):
         ref = oracle.prefix_stats(*w, X, sigma=kind)
     st = clada.prefix_stats(ctx, layer, to_dev(X, dtype))
     torch.cuda.synchronize()
-    np.testing.assert_allclose(to_np(st.abs_act_pool), ref["abs_act_pool"], rtol=1e-4, atol=2e-6)
+    # fp32 accumulation of d products: the absolute error of a pre-activation scales with the largest ones
+    # (a ReLU passes them on undamped), so the absolute floor does too
+    np.testing.assert_allclose(to_np(st.abs_act_pool), ref["abs_act_pool"], rtol=1e-4,
+                               atol=2e-6 * max(1.0, float(ref["abs_act_pool"].max())))
     for name in ("sum_abs_act", "sum_sq_act", "max_abs_act", "sum_sq_h", "A"):
         np.testing.assert_allclose(to_np(getattr(st, name)), ref[name], rtol=3e-5, atol=1e-6, err_msg=name)
     assert_close_y(to_np(st.y), ref["y"], TOL_Y[dtype], "prefill y")
