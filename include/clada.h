@@ -62,7 +62,7 @@ typedef enum { CLADA_F32 = 0, CLADA_BF16 = 1 } clada_dtype;
  * the caller's tensors and stream live on. */
 clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes);
 void clada_destroy(clada_ctx *ctx);
-const char *clada_status_str(clada_status s);
+const char *clada_status_str(int32_t s);   /* s: a clada_status; any other value gives "CLADA_ERR_UNKNOWN" */
 const char *clada_last_error(const clada_ctx *ctx);
 
 /* Launch-shape tuning knobs; results never depend on them beyond fp32 summation
@@ -116,8 +116,8 @@ typedef enum { CLADA_FFN_SWIGLU = 0, CLADA_FFN_RELU = 1, CLADA_FFN_GEGLU = 2 } c
 typedef struct {
     const void *w_gate, *w_up, *w_down; /* device, each [d_ff][d] neuron-major */
     int32_t d, d_ff;
-    clada_dtype dtype;
-    clada_ffn_kind kind;
+    int32_t dtype;                      /* a clada_dtype; an unknown value is CLADA_ERR_DTYPE */
+    int32_t kind;                       /* a clada_ffn_kind; an unknown value is CLADA_ERR_VALUE */
     const float *b_in, *b_out;          /* CLADA_FFN_RELU only */
 } clada_layer;
 
@@ -178,13 +178,13 @@ clada_status clada_cett_eval(clada_ctx *ctx, const clada_layer *layer, const voi
                              float eps, float *cett_out, float *mean_out, void *hip_stream);
 
 /* Cognitive-load signals (section 2.3.1, surprisal and entropy equations), per
- * row b of logits [B][V] (fp32 or bf16), natural log:
+ * row b of logits [B][V] (logits_dtype: a clada_dtype, fp32 or bf16), natural log:
  *   surprisal[b] = -log softmax(z_b)[token_ids[b]],  entropy[b] = -sum_v p_v log p_v.
  * One pass over the logits (online log-sum-exp).  A row holding NaN or +inf, or
  * only -inf, yields NaN for both; a token id outside [0,V) yields NaN surprisal.
  * These are device-side values: no status is raised for them. */
 clada_status clada_cognitive_signals(clada_ctx *ctx, const void *logits,
-                                     clada_dtype logits_dtype, int32_t B, int32_t V,
+                                     int32_t logits_dtype, int32_t B, int32_t V,
                                      const int32_t *token_ids, float *surprisal,
                                      float *entropy, void *hip_stream);
 

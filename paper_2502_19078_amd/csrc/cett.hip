@@ -233,11 +233,12 @@ extern "C" clada_status clada_threshold_search_cett(clada_ctx *ctx, const clada_
                                                     int32_t T, float bound, int32_t n_probes, float *tau_base_out,
                                                     float *mean_cett_out, void *hip_stream)
 {
-    clada_status st = check_common(ctx, layer, x_val, T);
-    if (st != CLADA_OK) return st;
+    if (!ctx) return CLADA_ERR_NULL;
     if (!tau_base_out) return clada_fail(ctx, CLADA_ERR_NULL, "tau_base_out is NULL");
     if (!(bound >= 0.0f && bound < 1.0f)) return clada_fail(ctx, CLADA_ERR_VALUE, "bound=%g outside [0,1)", (double)bound);
     if (n_probes < 1 || n_probes > 31) return clada_fail(ctx, CLADA_ERR_VALUE, "n_probes=%d outside [1,31]", n_probes);
+    clada_status st = check_common(ctx, layer, x_val, T);
+    if (st != CLADA_OK) return st;
     hipStream_t stream = (hipStream_t)hip_stream;
     const CettWs w = carve(ctx->ws + CLADA_WS_HEADER, layer->d, layer->d_ff, T);
     st = begin(ctx, layer, x_val, T, w, 1, 0.0f, stream);

@@ -105,7 +105,7 @@ void clada_destroy(clada_ctx *ctx)
     delete ctx;
 }
 
-const char *clada_status_str(clada_status s)
+const char *clada_status_str(int32_t s)
 {
     switch (s) {
     case CLADA_OK: return "CLADA_OK";

@@ -48,7 +48,7 @@ clada_status clada_fail(clada_ctx *ctx, clada_status s, const char *fmt, ...);
                               hipGetErrorString(e_));                                       \
     } while (0)
 
-static inline size_t dtype_size(clada_dtype t) { return t == CLADA_F32 ? 4 : 2; }
+static inline size_t dtype_size(int32_t t) { return t == CLADA_F32 ? 4 : 2; }
 static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 // Validation shared by the FFN calls.

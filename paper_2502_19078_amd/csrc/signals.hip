@@ -186,7 +186,7 @@ size_t clada_ws_signals(int32_t B, int32_t V)
 }
 
 extern "C" clada_status clada_cognitive_signals(clada_ctx *ctx, const void *logits,
-                                                clada_dtype logits_dtype, int32_t B, int32_t V,
+                                                int32_t logits_dtype, int32_t B, int32_t V,
                                                 const int32_t *token_ids, float *surprisal,
                                                 float *entropy, void *hip_stream)
 {

@@ -77,6 +77,12 @@ def test_validation_without_gpu(lib):
     assert lib.clada_threshold_calibrate(h, vp(base), 0, f(0.4), vp(base), None) == 2
     assert lib.clada_threshold_calibrate(h, vp(base), 10, f(1.0), vp(base), None) == 6
     assert lib.clada_threshold_calibrate(h, vp(base), 10, f(0.4), vp(base), None) == 5
+    # scalar checks come before the workspace check
+    assert lib.clada_threshold_search_cett(h, C.byref(ok), vp(base), 4, f(0.2), 0, vp(base), vp(base), None) == 6
+    assert lib.clada_threshold_search_cett(h, C.byref(ok), vp(base), 4, f(1.0), 8, vp(base), vp(base), None) == 6
+    assert lib.clada_static_mask_topk(h, vp(base), 32, 33, vp(base), vp(base), None) == 6
+    assert lib.clada_static_mask_topk(h, vp(base), 32, 8, vp(base), vp(base), None) == 5
+    assert lib.clada_status_str(99) == b"CLADA_ERR_UNKNOWN"
     out = b._CPrefixOut()
     assert lib.clada_prefix_stats(h, C.byref(ok), vp(base), 0, None, C.byref(out), None) == 2
     assert lib.clada_prefix_stats(h, C.byref(ok), vp(base), 4, None, None, None) == 1
