@@ -5,18 +5,20 @@
 // 16-wide M dimension.  Weights are still read once, and only for neurons kept by at least
 // one token (the union); every output row uses its own mask.
 //
-//   kernel A (gate + up -> h): workgroup p owns a contiguous run of neurons (whole octets, dealt
-//     out evenly), taken 16 at a time.  Its 8 waves
+//   kernel A (gate + up -> h): workgroup p owns a contiguous run of neurons (dealt out
+//     evenly, to within one), taken 16 at a time.  Its 8 waves
 //     split the d (= K) dimension: wave w keeps its slice of x as MFMA A-fragments in registers
 //     for the whole kernel and streams its slice of the 16 weight rows as B-fragments (lane =
 //     (neuron, k-group): 128 contiguous bytes of a row per pair of instructions, the row's whole slice over
 //     the k loop).  The 8 partial 16x16 tiles are summed through LDS in fixed order; SiLU, the
-//     per-token fp32 compare and the per-neuron 16-bit keep masks follow.  A ballot compacts
-//     the workgroup's union-kept neurons; the same MFMA loop over W_up rows gathered through
-//     that list gives u, and h = keep ? a*u : 0 goes to a [16][d_ff] fp32 buffer, together with
-//     one union flag per neuron.
+//     per-token fp32 compare and the per-neuron 16-bit keep masks follow.  The neurons of gate tile i
+//     that at least one token keeps (the union) are compacted by ballot and form up tile i: the same
+//     MFMA loop over their W_up rows gives u, and h = keep ? a*u : 0 goes to a [d_ff][16] fp32 buffer (16 tokens of a neuron = one 64-byte line).
+//     Gate and up tiles alternate (G0 G1 U0 G2 U1 ...), so the stream of row loads does not drain
+//     between the two projections.  The workgroup also leaves the list of its union-kept neurons,
+//     ascending, and their count for kernel B.
 //   kernel B (down): 2-D split -- column groups of 256 x row groups (a fixed range of neuron
-//     indices each, its kept neurons compacted from the union flags by ballot + scan), so only
+//     indices each: the lists of the gate/up workgroups that own them, laid end to end), so only
 //     R partial y's exist instead of one per workgroup.  Work is dealt to the waves in units of 32
 //     neurons x 128 columns (wave w: column half w & 1, neuron blocks w >> 1, + 4, ...).  W_down
 //     rows arrive as 256-byte segments, are staged per wave in LDS and read
@@ -34,8 +36,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 struct BatParams {
     const char *wg, *wu, *wd, *x;
     const float *tau;           // [B]
-    float *hbuf;                // [16][F] fp32, written for union-kept neurons only
-    unsigned char *uflag;       // [F] 1 iff the neuron is kept by at least one token
+    float *hbuf;                // [F][16] fp32 (neuron-major: one 64-byte line per neuron), written for union-kept neurons only
+    int *ulist;                 // [F] union-kept neurons: gate/up workgroup q writes its own, ascending, from
+                                //     the first neuron it owns (8 * (q * ceil(F/8) / P)) on
+    int *ucnt;                  // [P] how many each wrote
     unsigned char *keep;        // [B][F] or nullptr
     float *partial;             // [RG][B][d]
     int d, F, B, P, RG, CG;
@@ -46,6 +50,12 @@ __device__ __forceinline__ f32x4 mfma16(const u32x4 a, const u32x4 b, const f32x
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
+
+// a line of zeros in global memory (never written): what a load of a row that does not exist reads
+__device__ __align__(16) unsigned int k_zero16[4] = {0u, 0u, 0u, 0u};
+
+// first neuron of gate/up workgroup w of P (w = P: d_ff)
+__host__ __device__ __forceinline__ int bat_run_lo(int w, int F, int P) { return (int)((long long)w * F / P); }
 
 constexpr int MAX_TILES = 4;    // 16-neuron tiles per workgroup in kernel A (one 64-lane ballot compacts them)
 
@@ -58,6 +68,7 @@ k_bat_gateup(const BatParams p)
     __shared__ float s_a[MAX_TILES][16][16];
     __shared__ int s_km[MAX_TILES * 16];
     __shared__ int s_ul[MAX_TILES * 16];
+    __shared__ int s_ku[MAX_TILES];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -90,14 +101,12 @@ k_bat_gateup(const BatParams p)
         ld_row[i] = o / PB;
         ld_col[i] = o % PB;
     }
-    // Neurons are dealt out in contiguous runs of whole octets: workgroup q owns octets
-    // [q no / P, (q+1) no / P), at most 64 neurons, so every workgroup streams the same number of
-    // rows to within 8 (16-neuron granularity would leave an eighth of the chip idle at the end).
-    // A run longer than 64 neurons (d_ff above 16384) is worked off in rounds of 64: one ballot
-    // compacts a round's kept neurons.
-    const int no = (F + 7) / 8;
-    const int j_lo_all = 8 * (int)((long long)blk * no / P);
-    const int j_hi_all = min(8 * (int)((long long)(blk + 1) * no / P), F);
+    // Neurons are dealt out in contiguous runs: workgroup q owns [q F / P, (q+1) F / P), so every
+    // workgroup streams the same number of rows to within one (a row that a tile lacks costs no
+    // memory traffic; 16-neuron granularity would leave an eighth of the chip idle at the end).
+    // A run longer than 64 neurons (d_ff above 16384) is worked off in rounds of 64.
+    const int j_lo_all = bat_run_lo(blk, F, P);
+    const int j_hi_all = bat_run_lo(blk + 1, F, P);
 
     // this wave's slice of x as A-fragments: lane = (token n, k-group q)
     u32x4 xa[KSTEPS];
@@ -109,19 +118,6 @@ k_bat_gateup(const BatParams p)
     }
     __syncthreads();
 
-    // eight rows (half a tile) of one part; a row that does not exist (row < 0) loads nothing and
-    // contributes zeros
-    auto rows_load = [&](u32x4 (&wr)[NL], const char *w, auto row_of, int unit, int half) {
-        const int tile = unit / NPART, part = unit % NPART;
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int row = row_of(tile, 8 * half + ld_row[i]);
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (row >= 0)
-                v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(w + (size_t)row * rowb + koff + part * PB + ld_col[i]));
-            wr[i] = v;
-        }
-    };
     auto stage_write = [&](const u32x4 (&wr)[NL], int half) {
 #pragma unroll
         for (int i = 0; i < NL; ++i)
@@ -145,39 +141,6 @@ k_bat_gateup(const BatParams p)
 #pragma unroll
         for (int r = 0; r < 4; ++r) s_part[buf][wave][r * 64 + lane] = acc[r];
     };
-    // One pass over a list of tiles: D = X_slice * W_slice^T partial over this wave's k-slice.  The
-    // rows of the next part are requested as soon as the current ones sit in LDS; every path keeps
-    // a fixed number of loads in flight.
-    auto tile_pass = [&](const char *w, int ntiles, auto row_of, auto reduce) {
-        u32x4 wa[NL], wb[NL];
-        const int nunits = ntiles * NPART;
-        if (nunits > 0) {
-            rows_load(wa, w, row_of, 0, 0);
-            rows_load(wb, w, row_of, 0, 1);
-        }
-        for (int i = 0; i < ntiles; ++i) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int part = 0; part < NPART; ++part) {        // unrolled: x fragments stay in registers
-                const int u = i * NPART + part;
-                wave_sync();                                  // the previous part's fragment reads are done
-                if (u + 1 < nunits) {
-                    stage_write(wa, 0);
-                    rows_load(wa, w, row_of, u + 1, 0);
-                    stage_write(wb, 1);
-                    rows_load(wb, w, row_of, u + 1, 1);
-                } else {
-                    stage_write(wa, 0);
-                    stage_write(wb, 1);
-                }
-                wave_sync();
-                acc = part_mma(part, acc);
-            }
-            part_store(acc, i & 1);
-            __syncthreads();
-            reduce(i);
-        }
-    };
     // element (r, ln) of the 16x16 tile: token m = 4*(ln/16) + r, neuron ln%16; waves summed in order
     auto tile_sum = [&](int buf, int e) {
         float s = 0.0f;
@@ -185,6 +148,10 @@ k_bat_gateup(const BatParams p)
         for (int w = 0; w < 8; ++w) s += s_part[buf][w][e];
         return s;
     };
+    int nlist = 0;                                          // entries of this workgroup's union list so far (uniform)
+    // the token this thread compares for in the gate reduction, and its threshold (kept out of the tile loop)
+    const int red_m = 4 * ((tid & 63) >> 4) + (tid >> 6);
+    const float red_tau = (!DENSE && tid < 256 && red_m < B) ? p.tau[red_m] : 0.0f;
     for (int j_lo = j_lo_all; j_lo < j_hi_all; j_lo += 16 * MAX_TILES) {
     const int j_hi = min(j_lo + 16 * MAX_TILES, j_hi_all);
     const int nown = j_hi - j_lo;                           // <= 64
@@ -192,53 +159,130 @@ k_bat_gateup(const BatParams p)
     __syncthreads();                                        // the previous round is done with s_km, s_a, s_ul
     if (tid < MAX_TILES * 16) s_km[tid] = 0;
     __syncthreads();
-    auto gate_row = [&](int i, int rr) { return 16 * i + rr < nown ? j_lo + 16 * i + rr : -1; };
-    auto gate_reduce = [&](int i) {
+
+    // Every 16-neuron gate tile G_i is followed, one tile later, by the up tile U_i over the neurons of
+    // G_i that at least one token keeps: G0 G1 U0 G2 U1 ... G_{ni-1} U_{ni-2} U_{ni-1}.  The rows of
+    // the next tile in this order are requested while the current one is worked on, so the stream of
+    // loads never drains between the gate and the up projection; U_i's rows are known by then
+    // because G_i was reduced before the tile in front of U_i started.  (A single tile, ni = 1, has
+    // nothing to put between G0 and U0: U0's rows are requested only after G0 is reduced.)
+    const int nseq = 2 * ni;
+    auto seq_tile = [&](int sq, int &up, int &i) {
+        if (ni == 1) { up = sq; i = 0; }
+        else if (sq < 2) { up = 0; i = sq; }
+        else if (sq == nseq - 1) { up = 1; i = ni - 1; }
+        else if (sq & 1) { up = 0; i = (sq + 1) >> 1; }
+        else { up = 1; i = (sq >> 1) - 1; }
+    };
+    // Eight rows (half a tile) of one part of gate tile ti (up = 0: its neurons in order) or up tile ti
+    // (up = 1: its union-kept neurons through the compacted list).  A row that does not exist reads
+    // one shared line of zeros instead (a select on the address: no branch around any load).  up and ti are uniform; the list is read whether used or not, so
+    // the loads are issued without a branch on the kind of tile.
+    auto rows_load = [&](u32x4 (&wr)[NL], int up, int ti, int part, int half) {
+        const char *base = (up ? p.wu : p.wg) + (size_t)(j_lo + 16 * ti) * rowb + koff + part * PB;
+        const int lim = up ? s_ku[ti] : nown - 16 * ti;
+        int lr[NL];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int rr = 8 * half + ld_row[i];
+            const int viaList = s_ul[16 * ti + rr];
+            lr[i] = up ? viaList : rr;
+        }
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const char *src = 8 * half + ld_row[i] < lim ? base + (size_t)lr[i] * rowb + ld_col[i]
+                                                         : reinterpret_cast<const char *>(k_zero16);
+            wr[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+        }
+    };
+    auto gate_reduce = [&](int i, int buf) {
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
             const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = j_lo + 16 * i + nn;
-            const float a = gate_sigma_f32(tile_sum(i & 1, tid), p.gelu);
+            const float a = gate_sigma_f32(tile_sum(buf, tid), p.gelu);
             const bool valid = m < B && j < j_hi;
-            const bool keep = valid && (DENSE ? true : (fabsf(a) >= p.tau[m]));
+            const bool keep = valid && (DENSE ? true : (fabsf(a) >= red_tau));
             s_a[i][m][nn] = a;
             if (keep) atomicOr(&s_km[i * 16 + nn], 1 << m);
             if (p.keep && valid) p.keep[(size_t)m * F + j] = keep ? 1 : 0;
         }
     };
-
-    // ---------------------------------------------------------------- gate tiles
-    tile_pass(p.wg, ni, gate_row, gate_reduce);
-    __syncthreads();
-
-    // ---------------------------------------------------------------- union compaction (every wave)
-    const bool mine = lane < nown && s_km[lane] != 0;
-    const unsigned long long bal = __ballot(mine);
-    const int ku = __popcll(bal);
-    if (mine) s_ul[__popcll(bal & ((1ull << lane) - 1ull))] = lane;
-    if (wave == 0 && lane < nown) p.uflag[j_lo + lane] = mine ? 1 : 0;   // union flag of every owned neuron, for kernel B
-
-    // ---------------------------------------------------------------- up tiles over the union list
-    const int nu = (ku + 15) / 16;
-    auto up_row = [&](int u, int rr) {
-        const int e = 16 * u + rr;
-        return e < ku ? j_lo + s_ul[e] : -1;
+    // Union-kept neurons of gate tile i, compacted by ballot.  Every wave does it for itself (same
+    // values to the same LDS words), so a wave only ever reads what it wrote; wave 0 appends them
+    // to the workgroup's list in global memory for the down kernel.
+    auto compact = [&](int i) {
+        const bool mine = lane < 16 && s_km[16 * i + lane] != 0;       // never set past nown
+        const unsigned long long bal = __ballot(mine);
+        const int pos = __popcll(bal & ((1ull << lane) - 1ull));
+        if (mine) s_ul[16 * i + pos] = lane;
+        if (lane == 0) s_ku[i] = __popcll(bal);
+        if (wave == 0 && mine) p.ulist[j_lo_all + nlist + pos] = j_lo + 16 * i + lane;
+        nlist += __popcll(bal);
+        wave_sync();
     };
-    auto up_reduce = [&](int u) {
+    auto up_reduce = [&](int i, int buf) {
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
             const int m = 4 * (ln >> 4) + r, nn = ln & 15;
-            const int e2 = 16 * u + nn;
-            if (e2 < ku) {
-                const int l2 = s_ul[e2];
-                const int j = j_lo + l2;
-                const float usum = tile_sum(u & 1, tid);
-                const bool keep = (s_km[l2] >> m) & 1;
-                p.hbuf[(size_t)m * F + j] = keep ? s_a[l2 >> 4][m][l2 & 15] * usum : 0.0f;
+            if (nn < s_ku[i]) {
+                const int l2 = s_ul[16 * i + nn];
+                const int j = j_lo + 16 * i + l2;
+                const float usum = tile_sum(buf, tid);
+                const bool keep = (s_km[16 * i + l2] >> m) & 1;
+                p.hbuf[(size_t)j * 16 + m] = keep ? s_a[i][m][l2] * usum : 0.0f;
             }
         }
     };
-    tile_pass(p.wu, nu, up_row, up_reduce);
+
+    // D = X_slice * W_slice^T partial over this wave's k-slice, one tile of the sequence after the other
+    u32x4 wa[NL], wb[NL];
+    bool have = false;                                      // wa/wb hold the rows of the unit about to start
+    int ncomp = 0;                                          // gate tiles compacted so far
+    for (int sq = 0; sq < nseq; ++sq) {
+        int up, ti, nup = 0, nti = 0;
+        seq_tile(sq, up, ti);
+        bool nready = false;                                  // the tile after this one can be requested already
+        if (sq + 1 < nseq) {
+            seq_tile(sq + 1, nup, nti);
+            nready = !nup || nti < ncomp;
+        }
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int part = 0; part < NPART; ++part) {            // unrolled: x fragments stay in registers
+            if (!have) {
+                rows_load(wa, up, ti, part, 0);
+                rows_load(wb, up, ti, part, 1);
+            }
+            const bool last = part == NPART - 1;
+            const bool nxt = last ? nready : true;
+            const int lup = last ? nup : up, lti = last ? nti : ti, lpart = last ? 0 : part + 1;
+            wave_sync();                                      // the previous part's fragment reads are done
+            if (nxt) {
+                stage_write(wa, 0);
+                rows_load(wa, lup, lti, lpart, 0);
+                stage_write(wb, 1);
+                rows_load(wb, lup, lti, lpart, 1);
+            } else {
+                stage_write(wa, 0);
+                stage_write(wb, 1);
+            }
+            have = nxt;
+            wave_sync();
+            acc = part_mma(part, acc);
+        }
+        part_store(acc, sq & 1);
+        __syncthreads();
+        if (!up) {
+            gate_reduce(ti, sq & 1);
+            __syncthreads();                                  // the tile's keep masks are complete
+            compact(ti);
+            ++ncomp;
+        } else {
+            up_reduce(ti, sq & 1);
+        }
+    }
     }   // rounds
+    if (tid == 0) p.ucnt[blk] = nlist;
 }
 
 constexpr int DN_COLS = 256;                    // columns per workgroup in kernel B
@@ -246,6 +290,7 @@ constexpr int DN_SUB = 128;                     // columns staged per pass
 constexpr int DN_PITCH = DN_SUB * 2 + 32;       // LDS row pitch (bytes): 4 rows of a transpose read hit distinct banks
 constexpr int DN_TILE_BYTES = 32 * DN_PITCH;    // one wave's staging tile: 32 neurons x 128 columns
 constexpr int DN_MAX_ROWS = 2048;               // union neurons per row group
+constexpr int DN_MAX_WGS = 64;                  // gate/up workgroups per row group
 
 __global__ void __launch_bounds__(512)
 k_bat_down(const BatParams p)
@@ -253,8 +298,6 @@ k_bat_down(const BatParams p)
     extern __shared__ __align__(16) unsigned char smem_dn[];
     unsigned char *s_tile = smem_dn;                                    // [8][DN_TILE_BYTES], later the fold buffers
     int *s_rows = reinterpret_cast<int *>(smem_dn + 8 * DN_TILE_BYTES); // [DN_MAX_ROWS]
-    __shared__ int s_scan[8];
-    __shared__ int s_rng[2];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -263,28 +306,41 @@ k_bat_down(const BatParams p)
     const size_t rowb = (size_t)d * 2;
     const int col0 = cg * DN_COLS;
 
-    // ---- this row group's neurons [jlo, jhi): kept ones compacted in ascending order (ballot + scan)
-    const int jlo = (int)((long long)rg * F / p.RG), jhi = (int)((long long)(rg + 1) * F / p.RG);
-    if (tid == 0) s_rng[0] = 0;
-    __syncthreads();
-    for (int j0 = jlo; j0 < jhi; j0 += 512) {
-        const int j = j0 + tid;
-        const bool k = j < jhi && p.uflag[j] != 0;
-        const unsigned long long bal = __ballot(k);
-        if (lane == 0) s_scan[wave] = __popcll(bal);
-        __syncthreads();
-        int off = s_rng[0];
-        for (int w = 0; w < wave; ++w) off += s_scan[w];
-        if (k) s_rows[off + __popcll(bal & ((1ull << lane) - 1ull))] = j;
-        __syncthreads();
-        if (tid == 0) {
-            int t = s_rng[0];
-            for (int w = 0; w < 8; ++w) t += s_scan[w];
-            s_rng[0] = t;
-        }
-        __syncthreads();
+    // ---- this row group's neurons = those of the gate/up workgroups [w0, w1): their union lists, laid end
+    // to end (ascending).  The list entries are requested before the counts are known; an entry past
+    // its workgroup's count is stale memory inside the list array and is dropped.
+    const int w0 = (int)((long long)rg * p.P / p.RG), w1 = (int)((long long)(rg + 1) * p.P / p.RG);
+    const int nw = w1 - w0;                                             // <= DN_MAX_WGS (host check)
+    auto run_lo = [&](int w) { return bat_run_lo(w, F, p.P); };
+    const int cnt_l = lane < nw ? p.ucnt[w0 + lane] : 0;               // every wave: the counts, one per lane
+    constexpr int PRE = 4;                                              // entries per thread held in registers
+    int pre_v[PRE];
+#pragma unroll
+    for (int k = 0; k < PRE; ++k) {
+        const int w = wave + 8 * k;
+        const int jj = w < nw ? run_lo(w0 + w) + lane : F;
+        pre_v[k] = jj < F ? p.ulist[jj] : 0;
     }
-    const int nrows = s_rng[0];                                         // <= DN_MAX_ROWS (host check on F)
+    int inc = cnt_l;                                                    // inclusive scan over the lanes
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    const int exc = inc - cnt_l;
+    const int nrows = __shfl(inc, 63);                                  // <= DN_MAX_ROWS (host check)
+#pragma unroll
+    for (int k = 0; k < PRE; ++k) {
+        const int w = wave + 8 * k, ws = w < nw ? w : 0;
+        const int c = __shfl(cnt_l, ws), o = __shfl(exc, ws);
+        if (w < nw && lane < c) s_rows[o + lane] = pre_v[k];
+    }
+    // whatever the registers did not cover: more than 8 * PRE workgroups, or lists longer than 64
+    for (int w = wave; w < nw; w += 8) {
+        const int c = __shfl(cnt_l, w), o = __shfl(exc, w);
+        for (int e = (w < 8 * PRE ? 64 : 0) + lane; e < c; e += 64) s_rows[o + e] = p.ulist[run_lo(w0 + w) + e];
+    }
+    __syncthreads();
 
     // Wave w works on column half sub = w & 1 of the workgroup's 256 columns and on the 32-neuron
     // blocks rw, rw + 4, ... (rw = w >> 1): units of 32 rows x 128 columns dealt round-robin, so the
@@ -304,7 +360,7 @@ k_bat_down(const BatParams p)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int e = 32 * kb + 8 * q + i;
-            hv[i] = (e < nrows && n < B) ? p.hbuf[(size_t)n * F + s_rows[e]] : 0.0f;
+            hv[i] = (e < nrows && n < B) ? p.hbuf[(size_t)s_rows[e] * 16 + n] : 0.0f;
         }
     };
     // W_down[32 list entries][128 columns]: half-waves read 256-byte row pieces
@@ -419,7 +475,8 @@ k_bat_down(const BatParams p)
 
 size_t clada_ws_decode_batched(int32_t d_ff)
 {
-    return align_up(sizeof(float) * 16 * (size_t)d_ff, 256) + align_up((size_t)d_ff, 256);
+    return align_up(sizeof(float) * 16 * (size_t)d_ff, 256) + align_up(sizeof(int) * (size_t)d_ff, 256) +
+           align_up(sizeof(int) * COOP_MAX_WGS, 256);
 }
 
 // Returns CLADA_OK when the batched MFMA path ran, CLADA_ERR_SHAPE (without touching ctx->err) when
@@ -440,14 +497,24 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     int RG = P / CG;
     if (RG < 1) RG = 1;
     if (RG > 16) RG = 16;
-    while ((F + RG - 1) / RG + 1 > DN_MAX_ROWS && RG < 64) RG *= 2;     // wide layers: more, smaller row groups
-    if ((F + RG - 1) / RG + 1 > DN_MAX_ROWS) return CLADA_OK;
+    // row group rg = the neurons of the gate/up workgroups [rg P / RG, (rg+1) P / RG)
+    auto group_fits = [&](int rgs) {
+        if (rgs > P) return false;
+        for (int rg = 0; rg < rgs; ++rg) {
+            const int w0 = (int)((long long)rg * P / rgs), w1 = (int)((long long)(rg + 1) * P / rgs);
+            if (w1 - w0 > DN_MAX_WGS || bat_run_lo(w1, F, P) - bat_run_lo(w0, F, P) > DN_MAX_ROWS) return false;
+        }
+        return true;
+    };
+    while (!group_fits(RG) && RG < 64) RG *= 2;                         // wide layers: more, smaller row groups
+    if (!group_fits(RG)) return CLADA_OK;
 
     BatParams p;
     p.wg = (const char *)layer->w_gate; p.wu = (const char *)layer->w_up; p.wd = (const char *)layer->w_down;
     p.x = (const char *)x; p.tau = tau;
     p.hbuf = reinterpret_cast<float *>(scratch);
-    p.uflag = reinterpret_cast<unsigned char *>(scratch + align_up(sizeof(float) * 16 * (size_t)F, 256));
+    p.ulist = reinterpret_cast<int *>(scratch + align_up(sizeof(float) * 16 * (size_t)F, 256));
+    p.ucnt = reinterpret_cast<int *>(scratch + align_up(sizeof(float) * 16 * (size_t)F, 256) + align_up(sizeof(int) * (size_t)F, 256));
     p.keep = keep; p.partial = partial;
     p.d = d; p.F = F; p.B = B; p.P = P; p.RG = RG; p.CG = CG;
     p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
