@@ -310,51 +310,69 @@ __global__ void __launch_bounds__(1024)
 k_ffn_lists(const unsigned char *__restrict__ keep, int B, int F, int32_t *__restrict__ active_idx,
             int32_t *__restrict__ n_active, uint32_t *__restrict__ mask_bits)
 {
-    // Thread t owns the 32-flag words [t*wpt, (t+1)*wpt): it packs each token's flags into mask
-    // words, ORs them into union words, and after one workgroup-wide exclusive scan of the union
-    // popcounts writes its neurons' indices in ascending order.
+    // Pass 1, over (token, 32-flag word) pairs dealt to the threads round-robin (consecutive lanes =
+    // consecutive words of one token, so the tokens' rows are read side by side instead of one after
+    // the other): pack the flags into a mask word, OR it into the union word in LDS, count.
+    // Pass 2: thread t owns the union words [t*wpt, (t+1)*wpt) and, after one workgroup-wide exclusive
+    // scan of their popcounts, writes its neurons' indices in ascending order.
     __shared__ int s_wave[16];
     __shared__ int s_tok_cnt[CLADA_MAX_BATCH];
+    __shared__ unsigned int s_uni[CLADA_MAX_DFF / 32];
     constexpr int MAXW = 8;                                   // words per thread: covers d_ff <= 262144
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int words = (F + 31) / 32;
+    if (tid < CLADA_MAX_BATCH) s_tok_cnt[tid] = 0;
+    for (int w = tid; w < words; w += 1024) s_uni[w] = 0u;
+    __syncthreads();
+    const int pairs = B * words;
+    for (int idx0 = 0; idx0 < pairs; idx0 += 1024) {          // every lane stays in the loop: wave-wide sums below
+        const int idx = idx0 + tid;
+        const bool valid = idx < pairs;
+        const int b = valid ? idx / words : B - 1, w = valid ? idx - b * words : 0;
+        const unsigned char *row = keep + (size_t)b * F;
+        unsigned int bits = 0u;
+        const int j0 = 32 * w, nj = valid ? min(32, F - j0) : 0;
+        if (nj == 32 && (reinterpret_cast<size_t>(row + j0) & 3) == 0) {
+            // four flags per 32-bit load: high bit of every non-zero byte, gathered into a nibble
+            // by a multiplication whose sixteen partial products all land on different bits
+            const uint4 *r16 = reinterpret_cast<const uint4 *>(row + j0);
+            unsigned int v[8];
+            if ((reinterpret_cast<size_t>(r16) & 15) == 0) {
+                const uint4 lo = r16[0], hi = r16[1];
+                v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+            } else {
+                const unsigned int *r4 = reinterpret_cast<const unsigned int *>(row + j0);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = r4[e];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned int nz = ((((v[e] & 0x7f7f7f7fu) + 0x7f7f7f7fu) | v[e]) & 0x80808080u) >> 7;
+                bits |= ((nz * 0x01020408u) >> 24) << (4 * e);
+            }
+        } else {
+            for (int e = 0; e < nj; ++e) bits |= (row[j0 + e] != 0 ? 1u : 0u) << e;
+        }
+        if (mask_bits && valid) mask_bits[(size_t)b * words + w] = bits;
+        if (bits) atomicOr(&s_uni[w], bits);
+        // per-token counts: one LDS atomic per wave where the whole wave works on one token
+        const int pc = __popc(bits);
+        const int b0 = __builtin_amdgcn_readfirstlane(b);
+        if (__all(b == b0)) {
+            int t = pc;
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) t += __shfl_xor(t, o);
+            if (lane == 0 && t) atomicAdd(&s_tok_cnt[b0], t);
+        } else if (pc) {
+            atomicAdd(&s_tok_cnt[b], pc);
+        }
+    }
+    __syncthreads();
     const int wpt = (words + 1023) / 1024;
     const int w0 = min(words, tid * wpt), w1 = min(words, w0 + wpt);
-    if (tid < CLADA_MAX_BATCH) s_tok_cnt[tid] = 0;
-    __syncthreads();
     unsigned int uni[MAXW];
 #pragma unroll
-    for (int i = 0; i < MAXW; ++i) uni[i] = 0u;
-    for (int b = 0; b < B; ++b) {
-        const unsigned char *row = keep + (size_t)b * F;
-        const bool row_al4 = (reinterpret_cast<size_t>(row) & 3) == 0;
-        int cnt = 0;
-#pragma unroll
-        for (int i = 0; i < MAXW; ++i) {
-            const int w = w0 + i;
-            if (w < w1) {
-                unsigned int bits = 0u;
-                const int j0 = 32 * w, nj = min(32, F - j0);
-                if (nj == 32 && row_al4) {
-                    // four flags per 32-bit load: high bit of every non-zero byte, gathered into a nibble
-                    // by a multiplication whose sixteen partial products all land on different bits
-                    const unsigned int *r4 = reinterpret_cast<const unsigned int *>(row + j0);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const unsigned int v = r4[e];
-                        const unsigned int nz = ((((v & 0x7f7f7f7fu) + 0x7f7f7f7fu) | v) & 0x80808080u) >> 7;
-                        bits |= ((nz * 0x01020408u) >> 24) << (4 * e);
-                    }
-                } else {
-                    for (int e = 0; e < nj; ++e) bits |= (row[j0 + e] != 0 ? 1u : 0u) << e;
-                }
-                if (mask_bits) mask_bits[(size_t)b * words + w] = bits;
-                uni[i] |= bits;
-                cnt += __popc(bits);
-            }
-        }
-        if (cnt) atomicAdd(&s_tok_cnt[b], cnt);
-    }
+    for (int i = 0; i < MAXW; ++i) uni[i] = w0 + i < w1 ? s_uni[w0 + i] : 0u;
     int c = 0;
 #pragma unroll
     for (int i = 0; i < MAXW; ++i) c += __popc(uni[i]);
