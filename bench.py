@@ -416,9 +416,11 @@ def main():
 def pmc_probe(cfg, args, clada, binding, synth, torch, dev):
     """Short fixed workload for hardware-counter runs: 4 seeded layers of the configuration, 3 rounds of
     sparse calls at two sparsities (0.45 and 0.62), 4 dense-twin calls, 3 copies of a 256 MiB buffer
-    (the known-size transfer the FETCH_SIZE / WRITE_SIZE counters are scaled by)."""
+    (the known-size transfer the FETCH_SIZE / WRITE_SIZE counters are scaled by).  Batch 1 unless --batch
+    is given (then --shared-frac applies to the tokens of the batch)."""
     d, F = cfg.d, cfg.d_ff
-    ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, cfg.T, 0))
+    B = args.batch or 1
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, B, cfg.T, 0))
     for opt in args.option:
         k, v = opt.split("=")
         ctx.set_option(k, int(v))
@@ -429,13 +431,13 @@ def pmc_probe(cfg, args, clada, binding, synth, torch, dev):
         return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
 
     layers = [clada.Layer(*[to_dev(a) for a in synth.layer_weights(cfg, args.seed, l)]) for l in range(4)]
-    x = to_dev(synth.decode_hidden(cfg, args.seed, 0, 0, B=1))
+    x = to_dev(synth.decode_hidden(cfg, args.seed, 0, 0, B=B, shared_frac=args.shared_frac))
     # thresholds at the two sparsities from the library's own prefill statistics of layer 0
     st = clada.prefix_stats(ctx, layers[0], to_dev(synth.prefix_hidden(cfg, args.seed, 0)), want_y=False)
     src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
     for q in (0.45, 0.62):
-        tau = clada.threshold_calibrate(ctx, st.abs_act_pool, q)
+        tau = clada.threshold_calibrate(ctx, st.abs_act_pool, q).expand(B).contiguous()
         kept = []
         for _ in range(3):
             for layer in layers:

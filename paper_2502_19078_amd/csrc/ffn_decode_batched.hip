@@ -301,7 +301,12 @@ k_bat_down(const BatParams p)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int cg = blockIdx.x % p.CG, rg = blockIdx.x / p.CG;
+    // Workgroups go to the 8 XCDs round-robin by id, and each XCD has its own L2.  The column groups of
+    // one row group all read the same h lines and row list, so they are given ids of one residue
+    // class mod 8 where the grid divides evenly: an h line then crosses the fabric once, not 8 times.
+    int wg = blockIdx.x;
+    if (gridDim.x % 8 == 0) wg = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
+    const int cg = wg % p.CG, rg = wg / p.CG;
     const int d = p.d, F = p.F, B = p.B;
     const size_t rowb = (size_t)d * 2;
     const int col0 = cg * DN_COLS;
