@@ -38,7 +38,7 @@ struct BatParams {
     const float *tau;           // [B]
     float *hbuf;                // [F][16] fp32 (neuron-major: one 64-byte line per neuron), written for union-kept neurons only
     int *ulist;                 // [F] union-kept neurons: gate/up workgroup q writes its own, ascending, from
-                                //     the first neuron it owns (8 * (q * ceil(F/8) / P)) on
+                                //     the first neuron it owns (q * F / P) on
     int *ucnt;                  // [P] how many each wrote
     unsigned char *keep;        // [B][F] or nullptr
     float *partial;             // [RG][B][d]
@@ -59,12 +59,14 @@ __host__ __device__ __forceinline__ int bat_run_lo(int w, int F, int P) { return
 
 constexpr int MAX_TILES = 4;    // 16-neuron tiles per workgroup in kernel A (one 64-lane ballot compacts them)
 
-// KSTEPS = k-steps of 32 per wave: d = 8 waves * KSTEPS * 32.
-template <int KSTEPS, bool DENSE>
-__global__ void __launch_bounds__(512)
+// NW waves split d; KSTEPS = k-steps of 32 per wave: d = NW * KSTEPS * 32.  (NW = 5 gives the 5 and
+// 10 KiB rows whole-KiB slices; with 8 waves they would be 640 bytes, which streams slower.)
+template <int KSTEPS, int NW, bool DENSE>
+__global__ void __launch_bounds__(NW * 64)
 k_bat_gateup(const BatParams p)
 {
-    __shared__ float s_part[2][8][256];
+    static_assert(NW >= 4 && NW <= 8, "the tile reductions run on waves 0..3");
+    __shared__ float s_part[2][NW][256];
     __shared__ float s_a[MAX_TILES][16][16];
     __shared__ int s_km[MAX_TILES * 16];
     __shared__ int s_ul[MAX_TILES * 16];
@@ -91,7 +93,7 @@ k_bat_gateup(const BatParams p)
     constexpr int PB = SLICE / NPART, SP = PB / 64, PITCH = PB + 16;
     constexpr int NL = PB / 128;                            // load instructions per eight rows of a part
     static_assert(PB % 128 == 0 && PB <= 1024 && NPART * SP == KSTEPS, "slice split");
-    __shared__ __align__(16) char s_stage[8 * 16 * PITCH];
+    __shared__ __align__(16) char s_stage[NW * 16 * PITCH];
     char *stage = s_stage + wave * 16 * PITCH;
     const int koff = wave * SLICE;
     int ld_row[NL], ld_col[NL];                             // (row within the eight, byte within the part) of this lane's piece
@@ -145,7 +147,7 @@ k_bat_gateup(const BatParams p)
     auto tile_sum = [&](int buf, int e) {
         float s = 0.0f;
 #pragma unroll
-        for (int w = 0; w < 8; ++w) s += s_part[buf][w][e];
+        for (int w = 0; w < NW; ++w) s += s_part[buf][w][e];
         return s;
     };
     int nlist = 0;                                          // entries of this workgroup's union list so far (uniform)
@@ -493,7 +495,7 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     *ran = false;
     const int d = layer->d, F = layer->d_ff;
     if (layer->dtype != CLADA_BF16 || B < 2 || B > 16) return CLADA_OK;
-    const int ksteps = d / 256;                                  // 8 waves x ksteps x 32 = d
+    const int ksteps = d / 256;                                  // 8 waves x ksteps x 32 = d (5 waves x 16 or 32 x 32 for ksteps 10, 20)
     if (d % 256 != 0 || !(ksteps == 4 || ksteps == 8 || ksteps == 10 || ksteps == 12 || ksteps == 16 || ksteps == 20 ||
                           ksteps == 24 || ksteps == 32))
         return CLADA_OK;
@@ -524,13 +526,14 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     p.d = d; p.F = F; p.B = B; p.P = P; p.RG = RG; p.CG = CG;
     p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
 
-#define CLADA_BAT_CASE(KS)                                                                            \
-    if (d == 8 * 32 * KS) {                                                                            \
-        if (dense) hipLaunchKernelGGL((k_bat_gateup<KS, true>), dim3(P), dim3(512), 0, stream, p);    \
-        else       hipLaunchKernelGGL((k_bat_gateup<KS, false>), dim3(P), dim3(512), 0, stream, p);   \
+#define CLADA_BAT_CASE(D, KS, NW)                                                                            \
+    if (d == D) {                                                                                             \
+        static_assert(D == NW * 32 * KS, "waves x k-steps x 32 = d");                                         \
+        if (dense) hipLaunchKernelGGL((k_bat_gateup<KS, NW, true>), dim3(P), dim3(NW * 64), 0, stream, p);    \
+        else       hipLaunchKernelGGL((k_bat_gateup<KS, NW, false>), dim3(P), dim3(NW * 64), 0, stream, p);   \
     }
-    CLADA_BAT_CASE(4) CLADA_BAT_CASE(8) CLADA_BAT_CASE(10) CLADA_BAT_CASE(12) CLADA_BAT_CASE(16) CLADA_BAT_CASE(20)
-    CLADA_BAT_CASE(24) CLADA_BAT_CASE(32)
+    CLADA_BAT_CASE(1024, 4, 8) CLADA_BAT_CASE(2048, 8, 8) CLADA_BAT_CASE(2560, 16, 5) CLADA_BAT_CASE(3072, 12, 8)
+    CLADA_BAT_CASE(4096, 16, 8) CLADA_BAT_CASE(5120, 32, 5) CLADA_BAT_CASE(6144, 24, 8) CLADA_BAT_CASE(8192, 32, 8)
 #undef CLADA_BAT_CASE
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     const size_t lds = 8 * (size_t)DN_TILE_BYTES + sizeof(int) * DN_MAX_ROWS;

@@ -303,7 +303,7 @@ def test_kernel_event_timing_does_not_change_results(clada, B):
     ("c2", 1024, 520, 17),       # one past 16 tokens: two passes (9 + 8) of the matrix-core path
     ("c2", 2048, 700, 40),       # three passes (14 + 14 + 12)
     ("c2", 1024, 333, 64),       # the largest batch on the matrix-core path: four passes of 16
-    ("c2", 2560, 640, 4),        # further widths of the matrix-core path: 640-byte wave slices,
+    ("c2", 2560, 640, 4),        # further widths of the matrix-core path: five waves with 1 KiB slices,
     ("c2", 3072, 500, 3),        #   768-byte slices,
     ("c2", 6144, 300, 5),        #   two parts of 768 bytes,
     ("c2", 8192, 300, 3),        #   two parts of 1 KiB (the longest row)
