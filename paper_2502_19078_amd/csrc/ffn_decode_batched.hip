@@ -5,18 +5,18 @@
 // 16-wide M dimension.  Weights are still read once, and only for neurons kept by at least
 // one token (the union); every output row uses its own mask.
 //
-//   kernel A (gate + up -> h): workgroup p owns a contiguous run of neurons (dealt out
-//     evenly, to within one), taken 16 at a time.  Its 8 waves
-//     split the d (= K) dimension: wave w keeps its slice of x as MFMA A-fragments in registers
-//     for the whole kernel and streams its slice of the 16 weight rows as B-fragments (lane =
-//     (neuron, k-group): 128 contiguous bytes of a row per pair of instructions, the row's whole slice over
-//     the k loop).  The 8 partial 16x16 tiles are summed through LDS in fixed order; SiLU, the
-//     per-token fp32 compare and the per-neuron 16-bit keep masks follow.  The neurons of gate tile i
-//     that at least one token keeps (the union) are compacted by ballot and form up tile i: the same
-//     MFMA loop over their W_up rows gives u, and h = keep ? a*u : 0 goes to a [d_ff][16] fp32 buffer (16 tokens of a neuron = one 64-byte line).
-//     Gate and up tiles alternate (G0 G1 U0 G2 U1 ...), so the stream of row loads does not drain
-//     between the two projections.  The workgroup also leaves the list of its union-kept neurons,
-//     ascending, and their count for kernel B.
+//   kernel A (gate + up -> h): workgroup p owns a contiguous run of neurons (dealt out evenly, to
+//     within one), taken 16 at a time.  Its waves (8; 5 for 5 and 10 KiB rows) split the d (= K)
+//     dimension: wave w keeps its slice of x as MFMA A-fragments in registers for the whole kernel
+//     and streams its slice of the 16 weight rows as B-fragments (whole-KiB pieces of a row per
+//     load instruction, turned into the operand layout through a wave-private LDS tile).  The
+//     partial 16x16 tiles of the waves are summed through LDS in fixed order; sigma, the per-token
+//     fp32 compare and the per-neuron 16-bit keep masks follow.  The neurons of gate tile i that at
+//     least one token keeps (the union) are compacted by ballot and form up tile i: the same MFMA
+//     loop over their W_up rows gives u, and h = keep ? a*u : 0 goes to a [d_ff][16] fp32 buffer
+//     (the 16 tokens of a neuron = one 64-byte line).  Gate and up tiles alternate (G0 G1 U0 G2 U1
+//     ...), so the stream of row loads does not drain between the two projections.  The workgroup
+//     also leaves the list of its union-kept neurons, ascending, and their count for kernel B.
 //   kernel B (down): 2-D split -- column groups of 256 x row groups (a fixed range of neuron
 //     indices each: the lists of the gate/up workgroups that own them, laid end to end), so only
 //     R partial y's exist instead of one per workgroup.  Work is dealt to the waves in units of 32
@@ -178,8 +178,9 @@ k_bat_gateup(const BatParams p)
     };
     // Eight rows (half a tile) of one part of gate tile ti (up = 0: its neurons in order) or up tile ti
     // (up = 1: its union-kept neurons through the compacted list).  A row that does not exist reads
-    // one shared line of zeros instead (a select on the address: no branch around any load).  up and ti are uniform; the list is read whether used or not, so
-    // the loads are issued without a branch on the kind of tile.
+    // one shared line of zeros instead (a select on the address: no branch around any load).  up and
+    // ti are uniform; the list is read whether used or not, so the loads are issued without a branch
+    // on the kind of tile.
     auto rows_load = [&](u32x4 (&wr)[NL], int up, int ti, int part, int half) {
         const char *base = (up ? p.wu : p.wg) + (size_t)(j_lo + 16 * ti) * rowb + koff + part * PB;
         const int lim = up ? s_ku[ti] : nown - 16 * ti;
