@@ -955,7 +955,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     }
     // ---- batched MFMA path (bf16, supported widths): up to 16 tokens per pass; larger batches run
     // as ceil(B/16) passes of near-equal size, each re-reading the weights of its own union
-    if (B >= 2 && ctx->opt_decode_batched && !relu) {
+    if (B >= 2 && ctx->opt_decode_batched) {
         unsigned char *keep_region = reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256));
         char *scratch = reinterpret_cast<char *>(keep_region) + align_up((size_t)B * F, 256);
         const int n_groups = (B + 15) / 16, per_group = (B + n_groups - 1) / n_groups;     // per_group >= 2 whenever B >= 2

@@ -44,6 +44,8 @@ struct BatParams {
     float *partial;             // [RG][B][d]
     int d, F, B, P, RG, CG;
     int gelu;                   // sigma = tanh-form GELU instead of SiLU
+    int relu;                   // non-gated family: a = max(0, W_in x + b_in), h = a, no up tiles (wu unused)
+    const float *b_in;          // non-gated family: input bias [F] or nullptr
 };
 
 __device__ __forceinline__ f32x4 mfma16(const u32x4 a, const u32x4 b, const f32x4 c)
@@ -168,9 +170,11 @@ k_bat_gateup(const BatParams p)
     // loads never drains between the gate and the up projection; U_i's rows are known by then
     // because G_i was reduced before the tile in front of U_i started.  (A single tile, ni = 1, has
     // nothing to put between G0 and U0: U0's rows are requested only after G0 is reduced.)
-    const int nseq = 2 * ni;
+    // The non-gated family has gate tiles only: h is the activation itself.
+    const int nseq = p.relu ? ni : 2 * ni;
     auto seq_tile = [&](int sq, int &up, int &i) {
-        if (ni == 1) { up = sq; i = 0; }
+        if (p.relu) { up = 0; i = sq; }
+        else if (ni == 1) { up = sq; i = 0; }
         else if (sq < 2) { up = 0; i = sq; }
         else if (sq == nseq - 1) { up = 1; i = ni - 1; }
         else if (sq & 1) { up = 0; i = (sq + 1) >> 1; }
@@ -202,12 +206,19 @@ k_bat_gateup(const BatParams p)
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
             const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = j_lo + 16 * i + nn;
-            const float a = gate_sigma_f32(tile_sum(buf, tid), p.gelu);
             const bool valid = m < B && j < j_hi;
+            float a = tile_sum(buf, tid);
+            if (p.relu) {
+                if (p.b_in && valid) a += p.b_in[j];
+                a = a > 0.0f ? a : (a != a ? a : 0.0f);
+            } else {
+                a = gate_sigma_f32(a, p.gelu);
+            }
             const bool keep = valid && (DENSE ? true : (fabsf(a) >= red_tau));
             s_a[i][m][nn] = a;
             if (keep) atomicOr(&s_km[i * 16 + nn], 1 << m);
             if (p.keep && valid) p.keep[(size_t)m * F + j] = keep ? 1 : 0;
+            if (p.relu && j < j_hi) p.hbuf[(size_t)j * 16 + m] = keep ? a : 0.0f;     // read back for union-kept neurons only
         }
     };
     // Union-kept neurons of gate tile i, compacted by ballot.  Every wave does it for itself (same
@@ -526,6 +537,8 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     p.keep = keep; p.partial = partial;
     p.d = d; p.F = F; p.B = B; p.P = P; p.RG = RG; p.CG = CG;
     p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
+    p.relu = layer->kind == CLADA_FFN_RELU ? 1 : 0;
+    p.b_in = layer->b_in;
 
 #define CLADA_BAT_CASE(D, KS, NW)                                                                            \
     if (d == D) {                                                                                             \
@@ -546,7 +559,7 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     }
     hipLaunchKernelGGL(k_bat_down, dim3(CG * RG), dim3(512), lds, stream, p);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
-    clada_launch_finalize(2, partial, RG, B, d, (char *)y, stream);
+    clada_launch_finalize(2, partial, RG, B, d, (char *)y, stream, p.relu ? layer->b_out : nullptr);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     *ran = true;
     return CLADA_OK;

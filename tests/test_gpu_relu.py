@@ -29,7 +29,10 @@ CASES = [
     ("o350", 1024, 4096, 1),     # OPT-350M shape: 2 KiB rows, batch-1 kernel
     ("o27", 2560, 10240, 1),     # OPT-2.7B shape: 5 KiB rows, batch-1 kernel with balancing
     ("o27", 2560, 1000, 1),      # ragged neuron count, fewer neurons than the balanced kernel wants
-    ("o27", 2560, 640, 4),       # batch > 1: generic kernel, per-token thresholds
+    ("o27", 2560, 640, 4),       # batch > 1, bf16: matrix-core path (five waves), per-token thresholds
+    ("o350", 1024, 4096, 8),     # OPT-350M shape at batch 8: matrix-core path, gate tiles only
+    ("o27", 2560, 3000, 16),     # a full 16-token pass, ragged neuron count
+    ("o27", 2560, 900, 17),      # two passes (9 + 8)
     ("c1", 96, 200, 3),          # fp32, odd row length: generic kernel
     ("o27", 4096, 1024, 1),      # 8 KiB rows (OPT-6.7B width)
     ("o27", 5120, 768, 1),       # 10 KiB rows (OPT-13B width)
