@@ -3,7 +3,9 @@
 // element feeds B multiply-adds, which the vector ALUs cannot sustain at HBM speed, so the
 // three projections run as MFMA 16x16x32 (bf16 in, fp32 accumulate) with the tokens as the
 // 16-wide M dimension.  Weights are still read once, and only for neurons kept by at least
-// one token (the union); every output row uses its own mask.
+// one token (the union); every output row uses its own mask.  The GELU-gated family differs in
+// sigma only; the non-gated ReLU family has no up projection: kernel A runs gate tiles alone and
+// writes h = max(0, g + b_in) with the masks, and b_out is added by kernel C.
 //
 //   kernel A (gate + up -> h): workgroup p owns a contiguous run of neurons (dealt out evenly, to
 //     within one), taken 16 at a time.  Its waves (8; 5 for 5 and 10 KiB rows) split the d (= K)
