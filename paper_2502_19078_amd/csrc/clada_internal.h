@@ -56,9 +56,11 @@ clada_status clada_check_layer(clada_ctx *ctx, const clada_layer *layer);
 clada_status clada_require_swiglu(clada_ctx *ctx, const clada_layer *layer, const char *call);
 
 // Batched (B >= 2, bf16) MFMA decode path; *ran tells whether the shape was eligible and it ran.
+// list / list_n (device; nullptr for all neurons): run over the listed neurons only, all kept (dense must be set).
 clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, const void *x, int32_t B,
                                   const float *tau, void *y, unsigned char *keep, float *partial,
-                                  char *scratch, bool dense, hipStream_t stream, bool *ran);
+                                  char *scratch, bool dense, hipStream_t stream, bool *ran,
+                                  const int32_t *list = nullptr, const int32_t *list_n = nullptr);
 size_t clada_ws_decode_batched(int32_t d_ff);
 // Batch-1 decode over a neuron list with the streaming kernel, when the shape fits it (*ran).
 hipError_t clada_decode_list_b1(clada_ctx *ctx, const clada_layer *layer, const void *x, const int32_t *idx,

@@ -1050,6 +1050,26 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
     p.b_in = relu ? layer->b_in : nullptr;
     const float *b_out = relu ? layer->b_out : nullptr;
     const int nch = (d * es + 1023) / 1024;
+    // ---- matrix-core path (bf16, supported widths), up to 16 tokens per pass, as in the thresholded call
+    if (B >= 2 && ctx->opt_decode_batched) {
+        char *ws = ctx->ws + CLADA_WS_HEADER;
+        char *scratch = ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256) + align_up((size_t)B * F, 256);
+        const int n_groups = (B + 15) / 16, per_group = (B + n_groups - 1) / n_groups;
+        bool ran_all = false;
+        for (int g0 = 0; g0 < B; g0 += per_group) {
+            const int Bg = (B - g0 < per_group) ? B - g0 : per_group;
+            bool ran = false;
+            if (Bg >= 2) {
+                st = clada_decode_batched(ctx, layer, (const char *)x + (size_t)g0 * d * es, Bg, nullptr,
+                                          (char *)y + (size_t)g0 * d * es, nullptr, p.partial, scratch, true, stream, &ran,
+                                          idx, n_active);
+                if (st != CLADA_OK) return st;
+            }
+            ran_all = ran;
+            if (!ran) break;                                // not eligible, or a one-token remainder: generic kernels redo the batch
+        }
+        if (ran_all) return CLADA_OK;
+    }
     if (B == 1 && ctx->opt_decode_b1 >= 1 && !relu) {  // streaming kernel for whole-KiB rows
         bool ran = false;
         int Pl = 0;

@@ -48,6 +48,8 @@ struct BatParams {
     int gelu;                   // sigma = tanh-form GELU instead of SiLU
     int relu;                   // non-gated family: a = max(0, W_in x + b_in), h = a, no up tiles (wu unused)
     const float *b_in;          // non-gated family: input bias [F] or nullptr
+    const int *list, *list_n;   // prefix-static run (with DENSE): the neurons are the list_n[0] entries of list
+                                // (device), every one kept by every token; nullptr: all F neurons
 };
 
 __device__ __forceinline__ f32x4 mfma16(const u32x4 a, const u32x4 b, const f32x4 c)
@@ -75,6 +77,7 @@ k_bat_gateup(const BatParams p)
     __shared__ int s_km[MAX_TILES * 16];
     __shared__ int s_ul[MAX_TILES * 16];
     __shared__ int s_ku[MAX_TILES];
+    __shared__ int s_nl[MAX_TILES * 16];                    // neuron index of every entry of the round
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -111,8 +114,10 @@ k_bat_gateup(const BatParams p)
     // workgroup streams the same number of rows to within one (a row that a tile lacks costs no
     // memory traffic; 16-neuron granularity would leave an eighth of the chip idle at the end).
     // A run longer than 64 neurons (d_ff above 16384) is worked off in rounds of 64.
-    const int j_lo_all = bat_run_lo(blk, F, P);
-    const int j_hi_all = bat_run_lo(blk + 1, F, P);
+    // With a list the same holds for its entries (indices clamped into [0, d_ff) like the count).
+    const int Fn = p.list ? min(max(p.list_n[0], 0), F) : F;
+    const int j_lo_all = bat_run_lo(blk, Fn, P);
+    const int j_hi_all = bat_run_lo(blk + 1, Fn, P);
 
     // this wave's slice of x as A-fragments: lane = (token n, k-group q)
     u32x4 xa[KSTEPS];
@@ -159,11 +164,13 @@ k_bat_gateup(const BatParams p)
     const int red_m = 4 * ((tid & 63) >> 4) + (tid >> 6);
     const float red_tau = (!DENSE && tid < 256 && red_m < B) ? p.tau[red_m] : 0.0f;
     for (int j_lo = j_lo_all; j_lo < j_hi_all; j_lo += 16 * MAX_TILES) {
-    const int j_hi = min(j_lo + 16 * MAX_TILES, j_hi_all);
-    const int nown = j_hi - j_lo;                           // <= 64
+    const int nown = min(16 * MAX_TILES, j_hi_all - j_lo);  // <= 64
     const int ni = (nown + 15) / 16;                        // <= MAX_TILES
     __syncthreads();                                        // the previous round is done with s_km, s_a, s_ul
-    if (tid < MAX_TILES * 16) s_km[tid] = 0;
+    if (tid < MAX_TILES * 16) {
+        s_km[tid] = 0;
+        s_nl[tid] = tid >= nown ? 0 : p.list ? min(max(p.list[j_lo + tid], 0), F - 1) : j_lo + tid;
+    }
     __syncthreads();
 
     // Every 16-neuron gate tile G_i is followed, one tile later, by the up tile U_i over the neurons of
@@ -188,14 +195,14 @@ k_bat_gateup(const BatParams p)
     // ti are uniform; the list is read whether used or not, so the loads are issued without a branch
     // on the kind of tile.
     auto rows_load = [&](u32x4 (&wr)[NL], int up, int ti, int part, int half) {
-        const char *base = (up ? p.wu : p.wg) + (size_t)(j_lo + 16 * ti) * rowb + koff + part * PB;
+        const char *base = (up ? p.wu : p.wg) + koff + part * PB;
         const int lim = up ? s_ku[ti] : nown - 16 * ti;
         int lr[NL];
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int rr = 8 * half + ld_row[i];
             const int viaList = s_ul[16 * ti + rr];
-            lr[i] = up ? viaList : rr;
+            lr[i] = s_nl[16 * ti + (up ? viaList & 15 : rr)];
         }
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -207,8 +214,8 @@ k_bat_gateup(const BatParams p)
     auto gate_reduce = [&](int i, int buf) {
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
-            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = j_lo + 16 * i + nn;
-            const bool valid = m < B && j < j_hi;
+            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = s_nl[16 * i + nn];
+            const bool here = 16 * i + nn < nown, valid = m < B && here;
             float a = tile_sum(buf, tid);
             if (p.relu) {
                 if (p.b_in && valid) a += p.b_in[j];
@@ -220,7 +227,7 @@ k_bat_gateup(const BatParams p)
             s_a[i][m][nn] = a;
             if (keep) atomicOr(&s_km[i * 16 + nn], 1 << m);
             if (p.keep && valid) p.keep[(size_t)m * F + j] = keep ? 1 : 0;
-            if (p.relu && j < j_hi) p.hbuf[(size_t)j * 16 + m] = keep ? a : 0.0f;     // read back for union-kept neurons only
+            if (p.relu && here) p.hbuf[(size_t)j * 16 + m] = keep ? a : 0.0f;     // read back for union-kept neurons only
         }
     };
     // Union-kept neurons of gate tile i, compacted by ballot.  Every wave does it for itself (same
@@ -232,7 +239,7 @@ k_bat_gateup(const BatParams p)
         const int pos = __popcll(bal & ((1ull << lane) - 1ull));
         if (mine) s_ul[16 * i + pos] = lane;
         if (lane == 0) s_ku[i] = __popcll(bal);
-        if (wave == 0 && mine) p.ulist[j_lo_all + nlist + pos] = j_lo + 16 * i + lane;
+        if (wave == 0 && mine) p.ulist[j_lo_all + nlist + pos] = s_nl[16 * i + lane];
         nlist += __popcll(bal);
         wave_sync();
     };
@@ -242,7 +249,7 @@ k_bat_gateup(const BatParams p)
             const int m = 4 * (ln >> 4) + r, nn = ln & 15;
             if (nn < s_ku[i]) {
                 const int l2 = s_ul[16 * i + nn];
-                const int j = j_lo + 16 * i + l2;
+                const int j = s_nl[16 * i + l2];
                 const float usum = tile_sum(buf, tid);
                 const bool keep = (s_km[16 * i + l2] >> m) & 1;
                 p.hbuf[(size_t)j * 16 + m] = keep ? s_a[i][m][l2] * usum : 0.0f;
@@ -332,7 +339,8 @@ k_bat_down(const BatParams p)
     // its workgroup's count is stale memory inside the list array and is dropped.
     const int w0 = (int)((long long)rg * p.P / p.RG), w1 = (int)((long long)(rg + 1) * p.P / p.RG);
     const int nw = w1 - w0;                                             // <= DN_MAX_WGS (host check)
-    auto run_lo = [&](int w) { return bat_run_lo(w, F, p.P); };
+    const int Fn = p.list ? min(max(p.list_n[0], 0), F) : F;
+    auto run_lo = [&](int w) { return bat_run_lo(w, Fn, p.P); };
     const int cnt_l = lane < nw ? p.ucnt[w0 + lane] : 0;               // every wave: the counts, one per lane
     constexpr int PRE = 4;                                              // entries per thread held in registers
     int pre_v[PRE];
@@ -504,7 +512,8 @@ size_t clada_ws_decode_batched(int32_t d_ff)
 // the shape is not eligible and the caller should use the generic kernels.
 clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, const void *x, int32_t B,
                                   const float *tau, void *y, unsigned char *keep, float *partial,
-                                  char *scratch, bool dense, hipStream_t stream, bool *ran)
+                                  char *scratch, bool dense, hipStream_t stream, bool *ran,
+                                  const int32_t *list, const int32_t *list_n)
 {
     *ran = false;
     const int d = layer->d, F = layer->d_ff;
@@ -541,6 +550,7 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
     p.relu = layer->kind == CLADA_FFN_RELU ? 1 : 0;
     p.b_in = layer->b_in;
+    p.list = list; p.list_n = list_n;
 
 #define CLADA_BAT_CASE(D, KS, NW)                                                                            \
     if (d == D) {                                                                                             \

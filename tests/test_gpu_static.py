@@ -65,7 +65,10 @@ CASES = [
     ("c2", 1024, 1000, 1),
     ("c2", 4096, 640, 1),        # config 2's row length, whole-KiB rows
     ("c2", 72, 129, 4),
-    ("c5", 5120, 512, 2),
+    ("c5", 5120, 512, 2),        # batch > 1, bf16: matrix-core path over the list
+    ("c2", 4096, 3000, 8),       #   8 KiB rows, 8 tokens
+    ("c2", 1024, 20000, 16),     #   wide layer: several rounds per workgroup, 16 tokens
+    ("c2", 2048, 700, 17),       #   two passes (9 + 8)
     ("c5", 5120, 700, 1),        # 10 KiB rows: the unpipelined variant of the list kernel
     ("c1", 512, 4100, 1),        # fp32, 2 KiB rows, 16 entries per workgroup and a ragged tail
 ]
