@@ -12,6 +12,17 @@ DEV = "cuda:0"
 TOL_Y = {"f32": 1e-5, "bf16": 2e-2}
 TOL_SIGNAL = 1e-4
 BAND = 1e-3
+# Absolute floor of the band.  The kernels accumulate the gate pre-activation in fp32 (the precision the
+# mask decision is taken in); over d = 2048..5120 terms of size ~1/sqrt(d) its rounding error reaches
+# ~4e-6, and |sigma'| <= 1.13, so an activation within ~5e-6 of the threshold cannot be decided by any
+# fp32 evaluation.  It only matters for thresholds below 1e-2 (the q = 0 cases: tau = the smallest
+# magnitude of the row, 1e-4 .. 1e-16); at the paper's operating points (tau ~ 0.25) BAND * tau is 25x wider.
+BAND_ABS = 1e-5
+
+
+def band_width(tau):
+    """Half-width of the zone around tau in which the mask bit may fall on either side."""
+    return np.maximum(BAND * np.asarray(tau, np.float64), BAND_ABS)
 
 
 def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
@@ -56,7 +67,7 @@ def check_mask_band(mask_gpu, act_ref, tau, what=""):
     """Masks must agree except where |a_ref| lies within BAND*tau of tau; returns #flips."""
     mask_ref = np.abs(act_ref) >= tau[:, None]
     diff = mask_gpu != mask_ref
-    allowed = np.abs(np.abs(act_ref) - tau[:, None]) <= BAND * tau[:, None]
+    allowed = np.abs(np.abs(act_ref) - tau[:, None]) <= band_width(tau)[:, None]
     bad = diff & ~allowed
     assert not bad.any(), f"{what}: {bad.sum()} mask bits differ outside the +-{BAND} band around tau"
     return int(diff.sum())

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import synth
-from gpu_util import BAND, DEV, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
+from gpu_util import BAND, DEV, band_width, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
 
 pytestmark = pytest.mark.gpu
 SIG = "gelu_tanh"
@@ -53,7 +53,7 @@ def test_geglu_sparse_and_dense_parity(clada, cfg_name, d, F, B, b1):
         ref = oracle.sparse_decode(*w, x, tau.astype(np.float64), sigma=SIG)
         mask_gpu = unpack_bits(bits, F)
         diff = mask_gpu != ref["mask"]
-        band = np.abs(np.abs(ref["act"]) - tau[:, None]) <= BAND * np.maximum(tau[:, None], 1e-30)
+        band = np.abs(np.abs(ref["act"]) - tau[:, None]) <= band_width(tau)[:, None]
         assert not (diff & ~band).any(), f"q={q}: mask differs outside the band"
         ref_y = oracle.decode_given_mask(*w, x, mask_gpu, sigma=SIG)
         assert_close_y(to_np(y), ref_y, TOL_Y[cfg.dtype], f"geglu sparse q={q}")

@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import synth
-from gpu_util import BAND, DEV, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
+from gpu_util import BAND, DEV, band_width, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
 
 pytestmark = pytest.mark.gpu
 SEED_SHIFT = int(os.environ.get("CLADA_TEST_SEED_SHIFT", "0"))      # other shape draws for a longer hunt
@@ -69,7 +69,7 @@ def test_random_shape_parity(clada, i, dtype, d, F, B, kind, q):
     torch.cuda.synchronize()
     ref = run(tau=tau.astype(np.float64))
     mask_gpu = unpack_bits(bits, F)
-    band = np.abs(np.abs(ref["act"]) - tau[:, None]) <= BAND * np.maximum(tau[:, None], 1e-30)
+    band = np.abs(np.abs(ref["act"]) - tau[:, None]) <= band_width(tau)[:, None]
     assert not ((mask_gpu != ref["mask"]) & ~band).any(), "mask differs outside the band"
     assert_close_y(to_np(y), run(mask=mask_gpu)["y"], TOL_Y[dtype], "sparse")
     union = np.flatnonzero(mask_gpu.any(0))

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import synth
-from gpu_util import BAND, DEV, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
+from gpu_util import BAND, DEV, band_width, TOL_Y, assert_close_y, to_dev, to_np, unpack_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -60,7 +60,7 @@ def test_relu_sparse_and_dense_parity(clada, cfg_name, d, F, B, biases, b1):
         ref = oracle.relu_decode(*wb, x, tau=tau.astype(np.float64))
         mask_gpu = unpack_bits(bits, F)
         diff = mask_gpu != ref["mask"]
-        band = np.abs(ref["act"] - tau[:, None]) <= BAND * np.maximum(tau[:, None], 1e-30)
+        band = np.abs(ref["act"] - tau[:, None]) <= band_width(tau)[:, None]
         assert not (diff & ~band).any(), f"q={q}: mask differs outside the band"
         ref_y = oracle.relu_decode(*wb, x, mask=mask_gpu)["y"]
         assert_close_y(to_np(y), ref_y, TOL_Y[cfg.dtype], f"relu sparse q={q}")
