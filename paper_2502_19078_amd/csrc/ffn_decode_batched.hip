@@ -27,6 +27,8 @@
 //     back K-major with ds_read_b64_tr_b16 as MFMA B-fragments; h is split into bf16 hi + lo
 //     A-fragments (two MFMAs), so the down projection keeps ~fp32 accuracy of h.
 //   kernel C: k_ffn_finalize adds the R partials in fixed order.
+#include <atomic>
+
 #include "clada_internal.h"
 
 namespace {
@@ -563,11 +565,11 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
 #undef CLADA_BAT_CASE
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     const size_t lds = 8 * (size_t)DN_TILE_BYTES + sizeof(int) * DN_MAX_ROWS;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};                           // set once per process (two first callers may both set it)
+    if (!attr_set.load(std::memory_order_relaxed)) {
         CLADA_CHECK_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(k_bat_down),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_relaxed);
     }
     hipLaunchKernelGGL(k_bat_down, dim3(CG * RG), dim3(512), lds, stream, p);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
