@@ -1070,12 +1070,12 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
         }
         if (ran_all) return CLADA_OK;
     }
-    if (B == 1 && ctx->opt_decode_b1 >= 1 && !relu) {  // streaming kernel for whole-KiB rows
+    if (B == 1 && ctx->opt_decode_b1 >= 1) {            // streaming kernel for whole-KiB rows
         bool ran = false;
         int Pl = 0;
         CLADA_CHECK_HIP(ctx, clada_decode_list_b1(ctx, layer, x, idx, n_active, p.partial, &Pl, stream, &ran));
         if (ran) {
-            launch_finalize(es, p.partial, Pl, 1, d, (char *)y, nullptr, stream);
+            launch_finalize(es, p.partial, Pl, 1, d, (char *)y, nullptr, stream, nullptr, nullptr, b_out);
             CLADA_CHECK_HIP(ctx, hipGetLastError());
             return CLADA_OK;
         }

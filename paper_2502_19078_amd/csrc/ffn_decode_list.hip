@@ -18,11 +18,13 @@ struct ListParams {
     float *partial;             // [P][d]
     int d, F;
     int gelu;                   // sigma = tanh-form GELU instead of SiLU
+    const float *b_in;          // RELU: input bias [F] or nullptr
 };
 
 constexpr int LIST_MAXSEG = 1024;       // list entries per workgroup
 
-template <int ES, int NCH, int NW, bool PIPE>
+// RELU: the non-gated family -- no W_up rows, h = max(0, W_in[j,:] . x + b_in[j]).
+template <int ES, int NCH, int NW, bool PIPE, bool RELU = false>
 __global__ void __launch_bounds__(NW * 64)
 k_ffn_decode_list(const ListParams p)
 {
@@ -58,7 +60,7 @@ k_ffn_decode_list(const ListParams p)
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             g[c] = ld_stream16(p.wg + off + c * 1024);
-            u[c] = ld_stream16(p.wu + off + c * 1024);
+            if (!RELU) u[c] = ld_stream16(p.wu + off + c * 1024);
         }
 #pragma unroll
         for (int e = 0; e < NW; ++e) {
@@ -72,15 +74,19 @@ k_ffn_decode_list(const ListParams p)
         }
     };
     // h = sigma(gate . x) * (up . x) of this wave's neuron; x comes from LDS a chunk at a time
-    auto neuron_h = [&](const u32x4 (&g)[NCH], const u32x4 (&u)[NCH]) {
+    auto neuron_h = [&](const u32x4 (&g)[NCH], const u32x4 (&u)[NCH], int j) {
         float sg = 0.0f, su = 0.0f;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const u32x4 xv = *reinterpret_cast<const u32x4 *>(s_x + c * 1024 + loff);
             sg = dot16<ES>(g[c], xv, sg);
-            su = dot16<ES>(u[c], xv, su);
+            if (!RELU) su = dot16<ES>(u[c], xv, su);
         }
         sg = wave_sum(sg);
+        if (RELU) {
+            if (p.b_in) sg += p.b_in[j];
+            return sg > 0.0f ? sg : (sg != sg ? sg : 0.0f);
+        }
         su = wave_sum(su);
         return gate_sigma_f32(sg, p.gelu) * su;
     };
@@ -98,8 +104,8 @@ k_ffn_decode_list(const ListParams p)
         }
     };
     int par = 0;
-    auto consume = [&](const u32x4 (&g)[NCH], const u32x4 (&u)[NCH], const u32x4 (&dn)[NW][SL]) {
-        const float h = neuron_h(g, u);
+    auto consume = [&](const u32x4 (&g)[NCH], const u32x4 (&u)[NCH], const u32x4 (&dn)[NW][SL], int base) {
+        const float h = neuron_h(g, u, s_rows[base + wave]);
         if (lane == 0) s_h[par][wave] = h;
         __syncthreads();
         down_fma(dn, s_h[par], NW);
@@ -114,22 +120,22 @@ k_ffn_decode_list(const ListParams p)
         for (int c = 0; c < nfull; c += 2) {
             if (c + 1 < nfull) {
                 issue(gb, ub, db, (c + 1) * NW);
-                consume(ga, ua, da);
+                consume(ga, ua, da, c * NW);
                 if (c + 2 < nfull) {
                     issue(ga, ua, da, (c + 2) * NW);
-                    consume(gb, ub, db);
+                    consume(gb, ub, db, (c + 1) * NW);
                 } else {
-                    consume(gb, ub, db);
+                    consume(gb, ub, db, (c + 1) * NW);
                 }
             } else {
-                consume(ga, ua, da);
+                consume(ga, ua, da, c * NW);
             }
         }
     } else {
         for (int c = 0; c < nfull; ++c) {
             u32x4 g[NCH], u[NCH], dn[NW][SL];
             issue(g, u, dn, c * NW);
-            consume(g, u, dn);
+            consume(g, u, dn, c * NW);
         }
     }
     if (tail > 0) {                                   // ragged last group: fewer than NW neurons
@@ -156,9 +162,9 @@ k_ffn_decode_list(const ListParams p)
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 g[c] = ld_stream16(p.wg + off + c * 1024);
-                u[c] = ld_stream16(p.wu + off + c * 1024);
+                if (!RELU) u[c] = ld_stream16(p.wu + off + c * 1024);
             }
-            h = neuron_h(g, u);
+            h = neuron_h(g, u, s_rows[base + wave]);
         }
         if (lane == 0) s_h[par][wave] = h;
         __syncthreads();
@@ -179,9 +185,10 @@ k_ffn_decode_list(const ListParams p)
 }
 
 template <int ES, int NCH, bool PIPE>
-hipError_t launch_list(const ListParams &p, int P, hipStream_t st)
+hipError_t launch_list(const ListParams &p, int P, hipStream_t st, bool relu)
 {
-    hipLaunchKernelGGL((k_ffn_decode_list<ES, NCH, 8, PIPE>), dim3(P), dim3(512), 0, st, p);
+    if (relu) hipLaunchKernelGGL((k_ffn_decode_list<ES, NCH, 8, PIPE, true>), dim3(P), dim3(512), 0, st, p);
+    else      hipLaunchKernelGGL((k_ffn_decode_list<ES, NCH, 8, PIPE>), dim3(P), dim3(512), 0, st, p);
     return hipGetLastError();
 }
 
@@ -203,12 +210,15 @@ hipError_t clada_decode_list_b1(clada_ctx *ctx, const clada_layer *layer, const 
     p.wg = (const char *)layer->w_gate; p.wu = (const char *)layer->w_up; p.wd = (const char *)layer->w_down;
     p.x = (const char *)x; p.idx = idx; p.n_list = n_active; p.partial = partial; p.d = d; p.F = F;
     p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
+    const bool relu = layer->kind == CLADA_FFN_RELU;
+    p.b_in = relu ? layer->b_in : nullptr;
     hipError_t e;
-    if (es == 2 && nch == 8) e = launch_list<2, 8, true>(p, P, stream);
-    else if (es == 2 && nch == 10) e = launch_list<2, 10, false>(p, P, stream);
-    else if (es == 2 && nch == 2) e = launch_list<2, 2, true>(p, P, stream);
-    else if (es == 4 && nch == 2) e = launch_list<4, 2, true>(p, P, stream);
-    else if (es == 4 && nch == 8) e = launch_list<4, 8, true>(p, P, stream);
+    if (es == 2 && nch == 8) e = launch_list<2, 8, true>(p, P, stream, relu);
+    else if (es == 2 && nch == 10) e = launch_list<2, 10, false>(p, P, stream, relu);
+    else if (es == 2 && nch == 5) e = launch_list<2, 5, true>(p, P, stream, relu);
+    else if (es == 2 && nch == 2) e = launch_list<2, 2, true>(p, P, stream, relu);
+    else if (es == 4 && nch == 2) e = launch_list<4, 2, true>(p, P, stream, relu);
+    else if (es == 4 && nch == 8) e = launch_list<4, 8, true>(p, P, stream, relu);
     else return hipSuccess;
     *P_out = P;
     *ran = true;

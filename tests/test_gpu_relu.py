@@ -97,9 +97,12 @@ def test_relu_tau_zero_equals_dense_and_small_tau_drops_only_zeros(clada):
     assert_close_y(to_np(y0), to_np(yd), 2e-2, "tau=0 vs dense twin")
 
 
-def test_relu_static_list_decode(clada):
+@pytest.mark.parametrize("d,F,B", [(2560, 900, 2),      # matrix-core path over the list
+                                   (2560, 3000, 1),     # streaming list kernel, 5 KiB rows
+                                   (1024, 4096, 1),     # streaming list kernel, 2 KiB rows (OPT-350M shape)
+                                   (1000, 700, 1)])     # generic list kernel
+def test_relu_static_list_decode(clada, d, F, B):
     cfg = synth.CONFIGS["o27"]
-    d, F, B = 2560, 900, 2
     w = synth.relu_layer(cfg, 1, 1, d=d, d_ff=F)
     x = synth.decode_hidden(cfg, 1, 1, 0, B=B, d=d)
     ctx = clada.Context(0, clada.workspace_bytes(d, F, B, 0, 0))

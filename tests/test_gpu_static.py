@@ -70,6 +70,7 @@ CASES = [
     ("c2", 1024, 20000, 16),     #   wide layer: several rounds per workgroup, 16 tokens
     ("c2", 2048, 700, 17),       #   two passes (9 + 8)
     ("c5", 5120, 700, 1),        # 10 KiB rows: the unpipelined variant of the list kernel
+    ("c2", 2560, 900, 1),        # 5 KiB rows
     ("c1", 512, 4100, 1),        # fp32, 2 KiB rows, 16 entries per workgroup and a ragged tail
 ]
 
