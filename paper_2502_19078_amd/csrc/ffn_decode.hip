@@ -495,7 +495,8 @@ k_ffn_decode_b1(const B1Params p)
     constexpr int ROWB = NCH * 1024;
     constexpr int SL = (NCH + NW - 1) / NW;                 // column chunks owned by a wave
     constexpr int UPB = (DCH + NW - 1) / NW;                // W_up rows a wave takes per chunk
-    constexpr int K0MAX = 2 * (NW - 1);                     // own-first chunk: two W_up rows for waves 1..NW-1
+    // own-first chunk: two W_up rows for waves 1..NW-1 (one with 10 KiB rows, which would not fit the registers)
+    constexpr int K0MAX = (NCH > 8 ? 1 : 2) * (NW - 1);
     static_assert(!(DENSE && BAL), "the dense twin needs no balancing");
     __shared__ float s_a[64];
     __shared__ int s_flag[64];
@@ -650,7 +651,7 @@ k_ffn_decode_b1(const B1Params p)
             const int first = wave - 1;
             const int nup = first < own ? (own - first + NW - 2) / (NW - 1) : 0;
             if (nup == 1) up_rows(std::integral_constant<int, 1>{}, s_list, nullptr, true, first, NW - 1, s_h[0]);
-            else if (nup == 2) up_rows(std::integral_constant<int, 2>{}, s_list, nullptr, true, first, NW - 1, s_h[0]);
+            else if (nup == 2) up_rows(std::integral_constant<int, K0MAX >= 2 * (NW - 1) ? 2 : 1>{}, s_list, nullptr, true, first, NW - 1, s_h[0]);
         } else {
             // wave 0: read all P masks (lane handles records 4*lane .. 4*lane+3), no barriers
             // The wait is bounded: if the other workgroups' records do not arrive (they can only be
@@ -920,11 +921,11 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             // Balancing pays when the kept-row phase is long enough to hide the mask exchange behind the
             // workgroup's own first chunk: measured faster on the 7B/8B shapes (90-117 MB per matrix), slower
             // on 52 MB ReLU layers (17.0 vs 14.1 us) and on 8 MB ones (10.0 vs 6.4 us).  With 10 KiB gated rows
-            // the balanced variant also runs out of registers (57 vs 51 us per 13B-shape layer).
+            // (13B shape, own-first chunk of 7) it gains 2-3 % from sparsity 0.45 up and loses as much at 0.3.
             const double phase2_bytes = (relu ? 1.0 : 2.0) * (double)F * d * es;
             bool balance = !dense && ni_b <= 56 &&
                            (ctx->opt_decode_b1 == 3 ||
-                            (ctx->opt_decode_b1 == 1 && phase2_bytes >= 128e6 && (nch != 10 || relu)));
+                            (ctx->opt_decode_b1 == 1 && phase2_bytes >= 128e6));
             hipError_t eb = hipErrorNotSupported;
             for (int attempt = 0; attempt < 2 && eb == hipErrorNotSupported; ++attempt) {
                 if (relu) {
