@@ -528,7 +528,8 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     const int CG = (d + DN_COLS - 1) / DN_COLS;
     int RG = P / CG;
     if (RG < 1) RG = 1;
-    if (RG > 16) RG = 16;
+    if (RG > 64) RG = 64;
+    if (RG > 1 && (CG * RG) % 8 != 0 && (CG * (RG - 1)) % 8 == 0) --RG;     // a grid the XCD-aware map of the down kernel divides
     // row group rg = the neurons of the gate/up workgroups [rg P / RG, (rg+1) P / RG)
     auto group_fits = [&](int rgs) {
         if (rgs > P) return false;
