@@ -48,7 +48,6 @@ struct BatParams {
     float *partial;             // [RG][B][d]
     int d, F, B, P, RG, CG;
     int gelu;                   // sigma = tanh-form GELU instead of SiLU
-    int relu;                   // non-gated family: a = max(0, W_in x + b_in), h = a, no up tiles (wu unused)
     const float *b_in;          // non-gated family: input bias [F] or nullptr
     const int *list, *list_n;   // prefix-static run (with DENSE): the neurons are the list_n[0] entries of list
                                 // (device), every one kept by every token; nullptr: all F neurons
@@ -69,10 +68,15 @@ constexpr int MAX_TILES = 4;    // 16-neuron tiles per workgroup in kernel A (on
 
 // NW waves split d; KSTEPS = k-steps of 32 per wave: d = NW * KSTEPS * 32.  (NW = 5 gives the 5 and
 // 10 KiB rows whole-KiB slices; with 8 waves they would be 640 bytes, which streams slower.)
-template <int KSTEPS, int NW, bool DENSE>
+// LIST (with DENSE): the neurons are the entries of p.list, looked up through LDS; without it neuron
+// indices are plain arithmetic on the run's start (fewer registers: the 10 and 16 KiB rows need that).
+// RELU: the non-gated family (gate tiles only).  A template flag: as a run-time one it cost the
+// 10 and 16 KiB rows ~25 registers and pushed them into scratch (52 -> 68 us at the 13B shape).
+template <int KSTEPS, int NW, bool DENSE, bool LIST = false, bool RELU = false>
 __global__ void __launch_bounds__(NW * 64)
 k_bat_gateup(const BatParams p)
 {
+    static_assert(!LIST || DENSE, "a list run keeps every listed neuron");
     static_assert(NW >= 4 && NW <= 8, "the tile reductions run on waves 0..3");
     __shared__ float s_part[2][NW][256];
     __shared__ float s_a[MAX_TILES][16][16];
@@ -117,7 +121,7 @@ k_bat_gateup(const BatParams p)
     // memory traffic; 16-neuron granularity would leave an eighth of the chip idle at the end).
     // A run longer than 64 neurons (d_ff above 16384) is worked off in rounds of 64.
     // With a list the same holds for its entries (indices clamped into [0, d_ff) like the count).
-    const int Fn = p.list ? min(max(p.list_n[0], 0), F) : F;
+    const int Fn = LIST ? min(max(p.list_n[0], 0), F) : F;
     const int j_lo_all = bat_run_lo(blk, Fn, P);
     const int j_hi_all = bat_run_lo(blk + 1, Fn, P);
 
@@ -171,7 +175,7 @@ k_bat_gateup(const BatParams p)
     __syncthreads();                                        // the previous round is done with s_km, s_a, s_ul
     if (tid < MAX_TILES * 16) {
         s_km[tid] = 0;
-        s_nl[tid] = tid >= nown ? 0 : p.list ? min(max(p.list[j_lo + tid], 0), F - 1) : j_lo + tid;
+        if (LIST) s_nl[tid] = tid >= nown ? 0 : min(max(p.list[j_lo + tid], 0), F - 1);
     }
     __syncthreads();
 
@@ -182,9 +186,9 @@ k_bat_gateup(const BatParams p)
     // because G_i was reduced before the tile in front of U_i started.  (A single tile, ni = 1, has
     // nothing to put between G0 and U0: U0's rows are requested only after G0 is reduced.)
     // The non-gated family has gate tiles only: h is the activation itself.
-    const int nseq = p.relu ? ni : 2 * ni;
+    const int nseq = RELU ? ni : 2 * ni;
     auto seq_tile = [&](int sq, int &up, int &i) {
-        if (p.relu) { up = 0; i = sq; }
+        if (RELU) { up = 0; i = sq; }
         else if (ni == 1) { up = sq; i = 0; }
         else if (sq < 2) { up = 0; i = sq; }
         else if (sq == nseq - 1) { up = 1; i = ni - 1; }
@@ -197,14 +201,15 @@ k_bat_gateup(const BatParams p)
     // ti are uniform; the list is read whether used or not, so the loads are issued without a branch
     // on the kind of tile.
     auto rows_load = [&](u32x4 (&wr)[NL], int up, int ti, int part, int half) {
-        const char *base = (up ? p.wu : p.wg) + koff + part * PB;
+        const char *base = (up ? p.wu : p.wg) + (LIST ? (size_t)0 : (size_t)(j_lo + 16 * ti) * rowb) + koff + part * PB;
         const int lim = up ? s_ku[ti] : nown - 16 * ti;
-        int lr[NL];
+        int lr[NL];                                         // row relative to base
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int rr = 8 * half + ld_row[i];
             const int viaList = s_ul[16 * ti + rr];
-            lr[i] = s_nl[16 * ti + (up ? viaList & 15 : rr)];
+            if (LIST) lr[i] = s_nl[16 * ti + (up ? viaList & 15 : rr)];
+            else lr[i] = up ? viaList : rr;
         }
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -216,10 +221,10 @@ k_bat_gateup(const BatParams p)
     auto gate_reduce = [&](int i, int buf) {
         if (tid < 256) {
             const int r = tid >> 6, ln = tid & 63;
-            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = s_nl[16 * i + nn];
+            const int m = 4 * (ln >> 4) + r, nn = ln & 15, j = LIST ? s_nl[16 * i + nn] : j_lo + 16 * i + nn;
             const bool here = 16 * i + nn < nown, valid = m < B && here;
             float a = tile_sum(buf, tid);
-            if (p.relu) {
+            if (RELU) {
                 if (p.b_in && valid) a += p.b_in[j];
                 a = a > 0.0f ? a : (a != a ? a : 0.0f);
             } else {
@@ -229,7 +234,7 @@ k_bat_gateup(const BatParams p)
             s_a[i][m][nn] = a;
             if (keep) atomicOr(&s_km[i * 16 + nn], 1 << m);
             if (p.keep && valid) p.keep[(size_t)m * F + j] = keep ? 1 : 0;
-            if (p.relu && here) p.hbuf[(size_t)j * 16 + m] = keep ? a : 0.0f;     // read back for union-kept neurons only
+            if (RELU && here) p.hbuf[(size_t)j * 16 + m] = keep ? a : 0.0f;     // read back for union-kept neurons only
         }
     };
     // Union-kept neurons of gate tile i, compacted by ballot.  Every wave does it for itself (same
@@ -241,7 +246,7 @@ k_bat_gateup(const BatParams p)
         const int pos = __popcll(bal & ((1ull << lane) - 1ull));
         if (mine) s_ul[16 * i + pos] = lane;
         if (lane == 0) s_ku[i] = __popcll(bal);
-        if (wave == 0 && mine) p.ulist[j_lo_all + nlist + pos] = s_nl[16 * i + lane];
+        if (wave == 0 && mine) p.ulist[j_lo_all + nlist + pos] = LIST ? s_nl[16 * i + lane] : j_lo + 16 * i + lane;
         nlist += __popcll(bal);
         wave_sync();
     };
@@ -251,7 +256,7 @@ k_bat_gateup(const BatParams p)
             const int m = 4 * (ln >> 4) + r, nn = ln & 15;
             if (nn < s_ku[i]) {
                 const int l2 = s_ul[16 * i + nn];
-                const int j = s_nl[16 * i + l2];
+                const int j = LIST ? s_nl[16 * i + l2] : j_lo + 16 * i + l2;
                 const float usum = tile_sum(buf, tid);
                 const bool keep = (s_km[16 * i + l2] >> m) & 1;
                 p.hbuf[(size_t)j * 16 + m] = keep ? s_a[i][m][l2] * usum : 0.0f;
@@ -551,18 +556,24 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     p.keep = keep; p.partial = partial;
     p.d = d; p.F = F; p.B = B; p.P = P; p.RG = RG; p.CG = CG;
     p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
-    p.relu = layer->kind == CLADA_FFN_RELU ? 1 : 0;
+    const bool relu = layer->kind == CLADA_FFN_RELU;
     p.b_in = layer->b_in;
     p.list = list; p.list_n = list_n;
 
+#define CLADA_BAT_LAUNCH(KS, NW, RELU)                                                                                    \
+    {                                                                                                                      \
+        if (list)       hipLaunchKernelGGL((k_bat_gateup<KS, NW, true, true, RELU>), dim3(P), dim3(NW * 64), 0, stream, p);   \
+        else if (dense) hipLaunchKernelGGL((k_bat_gateup<KS, NW, true, false, RELU>), dim3(P), dim3(NW * 64), 0, stream, p);  \
+        else            hipLaunchKernelGGL((k_bat_gateup<KS, NW, false, false, RELU>), dim3(P), dim3(NW * 64), 0, stream, p); \
+    }
 #define CLADA_BAT_CASE(D, KS, NW)                                                                            \
     if (d == D) {                                                                                             \
         static_assert(D == NW * 32 * KS, "waves x k-steps x 32 = d");                                         \
-        if (dense) hipLaunchKernelGGL((k_bat_gateup<KS, NW, true>), dim3(P), dim3(NW * 64), 0, stream, p);    \
-        else       hipLaunchKernelGGL((k_bat_gateup<KS, NW, false>), dim3(P), dim3(NW * 64), 0, stream, p);   \
+        if (relu) CLADA_BAT_LAUNCH(KS, NW, true) else CLADA_BAT_LAUNCH(KS, NW, false)                         \
     }
     CLADA_BAT_CASE(1024, 4, 8) CLADA_BAT_CASE(2048, 8, 8) CLADA_BAT_CASE(2560, 16, 5) CLADA_BAT_CASE(3072, 12, 8)
     CLADA_BAT_CASE(4096, 16, 8) CLADA_BAT_CASE(5120, 32, 5) CLADA_BAT_CASE(6144, 24, 8) CLADA_BAT_CASE(8192, 32, 8)
+#undef CLADA_BAT_LAUNCH
 #undef CLADA_BAT_CASE
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     const size_t lds = 8 * (size_t)DN_TILE_BYTES + sizeof(int) * DN_MAX_ROWS;
@@ -574,7 +585,7 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
     }
     hipLaunchKernelGGL(k_bat_down, dim3(CG * RG), dim3(512), lds, stream, p);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
-    clada_launch_finalize(2, partial, RG, B, d, (char *)y, stream, p.relu ? layer->b_out : nullptr);
+    clada_launch_finalize(2, partial, RG, B, d, (char *)y, stream, relu ? layer->b_out : nullptr);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     *ran = true;
     return CLADA_OK;
