@@ -75,8 +75,9 @@ const char *clada_last_error(const clada_ctx *ctx);
  * "decode.batched" (1 = matrix-core kernels for bf16 batches of 2 and more, 16 tokens
  * per pass [default], 0 = the
  * generic kernels), "decode.spin_limit" (how often a balanced batch-1 kernel polls
- * for the other workgroups' masks before it gives up; default 2^21, about two
- * seconds; 0 = give up without polling; see clada_device_fault), "prefix.tile" (workgroup
+ * for the other workgroups' masks before it gives up; default 4096, a few
+ * milliseconds against the microseconds a healthy exchange takes;
+ * 0 = give up without polling; see clada_device_fault), "prefix.tile" (workgroup
  * tiles of the bf16 prefill GEMMs: 1 = 128 tokens, 2 = 256 tokens wherever the shape
  * allows, 0 = chosen by shape [default]), "diag.kernel_events" (1 = every decode call also
  * records HIP events around its kernels for clada_diag_kernel_times; default 0).
@@ -84,12 +85,15 @@ const char *clada_last_error(const clada_ctx *ctx);
 clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value);
 
 /* The balanced batch-1 decode kernel waits, inside the kernel, for the keep masks of
- * all its workgroups.  They can only stay away while something else holds the
- * compute units they need (two balanced calls overlapping from different streams
- * or processes: use one stream at a time, or option "decode.b1" = 2).  The wait is
- * bounded: past the limit the kernel gives up, the call's output and every later
- * output of the context is NaN, and this call (which synchronises the device)
- * reports *fault_out = 1.  A context that has faulted must be destroyed. */
+ * all its workgroups, one per compute unit.  They can only stay away while something
+ * else holds compute units they need: ANY kernel that runs at the same time on another
+ * stream, context or process and fills whole compute units can do that (a second
+ * balanced call, but also e.g. an attention kernel of the caller's own model).  A caller
+ * that overlaps other GPU work with the FFN calls should set option "decode.b1" = 2
+ * (no cross-workgroup wait anywhere).  The wait is bounded: past the limit the kernel
+ * gives up, the call's output and every later output of the context is NaN, and this
+ * call (which synchronises the device) reports *fault_out = 1.  A context that has
+ * faulted must be destroyed. */
 clada_status clada_device_fault(clada_ctx *ctx, int32_t *fault_out);
 
 /* Upper bound of the workspace any call needs for these sizes.  Pass 0 for a
@@ -196,6 +200,18 @@ clada_status clada_threshold(clada_ctx *ctx, const float *tau_base, const float 
                              const float *gamma, int32_t L, const float *surprisal,
                              const float *entropy, int32_t B, float tau_s, float tau_H,
                              float *tau_final, void *hip_stream);
+
+/* The two calls above as one launch (the generation phase of the algorithm "CLADA
+ * Inference" computes the signals and then the thresholds once per token, ahead of
+ * the layers): surprisal / entropy [B] as clada_cognitive_signals writes them, and
+ * tau_final [L][B] as clada_threshold would compute it from them -- the block that
+ * finishes a row of logits also writes that row's L thresholds.  Same arguments,
+ * same limits, same results bit for bit. */
+clada_status clada_signals_threshold(clada_ctx *ctx, const void *logits, int32_t logits_dtype,
+                                     int32_t B, int32_t V, const int32_t *token_ids,
+                                     const float *tau_base, const float *lambda, const float *gamma,
+                                     int32_t L, float tau_s, float tau_H, float *surprisal,
+                                     float *entropy, float *tau_final, void *hip_stream);
 
 /* Thresholded sparse SwiGLU FFN for one layer at decode time (algorithm "CLADA
  * Inference", generation phase: regenerate the mask by thresholding, then the

@@ -8,7 +8,7 @@ library is not built.
 """
 from .binding import (Context, Layer, PrefixStats, CladaError, cognitive_signals,  # noqa: F401
                       dense_ffn_decode, lib_path, load_library, prefix_stats,
-                      sparse_ffn_decode, threshold, threshold_calibrate,
+                      sparse_ffn_decode, threshold, threshold_calibrate, signals_threshold,
                       threshold_search_cett, cett_eval, static_mask_threshold,
                       static_mask_topk, static_ffn_decode, mask_pack, mask_unpack,
                       workspace_bytes, Graph, graph_begin, graph_end)

@@ -69,6 +69,7 @@ def load_library() -> C.CDLL:
     lib.clada_threshold_calibrate.argtypes = [vp, vp, C.c_int64, f32, vp, vp]
     lib.clada_cognitive_signals.argtypes = [vp, vp, C.c_int, i32, i32, vp, vp, vp, vp]
     lib.clada_threshold.argtypes = [vp, vp, vp, vp, i32, vp, vp, i32, f32, f32, vp, vp]
+    lib.clada_signals_threshold.argtypes = [vp, vp, C.c_int, i32, i32, vp, vp, vp, vp, i32, f32, f32, vp, vp, vp, vp]
     lib.clada_sparse_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp, vp, vp, vp, vp]
     lib.clada_dense_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp]
     lib.clada_diag_stream_read.argtypes = [vp, vp, C.c_size_t, i32, vp]
@@ -90,7 +91,7 @@ def load_library() -> C.CDLL:
     for name in ("clada_diag_stream_read", "clada_diag_copy", "clada_diag_kernel_times", "clada_device_fault",
                  "clada_threshold_search_cett", "clada_cett_eval", "clada_static_mask_threshold",
                  "clada_static_mask_topk", "clada_static_ffn_decode", "clada_mask_pack", "clada_mask_unpack", "clada_create", "clada_set_option", "clada_prefix_stats", "clada_threshold_calibrate",
-                 "clada_cognitive_signals", "clada_threshold", "clada_sparse_ffn_decode",
+                 "clada_cognitive_signals", "clada_threshold", "clada_signals_threshold", "clada_sparse_ffn_decode",
                  "clada_dense_ffn_decode"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -260,6 +261,25 @@ def threshold(ctx: Context, tau_base, lam, gam, surprisal, entropy, tau_s: float
                                        _ptr(entropy), B, float(tau_s), float(tau_H), _ptr(out),
                                        _stream(tau_base)))
     return out
+
+
+def signals_threshold(ctx: Context, logits: torch.Tensor, token_ids: torch.Tensor, tau_base, lam, gam,
+                      tau_s: float, tau_H: float, out: torch.Tensor | None = None):
+    """(surprisal [B], entropy [B], tau_final [L][B]) from one launch."""
+    B, V = logits.shape
+    L = tau_base.numel()
+    assert logits.is_cuda and logits.is_contiguous()
+    assert token_ids.is_cuda and token_ids.dtype == torch.int32 and token_ids.numel() == B
+    for t in (tau_base, lam, gam):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == L
+    s = torch.empty(B, dtype=torch.float32, device=logits.device)
+    h = torch.empty(B, dtype=torch.float32, device=logits.device)
+    if out is None:
+        out = torch.empty(L, B, dtype=torch.float32, device=logits.device)
+    ctx.check(ctx._lib.clada_signals_threshold(ctx._h, _ptr(logits), _dtype_code(logits), B, V, _ptr(token_ids),
+                                               _ptr(tau_base), _ptr(lam), _ptr(gam), L, float(tau_s), float(tau_H),
+                                               _ptr(s), _ptr(h), _ptr(out), _stream(logits)))
+    return s, h, out
 
 
 def sparse_ffn_decode(ctx: Context, layer: Layer, x: torch.Tensor, tau_final: torch.Tensor,

@@ -69,7 +69,8 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->opt_decode_b1 = 1;
     ctx->opt_decode_batched = 1;
     ctx->opt_decode_own_first = 0;
-    ctx->opt_decode_spin_limit = 1 << 21;
+    ctx->opt_decode_spin_limit = 1 << 12;
+    ctx->n_occ = 0;
     ctx->opt_prefix_tile = 0;
     ctx->capturing = 0;
     ctx->opt_diag_events = 0;

@@ -7,6 +7,8 @@
 
 #include "clada.h"
 
+#define CLADA_OCC_SLOTS 32
+
 struct clada_ctx {
     int device;
     int num_cu;
@@ -21,6 +23,11 @@ struct clada_ctx {
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)
     hipEvent_t ev[4];            // start/stop of the main decode kernel, start/stop of the final reduction
     int capturing;               // a clada_graph_begin is open
+    // workgroups per compute unit of the balanced batch-1 kernel instances on this context's device
+    // (asked of the runtime once per instance; the balanced kernel needs all its workgroups resident)
+    const void *occ_fn[CLADA_OCC_SLOTS];
+    int occ_val[CLADA_OCC_SLOTS];
+    int n_occ;
     char err[512];
 };
 
@@ -29,12 +36,12 @@ struct clada_ctx {
 
 // The first bytes of the workspace hold self-resetting arrival counters (zeroed
 // once at clada_create); the scratch area proper starts after them.
-#define CLADA_WS_HEADER (96 * 1024)
+#define CLADA_WS_HEADER (160 * 1024)
 enum { CTR_SIGNALS = 0, CTR_DECODE = 64, CTR_PREFIX = 128, CTR_CALIB = 192 };  // int32 slots
 // Control words of the cooperative decode kernel inside the header (byte offsets).
 #define COOP_MAX_WGS 256
 enum { COOP_EPOCH = 1024, COOP_FAULT = 1088, COOP_REC = 4096,
-       COOP_APUB = 8192 /* 256*64 floats = 64 KiB */ };
+       COOP_APUB = 8192 /* 256*64 tagged words of 8 bytes = 128 KiB */ };
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -232,32 +232,32 @@ k_ffn_decode(const DecodeParams p)
     }
 }
 
-// y[b][col] = sum_p partial[p][b][col].  A workgroup owns 32 columns; thread (slice, colgroup)
-// adds the partials p = slice, slice+32, ... (all loads issued together), the 32 slices are
+// y[b][col] = sum_p partial[p][b][col].  A workgroup owns 4*CG columns; thread (slice, colgroup)
+// adds the partials p = slice, slice+SL, ... (U loads in flight at a time), the SL slices are
 // folded by a fixed tree; one rounding to the output dtype.
-template <int ES>
-__global__ void __launch_bounds__(256)
+template <int ES, int CG, int SL, int U>
+__global__ void __launch_bounds__(CG * SL)
 k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict__ y, unsigned int *epoch,
                const float *__restrict__ bias, const int *__restrict__ fault)
 {
     if (epoch && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *epoch += 1u;   // cooperative call counter
-    __shared__ float4 s_sum[32][8];
-    const int cg = threadIdx.x & 7, sl = threadIdx.x >> 3;
-    const int col = blockIdx.x * 32 + cg * 4;
+    __shared__ float4 s_sum[SL][CG];
+    const int cg = threadIdx.x % CG, sl = threadIdx.x / CG;
+    const int col = blockIdx.x * (4 * CG) + cg * 4;
     const int b = blockIdx.y, B = gridDim.y;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     if (col < d) {
         const float *base = partial + (size_t)b * d + col;
         const size_t pstride = (size_t)B * d;
         int q = sl;
-        for (; q + 7 * 32 < P; q += 8 * 32) {
-            float4 v[8];
+        for (; q + (U - 1) * SL < P; q += U * SL) {
+            float4 v[U];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4 *>(base + (size_t)(q + u * 32) * pstride);
+            for (int u = 0; u < U; ++u) v[u] = *reinterpret_cast<const float4 *>(base + (size_t)(q + u * SL) * pstride);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+            for (int u = 0; u < U; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
         }
-        for (; q < P; q += 32) {
+        for (; q < P; q += SL) {
             const float4 v = *reinterpret_cast<const float4 *>(base + (size_t)q * pstride);
             s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
         }
@@ -265,7 +265,7 @@ k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict
     s_sum[sl][cg] = s;
     __syncthreads();
 #pragma unroll
-    for (int h = 16; h >= 1; h >>= 1) {
+    for (int h = SL / 2; h >= 1; h >>= 1) {
         if (sl < h) {
             const float4 v = s_sum[sl + h][cg];
             s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
@@ -290,18 +290,25 @@ k_ffn_finalize(const float *__restrict__ partial, int P, int d, char *__restrict
     }
 }
 
+template <int ES, int CG, int SL, int U>
+void launch_finalize_shape(const float *partial, int P, int B, int d, char *y, unsigned int *epoch, hipStream_t stream,
+                           hipEvent_t ev_start, hipEvent_t ev_stop, const float *bias, const int *fault)
+{
+    const dim3 grid((d + 4 * CG - 1) / (4 * CG), B);
+    auto kern = k_ffn_finalize<ES, CG, SL, U>;
+    if (ev_start) hipExtLaunchKernelGGL(kern, grid, dim3(CG * SL), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias, fault);
+    else hipLaunchKernelGGL(kern, grid, dim3(CG * SL), 0, stream, partial, P, d, y, epoch, bias, fault);
+}
+
 void launch_finalize(int es, const float *partial, int P, int B, int d, char *y, unsigned int *epoch, hipStream_t stream,
                      hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, const float *bias = nullptr,
                      const int *fault = nullptr)
 {
-    const dim3 grid((d + 31) / 32, B);
-    if (ev_start) {
-        if (es == 4) hipExtLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias, fault);
-        else         hipExtLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, ev_start, ev_stop, 0, partial, P, d, y, epoch, bias, fault);
-        return;
-    }
-    if (es == 4) hipLaunchKernelGGL(k_ffn_finalize<4>, grid, dim3(256), 0, stream, partial, P, d, y, epoch, bias, fault);
-    else         hipLaunchKernelGGL(k_ffn_finalize<2>, grid, dim3(256), 0, stream, partial, P, d, y, epoch, bias, fault);
+    // 8 column groups x 32 slices, 8 loads in flight per thread.  The kernel is one dependent round trip
+    // through memory plus its launch, about 4 us whatever its shape: 64 to 256 slices, 8 to 32 columns
+    // per workgroup and 128 to 512 workgroups all measured 3.96 - 4.2 us on the 7B layer (4 MB of partials).
+    if (es == 4) launch_finalize_shape<4, 8, 32, 8>(partial, P, B, d, y, epoch, stream, ev_start, ev_stop, bias, fault);
+    else launch_finalize_shape<2, 8, 32, 8>(partial, P, B, d, y, epoch, stream, ev_start, ev_stop, bias, fault);
 }
 
 // Ascending union index list, counts and per-token bit masks from the keep
@@ -433,17 +440,6 @@ __device__ __forceinline__ int select_bit(unsigned long long m, int t)
 //           h * W_down[j, slice] into its 8 (bf16) or 4 (fp32) accumulators per chunk.
 //   No cross-wave fold (each wave owns its columns) and plenty of bytes in flight, so a
 //   workgroup with more kept neurons than its neighbours simply streams longer at its own rate.
-#ifdef CLADA_TIMESTAMPS
-// Development aid: per-workgroup wall-clock stamps at the phase boundaries of k_ffn_decode_b1.
-__device__ long long g_b1_stamps[512 * 8];
-#define B1_STAMP(slot) do { if (tid == 0) g_b1_stamps[blk * 8 + (slot)] = wall_clock64(); } while (0)
-extern "C" int clada_debug_fetch_stamps(long long *host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_b1_stamps), sizeof(long long) * n);
-}
-#else
-#define B1_STAMP(slot) do { } while (0)
-#endif
 
 struct B1Params {
     const char *wg, *wu, *wd, *x;
@@ -451,7 +447,7 @@ struct B1Params {
     float *partial;             // [P][d]
     unsigned char *keep;        // [F] or nullptr
     unsigned long long *rec;    // [P] keep mask (bit i = neuron blk + P*i, i < 56) | epoch tag in bits 56..63
-    float *apub;                // [P][64] published activations
+    unsigned long long *apub;   // [P][64] published activations: fp32 bits | 32-bit call counter in the high half
     const unsigned int *epoch;  // device-side counter of balanced calls, advanced by k_ffn_finalize
                                 // (read at kernel start, so graph replays stay correct)
     const float *b_in;          // RELU: input bias [F] or nullptr
@@ -513,7 +509,6 @@ k_ffn_decode_b1(const B1Params p)
     const int ni = blk < F ? (F - blk + P - 1) / P : 0;     // <= 64 (<= 56 when BAL)
 
     const int loff = lane * 16;
-    B1_STAMP(0);
 
     auto load_row = [&](u32x4 (&buf)[NCH], const char *w, int j) {
         const char *row = w + (size_t)j * ROWB + loff;
@@ -529,7 +524,27 @@ k_ffn_decode_b1(const B1Params p)
     for (int c = 0; c < NCH; ++c) xr[c] = *reinterpret_cast<const u32x4 *>(p.x + c * 1024 + loff);
     const float tau = DENSE ? 0.0f : p.tau[0];
     unsigned long long tag = 0ull;
-    if (BAL) tag = (unsigned long long)((*p.epoch + 1u) & 0xffu) << 56;
+    unsigned int call_no = 0u;                              // this balanced call's number on the context
+    if (BAL) {
+        call_no = *p.epoch + 1u;
+        tag = (unsigned long long)(call_no & 0xffu) << 56;
+    }
+    // An activation another workgroup published: the word carries the number of the call that wrote it, so
+    // it validates itself and needs no ordering against the mask record that announced it.  Bounded like the
+    // wait for the records (the store was issued before the record's, so a second poll is already rare).
+    auto published_act = [&](int slot) -> float {
+        unsigned long long v = 0ull;
+        bool ok = false;
+        for (int spins = 0; spins <= p.max_spins && !ok; ++spins) {
+            v = __hip_atomic_load(p.apub + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = (unsigned int)(v >> 32) == call_no;
+        }
+        if (!ok) {
+            __hip_atomic_store(p.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return 0.0f;
+        }
+        return __uint_as_float((unsigned int)v);
+    };
 
     auto gate_finish = [&](const u32x4 (&buf)[NCH], int i) {
         float s = 0.0f;
@@ -560,9 +575,7 @@ k_ffn_decode_b1(const B1Params p)
             gate_finish(ga, i);
         }
     }
-    B1_STAMP(1);
     __syncthreads();
-    B1_STAMP(2);
 
     // every wave derives the same ascending list
     const unsigned long long mask = __ballot(lane < ni && s_flag[lane] != 0);
@@ -618,7 +631,7 @@ k_ffn_decode_b1(const B1Params p)
             const int e = first + r * stride;
             const int j = local ? blk + P * rows[e] : rows[e];
             if (local) av[r] = s_a[rows[e]];
-            else av[r] = __hip_atomic_load(p.apub + aidx[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else av[r] = published_act(aidx[e]);
             if (!RELU) load_row(up[r], p.wu, j);
         }
 #pragma unroll
@@ -640,9 +653,14 @@ k_ffn_decode_b1(const B1Params p)
         const int K0 = min(p.K0, K0MAX);
         const int own = min(kp, K0);
         if (wave == 0) {
+            // Every published word is one 64-bit atomic object that names the call it belongs to (the mask
+            // record by an 8-bit tag -- every call rewrites every record --, an activation by the full call
+            // number), so readers never pair a fresh word with a stale one and no release/acquire is needed.
+            // (An agent-scope release here writes back the XCD's L2: measured +9.5 us per call.)
             if (lane < ni)
-                __hip_atomic_store(p.apub + blk * 64 + lane, s_a[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // = wait for the stores' acknowledgements
+                __hip_atomic_store(p.apub + blk * 64 + lane,
+                                   ((unsigned long long)call_no << 32) | __float_as_uint(s_a[lane]),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (lane == 0) __hip_atomic_store(p.rec + blk, mask | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         u32x4 dn0[K0MAX][SL];
@@ -729,7 +747,6 @@ k_ffn_decode_b1(const B1Params p)
             if (lane == 0) s_n2 = hi - lo;
             }
         }
-        B1_STAMP(7);
         __syncthreads();
         // first chunk of the balanced share: its loads go out before chunk 0 is consumed
         const int n2 = s_n2;
@@ -745,7 +762,7 @@ k_ffn_decode_b1(const B1Params p)
             for (int r = 0; r < UPB; ++r)
                 if (r < nup) {
                     const int e = wave + r * NW;
-                    av[r] = __hip_atomic_load(p.apub + s_l2a[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    av[r] = published_act(s_l2a[e]);
                     if (!RELU) load_row(up[r], p.wu, s_l2row[e]);
                 }
             down_fma(std::integral_constant<int, K0MAX>{}, dn0, s_h[0], own);
@@ -761,9 +778,7 @@ k_ffn_decode_b1(const B1Params p)
                     }
                     if (lane == 0) s_h[1][wave + r * NW] = RELU ? av[r] : av[r] * s0;
                 }
-            B1_STAMP(3);
             __syncthreads();
-            B1_STAMP(4);
             down_fma(std::integral_constant<int, DCH>{}, dn, s_h[1], nc);
         }
         // rest of the share (rare: more than DCH extra neurons)
@@ -790,13 +805,10 @@ k_ffn_decode_b1(const B1Params p)
             if (nup == 1) up_rows(std::integral_constant<int, 1>{}, s_list + c0, nullptr, true, wave, NW, s_h[par]);
             else if (nup == 2) up_rows(std::integral_constant<int, UPB >= 2 ? 2 : 1>{}, s_list + c0, nullptr, true, wave, NW, s_h[par]);
             else if (nup == 3) up_rows(std::integral_constant<int, UPB >= 3 ? 3 : 1>{}, s_list + c0, nullptr, true, wave, NW, s_h[par]);
-            B1_STAMP(3);
             __syncthreads();
-            B1_STAMP(4);
             down_fma(std::integral_constant<int, DCH>{}, dn, s_h[par], nc);
         }
     }
-    B1_STAMP(5);
     // each wave owns its columns: straight to the partial, no fold
     float *dst = p.partial + (size_t)blk * p.d;
 #pragma unroll
@@ -809,7 +821,6 @@ k_ffn_decode_b1(const B1Params p)
                     make_float4(acc[s][k], acc[s][k + 1], acc[s][k + 2], acc[s][k + 3]);
         }
     }
-    B1_STAMP(6);
 }
 
 template <int ES, int NCH, int DCH, bool DENSE, bool BAL, bool RELU = false>
@@ -817,12 +828,21 @@ hipError_t launch_b1_variant(clada_ctx *ctx, const B1Params &p, int P, hipStream
 {
     auto kern = k_ffn_decode_b1<ES, NCH, 8, DCH, DENSE, BAL, RELU>;
     if (BAL) {          // spinning on other workgroups' records needs every workgroup resident at once
-        static int occ = -1;
+        // (the answer is kept in the context: it belongs to the context's device, and a context is used by
+        // one thread at a time)
+        const void *fn = reinterpret_cast<const void *>(kern);
+        int occ = -1;
+        for (int i = 0; i < ctx->n_occ; ++i)
+            if (ctx->occ_fn[i] == fn) occ = ctx->occ_val[i];
         if (occ < 0) {
             int nb = 0;
             hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, 512, 0);
             if (e != hipSuccess) return e;
             occ = nb;
+            if (ctx->n_occ < CLADA_OCC_SLOTS) {
+                ctx->occ_fn[ctx->n_occ] = fn;
+                ctx->occ_val[ctx->n_occ++] = nb;
+            }
         }
         if ((long long)occ * ctx->num_cu < P) return hipErrorNotSupported;
     }
@@ -909,7 +929,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             B1Params b;
             b.wg = p.wg; b.wu = p.wu; b.wd = p.wd; b.x = p.x; b.tau = tau; b.partial = p.partial; b.keep = p.keep;
             b.rec = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_REC);
-            b.apub = reinterpret_cast<float *>(ctx->ws + COOP_APUB);
+            b.apub = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_APUB);
             unsigned int *epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
             b.epoch = epoch;
             b.b_in = p.b_in;

@@ -52,11 +52,29 @@ constexpr int SIG_THREADS = 256;
 constexpr int SIG_GROUP = 8;                       // logits folded per online update
 constexpr int SIG_CHUNK = SIG_THREADS * SIG_GROUP * 2;   // logits per block
 
+// Optional tail of the signals kernel: the token-aware thresholds of all layers for the row just finished
+// (final-threshold equation of section 3.2.3); L = 0 switches it off.
+struct ThresholdTail {
+    const float *tau_base, *lambda, *gamma;   // [L]
+    float *tau_final;                         // [L][B]
+    float tau_s, tau_H;
+    int L;
+};
+
+// tau_base * (1 + lambda*[s > tau_s] + gamma*[H > tau_H]), in the association of the printed formula
+__device__ __forceinline__ float tau_final_f32(float tau_base, float lambda, float gamma, float s, float H,
+                                               float tau_s, float tau_H)
+{
+    const float is = s > tau_s ? 1.0f : 0.0f;
+    const float ih = H > tau_H ? 1.0f : 0.0f;
+    return tau_base * (1.0f + lambda * is + gamma * ih);
+}
+
 template <int ES>
 __global__ void __launch_bounds__(SIG_THREADS)
 k_signals(const char *__restrict__ logits, int V, const int32_t *__restrict__ tok,
           float *__restrict__ part /* [B][NB][4] */, int *__restrict__ counters,
-          float *__restrict__ surprisal, float *__restrict__ entropy)
+          float *__restrict__ surprisal, float *__restrict__ entropy, const ThresholdTail th)
 {
     __shared__ Lse s_w[SIG_THREADS / 64];
     __shared__ int s_last;
@@ -109,16 +127,17 @@ k_signals(const char *__restrict__ logits, int V, const int32_t *__restrict__ to
     if (tid == 0) {
         Lse r = s_w[0];
         for (int w = 1; w < SIG_THREADS / 64; ++w) r = lse_merge(r, s_w[w]);
-        // agent-scope (write-through) stores, their acknowledgements, then the arrival count: the block that
-        // folds the partials may run on another XCD, and a release fence at that scope would write back the L2
+        // agent-scope (write-through) stores, one release at that scope, then the arrival count: the block
+        // that folds the partials may run on another XCD
         float *dst = part + ((size_t)b * nb + blockIdx.x) * 4;
         __hip_atomic_store(dst + 0, r.m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(dst + 1, r.Z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(dst + 2, r.T, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(dst + 3, r.bad ? 1.0f : 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         const int prev = __hip_atomic_fetch_add(&counters[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (prev == nb - 1);
+        if (prev == nb - 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // the other blocks' partials
     }
     __syncthreads();
     if (s_last && tid < 64) {
@@ -143,9 +162,9 @@ k_signals(const char *__restrict__ logits, int V, const int32_t *__restrict__ to
             other.bad = __shfl_xor(r.bad, o);
             r = ((tid & o) == 0) ? lse_merge(r, other) : lse_merge(other, r);
         }
+        float H = 0.0f, s = 0.0f;
         if (tid == 0) {
             __hip_atomic_store(&counters[b], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-            float H, s;
             if (r.bad || !(r.Z > 0.0f)) {
                 H = NAN;
                 s = NAN;
@@ -158,6 +177,14 @@ k_signals(const char *__restrict__ logits, int V, const int32_t *__restrict__ to
             entropy[b] = H;
             surprisal[b] = s;
         }
+        if (th.L > 0) {                         // this row's thresholds for every layer, from the registers
+            H = __shfl(H, 0);
+            s = __shfl(s, 0);
+            const int B = gridDim.y;
+            for (int l = tid; l < th.L; l += 64)
+                th.tau_final[(size_t)l * B + b] =
+                    tau_final_f32(th.tau_base[l], th.lambda[l], th.gamma[l], s, H, th.tau_s, th.tau_H);
+        }
     }
 }
 
@@ -169,10 +196,7 @@ k_threshold(const float *__restrict__ tau_base, const float *__restrict__ lambda
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= L * B) return;
     const int l = idx / B, b = idx - l * B;
-    const float is = s[b] > tau_s ? 1.0f : 0.0f;
-    const float ih = H[b] > tau_H ? 1.0f : 0.0f;
-    // same association as the printed formula: 1 + lambda*I + gamma*I, then times tau_base
-    out[idx] = tau_base[l] * (1.0f + lambda[l] * is + gamma[l] * ih);
+    out[idx] = tau_final_f32(tau_base[l], lambda[l], gamma[l], s[b], H[b], tau_s, tau_H);
 }
 
 }  // namespace
@@ -185,12 +209,10 @@ size_t clada_ws_signals(int32_t B, int32_t V)
     return align_up(sizeof(float) * 4 * (size_t)B * signals_blocks(V), 256);
 }
 
-extern "C" clada_status clada_cognitive_signals(clada_ctx *ctx, const void *logits,
-                                                int32_t logits_dtype, int32_t B, int32_t V,
-                                                const int32_t *token_ids, float *surprisal,
-                                                float *entropy, void *hip_stream)
+// Argument checks shared by the three signal entry points (host only, before any HIP call).
+static clada_status check_signals_args(clada_ctx *ctx, const void *logits, int32_t logits_dtype, int32_t B, int32_t V,
+                                       const int32_t *token_ids, const float *surprisal, const float *entropy)
 {
-    if (!ctx) return CLADA_ERR_NULL;
     if (!logits || !token_ids || !surprisal || !entropy)
         return clada_fail(ctx, CLADA_ERR_NULL, "logits, token_ids, surprisal or entropy is NULL");
     if (logits_dtype != CLADA_F32 && logits_dtype != CLADA_BF16)
@@ -199,20 +221,72 @@ extern "C" clada_status clada_cognitive_signals(clada_ctx *ctx, const void *logi
     if (V < 1 || V > (1 << 24)) return clada_fail(ctx, CLADA_ERR_SHAPE, "V=%d outside [1,2^24]", V);
     if (((uintptr_t)logits & (dtype_size(logits_dtype) - 1)) != 0)
         return clada_fail(ctx, CLADA_ERR_ALIGN, "logits not aligned to their element size");
+    return CLADA_OK;
+}
+
+static clada_status check_threshold_args(clada_ctx *ctx, const float *tau_base, const float *lambda, const float *gamma,
+                                         int32_t L, int32_t B, float tau_s, float tau_H, const float *tau_final)
+{
+    if (!tau_base || !lambda || !gamma || !tau_final)
+        return clada_fail(ctx, CLADA_ERR_NULL, "an array pointer is NULL");
+    if (L < 1 || L > CLADA_MAX_LAYERS) return clada_fail(ctx, CLADA_ERR_SHAPE, "L=%d outside [1,%d]", L, CLADA_MAX_LAYERS);
+    if (B < 1 || B > CLADA_MAX_BATCH) return clada_fail(ctx, CLADA_ERR_SHAPE, "B=%d outside [1,%d]", B, CLADA_MAX_BATCH);
+    if (tau_s != tau_s || tau_H != tau_H) return clada_fail(ctx, CLADA_ERR_VALUE, "tau_s or tau_H is NaN");
+    return CLADA_OK;
+}
+
+static hipError_t launch_signals(const void *logits, int32_t logits_dtype, int32_t B, int32_t V, const int32_t *token_ids,
+                                 float *part, int *counters, float *surprisal, float *entropy, const ThresholdTail &th,
+                                 hipStream_t st)
+{
+    const dim3 grid(signals_blocks(V), B);
+    if (logits_dtype == CLADA_F32)
+        hipLaunchKernelGGL(k_signals<4>, grid, dim3(SIG_THREADS), 0, st, (const char *)logits, V, token_ids,
+                           part, counters, surprisal, entropy, th);
+    else
+        hipLaunchKernelGGL(k_signals<2>, grid, dim3(SIG_THREADS), 0, st, (const char *)logits, V, token_ids,
+                           part, counters, surprisal, entropy, th);
+    return hipGetLastError();
+}
+
+extern "C" clada_status clada_cognitive_signals(clada_ctx *ctx, const void *logits,
+                                                int32_t logits_dtype, int32_t B, int32_t V,
+                                                const int32_t *token_ids, float *surprisal,
+                                                float *entropy, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    clada_status cs = check_signals_args(ctx, logits, logits_dtype, B, V, token_ids, surprisal, entropy);
+    if (cs != CLADA_OK) return cs;
     const size_t need = CLADA_WS_HEADER + clada_ws_signals(B, V);
     if (ctx->ws_bytes < need)
         return clada_fail(ctx, CLADA_ERR_WORKSPACE, "workspace %zu < %zu bytes needed", ctx->ws_bytes, need);
     int *counters = reinterpret_cast<int *>(ctx->ws) + CTR_SIGNALS;
     float *part = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
-    const dim3 grid(signals_blocks(V), B);
-    hipStream_t st = (hipStream_t)hip_stream;
-    if (logits_dtype == CLADA_F32)
-        hipLaunchKernelGGL(k_signals<4>, grid, dim3(SIG_THREADS), 0, st, (const char *)logits, V, token_ids,
-                           part, counters, surprisal, entropy);
-    else
-        hipLaunchKernelGGL(k_signals<2>, grid, dim3(SIG_THREADS), 0, st, (const char *)logits, V, token_ids,
-                           part, counters, surprisal, entropy);
-    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    ThresholdTail th = {};
+    CLADA_CHECK_HIP(ctx, launch_signals(logits, logits_dtype, B, V, token_ids, part, counters, surprisal, entropy, th,
+                                        (hipStream_t)hip_stream));
+    return CLADA_OK;
+}
+
+extern "C" clada_status clada_signals_threshold(clada_ctx *ctx, const void *logits, int32_t logits_dtype, int32_t B,
+                                                int32_t V, const int32_t *token_ids, const float *tau_base,
+                                                const float *lambda, const float *gamma, int32_t L, float tau_s,
+                                                float tau_H, float *surprisal, float *entropy, float *tau_final,
+                                                void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    clada_status cs = check_signals_args(ctx, logits, logits_dtype, B, V, token_ids, surprisal, entropy);
+    if (cs != CLADA_OK) return cs;
+    cs = check_threshold_args(ctx, tau_base, lambda, gamma, L, B, tau_s, tau_H, tau_final);
+    if (cs != CLADA_OK) return cs;
+    const size_t need = CLADA_WS_HEADER + clada_ws_signals(B, V);
+    if (ctx->ws_bytes < need)
+        return clada_fail(ctx, CLADA_ERR_WORKSPACE, "workspace %zu < %zu bytes needed", ctx->ws_bytes, need);
+    int *counters = reinterpret_cast<int *>(ctx->ws) + CTR_SIGNALS;
+    float *part = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
+    const ThresholdTail th = {tau_base, lambda, gamma, tau_final, tau_s, tau_H, L};
+    CLADA_CHECK_HIP(ctx, launch_signals(logits, logits_dtype, B, V, token_ids, part, counters, surprisal, entropy, th,
+                                        (hipStream_t)hip_stream));
     return CLADA_OK;
 }
 
@@ -222,11 +296,9 @@ extern "C" clada_status clada_threshold(clada_ctx *ctx, const float *tau_base, c
                                         float *tau_final, void *hip_stream)
 {
     if (!ctx) return CLADA_ERR_NULL;
-    if (!tau_base || !lambda || !gamma || !surprisal || !entropy || !tau_final)
-        return clada_fail(ctx, CLADA_ERR_NULL, "an array pointer is NULL");
-    if (L < 1 || L > CLADA_MAX_LAYERS) return clada_fail(ctx, CLADA_ERR_SHAPE, "L=%d outside [1,%d]", L, CLADA_MAX_LAYERS);
-    if (B < 1 || B > CLADA_MAX_BATCH) return clada_fail(ctx, CLADA_ERR_SHAPE, "B=%d outside [1,%d]", B, CLADA_MAX_BATCH);
-    if (tau_s != tau_s || tau_H != tau_H) return clada_fail(ctx, CLADA_ERR_VALUE, "tau_s or tau_H is NaN");
+    if (!surprisal || !entropy) return clada_fail(ctx, CLADA_ERR_NULL, "an array pointer is NULL");
+    clada_status cs = check_threshold_args(ctx, tau_base, lambda, gamma, L, B, tau_s, tau_H, tau_final);
+    if (cs != CLADA_OK) return cs;
     if (ctx->ws_bytes == 0) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "context has no device");
     const int n = L * B;
     hipLaunchKernelGGL(k_threshold, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, tau_base,

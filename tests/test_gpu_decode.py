@@ -354,3 +354,27 @@ def test_bounded_wait_of_the_balanced_kernel_gives_up_cleanly(clada):
     again = clada.sparse_ffn_decode(fresh, layer, xd, td)
     torch.cuda.synchronize()
     assert not fresh.device_fault() and torch.equal(again, good)
+
+
+def test_many_balanced_calls_on_one_context_stay_identical(clada):
+    """The balanced kernel tags its records with an 8-bit call counter that lives on the device: more than
+    256 calls on one context (the tag wraps) must keep giving the first call's bits, and the oracle's result."""
+    cfg, w, x = _case("c2", 14, 4096, 11008, 1)
+    tau = _tau_for(w, x, 0.45)
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+    ctx.set_option("decode.b1", 3)
+    y0, idx0, cnt0, bits0 = clada.sparse_ffn_decode(ctx, layer, xd, td, want_lists=True)
+    torch.cuda.synchronize()
+    _check_against_oracle(cfg, w, x, tau, y0, idx0.cpu().numpy(), cnt0.cpu().numpy(), unpack_bits(bits0, 11008),
+                          "first balanced call")
+    y0, idx0 = y0.clone(), idx0.clone()
+    for i in range(1, 321):
+        if i % 40 == 0:
+            y, idx, cnt, _ = clada.sparse_ffn_decode(ctx, layer, xd, td, want_lists=True)
+            assert torch.equal(idx, idx0) and torch.equal(cnt, cnt0), f"call {i}: index list changed"
+        else:
+            y = clada.sparse_ffn_decode(ctx, layer, xd, td)
+        assert torch.equal(y, y0), f"call {i}: output bits changed"
+    assert not ctx.device_fault()

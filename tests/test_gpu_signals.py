@@ -129,6 +129,44 @@ def test_threshold_parity_all_indicator_patterns(clada, ctx):
     np.testing.assert_allclose(out.cpu().numpy()[0], [1.0, 1.80, 1.12, 1.92], rtol=2e-7)
 
 
+@pytest.mark.parametrize("cfg_name,B,V,L", [("c1", 16, 1000, 1), ("c2", 1, 32000, 32), ("c4", 3, 128256, 200),
+                                            ("c5", 16, 32000, 40), ("c1", 64, 4097, 4096)])
+def test_signals_and_thresholds_in_one_launch(clada, ctx, cfg_name, B, V, L):
+    """clada_signals_threshold against the oracle's signals and threshold, every indicator pattern and both
+    signs of the coefficients; and bit for bit against the two separate calls."""
+    cfg = synth.CONFIGS[cfg_name]
+    z, _ = synth.logits(cfg, 5, 0, B=B, V=V)
+    tok = synth.draw_tokens(cfg, 5, 0, z)
+    if B > 2:
+        tok = np.array(tok)
+        tok[1] = V + 3                                  # surprisal NaN: its indicator must stay off
+    s_ref, h_ref = oracle.signals(z, tok)
+    r = np.random.default_rng(L)
+    tb = np.abs(r.standard_normal(L)).astype(np.float32)
+    f = lambda a: torch.from_numpy(np.asarray(a)).to(DEV)
+    zd, td = to_dev(z, "f32"), f(np.asarray(tok, np.int32))
+    for lam_v, gam_v in ((0.80, 0.12), (-0.80, -0.12)):
+        lam, gam = np.full(L, lam_v, np.float32), np.full(L, gam_v, np.float32)
+        # (the scalars travel as fp32: the oracle gets the same rounded values)
+        for tau_s, tau_h in ((float(np.float32(np.nanmedian(s_ref))), float(np.float32(np.nanmedian(h_ref)))),
+                             (np.inf, np.inf), (-np.inf, -np.inf)):
+            s, h, out = clada.signals_threshold(ctx, zd, td, f(tb), f(lam), f(gam), tau_s, tau_h)
+            s2, h2 = clada.cognitive_signals(ctx, zd, td)
+            out2 = clada.threshold(ctx, f(tb), f(lam), f(gam), s2, h2, tau_s, tau_h)
+            torch.cuda.synchronize()
+            assert torch.equal(s.view(torch.int32), s2.view(torch.int32)) and torch.equal(h.view(torch.int32), h2.view(torch.int32))
+            assert torch.equal(out, out2) and out.shape == (L, B)
+            np.testing.assert_allclose(s.cpu().numpy(), s_ref, atol=TOL_SIGNAL, rtol=0)
+            np.testing.assert_allclose(h.cpu().numpy(), h_ref, atol=TOL_SIGNAL, rtol=0)
+            # thresholds: the oracle's formula on the device's own fp32 signals (a signal within 1e-4 of
+            # tau_s may fall on either side of it, the medians above are such values)
+            ref = oracle.threshold(tb, lam, gam, s.cpu().numpy(), h.cpu().numpy(), tau_s, tau_h)
+            np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=2e-7, atol=0)
+            ref64 = oracle.threshold(tb, lam, gam, s_ref, h_ref, tau_s, tau_h)
+            clear = (np.abs(s_ref - tau_s) > TOL_SIGNAL) & (np.abs(h_ref - tau_h) > TOL_SIGNAL)
+            np.testing.assert_allclose(out.cpu().numpy()[:, clear], ref64[:, clear], rtol=2e-7, atol=0)
+
+
 @pytest.mark.parametrize("n,q", [(1, 0.4), (5, 0.0), (1000, 0.45), (4099, 0.3), (1 << 20, 0.45), (3_000_001, 0.6)])
 def test_calibrate_exact_order_statistic(clada, ctx, n, q):
     r = np.random.default_rng(n)
