@@ -213,6 +213,23 @@ clada_status clada_signals_threshold(clada_ctx *ctx, const void *logits, int32_t
                                      int32_t L, float tau_s, float tau_H, float *surprisal,
                                      float *entropy, float *tau_final, void *hip_stream);
 
+/* clada_cognitive_signals for callers that cannot allocate device memory at all, not
+ * even a context's workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results bit for bit, but the
+ * kernel's scratch (block partials and arrival counters) is a fixed array inside the
+ * library's device code, about 256 KiB on every GPU the library runs on, held until the
+ * process ends; the call makes no hipMalloc / hipFree and uses no workspace, so `ctx`
+ * may be a context created with workspace_bytes == 0 (it only carries the error text).
+ * The device the stream and the tensors live on must be the current one (hipSetDevice).
+ * V above CLADA_STATIC_SIGNALS_MAX_V is rejected with CLADA_ERR_SHAPE.  The first call
+ * on a device looks the array's address up (make it outside a graph capture).  All
+ * calls on one GPU share the array: calls that overlap on one GPU (two streams, two
+ * threads) race on it -- issue them on one stream. */
+#define CLADA_STATIC_SIGNALS_MAX_V (1 << 20)
+clada_status clada_cognitive_signals_static(clada_ctx *ctx, const void *logits, int32_t logits_dtype,
+                                            int32_t B, int32_t V, const int32_t *token_ids,
+                                            float *surprisal, float *entropy, void *hip_stream);
+
 /* Thresholded sparse SwiGLU FFN for one layer at decode time (algorithm "CLADA
  * Inference", generation phase: regenerate the mask by thresholding, then the
  * sparse forward pass).  For each token b of x [B][d]:

@@ -69,6 +69,8 @@ def load_library() -> C.CDLL:
     lib.clada_threshold_calibrate.argtypes = [vp, vp, C.c_int64, f32, vp, vp]
     lib.clada_cognitive_signals.argtypes = [vp, vp, C.c_int, i32, i32, vp, vp, vp, vp]
     lib.clada_threshold.argtypes = [vp, vp, vp, vp, i32, vp, vp, i32, f32, f32, vp, vp]
+    lib.clada_cognitive_signals_static.argtypes = [vp, vp, C.c_int, i32, i32, vp, vp, vp, vp]
+    lib.clada_cognitive_signals_static.restype = C.c_int
     lib.clada_signals_threshold.argtypes = [vp, vp, C.c_int, i32, i32, vp, vp, vp, vp, i32, f32, f32, vp, vp, vp, vp]
     lib.clada_sparse_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp, vp, vp, vp, vp]
     lib.clada_dense_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp]
@@ -246,6 +248,22 @@ def cognitive_signals(ctx: Context, logits: torch.Tensor, token_ids: torch.Tenso
     h = torch.empty(B, dtype=torch.float32, device=logits.device)
     ctx.check(ctx._lib.clada_cognitive_signals(ctx._h, _ptr(logits), _dtype_code(logits), B, V,
                                                _ptr(token_ids), _ptr(s), _ptr(h), _stream(logits)))
+    return s, h
+
+
+def cognitive_signals_static(ctx: Context, logits: torch.Tensor, token_ids: torch.Tensor,
+                             out: tuple[torch.Tensor, torch.Tensor] | None = None):
+    """clada_cognitive_signals_static: scratch inside the library, nothing allocated by the call when `out`
+    = (surprisal, entropy) is given."""
+    B, V = logits.shape
+    assert logits.is_cuda and logits.is_contiguous()
+    assert token_ids.is_cuda and token_ids.dtype == torch.int32 and token_ids.numel() == B
+    if out is None:
+        out = (torch.empty(B, dtype=torch.float32, device=logits.device),
+               torch.empty(B, dtype=torch.float32, device=logits.device))
+    s, h = out
+    ctx.check(ctx._lib.clada_cognitive_signals_static(ctx._h, _ptr(logits), _dtype_code(logits), B, V,
+                                                      _ptr(token_ids), _ptr(s), _ptr(h), _stream(logits)))
     return s, h
 
 

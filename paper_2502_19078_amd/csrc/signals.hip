@@ -10,6 +10,8 @@
 // the result is bit-reproducible.
 #include <math.h>
 
+#include <mutex>
+
 #include "clada_internal.h"
 
 namespace {
@@ -304,5 +306,67 @@ extern "C" clada_status clada_threshold(clada_ctx *ctx, const float *tau_base, c
     hipLaunchKernelGGL(k_threshold, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, tau_base,
                        lambda, gamma, L, surprisal, entropy, B, tau_s, tau_H, tau_final);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
+    return CLADA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// clada_cognitive_signals for callers that cannot allocate (see clada.h).  The block partials and the
+// arrival counters, which the entry point above keeps in the context's workspace, live in this file-scope
+// device array; every GPU the library runs on holds its own copy until the process ends.
+//   bytes [0, 256)   : arrival counters, one int32 per row (self-resetting: the block that folds a row
+//                      stores 0 again, and the array starts zeroed when the code object is loaded)
+//   bytes [256, end) : partials [B][blocks][4] fp32
+constexpr int STATIC_SIG_BLOCKS = CLADA_STATIC_SIGNALS_MAX_V / SIG_CHUNK;
+constexpr size_t STATIC_SIG_BYTES = 256 + sizeof(float) * 4 * (size_t)CLADA_MAX_BATCH * STATIC_SIG_BLOCKS;
+static_assert(CLADA_STATIC_SIGNALS_MAX_V % SIG_CHUNK == 0, "whole blocks");
+static_assert(sizeof(int) * CLADA_MAX_BATCH <= 256, "counters fit their slot");
+static __device__ __align__(256) unsigned char scratch[STATIC_SIG_BYTES];
+
+// In host code `scratch` is only a handle for the runtime's symbol lookup, not a device address: the
+// address of each device's copy is asked for once, with that device current, and kept here.
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char *g_scratch_ptr[STATIC_MAX_DEVICES];
+
+static hipError_t static_scratch_of_current_device(unsigned char **out, int *device_out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    *device_out = dev;
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+extern "C" clada_status clada_cognitive_signals_static(clada_ctx *ctx, const void *logits, int32_t logits_dtype,
+                                                       int32_t B, int32_t V, const int32_t *token_ids,
+                                                       float *surprisal, float *entropy, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    clada_status cs = check_signals_args(ctx, logits, logits_dtype, B, V, token_ids, surprisal, entropy);
+    if (cs != CLADA_OK) return cs;
+    if (V > CLADA_STATIC_SIGNALS_MAX_V)
+        return clada_fail(ctx, CLADA_ERR_SHAPE, "V=%d exceeds %d, the most the static scratch array holds partials for",
+                          V, CLADA_STATIC_SIGNALS_MAX_V);
+    unsigned char *base = nullptr;
+    int dev = -1;
+    const hipError_t e = static_scratch_of_current_device(&base, &dev);
+    if (e != hipSuccess)
+        return clada_fail(ctx, CLADA_ERR_HIP, "address of the static scratch array on device %d: %s", dev,
+                          hipGetErrorString(e));
+    int *counters = reinterpret_cast<int *>(base);
+    float *part = reinterpret_cast<float *>(base + 256);
+    ThresholdTail th = {};
+    CLADA_CHECK_HIP(ctx, launch_signals(logits, logits_dtype, B, V, token_ids, part, counters, surprisal, entropy, th,
+                                        (hipStream_t)hip_stream));
     return CLADA_OK;
 }
