@@ -196,21 +196,25 @@ def main():
         return C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
 
     INF = float("inf")
+    lam_neg, gam_neg = -lam, -gam                     # the regression table's signs (reading R5)
 
-    def step_body(dense, ts, th):
+    def signals_and_thresholds(ts, th, lam_t, gam_t, sp):
+        # one launch: surprisal, entropy and the L thresholds of this step's token(s)
+        ctx.check(lib.clada_signals_threshold(h, z_cur.data_ptr(), binding.F32, B, V, tok_cur.data_ptr(),
+                                              tau_base.data_ptr(), lam_t.data_ptr(), gam_t.data_ptr(), L, ts, th,
+                                              sur.data_ptr(), ent.data_ptr(), tau_final.data_ptr(), sp))
+
+    def step_body(dense, ts, th, lam_t, gam_t, counts=None):
         sp = stream_ptr()
-        ctx.check(lib.clada_cognitive_signals(h, z_cur.data_ptr(), binding.F32, B, V, tok_cur.data_ptr(),
-                                              sur.data_ptr(), ent.data_ptr(), sp))
-        ctx.check(lib.clada_threshold(h, tau_base.data_ptr(), lam.data_ptr(), gam.data_ptr(), L, sur.data_ptr(),
-                                      ent.data_ptr(), B, ts, th, tau_final.data_ptr(), sp))
+        signals_and_thresholds(ts, th, lam_t, gam_t, sp)
         for l in range(L):
             if dense:
                 ctx.check(lib.clada_dense_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
                                                      y_out[l].data_ptr(), sp))
             else:
                 ctx.check(lib.clada_sparse_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
-                                                      tau_final[l].data_ptr(), y_out[l].data_ptr(),
-                                                      None, None, None, sp))
+                                                      tau_final[l].data_ptr(), y_out[l].data_ptr(), None,
+                                                      counts[l].data_ptr() if counts is not None else None, None, sp))
 
     def load_inputs(s):
         x_cur.copy_(x_all[s], non_blocking=True)
@@ -219,17 +223,17 @@ def main():
 
     side = torch.cuda.Stream()
 
-    def make_runner(dense, ts, th):
+    def make_runner(dense, ts, th, lam_t, gam_t):
         """One decode step as a replayable HIP graph (or an eager call sequence with --no-graph)."""
         if args.no_graph:
-            return lambda: step_body(dense, ts, th)
+            return lambda: step_body(dense, ts, th, lam_t, gam_t)
         load_inputs(0)
         torch.cuda.synchronize()
         with torch.cuda.stream(side):
-            step_body(dense, ts, th)                    # eager once: first calls set kernel attributes
+            step_body(dense, ts, th, lam_t, gam_t)      # eager once: first calls set kernel attributes
             side.synchronize()
             clada.graph_begin(ctx)                      # the library's own capture (clada_graph_*)
-            step_body(dense, ts, th)
+            step_body(dense, ts, th, lam_t, gam_t)
             g = clada.graph_end(ctx)
         torch.cuda.synchronize()
         return g.launch                                 # replays on the current stream; the bound method keeps g alive
@@ -246,36 +250,57 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / K
 
-    def measure_regime(ts, th):
-        """Step time, measured sparsity and per-call duration (HIP events on the launch stream)."""
-        ms = timed(make_runner(False, ts, th))
+    REPLAYS = 50
+
+    def replay_stats(run):
+        """10 warm-ups, then REPLAYS replays of the step, each bracketed by HIP events on the launch stream (the
+        inputs cycle through the run's steps and are refreshed outside the bracket): median and min in ms."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(REPLAYS)]
+        for i in range(10 + REPLAYS):
+            load_inputs(i % nsteps)
+            if i >= 10:
+                evs[i - 10][0].record()
+            run()
+            if i >= 10:
+                evs[i - 10][1].record()
+        torch.cuda.synchronize()
+        t = np.array([a.elapsed_time(b) for a, b in evs])
+        return float(np.median(t)), float(t.min())
+
+    def check_outputs(what):
+        """The timed steps must have produced valid output: a balanced call that gave up its bounded wait turns
+        every later y of the context into NaN."""
+        torch.cuda.synchronize()
+        if ctx.device_fault() or not bool(torch.isfinite(y_out.float()).all()):
+            print(f"bench.py: invalid output after {what} (device fault flag or non-finite y)", file=sys.stderr)
+            sys.exit(3)
+
+    def measure_regime(ts, th, lam_t=lam, gam_t=gam, detail=True):
+        """Step time (mean over K different-input replays by the host clock; median and min over REPLAYS replays
+        by HIP events), measured sparsity and, with detail, per-call and per-kernel durations."""
+        run = make_runner(False, ts, th, lam_t, gam_t)
+        ms = timed(run)
+        med, mn = replay_stats(run)
+        check_outputs("the timed sparse steps")
         cnt = torch.empty(K, L, 1 + B, dtype=torch.int32, device=dev)
         for i, s in enumerate(range(W, W + K)):                     # untimed pass: kept counts
             load_inputs(s)
-            sp = stream_ptr()
-            ctx.check(lib.clada_cognitive_signals(h, z_cur.data_ptr(), binding.F32, B, V, tok_cur.data_ptr(),
-                                                  sur.data_ptr(), ent.data_ptr(), sp))
-            ctx.check(lib.clada_threshold(h, tau_base.data_ptr(), lam.data_ptr(), gam.data_ptr(), L,
-                                          sur.data_ptr(), ent.data_ptr(), B, ts, th, tau_final.data_ptr(), sp))
-            for l in range(L):
-                ctx.check(lib.clada_sparse_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
-                                                      tau_final[l].data_ptr(), y_out[l].data_ptr(), None,
-                                                      cnt[i, l].data_ptr(), None, sp))
+            step_body(False, ts, th, lam_t, gam_t, counts=cnt[i])
         torch.cuda.synchronize()
         cnt_np = cnt.cpu().numpy()
         n_union = cnt_np[:, :, 0].astype(np.float64).mean()
-        res = {"ms": ms, "rho_union": 1.0 - n_union / F, "rho_token": 1.0 - cnt_np[:, :, 1:].mean() / F,
+        res = {"ms": ms, "ms_median": med, "ms_min": mn, "rho_union": 1.0 - n_union / F,
+               "rho_token": 1.0 - cnt_np[:, :, 1:].mean() / F,
                "bytes_layer": (F + (nmat - 1.0) * n_union) * d * es}
+        if not detail:
+            return res
         nprobe = min(K, 8)                                           # events around every per-layer call
         evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
                for _ in range(nprobe)]
         for i in range(nprobe):
             load_inputs(W + i)
             sp = stream_ptr()
-            ctx.check(lib.clada_cognitive_signals(h, z_cur.data_ptr(), binding.F32, B, V, tok_cur.data_ptr(),
-                                                  sur.data_ptr(), ent.data_ptr(), sp))
-            ctx.check(lib.clada_threshold(h, tau_base.data_ptr(), lam.data_ptr(), gam.data_ptr(), L,
-                                          sur.data_ptr(), ent.data_ptr(), B, ts, th, tau_final.data_ptr(), sp))
+            signals_and_thresholds(ts, th, lam_t, gam_t, sp)
             for l in range(L):
                 evs[i][l][0].record()
                 ctx.check(lib.clada_sparse_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
@@ -291,10 +316,7 @@ def main():
         for i in range(nprobe):
             load_inputs(W + i)
             sp = stream_ptr()
-            ctx.check(lib.clada_cognitive_signals(h, z_cur.data_ptr(), binding.F32, B, V, tok_cur.data_ptr(),
-                                                  sur.data_ptr(), ent.data_ptr(), sp))
-            ctx.check(lib.clada_threshold(h, tau_base.data_ptr(), lam.data_ptr(), gam.data_ptr(), L,
-                                          sur.data_ptr(), ent.data_ptr(), B, ts, th, tau_final.data_ptr(), sp))
+            signals_and_thresholds(ts, th, lam_t, gam_t, sp)
             for l in range(L):
                 ctx.check(lib.clada_sparse_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
                                                       tau_final[l].data_ptr(), y_out[l].data_ptr(),
@@ -310,7 +332,12 @@ def main():
 
     nat = measure_regime(tau_s, tau_H)            # the method as defined: thresholds follow the signals
     off = measure_regime(INF, INF)                # indicators off: tau_final = tau_base (target sparsity)
-    ms_dense = timed(make_runner(True, tau_s, tau_H))
+    on = measure_regime(-INF, -INF, detail=False)                       # both indicators always on: factor 1.92
+    neg = measure_regime(tau_s, tau_H, lam_neg, gam_neg, detail=False)  # natural, coefficients -0.80 / -0.12
+    run_dense = make_runner(True, tau_s, tau_H, lam, gam)
+    ms_dense = timed(run_dense)
+    dense_med, dense_min = replay_stats(run_dense)
+    check_outputs("the dense-twin steps")
     ms_sparse, rho_union, rho_token = nat["ms"], nat["rho_union"], nat["rho_token"]
     bytes_layer, call_us = nat["bytes_layer"], nat["call_us"]
     bytes_probe, main_us = nat["bytes_probe"], nat["main_us"]
@@ -356,8 +383,16 @@ def main():
         "speedup_vs_dense": round(ms_dense / ms_sparse, 4),
         "ideal_speedup": round(ideal(rho_union), 4),
         "regime": "natural: tau_s, tau_H = medians of the run's own surprisal/entropy streams",
+        # ms_per_step is the host-clock mean over K steps on K different inputs; these are HIP-event times of
+        # single graph replays (inputs refreshed outside the bracket)
+        "replays": {"n": REPLAYS, "ms_median": round(nat["ms_median"], 4), "ms_min": round(nat["ms_min"], 4),
+                    "dense_ms_median": round(dense_med, 4), "dense_ms_min": round(dense_min, 4)},
+        "value_at_target_sparsity": round(B * 1e3 / off["ms"], 2),   # indicators off: rho = the configuration's target
+        "device_fault": False,
         "regime_indicators_off": {
             "ms_per_step": round(off["ms"], 4), "tokens_per_s": round(B * 1e3 / off["ms"], 2),
+            "ms_median": round(off["ms_median"], 4), "ms_min": round(off["ms_min"], 4),
+            "step_frac_of_hbm_peak": round(off["bytes_layer"] * L / (off["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "sparsity_union": round(float(off["rho_union"]), 4),
             "speedup_vs_dense": round(ms_dense / off["ms"], 4),
             "ideal_speedup": round(ideal(off["rho_union"]), 4),
@@ -368,6 +403,8 @@ def main():
             "kernel_frac": round(off["bytes_probe"] / (off["main_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
             "call_gbs": round(off["bytes_probe"] / (off["call_us"] * 1e-6) / 1e9, 1),
             "call_frac": round(off["bytes_probe"] / (off["call_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+        "regime_indicators_on": _light(on, ms_dense, ideal, B, L),
+        "regime_negative_coefficients": dict(_light(neg, ms_dense, ideal, B, L), **{"lambda": -0.80, "gamma": -0.12}),
         "step_gbs_on_bytes_touched": round(bytes_layer * L / (ms_sparse * 1e-3) / 1e9, 1),
         "dense_step_gbs": round(bytes_dense * L / (ms_dense * 1e-3) / 1e9, 1),
         "stream_read_ceiling_gbs": round(ceil_gbs, 1),   # whole-row streaming of one 90 MB matrix per launch, launch gaps included
@@ -380,7 +417,7 @@ def main():
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "bytes_per_launch": round(bytes_probe), "us_per_launch": round(main_us, 2),
-                     "traffic": _traffic() if args.config == "c2" else None,
+                     **_traffic(args.config, B, bytes_probe),
                      # the whole C-ABI call = that kernel + the fixed-order final reduction (k_ffn_finalize)
                      # + the launch gap between them, timed with HIP events around the call
                      "call": {"us": round(call_us, 2), "finalize_us": round(nat["finalize_us"], 2),
@@ -487,14 +524,31 @@ def prefill_probe(cfg, args, clada, synth, torch, dev):
     print(json.dumps(out))
 
 
-def _traffic():
-    """HBM bytes per launch from the committed rocprofv3 counter summary, if present."""
-    p = os.path.join(ROOT, "profiles", "traffic_sparse_ffn_decode_c2.json")
+def _light(r, ms_dense, ideal, B, L):
+    """JSON entry of a regime measured without the per-call probes."""
+    return {"ms_per_step": round(r["ms"], 4), "ms_median": round(r["ms_median"], 4), "ms_min": round(r["ms_min"], 4),
+            "tokens_per_s": round(B * 1e3 / r["ms"], 2), "sparsity_union": round(float(r["rho_union"]), 4),
+            "speedup_vs_dense": round(ms_dense / r["ms"], 4), "ideal_speedup": round(ideal(r["rho_union"]), 4),
+            "step_frac_of_hbm_peak": round(r["bytes_layer"] * L / (r["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
+def _traffic(config, B, bytes_per_launch):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary: the entry
+    whose algorithmic bytes are within 3 % of this run's (counters cannot be read inside the run), else null."""
+    p = os.path.join(ROOT, "profiles", f"traffic_sparse_ffn_decode_{config}.json")
     try:
         with open(p) as f:
-            return json.load(f).get("hbm_bytes_per_launch")
+            entries = json.load(f)["entries"]
     except Exception:
-        return None
+        return {"traffic": None, "traffic_note": "no committed counter summary for this workload"}
+    entries = [e for e in entries if e.get("B", 1) == B]
+    if entries:
+        e = min(entries, key=lambda e: abs(e["algorithmic_bytes_per_launch"] - bytes_per_launch))
+        if abs(e["algorithmic_bytes_per_launch"] - bytes_per_launch) <= 0.03 * bytes_per_launch:
+            return {"traffic": e["hbm_bytes_per_launch"],
+                    "traffic_source": f"profiles/{os.path.basename(p)}: rocprofv3 FETCH_SIZE + WRITE_SIZE of a committed "
+                                      f"run at sparsity {e['rho']:.3f} ({e['algorithmic_bytes_per_launch']} algorithmic bytes)"}
+    return {"traffic": None, "traffic_note": "the committed counter runs are at other sparsities than this run"}
 
 
 if __name__ == "__main__":
