@@ -284,6 +284,32 @@ clada_status clada_mask_pack(clada_ctx *ctx, const int32_t *active_idx, const in
 clada_status clada_mask_unpack(clada_ctx *ctx, const uint32_t *mask_bits, int32_t d_ff,
                                int32_t *active_idx, int32_t *n_active, void *hip_stream);
 
+/* Sparse storage of a mask (the same two passages): the ascending positions j_0 < j_1 < ...
+ * at which mask_bits differs from ref_bits, a reference mask of the same layer such as
+ * its prefix-static mask or the previous token's mask (ref_bits NULL = the all-zero mask:
+ * the positions are the kept neurons), written as the gaps g_i = j_i - j_{i-1} - 1
+ * (j_{-1} = -1), each gap a little-endian base-128 number: 7 value bits per byte, low
+ * group first, high bit set on every byte but the last.  About one byte per neuron that
+ * changed, against d_ff/8 bytes for the bit mask (which no code beats for an unrelated
+ * mask at ~50 % sparsity).  Masks are ceil(d_ff/32) words as above; bits past d_ff are
+ * ignored on input and zero on output.
+ *   clada_mask_sparse_encode: stream [stream_capacity] bytes; n_out [2] = {bytes written,
+ *     positions coded}; if the stream does not fit the capacity, n_out[0] = -1 and the
+ *     stream's contents are unspecified (n_out[1] is still the number of positions).
+ *     clada_mask_sparse_max_bytes(d_ff) is a capacity that always fits.
+ *   clada_mask_sparse_decode: mask_bits = ref_bits with the coded positions flipped
+ *     (mask_bits may be the same array as ref_bits).  n_bytes [1] is read on the device and
+ *     clamped to [0, stream_capacity]; positions >= d_ff and bytes after the last complete
+ *     number are ignored, so a damaged stream cannot write out of bounds.
+ * Both exact; all arrays device. */
+size_t clada_mask_sparse_max_bytes(int32_t d_ff);
+clada_status clada_mask_sparse_encode(clada_ctx *ctx, const uint32_t *mask_bits, const uint32_t *ref_bits,
+                                      int32_t d_ff, uint8_t *stream, int32_t stream_capacity,
+                                      int32_t *n_out, void *hip_stream);
+clada_status clada_mask_sparse_decode(clada_ctx *ctx, const uint8_t *stream, const int32_t *n_bytes,
+                                      int32_t stream_capacity, const uint32_t *ref_bits, int32_t d_ff,
+                                      uint32_t *mask_bits, void *hip_stream);
+
 /* Sparse SwiGLU FFN over a given neuron list (the sparse forward pass of the
  * algorithm "CLADA Inference" with a mask that does not depend on the token):
  *   y_b = sum_{j in active_idx[0..n_active[0])} SiLU(W_gate[j,:] . x_b) (W_up[j,:] . x_b) W_down[j,:]

@@ -83,6 +83,12 @@ def load_library() -> C.CDLL:
     lib.clada_static_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp, vp, vp]
     lib.clada_mask_pack.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.clada_mask_unpack.argtypes = [vp, vp, i32, vp, vp, vp]
+    lib.clada_mask_sparse_max_bytes.argtypes = [i32]
+    lib.clada_mask_sparse_max_bytes.restype = C.c_size_t
+    lib.clada_mask_sparse_encode.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
+    lib.clada_mask_sparse_encode.restype = C.c_int
+    lib.clada_mask_sparse_decode.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
+    lib.clada_mask_sparse_decode.restype = C.c_int
     lib.clada_device_fault.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.clada_graph_begin.argtypes = [vp, vp]
     lib.clada_graph_end.argtypes = [vp, vp, C.POINTER(vp)]
@@ -367,6 +373,34 @@ def mask_unpack(ctx: Context, mask_bits: torch.Tensor, d_ff: int):
     n = torch.empty(1, dtype=torch.int32, device=mask_bits.device)
     ctx.check(ctx._lib.clada_mask_unpack(ctx._h, _ptr(mask_bits), int(d_ff), _ptr(idx), _ptr(n), _stream(mask_bits)))
     return idx, n
+
+
+def mask_sparse_encode(ctx: Context, mask_bits: torch.Tensor, ref_bits: torch.Tensor | None, d_ff: int,
+                       capacity: int | None = None):
+    """Bit mask (against a reference mask or None) -> (stream uint8 [capacity], n int32 [2] = bytes or -1, positions)."""
+    words = (d_ff + 31) // 32
+    assert mask_bits.is_cuda and mask_bits.dtype == torch.int32 and mask_bits.numel() >= words and mask_bits.is_contiguous()
+    assert ref_bits is None or (ref_bits.is_cuda and ref_bits.dtype == torch.int32 and ref_bits.numel() >= words
+                                and ref_bits.is_contiguous())
+    if capacity is None:
+        capacity = int(ctx._lib.clada_mask_sparse_max_bytes(int(d_ff)))
+    stream = torch.empty(max(capacity, 1), dtype=torch.uint8, device=mask_bits.device)
+    n = torch.empty(2, dtype=torch.int32, device=mask_bits.device)
+    ctx.check(ctx._lib.clada_mask_sparse_encode(ctx._h, _ptr(mask_bits), _ptr(ref_bits), int(d_ff), _ptr(stream),
+                                                int(capacity), _ptr(n), _stream(mask_bits)))
+    return stream, n
+
+
+def mask_sparse_decode(ctx: Context, stream: torch.Tensor, n_bytes: torch.Tensor, ref_bits: torch.Tensor | None,
+                       d_ff: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Stream (+ the reference it was coded against) -> bit mask [ceil(d_ff/32)] int32."""
+    assert stream.is_cuda and stream.dtype == torch.uint8 and stream.is_contiguous()
+    assert n_bytes.is_cuda and n_bytes.dtype == torch.int32 and n_bytes.numel() >= 1
+    if out is None:
+        out = torch.empty((d_ff + 31) // 32, dtype=torch.int32, device=stream.device)
+    ctx.check(ctx._lib.clada_mask_sparse_decode(ctx._h, _ptr(stream), _ptr(n_bytes), int(stream.numel()), _ptr(ref_bits),
+                                                int(d_ff), _ptr(out), _stream(stream)))
+    return out
 
 
 def static_ffn_decode(ctx: Context, layer: Layer, x: torch.Tensor, active_idx: torch.Tensor,

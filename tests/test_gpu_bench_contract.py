@@ -29,3 +29,11 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     cpu = j["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["unit"] == "tokens/s"
     assert j["value"] == pytest.approx(1e3 / j["ms_per_step"], rel=1e-3)
+    # regimes of the measurement plan, replay statistics, validity of the timed outputs
+    for k in ("regime_indicators_off", "regime_indicators_on", "regime_negative_coefficients"):
+        assert j[k]["ms_per_step"] > 0 and 0.0 <= j[k]["sparsity_union"] <= 1.0 and j[k]["ms_min"] <= j[k]["ms_median"]
+    assert j["regime_indicators_on"]["sparsity_union"] >= j["sparsity_union"] >= j["regime_negative_coefficients"]["sparsity_union"]
+    assert j["replays"]["n"] >= 50 and j["replays"]["ms_min"] <= j["replays"]["ms_median"]
+    assert j["value_at_target_sparsity"] == pytest.approx(1e3 / j["regime_indicators_off"]["ms_per_step"], rel=1e-3)
+    assert j["device_fault"] is False
+    assert "traffic" in roof
