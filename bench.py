@@ -334,6 +334,67 @@ def main():
     off = measure_regime(INF, INF)                # indicators off: tau_final = tau_base (target sparsity)
     on = measure_regime(-INF, -INF, detail=False)                       # both indicators always on: factor 1.92
     neg = measure_regime(tau_s, tau_H, lam_neg, gam_neg, detail=False)  # natural, coefficients -0.80 / -0.12
+    # ---- the whole-stack entry point (B = 1): the same step as signals+thresholds and ONE persistent launch
+    stack = None
+    if B == 1:
+        arr = binding.layer_array(layers)
+        x_flat, y_flat, tau_flat = x_cur.view(L, d), y_out.view(L, d), tau_final.view(L)
+
+        def stack_body(dense, ts, th):
+            sp = stream_ptr()
+            signals_and_thresholds(ts, th, lam, gam, sp)
+            if dense:
+                ctx.check(lib.clada_dense_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), y_flat.data_ptr(), sp))
+            else:
+                ctx.check(lib.clada_sparse_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), tau_flat.data_ptr(),
+                                                            y_flat.data_ptr(), None, sp))
+
+        def make_stack_runner(dense, ts, th):
+            if args.no_graph:
+                return lambda: stack_body(dense, ts, th)
+            load_inputs(0)
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                stack_body(dense, ts, th)
+                side.synchronize()
+                clada.graph_begin(ctx)
+                stack_body(dense, ts, th)
+                g = clada.graph_end(ctx)
+            torch.cuda.synchronize()
+            return g.launch
+
+        stack = {}
+        ctx.set_option("decode.stack", 1)                   # the persistent kernel; off by default (slower, see "what")
+        for name, (ts, th), reg in (("natural", (tau_s, tau_H), nat), ("indicators_off", (INF, INF), off)):
+            load_inputs(W)
+            step_body(False, ts, th, lam, gam)              # per-layer calls on the same inputs: the reference bits
+            torch.cuda.synchronize()
+            y_want = y_out.clone()
+            run = make_stack_runner(False, ts, th)
+            load_inputs(W)
+            run()
+            torch.cuda.synchronize()
+            same = bool(torch.equal(y_out, y_want))
+            ms = timed(run)
+            med, mn = replay_stats(run)
+            check_outputs("the whole-stack steps")
+            stack[name] = {"ms_per_step": round(ms, 4), "ms_median": round(med, 4), "ms_min": round(mn, 4),
+                           "tokens_per_s": round(1e3 / ms, 2), "sparsity_union": round(float(reg["rho_union"]), 4),
+                           "step_gbs_on_bytes_touched": round(reg["bytes_layer"] * L / (ms * 1e-3) / 1e9, 1),
+                           "step_frac_of_hbm_peak": round(reg["bytes_layer"] * L / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                           "bit_identical_to_per_layer_calls": same}
+        run = make_stack_runner(True, tau_s, tau_H)
+        ms_dense_stack = timed(run)
+        check_outputs("the dense whole-stack steps")
+        for name, reg in (("natural", nat), ("indicators_off", off)):
+            stack[name]["speedup_vs_dense_stack"] = round(ms_dense_stack / stack[name]["ms_per_step"], 4)
+            stack[name]["ideal_speedup"] = round(nmat / (nmat - (nmat - 1.0) * reg["rho_union"]), 4)
+        stack["dense_ms_per_step"] = round(ms_dense_stack, 4)
+        ctx.set_option("decode.stack", 0)
+        stack["what"] = ("clada_sparse_ffn_stack_decode with option decode.stack=1: one persistent launch for the L independent "
+                         "layers of a step (no kernel boundary, no separate reduction launch per layer).  Measured for the "
+                         "record: it is slower than the per-layer launches for sparse stacks, which is why it is off by "
+                         "default; value and ms_per_step above are the per-layer calls")
     run_dense = make_runner(True, tau_s, tau_H, lam, gam)
     ms_dense = timed(run_dense)
     dense_med, dense_min = replay_stats(run_dense)
@@ -405,6 +466,7 @@ def main():
             "call_frac": round(off["bytes_probe"] / (off["call_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "regime_indicators_on": _light(on, ms_dense, ideal, B, L),
         "regime_negative_coefficients": dict(_light(neg, ms_dense, ideal, B, L), **{"lambda": -0.80, "gamma": -0.12}),
+        "stack_entry": stack,
         "step_gbs_on_bytes_touched": round(bytes_layer * L / (ms_sparse * 1e-3) / 1e9, 1),
         "dense_step_gbs": round(bytes_dense * L / (ms_dense * 1e-3) / 1e9, 1),
         "stream_read_ceiling_gbs": round(ceil_gbs, 1),   # whole-row streaming of one 90 MB matrix per launch, launch gaps included

@@ -69,6 +69,7 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->opt_decode_b1 = 1;
     ctx->opt_decode_batched = 1;
     ctx->opt_decode_own_first = 0;
+    ctx->opt_decode_stack = 0;
     ctx->opt_decode_spin_limit = 1 << 12;
     ctx->n_occ = 0;
     ctx->opt_prefix_tile = 0;
@@ -139,6 +140,11 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
     if (!strcmp(name, "decode.batched")) {
         if (value < 0 || value > 1) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.batched=%d outside [0,1]", value);
         ctx->opt_decode_batched = value;
+        return CLADA_OK;
+    }
+    if (!strcmp(name, "decode.stack")) {
+        if (value < 0 || value > 1) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.stack=%d outside [0,1]", value);
+        ctx->opt_decode_stack = value;
         return CLADA_OK;
     }
     if (!strcmp(name, "decode.own_first")) {

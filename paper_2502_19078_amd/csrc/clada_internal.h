@@ -18,6 +18,7 @@ struct clada_ctx {
     int opt_decode_b1;           // batch-1 split-d kernel: 0 off (generic kernels), 1 balancing where it pays, 2 never, 3 always
     int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
     int opt_decode_batched;      // 1: MFMA path for 2 <= B <= 16 (bf16), 0: generic kernels
+    int opt_decode_stack;        // whole-stack calls: 0 = L per-layer launches inside the call, 1 = one persistent kernel
     int opt_decode_spin_limit;   // polls a balanced batch-1 kernel makes before it gives up (see clada.h)
     int opt_prefix_tile;         // gate/up prefill GEMM: 0 choose by T, 1 = 128-token tiles, 2 = 256-token tiles
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)
@@ -36,12 +37,15 @@ struct clada_ctx {
 
 // The first bytes of the workspace hold self-resetting arrival counters (zeroed
 // once at clada_create); the scratch area proper starts after them.
-#define CLADA_WS_HEADER (160 * 1024)
+#define CLADA_WS_HEADER (416 * 1024)
 enum { CTR_SIGNALS = 0, CTR_DECODE = 64, CTR_PREFIX = 128, CTR_CALIB = 192 };  // int32 slots
-// Control words of the cooperative decode kernel inside the header (byte offsets).
+// Control words of the cooperative decode kernels inside the header (byte offsets).
 #define COOP_MAX_WGS 256
-enum { COOP_EPOCH = 1024, COOP_FAULT = 1088, COOP_REC = 4096,
-       COOP_APUB = 8192 /* 256*64 tagged words of 8 bytes = 128 KiB */ };
+enum { COOP_EPOCH = 1024, COOP_FAULT = 1088, STACK_EPOCH = 1152,
+       COOP_REC = 4096 /* 256 records of 8 bytes */, STACK_REC = 6144 /* 3 x 256 records */,
+       STACK_KCNT = 12288 /* 3 x 256 int32 */,
+       COOP_APUB = 16384 /* 256*64 tagged words of 8 bytes = 128 KiB */,
+       STACK_APUB = 16384 + 131072 /* 2 x 128 KiB, ends at 400 KiB */ };
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -25,6 +25,15 @@
 
 namespace {
 
+// The partial-output region at the start of the decode scratch: [P][B][d] fp32 for up to CLADA_MAX_DECODE_WGS
+// workgroups, and at least three buffers of [COOP_MAX_WGS][d] for the whole-stack kernel (B = 1).
+size_t ws_partial_bytes(int B, int d)
+{
+    size_t rows = (size_t)CLADA_MAX_DECODE_WGS * B;
+    if (rows < 3 * (size_t)COOP_MAX_WGS) rows = 3 * (size_t)COOP_MAX_WGS;
+    return align_up(sizeof(float) * rows * d, 256);
+}
+
 struct DecodeParams {
     const char *wg, *wu, *wd;   // [F][d] neuron-major
     const char *x;              // [B][d]
@@ -470,6 +479,225 @@ __device__ __forceinline__ int wave_excl_scan(int v, int lane, int *total)
     return inc - v;
 }
 
+// ---- whole-stack variant: one persistent launch runs the L layers of a decode step (the future-work item
+// "whole-stack persistence" next to mask compression).  Layers are independent problems (layer l has its own
+// input row), so a workgroup that has finished its share of layer l goes straight on to the gate rows of
+// layer l+1, and the fixed-order sum of the P partial outputs of layer l is done by all workgroups (each
+// its own columns) in the middle of layer l+1, when every partial has long arrived: no kernel boundary and
+// no separate reduction launch per layer.
+#define CLADA_STACK_MAX_LAYERS 48
+struct StackParams {
+    const char *wg[CLADA_STACK_MAX_LAYERS], *wu[CLADA_STACK_MAX_LAYERS], *wd[CLADA_STACK_MAX_LAYERS];
+    const float *b_in[CLADA_STACK_MAX_LAYERS], *b_out[CLADA_STACK_MAX_LAYERS];     // RELU only
+    const char *x;              // [L][d]
+    char *y;                    // [L][d]
+    const float *tau;           // [L] (unused when DENSE)
+    float *partial;             // [3][P][d], slot = layer number % 3
+    unsigned long long *rec;    // [3][P] mask records / arrival records, slot = layer number % 3
+    unsigned long long *apub;   // [2][P][64]
+    unsigned int *epoch;        // layer numbers used up by the stack kernels of this context (advanced at kernel end)
+    int *kcnt;                  // [3][P] kept neurons per workgroup
+    int *n_active;              // [L][2] or nullptr
+    int *fault;
+    int max_spins, d, F, K0, gelu, L;
+};
+
+// The kernel reads these parameters through the kernel-argument segment's own address (constant address
+// space, scalar loads): indexing the per-layer tables of a by-value copy with the running layer number made
+// the compiler keep the whole copy in vector registers (+110 registers in every phase, spills in the hot loop).
+typedef const __attribute__((address_space(4))) StackParams *StackArgs;
+
+// Partial outputs cross workgroups inside one kernel: written through to memory (agent scope, the sc1 bit),
+// read past the caches.  The language offers relaxed atomics of at most 64 bits for that, and four 8-byte
+// write-through stores per 32 bytes turned every line of the partial into four partial-line writes; a whole
+// 16-byte group goes out as one buffer store with the sc1 cache policy (16 in the builtin's last argument).
+// (Written as inline assembly the same store lost data: the compiler cannot see that an asm statement is a
+// store, so it did not keep the next write to the data registers away from it.)
+__device__ __forceinline__ void store_through16(__amdgpu_buffer_rsrc_t row, int byte_off, float a, float b, float c, float d)
+{
+    const u32x4 v = {__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
+    __builtin_amdgcn_raw_buffer_store_b128(v, row, byte_off, 0, 16);
+}
+__device__ __forceinline__ float4 load_through(const float *src)
+{
+    const unsigned long long lo = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(src), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long hi = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(src) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float4(__uint_as_float((unsigned int)lo), __uint_as_float((unsigned int)(lo >> 32)),
+                       __uint_as_float((unsigned int)hi), __uint_as_float((unsigned int)(hi >> 32)));
+}
+
+// y of stack layer l from the P partials, this workgroup's columns only, in the summation order of
+// k_ffn_finalize (32 slices of P/32 partials each, then a fixed tree), so the result has the same bits as the
+// per-layer call's.  A workgroup announces "my partial of layer l is in memory" with its record of layer l+1
+// (published at the end of that layer's gate phase, when nothing of the workgroup is in flight any more), so
+// once a workgroup holds all P records of layer l+1 it may read every partial of layer l.  The balanced
+// kernel holds them anyway after its mask exchange; otherwise wave 0 reads them during the gate phase of
+// layer l+2.  The reduction itself rides along with that gate phase in steps placed between the row loads,
+// so that no trip through memory stops the stream of weight rows: (1) [wave 0, if not known yet] ask for the
+// records, check them, tell the other waves through LDS, (2) ask for this thread's eight partial values,
+// (3) add them, slice sum to LDS, and after the gate phase's barrier (4) the tree, the rounding and the
+// store.  Partial buffers, kept counts and records rotate over three slots (layer number % 3): the record of
+// the empty layer that ends a launch must not land on records a slower workgroup is still reading.
+struct StackReduce {
+    StackArgs pp;                   // the launch's parameters, read where needed (scalar loads)
+    float4 (*s_sum)[16];
+    volatile int *s_arrived;        // LDS: layer index (of this launch) whose preceding records are all in
+    int P, d, G, cg, sl, col, slot, layer, wave;
+    bool active;
+    const unsigned long long *rec;  // records that confirm the partials wanted
+    unsigned long long tag;
+    unsigned long long m[4];
+    bool asked;
+    float4 v[8];
+    int state;          // 0 waiting for the records, 2 partials asked, 3 slice sum in LDS (or nothing to do)
+
+    __device__ __forceinline__ StackReduce(StackArgs pp_, float4 (*s)[16], volatile int *arr)
+        : pp(pp_), s_sum(s), s_arrived(arr), asked(false), state(3) {}
+
+    // reduction of the layer with number g, to be done inside launch-local layer `layer_now` (number g + 2)
+    __device__ __forceinline__ void begin(unsigned int g, int layer_now, int tid, int wave_)
+    {
+        P = gridDim.x; d = pp->d;
+        const int n4 = d / 4;
+        G = (n4 + P - 1) / P;                               // float4 columns per workgroup (<= 16)
+        cg = tid % G; sl = tid / G;
+        col = ((int)blockIdx.x * G + cg) * 4;
+        active = sl < 32 && col < d;
+        slot = (int)(g % 3u);
+        layer = layer_now; wave = wave_;
+        rec = pp->rec + ((g + 1u) % 3u) * P;
+        tag = (unsigned long long)((g + 2u) & 0xffu) << 56;     // tag of layer g + 1 = (its number + 1) & 255
+        asked = false;
+        // waves without a column of the reduction have nothing to load; wave 0 may still have to read records
+        state = (wave * 64 < 32 * G || wave == 0) ? 0 : 3;
+    }
+    __device__ __forceinline__ void ask_records(int lane)
+    {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = 4 * lane + u;
+            m[u] = q < P ? __hip_atomic_load(rec + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : tag;
+        }
+        asked = true;
+    }
+    __device__ __forceinline__ bool records_ok() const
+    {
+        bool ok = true;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ok = ok && ((m[u] & (0xffull << 56)) == tag);
+        return __ballot(ok) == ~0ull;
+    }
+    __device__ __forceinline__ void ask_partials()
+    {
+        const float *base = pp->partial + (size_t)slot * P * d + col;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int q = sl + 32 * u;
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (active && q < P) v[u] = load_through(base + (size_t)q * d);
+        }
+        state = 2;
+    }
+    __device__ __forceinline__ void add_partials()
+    {
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+        if (sl < 32) s_sum[sl][cg] = s;
+        state = 3;
+    }
+    // one step per call, never waits (the caller places the calls between its own loads)
+    __device__ __forceinline__ void step(int lane)
+    {
+        if (state == 0) {
+            if (*s_arrived == layer) {
+                ask_partials();
+            } else if (wave == 0) {
+                if (asked && records_ok()) {
+                    if (lane == 0) *s_arrived = layer;
+                    ask_partials();
+                } else {
+                    ask_records(lane);
+                }
+            }
+        } else if (state == 2) {
+            add_partials();
+        }
+    }
+    // whatever is left, waiting (bounded) where it must
+    __device__ __forceinline__ void finish(int lane)
+    {
+        if (state == 0) {
+            if (*s_arrived != layer) {
+                if (wave == 0) {
+                    bool ok = asked && records_ok();
+                    for (int spins = 0; spins <= pp->max_spins && !ok; ++spins) {
+                        ask_records(lane);
+                        ok = records_ok();
+                        if (!ok) __builtin_amdgcn_s_sleep(8);
+                    }
+                    if (lane == 0) {
+                        if (!ok) __hip_atomic_store(pp->fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        *s_arrived = layer;
+                    }
+                } else {
+                    // wave 0 sets the flag in every case, at the latest at the end of its own gate rows
+                    for (int spins = 0; spins < (1 << 24) && *s_arrived != layer; ++spins) __builtin_amdgcn_s_sleep(2);
+                    if (*s_arrived != layer && lane == 0) __hip_atomic_store(pp->fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            ask_partials();
+        }
+        if (state == 2) add_partials();
+    }
+    // after a workgroup barrier that follows finish(): tree over the 32 slices, rounding, store of y[l]
+    template <int ES, bool RELU>
+    __device__ __forceinline__ void tree_and_store(int l, int tid)
+    {
+        const int lane = tid & 63;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (sl < 32) s = s_sum[sl][cg];
+#pragma unroll
+        for (int h = 16; h >= 1; h >>= 1) {
+            if (sl < h) {
+                const float4 w = s_sum[sl + h][cg];
+                s.x += w.x; s.y += w.y; s.z += w.z; s.w += w.w;
+                s_sum[sl][cg] = s;
+            }
+            __syncthreads();
+        }
+        if (sl == 0 && col < d) {
+            if (__hip_atomic_load(pp->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) s.x = s.y = s.z = s.w = __int_as_float(0x7fc00000);
+            if (RELU && pp->b_out[l]) {
+                const float4 bv = *reinterpret_cast<const float4 *>(pp->b_out[l] + col);
+                s.x += bv.x; s.y += bv.y; s.z += bv.z; s.w += bv.w;
+            }
+            char *y = pp->y + (size_t)l * d * ES;
+            if (ES == 4) {
+                *reinterpret_cast<float4 *>(y + (size_t)col * 4) = s;
+            } else {
+                uint2 o;
+                o.x = f32_to_bf16_bits(s.x) | (f32_to_bf16_bits(s.y) << 16);
+                o.y = f32_to_bf16_bits(s.z) | (f32_to_bf16_bits(s.w) << 16);
+                *reinterpret_cast<uint2 *>(y + (size_t)col * 2) = o;
+            }
+        }
+        // kept neurons of the layer: the workgroups' counts, summed by one wave of workgroup 0
+        if (pp->n_active && blockIdx.x == 0 && tid >= 64 && tid < 128) {
+            int c = 0;
+            for (int q = lane; q < P; q += 64) c += __hip_atomic_load(pp->kcnt + slot * P + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) c += __shfl_xor(c, o);
+            if (lane == 0) { pp->n_active[2 * l] = c; pp->n_active[2 * l + 1] = c; }
+        }
+        state = 3;
+    }
+};
+
+struct NoStackReduce {       // the per-layer kernel has nothing to ride along
+    template <typename P, typename S, typename A> __device__ __forceinline__ NoStackReduce(const P &, S, A) {}
+};
+
 // BAL = cross-workgroup load balancing (sparse calls): a workgroup's kept count is binomial, and
 // measured per-workgroup timelines show the busiest workgroup finishing ~5 us after the average
 // one.  After the gate phase every workgroup publishes its keep mask (<= 56 neurons -> one 64-bit
@@ -483,9 +711,11 @@ __device__ __forceinline__ int wave_excl_scan(int v, int lane, int *total)
 // 7 us slower than the separate k_ffn_finalize launch: each agent-scope round trip costs ~3 us
 // here.  For the same reason balancing only pays when chunk 0 is long enough to hide two hops.)
 // RELU: the non-gated family -- no W_up rows at all, h is the activation itself.
-template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL, bool RELU = false>
+// STACK: the whole-stack variant described above (parameters StackParams; the per-layer state below is
+// rebuilt from them at the top of every layer).
+template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL, bool RELU = false, bool STACK = false>
 __global__ void __launch_bounds__(NW * 64)
-k_ffn_decode_b1(const B1Params p)
+k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
 {
     constexpr int VEC = 16 / ES;
     constexpr int ROWB = NCH * 1024;
@@ -501,14 +731,57 @@ k_ffn_decode_b1(const B1Params p)
     __shared__ int s_l2row[64];                             // balanced share: weight row ...
     __shared__ int s_l2a[64];                               // ... and index of its published activation
     __shared__ int s_n2;
+    __shared__ float4 s_sum[STACK ? 32 : 1][16];            // STACK: slices of the final reduction
+    __shared__ int s_arrived;                               // STACK: see StackReduce
+    __shared__ __align__(16) unsigned char s_x[STACK ? NCH * 1024 : 16];    // STACK: the layer's input row
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int blk = blockIdx.x, P = gridDim.x;
-    const int F = p.F;
+    StackArgs ka = nullptr;
+    int F;
+    if constexpr (STACK) {
+        ka = (StackArgs)__builtin_amdgcn_kernarg_segment_ptr();    // = pp, the only argument
+        F = ka->F;
+    } else {
+        F = pp.F;
+    }
     const int ni = blk < F ? (F - blk + P - 1) / P : 0;     // <= 64 (<= 56 when BAL)
 
     const int loff = lane * 16;
+    unsigned int g0 = 0u;                                   // STACK: number of this launch's first layer on the context
+    int n_layers = 1;
+    if constexpr (STACK) {
+        g0 = *ka->epoch;
+        n_layers = ka->L;
+        if (threadIdx.x == 0) s_arrived = -1;               // first read two layers (many barriers) from here
+    }
+#pragma clang loop unroll(disable)
+  for (int layer = 0; layer < n_layers; ++layer) {
+    // STACK: the lane-dependent values are made opaque per layer, or the compiler hoists every address
+    // offset derived from them out of the loop and holds ~50 more registers across the whole body
+    int tid_l = threadIdx.x;
+    if constexpr (STACK) asm volatile("" : "+v"(tid_l));
+    const int tid = tid_l, lane = tid & 63, loff = lane * 16;
+    B1Params p;
+    if constexpr (STACK) {
+        const unsigned int g = g0 + (unsigned int)layer;
+        p.wg = ka->wg[layer]; p.wu = ka->wu[layer]; p.wd = ka->wd[layer];
+        p.x = ka->x + (size_t)layer * ROWB;
+        p.tau = ka->tau + layer;
+        p.partial = ka->partial + (size_t)(g % 3u) * P * ka->d;
+        p.keep = nullptr;
+        p.rec = ka->rec + (g % 3u) * P;
+        p.apub = ka->apub + (size_t)(g & 1u) * P * 64;
+        p.epoch = nullptr;
+        p.b_in = RELU ? ka->b_in[layer] : nullptr;
+        p.fault = ka->fault;
+        p.max_spins = ka->max_spins;
+        p.d = ka->d; p.F = F; p.K0 = ka->K0; p.gelu = ka->gelu;
+    } else {
+        p = pp;
+    }
+    (void)ka;
 
     auto load_row = [&](u32x4 (&buf)[NCH], const char *w, int j) {
         const char *row = w + (size_t)j * ROWB + loff;
@@ -519,14 +792,27 @@ k_ffn_decode_b1(const B1Params p)
     // first gate row on its way before anything else
     u32x4 ga[NCH], gb[NCH];
     if (wave < ni) load_row(ga, p.wg, blk + P * wave);
-    u32x4 xr[NCH];
+    // x: held packed in registers; the whole-stack kernel, which has less room (state of the reduction that
+    // rides along, loop-carried scalars), keeps it in LDS and reads a chunk where it is used
+    u32x4 xr[STACK ? 1 : NCH];
+    if constexpr (STACK) {
+        for (int o = tid * 16; o < ROWB; o += NW * 64 * 16)
+            *reinterpret_cast<u32x4 *>(s_x + o) = *reinterpret_cast<const u32x4 *>(p.x + o);
+        __syncthreads();
+    } else {
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) xr[c] = *reinterpret_cast<const u32x4 *>(p.x + c * 1024 + loff);
+        for (int c = 0; c < NCH; ++c) xr[c] = *reinterpret_cast<const u32x4 *>(p.x + c * 1024 + loff);
+    }
+    auto xv = [&](int c) -> u32x4 {
+        if constexpr (STACK) return *reinterpret_cast<const u32x4 *>(s_x + c * 1024 + loff);
+        else return xr[c];
+    };
     const float tau = DENSE ? 0.0f : p.tau[0];
     unsigned long long tag = 0ull;
     unsigned int call_no = 0u;                              // this balanced call's number on the context
-    if (BAL) {
-        call_no = *p.epoch + 1u;
+    if (BAL || STACK) {
+        if constexpr (STACK) call_no = g0 + (unsigned int)layer + 1u;
+        else call_no = *p.epoch + 1u;
         tag = (unsigned long long)(call_no & 0xffu) << 56;
     }
     // An activation another workgroup published: the word carries the number of the call that wrote it, so
@@ -549,7 +835,7 @@ k_ffn_decode_b1(const B1Params p)
     auto gate_finish = [&](const u32x4 (&buf)[NCH], int i) {
         float s = 0.0f;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) s = dot16<ES>(buf[c], xr[c], s);
+        for (int c = 0; c < NCH; ++c) s = dot16<ES>(buf[c], xv(c), s);
         s = wave_sum(s);
         const float a = ffn_act<RELU>(s, p.b_in, (size_t)(blk + P * i), p.gelu);
         const bool keep = DENSE ? true : (fabsf(a) >= tau);
@@ -559,9 +845,15 @@ k_ffn_decode_b1(const B1Params p)
             if (p.keep) p.keep[blk + P * i] = keep ? 1 : 0;
         }
     };
+    // STACK: the final reduction of the layer before the previous one rides along with this gate phase
+    std::conditional_t<STACK, StackReduce, NoStackReduce> red(ka, s_sum, &s_arrived);
+    if constexpr (STACK) {
+        if (layer >= 2) red.begin(g0 + (unsigned int)layer - 2u, layer, tid, wave);
+    }
     // ---------------------------------------------------------------- gate phase: the next row is
     // requested before the current one is reduced; every path has a fixed number of loads in flight
     for (int i = wave; i < ni; i += 2 * NW) {
+        if constexpr (STACK) red.step(lane);
         if (i + NW < ni) {
             load_row(gb, p.wg, blk + P * (i + NW));
             gate_finish(ga, i);
@@ -575,11 +867,29 @@ k_ffn_decode_b1(const B1Params p)
             gate_finish(ga, i);
         }
     }
+    if constexpr (STACK) {
+        if (layer >= 2) red.finish(lane);
+        // nothing of this wave is in flight any more, so the write-through stores of the previous layer's
+        // partial have been acknowledged by memory (the vector-memory counter at zero says exactly that for
+        // stores that bypass the caches): after the barrier that partial is announced.  A release fence at
+        // agent scope would do the same formally, but it writes the whole L2 back (+9.5 us per layer measured).
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     __syncthreads();
+    if constexpr (STACK) {
+        // the record of this layer doubles as "my partial of the previous layer is in memory"; the balanced
+        // kernel publishes it with its mask below
+        if (!BAL && tid == 0) __hip_atomic_store(p.rec + blk, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (layer >= 2) red.template tree_and_store<ES, RELU>(layer - 2, tid);
+    }
 
     // every wave derives the same ascending list
     const unsigned long long mask = __ballot(lane < ni && s_flag[lane] != 0);
     const int kp = __popcll(mask);
+    if constexpr (STACK && !DENSE) {
+        if (ka->n_active && tid == 0)
+            __hip_atomic_store(ka->kcnt + ((g0 + (unsigned int)layer) % 3u) * P + blk, kp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if ((mask >> lane) & 1ull) s_list[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
 
     float acc[SL][VEC];
@@ -640,7 +950,7 @@ k_ffn_decode_b1(const B1Params p)
             if (!RELU) {
                 s0 = 0.0f;
 #pragma unroll
-                for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xr[c], s0);
+                for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xv(c), s0);
                 s0 = wave_sum(s0);
             }
             if (lane == 0) hs[first + r * stride] = RELU ? av[r] : av[r] * s0;
@@ -746,6 +1056,9 @@ k_ffn_decode_b1(const B1Params p)
             }
             if (lane == 0) s_n2 = hi - lo;
             }
+            if constexpr (STACK) {
+                if (lane == 0) s_arrived = layer + 1;      // all records of this layer seen (or given up, flagged)
+            }
         }
         __syncthreads();
         // first chunk of the balanced share: its loads go out before chunk 0 is consumed
@@ -773,7 +1086,7 @@ k_ffn_decode_b1(const B1Params p)
                     if (!RELU) {
                         s0 = 0.0f;
 #pragma unroll
-                        for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xr[c], s0);
+                        for (int c = 0; c < NCH; ++c) s0 = dot16<ES>(up[r][c], xv(c), s0);
                         s0 = wave_sum(s0);
                     }
                     if (lane == 0) s_h[1][wave + r * NW] = RELU ? av[r] : av[r] * s0;
@@ -811,15 +1124,46 @@ k_ffn_decode_b1(const B1Params p)
     }
     // each wave owns its columns: straight to the partial, no fold
     float *dst = p.partial + (size_t)blk * p.d;
+    __amdgpu_buffer_rsrc_t dst_row = __builtin_amdgcn_make_buffer_rsrc(dst, 0, p.d * 4, 0x00020000);   // raw bytes, bounds = the row
 #pragma unroll
     for (int s = 0; s < SL; ++s) {
         const int c = wave + s * NW;
         if (c < NCH) {
 #pragma unroll
-            for (int k = 0; k < VEC; k += 4)
-                *reinterpret_cast<float4 *>(dst + (c * 64 + lane) * VEC + k) =
-                    make_float4(acc[s][k], acc[s][k + 1], acc[s][k + 2], acc[s][k + 3]);
+            for (int k = 0; k < VEC; k += 4) {
+                if constexpr (STACK) {
+                    store_through16(dst_row, ((c * 64 + lane) * VEC + k) * 4, acc[s][k], acc[s][k + 1], acc[s][k + 2], acc[s][k + 3]);
+                } else {
+                    *reinterpret_cast<float4 *>(dst + (c * 64 + lane) * VEC + k) =
+                        make_float4(acc[s][k], acc[s][k + 1], acc[s][k + 2], acc[s][k + 3]);
+                }
+            }
         }
+    }
+    if constexpr (STACK) __syncthreads();          // the LDS arrays are free for the next layer
+  }     // layers
+    if constexpr (STACK) {
+        // drain: a record of one more (empty) layer announces the last partial, then the two reductions still owed
+        const int tid = threadIdx.x, lane = tid & 63;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        const unsigned int g_end = g0 + (unsigned int)n_layers;
+        if (tid == 0)
+            __hip_atomic_store(ka->rec + (g_end % 3u) * P + blk, (unsigned long long)((g_end + 1u) & 0xffu) << 56,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        StackReduce red(ka, s_sum, &s_arrived);
+        for (int l = n_layers >= 2 ? n_layers - 2 : 0; l < n_layers; ++l) {
+            // both wait for the records of the empty layer: those confirm every earlier partial of their senders
+            red.begin(g0 + (unsigned int)l, n_layers + 1, tid, wave);
+            red.rec = ka->rec + (g_end % 3u) * P;
+            red.tag = (unsigned long long)((g_end + 1u) & 0xffu) << 56;
+            red.finish(lane);
+            __syncthreads();
+            red.template tree_and_store<ES, RELU>(l, tid);
+        }
+        // the empty layer uses up a number too (its records must not be mistaken for the next launch's first
+        // layer); every workgroup has read the counter at its start: they all sent that record
+        if (blk == 0 && tid == 0) *ka->epoch = g_end + 1u;
     }
 }
 
@@ -904,7 +1248,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     p.wg = (const char *)layer->w_gate; p.wu = (const char *)layer->w_up; p.wd = (const char *)layer->w_down;
     p.x = (const char *)x; p.tau = tau;
     p.partial = reinterpret_cast<float *>(ws);
-    p.keep = lists ? reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256)) : nullptr;
+    p.keep = lists ? reinterpret_cast<unsigned char *>(ws + ws_partial_bytes(B, d)) : nullptr;
     p.idx = nullptr; p.n_list = nullptr; p.b_in = nullptr;
     p.gelu = layer->kind == CLADA_FFN_GEGLU ? 1 : 0;
     p.d = d; p.F = F; p.ni_max = (F + P - 1) / P;
@@ -977,7 +1321,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     // ---- batched MFMA path (bf16, supported widths): up to 16 tokens per pass; larger batches run
     // as ceil(B/16) passes of near-equal size, each re-reading the weights of its own union
     if (B >= 2 && ctx->opt_decode_batched) {
-        unsigned char *keep_region = reinterpret_cast<unsigned char *>(ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256));
+        unsigned char *keep_region = reinterpret_cast<unsigned char *>(ws + ws_partial_bytes(B, d));
         char *scratch = reinterpret_cast<char *>(keep_region) + align_up((size_t)B * F, 256);
         const int n_groups = (B + 15) / 16, per_group = (B + n_groups - 1) / n_groups;     // per_group >= 2 whenever B >= 2
         bool ran_all = false;
@@ -1074,7 +1418,7 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
     // ---- matrix-core path (bf16, supported widths), up to 16 tokens per pass, as in the thresholded call
     if (B >= 2 && ctx->opt_decode_batched) {
         char *ws = ctx->ws + CLADA_WS_HEADER;
-        char *scratch = ws + align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256) + align_up((size_t)B * F, 256);
+        char *scratch = ws + ws_partial_bytes(B, d) + align_up((size_t)B * F, 256);
         const int n_groups = (B + 15) / 16, per_group = (B + n_groups - 1) / n_groups;
         bool ran_all = false;
         for (int g0 = 0; g0 < B; g0 += per_group) {
@@ -1123,6 +1467,117 @@ clada_status run_list_decode(clada_ctx *ctx, const clada_layer *layer, const voi
     return CLADA_OK;
 }
 
+// ---- whole-stack entry points (B = 1)
+template <int ES, int NCH, int DCH, bool DENSE, bool BAL, bool RELU>
+hipError_t launch_stack_variant(clada_ctx *ctx, const StackParams &p, int P, hipStream_t st)
+{
+    auto kern = k_ffn_decode_b1<ES, NCH, 8, DCH, DENSE, BAL, RELU, true>;
+    // every workgroup waits for the others' partials (and masks): all of them must be resident at once
+    const void *fn = reinterpret_cast<const void *>(kern);
+    int occ = -1;
+    for (int i = 0; i < ctx->n_occ; ++i)
+        if (ctx->occ_fn[i] == fn) occ = ctx->occ_val[i];
+    if (occ < 0) {
+        int nb = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, 512, 0);
+        if (e != hipSuccess) return e;
+        occ = nb;
+        if (ctx->n_occ < CLADA_OCC_SLOTS) {
+            ctx->occ_fn[ctx->n_occ] = fn;
+            ctx->occ_val[ctx->n_occ++] = nb;
+        }
+    }
+    if ((long long)occ * ctx->num_cu < P) return hipErrorNotSupported;
+    hipLaunchKernelGGL(kern, dim3(P), dim3(512), 0, st, p);
+    return hipGetLastError();
+}
+
+template <int ES, int NCH, int DCH, bool RELU = false>
+hipError_t launch_stack(clada_ctx *ctx, const StackParams &p, int P, bool dense, bool balance, hipStream_t st)
+{
+    if (dense) return launch_stack_variant<ES, NCH, DCH, true, false, RELU>(ctx, p, P, st);
+    if (balance) return launch_stack_variant<ES, NCH, DCH, false, true, RELU>(ctx, p, P, st);
+    return launch_stack_variant<ES, NCH, DCH, false, false, RELU>(ctx, p, P, st);
+}
+
+clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L, const void *x, const float *tau,
+                              void *y, int32_t *n_active, bool dense, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    if (!layers) return clada_fail(ctx, CLADA_ERR_NULL, "layers is NULL");
+    if (L < 1 || L > CLADA_MAX_LAYERS) return clada_fail(ctx, CLADA_ERR_SHAPE, "L=%d outside [1,%d]", L, CLADA_MAX_LAYERS);
+    for (int l = 0; l < L; ++l) {
+        clada_status st = clada_check_layer(ctx, &layers[l]);
+        if (st != CLADA_OK) return st;
+        if (layers[l].d != layers[0].d || layers[l].d_ff != layers[0].d_ff || layers[l].dtype != layers[0].dtype ||
+            layers[l].kind != layers[0].kind)
+            return clada_fail(ctx, CLADA_ERR_SHAPE, "layer %d differs from layer 0 in d, d_ff, dtype or kind", l);
+    }
+    if (!x || !y || (!dense && !tau)) return clada_fail(ctx, CLADA_ERR_NULL, "x, y or tau_final is NULL");
+    if (!aligned16(x) || !aligned16(y)) return clada_fail(ctx, CLADA_ERR_ALIGN, "x and y must be 16-byte aligned");
+    const int d = layers[0].d, F = layers[0].d_ff;
+    const size_t need = CLADA_WS_HEADER + clada_ws_decode(d, F, 1);
+    if (ctx->ws_bytes < need)
+        return clada_fail(ctx, CLADA_ERR_WORKSPACE, "workspace %zu < %zu bytes needed", ctx->ws_bytes, need);
+    const int es = (int)dtype_size(layers[0].dtype);
+    const int nch = (d * es + 1023) / 1024;
+    const bool relu = layers[0].kind == CLADA_FFN_RELU;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int Pb = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
+    const int ni_b = Pb > 0 ? (F + Pb - 1) / Pb : 0;
+    // shapes the persistent kernel is built for (the widths of the models the paper evaluates); anything
+    // else, and a launch that cannot hold all its workgroups at once, runs as L per-layer calls
+    const bool shape_ok = (d * es) % 1024 == 0 && es == 2 &&
+                          (relu ? nch == 5 : (nch == 4 || nch == 8 || nch == 10));
+    bool persistent = ctx->opt_decode_stack == 1 && ctx->opt_decode_b1 >= 1 && shape_ok && F >= Pb && ni_b <= 64;
+    if (persistent) {
+        const double phase2_bytes = (relu ? 1.0 : 2.0) * (double)F * d * es;
+        const bool balance = !dense && ni_b <= 56 &&
+                             (ctx->opt_decode_b1 == 3 || (ctx->opt_decode_b1 == 1 && phase2_bytes >= 128e6));
+        for (int l0 = 0; l0 < L && persistent; l0 += CLADA_STACK_MAX_LAYERS) {
+            const int n = L - l0 < CLADA_STACK_MAX_LAYERS ? L - l0 : CLADA_STACK_MAX_LAYERS;
+            StackParams sp;
+            memset(&sp, 0, sizeof(sp));
+            for (int l = 0; l < n; ++l) {
+                sp.wg[l] = (const char *)layers[l0 + l].w_gate;
+                sp.wu[l] = (const char *)layers[l0 + l].w_up;
+                sp.wd[l] = (const char *)layers[l0 + l].w_down;
+                sp.b_in[l] = relu ? layers[l0 + l].b_in : nullptr;
+                sp.b_out[l] = relu ? layers[l0 + l].b_out : nullptr;
+            }
+            sp.x = (const char *)x + (size_t)l0 * d * es;
+            sp.y = (char *)y + (size_t)l0 * d * es;
+            sp.tau = tau ? tau + l0 : nullptr;
+            sp.partial = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
+            sp.rec = reinterpret_cast<unsigned long long *>(ctx->ws + STACK_REC);
+            sp.apub = reinterpret_cast<unsigned long long *>(ctx->ws + STACK_APUB);
+            sp.epoch = reinterpret_cast<unsigned int *>(ctx->ws + STACK_EPOCH);
+            sp.kcnt = reinterpret_cast<int *>(ctx->ws + STACK_KCNT);
+            sp.n_active = (n_active && !dense) ? n_active + 2 * l0 : nullptr;
+            sp.fault = reinterpret_cast<int *>(ctx->ws + COOP_FAULT);
+            sp.max_spins = ctx->opt_decode_spin_limit;
+            sp.d = d; sp.F = F; sp.L = n;
+            sp.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
+            sp.gelu = layers[0].kind == CLADA_FFN_GEGLU ? 1 : 0;
+            hipError_t e = hipErrorNotSupported;
+            if (relu) e = launch_stack<2, 5, 16, true>(ctx, sp, Pb, dense, balance, stream);
+            else if (nch == 8) e = launch_stack<2, 8, 16>(ctx, sp, Pb, dense, balance, stream);
+            else if (nch == 10) e = launch_stack<2, 10, 8>(ctx, sp, Pb, dense, balance, stream);
+            else if (nch == 4) e = launch_stack<2, 4, 16>(ctx, sp, Pb, dense, balance, stream);
+            if (e == hipErrorNotSupported && l0 == 0) { persistent = false; break; }
+            CLADA_CHECK_HIP(ctx, e);
+        }
+        if (persistent) return CLADA_OK;
+    }
+    for (int l = 0; l < L; ++l) {
+        clada_status st = run_decode(ctx, &layers[l], (const char *)x + (size_t)l * d * es, 1, tau ? tau + l : nullptr,
+                                     (char *)y + (size_t)l * d * es, nullptr, n_active ? n_active + 2 * l : nullptr,
+                                     nullptr, dense, hip_stream);
+        if (st != CLADA_OK) return st;
+    }
+    return CLADA_OK;
+}
+
 }  // namespace
 
 extern "C" clada_status clada_static_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
@@ -1141,7 +1596,7 @@ void clada_launch_finalize(int es, const float *partial, int P, int B, int d, ch
 size_t clada_ws_decode(int32_t d, int32_t d_ff, int32_t B)
 {
     if (B <= 0) return 0;
-    return align_up(sizeof(float) * (size_t)CLADA_MAX_DECODE_WGS * B * d, 256) + align_up((size_t)B * d_ff, 256) +
+    return ws_partial_bytes(B, d) + align_up((size_t)B * d_ff, 256) +
            clada_ws_decode_batched(d_ff);
 }
 
@@ -1157,4 +1612,17 @@ extern "C" clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer
                                                int32_t B, void *y, void *hip_stream)
 {
     return run_decode(ctx, layer, x, B, nullptr, y, nullptr, nullptr, nullptr, true, hip_stream);
+}
+
+extern "C" clada_status clada_sparse_ffn_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L,
+                                                      const void *x, const float *tau_final, void *y,
+                                                      int32_t *n_active, void *hip_stream)
+{
+    return run_stack_decode(ctx, layers, L, x, tau_final, y, n_active, false, hip_stream);
+}
+
+extern "C" clada_status clada_dense_ffn_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L,
+                                                     const void *x, void *y, void *hip_stream)
+{
+    return run_stack_decode(ctx, layers, L, x, nullptr, y, nullptr, true, hip_stream);
 }

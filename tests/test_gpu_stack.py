@@ -1,0 +1,154 @@
+"""GPU parity: the whole-stack calls (one persistent launch for L layers) against the per-layer calls,
+bit for bit, and against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import DEV, TOL_Y, assert_close_y, check_mask_band, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def clada():
+    import paper_2502_19078_amd as m
+    m.load_library()
+    return m
+
+
+def _stack(clada, cfg_name, d, F, L, seed, relu=False, geglu=False):
+    from paper_2502_19078_amd import binding
+    cfg = synth.CONFIGS[cfg_name]
+    ws, layers = [], []
+    for l in range(L):
+        if relu:
+            w = synth.relu_layer(cfg, seed, l, d=d, d_ff=F)
+            layers.append(clada.Layer(to_dev(w[0], cfg.dtype), None, to_dev(w[2], cfg.dtype), kind=binding.RELU,
+                                      b_in=torch.from_numpy(w[1]).to(DEV), b_out=torch.from_numpy(w[3]).to(DEV)))
+        else:
+            w = synth.layer_weights(cfg, seed, l, d=d, d_ff=F)
+            layers.append(clada.Layer(*[to_dev(a, cfg.dtype) for a in w], kind=binding.GEGLU if geglu else binding.SWIGLU))
+        ws.append(w)
+    x = np.concatenate([synth.decode_hidden(cfg, seed, l, 0, B=1, d=d) for l in range(L)])       # [L][d]
+    return cfg, ws, layers, x
+
+
+# cfg, d, F, L, q, options: shapes with a persistent instance (4, 8 and 10 KiB rows; balanced and not; odd
+# and even L; F not a multiple of the workgroup count), and shapes that run as per-layer calls inside the call
+CASES = [
+    ("c2", 4096, 11008, 5, 0.45, {}),                 # 7B layer shape: balanced persistent kernel
+    ("c2", 4096, 11008, 2, 0.45, {"decode.b1": 2}),   # the same without balancing
+    ("c2", 4096, 2700, 7, 0.60, {"decode.b1": 3}),    # balancing forced on a short layer, ragged neuron count
+    ("c2", 4096, 2700, 3, 0.30, {}),                  # short layer: no balancing by default
+    ("c5", 5120, 13824, 3, 0.50, {}),                 # 13B layer shape (10 KiB rows)
+    ("c2", 2048, 16384, 4, 0.45, {}),                 # 4 KiB rows, 64 neurons per workgroup: unbalanced
+    ("c2", 1024, 1000, 3, 0.45, {}),                  # no persistent instance: per-layer calls inside
+    ("c1", 512, 1376, 2, 0.40, {}),                   # fp32: per-layer calls inside
+]
+
+
+@pytest.mark.parametrize("cfg_name,d,F,L,q,opts", CASES)
+def test_stack_call_is_the_per_layer_calls_bit_for_bit(clada, cfg_name, d, F, L, q, opts):
+    cfg, ws, layers, x = _stack(clada, cfg_name, d, F, L, seed=21)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, 0, 0))
+    ctx.set_option("decode.stack", 1)                   # the persistent kernel (off by default)
+    for k, v in opts.items():
+        ctx.set_option(k, v)
+    tau = np.array([np.quantile(np.abs(oracle.gate_act(ws[l][0], x[l:l + 1])), q) for l in range(L)], np.float32)
+    tau[L - 1] *= 1.92                                  # thresholds differ per layer
+    xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
+    y_ref, cnt_ref = [], []
+    for l in range(L):
+        yl, _, cl, _ = clada.sparse_ffn_decode(ctx, layers[l], xd[l:l + 1].contiguous(), td[l:l + 1].contiguous(), want_lists=True)
+        y_ref.append(yl[0].clone())
+        cnt_ref.append(cl.clone())
+    for rep in range(3):                                # repeated launches: counters and parities carry over
+        y, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td, want_counts=True)
+        torch.cuda.synchronize()
+        for l in range(L):
+            assert torch.equal(y[l], y_ref[l]), f"rep {rep} layer {l}: bits differ from the per-layer call"
+            assert torch.equal(cnt[l], cnt_ref[l]), f"rep {rep} layer {l}: kept count"
+    assert not ctx.device_fault()
+    # dense twin
+    yd = clada.dense_ffn_stack_decode(ctx, layers, xd)
+    for l in range(L):
+        assert torch.equal(yd[l], clada.dense_ffn_decode(ctx, layers[l], xd[l:l + 1].contiguous())[0])
+    # per-layer calls still work on the same context afterwards
+    assert torch.equal(clada.sparse_ffn_decode(ctx, layers[0], xd[:1].contiguous(), td[:1].contiguous())[0], y_ref[0])
+    # and the oracle, on two layers
+    for l in (0, L - 1):
+        ref = oracle.sparse_decode(*ws[l], x[l:l + 1], tau[l:l + 1].astype(np.float64))
+        assert abs(int(cnt[l, 0]) - int(ref["n_active"][0])) <= 3
+        if int(cnt[l, 0]) == int(ref["n_active"][0]):
+            assert_close_y(to_np(y[l:l + 1]), ref["y"], TOL_Y[cfg.dtype], f"layer {l} vs oracle")
+
+
+def test_stack_call_other_families_and_long_stacks(clada):
+    # non-gated ReLU family at the OPT-2.7B width (5 KiB rows, biases)
+    cfg, ws, layers, x = _stack(clada, "o27", 2560, 10240, 3, seed=22, relu=True)
+    ctx = clada.Context(0, clada.workspace_bytes(2560, 10240, 1, 0, 0))
+    ctx.set_option("decode.stack", 1)
+    xd = to_dev(x, cfg.dtype)
+    td = torch.full((3,), 0.05, dtype=torch.float32, device=DEV)
+    y = clada.sparse_ffn_stack_decode(ctx, layers, xd, td)
+    for l in range(3):
+        assert torch.equal(y[l], clada.sparse_ffn_decode(ctx, layers[l], xd[l:l + 1].contiguous(), td[l:l + 1].contiguous())[0])
+    ref = oracle.relu_decode(*ws[1], x[1:2], tau=np.array([0.05]))
+    assert_close_y(to_np(y[1:2]), ref["y"], TOL_Y[cfg.dtype], "relu stack vs oracle")
+    # GELU-gated family, and more layers than one launch takes (the same small layers listed 25 times each)
+    cfg, ws, layers, x = _stack(clada, "c2", 4096, 512, 2, seed=23, geglu=True)
+    long_layers = layers * 25
+    xd = to_dev(np.tile(x, (25, 1)), cfg.dtype)
+    td = torch.full((50,), 0.1, dtype=torch.float32, device=DEV)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 512, 1, 0, 0))
+    ctx.set_option("decode.stack", 1)
+    y = clada.sparse_ffn_stack_decode(ctx, long_layers, xd, td)
+    y0 = clada.sparse_ffn_decode(ctx, layers[0], xd[:1].contiguous(), td[:1].contiguous())[0]
+    y1 = clada.sparse_ffn_decode(ctx, layers[1], xd[1:2].contiguous(), td[:1].contiguous())[0]
+    torch.cuda.synchronize()
+    for l in range(50):
+        assert torch.equal(y[l], y0 if l % 2 == 0 else y1), f"layer {l}"
+    assert not ctx.device_fault()
+
+
+def test_stack_call_rejects_mixed_layers_and_bad_arguments(clada):
+    from paper_2502_19078_amd.binding import CladaError
+    cfg, ws, layers, x = _stack(clada, "c2", 1024, 300, 2, seed=24)
+    other = clada.Layer(*[to_dev(a, cfg.dtype) for a in synth.layer_weights(cfg, 24, 5, d=1024, d_ff=301)])
+    ctx = clada.Context(0, clada.workspace_bytes(1024, 301, 1, 0, 0))
+    xd, td = to_dev(x, cfg.dtype), torch.zeros(2, device=DEV)
+    with pytest.raises(CladaError):
+        clada.sparse_ffn_stack_decode(ctx, [layers[0], other], xd, td)
+    with pytest.raises(CladaError):
+        ctx.check(ctx._lib.clada_sparse_ffn_stack_decode(ctx._h, None, 2, xd.data_ptr(), td.data_ptr(), xd.data_ptr(), None, None))
+
+
+def test_bounded_waits_of_the_stack_kernel_give_up_cleanly(clada):
+    """Spin limit forced to zero from the host: every workgroup still runs to its end, the outputs are NaN
+    and the context reports the fault."""
+    cfg, ws, layers, x = _stack(clada, "c2", 4096, 11008, 3, seed=25)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+    ctx.set_option("decode.b1", 3)
+    ctx.set_option("decode.stack", 1)
+    xd, td = to_dev(x, cfg.dtype), torch.full((3,), 0.25, dtype=torch.float32, device=DEV)
+    good = clada.sparse_ffn_stack_decode(ctx, layers, xd, td).clone()
+    assert not ctx.device_fault() and torch.isfinite(good.float()).all()
+    ctx.set_option("decode.spin_limit", 0)
+    bad = clada.sparse_ffn_stack_decode(ctx, layers, xd, td)
+    torch.cuda.synchronize()
+    assert ctx.device_fault() and torch.isnan(bad.float()).any()
+
+
+def test_stack_call_default_mode_issues_the_per_layer_launches(clada):
+    """Without the option the call is the per-layer launches issued by the library: same bits, same counts."""
+    cfg, ws, layers, x = _stack(clada, "c2", 4096, 2752, 3, seed=26)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 2752, 1, 0, 0))
+    xd, td = to_dev(x, cfg.dtype), torch.full((3,), 0.25, dtype=torch.float32, device=DEV)
+    y, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td, want_counts=True)
+    for l in range(3):
+        yl, _, cl, _ = clada.sparse_ffn_decode(ctx, layers[l], xd[l:l + 1].contiguous(), td[l:l + 1].contiguous(), want_lists=True)
+        assert torch.equal(y[l], yl[0]) and torch.equal(cnt[l], cl)
+    ctx.set_option("decode.stack", 1)
+    assert torch.equal(clada.sparse_ffn_stack_decode(ctx, layers, xd, td), y)

@@ -170,3 +170,58 @@ def test_unmutated_oracle_passes_every_pin_used_above():
     for pins in (FFN_PINS, SIGNAL_PINS, CETT_PINS, MASK_PINS, RELU_PINS, GEGLU_PINS):
         for pin in pins:
             pin()
+
+
+# ---- the stored-mask formats (oracle/mask_codec.py, plain Python): the same game on its source text
+import importlib.util
+import types
+
+import test_oracle_mask_codec as t_codec
+
+CODEC_SRC = os.path.join(os.path.dirname(oracle.__file__), "mask_codec.py")
+CODEC_PINS = [
+    lambda: t_codec.test_hand_worked_example(),
+    lambda: t_codec.test_bit_mask_is_numpy_packbits_and_round_trips(1376, 0.6),
+    lambda: t_codec.test_sparse_form_round_trips_and_matches_its_definition(300, 0.5, 0.02),
+    lambda: t_codec.test_sparse_form_round_trips_and_matches_its_definition(262144, 0.3, 0.0002),
+    lambda: t_codec.test_worst_case_length_bound_is_attained_only_by_wide_gaps(),
+]
+CODEC_MUTATIONS = [
+    ("bit order inside a word reversed", "words[j // 32] |= 1 << (j % 32)", "words[j // 32] |= 1 << (31 - j % 32)"),
+    ("gap not reduced by one", "gap = j - prev - 1", "gap = j - prev"),
+    ("first gap measured from position 0 instead of -1", "    prev = -1\n    n = 0", "    prev = 0\n    n = 0"),
+    ("high group first", "out.append((gap & 127) | 128)\n                gap >>= 7\n            out.append(gap)",
+     "out.append((gap >> 7) | 128)\n                gap &= 127\n            out.append(gap)"),
+    ("continuation bit on the last byte instead of the others", "out.append((gap & 127) | 128)", "out.append(gap & 127)"),
+    ("groups of 8 bits", "gap >>= 7", "gap >>= 8"),
+    ("decoder forgets the reference", "words = [int(w) for w in ref_words] if ref_words is not None else [0] * mask_words(d_ff)",
+     "words = [0] * mask_words(d_ff)"),
+    ("decoder sets instead of flips", "words[pos // 32] ^= 1 << (pos % 32)", "words[pos // 32] |= 1 << (pos % 32)"),
+    ("decoder shifts groups by 8", "shift += 7", "shift += 8"),
+    ("encoder compares with the mask itself", "if bit != ref:", "if bit:"),
+]
+
+
+@pytest.mark.parametrize("what,find,repl", CODEC_MUTATIONS, ids=[m[0] for m in CODEC_MUTATIONS])
+def test_planted_mistake_in_the_mask_codec_is_caught(what, find, repl):
+    text = open(CODEC_SRC).read()
+    assert text.count(find) >= 1, f"pattern for '{what}' not found"
+    mutant = types.ModuleType("mask_codec_mutant")
+    exec(compile(text.replace(find, repl, 1), "mask_codec_mutant.py", "exec"), mutant.__dict__)
+    real = t_codec.mc
+    t_codec.mc = mutant
+    try:
+        caught = 0
+        for pin in CODEC_PINS:
+            try:
+                pin()
+            except (AssertionError, IndexError, ValueError):
+                caught += 1
+        assert caught >= 1, f"no pin noticed: {what}"
+    finally:
+        t_codec.mc = real
+
+
+def test_unmutated_mask_codec_passes_its_pins():
+    for pin in CODEC_PINS:
+        pin()
