@@ -713,7 +713,9 @@ struct NoStackReduce {       // the per-layer kernel has nothing to ride along
 // RELU: the non-gated family -- no W_up rows at all, h is the activation itself.
 // STACK: the whole-stack variant described above (parameters StackParams; the per-layer state below is
 // rebuilt from them at the top of every layer).
-template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL, bool RELU = false, bool STACK = false>
+// ROUNDS: more than 64 neurons per workgroup, worked off 64 at a time (a template flag: an enclosing loop
+// of unknown trip count costs the kernel ~50 registers, which the balanced instances do not have).
+template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL, bool RELU = false, bool STACK = false, bool ROUNDS = false>
 __global__ void __launch_bounds__(NW * 64)
 k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
 {
@@ -723,7 +725,11 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     constexpr int UPB = (DCH + NW - 1) / NW;                // W_up rows a wave takes per chunk
     // own-first chunk: two W_up rows for waves 1..NW-1 (one with 10 KiB rows, which would not fit the registers)
     constexpr int K0MAX = (NCH > 8 ? 1 : 2) * (NW - 1);
+    // x in LDS instead of registers: the whole-stack kernel, and rows of 12 and 16 KiB (two row buffers of the
+    // gate phase alone are 96 / 128 registers there)
+    constexpr bool XLDS = STACK || NCH > 10;
     static_assert(!(DENSE && BAL), "the dense twin needs no balancing");
+    static_assert(!(ROUNDS && (BAL || STACK)), "rounds only in the plain split-d kernel");
     __shared__ float s_a[64];
     __shared__ int s_flag[64];
     __shared__ int s_list[64];
@@ -733,7 +739,7 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     __shared__ int s_n2;
     __shared__ float4 s_sum[STACK ? 32 : 1][16];            // STACK: slices of the final reduction
     __shared__ int s_arrived;                               // STACK: see StackReduce
-    __shared__ __align__(16) unsigned char s_x[STACK ? NCH * 1024 : 16];    // STACK: the layer's input row
+    __shared__ __align__(16) unsigned char s_x[(STACK || NCH > 10) ? NCH * 1024 : 16];    // the layer's input row where it is not held in registers
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -746,7 +752,7 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     } else {
         F = pp.F;
     }
-    const int ni = blk < F ? (F - blk + P - 1) / P : 0;     // <= 64 (<= 56 when BAL)
+    const int ni_all = blk < F ? (F - blk + P - 1) / P : 0; // this workgroup's neurons: blk, blk + P, ... (<= 56 when BAL)
 
     const int loff = lane * 16;
     unsigned int g0 = 0u;                                   // STACK: number of this launch's first layer on the context
@@ -789,13 +795,24 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
         for (int c = 0; c < NCH; ++c) buf[c] = ld_stream16(row + c * 1024);
     };
 
+    float acc[SL][VEC];
+#pragma unroll
+    for (int s = 0; s < SL; ++s)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[s][e] = 0.0f;
+
+    // More than 64 neurons per workgroup (d_ff above 64 P: the 70B-class layers) are worked off in rounds of
+    // 64, gate rows and kept rows of a round before the next round's; the accumulators run through.  (The
+    // balanced and the whole-stack variants are only launched where one round covers everything.)
+   for (int r0 = 0; r0 < (ROUNDS ? ni_all : 1); r0 += 64) {
+    const int ni = ROUNDS ? min(64, ni_all - r0) : ni_all;
+    const int nb0 = blk + P * r0;                           // the round's first neuron
     // first gate row on its way before anything else
     u32x4 ga[NCH], gb[NCH];
-    if (wave < ni) load_row(ga, p.wg, blk + P * wave);
-    // x: held packed in registers; the whole-stack kernel, which has less room (state of the reduction that
-    // rides along, loop-carried scalars), keeps it in LDS and reads a chunk where it is used
-    u32x4 xr[STACK ? 1 : NCH];
-    if constexpr (STACK) {
+    if (wave < ni) load_row(ga, p.wg, nb0 + P * wave);
+    // x: held packed in registers; where there is less room (XLDS) it sits in LDS and a chunk is read where it is used
+    u32x4 xr[XLDS ? 1 : NCH];
+    if constexpr (XLDS) {
         for (int o = tid * 16; o < ROWB; o += NW * 64 * 16)
             *reinterpret_cast<u32x4 *>(s_x + o) = *reinterpret_cast<const u32x4 *>(p.x + o);
         __syncthreads();
@@ -804,7 +821,7 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
         for (int c = 0; c < NCH; ++c) xr[c] = *reinterpret_cast<const u32x4 *>(p.x + c * 1024 + loff);
     }
     auto xv = [&](int c) -> u32x4 {
-        if constexpr (STACK) return *reinterpret_cast<const u32x4 *>(s_x + c * 1024 + loff);
+        if constexpr (XLDS) return *reinterpret_cast<const u32x4 *>(s_x + c * 1024 + loff);
         else return xr[c];
     };
     const float tau = DENSE ? 0.0f : p.tau[0];
@@ -837,12 +854,12 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
 #pragma unroll
         for (int c = 0; c < NCH; ++c) s = dot16<ES>(buf[c], xv(c), s);
         s = wave_sum(s);
-        const float a = ffn_act<RELU>(s, p.b_in, (size_t)(blk + P * i), p.gelu);
+        const float a = ffn_act<RELU>(s, p.b_in, (size_t)(nb0 + P * i), p.gelu);
         const bool keep = DENSE ? true : (fabsf(a) >= tau);
         if (lane == 0) {
             s_a[i] = a;
             s_flag[i] = keep ? 1 : 0;
-            if (p.keep) p.keep[blk + P * i] = keep ? 1 : 0;
+            if (p.keep) p.keep[nb0 + P * i] = keep ? 1 : 0;
         }
     };
     // STACK: the final reduction of the layer before the previous one rides along with this gate phase
@@ -855,10 +872,10 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     for (int i = wave; i < ni; i += 2 * NW) {
         if constexpr (STACK) red.step(lane);
         if (i + NW < ni) {
-            load_row(gb, p.wg, blk + P * (i + NW));
+            load_row(gb, p.wg, nb0 + P * (i + NW));
             gate_finish(ga, i);
             if (i + 2 * NW < ni) {
-                load_row(ga, p.wg, blk + P * (i + 2 * NW));
+                load_row(ga, p.wg, nb0 + P * (i + 2 * NW));
                 gate_finish(gb, i + NW);
             } else {
                 gate_finish(gb, i + NW);
@@ -892,12 +909,6 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     }
     if ((mask >> lane) & 1ull) s_list[__popcll(mask & ((1ull << lane) - 1ull))] = lane;
 
-    float acc[SL][VEC];
-#pragma unroll
-    for (int s = 0; s < SL; ++s)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[s][e] = 0.0f;
-
     // h * W_down[j, slice] for one chunk of neurons, straight from the loaded registers
     auto down_fma = [&](auto dnc, const u32x4 (&dn)[decltype(dnc)::value][SL], const float *hs, int nvalid) {
         constexpr int N = decltype(dnc)::value;
@@ -918,7 +929,7 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
 #pragma unroll
         for (int e = 0; e < N; ++e) {
             if (e < nvalid) {
-                const int j = local ? blk + P * rows[e] : rows[e];
+                const int j = local ? nb0 + P * rows[e] : rows[e];
 #pragma unroll
                 for (int s = 0; s < SL; ++s) {
                     const int c = wave + s * NW;
@@ -939,7 +950,7 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int e = first + r * stride;
-            const int j = local ? blk + P * rows[e] : rows[e];
+            const int j = local ? nb0 + P * rows[e] : rows[e];
             if (local) av[r] = s_a[rows[e]];
             else av[r] = published_act(aidx[e]);
             if (!RELU) load_row(up[r], p.wu, j);
@@ -1122,6 +1133,8 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
             down_fma(std::integral_constant<int, DCH>{}, dn, s_h[par], nc);
         }
     }
+    if (ROUNDS && r0 + 64 < ni_all) __syncthreads();       // the LDS arrays are free for the next round
+   }    // rounds
     // each wave owns its columns: straight to the partial, no fold
     float *dst = p.partial + (size_t)blk * p.d;
     __amdgpu_buffer_rsrc_t dst_row = __builtin_amdgcn_make_buffer_rsrc(dst, 0, p.d * 4, 0x00020000);   // raw bytes, bounds = the row
@@ -1170,7 +1183,10 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
 template <int ES, int NCH, int DCH, bool DENSE, bool BAL, bool RELU = false>
 hipError_t launch_b1_variant(clada_ctx *ctx, const B1Params &p, int P, hipStream_t st)
 {
-    auto kern = k_ffn_decode_b1<ES, NCH, 8, DCH, DENSE, BAL, RELU>;
+    const bool rounds = (p.F + P - 1) / P > 64;
+    if constexpr (BAL) { if (rounds) return hipErrorNotSupported; }
+    auto kern = (!BAL && rounds) ? k_ffn_decode_b1<ES, NCH, 8, DCH, DENSE, false, RELU, false, !BAL>
+                                 : k_ffn_decode_b1<ES, NCH, 8, DCH, DENSE, BAL, RELU>;
     if (BAL) {          // spinning on other workgroups' records needs every workgroup resident at once
         // (the answer is kept in the context: it belongs to the context's device, and a context is used by
         // one thread at a time)
@@ -1264,12 +1280,12 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
     // ---- split-d path (decode batch 1, whole-KiB rows, <= 64 neurons per workgroup)
     // (exactly the instantiations launched below: a shape admitted here without one would fail the call)
     const bool b1_shape = relu ? (es == 2 && (nch == 2 || nch == 5 || nch == 8 || nch == 10))
-                          : es == 2 ? (nch == 2 || nch == 4 || nch == 5 || nch == 8 || nch == 10)
+                          : es == 2 ? (nch == 2 || nch == 4 || nch == 5 || nch == 8 || nch == 10 || nch == 12 || nch == 16)
                                     : (nch == 2 || nch == 8);
     if (ctx->opt_decode_b1 >= 1 && B == 1 && (d * es) % 1024 == 0 && b1_shape) {
         const int Pb = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
         const int ni_b = (F + Pb - 1) / Pb;
-        if (F >= Pb && ni_b <= 64) {
+        if (F >= Pb && ni_b <= 1024) {
             B1Params b;
             b.wg = p.wg; b.wu = p.wu; b.wd = p.wd; b.x = p.x; b.tau = tau; b.partial = p.partial; b.keep = p.keep;
             b.rec = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_REC);
@@ -1300,6 +1316,8 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
                 }
                 else if (es == 2 && nch == 8) eb = launch_b1<2, 8, 16>(ctx, b, Pb, dense, balance, stream);
                 else if (es == 2 && nch == 10) eb = launch_b1<2, 10, 8>(ctx, b, Pb, dense, balance, stream);
+                else if (es == 2 && nch == 12) eb = launch_b1<2, 12, 8>(ctx, b, Pb, dense, balance, stream);
+                else if (es == 2 && nch == 16) eb = launch_b1<2, 16, 8>(ctx, b, Pb, dense, balance, stream);
                 else if (es == 2 && nch == 5) eb = launch_b1<2, 5, 16>(ctx, b, Pb, dense, balance, stream);
                 else if (es == 2 && nch == 4) eb = launch_b1<2, 4, 16>(ctx, b, Pb, dense, balance, stream);
                 else if (es == 2 && nch == 2) eb = launch_b1<2, 2, 16>(ctx, b, Pb, dense, balance, stream);

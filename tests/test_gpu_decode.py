@@ -419,3 +419,28 @@ def test_fp32_few_neurons_meet_the_bar_their_conditioning_allows(clada, seed, la
             rel = np.linalg.norm(to_np(got) - ref, axis=1)[nr > 0] / nr[nr > 0]
             worst = max(worst, float(rel.max()))
     print(f"[few neurons] seed={seed} F={F} B={B}: worst row {worst:.2e}")
+
+
+@pytest.mark.parametrize("d,F,q", [(6144, 700, 0.45), (8192, 1030, 0.5), (8192, 14336, 0.45),
+                                   (8192, 28672, 0.5),      # 70B-class layer: 112 neurons per workgroup, two rounds of the split-d kernel
+                                   (1024, 40000, 0.45)])    # 157 per workgroup: three rounds
+def test_rows_of_12_and_16_kib_on_the_split_d_kernel(clada, d, F, q):
+    """Batch 1 at d = 6144 and 8192 (bf16): the split-d kernel with x in LDS, balanced and not, and the generic
+    kernel give the same mask and, each, the oracle's output."""
+    cfg, w, x = _case("c2", 15, d, F, 1)
+    tau = _tau_for(w, x, q)
+    layer = clada.Layer(*[to_dev(a, cfg.dtype) for a in w])
+    xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, 0, 0))
+    masks = []
+    for b1 in (1, 2, 3, 0):
+        ctx.set_option("decode.b1", b1)
+        y, idx, cnt, bits = clada.sparse_ffn_decode(ctx, layer, xd, td, want_lists=True)
+        torch.cuda.synchronize()
+        mask = unpack_bits(bits, F)
+        _check_against_oracle(cfg, w, x, tau, y, idx.cpu().numpy(), cnt.cpu().numpy(), mask, f"d={d} F={F} decode.b1={b1}")
+        masks.append(mask)
+        yd = clada.dense_ffn_decode(ctx, layer, xd)
+        assert_close_y(to_np(yd), oracle.dense_decode(*w, x), TOL_Y[cfg.dtype], f"dense twin decode.b1={b1}")
+    assert all(np.array_equal(m, masks[0]) for m in masks)
+    assert not ctx.device_fault()
