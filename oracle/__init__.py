@@ -309,3 +309,41 @@ def relu_prefix_stats(w_in, b_in, w_out, b_out, x, want_y=True, want_pool=True):
     res["y"] = y
     res["abs_act_pool"] = pool
     return res
+
+
+def _relu_args(w_in, b_in, w_out, b_out, x):
+    wi, pi = _f32(w_in)
+    wo, po = _f32(w_out)
+    F, d = wi.shape
+    assert wo.shape == (F, d)
+    xx, px = _f32(x)
+    T = xx.shape[0]
+    assert xx.shape == (T, d)
+    keep = [wi, wo, xx]
+    pbi = pbo = None
+    if b_in is not None:
+        bi, pbi = _f32(b_in)
+        keep.append(bi)
+    if b_out is not None:
+        bo, pbo = _f32(b_out)
+        keep.append(bo)
+    return keep, (pi, pbi, po, pbo, d, F, px, T)
+
+
+def relu_cett(w_in, b_in, w_out, b_out, x, eps):
+    """Per-token CETT of the non-gated ReLU FFN over x [T][d] at cut threshold eps, and its mean."""
+    keep, args = _relu_args(w_in, b_in, w_out, b_out, x)
+    out, po = _out((args[-1],))
+    mean = C.c_double()
+    rc = _load().clada_oracle_relu_cett(*args, C.c_double(float(eps)), po, C.byref(mean))
+    assert rc == 0, rc
+    return out, mean.value
+
+
+def relu_cett_search(w_in, b_in, w_out, b_out, x, bound=0.2):
+    """(tau_base, mean CETT at tau_base, rc) for the ReLU FFN; rc as in cett_search."""
+    keep, args = _relu_args(w_in, b_in, w_out, b_out, x)
+    tau, mean = C.c_double(), C.c_double()
+    rc = _load().clada_oracle_relu_cett_search(*args, C.c_double(float(bound)), C.byref(tau), C.byref(mean))
+    assert rc in (0, 3, 4), rc
+    return tau.value, mean.value, rc

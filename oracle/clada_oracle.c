@@ -708,3 +708,131 @@ int clada_oracle_relu_prefix_stats(const float *w_in, const float *b_in, const f
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * CETT of the non-gated ReLU FFN (the OPT models of the experimental set-up;
+ * section 3.2.2 writes the quantity for a generic MLP):
+ *   a_j = max(0, W_in[j,:].x + b_in[j]),  n_j(x) = a_j W_out[j,:],
+ *   MLP(x) = sum_j n_j(x) + b_out,
+ *   CETT(x; eps) = || sum_{j : a_j < eps} n_j(x) ||_2 / || MLP(x) ||_2
+ * (strict cut as in the decode step, NaN never cut; a token whose output is
+ * zero counts as 0).  The bias belongs to the layer's output, not to any
+ * neuron, so it appears in the denominator only.
+ * ---------------------------------------------------------------------- */
+static double relu_act(const float *w_in, const float *b_in, int j, const float *xt, int d)
+{
+    double g = dot_fd(w_in + (size_t)j * d, xt, d) + (b_in ? (double)b_in[j] : 0.0);
+    return g > 0.0 ? g : (g != g ? g : 0.0);
+}
+
+int clada_oracle_relu_cett(const float *w_in, const float *b_in, const float *w_out, const float *b_out,
+                           int d, int d_ff, const float *x, int T, double eps,
+                           double *cett, double *mean)
+{
+    if (!w_in || !w_out || !x || !cett || d <= 0 || d_ff <= 0 || T <= 0) return 1;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const float *xt = x + (size_t)t * d;
+        double *cut = (double *)calloc((size_t)d, sizeof(double));
+        double *full = (double *)calloc((size_t)d, sizeof(double));
+        if (!cut || !full) { bad = 1; free(cut); free(full); continue; }
+        for (int j = 0; j < d_ff; ++j) {
+            double a = relu_act(w_in, b_in, j, xt, d);
+            const float *wo = w_out + (size_t)j * d;
+            int is_cut = a < eps;
+            for (int i = 0; i < d; ++i) {
+                double n = a * (double)wo[i];
+                full[i] += n;
+                if (is_cut) cut[i] += n;
+            }
+        }
+        double nc = 0.0, nf = 0.0;
+        for (int i = 0; i < d; ++i) {
+            double f = full[i] + (b_out ? (double)b_out[i] : 0.0);
+            nc += cut[i] * cut[i];
+            nf += f * f;
+        }
+        cett[t] = nf > 0.0 ? sqrt(nc) / sqrt(nf) : 0.0;
+        free(cut);
+        free(full);
+    }
+    if (bad) return 2;
+    if (mean) {
+        double s = 0.0;
+        for (int t = 0; t < T; ++t) s += cett[t];
+        *mean = s / (double)T;
+    }
+    return 0;
+}
+
+/* The base-threshold search for the ReLU FFN: as clada_oracle_cett_search, every
+ * distinct activation value a candidate, the last feasible one wins.  (About
+ * half the activations are exactly zero; eps = 0 cuts nothing and is always
+ * feasible.)  Return codes as there. */
+int clada_oracle_relu_cett_search(const float *w_in, const float *b_in, const float *w_out,
+                                  const float *b_out, int d, int d_ff, const float *x, int T,
+                                  double bound, double *tau, double *mean_at_tau)
+{
+    if (!w_in || !w_out || !x || !tau || d <= 0 || d_ff <= 0 || T <= 0) return 1;
+    size_t N = (size_t)T * (size_t)d_ff;
+    cett_event *ev = (cett_event *)malloc(sizeof(cett_event) * N);
+    double *c = (double *)calloc((size_t)T * (size_t)d, sizeof(double));
+    double *den = (double *)malloc(sizeof(double) * (size_t)T);
+    double *cur = (double *)calloc((size_t)T, sizeof(double));
+    if (!ev || !c || !den || !cur) { free(ev); free(c); free(den); free(cur); return 2; }
+
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const float *xt = x + (size_t)t * d;
+        double *full = c + (size_t)t * d;                 /* borrowed as the dense sum, cleared below */
+        for (int j = 0; j < d_ff; ++j) {
+            double a = relu_act(w_in, b_in, j, xt, d);
+            cett_event e = { a, t, j };
+            ev[(size_t)t * d_ff + j] = e;
+            const float *wo = w_out + (size_t)j * d;
+            for (int i = 0; i < d; ++i) full[i] += a * (double)wo[i];
+        }
+        double nf = 0.0;
+        for (int i = 0; i < d; ++i) {
+            double f = full[i] + (b_out ? (double)b_out[i] : 0.0);
+            nf += f * f;
+            full[i] = 0.0;
+        }
+        den[t] = sqrt(nf);
+    }
+    size_t n_ev = 0;
+    for (size_t k = 0; k < N; ++k)
+        if (ev[k].v == ev[k].v) ev[n_ev++] = ev[k];       /* NaN is never cut */
+    qsort(ev, n_ev, sizeof(cett_event), cmp_event);
+
+    int found = 0;
+    double best = 0.0, best_mean = 0.0;
+    size_t k = 0;
+    while (k < n_ev) {
+        double v = ev[k].v;
+        double s = 0.0;
+        for (int t = 0; t < T; ++t) s += cur[t];
+        double m = s / (double)T;
+        if (m <= bound) { found = 1; best = v; best_mean = m; }
+        while (k < n_ev && ev[k].v == v) {
+            int t = ev[k].t, j = ev[k].j;
+            const float *wo = w_out + (size_t)j * d;
+            double *ct = c + (size_t)t * d;
+            double nc = 0.0;
+            for (int i = 0; i < d; ++i) { ct[i] += v * (double)wo[i]; nc += ct[i] * ct[i]; }
+            cur[t] = den[t] > 0.0 ? sqrt(nc) / den[t] : 0.0;
+            ++k;
+        }
+    }
+    double s = 0.0;
+    for (int t = 0; t < T; ++t) s += cur[t];
+    double all_cut = s / (double)T;
+    int rc = 0;
+    if (all_cut <= bound) { rc = 3; best = INFINITY; best_mean = all_cut; }
+    else if (!found) rc = 4;
+    *tau = best;
+    if (mean_at_tau) *mean_at_tau = best_mean;
+    free(ev); free(c); free(den); free(cur);
+    return rc;
+}

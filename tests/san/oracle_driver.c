@@ -71,6 +71,9 @@ int main(void)
             CHECK(clada_oracle_relu_decode(wg, bi, wd, bo, d, F, x, B, tau, NULL, y, act, mask, idx, na));
             CHECK(clada_oracle_relu_decode(wg, NULL, wd, NULL, d, F, x, B, NULL, mask, y, act, NULL, NULL, NULL));
             CHECK(clada_oracle_relu_prefix_stats(wg, bi, wd, bo, d, F, X, T, Y, agg[0], agg[1], agg[2], agg[3], agg[4], pool));
+            CHECK(clada_oracle_relu_cett(wg, bi, wd, bo, d, F, X, T, 0.3, ce, &mean));
+            CHECK(clada_oracle_relu_cett(wg, NULL, wd, NULL, d, F, X, T, INFINITY, ce, NULL));
+            { int rc = clada_oracle_relu_cett_search(wg, bi, wd, bo, d, F, X, T, 0.2, &tb, &mean); if (rc != 0 && rc != 3 && rc != 4) { printf("relu_cett_search -> %d\n", rc); fails++; } }
             free(wg); free(wu); free(wd); free(x); free(X); free(bi); free(bo); free(y); free(act); free(tau); free(Y);
             for (int i = 0; i < 5; ++i) free(agg[i]);
             free(pool); free(ce); free(mask); free(idx); free(na);

@@ -66,8 +66,27 @@ RELU_PINS = [
     lambda: t_relu.test_prefix_stats_match_numpy_and_the_decode_function(),
 ]
 
+RELU_CETT_PINS = [
+    lambda: t_relu.test_cett_hand_case(),
+    lambda: t_relu.test_cett_is_dense_minus_sparse_over_dense_and_search_is_brute_force(0),
+    lambda: t_relu.test_cett_search_takes_the_last_feasible_value_not_the_first_crossing(),
+]
+
 # (what is planted, text to find, replacement, pins that must notice)
 MUTATIONS = [
+    ("ReLU CETT denominator without the output bias",
+     "            double f = full[i] + (b_out ? (double)b_out[i] : 0.0);\n            nc += cut[i] * cut[i];",
+     "            double f = full[i];\n            nc += cut[i] * cut[i];", RELU_CETT_PINS),
+    ("ReLU CETT cut not strict", "            int is_cut = a < eps;", "            int is_cut = a <= eps;", RELU_CETT_PINS),
+    ("ReLU CETT numerator carries the output bias",
+     "                if (is_cut) cut[i] += n;\n            }\n        }\n        double nc = 0.0, nf = 0.0;\n        for (int i = 0; i < d; ++i) {\n            double f = full[i] + (b_out",
+     "                if (is_cut) cut[i] += n;\n            }\n        }\n        double nc = 0.0, nf = 0.0;\n        for (int i = 0; i < d; ++i) {\n            cut[i] += (b_out ? (double)b_out[i] : 0.0);\n            double f = full[i] + (b_out", RELU_CETT_PINS),
+    ("ReLU CETT search stops at the first infeasible candidate",
+     "        if (m <= bound) { found = 1; best = v; best_mean = m; }\n        while (k < n_ev && ev[k].v == v) {\n            int t = ev[k].t, j = ev[k].j;\n            const float *wo",
+     "        if (m <= bound) { found = 1; best = v; best_mean = m; } else if (found) break;\n        while (k < n_ev && ev[k].v == v) {\n            int t = ev[k].t, j = ev[k].j;\n            const float *wo", RELU_CETT_PINS),
+    ("ReLU CETT search denominator without the bias",
+     "            double f = full[i] + (b_out ? (double)b_out[i] : 0.0);\n            nf += f * f;\n            full[i] = 0.0;",
+     "            double f = full[i];\n            nf += f * f;\n            full[i] = 0.0;", RELU_CETT_PINS),
     ("SiLU with the exponent's sign flipped",
      "return g / (1.0 + exp(-g));", "return g / (1.0 + exp(g));", FFN_PINS),
     ("up-projection factor dropped in the decode path",
@@ -167,7 +186,7 @@ def test_planted_mistake_is_caught(tmp_path, what, find, repl, pins):
 
 
 def test_unmutated_oracle_passes_every_pin_used_above():
-    for pins in (FFN_PINS, SIGNAL_PINS, CETT_PINS, MASK_PINS, RELU_PINS, GEGLU_PINS):
+    for pins in (FFN_PINS, SIGNAL_PINS, CETT_PINS, MASK_PINS, RELU_PINS, GEGLU_PINS, RELU_CETT_PINS):
         for pin in pins:
             pin()
 

@@ -77,3 +77,58 @@ def test_prefix_stats_match_numpy_and_the_decode_function():
     np.testing.assert_allclose(r["A"], np.sqrt((a * a).sum(0)) * np.linalg.norm(wo.astype(np.float64), axis=1), rtol=1e-12)
     # the prefill output is the dense decode of every prefix token
     np.testing.assert_allclose(r["y"], oracle.relu_decode(wi, bi, wo, bo, x)["y"], rtol=1e-12, atol=1e-13)
+
+
+def test_cett_hand_case():
+    """The hand case above: a = (1.5, 0, 0.75), rows (1,1), (5,5), (2,-2), b_out = (0.125, -0.125).
+    MLP(x) = (1.5 + 1.5 + 0.125, 1.5 - 1.5 - 0.125) = (3.125, -0.125).  eps = 1: neurons 1 (a = 0) and 2 are
+    cut, their contribution is 0.75 (2, -2) = (1.5, -1.5); eps = 0.75 cuts only the zero neuron (strict)."""
+    wi = np.array([[1, 0], [-1, -1], [0, 0.5]], np.float32)
+    bi = np.array([0.5, 1.0, -0.25], np.float32)
+    wo = np.array([[1, 1], [5, 5], [2, -2]], np.float32)
+    bo = np.array([0.125, -0.125], np.float32)
+    x = np.array([[1, 2]], np.float32)
+    den = np.hypot(3.125, 0.125)
+    c, m = oracle.relu_cett(wi, bi, wo, bo, x, 1.0)
+    assert c[0] == pytest.approx(np.hypot(1.5, 1.5) / den, rel=1e-15) and m == c[0]
+    assert oracle.relu_cett(wi, bi, wo, bo, x, 0.75)[0][0] == 0.0
+    assert oracle.relu_cett(wi, bi, wo, bo, x, 0.0)[0][0] == 0.0
+    c, _ = oracle.relu_cett(wi, bi, wo, bo, x, np.inf)               # everything cut: the bias stays
+    assert c[0] == pytest.approx(np.hypot(3.0, 0.0) / den, rel=1e-15)
+    c, _ = oracle.relu_cett(wi, None, wo, None, x, np.inf)           # without biases: a = (1, 0, 1), all cut = the output
+    assert c[0] == pytest.approx(1.0, rel=1e-15)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_cett_is_dense_minus_sparse_over_dense_and_search_is_brute_force(seed):
+    wi, bi, wo, bo, x = _toy(seed, 24, 40, 6)
+    act = oracle.relu_decode(wi, bi, wo, bo, x)["act"]
+    dense = oracle.relu_decode(wi, bi, wo, bo, x)["y"]
+    cands = np.unique(act)
+    means = []
+    for eps in list(cands) + [np.inf]:
+        kept = oracle.relu_decode(wi, bi, wo, bo, x, tau=eps)["y"]                 # keeps a >= eps, adds b_out
+        want = np.linalg.norm(dense - kept, axis=1) / np.linalg.norm(dense, axis=1)
+        got, mean = oracle.relu_cett(wi, bi, wo, bo, x, eps)
+        np.testing.assert_allclose(got, want, rtol=1e-9, atol=1e-12)
+        assert mean == pytest.approx(want.mean(), rel=1e-9, abs=1e-12)
+        means.append(want.mean())
+    assert means[0] == 0.0                                                           # the smallest value cuts nothing
+    for bound in (0.0, 0.05, 0.2, 0.5):
+        feasible = [i for i in range(len(cands)) if means[i] <= bound * (1 + 1e-12)]
+        tau, mean, rc = oracle.relu_cett_search(wi, bi, wo, bo, x, bound)
+        assert rc == 0 and tau == cands[feasible[-1]] and mean == pytest.approx(means[feasible[-1]], rel=1e-9, abs=1e-12)
+    tau, mean, rc = oracle.relu_cett_search(wi, None, wo, None, x, 0.999999)         # without a bias cutting all loses all: 1 > bound
+    assert rc == 0 and np.isfinite(tau)
+
+
+def test_cett_search_takes_the_last_feasible_value_not_the_first_crossing():
+    """Constructed: a = (1, 2, 3), output rows (1,0), (-0.5,0), (0,1), so MLP(x) = (0, 3).  eps = 2 cuts the first
+    neuron (CETT 1/3), eps = 3 cuts the first two, whose contributions cancel (CETT 0): with bound 0.2 the
+    feasible values are 1 and 3, and the maximum is 3 although 2 already broke the bound."""
+    wi = np.array([[1, 0], [2, 0], [0, 3]], np.float32)
+    wo = np.array([[1, 0], [-0.5, 0], [0, 1]], np.float32)
+    x = np.array([[1, 1]], np.float32)
+    assert [oracle.relu_cett(wi, None, wo, None, x, e)[1] for e in (1, 2, 3)] == [0.0, pytest.approx(1 / 3), 0.0]
+    tau, mean, rc = oracle.relu_cett_search(wi, None, wo, None, x, 0.2)
+    assert (tau, mean, rc) == (3.0, 0.0, 0)
