@@ -112,8 +112,9 @@ size_t clada_workspace_bytes(int32_t d, int32_t d_ff, int32_t B, int32_t T, int3
  *   y_b = sum_{j kept} a_bj W_out[j,:] + b_out.
  * For it w_gate holds W_in [d_ff][d], w_down holds W_out neuron-major [d_ff][d]
  * (HF fc2.weight transposed), w_up is ignored; b_in [d_ff] and b_out [d] are fp32
- * device arrays or NULL (zero).  Supported by clada_prefix_stats (h = a), the decode
- * calls and clada_static_ffn_decode; the CETT calls return CLADA_ERR_VALUE for it.
+ * device arrays or NULL (zero).  Supported by every entry point; in the CETT calls
+ * n_j(x) = a_j W_out[j,:] and MLP(x) = sum_j n_j(x) + b_out (the bias is the layer's,
+ * not a neuron's: it enters the denominator only).
  * CLADA_FFN_GEGLU: the gated FFN of the Gemma model the paper also evaluates -- as
  * CLADA_FFN_SWIGLU in every respect (three matrices, no biases, every entry point)
  * except sigma = GELU in its tanh form,

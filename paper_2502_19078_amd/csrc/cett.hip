@@ -23,7 +23,7 @@ k_cett_begin(CettState *st, const float *__restrict__ rowsq, int n_tn, int T, fl
              int search, float eps)
 {
     const int t = blockIdx.x * 256 + threadIdx.x;
-    if (t < T) {
+    if (t < T && rowsq) {                 // (the non-gated family's denominators come from k_cett_row_norm)
         float s = 0.0f;
         for (int i = 0; i < n_tn; ++i) s += rowsq[(size_t)i * T + t];
         den[t] = sqrtf(s);
@@ -35,6 +35,27 @@ k_cett_begin(CettState *st, const float *__restrict__ rowsq, int n_tn, int T, fl
         st->mean_lo = 0.0f;
         st->mean_mid = 0.0f;
     }
+}
+
+// den[t] = || y[t,:] ||_2 of a stored output (layer dtype): the denominators of the non-gated family, whose
+// output carries the bias b_out that no neuron owns (the projection's own epilogue adds it to y; the row-norm
+// epilogues do not know about it).  One wave per token: lane-strided sums of squares, then a fixed butterfly.
+template <int ES>
+__global__ void __launch_bounds__(256)
+k_cett_row_norm(const char *__restrict__ y, int T, int d, float *__restrict__ den)
+{
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (t >= T) return;
+    const char *row = y + (size_t)t * d * ES;
+    float s = 0.0f;
+    for (int i = lane; i < d; i += 64) {
+        const float v = ES == 4 ? reinterpret_cast<const float *>(row)[i]
+                                : __uint_as_float((unsigned int)reinterpret_cast<const unsigned short *>(row)[i] << 16);
+        s = fmaf(v, v, s);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) den[t] = sqrtf(s);
 }
 
 // hcut = h where |a| < eps (strict, NaN never cut), 0 elsewhere; eps = the probe in the state.
@@ -131,7 +152,7 @@ __global__ void k_cett_finish(const CettState *st, float *tau_out, float *mean_o
 
 struct CettWs {
     float *part, *pool, *rowsq_den, *rowsq_num, *den, *splitk;
-    char *h, *hcut;
+    char *h, *hcut, *ytmp;
     CettState *state;
 };
 
@@ -150,6 +171,7 @@ CettWs carve(char *ws, int d, int F, int T)
     w.rowsq_num = reinterpret_cast<float *>(take(sizeof(float) * n_tn * T));
     w.den = reinterpret_cast<float *>(take(sizeof(float) * (size_t)T));
     w.state = reinterpret_cast<CettState *>(take(sizeof(CettState)));
+    w.ytmp = take((size_t)T * d * 4);
     const size_t sk = clada_ws_down_splitk(d, F, T);
     w.splitk = sk ? reinterpret_cast<float *>(take(sk)) : nullptr;
     return w;
@@ -159,7 +181,6 @@ clada_status check_common(clada_ctx *ctx, const clada_layer *layer, const void *
 {
     if (!ctx) return CLADA_ERR_NULL;
     clada_status st = clada_check_layer(ctx, layer);
-    if (st == CLADA_OK) st = clada_require_swiglu(ctx, layer, "the CETT calls");
     if (st != CLADA_OK) return st;
     if (!x) return clada_fail(ctx, CLADA_ERR_NULL, "x_val is NULL");
     if (T < 1 || T > (1 << 20)) return clada_fail(ctx, CLADA_ERR_SHAPE, "T=%d outside [1,2^20]", T);
@@ -176,8 +197,20 @@ clada_status begin(clada_ctx *ctx, const clada_layer *layer, const void *x, int 
 {
     const int n_tn = clada_prefix_col_tiles(layer->d);
     CLADA_CHECK_HIP(ctx, clada_prefix_gateup(layer, x, T, w.part, w.pool, w.h, ctx->opt_prefix_tile, stream));
-    CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.h, T, nullptr, w.rowsq_den, w.splitk, ctx->opt_prefix_tile, stream));
-    hipLaunchKernelGGL(k_cett_begin, dim3((T + 255) / 256), dim3(256), 0, stream, w.state, w.rowsq_den, n_tn, T,
+    const float *rowsq_den = w.rowsq_den;
+    if (layer->kind == CLADA_FFN_RELU) {
+        // || sum_j a_j W_out[j,:] + b_out ||: through the stored output, which carries the bias
+        CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.h, T, w.ytmp, nullptr, w.splitk, ctx->opt_prefix_tile, stream));
+        if (layer->dtype == CLADA_BF16)
+            hipLaunchKernelGGL(k_cett_row_norm<2>, dim3((T + 3) / 4), dim3(256), 0, stream, w.ytmp, T, layer->d, w.den);
+        else
+            hipLaunchKernelGGL(k_cett_row_norm<4>, dim3((T + 3) / 4), dim3(256), 0, stream, w.ytmp, T, layer->d, w.den);
+        CLADA_CHECK_HIP(ctx, hipGetLastError());
+        rowsq_den = nullptr;
+    } else {
+        CLADA_CHECK_HIP(ctx, clada_prefix_down(layer, w.h, T, nullptr, w.rowsq_den, w.splitk, ctx->opt_prefix_tile, stream));
+    }
+    hipLaunchKernelGGL(k_cett_begin, dim3((T + 255) / 256), dim3(256), 0, stream, w.state, rowsq_den, n_tn, T,
                        w.den, search, eps);
     CLADA_CHECK_HIP(ctx, hipGetLastError());
     return CLADA_OK;
@@ -212,7 +245,8 @@ size_t clada_ws_cett(int32_t d, int32_t d_ff, int32_t T)
     const size_t Fp = align_up((size_t)d_ff, 64);
     return align_up(sizeof(float) * 4 * n_tm * d_ff, 256) + align_up(sizeof(float) * (size_t)T * d_ff, 256) +
            2 * align_up((size_t)T * Fp * 4, 256) + 2 * align_up(sizeof(float) * n_tn * T, 256) +
-           align_up(sizeof(float) * (size_t)T, 256) + 256 + clada_ws_down_splitk(d, d_ff, T);
+           align_up(sizeof(float) * (size_t)T, 256) + 256 + align_up((size_t)T * d * 4, 256) +
+           clada_ws_down_splitk(d, d_ff, T);
 }
 
 extern "C" clada_status clada_cett_eval(clada_ctx *ctx, const clada_layer *layer, const void *x_val, int32_t T,

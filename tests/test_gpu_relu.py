@@ -140,14 +140,59 @@ def test_relu_prefix_stats_parity_and_calibration(clada, cfg_name, d, F, T, tile
     assert float(tau.item()) > 0.0                      # above the ReLU's own zeros
 
 
-def test_relu_rejected_by_the_cett_calls(clada):
-    from paper_2502_19078_amd.binding import CladaError
-    cfg = synth.CONFIGS["o27"]
-    w = synth.relu_layer(cfg, 1, 1, d=256, d_ff=128)
-    ctx = clada.Context(0, clada.workspace_bytes(256, 128, 1, 64, 0))
+# as in test_gpu_cett.py; for bf16 the denominator additionally goes through the stored (bf16) output
+TOL_CETT = {"f32": 2e-5, "bf16": 3 * 2.0 ** -9}
+
+
+@pytest.mark.parametrize("cfg_name,d,F,T,tile", [("o27", 2560, 700, 300, 1), ("o27", 2560, 1024, 257, 2),
+                                                 ("o350", 1024, 4096, 512, 0), ("c1", 96, 200, 130, 0), ("c1", 8, 5, 1, 0)])
+def test_relu_cett_eval_and_search_parity(clada, cfg_name, d, F, T, tile):
+    """CETT of the non-gated family: n_j = a_j W_out[j,:], the output bias in the denominator only.  The cut
+    set is read off the device's own activation pool (band-validated) and the oracle evaluated on it."""
+    cfg = synth.CONFIGS[cfg_name]
+    dt = cfg.dtype
+    w = synth.relu_layer(cfg, 6, 3, d=d, d_ff=F)
+    if dt == "bf16":
+        w = (synth.store(w[0], dt), w[1], synth.store(w[2], dt), w[3])
+    X = synth.prefix_hidden(cfg, 6, 3, T=T, d=d)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, 0, T, 0))
+    ctx.set_option("prefix.tile", tile)
     layer = _layer(clada, cfg, w)
-    X = to_dev(synth.prefix_hidden(cfg, 1, 1, T=64, d=256), cfg.dtype)
-    with pytest.raises(CladaError):
-        clada.threshold_search_cett(ctx, layer, X)
-    with pytest.raises(CladaError):
-        clada.cett_eval(ctx, layer, X, 0.1)
+    Xd = to_dev(X, dt)
+    a_ref = oracle.relu_prefix_stats(*w, X, want_y=False)["abs_act_pool"]
+    pool_gpu = clada.prefix_stats(ctx, layer, Xd, want_y=False).abs_act_pool.cpu().numpy()
+    dense = oracle.relu_decode(*w, X)["y"]
+    nd = np.linalg.norm(dense, axis=1)
+    pos = np.sort(a_ref[a_ref > 0])
+    for qq in (0.0, 0.3, 0.8):
+        eps = float(np.float32(pos[int(qq * (len(pos) - 1))] * 1.00037 + 1e-9))
+        got, mean = clada.cett_eval(ctx, layer, Xd, eps)
+        torch.cuda.synchronize()
+        cut_gpu = pool_gpu < np.float32(eps)
+        flips = cut_gpu != (a_ref < eps)
+        assert not (flips & (np.abs(a_ref - eps) > band_width(eps))).any(), "cut sets differ outside the band"
+        kept = oracle.relu_decode(*w, X, mask=~cut_gpu)["y"]                    # keeps the rest, adds b_out
+        ref = np.where(nd > 0, np.linalg.norm(dense - kept, axis=1) / np.where(nd > 0, nd, 1.0), 0.0)
+        np.testing.assert_allclose(to_np(got), ref, rtol=TOL_CETT[dt], atol=1e-6, err_msg=f"q={qq}")
+        assert float(mean.item()) == pytest.approx(ref.mean(), rel=TOL_CETT[dt], abs=1e-6)
+        if not flips.any():
+            np.testing.assert_allclose(to_np(got), oracle.relu_cett(*w, X, eps)[0], rtol=TOL_CETT[dt], atol=1e-6)
+    got, mean = clada.cett_eval(ctx, layer, Xd, 0.0)
+    assert torch.all(got == 0) and float(mean.item()) == 0.0
+    # search: feasible just below, infeasible just above (both by the oracle), near the oracle's maximum
+    for bound in (0.2, 0.05):
+        tau_d, mean_d = clada.threshold_search_cett(ctx, layer, Xd, bound)
+        torch.cuda.synchronize()
+        tau, mean = float(tau_d.item()), float(mean_d.item())
+        tol = TOL_CETT[dt] if dt == "bf16" else 1e-4
+        tau_ref, _, rc = oracle.relu_cett_search(*w, X, bound)
+        m_below = oracle.relu_cett(*w, X, tau * (1 - 1e-5))[1]
+        assert m_below <= bound * (1 + tol) + 1e-6
+        assert mean == pytest.approx(m_below, rel=tol, abs=1e-6) and mean <= bound
+        if rc == 3:     # even cutting every neuron stays within the bound (the bias carries the output): no maximum
+            assert tau > a_ref.max()
+            continue
+        m_above = oracle.relu_cett(*w, X, tau * (1 + 1e-5))[1]
+        assert m_above >= bound * (1 - tol) - 1e-6
+        if rc == 0 and T * F >= 20000:
+            assert tau == pytest.approx(tau_ref, rel=2e-3 if dt == "bf16" else 1e-4)
