@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--temperature", type=float, default=1.0, help="divide the Zipf logits by this (peaked < 1 < flat)")
     ap.add_argument("--tau-s", type=float, default=None, help="fix the surprisal threshold (default: median of the run's own stream)")
     ap.add_argument("--tau-h", type=float, default=None, help="fix the entropy threshold (default: median of the run's own stream)")
+    ap.add_argument("--regimes", default="natural,off,on,neg,stack",
+                    help="which measurements to run besides the natural regime and the dense twin (comma list of off, on, "
+                         "neg, stack); a profiler run restricts them so that a kernel's average covers one regime")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run only a short fixed call sequence (for rocprofv3 --pmc counter runs) and exit")
     ap.add_argument("--prefill-probe", action="store_true",
@@ -154,7 +157,7 @@ def main():
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     # the paper's own calibration (error-bounded search, bound 0.2) on the same prefix, for comparison
     cett_info = None
-    if not relu:
+    if True:
         clada.threshold_search_cett(ctx, layers[L - 1], Xp, 0.2)
         e0.record()
         tau_cett, mean_cett = clada.threshold_search_cett(ctx, layers[L - 1], Xp, 0.2)
@@ -330,13 +333,14 @@ def main():
         res["bytes_probe"] = (F + (nmat - 1.0) * cnt_np[:nprobe, :, 0].astype(np.float64).mean()) * d * es
         return res
 
+    want = set(args.regimes.split(","))
     nat = measure_regime(tau_s, tau_H)            # the method as defined: thresholds follow the signals
-    off = measure_regime(INF, INF)                # indicators off: tau_final = tau_base (target sparsity)
-    on = measure_regime(-INF, -INF, detail=False)                       # both indicators always on: factor 1.92
-    neg = measure_regime(tau_s, tau_H, lam_neg, gam_neg, detail=False)  # natural, coefficients -0.80 / -0.12
+    off = measure_regime(INF, INF) if "off" in want else None          # indicators off: tau_final = tau_base (target sparsity)
+    on = measure_regime(-INF, -INF, detail=False) if "on" in want else None                       # both indicators always on: factor 1.92
+    neg = measure_regime(tau_s, tau_H, lam_neg, gam_neg, detail=False) if "neg" in want else None  # natural, coefficients -0.80 / -0.12
     # ---- the whole-stack entry point (B = 1): the same step as signals+thresholds and ONE persistent launch
     stack = None
-    if B == 1:
+    if B == 1 and "stack" in want and off is not None:
         arr = binding.layer_array(layers)
         x_flat, y_flat, tau_flat = x_cur.view(L, d), y_out.view(L, d), tau_final.view(L)
 
@@ -448,9 +452,9 @@ def main():
         # single graph replays (inputs refreshed outside the bracket)
         "replays": {"n": REPLAYS, "ms_median": round(nat["ms_median"], 4), "ms_min": round(nat["ms_min"], 4),
                     "dense_ms_median": round(dense_med, 4), "dense_ms_min": round(dense_min, 4)},
-        "value_at_target_sparsity": round(B * 1e3 / off["ms"], 2),   # indicators off: rho = the configuration's target
+        "value_at_target_sparsity": round(B * 1e3 / off["ms"], 2) if off else None,   # indicators off: rho = the configuration's target
         "device_fault": False,
-        "regime_indicators_off": {
+        "regime_indicators_off": None if off is None else {
             "ms_per_step": round(off["ms"], 4), "tokens_per_s": round(B * 1e3 / off["ms"], 2),
             "ms_median": round(off["ms_median"], 4), "ms_min": round(off["ms_min"], 4),
             "step_frac_of_hbm_peak": round(off["bytes_layer"] * L / (off["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -464,8 +468,8 @@ def main():
             "kernel_frac": round(off["bytes_probe"] / (off["main_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
             "call_gbs": round(off["bytes_probe"] / (off["call_us"] * 1e-6) / 1e9, 1),
             "call_frac": round(off["bytes_probe"] / (off["call_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
-        "regime_indicators_on": _light(on, ms_dense, ideal, B, L),
-        "regime_negative_coefficients": dict(_light(neg, ms_dense, ideal, B, L), **{"lambda": -0.80, "gamma": -0.12}),
+        "regime_indicators_on": _light(on, ms_dense, ideal, B, L) if on else None,
+        "regime_negative_coefficients": dict(_light(neg, ms_dense, ideal, B, L), **{"lambda": -0.80, "gamma": -0.12}) if neg else None,
         "stack_entry": stack,
         "step_gbs_on_bytes_touched": round(bytes_layer * L / (ms_sparse * 1e-3) / 1e9, 1),
         "dense_step_gbs": round(bytes_dense * L / (ms_dense * 1e-3) / 1e9, 1),
