@@ -518,7 +518,7 @@ def main():
 
 def pmc_probe(cfg, args, clada, binding, synth, torch, dev):
     """Short fixed workload for hardware-counter runs: 4 seeded layers of the configuration, 3 rounds of
-    sparse calls at two sparsities (0.45 and 0.62), 4 dense-twin calls, 3 copies of a 256 MiB buffer
+    sparse calls at three sparsities (0.45, 0.62 and 0.66), 4 dense-twin calls, 3 copies of a 256 MiB buffer
     (the known-size transfer the FETCH_SIZE / WRITE_SIZE counters are scaled by).  Batch 1 unless --batch
     is given (then --shared-frac applies to the tokens of the batch)."""
     d, F = cfg.d, cfg.d_ff
@@ -539,7 +539,7 @@ def pmc_probe(cfg, args, clada, binding, synth, torch, dev):
     st = clada.prefix_stats(ctx, layers[0], to_dev(synth.prefix_hidden(cfg, args.seed, 0)), want_y=False)
     src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
-    for q in (0.45, 0.62):
+    for q in (0.45, 0.62, 0.66):
         tau = clada.threshold_calibrate(ctx, st.abs_act_pool, q).expand(B).contiguous()
         kept = []
         for _ in range(3):
