@@ -48,8 +48,9 @@ int main()
     EXPECT(clada_threshold_search_cett(ctx, &ok, p, 4, 0.2f, 31, (float *)p, (float *)p, nullptr), CLADA_ERR_WORKSPACE);
     EXPECT(clada_threshold_search_cett(ctx, &ok, p, 4, 0.2f, 0, (float *)p, (float *)p, nullptr), CLADA_ERR_VALUE);
     EXPECT(clada_cett_eval(ctx, &bad, p, 4, 0.1f, (float *)p, (float *)p, nullptr), CLADA_ERR_WORKSPACE);
-    bad = ok; bad.kind = CLADA_FFN_RELU;
-    EXPECT(clada_cett_eval(ctx, &bad, p, 4, 0.1f, (float *)p, (float *)p, nullptr), CLADA_ERR_VALUE);
+    bad = ok; bad.kind = CLADA_FFN_RELU; bad.w_up = nullptr;      // the non-gated family is accepted by the CETT calls
+    EXPECT(clada_cett_eval(ctx, &bad, p, 4, 0.1f, (float *)p, (float *)p, nullptr), CLADA_ERR_WORKSPACE);
+    EXPECT(clada_threshold_search_cett(ctx, &bad, p, 4, 0.2f, 31, (float *)p, (float *)p, nullptr), CLADA_ERR_WORKSPACE);
     EXPECT(clada_cognitive_signals(ctx, p, CLADA_F32, 1, 10, (const int32_t *)p, (float *)p, (float *)p, nullptr), CLADA_ERR_WORKSPACE);
     EXPECT(clada_cognitive_signals(ctx, p, 5, 1, 10, (const int32_t *)p, (float *)p, (float *)p, nullptr), CLADA_ERR_DTYPE);
     EXPECT(clada_cognitive_signals(ctx, p, CLADA_F32, 65, 10, (const int32_t *)p, (float *)p, (float *)p, nullptr), CLADA_ERR_SHAPE);
@@ -58,7 +59,39 @@ int main()
     EXPECT(clada_static_mask_topk(ctx, (const float *)p, 32, 33, (int32_t *)p, (int32_t *)p, nullptr), CLADA_ERR_VALUE);
     EXPECT(clada_mask_pack(ctx, (const int32_t *)p, (const int32_t *)p, 0, (uint32_t *)p, nullptr), CLADA_ERR_SHAPE);
     EXPECT(clada_mask_unpack(ctx, (const uint32_t *)p, 32, (int32_t *)p, (int32_t *)p, nullptr), CLADA_ERR_WORKSPACE);
+    // fused signals + thresholds, the variant on the static scratch array, sparse mask storage, whole-stack calls
+    EXPECT(clada_signals_threshold(ctx, p, CLADA_F32, 1, 10, (const int32_t *)p, (const float *)p, (const float *)p,
+                                   (const float *)p, 0, 0.f, 0.f, (float *)p, (float *)p, (float *)p, nullptr), CLADA_ERR_SHAPE);
+    EXPECT(clada_signals_threshold(ctx, p, CLADA_F32, 1, 10, (const int32_t *)p, (const float *)p, (const float *)p,
+                                   (const float *)p, 2, 0.f, 0.f, (float *)p, (float *)p, nullptr, nullptr), CLADA_ERR_NULL);
+    EXPECT(clada_signals_threshold(ctx, p, CLADA_F32, 1, 10, (const int32_t *)p, (const float *)p, (const float *)p,
+                                   (const float *)p, 2, 0.f, 0.f, (float *)p, (float *)p, (float *)p, nullptr), CLADA_ERR_WORKSPACE);
+    EXPECT(clada_cognitive_signals_static(ctx, p, CLADA_F32, 1, CLADA_STATIC_SIGNALS_MAX_V + 1, (const int32_t *)p,
+                                          (float *)p, (float *)p, nullptr), CLADA_ERR_SHAPE);
+    EXPECT(clada_cognitive_signals_static(ctx, p, 5, 1, 10, (const int32_t *)p, (float *)p, (float *)p, nullptr), CLADA_ERR_DTYPE);
+    EXPECT(clada_cognitive_signals_static(nullptr, p, CLADA_F32, 1, 10, (const int32_t *)p, (float *)p, (float *)p, nullptr), CLADA_ERR_NULL);
+    if (clada_mask_sparse_max_bytes(0) != 0 || clada_mask_sparse_max_bytes(100) != 100 ||
+        clada_mask_sparse_max_bytes(262144) != 262144 + 2048 + 16) ++fails;
+    EXPECT(clada_mask_sparse_encode(ctx, (const uint32_t *)p, nullptr, 0, (uint8_t *)p, 16, (int32_t *)p, nullptr), CLADA_ERR_SHAPE);
+    EXPECT(clada_mask_sparse_encode(ctx, (const uint32_t *)p, nullptr, 64, (uint8_t *)p, -1, (int32_t *)p, nullptr), CLADA_ERR_SHAPE);
+    EXPECT(clada_mask_sparse_encode(ctx, (const uint32_t *)p, nullptr, 64, nullptr, 16, (int32_t *)p, nullptr), CLADA_ERR_NULL);
+    EXPECT(clada_mask_sparse_encode(ctx, (const uint32_t *)p, nullptr, 64, (uint8_t *)p, 16, (int32_t *)p, nullptr), CLADA_ERR_WORKSPACE);
+    EXPECT(clada_mask_sparse_decode(ctx, (const uint8_t *)p, (const int32_t *)p, 16, nullptr, 1 << 30, (uint32_t *)p, nullptr), CLADA_ERR_SHAPE);
+    EXPECT(clada_mask_sparse_decode(ctx, (const uint8_t *)p, nullptr, 16, nullptr, 64, (uint32_t *)p, nullptr), CLADA_ERR_NULL);
+    EXPECT(clada_mask_sparse_decode(ctx, (const uint8_t *)p, (const int32_t *)p, 16, nullptr, 64, (uint32_t *)p, nullptr), CLADA_ERR_WORKSPACE);
+    {
+        clada_layer two[2] = {ok, ok};
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, nullptr, 2, p, (const float *)p, p, nullptr, nullptr), CLADA_ERR_NULL);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 0, p, (const float *)p, p, nullptr, nullptr), CLADA_ERR_SHAPE);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 2, p, nullptr, p, nullptr, nullptr), CLADA_ERR_NULL);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 2, p, (const float *)p, p, nullptr, nullptr), CLADA_ERR_WORKSPACE);
+        EXPECT(clada_dense_ffn_stack_decode(ctx, two, 2, p, p, nullptr), CLADA_ERR_WORKSPACE);
+        two[1].d_ff = ok.d_ff * 2;
+        EXPECT(clada_dense_ffn_stack_decode(ctx, two, 2, p, p, nullptr), CLADA_ERR_SHAPE);
+    }
     // options, error text, fault query, graph helpers
+    EXPECT(clada_set_option(ctx, "decode.stack", 1), CLADA_OK);
+    EXPECT(clada_set_option(ctx, "decode.stack", 2), CLADA_ERR_VALUE);
     EXPECT(clada_set_option(ctx, "decode.b1", 3), CLADA_OK);
     EXPECT(clada_set_option(ctx, "decode.b1", 4), CLADA_ERR_VALUE);
     EXPECT(clada_set_option(ctx, "prefix.tile", 2), CLADA_OK);
