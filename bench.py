@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--temperature", type=float, default=1.0, help="divide the Zipf logits by this (peaked < 1 < flat)")
     ap.add_argument("--tau-s", type=float, default=None, help="fix the surprisal threshold (default: median of the run's own stream)")
     ap.add_argument("--tau-h", type=float, default=None, help="fix the entropy threshold (default: median of the run's own stream)")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="B = 1: time the step through L per-layer calls on one stream instead of the whole-stack call")
     ap.add_argument("--regimes", default="natural,off,on,neg,stack",
                     help="which measurements to run besides the natural regime and the dense twin (comma list of off, on, "
                          "neg, stack); a profiler run restricts them so that a kernel's average covers one regime")
@@ -207,9 +209,23 @@ def main():
                                               tau_base.data_ptr(), lam_t.data_ptr(), gam_t.data_ptr(), L, ts, th,
                                               sur.data_ptr(), ent.data_ptr(), tau_final.data_ptr(), sp))
 
-    def step_body(dense, ts, th, lam_t, gam_t, counts=None):
+    # B = 1: the FFN stack of a step goes through the whole-stack call (the layers of the workload are
+    # independent problems; by default the library runs even and odd layers on two streams); the per-layer
+    # calls are measured beside it.  B >= 2: per-layer calls.
+    use_stack = B == 1 and not args.per_layer
+    arr = binding.layer_array(layers)
+    x_flat, y_flat, tau_flat = x_cur.view(L * B, d), y_out.view(L * B, d), tau_final.view(L * B)
+
+    def step_body(dense, ts, th, lam_t, gam_t, counts=None, per_layer=False):
         sp = stream_ptr()
         signals_and_thresholds(ts, th, lam_t, gam_t, sp)
+        if use_stack and not per_layer and counts is None:
+            if dense:
+                ctx.check(lib.clada_dense_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), y_flat.data_ptr(), sp))
+            else:
+                ctx.check(lib.clada_sparse_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), tau_flat.data_ptr(),
+                                                            y_flat.data_ptr(), None, sp))
+            return
         for l in range(L):
             if dense:
                 ctx.check(lib.clada_dense_ffn_decode(h, C.byref(cl[l]), x_cur[l].data_ptr(), B,
@@ -226,17 +242,17 @@ def main():
 
     side = torch.cuda.Stream()
 
-    def make_runner(dense, ts, th, lam_t, gam_t):
+    def make_runner(dense, ts, th, lam_t, gam_t, per_layer=False):
         """One decode step as a replayable HIP graph (or an eager call sequence with --no-graph)."""
         if args.no_graph:
-            return lambda: step_body(dense, ts, th, lam_t, gam_t)
+            return lambda: step_body(dense, ts, th, lam_t, gam_t, per_layer=per_layer)
         load_inputs(0)
         torch.cuda.synchronize()
         with torch.cuda.stream(side):
-            step_body(dense, ts, th, lam_t, gam_t)      # eager once: first calls set kernel attributes
+            step_body(dense, ts, th, lam_t, gam_t, per_layer=per_layer)      # eager once: first calls set kernel attributes
             side.synchronize()
             clada.graph_begin(ctx)                      # the library's own capture (clada_graph_*)
-            step_body(dense, ts, th, lam_t, gam_t)
+            step_body(dense, ts, th, lam_t, gam_t, per_layer=per_layer)
             g = clada.graph_end(ctx)
         torch.cuda.synchronize()
         return g.launch                                 # replays on the current stream; the bound method keeps g alive
@@ -278,10 +294,10 @@ def main():
             print(f"bench.py: invalid output after {what} (device fault flag or non-finite y)", file=sys.stderr)
             sys.exit(3)
 
-    def measure_regime(ts, th, lam_t=lam, gam_t=gam, detail=True):
+    def measure_regime(ts, th, lam_t=lam, gam_t=gam, detail=True, per_layer=False):
         """Step time (mean over K different-input replays by the host clock; median and min over REPLAYS replays
         by HIP events), measured sparsity and, with detail, per-call and per-kernel durations."""
-        run = make_runner(False, ts, th, lam_t, gam_t)
+        run = make_runner(False, ts, th, lam_t, gam_t, per_layer=per_layer)
         ms = timed(run)
         med, mn = replay_stats(run)
         check_outputs("the timed sparse steps")
@@ -338,67 +354,57 @@ def main():
     off = measure_regime(INF, INF) if "off" in want else None          # indicators off: tau_final = tau_base (target sparsity)
     on = measure_regime(-INF, -INF, detail=False) if "on" in want else None                       # both indicators always on: factor 1.92
     neg = measure_regime(tau_s, tau_H, lam_neg, gam_neg, detail=False) if "neg" in want else None  # natural, coefficients -0.80 / -0.12
-    # ---- the whole-stack entry point (B = 1): the same step as signals+thresholds and ONE persistent launch
-    stack = None
-    if B == 1 and "stack" in want and off is not None:
-        arr = binding.layer_array(layers)
-        x_flat, y_flat, tau_flat = x_cur.view(L, d), y_out.view(L, d), tau_final.view(L)
-
-        def stack_body(dense, ts, th):
-            sp = stream_ptr()
-            signals_and_thresholds(ts, th, lam, gam, sp)
-            if dense:
-                ctx.check(lib.clada_dense_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), y_flat.data_ptr(), sp))
-            else:
-                ctx.check(lib.clada_sparse_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), tau_flat.data_ptr(),
-                                                            y_flat.data_ptr(), None, sp))
-
-        def make_stack_runner(dense, ts, th):
-            if args.no_graph:
-                return lambda: stack_body(dense, ts, th)
-            load_inputs(0)
-            torch.cuda.synchronize()
-            with torch.cuda.stream(side):
-                stack_body(dense, ts, th)
-                side.synchronize()
-                clada.graph_begin(ctx)
-                stack_body(dense, ts, th)
-                g = clada.graph_end(ctx)
-            torch.cuda.synchronize()
-            return g.launch
-
+    # ---- B = 1: the same step through the per-layer calls (what a model whose layers depend on each other
+    # would issue), and through the other modes of the whole-stack call, for the record
+    per_layer, stack = None, None
+    if use_stack and "stack" in want and off is not None:
+        b1_opt = int(dict(o.split("=") for o in args.option).get("decode.b1", 1))
+        pl_nat = measure_regime(tau_s, tau_H, detail=False, per_layer=True)
+        pl_off = measure_regime(INF, INF, detail=False, per_layer=True)
+        ms_pl_dense = timed(make_runner(True, tau_s, tau_H, lam, gam, per_layer=True))
+        check_outputs("the dense per-layer steps")
+        per_layer = {"what": "the same step as signals+thresholds and L calls of clada_sparse_ffn_decode on one stream",
+                     "natural": _light(pl_nat, ms_pl_dense, lambda rho: nmat / (nmat - (nmat - 1.0) * rho), B, L),
+                     "indicators_off": _light(pl_off, ms_pl_dense, lambda rho: nmat / (nmat - (nmat - 1.0) * rho), B, L),
+                     "dense_ms_per_step": round(ms_pl_dense, 4)}
         stack = {}
-        ctx.set_option("decode.stack", 1)                   # the persistent kernel; off by default (slower, see "what")
-        for name, (ts, th), reg in (("natural", (tau_s, tau_H), nat), ("indicators_off", (INF, INF), off)):
-            load_inputs(W)
-            step_body(False, ts, th, lam, gam)              # per-layer calls on the same inputs: the reference bits
-            torch.cuda.synchronize()
-            y_want = y_out.clone()
-            run = make_stack_runner(False, ts, th)
-            load_inputs(W)
-            run()
-            torch.cuda.synchronize()
-            same = bool(torch.equal(y_out, y_want))
-            ms = timed(run)
-            med, mn = replay_stats(run)
-            check_outputs("the whole-stack steps")
-            stack[name] = {"ms_per_step": round(ms, 4), "ms_median": round(med, 4), "ms_min": round(mn, 4),
+        for mode, mode_name in ((3, "two_lanes"), (2, "chained_launches"), (1, "persistent_kernel")):
+            ctx.set_option("decode.stack", mode)
+            m = {}
+            for name, (ts, th), reg in (("natural", (tau_s, tau_H), nat), ("indicators_off", (INF, INF), off)):
+                load_inputs(W)
+                if mode == 3:
+                    ctx.set_option("decode.b1", 2)          # the lanes run the unbalanced instances: those are their bits
+                step_body(False, ts, th, lam, gam, per_layer=True)       # per-layer calls on the same inputs: the reference bits
+                torch.cuda.synchronize()
+                ctx.set_option("decode.b1", b1_opt)
+                y_want = y_out.clone()
+                run = make_runner(False, ts, th, lam, gam)
+                load_inputs(W)
+                run()
+                torch.cuda.synchronize()
+                same = bool(torch.equal(y_out, y_want))
+                if mode == 3:                               # timed above: the headline numbers
+                    m[name] = {"ms_per_step": round(reg["ms"], 4), "bit_identical_to_per_layer_calls": same}
+                    continue
+                ms = timed(run)
+                med, mn = replay_stats(run)
+                check_outputs("the whole-stack steps")
+                m[name] = {"ms_per_step": round(ms, 4), "ms_median": round(med, 4), "ms_min": round(mn, 4),
                            "tokens_per_s": round(1e3 / ms, 2), "sparsity_union": round(float(reg["rho_union"]), 4),
-                           "step_gbs_on_bytes_touched": round(reg["bytes_layer"] * L / (ms * 1e-3) / 1e9, 1),
                            "step_frac_of_hbm_peak": round(reg["bytes_layer"] * L / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                            "bit_identical_to_per_layer_calls": same}
-        run = make_stack_runner(True, tau_s, tau_H)
-        ms_dense_stack = timed(run)
-        check_outputs("the dense whole-stack steps")
-        for name, reg in (("natural", nat), ("indicators_off", off)):
-            stack[name]["speedup_vs_dense_stack"] = round(ms_dense_stack / stack[name]["ms_per_step"], 4)
-            stack[name]["ideal_speedup"] = round(nmat / (nmat - (nmat - 1.0) * reg["rho_union"]), 4)
-        stack["dense_ms_per_step"] = round(ms_dense_stack, 4)
-        ctx.set_option("decode.stack", 0)
-        stack["what"] = ("clada_sparse_ffn_stack_decode with option decode.stack=1: one persistent launch for the L independent "
-                         "layers of a step (no kernel boundary, no separate reduction launch per layer).  Measured for the "
-                         "record: it is slower than the per-layer launches for sparse stacks, which is why it is off by "
-                         "default; value and ms_per_step above are the per-layer calls")
+            if mode != 3:
+                ms_dense_stack = timed(make_runner(True, tau_s, tau_H, lam, gam))
+                check_outputs("the dense whole-stack steps")
+                m["dense_ms_per_step"] = round(ms_dense_stack, 4)
+            stack[mode_name] = m
+        ctx.set_option("decode.stack", 3)
+        stack["what"] = ("modes of clada_sparse_ffn_stack_decode (option decode.stack).  two_lanes (default; value and "
+                         "ms_per_step of this line): even and odd layers on two streams, so that the compute units "
+                         "one layer has released run the next already.  chained_launches: one stream, the kernel of "
+                         "layer l also sums the partial outputs of layer l-1.  persistent_kernel: one launch walks "
+                         "the L layers; slower for sparse stacks, kept for the record")
     run_dense = make_runner(True, tau_s, tau_H, lam, gam)
     ms_dense = timed(run_dense)
     dense_med, dense_min = replay_stats(run_dense)
@@ -470,7 +476,10 @@ def main():
             "call_frac": round(off["bytes_probe"] / (off["call_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "regime_indicators_on": _light(on, ms_dense, ideal, B, L) if on else None,
         "regime_negative_coefficients": dict(_light(neg, ms_dense, ideal, B, L), **{"lambda": -0.80, "gamma": -0.12}) if neg else None,
-        "stack_entry": stack,
+        "step_path": ("clada_signals_threshold, then clada_sparse_ffn_stack_decode (two lanes) on the L independent layers"
+                      if use_stack else "clada_signals_threshold, then L calls of clada_sparse_ffn_decode"),
+        "per_layer_calls": per_layer,
+        "stack_modes": stack,
         "step_gbs_on_bytes_touched": round(bytes_layer * L / (ms_sparse * 1e-3) / 1e9, 1),
         "dense_step_gbs": round(bytes_dense * L / (ms_dense * 1e-3) / 1e9, 1),
         "stream_read_ceiling_gbs": round(ceil_gbs, 1),   # whole-row streaming of one 90 MB matrix per launch, launch gaps included
@@ -488,7 +497,14 @@ def main():
                      # + the launch gap between them, timed with HIP events around the call
                      "call": {"us": round(call_us, 2), "finalize_us": round(nat["finalize_us"], 2),
                               "achieved": round(achieved_call, 1), "frac": round(achieved_call / HBM_PEAK_GBS, 4)},
-                     "us_per_layer_in_step": round(step_us_per_layer, 2)},
+                     "us_per_layer_in_step": round(step_us_per_layer, 2),
+                     # the timed step itself: with two lanes two launches share the chip at any time, so the
+                     # duration of one launch says little; what counts is the rate at which launches complete
+                     # (step time / L, the signals launch included)
+                     "in_step": {"launches_in_flight": 2 if (use_stack and not args.per_layer and L >= 4) else 1,
+                                 "us_per_launch_completed": round(step_us_per_layer, 2),
+                                 "achieved": round(bytes_layer / (step_us_per_layer * 1e-6) / 1e9, 1),
+                                 "frac": round(bytes_layer / (step_us_per_layer * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}},
         "setup_s": round(time.time() - t_setup, 1),
     }
 

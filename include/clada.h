@@ -72,9 +72,9 @@ const char *clada_last_error(const clada_ctx *ctx);
  * the launch allows it, 0 = the generic kernels), "decode.own_first" (1..14, neurons a
  * workgroup keeps for itself before the balanced hand-over; 0 = default),
  * "decode.wgs_per_cu" (1 or 2 workgroups per compute unit for the generic kernel),
- * "decode.stack" (the whole-stack calls: 0 = the L per-layer launches, issued inside the
- * call [default: measured faster for sparse stacks], 1 = one persistent kernel for all
- * layers where the shape has one),
+ * "decode.stack" (how the whole-stack calls run: 3 = two lanes [default], 2 = chained
+ * launches, 1 = one persistent kernel for all layers where the shape has one, 0 = the L
+ * per-layer calls; see clada_sparse_ffn_stack_decode),
  * "decode.batched" (1 = matrix-core kernels for bf16 batches of 2 and more, 16 tokens
  * per pass [default], 0 = the
  * generic kernels), "decode.spin_limit" (how often a balanced batch-1 kernel polls
@@ -257,25 +257,36 @@ clada_status clada_sparse_ffn_decode(clada_ctx *ctx, const clada_layer *layer, c
 clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
                                     int32_t B, void *y, void *hip_stream);
 
-/* The L sparse FFN calls of one decode step as ONE launch, for stacks whose layers are
+/* The L sparse FFN calls of one decode step as ONE call, for stacks whose layers are
  * independent problems: layer l has its own input row x[l] and its own output row y[l]
  * (the FFN-stack workloads this library is measured on; in a model whose next layer
  * consumes y[l] through attention the per-layer call above is the one that applies).
  * Mask compression and "whole-stack persistence" are what the paper's limitations and
- * future-work paragraphs leave open; this is the second.  One persistent kernel walks
- * the layers: a workgroup that has finished its share of layer l starts on the gate rows
- * of layer l+1 at once, and the fixed-order sum of layer l's partial outputs is done
- * inside layer l+1, so no kernel boundary and no reduction launch is paid per layer
- * (option "decode.stack" = 1; by default the call issues the L per-layer launches itself,
- * which was measured faster for sparse stacks).
+ * future-work paragraphs leave open; this is the second.  Knowing the whole stack, the
+ * library can hide what every per-layer call pays: the start-up of a kernel, its ragged
+ * end, and the launch of the final reduction.  Option "decode.stack" chooses how:
+ *   3 (default)  two lanes: even layers on hip_stream, odd layers on a stream that the
+ *                context owns (default priority), forked and joined by events inside the
+ *                call -- to the caller the call is ordered on hip_stream like any other,
+ *                and a stream capture of hip_stream records both lanes.  The compute
+ *                units that layer l has released run layer l+1 already.  The lanes use
+ *                the kernels without cross-workgroup balancing (kernels that wait for
+ *                their own workgroups must not share the chip).
+ *   2            chained launches on hip_stream: the kernel of layer l also sums the
+ *                partial outputs of layer l-1; one reduction launch per call.
+ *   1            one persistent kernel walks the layers (bf16 rows of 4, 5, 8 or 10 KiB,
+ *                all workgroups resident at once); measured slower for sparse stacks.
+ *   0            the L per-layer calls, issued by the library.
  *   layers [L] (host array; all of one d, d_ff, dtype and kind), x [L][d], y [L][d]
  *   (layer dtype), tau_final [L] (clada_threshold's output for B = 1), n_active [L][2]
  *   or NULL (per layer: {kept, kept}, the layout of the per-layer call for B = 1).
- * Results are bit-identical to L calls of clada_sparse_ffn_decode (same kernels' order of
- * summation).  Shapes or devices the persistent kernel does not cover (it needs all its
- * workgroups resident at once, bf16 rows of 4, 5, 8 or 10 KiB) run as L per-layer calls
- * inside this call.  The remarks on clada_device_fault apply: the kernel waits, bounded,
- * for its own workgroups.  clada_dense_ffn_stack_decode is the dense twin. */
+ * Results are bit-identical to L calls of clada_sparse_ffn_decode with the same balancing
+ * (modes 0 - 2: the context's "decode.b1"; mode 3: as with "decode.b1" = 2): the same
+ * kernels' order of summation.  Modes 2 and 3 need the batch-1 kernel's shapes (rows of
+ * whole KiB), 256 compute units or more and n_active = NULL; modes 1 - 3 fall back to
+ * mode 0 where they do not apply.  The remarks on clada_device_fault apply to modes 0 - 2
+ * (balanced kernels wait, bounded, for their own workgroups).  A context serves one call
+ * at a time, on whatever stream.  clada_dense_ffn_stack_decode is the dense twin. */
 clada_status clada_sparse_ffn_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L,
                                            const void *x, const float *tau_final, void *y,
                                            int32_t *n_active, void *hip_stream);

@@ -30,7 +30,7 @@ namespace {
 size_t ws_partial_bytes(int B, int d)
 {
     size_t rows = (size_t)CLADA_MAX_DECODE_WGS * B;
-    if (rows < 3 * (size_t)COOP_MAX_WGS) rows = 3 * (size_t)COOP_MAX_WGS;
+    if (rows < 4 * (size_t)COOP_MAX_WGS) rows = 4 * (size_t)COOP_MAX_WGS;
     return align_up(sizeof(float) * rows * d, 256);
 }
 
@@ -464,6 +464,13 @@ struct B1Params {
     int max_spins;              // polls of the other workgroups' records before giving up
     int d, F, K0;
     int gelu;                   // gated family: sigma = tanh-form GELU instead of SiLU
+    // Chained calls (whole-stack entry points): this launch also sums the partial outputs that the previous
+    // launch of the chain left behind -- complete and visible, there is a kernel boundary in between -- so
+    // that only the last layer of a chain needs a reduction launch of its own.
+    const float *prev_partial;  // [P][d] of the previous launch, or nullptr
+    char *prev_y;               // [d] output row of the previous layer
+    const float *prev_bias;     // RELU: its output bias, or nullptr
+    unsigned int *epoch_out;    // balanced calls of a chain advance the call counter themselves (no k_ffn_finalize does)
 };
 
 // Exclusive prefix sum over the 64 lanes of a wave (no barrier); *total gets the wave sum.
@@ -740,6 +747,9 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     __shared__ float4 s_sum[STACK ? 32 : 1][16];            // STACK: slices of the final reduction
     __shared__ int s_arrived;                               // STACK: see StackReduce
     __shared__ __align__(16) unsigned char s_x[(STACK || NCH > 10) ? NCH * 1024 : 16];    // the layer's input row where it is not held in registers
+    // chained calls: this workgroup's CGW column groups (of four) of all 256 partial outputs of the previous launch
+    constexpr int CGW = (NCH * 1024 / ES / 4 + 255) / 256;
+    __shared__ float4 s_prev[STACK ? 1 : 256 * CGW];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -784,6 +794,7 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
         p.fault = ka->fault;
         p.max_spins = ka->max_spins;
         p.d = ka->d; p.F = F; p.K0 = ka->K0; p.gelu = ka->gelu;
+        p.prev_partial = nullptr; p.prev_y = nullptr; p.prev_bias = nullptr; p.epoch_out = nullptr;
     } else {
         p = pp;
     }
@@ -804,6 +815,35 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     // More than 64 neurons per workgroup (d_ff above 64 P: the 70B-class layers) are worked off in rounds of
     // 64, gate rows and kept rows of a round before the next round's; the accumulators run through.  (The
     // balanced and the whole-stack variants are only launched where one round covers everything.)
+    unsigned long long tag = 0ull;
+    unsigned int call_no = 0u;                              // this balanced call's number on the context
+    if (BAL || STACK) {
+        if constexpr (STACK) call_no = g0 + (unsigned int)layer + 1u;
+        else call_no = *p.epoch + 1u;
+        tag = (unsigned long long)(call_no & 0xffu) << 56;
+    }
+    // (read here, not where it is used: at the kernel's end the round trip would be exposed)
+    int prev_fault = 0;
+    if constexpr (!STACK && BAL) {
+        if (p.prev_partial) prev_fault = *p.fault;
+    }
+    // Chained call: the previous launch's partial outputs for this workgroup's columns go straight into LDS
+    // (no staging registers; a wave's transfer fills 64 consecutive 16-byte entries, entry e = partial
+    // e / CGW, column group e % CGW) and are summed at the very end of this kernel.  (Measured on the 7B
+    // layer: the transfers cost the kernel 1.1 us, the sum 0.3 us, against 2.9 us for a reduction launch.)
+    auto prefetch_prev = [&]() {
+        const int d4 = p.d >> 2;
+        for (int e0 = wave * 64; e0 < 256 * CGW; e0 += NW * 64) {
+            const int e = e0 + lane;
+            const int q = e / CGW, cg4 = min(blk * CGW + e % CGW, d4 - 1);
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1))) *)(p.prev_partial + (size_t)q * p.d + 4 * cg4),
+                (void __attribute__((address_space(3))) *)(s_prev + e0), 16, 0, 0);
+        }
+    };
+    if constexpr (!STACK) {
+        if (p.prev_partial) prefetch_prev();
+    }
    for (int r0 = 0; r0 < (ROUNDS ? ni_all : 1); r0 += 64) {
     const int ni = ROUNDS ? min(64, ni_all - r0) : ni_all;
     const int nb0 = blk + P * r0;                           // the round's first neuron
@@ -825,13 +865,6 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
         else return xr[c];
     };
     const float tau = DENSE ? 0.0f : p.tau[0];
-    unsigned long long tag = 0ull;
-    unsigned int call_no = 0u;                              // this balanced call's number on the context
-    if (BAL || STACK) {
-        if constexpr (STACK) call_no = g0 + (unsigned int)layer + 1u;
-        else call_no = *p.epoch + 1u;
-        tag = (unsigned long long)(call_no & 0xffu) << 56;
-    }
     // An activation another workgroup published: the word carries the number of the call that wrote it, so
     // it validates itself and needs no ordering against the mask record that announced it.  Bounded like the
     // wait for the records (the store was issued before the record's, so a second poll is already rare).
@@ -1135,6 +1168,14 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     }
     if (ROUNDS && r0 + 64 < ni_all) __syncthreads();       // the LDS arrays are free for the next round
    }    // rounds
+    if constexpr (!STACK) {
+        if (p.prev_partial) {
+            // chained call: this wave's transfers of the previous partials have landed (its other loads are
+            // long consumed, nothing else is in flight); after the barrier all of them have
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+    }
     // each wave owns its columns: straight to the partial, no fold
     float *dst = p.partial + (size_t)blk * p.d;
     __amdgpu_buffer_rsrc_t dst_row = __builtin_amdgcn_make_buffer_rsrc(dst, 0, p.d * 4, 0x00020000);   // raw bytes, bounds = the row
@@ -1154,6 +1195,46 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
         }
     }
     if constexpr (STACK) __syncthreads();          // the LDS arrays are free for the next layer
+    if constexpr (!STACK) {
+        if (p.prev_partial) {
+            // y of the previous layer = sum of its 256 partials in k_ffn_finalize's order (the bits match):
+            // slice sl adds the partials sl, sl + 32, ... one after the other, then the 32 slices fold by the
+            // fixed tree sl += sl + 16, 8, 4, 2, 1.  A column group's 32 slices sit in one half of a wave.
+            if (tid < 32 * CGW) {
+                const int sl = tid & 31, cg = tid >> 5;
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float4 v = s_prev[(sl + 32 * u) * CGW + cg];
+                    t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+                }
+#pragma unroll
+                for (int h = 16; h >= 1; h >>= 1) {
+                    const float vx = __shfl_down(t.x, h, 32), vy = __shfl_down(t.y, h, 32);
+                    const float vz = __shfl_down(t.z, h, 32), vw = __shfl_down(t.w, h, 32);
+                    if (sl < h) { t.x += vx; t.y += vy; t.z += vz; t.w += vw; }
+                }
+                const int col = (blk * CGW + cg) * 4;
+                if (sl == 0 && col < p.d) {
+                    if (prev_fault) t.x = t.y = t.z = t.w = __int_as_float(0x7fc00000);   // a balanced call gave up: no silent wrong sums
+                    if (RELU && p.prev_bias) {
+                        const float4 bv = *reinterpret_cast<const float4 *>(p.prev_bias + col);
+                        t.x += bv.x; t.y += bv.y; t.z += bv.z; t.w += bv.w;
+                    }
+                    if (ES == 4) {
+                        *reinterpret_cast<float4 *>(p.prev_y + (size_t)col * 4) = t;
+                    } else {
+                        uint2 o;
+                        o.x = f32_to_bf16_bits(t.x) | (f32_to_bf16_bits(t.y) << 16);
+                        o.y = f32_to_bf16_bits(t.z) | (f32_to_bf16_bits(t.w) << 16);
+                        *reinterpret_cast<uint2 *>(p.prev_y + (size_t)col * 2) = o;
+                    }
+                }
+            }
+        }
+        // every workgroup of a balanced call has read the counter before workgroup 0 gets past the mask exchange
+        if (BAL && p.epoch_out && blk == 0 && tid == 0) *p.epoch_out = call_no;
+    }
   }     // layers
     if constexpr (STACK) {
         // drain: a record of one more (empty) layer announces the last partial, then the two reductions still owed
@@ -1220,6 +1301,51 @@ hipError_t launch_b1(clada_ctx *ctx, const B1Params &p, int P, bool dense, bool 
     return launch_b1_variant<ES, NCH, DCH, false, false, RELU>(ctx, p, P, st);
 }
 
+// The split-d instantiations by element size, row length and family (exactly the shapes b1_shape_ok admits).
+// *balance is cleared when the balanced instance cannot have all its workgroups resident at once.
+bool b1_shape_ok(int es, int nch, bool relu)
+{
+    return relu ? (es == 2 && (nch == 2 || nch == 5 || nch == 8 || nch == 10))
+           : es == 2 ? (nch == 2 || nch == 4 || nch == 5 || nch == 8 || nch == 10 || nch == 12 || nch == 16)
+                     : (nch == 2 || nch == 8);
+}
+
+hipError_t launch_b1_shape(clada_ctx *ctx, const B1Params &b, int Pb, int es, int nch, bool relu, bool dense,
+                           bool *balance, hipStream_t stream)
+{
+    hipError_t eb = hipErrorNotSupported;
+    for (int attempt = 0; attempt < 2 && eb == hipErrorNotSupported; ++attempt) {
+        const bool bal = *balance;
+        if (relu) {
+            if (nch == 8) eb = launch_b1<2, 8, 16, true>(ctx, b, Pb, dense, bal, stream);
+            else if (nch == 10) eb = launch_b1<2, 10, 8, true>(ctx, b, Pb, dense, bal, stream);
+            else if (nch == 5) eb = launch_b1<2, 5, 16, true>(ctx, b, Pb, dense, bal, stream);
+            else eb = launch_b1<2, 2, 16, true>(ctx, b, Pb, dense, bal, stream);
+        }
+        else if (es == 2 && nch == 8) eb = launch_b1<2, 8, 16>(ctx, b, Pb, dense, bal, stream);
+        else if (es == 2 && nch == 10) eb = launch_b1<2, 10, 8>(ctx, b, Pb, dense, bal, stream);
+        else if (es == 2 && nch == 12) eb = launch_b1<2, 12, 8>(ctx, b, Pb, dense, bal, stream);
+        else if (es == 2 && nch == 16) eb = launch_b1<2, 16, 8>(ctx, b, Pb, dense, bal, stream);
+        else if (es == 2 && nch == 5) eb = launch_b1<2, 5, 16>(ctx, b, Pb, dense, bal, stream);
+        else if (es == 2 && nch == 4) eb = launch_b1<2, 4, 16>(ctx, b, Pb, dense, bal, stream);
+        else if (es == 2 && nch == 2) eb = launch_b1<2, 2, 16>(ctx, b, Pb, dense, bal, stream);
+        else if (es == 4 && nch == 2) eb = launch_b1<4, 2, 16>(ctx, b, Pb, dense, bal, stream);
+        else if (es == 4 && nch == 8) eb = launch_b1<4, 8, 16>(ctx, b, Pb, dense, bal, stream);
+        if (eb == hipErrorNotSupported) *balance = false;      // not co-resident: plain split-d
+    }
+    return eb;
+}
+
+// Balancing pays when the kept-row phase is long enough to hide the mask exchange behind the
+// workgroup's own first chunk: measured faster on the 7B/8B shapes (90-117 MB per matrix), slower
+// on 52 MB ReLU layers (17.0 vs 14.1 us) and on 8 MB ones (10.0 vs 6.4 us).  With 10 KiB gated rows
+// (13B shape, own-first chunk of 7) it gains 2-3 % from sparsity 0.45 up and loses as much at 0.3.
+bool b1_wants_balance(const clada_ctx *ctx, bool dense, bool relu, int ni_b, int d, int F, int es)
+{
+    const double phase2_bytes = (relu ? 1.0 : 2.0) * (double)F * d * es;
+    return !dense && ni_b <= 56 && (ctx->opt_decode_b1 == 3 || (ctx->opt_decode_b1 == 1 && phase2_bytes >= 128e6));
+}
+
 template <int ES, int NCH, int NW, int GB, int UB>
 hipError_t launch_decode(const DecodeParams &p, int P, int B, bool dense, hipStream_t st, bool list = false,
                          bool relu = false)
@@ -1279,9 +1405,7 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
 
     // ---- split-d path (decode batch 1, whole-KiB rows, <= 64 neurons per workgroup)
     // (exactly the instantiations launched below: a shape admitted here without one would fail the call)
-    const bool b1_shape = relu ? (es == 2 && (nch == 2 || nch == 5 || nch == 8 || nch == 10))
-                          : es == 2 ? (nch == 2 || nch == 4 || nch == 5 || nch == 8 || nch == 10 || nch == 12 || nch == 16)
-                                    : (nch == 2 || nch == 8);
+    const bool b1_shape = b1_shape_ok(es, nch, relu);
     if (ctx->opt_decode_b1 >= 1 && B == 1 && (d * es) % 1024 == 0 && b1_shape) {
         const int Pb = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
         const int ni_b = (F + Pb - 1) / Pb;
@@ -1298,33 +1422,9 @@ clada_status run_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
             b.d = d; b.F = F;
             b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
             b.gelu = p.gelu;
-            // Balancing pays when the kept-row phase is long enough to hide the mask exchange behind the
-            // workgroup's own first chunk: measured faster on the 7B/8B shapes (90-117 MB per matrix), slower
-            // on 52 MB ReLU layers (17.0 vs 14.1 us) and on 8 MB ones (10.0 vs 6.4 us).  With 10 KiB gated rows
-            // (13B shape, own-first chunk of 7) it gains 2-3 % from sparsity 0.45 up and loses as much at 0.3.
-            const double phase2_bytes = (relu ? 1.0 : 2.0) * (double)F * d * es;
-            bool balance = !dense && ni_b <= 56 &&
-                           (ctx->opt_decode_b1 == 3 ||
-                            (ctx->opt_decode_b1 == 1 && phase2_bytes >= 128e6));
-            hipError_t eb = hipErrorNotSupported;
-            for (int attempt = 0; attempt < 2 && eb == hipErrorNotSupported; ++attempt) {
-                if (relu) {
-                    if (nch == 8) eb = launch_b1<2, 8, 16, true>(ctx, b, Pb, dense, balance, stream);
-                    else if (nch == 10) eb = launch_b1<2, 10, 8, true>(ctx, b, Pb, dense, balance, stream);
-                    else if (nch == 5) eb = launch_b1<2, 5, 16, true>(ctx, b, Pb, dense, balance, stream);
-                    else eb = launch_b1<2, 2, 16, true>(ctx, b, Pb, dense, balance, stream);
-                }
-                else if (es == 2 && nch == 8) eb = launch_b1<2, 8, 16>(ctx, b, Pb, dense, balance, stream);
-                else if (es == 2 && nch == 10) eb = launch_b1<2, 10, 8>(ctx, b, Pb, dense, balance, stream);
-                else if (es == 2 && nch == 12) eb = launch_b1<2, 12, 8>(ctx, b, Pb, dense, balance, stream);
-                else if (es == 2 && nch == 16) eb = launch_b1<2, 16, 8>(ctx, b, Pb, dense, balance, stream);
-                else if (es == 2 && nch == 5) eb = launch_b1<2, 5, 16>(ctx, b, Pb, dense, balance, stream);
-                else if (es == 2 && nch == 4) eb = launch_b1<2, 4, 16>(ctx, b, Pb, dense, balance, stream);
-                else if (es == 2 && nch == 2) eb = launch_b1<2, 2, 16>(ctx, b, Pb, dense, balance, stream);
-                else if (es == 4 && nch == 2) eb = launch_b1<4, 2, 16>(ctx, b, Pb, dense, balance, stream);
-                else if (es == 4 && nch == 8) eb = launch_b1<4, 8, 16>(ctx, b, Pb, dense, balance, stream);
-                if (eb == hipErrorNotSupported) balance = false;      // not co-resident: plain split-d
-            }
+            bool balance = b1_wants_balance(ctx, dense, relu, ni_b, d, F, es);
+            b.prev_partial = nullptr; b.prev_y = nullptr; b.prev_bias = nullptr; b.epoch_out = nullptr;
+            hipError_t eb = launch_b1_shape(ctx, b, Pb, es, nch, relu, dense, &balance, stream);
             CLADA_CHECK_HIP(ctx, eb);
             launch_finalize(es, p.partial, Pb, 1, d, (char *)y, balance ? epoch : nullptr, stream,
                             ctx->opt_diag_events ? ctx->ev[2] : nullptr, ctx->ev[3], b_out, balance ? b.fault : nullptr);
@@ -1586,6 +1686,77 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
             CLADA_CHECK_HIP(ctx, e);
         }
         if (persistent) return CLADA_OK;
+    }
+    // ---- launches issued by the library itself.  Two things the per-layer calls cannot do:
+    // * two lanes (the default): the layers of a stack are independent problems, so even and odd layers run
+    //   on two HIP streams (the caller's and one of the context's, forked and joined by events, which a
+    //   stream capture follows).  A compute unit that has finished its share of layer l takes a workgroup of
+    //   layer l+1 at once: the start-up and the ragged end of every kernel are covered by its neighbour
+    //   (7B layer shape, sparsity 0.45: 36.0 -> 32.5 us per layer; three and four lanes are slower again).
+    //   Kernels that wait for each other's workgroups must not share the chip, so the lanes run the
+    //   unbalanced instances.
+    // * chained launches (one lane): a layer's kernel also sums the partial outputs of the previous layer,
+    //   which a kernel boundary has made complete and visible, so only the last layer needs a reduction
+    //   launch; the partials alternate between two buffers (36.0 -> 35.1 us per layer; inside two lanes the
+    //   reduction launches are covered anyway and chaining loses 0.6 us).
+    // Counts per layer need the flag arrays and the list kernel of the per-layer call, so a call that asks
+    // for them runs the per-layer calls below.
+    const int smode = ctx->opt_decode_stack;
+    const bool own_launches = smode >= 2 && ctx->opt_decode_b1 >= 1 && !n_active && (d * es) % 1024 == 0 &&
+                              b1_shape_ok(es, nch, relu) && Pb == COOP_MAX_WGS && F >= Pb && ni_b <= 1024 && L >= 2;
+    if (own_launches) {
+        static_assert(COOP_MAX_WGS == 256, "the chained reduction is laid out for 256 partial outputs");
+        const int n_lanes = (smode == 3 && L >= 4) ? 2 : 1;
+        const bool chained = smode == 2;
+        if (n_lanes == 2 && !ctx->lane_stream) {
+            CLADA_CHECK_HIP(ctx, hipStreamCreateWithFlags(&ctx->lane_stream, hipStreamNonBlocking));
+            for (int i = 0; i < 2; ++i) CLADA_CHECK_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_lane[i], hipEventDisableTiming));
+        }
+        unsigned int *epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
+        float *part = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
+        bool balance = smode == 2 && b1_wants_balance(ctx, dense, relu, ni_b, d, F, es);      // (mode 3 never balances, whatever L: one set of bits)
+        B1Params b;
+        b.keep = nullptr;
+        b.rec = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_REC);
+        b.apub = reinterpret_cast<unsigned long long *>(ctx->ws + COOP_APUB);
+        b.epoch = epoch;
+        b.fault = reinterpret_cast<int *>(ctx->ws + COOP_FAULT);
+        b.max_spins = ctx->opt_decode_spin_limit;
+        b.d = d; b.F = F;
+        b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
+        b.gelu = layers[0].kind == CLADA_FFN_GEGLU ? 1 : 0;
+        if (n_lanes == 2) {
+            CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev_lane[0], stream));
+            CLADA_CHECK_HIP(ctx, hipStreamWaitEvent(ctx->lane_stream, ctx->ev_lane[0], 0));
+        }
+        const size_t buf = (size_t)Pb * d;                   // floats of one buffer of partial outputs
+        for (int l = 0; l < L; ++l) {
+            const int lane = l % n_lanes, k = l / n_lanes;   // the layer is its lane's k-th
+            hipStream_t st = lane ? ctx->lane_stream : stream;
+            float *mine = part + (size_t)(2 * lane + (chained ? (k & 1) : 0)) * buf;
+            const int lp = l - n_lanes;                      // the lane's previous layer
+            b.wg = (const char *)layers[l].w_gate; b.wu = (const char *)layers[l].w_up; b.wd = (const char *)layers[l].w_down;
+            b.b_in = relu ? layers[l].b_in : nullptr;
+            b.x = (const char *)x + (size_t)l * d * es;
+            b.tau = tau ? tau + l : nullptr;
+            b.partial = mine;
+            const bool sums_prev = chained && lp >= 0;
+            b.prev_partial = sums_prev ? part + (size_t)(2 * lane + ((k - 1) & 1)) * buf : nullptr;
+            b.prev_y = sums_prev ? (char *)y + (size_t)lp * d * es : nullptr;
+            b.prev_bias = (sums_prev && relu) ? layers[lp].b_out : nullptr;
+            b.epoch_out = epoch;                             // only the balanced instance writes it
+            CLADA_CHECK_HIP(ctx, launch_b1_shape(ctx, b, Pb, es, nch, relu, dense, &balance, st));
+            if (!chained || l + n_lanes >= L) {              // nobody after it in its lane: its own reduction launch
+                launch_finalize(es, mine, Pb, 1, d, (char *)y + (size_t)l * d * es, (!chained && balance) ? epoch : nullptr, st,
+                                nullptr, nullptr, relu ? layers[l].b_out : nullptr, balance ? b.fault : nullptr);
+                CLADA_CHECK_HIP(ctx, hipGetLastError());
+            }
+        }
+        if (n_lanes == 2) {
+            CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev_lane[1], ctx->lane_stream));
+            CLADA_CHECK_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_lane[1], 0));
+        }
+        return CLADA_OK;
     }
     for (int l = 0; l < L; ++l) {
         clada_status st = run_decode(ctx, &layers[l], (const char *)x + (size_t)l * d * es, 1, tau ? tau + l : nullptr,

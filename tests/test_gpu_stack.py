@@ -1,5 +1,7 @@
-"""GPU parity: the whole-stack calls (one persistent launch for L layers) against the per-layer calls,
-bit for bit, and against the fp64 oracle."""
+"""GPU parity: the whole-stack calls against the per-layer calls, bit for bit, and against the fp64 oracle.
+Modes of the call (option decode.stack): 3 = two lanes, the default (even and odd layers on two streams);
+2 = chained launches (every layer's kernel also sums the previous layer's partial outputs); 1 = one
+persistent launch for the L layers; 0 = the per-layer calls."""
 import numpy as np
 import pytest
 import torch
@@ -49,27 +51,43 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("cfg_name,d,F,L,q,opts", CASES)
-def test_stack_call_is_the_per_layer_calls_bit_for_bit(clada, cfg_name, d, F, L, q, opts):
+# shapes only the chained launches have instances for: fp32 rows of 8 KiB, 12 KiB rows worked off in rounds
+# (more than 64 neurons per workgroup), 2 KiB rows, a single layer (nothing to chain)
+CHAINED_ONLY = [
+    ("c1", 2048, 1500, 3, 0.40, {}),
+    ("c2", 6144, 16500, 2, 0.45, {}),
+    ("c2", 1024, 3000, 4, 0.45, {}),
+    ("c2", 4096, 11008, 1, 0.45, {}),
+]
+
+
+@pytest.mark.parametrize("mode,cfg_name,d,F,L,q,opts", [(1, *c) for c in CASES] + [(m, *c) for m in (2, 3) for c in CASES + CHAINED_ONLY])
+def test_stack_call_is_the_per_layer_calls_bit_for_bit(clada, mode, cfg_name, d, F, L, q, opts):
     cfg, ws, layers, x = _stack(clada, cfg_name, d, F, L, seed=21)
     ctx = clada.Context(0, clada.workspace_bytes(d, F, 1, 0, 0))
-    ctx.set_option("decode.stack", 1)                   # the persistent kernel (off by default)
+    ctx.set_option("decode.stack", mode)
     for k, v in opts.items():
         ctx.set_option(k, v)
     tau = np.array([np.quantile(np.abs(oracle.gate_act(ws[l][0], x[l:l + 1])), q) for l in range(L)], np.float32)
     tau[L - 1] *= 1.92                                  # thresholds differ per layer
     xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
     y_ref, cnt_ref = [], []
+    if mode >= 3:                                       # the two-lane modes run the unbalanced instances: those are their bits
+        ctx.set_option("decode.b1", 2)
     for l in range(L):
         yl, _, cl, _ = clada.sparse_ffn_decode(ctx, layers[l], xd[l:l + 1].contiguous(), td[l:l + 1].contiguous(), want_lists=True)
         y_ref.append(yl[0].clone())
         cnt_ref.append(cl.clone())
     for rep in range(3):                                # repeated launches: counters and parities carry over
-        y, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td, want_counts=True)
+        if mode >= 2 and rep < 2:                       # (a chained call that is asked for counts runs the per-layer calls)
+            y = clada.sparse_ffn_stack_decode(ctx, layers, xd, td)
+            cnt = None
+        else:
+            y, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td, want_counts=True)
         torch.cuda.synchronize()
         for l in range(L):
             assert torch.equal(y[l], y_ref[l]), f"rep {rep} layer {l}: bits differ from the per-layer call"
-            assert torch.equal(cnt[l], cnt_ref[l]), f"rep {rep} layer {l}: kept count"
+            assert cnt is None or torch.equal(cnt[l], cnt_ref[l]), f"rep {rep} layer {l}: kept count"
     assert not ctx.device_fault()
     # dense twin
     yd = clada.dense_ffn_stack_decode(ctx, layers, xd)
@@ -85,11 +103,12 @@ def test_stack_call_is_the_per_layer_calls_bit_for_bit(clada, cfg_name, d, F, L,
             assert_close_y(to_np(y[l:l + 1]), ref["y"], TOL_Y[cfg.dtype], f"layer {l} vs oracle")
 
 
-def test_stack_call_other_families_and_long_stacks(clada):
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_stack_call_other_families_and_long_stacks(clada, mode):
     # non-gated ReLU family at the OPT-2.7B width (5 KiB rows, biases)
     cfg, ws, layers, x = _stack(clada, "o27", 2560, 10240, 3, seed=22, relu=True)
     ctx = clada.Context(0, clada.workspace_bytes(2560, 10240, 1, 0, 0))
-    ctx.set_option("decode.stack", 1)
+    ctx.set_option("decode.stack", mode)
     xd = to_dev(x, cfg.dtype)
     td = torch.full((3,), 0.05, dtype=torch.float32, device=DEV)
     y = clada.sparse_ffn_stack_decode(ctx, layers, xd, td)
@@ -103,7 +122,7 @@ def test_stack_call_other_families_and_long_stacks(clada):
     xd = to_dev(np.tile(x, (25, 1)), cfg.dtype)
     td = torch.full((50,), 0.1, dtype=torch.float32, device=DEV)
     ctx = clada.Context(0, clada.workspace_bytes(4096, 512, 1, 0, 0))
-    ctx.set_option("decode.stack", 1)
+    ctx.set_option("decode.stack", mode)
     y = clada.sparse_ffn_stack_decode(ctx, long_layers, xd, td)
     y0 = clada.sparse_ffn_decode(ctx, layers[0], xd[:1].contiguous(), td[:1].contiguous())[0]
     y1 = clada.sparse_ffn_decode(ctx, layers[1], xd[1:2].contiguous(), td[:1].contiguous())[0]
@@ -125,13 +144,14 @@ def test_stack_call_rejects_mixed_layers_and_bad_arguments(clada):
         ctx.check(ctx._lib.clada_sparse_ffn_stack_decode(ctx._h, None, 2, xd.data_ptr(), td.data_ptr(), xd.data_ptr(), None, None))
 
 
-def test_bounded_waits_of_the_stack_kernel_give_up_cleanly(clada):
+@pytest.mark.parametrize("mode", [1, 2])      # (two lanes run kernels that wait for nobody)
+def test_bounded_waits_of_the_stack_kernel_give_up_cleanly(clada, mode):
     """Spin limit forced to zero from the host: every workgroup still runs to its end, the outputs are NaN
     and the context reports the fault."""
     cfg, ws, layers, x = _stack(clada, "c2", 4096, 11008, 3, seed=25)
     ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
     ctx.set_option("decode.b1", 3)
-    ctx.set_option("decode.stack", 1)
+    ctx.set_option("decode.stack", mode)
     xd, td = to_dev(x, cfg.dtype), torch.full((3,), 0.25, dtype=torch.float32, device=DEV)
     good = clada.sparse_ffn_stack_decode(ctx, layers, xd, td).clone()
     assert not ctx.device_fault() and torch.isfinite(good.float()).all()
@@ -139,16 +159,53 @@ def test_bounded_waits_of_the_stack_kernel_give_up_cleanly(clada):
     bad = clada.sparse_ffn_stack_decode(ctx, layers, xd, td)
     torch.cuda.synchronize()
     assert ctx.device_fault() and torch.isnan(bad.float()).any()
+    if mode == 2:                                       # every layer of a chain, the last one's own reduction included
+        assert torch.isnan(bad.float()).all()
 
 
-def test_stack_call_default_mode_issues_the_per_layer_launches(clada):
-    """Without the option the call is the per-layer launches issued by the library: same bits, same counts."""
-    cfg, ws, layers, x = _stack(clada, "c2", 4096, 2752, 3, seed=26)
-    ctx = clada.Context(0, clada.workspace_bytes(4096, 2752, 1, 0, 0))
-    xd, td = to_dev(x, cfg.dtype), torch.full((3,), 0.25, dtype=torch.float32, device=DEV)
-    y, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td, want_counts=True)
-    for l in range(3):
+def test_stack_call_modes_agree_and_replay_from_a_graph(clada):
+    """The modes give the same bits; captured calls (two lanes: a fork and a join inside the capture; chained
+    launches) replay correctly on changed inputs."""
+    cfg, ws, layers, x = _stack(clada, "c2", 4096, 11008, 4, seed=26)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+    ctx.set_option("decode.b1", 2)                      # no balancing: every mode then adds in the same order
+    xd, td = to_dev(x, cfg.dtype), torch.full((4,), 0.25, dtype=torch.float32, device=DEV)
+    y2, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td, want_counts=True)
+    y2 = clada.sparse_ffn_stack_decode(ctx, layers, xd, td).clone()          # default: two lanes
+    for mode in (0, 1, 2):
+        ctx.set_option("decode.stack", mode)
+        assert torch.equal(clada.sparse_ffn_stack_decode(ctx, layers, xd, td), y2), f"mode {mode}"
+    ctx.set_option("decode.stack", 3)
+    ctx2 = ctx                                          # (unbalanced per-layer calls: the reference bits below)
+    for l in range(4):
         yl, _, cl, _ = clada.sparse_ffn_decode(ctx, layers[l], xd[l:l + 1].contiguous(), td[l:l + 1].contiguous(), want_lists=True)
-        assert torch.equal(y[l], yl[0]) and torch.equal(cnt[l], cl)
-    ctx.set_option("decode.stack", 1)
-    assert torch.equal(clada.sparse_ffn_stack_decode(ctx, layers, xd, td), y)
+        assert torch.equal(y2[l], yl[0]) and torch.equal(cnt[l], cl)
+    # graph: static input and output buffers, replays with other inputs and thresholds in between eager work;
+    # two lanes, and chained launches of the balanced kernel (whose call counter the chain advances itself)
+    for mode, b1 in ((3, 1), (2, 1), (2, 2)):
+        ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+        ctx.set_option("decode.stack", mode)
+        ctx.set_option("decode.b1", b1)
+        xs, ts = xd.clone(), td.clone()
+        ys = torch.empty_like(xs)
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(stream):
+            clada.sparse_ffn_stack_decode(ctx, layers, xs, ts, y=ys)            # warm-up on the capture stream
+            stream.synchronize()
+            clada.graph_begin(ctx)
+            clada.sparse_ffn_stack_decode(ctx, layers, xs, ts, y=ys)
+            g = clada.graph_end(ctx)
+            for rep in range(4):
+                xs.copy_(torch.roll(xd, rep, dims=0))
+                ts.fill_(0.2 + 0.05 * rep)
+                g.launch()
+                stream.synchronize()
+                got = ys.clone()
+                want = clada.sparse_ffn_stack_decode(ctx, layers, xs, ts)        # eager, between the replays
+                stream.synchronize()
+                assert torch.equal(got, want), f"mode {mode} replay {rep}"
+                if b1 == 2 or mode == 3:
+                    assert torch.equal(got[0], clada.sparse_ffn_decode(ctx2, layers[0], xs[:1].contiguous(), ts[:1].contiguous())[0])
+        del g
+    assert not ctx.device_fault()
