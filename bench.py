@@ -212,7 +212,7 @@ def main():
     # B = 1: the FFN stack of a step goes through the whole-stack call (the layers of the workload are
     # independent problems; by default the library runs even and odd layers on two streams); the per-layer
     # calls are measured beside it.  B >= 2: per-layer calls.
-    use_stack = B == 1 and not args.per_layer
+    use_stack = not args.per_layer
     arr = binding.layer_array(layers)
     x_flat, y_flat, tau_flat = x_cur.view(L * B, d), y_out.view(L * B, d), tau_final.view(L * B)
 
@@ -221,9 +221,9 @@ def main():
         signals_and_thresholds(ts, th, lam_t, gam_t, sp)
         if use_stack and not per_layer and counts is None:
             if dense:
-                ctx.check(lib.clada_dense_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), y_flat.data_ptr(), sp))
+                ctx.check(lib.clada_dense_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), B, y_flat.data_ptr(), sp))
             else:
-                ctx.check(lib.clada_sparse_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), tau_flat.data_ptr(),
+                ctx.check(lib.clada_sparse_ffn_stack_decode(h, arr, L, x_flat.data_ptr(), B, tau_flat.data_ptr(),
                                                             y_flat.data_ptr(), None, sp))
             return
         for l in range(L):
@@ -368,7 +368,7 @@ def main():
                      "indicators_off": _light(pl_off, ms_pl_dense, lambda rho: nmat / (nmat - (nmat - 1.0) * rho), B, L),
                      "dense_ms_per_step": round(ms_pl_dense, 4)}
         stack = {}
-        for mode, mode_name in ((3, "two_lanes"), (2, "chained_launches"), (1, "persistent_kernel")):
+        for mode, mode_name in ((3, "two_lanes"), (2, "chained_launches"), (1, "persistent_kernel")) if B == 1 else ((3, "three_lanes"),):
             ctx.set_option("decode.stack", mode)
             m = {}
             for name, (ts, th), reg in (("natural", (tau_s, tau_H), nat), ("indicators_off", (INF, INF), off)):
@@ -476,8 +476,8 @@ def main():
             "call_frac": round(off["bytes_probe"] / (off["call_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "regime_indicators_on": _light(on, ms_dense, ideal, B, L) if on else None,
         "regime_negative_coefficients": dict(_light(neg, ms_dense, ideal, B, L), **{"lambda": -0.80, "gamma": -0.12}) if neg else None,
-        "step_path": ("clada_signals_threshold, then clada_sparse_ffn_stack_decode (two lanes) on the L independent layers"
-                      if use_stack else "clada_signals_threshold, then L calls of clada_sparse_ffn_decode"),
+        "step_path": (f"clada_signals_threshold, then clada_sparse_ffn_stack_decode ({'two' if B == 1 else 'three'} lanes) on the "
+                      "L independent layers" if use_stack else "clada_signals_threshold, then L calls of clada_sparse_ffn_decode"),
         "per_layer_calls": per_layer,
         "stack_modes": stack,
         "step_gbs_on_bytes_touched": round(bytes_layer * L / (ms_sparse * 1e-3) / 1e9, 1),
@@ -501,7 +501,7 @@ def main():
                      # the timed step itself: with two lanes two launches share the chip at any time, so the
                      # duration of one launch says little; what counts is the rate at which launches complete
                      # (step time / L, the signals launch included)
-                     "in_step": {"launches_in_flight": 2 if (use_stack and not args.per_layer and L >= 4) else 1,
+                     "in_step": {"lanes": (2 if B == 1 else 3) if (use_stack and L >= 4) else 1,
                                  "us_per_launch_completed": round(step_us_per_layer, 2),
                                  "achieved": round(bytes_layer / (step_us_per_layer * 1e-6) / 1e9, 1),
                                  "frac": round(bytes_layer / (step_us_per_layer * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}},

@@ -277,21 +277,23 @@ clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer *layer, co
  *   1            one persistent kernel walks the layers (bf16 rows of 4, 5, 8 or 10 KiB,
  *                all workgroups resident at once); measured slower for sparse stacks.
  *   0            the L per-layer calls, issued by the library.
- *   layers [L] (host array; all of one d, d_ff, dtype and kind), x [L][d], y [L][d]
- *   (layer dtype), tau_final [L] (clada_threshold's output for B = 1), n_active [L][2]
- *   or NULL (per layer: {kept, kept}, the layout of the per-layer call for B = 1).
+ *   layers [L] (host array; all of one d, d_ff, dtype and kind), x [L][B][d], y [L][B][d]
+ *   (layer dtype), tau_final [L][B] (clada_threshold's output), 1 <= B <= 64, n_active
+ *   [L][1 + B] or NULL (per layer, the layout of the per-layer call).
  * Results are bit-identical to L calls of clada_sparse_ffn_decode with the same balancing
  * (modes 0 - 2: the context's "decode.b1"; mode 3: as with "decode.b1" = 2): the same
- * kernels' order of summation.  Modes 2 and 3 need the batch-1 kernel's shapes (rows of
- * whole KiB), 256 compute units or more and n_active = NULL; modes 1 - 3 fall back to
- * mode 0 where they do not apply.  The remarks on clada_device_fault apply to modes 0 - 2
+ * kernels' order of summation.  For B = 1, modes 2 and 3 need the batch-1 kernel's shapes
+ * (rows of whole KiB), 256 compute units or more and n_active = NULL.  For B >= 2 there is
+ * mode 3 only: the units (layer, pass of up to 16 tokens) of the matrix-core path go round
+ * three lanes, where that path applies (bf16, its widths) and n_active = NULL.  Every mode
+ * falls back to mode 0 where it does not apply.  The remarks on clada_device_fault apply to modes 0 - 2
  * (balanced kernels wait, bounded, for their own workgroups).  A context serves one call
  * at a time, on whatever stream.  clada_dense_ffn_stack_decode is the dense twin. */
 clada_status clada_sparse_ffn_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L,
-                                           const void *x, const float *tau_final, void *y,
+                                           const void *x, int32_t B, const float *tau_final, void *y,
                                            int32_t *n_active, void *hip_stream);
 clada_status clada_dense_ffn_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L,
-                                          const void *x, void *y, void *hip_stream);
+                                          const void *x, int32_t B, void *y, void *hip_stream);
 
 /* Prefix-static masks.  The generation phase of the algorithm "CLADA Inference"
  * says the masks are regenerated "by thresholding A": read literally, the

@@ -74,9 +74,9 @@ def load_library() -> C.CDLL:
     lib.clada_signals_threshold.argtypes = [vp, vp, C.c_int, i32, i32, vp, vp, vp, vp, i32, f32, f32, vp, vp, vp, vp]
     lib.clada_sparse_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp, vp, vp, vp, vp]
     lib.clada_dense_ffn_decode.argtypes = [vp, C.POINTER(_CLayer), vp, i32, vp, vp]
-    lib.clada_sparse_ffn_stack_decode.argtypes = [vp, C.POINTER(_CLayer), i32, vp, vp, vp, vp, vp]
+    lib.clada_sparse_ffn_stack_decode.argtypes = [vp, C.POINTER(_CLayer), i32, vp, i32, vp, vp, vp, vp]
     lib.clada_sparse_ffn_stack_decode.restype = C.c_int
-    lib.clada_dense_ffn_stack_decode.argtypes = [vp, C.POINTER(_CLayer), i32, vp, vp, vp]
+    lib.clada_dense_ffn_stack_decode.argtypes = [vp, C.POINTER(_CLayer), i32, vp, i32, vp, vp]
     lib.clada_dense_ffn_stack_decode.restype = C.c_int
     lib.clada_diag_stream_read.argtypes = [vp, vp, C.c_size_t, i32, vp]
     lib.clada_diag_copy.argtypes = [vp, vp, vp, C.c_size_t, vp]
@@ -345,27 +345,32 @@ def layer_array(layers):
     return (_CLayer * len(layers))(*[l.c_struct() for l in layers])
 
 
+def _stack_batch(layers, x):
+    L = len(layers)
+    assert x.is_cuda and x.is_contiguous() and x.shape[0] == L and x.dim() in (2, 3) and x.dtype == layers[0].w_gate.dtype
+    return L, (1 if x.dim() == 2 else x.shape[1])
+
+
 def sparse_ffn_stack_decode(ctx: Context, layers, x: torch.Tensor, tau_final: torch.Tensor,
                             y: torch.Tensor | None = None, want_counts: bool = False, c_layers=None):
-    """x [L][d], tau_final [L] -> y [L][d] (and n_active [L][2] int32 with want_counts): one launch for the stack."""
-    L = len(layers)
+    """x [L][d] or [L][B][d], tau_final [L] or [L][B] -> y like x (and n_active [L][1+B] int32 with
+    want_counts): the L layers of a stack in one call."""
+    L, B = _stack_batch(layers, x)
     arr = c_layers if c_layers is not None else layer_array(layers)
-    assert x.is_cuda and x.is_contiguous() and x.shape[0] == L and x.dtype == layers[0].w_gate.dtype
-    assert tau_final.is_cuda and tau_final.dtype == torch.float32 and tau_final.numel() == L and tau_final.is_contiguous()
+    assert tau_final.is_cuda and tau_final.dtype == torch.float32 and tau_final.numel() == L * B and tau_final.is_contiguous()
     if y is None:
         y = torch.empty_like(x)
-    cnt = torch.empty(L, 2, dtype=torch.int32, device=x.device) if want_counts else None
-    ctx.check(ctx._lib.clada_sparse_ffn_stack_decode(ctx._h, arr, L, _ptr(x), _ptr(tau_final), _ptr(y), _ptr(cnt), _stream(x)))
+    cnt = torch.empty(L, 1 + B, dtype=torch.int32, device=x.device) if want_counts else None
+    ctx.check(ctx._lib.clada_sparse_ffn_stack_decode(ctx._h, arr, L, _ptr(x), B, _ptr(tau_final), _ptr(y), _ptr(cnt), _stream(x)))
     return (y, cnt) if want_counts else y
 
 
 def dense_ffn_stack_decode(ctx: Context, layers, x: torch.Tensor, y: torch.Tensor | None = None, c_layers=None):
-    L = len(layers)
+    L, B = _stack_batch(layers, x)
     arr = c_layers if c_layers is not None else layer_array(layers)
-    assert x.is_cuda and x.is_contiguous() and x.shape[0] == L and x.dtype == layers[0].w_gate.dtype
     if y is None:
         y = torch.empty_like(x)
-    ctx.check(ctx._lib.clada_dense_ffn_stack_decode(ctx._h, arr, L, _ptr(x), _ptr(y), _stream(x)))
+    ctx.check(ctx._lib.clada_dense_ffn_stack_decode(ctx._h, arr, L, _ptr(x), B, _ptr(y), _stream(x)))
     return y
 
 

@@ -76,8 +76,8 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->capturing = 0;
     ctx->opt_diag_events = 0;
     ctx->ev[0] = ctx->ev[1] = ctx->ev[2] = ctx->ev[3] = nullptr;
-    ctx->lane_stream = nullptr;
-    ctx->ev_lane[0] = ctx->ev_lane[1] = nullptr;
+    ctx->lane_stream[0] = ctx->lane_stream[1] = nullptr;
+    ctx->ev_lane[0] = ctx->ev_lane[1] = ctx->ev_lane[2] = nullptr;
     ctx->err[0] = 0;
     if (workspace_bytes > 0) {
         hipError_t e = hipSetDevice(device_id);
@@ -105,9 +105,10 @@ void clada_destroy(clada_ctx *ctx)
     if (!ctx) return;
     for (int i = 0; i < 4; ++i)
         if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 3; ++i)
         if (ctx->ev_lane[i]) (void)hipEventDestroy(ctx->ev_lane[i]);
-    if (ctx->lane_stream) (void)hipStreamDestroy(ctx->lane_stream);
+    for (int i = 0; i < 2; ++i)
+        if (ctx->lane_stream[i]) (void)hipStreamDestroy(ctx->lane_stream[i]);
     if (ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
 }

@@ -24,8 +24,8 @@ struct clada_ctx {
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)
     hipEvent_t ev[4];            // start/stop of the main decode kernel, start/stop of the final reduction
     int capturing;               // a clada_graph_begin is open
-    hipStream_t lane_stream;     // second lane of the whole-stack calls (created at the first such call, default priority)
-    hipEvent_t ev_lane[2];       // fork and join of the two lanes
+    hipStream_t lane_stream[2];  // further lanes of the whole-stack calls (created at the first such call, default priority)
+    hipEvent_t ev_lane[3];       // fork, and the join of either further lane
     // workgroups per compute unit of the balanced batch-1 kernel instances on this context's device
     // (asked of the runtime once per instance; the balanced kernel needs all its workgroups resident)
     const void *occ_fn[CLADA_OCC_SLOTS];
@@ -75,6 +75,8 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
                                   char *scratch, bool dense, hipStream_t stream, bool *ran,
                                   const int32_t *list = nullptr, const int32_t *list_n = nullptr);
 size_t clada_ws_decode_batched(int32_t d_ff);
+size_t clada_ws_decode_batched_partial(int32_t d);
+bool clada_decode_batched_eligible(const clada_ctx *ctx, const clada_layer *layer, int32_t B);
 // Batch-1 decode over a neuron list with the streaming kernel, when the shape fits it (*ran).
 hipError_t clada_decode_list_b1(clada_ctx *ctx, const clada_layer *layer, const void *x, const int32_t *idx,
                                 const int32_t *n_active, float *partial, int *P_out, hipStream_t stream, bool *ran);

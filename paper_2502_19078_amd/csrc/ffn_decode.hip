@@ -1618,8 +1618,39 @@ hipError_t launch_stack(clada_ctx *ctx, const StackParams &p, int P, bool dense,
     return launch_stack_variant<ES, NCH, DCH, false, false, RELU>(ctx, p, P, st);
 }
 
-clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L, const void *x, const float *tau,
-                              void *y, int32_t *n_active, bool dense, void *hip_stream)
+// Lanes of the whole-stack calls: lane 0 is the caller's stream, the others belong to the context.  lanes_fork
+// makes the further lanes wait for what the caller's stream holds so far, lanes_join makes the caller's stream
+// wait for them; both are events, so a capture of the caller's stream takes the lanes in.
+hipError_t lanes_fork(clada_ctx *ctx, int n_lanes, hipStream_t stream)
+{
+    if (n_lanes < 2) return hipSuccess;
+    hipError_t e;
+    for (int i = 0; i < n_lanes - 1; ++i)
+        if (!ctx->lane_stream[i] && (e = hipStreamCreateWithFlags(&ctx->lane_stream[i], hipStreamNonBlocking)) != hipSuccess) return e;
+    for (int i = 0; i < 3; ++i)
+        if (!ctx->ev_lane[i] && (e = hipEventCreateWithFlags(&ctx->ev_lane[i], hipEventDisableTiming)) != hipSuccess) return e;
+    if ((e = hipEventRecord(ctx->ev_lane[0], stream)) != hipSuccess) return e;
+    for (int i = 0; i < n_lanes - 1; ++i)
+        if ((e = hipStreamWaitEvent(ctx->lane_stream[i], ctx->ev_lane[0], 0)) != hipSuccess) return e;
+    return hipSuccess;
+}
+
+hipError_t lanes_join(clada_ctx *ctx, int n_lanes, hipStream_t stream)
+{
+    hipError_t e;
+    for (int i = 0; i < n_lanes - 1; ++i) {
+        if ((e = hipEventRecord(ctx->ev_lane[1 + i], ctx->lane_stream[i])) != hipSuccess) return e;
+        if ((e = hipStreamWaitEvent(stream, ctx->ev_lane[1 + i], 0)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Scratch of lane 1 and 2 for batches (lane 0 uses the regions of the per-layer call): partial outputs of one
+// pass and the batched path's own scratch, behind everything else of the decode workspace.
+size_t ws_lane_bytes(int d, int F) { return clada_ws_decode_batched_partial(d) + clada_ws_decode_batched(F); }
+
+clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L, const void *x, int32_t B,
+                              const float *tau, void *y, int32_t *n_active, bool dense, void *hip_stream)
 {
     if (!ctx) return CLADA_ERR_NULL;
     if (!layers) return clada_fail(ctx, CLADA_ERR_NULL, "layers is NULL");
@@ -1632,9 +1663,10 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
             return clada_fail(ctx, CLADA_ERR_SHAPE, "layer %d differs from layer 0 in d, d_ff, dtype or kind", l);
     }
     if (!x || !y || (!dense && !tau)) return clada_fail(ctx, CLADA_ERR_NULL, "x, y or tau_final is NULL");
+    if (B < 1 || B > CLADA_MAX_BATCH) return clada_fail(ctx, CLADA_ERR_SHAPE, "B=%d outside [1,%d]", B, CLADA_MAX_BATCH);
     if (!aligned16(x) || !aligned16(y)) return clada_fail(ctx, CLADA_ERR_ALIGN, "x and y must be 16-byte aligned");
     const int d = layers[0].d, F = layers[0].d_ff;
-    const size_t need = CLADA_WS_HEADER + clada_ws_decode(d, F, 1);
+    const size_t need = CLADA_WS_HEADER + clada_ws_decode(d, F, B);
     if (ctx->ws_bytes < need)
         return clada_fail(ctx, CLADA_ERR_WORKSPACE, "workspace %zu < %zu bytes needed", ctx->ws_bytes, need);
     const int es = (int)dtype_size(layers[0].dtype);
@@ -1647,7 +1679,7 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
     // else, and a launch that cannot hold all its workgroups at once, runs as L per-layer calls
     const bool shape_ok = (d * es) % 1024 == 0 && es == 2 &&
                           (relu ? nch == 5 : (nch == 4 || nch == 8 || nch == 10));
-    bool persistent = ctx->opt_decode_stack == 1 && ctx->opt_decode_b1 >= 1 && shape_ok && F >= Pb && ni_b <= 64;
+    bool persistent = B == 1 && ctx->opt_decode_stack == 1 && ctx->opt_decode_b1 >= 1 && shape_ok && F >= Pb && ni_b <= 64;
     if (persistent) {
         const double phase2_bytes = (relu ? 1.0 : 2.0) * (double)F * d * es;
         const bool balance = !dense && ni_b <= 56 &&
@@ -1702,16 +1734,12 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
     // Counts per layer need the flag arrays and the list kernel of the per-layer call, so a call that asks
     // for them runs the per-layer calls below.
     const int smode = ctx->opt_decode_stack;
-    const bool own_launches = smode >= 2 && ctx->opt_decode_b1 >= 1 && !n_active && (d * es) % 1024 == 0 &&
+    const bool own_launches = B == 1 && smode >= 2 && ctx->opt_decode_b1 >= 1 && !n_active && (d * es) % 1024 == 0 &&
                               b1_shape_ok(es, nch, relu) && Pb == COOP_MAX_WGS && F >= Pb && ni_b <= 1024 && L >= 2;
     if (own_launches) {
         static_assert(COOP_MAX_WGS == 256, "the chained reduction is laid out for 256 partial outputs");
         const int n_lanes = (smode == 3 && L >= 4) ? 2 : 1;
         const bool chained = smode == 2;
-        if (n_lanes == 2 && !ctx->lane_stream) {
-            CLADA_CHECK_HIP(ctx, hipStreamCreateWithFlags(&ctx->lane_stream, hipStreamNonBlocking));
-            for (int i = 0; i < 2; ++i) CLADA_CHECK_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_lane[i], hipEventDisableTiming));
-        }
         unsigned int *epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
         float *part = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
         bool balance = smode == 2 && b1_wants_balance(ctx, dense, relu, ni_b, d, F, es);      // (mode 3 never balances, whatever L: one set of bits)
@@ -1725,14 +1753,11 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
         b.d = d; b.F = F;
         b.K0 = ctx->opt_decode_own_first > 0 ? ctx->opt_decode_own_first : 14;
         b.gelu = layers[0].kind == CLADA_FFN_GEGLU ? 1 : 0;
-        if (n_lanes == 2) {
-            CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev_lane[0], stream));
-            CLADA_CHECK_HIP(ctx, hipStreamWaitEvent(ctx->lane_stream, ctx->ev_lane[0], 0));
-        }
+        CLADA_CHECK_HIP(ctx, lanes_fork(ctx, n_lanes, stream));
         const size_t buf = (size_t)Pb * d;                   // floats of one buffer of partial outputs
         for (int l = 0; l < L; ++l) {
             const int lane = l % n_lanes, k = l / n_lanes;   // the layer is its lane's k-th
-            hipStream_t st = lane ? ctx->lane_stream : stream;
+            hipStream_t st = lane ? ctx->lane_stream[lane - 1] : stream;
             float *mine = part + (size_t)(2 * lane + (chained ? (k & 1) : 0)) * buf;
             const int lp = l - n_lanes;                      // the lane's previous layer
             b.wg = (const char *)layers[l].w_gate; b.wu = (const char *)layers[l].w_up; b.wd = (const char *)layers[l].w_down;
@@ -1752,15 +1777,48 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
                 CLADA_CHECK_HIP(ctx, hipGetLastError());
             }
         }
-        if (n_lanes == 2) {
-            CLADA_CHECK_HIP(ctx, hipEventRecord(ctx->ev_lane[1], ctx->lane_stream));
-            CLADA_CHECK_HIP(ctx, hipStreamWaitEvent(stream, ctx->ev_lane[1], 0));
-        }
+        CLADA_CHECK_HIP(ctx, lanes_join(ctx, n_lanes, stream));
+        return CLADA_OK;
+    }
+    // ---- batches on the matrix-core path: the units (layer, pass of up to 16 tokens) go round three lanes, each
+    // with its own partial outputs and scratch.  The path's three launches per unit and its thin ends weigh
+    // more than at batch 1 (c3 layer shape, B = 8: 69.5 -> 60.2 -> 58.5 us per layer with one, two, three lanes).
+    const int n_groups = (B + 15) / 16, per_group = (B + n_groups - 1) / n_groups;
+    if (B >= 2 && smode == 3 && !n_active && ctx->opt_decode_batched && L * n_groups >= 3 &&
+        clada_decode_batched_eligible(ctx, &layers[0], per_group) &&
+        clada_decode_batched_eligible(ctx, &layers[0], B - (n_groups - 1) * per_group)) {
+        const int n_lanes = 3;
+        char *ws = ctx->ws + CLADA_WS_HEADER;
+        char *lane_base[3];
+        lane_base[0] = nullptr;
+        lane_base[1] = ws + clada_ws_decode(d, F, B) - 2 * ws_lane_bytes(d, F);
+        lane_base[2] = lane_base[1] + ws_lane_bytes(d, F);
+        CLADA_CHECK_HIP(ctx, lanes_fork(ctx, n_lanes, stream));
+        int unit = 0;
+        for (int l = 0; l < L; ++l)
+            for (int g0 = 0; g0 < B; g0 += per_group, ++unit) {
+                const int Bg = (B - g0 < per_group) ? B - g0 : per_group;
+                const int lane = unit % n_lanes;
+                float *partial = lane ? reinterpret_cast<float *>(lane_base[lane]) : reinterpret_cast<float *>(ws);
+                char *scratch = lane ? lane_base[lane] + clada_ws_decode_batched_partial(d)
+                                     : ws + ws_partial_bytes(B, d) + align_up((size_t)B * F, 256);
+                const size_t row = (size_t)l * B + g0;
+                bool ran = false;
+                clada_status st = clada_decode_batched(ctx, &layers[l], (const char *)x + row * d * es, Bg, tau ? tau + row : nullptr,
+                                                       (char *)y + row * d * es, nullptr, partial, scratch, dense,
+                                                       lane ? ctx->lane_stream[lane - 1] : stream, &ran);
+                if (st != CLADA_OK || !ran) {
+                    (void)lanes_join(ctx, n_lanes, stream);      // leave no lane forked (a capture would not end)
+                    return st != CLADA_OK ? st : clada_fail(ctx, CLADA_ERR_SHAPE, "batched path refused a unit it had accepted");
+                }
+            }
+        CLADA_CHECK_HIP(ctx, lanes_join(ctx, n_lanes, stream));
         return CLADA_OK;
     }
     for (int l = 0; l < L; ++l) {
-        clada_status st = run_decode(ctx, &layers[l], (const char *)x + (size_t)l * d * es, 1, tau ? tau + l : nullptr,
-                                     (char *)y + (size_t)l * d * es, nullptr, n_active ? n_active + 2 * l : nullptr,
+        const size_t row = (size_t)l * B;
+        clada_status st = run_decode(ctx, &layers[l], (const char *)x + row * d * es, B, tau ? tau + row : nullptr,
+                                     (char *)y + row * d * es, nullptr, n_active ? n_active + (size_t)(1 + B) * l : nullptr,
                                      nullptr, dense, hip_stream);
         if (st != CLADA_OK) return st;
     }
@@ -1786,7 +1844,7 @@ size_t clada_ws_decode(int32_t d, int32_t d_ff, int32_t B)
 {
     if (B <= 0) return 0;
     return ws_partial_bytes(B, d) + align_up((size_t)B * d_ff, 256) +
-           clada_ws_decode_batched(d_ff);
+           clada_ws_decode_batched(d_ff) + (B >= 2 ? 2 * ws_lane_bytes(d, d_ff) : 0);
 }
 
 extern "C" clada_status clada_sparse_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
@@ -1804,14 +1862,14 @@ extern "C" clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer
 }
 
 extern "C" clada_status clada_sparse_ffn_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L,
-                                                      const void *x, const float *tau_final, void *y,
+                                                      const void *x, int32_t B, const float *tau_final, void *y,
                                                       int32_t *n_active, void *hip_stream)
 {
-    return run_stack_decode(ctx, layers, L, x, tau_final, y, n_active, false, hip_stream);
+    return run_stack_decode(ctx, layers, L, x, B, tau_final, y, n_active, false, hip_stream);
 }
 
 extern "C" clada_status clada_dense_ffn_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L,
-                                                     const void *x, void *y, void *hip_stream)
+                                                     const void *x, int32_t B, void *y, void *hip_stream)
 {
-    return run_stack_decode(ctx, layers, L, x, nullptr, y, nullptr, true, hip_stream);
+    return run_stack_decode(ctx, layers, L, x, B, nullptr, y, nullptr, true, hip_stream);
 }

@@ -515,20 +515,16 @@ size_t clada_ws_decode_batched(int32_t d_ff)
            align_up(sizeof(int) * COOP_MAX_WGS, 256);
 }
 
-// Returns CLADA_OK when the batched MFMA path ran, CLADA_ERR_SHAPE (without touching ctx->err) when
-// the shape is not eligible and the caller should use the generic kernels.
-clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, const void *x, int32_t B,
-                                  const float *tau, void *y, unsigned char *keep, float *partial,
-                                  char *scratch, bool dense, hipStream_t stream, bool *ran,
-                                  const int32_t *list, const int32_t *list_n)
+// Launch shape of the batched path for a layer and a pass of B tokens; false when the shape is not eligible
+// (decided by dtype and sizes alone, before anything is launched).
+static bool bat_plan(const clada_ctx *ctx, const clada_layer *layer, int B, int *P_out, int *CG_out, int *RG_out)
 {
-    *ran = false;
     const int d = layer->d, F = layer->d_ff;
-    if (layer->dtype != CLADA_BF16 || B < 2 || B > 16) return CLADA_OK;
+    if (layer->dtype != CLADA_BF16 || B < 2 || B > 16) return false;
     const int ksteps = d / 256;                                  // 8 waves x ksteps x 32 = d (5 waves x 16 or 32 x 32 for ksteps 10, 20)
     if (d % 256 != 0 || !(ksteps == 4 || ksteps == 8 || ksteps == 10 || ksteps == 12 || ksteps == 16 || ksteps == 20 ||
                           ksteps == 24 || ksteps == 32))
-        return CLADA_OK;
+        return false;
     const int P = ctx->num_cu < COOP_MAX_WGS ? ctx->num_cu : COOP_MAX_WGS;
     const int CG = (d + DN_COLS - 1) / DN_COLS;
     int RG = P / CG;
@@ -545,7 +541,34 @@ clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, cons
         return true;
     };
     while (!group_fits(RG) && RG < 64) RG *= 2;                         // wide layers: more, smaller row groups
-    if (!group_fits(RG)) return CLADA_OK;
+    if (!group_fits(RG)) return false;
+    *P_out = P; *CG_out = CG; *RG_out = RG;
+    return true;
+}
+
+bool clada_decode_batched_eligible(const clada_ctx *ctx, const clada_layer *layer, int32_t B)
+{
+    int P, CG, RG;
+    return bat_plan(ctx, layer, B, &P, &CG, &RG);
+}
+
+// Bytes of partial outputs one pass of the batched path writes at most: [RG <= 64][B <= 16][d] fp32.
+size_t clada_ws_decode_batched_partial(int32_t d)
+{
+    return align_up(sizeof(float) * 64 * 16 * (size_t)d, 256);
+}
+
+// Runs the batched MFMA path when the shape is eligible (*ran; an ineligible shape launches nothing and the
+// caller uses the generic kernels).
+clada_status clada_decode_batched(clada_ctx *ctx, const clada_layer *layer, const void *x, int32_t B,
+                                  const float *tau, void *y, unsigned char *keep, float *partial,
+                                  char *scratch, bool dense, hipStream_t stream, bool *ran,
+                                  const int32_t *list, const int32_t *list_n)
+{
+    *ran = false;
+    const int d = layer->d, F = layer->d_ff;
+    int P, CG, RG;
+    if (!bat_plan(ctx, layer, B, &P, &CG, &RG)) return CLADA_OK;
 
     BatParams p;
     p.wg = (const char *)layer->w_gate; p.wu = (const char *)layer->w_up; p.wd = (const char *)layer->w_down;

@@ -81,13 +81,15 @@ int main()
     EXPECT(clada_mask_sparse_decode(ctx, (const uint8_t *)p, (const int32_t *)p, 16, nullptr, 64, (uint32_t *)p, nullptr), CLADA_ERR_WORKSPACE);
     {
         clada_layer two[2] = {ok, ok};
-        EXPECT(clada_sparse_ffn_stack_decode(ctx, nullptr, 2, p, (const float *)p, p, nullptr, nullptr), CLADA_ERR_NULL);
-        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 0, p, (const float *)p, p, nullptr, nullptr), CLADA_ERR_SHAPE);
-        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 2, p, nullptr, p, nullptr, nullptr), CLADA_ERR_NULL);
-        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 2, p, (const float *)p, p, nullptr, nullptr), CLADA_ERR_WORKSPACE);
-        EXPECT(clada_dense_ffn_stack_decode(ctx, two, 2, p, p, nullptr), CLADA_ERR_WORKSPACE);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, nullptr, 2, p, 1, (const float *)p, p, nullptr, nullptr), CLADA_ERR_NULL);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 0, p, 1, (const float *)p, p, nullptr, nullptr), CLADA_ERR_SHAPE);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 2, p, 1, nullptr, p, nullptr, nullptr), CLADA_ERR_NULL);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 2, p, 1, (const float *)p, p, nullptr, nullptr), CLADA_ERR_WORKSPACE);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 2, p, 65, (const float *)p, p, nullptr, nullptr), CLADA_ERR_SHAPE);
+        EXPECT(clada_sparse_ffn_stack_decode(ctx, two, 2, p, 8, (const float *)p, p, nullptr, nullptr), CLADA_ERR_WORKSPACE);
+        EXPECT(clada_dense_ffn_stack_decode(ctx, two, 2, p, 1, p, nullptr), CLADA_ERR_WORKSPACE);
         two[1].d_ff = ok.d_ff * 2;
-        EXPECT(clada_dense_ffn_stack_decode(ctx, two, 2, p, p, nullptr), CLADA_ERR_SHAPE);
+        EXPECT(clada_dense_ffn_stack_decode(ctx, two, 2, p, 1, p, nullptr), CLADA_ERR_SHAPE);
     }
     // options, error text, fault query, graph helpers
     EXPECT(clada_set_option(ctx, "decode.stack", 1), CLADA_OK);

@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import synth
-from gpu_util import DEV, TOL_Y, assert_close_y, check_mask_band, to_dev, to_np
+from gpu_util import DEV, TOL_Y, assert_close_y, check_mask_band, to_dev, to_np, unpack_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -141,7 +141,7 @@ def test_stack_call_rejects_mixed_layers_and_bad_arguments(clada):
     with pytest.raises(CladaError):
         clada.sparse_ffn_stack_decode(ctx, [layers[0], other], xd, td)
     with pytest.raises(CladaError):
-        ctx.check(ctx._lib.clada_sparse_ffn_stack_decode(ctx._h, None, 2, xd.data_ptr(), td.data_ptr(), xd.data_ptr(), None, None))
+        ctx.check(ctx._lib.clada_sparse_ffn_stack_decode(ctx._h, None, 2, xd.data_ptr(), 1, td.data_ptr(), xd.data_ptr(), None, None))
 
 
 @pytest.mark.parametrize("mode", [1, 2])      # (two lanes run kernels that wait for nobody)
@@ -208,4 +208,84 @@ def test_stack_call_modes_agree_and_replay_from_a_graph(clada):
                 if b1 == 2 or mode == 3:
                     assert torch.equal(got[0], clada.sparse_ffn_decode(ctx2, layers[0], xs[:1].contiguous(), ts[:1].contiguous())[0])
         del g
+    assert not ctx.device_fault()
+
+
+def _batch_stack(clada, cfg_name, d, F, L, B, seed, shared_frac=0.5):
+    cfg = synth.CONFIGS[cfg_name]
+    ws = [synth.layer_weights(cfg, seed, l, d=d, d_ff=F) for l in range(L)]
+    layers = [clada.Layer(*[to_dev(a, cfg.dtype) for a in w]) for w in ws]
+    x = np.stack([synth.decode_hidden(cfg, seed, l, 0, B=B, d=d, shared_frac=shared_frac) for l in range(L)])   # [L][B][d]
+    return cfg, ws, layers, x
+
+
+# cfg, d, F, L, B: three lanes on the matrix-core path (one and two passes of tokens per layer, 4 and 10 KiB
+# rows, fewer units than lanes), and batches that path does not take (fp32; a width it has no instance for)
+BATCH_CASES = [
+    ("c3", 4096, 3000, 5, 8),
+    ("c5", 5120, 2100, 4, 16),
+    ("c3", 4096, 1500, 3, 20),
+    ("c3", 2048, 1024, 1, 4),
+    ("c1", 512, 700, 3, 4),
+    ("c3", 1536, 900, 3, 3),
+]
+
+
+@pytest.mark.parametrize("cfg_name,d,F,L,B", BATCH_CASES)
+def test_batched_stack_call_is_the_per_layer_calls_bit_for_bit(clada, cfg_name, d, F, L, B):
+    cfg, ws, layers, x = _batch_stack(clada, cfg_name, d, F, L, B, seed=31)
+    ctx = clada.Context(0, clada.workspace_bytes(d, F, B, 0, 0))
+    tau = np.stack([np.quantile(np.abs(oracle.gate_act(ws[l][0], x[l])), 0.45, axis=1) for l in range(L)]).astype(np.float32)
+    xd, td = to_dev(x, cfg.dtype), torch.from_numpy(tau).to(DEV)
+    y_ref, cnt_ref, yd_ref = [], [], []
+    for l in range(L):
+        yl, _, cl, _ = clada.sparse_ffn_decode(ctx, layers[l], xd[l], td[l], want_lists=True)
+        y_ref.append(yl.clone())
+        cnt_ref.append(cl.clone())
+        yd_ref.append(clada.dense_ffn_decode(ctx, layers[l], xd[l]).clone())
+    for rep in range(3):
+        if rep < 2:
+            y, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td), None
+        else:
+            y, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td, want_counts=True)
+        torch.cuda.synchronize()
+        for l in range(L):
+            assert torch.equal(y[l], y_ref[l]), f"rep {rep} layer {l}: bits differ from the per-layer call"
+            assert cnt is None or torch.equal(cnt[l], cnt_ref[l])
+    yd = clada.dense_ffn_stack_decode(ctx, layers, xd)
+    for l in range(L):
+        assert torch.equal(yd[l], yd_ref[l])
+    # the oracle, on the last layer: masks inside the band, y on the device's own masks
+    l = L - 1
+    ref = oracle.sparse_decode(*ws[l], x[l], tau[l].astype(np.float64))
+    _, _, _, bits = clada.sparse_ffn_decode(ctx, layers[l], xd[l], td[l], want_lists=True)
+    mask = unpack_bits(bits, F)
+    check_mask_band(mask, ref["act"], tau[l], "batched stack")
+    want = oracle.decode_given_mask(*ws[l], x[l], mask)
+    assert_close_y(to_np(y[l]), want, TOL_Y[cfg.dtype], f"layer {l} vs oracle on the device's masks")
+
+
+def test_batched_stack_call_replays_from_a_graph(clada):
+    cfg, ws, layers, x = _batch_stack(clada, "c3", 4096, 2048, 6, 8, seed=32)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 2048, 8, 0, 0))
+    xd = to_dev(x, cfg.dtype)
+    td = torch.full((6, 8), 0.2, dtype=torch.float32, device=DEV)
+    xs, ts, ys = xd.clone(), td.clone(), torch.empty_like(xd)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        clada.sparse_ffn_stack_decode(ctx, layers, xs, ts, y=ys)
+        stream.synchronize()
+        clada.graph_begin(ctx)
+        clada.sparse_ffn_stack_decode(ctx, layers, xs, ts, y=ys)
+        g = clada.graph_end(ctx)
+        for rep in range(4):
+            xs.copy_(torch.roll(xd, rep, dims=0))
+            ts.fill_(0.15 + 0.05 * rep)
+            g.launch()
+            stream.synchronize()
+            got = ys.clone()
+            for l in (0, 5):
+                assert torch.equal(got[l], clada.sparse_ffn_decode(ctx, layers[l], xs[l], ts[l])), f"replay {rep} layer {l}"
+            stream.synchronize()
     assert not ctx.device_fault()
