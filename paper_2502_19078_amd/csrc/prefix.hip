@@ -406,7 +406,9 @@ k_prefix_gateup_bf16(const GateUpParams p)
 // Epilogue of the 256-token kernel for one wave: 128 tokens (rows tm128*128 ..) x 64 neurons, gate
 // accumulators acc[0], up accumulators acc[1].  FULL = the whole block lies inside [T] x [F], so no
 // element needs a bounds check.  Writes the per-neuron partial sums of these 128 tokens.
-template <bool FULL>
+// SINGLE (non-gated family): the tile is 256 neurons wide and both accumulator sets are pre-activations, acc[w]
+// of the neurons tn*256 + w*128 + ...
+template <bool FULL, bool SINGLE>
 __device__ __forceinline__ void wide_epilogue(const f32x16 (&acc)[2][4][2], const GateUpParams &p, int tm128, int tn,
                                               int wn, int lane)
 {
@@ -414,8 +416,9 @@ __device__ __forceinline__ void wide_epilogue(const f32x16 (&acc)[2][4][2], cons
     const int t0 = tm128 * 128 + 4 * (lane >> 5);          // row of accumulator register 0 of block mb = 0
     const size_t F1 = (size_t)p.F, Fp1 = (size_t)p.Fp;
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const int j = tn * BN + wn * 64 + nb * 32 + n;
+    for (int wnb = 0; wnb < (SINGLE ? 4 : 2); ++wnb) {
+        const int w = wnb >> 1, nb = wnb & 1;
+        const int j = tn * (SINGLE ? 2 * BN : BN) + w * BN + wn * 64 + nb * 32 + n;
         const bool jok = FULL || j < p.F;
         const float bj = (p.relu && p.b_in && jok) ? p.b_in[j] : 0.0f;
         float s_abs = 0.f, s_sq = 0.f, mx = 0.f, s_h2 = 0.f;
@@ -425,8 +428,8 @@ __device__ __forceinline__ void wide_epilogue(const f32x16 (&acc)[2][4][2], cons
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 float a, h;
-                if (p.relu) {
-                    const float g = acc[0][mb][nb][r] + bj;
+                if (SINGLE || p.relu) {
+                    const float g = acc[SINGLE ? w : 0][mb][nb][r] + bj;
                     a = g > 0.0f ? g : (g != g ? g : 0.0f);
                     h = a;
                 } else {
@@ -489,22 +492,27 @@ __device__ __forceinline__ void wide_epilogue(const f32x16 (&acc)[2][4][2], cons
 constexpr int GW_STAGE = 32 * 1024;    // X 256 x 64 B | gate 128 x 64 B | up 128 x 64 B
 constexpr int GW_G = 16 * 1024, GW_U = 24 * 1024;
 
+// SINGLE: the non-gated family has one input matrix, so the second operand is the next 128 rows of the same
+// matrix and the workgroup tile is 256 tokens x 256 neurons of one GEMM (nothing is computed twice).
+template <bool SINGLE>
 __global__ void __launch_bounds__(256)
 k_prefix_gateup_bf16_wide(const GateUpParams p)
 {
     __shared__ __align__(16) char s_w[4 * GW_STAGE];
 
+    constexpr int TN = SINGLE ? 2 * BN : BN;                // neurons per workgroup tile
+    const int n_tn = SINGLE ? (p.F + TN - 1) / TN : p.n_tn;
     const int n_tmw = (p.T + 255) / 256;
     int tm, tn;
     if (n_tmw % 8 == 0) {                                   // 8 token tiles x 4 neuron tiles per XCD at a time
-        const int tn_pad = (p.n_tn + 3) / 4 * 4;
+        const int tn_pad = (n_tn + 3) / 4 * 4;
         const int o = remap_block(blockIdx.x, n_tmw * tn_pad);
         const int sb = o >> 5, w = o & 31, tmb = n_tmw >> 3;
         tm = (sb % tmb) * 8 + (w & 7);
         tn = (sb / tmb) * 4 + (w >> 3);
-        if (tn >= p.n_tn) return;
+        if (tn >= n_tn) return;
     } else {
-        const int total = n_tmw * p.n_tn;
+        const int total = n_tmw * n_tn;
         const int tile = remap_block(blockIdx.x, total);
         if (tile >= total) return;
         tm = tile % n_tmw;
@@ -536,9 +544,10 @@ k_prefix_gateup_bf16_wide(const GateUpParams p)
     }
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-        const int j = min(tn * BN + 16 * (wave + 4 * c) + lr, p.F - 1);
+        const int j = min(tn * TN + 16 * (wave + 4 * c) + lr, p.F - 1);
         gg[c] = p.wg + (size_t)j * rowbytes + koff;
-        gu[c] = p.wu + (size_t)j * rowbytes + koff;
+        if (SINGLE) gu[c] = p.wg + (size_t)min(j + BN, p.F - 1) * rowbytes + koff;
+        else gu[c] = p.wu + (size_t)j * rowbytes + koff;
     }
     const int nk = p.d / 32;
     // transfer i (0..7) of this wave for k-tile kt: four X pieces, two gate, two up
@@ -679,8 +688,8 @@ k_prefix_gateup_bf16_wide(const GateUpParams p)
 
     // ------------------------------------------------------------------ epilogue: this wave's 128 tokens x 64 neurons
     const int tm128 = 2 * tm + wm;
-    if (tm128 * 128 + 128 <= p.T && tn * BN + BN <= p.F) wide_epilogue<true>(acc, p, tm128, tn, wn, lane);
-    else wide_epilogue<false>(acc, p, tm128, tn, wn, lane);
+    if (tm128 * 128 + 128 <= p.T && tn * TN + TN <= p.F) wide_epilogue<true, SINGLE>(acc, p, tm128, tn, wn, lane);
+    else wide_epilogue<false, SINGLE>(acc, p, tm128, tn, wn, lane);
 }
 
 struct DownParams {
@@ -1323,9 +1332,14 @@ hipError_t clada_prefix_gateup(const clada_layer *layer, const void *x, int T, f
     const int n_tmw = (T + 255) / 256;
     const bool wide_ok = es == 2 && d % 64 == 0;
     const bool wide = wide_ok && (tile_mode == 2 || (tile_mode == 0 && T > 128));     // measured faster from T = 512 down
-    if (wide) {
+    if (wide && relu) {                                     // one GEMM over 256-neuron tiles
+        const int n_tn2 = (F + 2 * BN - 1) / (2 * BN);
+        const int blocks = n_tmw % 8 == 0 ? n_tmw * ((n_tn2 + 3) / 4 * 4) : n_tmw * n_tn2;
+        hipLaunchKernelGGL(k_prefix_gateup_bf16_wide<true>, dim3((blocks + 7) / 8 * 8), dim3(256), 0, stream, g);
+    }
+    else if (wide) {
         const int blocks = n_tmw % 8 == 0 ? n_tmw * ((g.n_tn + 3) / 4 * 4) : n_tmw * g.n_tn;
-        hipLaunchKernelGGL(k_prefix_gateup_bf16_wide, dim3((blocks + 7) / 8 * 8), dim3(256), 0, stream, g);
+        hipLaunchKernelGGL(k_prefix_gateup_bf16_wide<false>, dim3((blocks + 7) / 8 * 8), dim3(256), 0, stream, g);
     }
     else if (es == 4) hipLaunchKernelGGL(k_prefix_gateup<4>, dim3(grid), dim3(256), 0, stream, g);
     else if (d % 64 == 0) hipLaunchKernelGGL(k_prefix_gateup_bf16, dim3((total_blk + 7) / 8 * 8), dim3(256), 0, stream, g);
