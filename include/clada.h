@@ -288,7 +288,9 @@ clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer *layer, co
  * three lanes, where that path applies (bf16, its widths) and n_active = NULL.  Every mode
  * falls back to mode 0 where it does not apply.  The remarks on clada_device_fault apply to modes 0 - 2
  * (balanced kernels wait, bounded, for their own workgroups).  A context serves one call
- * at a time, on whatever stream.  clada_dense_ffn_stack_decode is the dense twin. */
+ * at a time, on whatever stream.  The first call in mode 3 creates the context's lane streams
+ * and events: make it before hip_stream is captured.  clada_dense_ffn_stack_decode is the
+ * dense twin. */
 clada_status clada_sparse_ffn_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t L,
                                            const void *x, int32_t B, const float *tau_final, void *y,
                                            int32_t *n_active, void *hip_stream);
