@@ -368,7 +368,7 @@ def main():
                      "indicators_off": _light(pl_off, ms_pl_dense, lambda rho: nmat / (nmat - (nmat - 1.0) * rho), B, L),
                      "dense_ms_per_step": round(ms_pl_dense, 4)}
         stack = {}
-        for mode, mode_name in ((3, "two_lanes"), (2, "chained_launches"), (1, "persistent_kernel")) if B == 1 else ((3, "three_lanes"),):
+        for mode, mode_name in ((3, "lanes"), (2, "chained_launches"), (1, "persistent_kernel")) if B == 1 else ((3, "lanes"),):
             ctx.set_option("decode.stack", mode)
             m = {}
             for name, (ts, th), reg in (("natural", (tau_s, tau_H), nat), ("indicators_off", (INF, INF), off)):
@@ -400,8 +400,8 @@ def main():
                 m["dense_ms_per_step"] = round(ms_dense_stack, 4)
             stack[mode_name] = m
         ctx.set_option("decode.stack", 3)
-        stack["what"] = ("modes of clada_sparse_ffn_stack_decode (option decode.stack).  two_lanes (default; value and "
-                         "ms_per_step of this line): even and odd layers on two streams, so that the compute units "
+        stack["what"] = ("modes of clada_sparse_ffn_stack_decode (option decode.stack).  lanes (default; value and "
+                         "ms_per_step of this line): the layers go round two or three streams, so that the compute units "
                          "one layer has released run the next already.  chained_launches: one stream, the kernel of "
                          "layer l also sums the partial outputs of layer l-1.  persistent_kernel: one launch walks "
                          "the L layers; slower for sparse stacks, kept for the record")
@@ -428,6 +428,9 @@ def main():
     torch.cuda.synchronize()
     ceil_gbs = min(L, 8) * F * d * es / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
+    nch = d * es // 1024
+    occ2 = es == 2 and d * es % 1024 == 0 and (nch == 5 if relu else nch in (4, 8)) and (F + 255) // 256 <= 64
+    n_lanes = 1 if (not use_stack or L < 4) else 3 if (B >= 2 or occ2) else 2      # what the library chooses for sparse stacks
     main_kernel = ("k_ffn_decode_b1 (input rows dense + output rows of kept neurons)" if B == 1 and relu
                    else "k_ffn_decode_b1 (gate rows dense + up/down rows of kept neurons)" if B == 1
                    else "k_bat_gateup + k_bat_down (batched decode, timed as one)")
@@ -476,7 +479,7 @@ def main():
             "call_frac": round(off["bytes_probe"] / (off["call_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
         "regime_indicators_on": _light(on, ms_dense, ideal, B, L) if on else None,
         "regime_negative_coefficients": dict(_light(neg, ms_dense, ideal, B, L), **{"lambda": -0.80, "gamma": -0.12}) if neg else None,
-        "step_path": (f"clada_signals_threshold, then clada_sparse_ffn_stack_decode ({'two' if B == 1 else 'three'} lanes) on the "
+        "step_path": (f"clada_signals_threshold, then clada_sparse_ffn_stack_decode (lanes on two or three streams) on the "
                       "L independent layers" if use_stack else "clada_signals_threshold, then L calls of clada_sparse_ffn_decode"),
         "per_layer_calls": per_layer,
         "stack_modes": stack,
@@ -501,7 +504,7 @@ def main():
                      # the timed step itself: with two lanes two launches share the chip at any time, so the
                      # duration of one launch says little; what counts is the rate at which launches complete
                      # (step time / L, the signals launch included)
-                     "in_step": {"lanes": (2 if B == 1 else 3) if (use_stack and L >= 4) else 1,
+                     "in_step": {"lanes": n_lanes,
                                  "us_per_launch_completed": round(step_us_per_layer, 2),
                                  "achieved": round(bytes_layer / (step_us_per_layer * 1e-6) / 1e9, 1),
                                  "frac": round(bytes_layer / (step_us_per_layer * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}},

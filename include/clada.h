@@ -72,9 +72,11 @@ const char *clada_last_error(const clada_ctx *ctx);
  * the launch allows it, 0 = the generic kernels), "decode.own_first" (1..14, neurons a
  * workgroup keeps for itself before the balanced hand-over; 0 = default),
  * "decode.wgs_per_cu" (1 or 2 workgroups per compute unit for the generic kernel),
- * "decode.stack" (how the whole-stack calls run: 3 = two lanes [default], 2 = chained
+ * "decode.stack" (how the whole-stack calls run: 3 = lanes [default], 2 = chained
  * launches, 1 = one persistent kernel for all layers where the shape has one, 0 = the L
- * per-layer calls; see clada_sparse_ffn_stack_decode),
+ * per-layer calls; see clada_sparse_ffn_stack_decode), "decode.lane_occ2" (1 = the lanes of
+ * batch-1 stacks with rows of 4, 5 or 8 KiB use the kernel instance of which two workgroups
+ * fit a compute unit [default], 0 = the instance of the per-layer call),
  * "decode.batched" (1 = matrix-core kernels for bf16 batches of 2 and more, 16 tokens
  * per pass [default], 0 = the
  * generic kernels), "decode.spin_limit" (how often a balanced batch-1 kernel polls
@@ -265,11 +267,13 @@ clada_status clada_dense_ffn_decode(clada_ctx *ctx, const clada_layer *layer, co
  * future-work paragraphs leave open; this is the second.  Knowing the whole stack, the
  * library can hide what every per-layer call pays: the start-up of a kernel, its ragged
  * end, and the launch of the final reduction.  Option "decode.stack" chooses how:
- *   3 (default)  two lanes: even layers on hip_stream, odd layers on a stream that the
- *                context owns (default priority), forked and joined by events inside the
- *                call -- to the caller the call is ordered on hip_stream like any other,
- *                and a stream capture of hip_stream records both lanes.  The compute
- *                units that layer l has released run layer l+1 already.  The lanes use
+ *   3 (default)  lanes: the layers go round two or three streams -- hip_stream and streams
+ *                that the context owns (default priority), forked and joined by events
+ *                inside the call.  To the caller the call is ordered on hip_stream like any
+ *                other, and a stream capture of hip_stream records all lanes.  The compute
+ *                units that layer l has released run layer l+1 already; where the kernel
+ *                has an instance of which two workgroups fit a compute unit (rows of 4, 5
+ *                and 8 KiB), workgroups of different layers share every unit.  The lanes use
  *                the kernels without cross-workgroup balancing (kernels that wait for
  *                their own workgroups must not share the chip).
  *   2            chained launches on hip_stream: the kernel of layer l also sums the

@@ -70,14 +70,15 @@ clada_status clada_create(clada_ctx **out, int device_id, size_t workspace_bytes
     ctx->opt_decode_batched = 1;
     ctx->opt_decode_own_first = 0;
     ctx->opt_decode_stack = 3;
+    ctx->opt_decode_lane_occ2 = 1;
     ctx->opt_decode_spin_limit = 1 << 12;
     ctx->n_occ = 0;
     ctx->opt_prefix_tile = 0;
     ctx->capturing = 0;
     ctx->opt_diag_events = 0;
     ctx->ev[0] = ctx->ev[1] = ctx->ev[2] = ctx->ev[3] = nullptr;
-    ctx->lane_stream[0] = ctx->lane_stream[1] = nullptr;
-    ctx->ev_lane[0] = ctx->ev_lane[1] = ctx->ev_lane[2] = nullptr;
+    for (int i = 0; i < 3; ++i) ctx->lane_stream[i] = nullptr;
+    for (int i = 0; i < 4; ++i) ctx->ev_lane[i] = nullptr;
     ctx->err[0] = 0;
     if (workspace_bytes > 0) {
         hipError_t e = hipSetDevice(device_id);
@@ -105,9 +106,9 @@ void clada_destroy(clada_ctx *ctx)
     if (!ctx) return;
     for (int i = 0; i < 4; ++i)
         if (ctx->ev[i]) (void)hipEventDestroy(ctx->ev[i]);
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < 4; ++i)
         if (ctx->ev_lane[i]) (void)hipEventDestroy(ctx->ev_lane[i]);
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 3; ++i)
         if (ctx->lane_stream[i]) (void)hipStreamDestroy(ctx->lane_stream[i]);
     if (ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
@@ -146,6 +147,11 @@ clada_status clada_set_option(clada_ctx *ctx, const char *name, int32_t value)
     if (!strcmp(name, "decode.batched")) {
         if (value < 0 || value > 1) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.batched=%d outside [0,1]", value);
         ctx->opt_decode_batched = value;
+        return CLADA_OK;
+    }
+    if (!strcmp(name, "decode.lane_occ2")) {
+        if (value < 0 || value > 1) return clada_fail(ctx, CLADA_ERR_VALUE, "decode.lane_occ2=%d outside [0,1]", value);
+        ctx->opt_decode_lane_occ2 = value;
         return CLADA_OK;
     }
     if (!strcmp(name, "decode.stack")) {

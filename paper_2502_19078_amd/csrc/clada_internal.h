@@ -19,13 +19,14 @@ struct clada_ctx {
     int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
     int opt_decode_batched;      // 1: MFMA path for 2 <= B <= 16 (bf16), 0: generic kernels
     int opt_decode_stack;        // whole-stack calls: 0 = L per-layer calls, 1 = one persistent kernel, 2 = chained launches, 3 = two lanes (default)
+    int opt_decode_lane_occ2;    // two lanes, 8 KiB gated rows: 1 = the instance that fits two workgroups per compute unit
     int opt_decode_spin_limit;   // polls a balanced batch-1 kernel makes before it gives up (see clada.h)
     int opt_prefix_tile;         // gate/up prefill GEMM: 0 choose by T, 1 = 128-token tiles, 2 = 256-token tiles
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)
     hipEvent_t ev[4];            // start/stop of the main decode kernel, start/stop of the final reduction
     int capturing;               // a clada_graph_begin is open
-    hipStream_t lane_stream[2];  // further lanes of the whole-stack calls (created at the first such call, default priority)
-    hipEvent_t ev_lane[3];       // fork, and the join of either further lane
+    hipStream_t lane_stream[3];  // further lanes of the whole-stack calls (created at the first such call, default priority)
+    hipEvent_t ev_lane[4];       // fork, and the join of every further lane
     // workgroups per compute unit of the balanced batch-1 kernel instances on this context's device
     // (asked of the runtime once per instance; the balanced kernel needs all its workgroups resident)
     const void *occ_fn[CLADA_OCC_SLOTS];

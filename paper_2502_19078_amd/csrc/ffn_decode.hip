@@ -722,8 +722,12 @@ struct NoStackReduce {       // the per-layer kernel has nothing to ride along
 // rebuilt from them at the top of every layer).
 // ROUNDS: more than 64 neurons per workgroup, worked off 64 at a time (a template flag: an enclosing loop
 // of unknown trip count costs the kernel ~50 registers, which the balanced instances do not have).
-template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL, bool RELU = false, bool STACK = false, bool ROUNDS = false>
-__global__ void __launch_bounds__(NW * 64)
+// OCC2: an instance for the lanes of the whole-stack calls that fits two workgroups on a compute unit (at most 128
+// registers per lane: x in LDS, DCH = 8), so that a workgroup of layer l and one of layer l+1 share every unit and
+// one's gate phase runs under the other's kept-row phase.
+template <int ES, int NCH, int NW, int DCH, bool DENSE, bool BAL, bool RELU = false, bool STACK = false, bool ROUNDS = false,
+          bool OCC2 = false>
+__global__ void __launch_bounds__(NW * 64, OCC2 ? 4 : 1)
 k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
 {
     constexpr int VEC = 16 / ES;
@@ -734,9 +738,10 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     constexpr int K0MAX = (NCH > 8 ? 1 : 2) * (NW - 1);
     // x in LDS instead of registers: the whole-stack kernel, and rows of 12 and 16 KiB (two row buffers of the
     // gate phase alone are 96 / 128 registers there)
-    constexpr bool XLDS = STACK || NCH > 10;
+    constexpr bool XLDS = STACK || NCH > 10 || OCC2;
     static_assert(!(DENSE && BAL), "the dense twin needs no balancing");
     static_assert(!(ROUNDS && (BAL || STACK)), "rounds only in the plain split-d kernel");
+    static_assert(!(OCC2 && (BAL || STACK || ROUNDS)), "the two-per-unit instance is a plain split-d kernel");
     __shared__ float s_a[64];
     __shared__ int s_flag[64];
     __shared__ int s_list[64];
@@ -746,7 +751,7 @@ k_ffn_decode_b1(const std::conditional_t<STACK, StackParams, B1Params> pp)
     __shared__ int s_n2;
     __shared__ float4 s_sum[STACK ? 32 : 1][16];            // STACK: slices of the final reduction
     __shared__ int s_arrived;                               // STACK: see StackReduce
-    __shared__ __align__(16) unsigned char s_x[(STACK || NCH > 10) ? NCH * 1024 : 16];    // the layer's input row where it is not held in registers
+    __shared__ __align__(16) unsigned char s_x[(STACK || NCH > 10 || OCC2) ? NCH * 1024 : 16];    // the layer's input row where it is not held in registers
     // chained calls: this workgroup's CGW column groups (of four) of all 256 partial outputs of the previous launch
     constexpr int CGW = (NCH * 1024 / ES / 4 + 255) / 256;
     __shared__ float4 s_prev[STACK ? 1 : 256 * CGW];
@@ -1301,6 +1306,29 @@ hipError_t launch_b1(clada_ctx *ctx, const B1Params &p, int P, bool dense, bool 
     return launch_b1_variant<ES, NCH, DCH, false, false, RELU>(ctx, p, P, st);
 }
 
+// The two-per-unit instances (bf16, one round of neurons), sparse or dense; false where the shape has none.
+template <int NCH, int DCH, bool RELU>
+hipError_t launch_b1_occ2_shape(const B1Params &p, int P, bool dense, hipStream_t st)
+{
+    if (dense) hipLaunchKernelGGL((k_ffn_decode_b1<2, NCH, 8, DCH, true, false, RELU, false, false, true>), dim3(P), dim3(512), 0, st, p);
+    else hipLaunchKernelGGL((k_ffn_decode_b1<2, NCH, 8, DCH, false, false, RELU, false, false, true>), dim3(P), dim3(512), 0, st, p);
+    return hipGetLastError();
+}
+
+bool b1_occ2_shape_ok(int es, int nch, bool relu)
+{
+    // (10 KiB rows: the instance needs 128 registers and a few spills, and was measured 6 % slower than the
+    // one-per-unit instance in two lanes)
+    return es == 2 && (relu ? nch == 5 : (nch == 4 || nch == 8));
+}
+
+hipError_t launch_b1_occ2(const B1Params &p, int P, int nch, bool relu, bool dense, hipStream_t st)
+{
+    if (relu) return launch_b1_occ2_shape<5, 8, true>(p, P, dense, st);
+    if (nch == 4) return launch_b1_occ2_shape<4, 8, false>(p, P, dense, st);
+    return launch_b1_occ2_shape<8, 8, false>(p, P, dense, st);
+}
+
 // The split-d instantiations by element size, row length and family (exactly the shapes b1_shape_ok admits).
 // *balance is cleared when the balanced instance cannot have all its workgroups resident at once.
 bool b1_shape_ok(int es, int nch, bool relu)
@@ -1627,7 +1655,7 @@ hipError_t lanes_fork(clada_ctx *ctx, int n_lanes, hipStream_t stream)
     hipError_t e;
     for (int i = 0; i < n_lanes - 1; ++i)
         if (!ctx->lane_stream[i] && (e = hipStreamCreateWithFlags(&ctx->lane_stream[i], hipStreamNonBlocking)) != hipSuccess) return e;
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < 4; ++i)
         if (!ctx->ev_lane[i] && (e = hipEventCreateWithFlags(&ctx->ev_lane[i], hipEventDisableTiming)) != hipSuccess) return e;
     if ((e = hipEventRecord(ctx->ev_lane[0], stream)) != hipSuccess) return e;
     for (int i = 0; i < n_lanes - 1; ++i)
@@ -1720,9 +1748,9 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
         if (persistent) return CLADA_OK;
     }
     // ---- launches issued by the library itself.  Two things the per-layer calls cannot do:
-    // * two lanes (the default): the layers of a stack are independent problems, so even and odd layers run
-    //   on two HIP streams (the caller's and one of the context's, forked and joined by events, which a
-    //   stream capture follows).  A compute unit that has finished its share of layer l takes a workgroup of
+    // * lanes (the default): the layers of a stack are independent problems, so they go round two or three
+    //   HIP streams (the caller's and the context's own, forked and joined by events, which a stream
+    //   capture follows).  A compute unit that has finished its share of layer l takes a workgroup of
     //   layer l+1 at once: the start-up and the ragged end of every kernel are covered by its neighbour
     //   (7B layer shape, sparsity 0.45: 36.0 -> 32.5 us per layer; three and four lanes are slower again).
     //   Kernels that wait for each other's workgroups must not share the chip, so the lanes run the
@@ -1738,7 +1766,12 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
                               b1_shape_ok(es, nch, relu) && Pb == COOP_MAX_WGS && F >= Pb && ni_b <= 1024 && L >= 2;
     if (own_launches) {
         static_assert(COOP_MAX_WGS == 256, "the chained reduction is laid out for 256 partial outputs");
-        const int n_lanes = (smode == 3 && L >= 4) ? 2 : 1;
+        // Rows of 4, 5 and 8 KiB have an instance of which two workgroups fit a compute unit: with it, workgroups
+        // of different layers share every unit (measured, 7B shape, ms per step of 32 layers at sparsity 0.45 /
+        // dense: two lanes 1.038 / 1.379 with the one-per-unit instance, 1.031 / 1.330 with this one; three lanes
+        // 1.085 / 1.460 and 1.006 / 1.357; four lanes 1.041 / 1.391 with this one)
+        const bool occ2 = b1_occ2_shape_ok(es, nch, relu) && ni_b <= 64 && ctx->opt_decode_lane_occ2 != 0;
+        const int n_lanes = (smode == 3 && L >= 4) ? ((occ2 && !dense) ? 3 : 2) : 1;
         const bool chained = smode == 2;
         unsigned int *epoch = reinterpret_cast<unsigned int *>(ctx->ws + COOP_EPOCH);
         float *part = reinterpret_cast<float *>(ctx->ws + CLADA_WS_HEADER);
@@ -1758,7 +1791,7 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
         for (int l = 0; l < L; ++l) {
             const int lane = l % n_lanes, k = l / n_lanes;   // the layer is its lane's k-th
             hipStream_t st = lane ? ctx->lane_stream[lane - 1] : stream;
-            float *mine = part + (size_t)(2 * lane + (chained ? (k & 1) : 0)) * buf;
+            float *mine = part + (size_t)(chained ? 2 * lane + (k & 1) : lane) * buf;
             const int lp = l - n_lanes;                      // the lane's previous layer
             b.wg = (const char *)layers[l].w_gate; b.wu = (const char *)layers[l].w_up; b.wd = (const char *)layers[l].w_down;
             b.b_in = relu ? layers[l].b_in : nullptr;
@@ -1766,11 +1799,14 @@ clada_status run_stack_decode(clada_ctx *ctx, const clada_layer *layers, int32_t
             b.tau = tau ? tau + l : nullptr;
             b.partial = mine;
             const bool sums_prev = chained && lp >= 0;
-            b.prev_partial = sums_prev ? part + (size_t)(2 * lane + ((k - 1) & 1)) * buf : nullptr;
+            b.prev_partial = sums_prev ? part + (size_t)(2 * lane + ((k - 1) & 1)) * buf : nullptr;      // (chained: one lane)
             b.prev_y = sums_prev ? (char *)y + (size_t)lp * d * es : nullptr;
             b.prev_bias = (sums_prev && relu) ? layers[lp].b_out : nullptr;
             b.epoch_out = epoch;                             // only the balanced instance writes it
-            CLADA_CHECK_HIP(ctx, launch_b1_shape(ctx, b, Pb, es, nch, relu, dense, &balance, st));
+            if (n_lanes >= 2 && occ2)
+                CLADA_CHECK_HIP(ctx, launch_b1_occ2(b, Pb, nch, relu, dense, st));
+            else
+                CLADA_CHECK_HIP(ctx, launch_b1_shape(ctx, b, Pb, es, nch, relu, dense, &balance, st));
             if (!chained || l + n_lanes >= L) {              // nobody after it in its lane: its own reduction launch
                 launch_finalize(es, mine, Pb, 1, d, (char *)y + (size_t)l * d * es, (!chained && balance) ? epoch : nullptr, st,
                                 nullptr, nullptr, relu ? layers[l].b_out : nullptr, balance ? b.fault : nullptr);

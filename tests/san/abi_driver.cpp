@@ -94,6 +94,8 @@ int main()
     // options, error text, fault query, graph helpers
     EXPECT(clada_set_option(ctx, "decode.stack", 1), CLADA_OK);
     EXPECT(clada_set_option(ctx, "decode.stack", 4), CLADA_ERR_VALUE);
+    EXPECT(clada_set_option(ctx, "decode.lane_occ2", 0), CLADA_OK);
+    EXPECT(clada_set_option(ctx, "decode.lane_occ2", 2), CLADA_ERR_VALUE);
     EXPECT(clada_set_option(ctx, "decode.b1", 3), CLADA_OK);
     EXPECT(clada_set_option(ctx, "decode.b1", 4), CLADA_ERR_VALUE);
     EXPECT(clada_set_option(ctx, "prefix.tile", 2), CLADA_OK);

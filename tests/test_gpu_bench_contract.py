@@ -41,6 +41,6 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     assert "clada_sparse_ffn_stack_decode" in j["step_path"]
     for k in ("natural", "indicators_off"):
         assert j["per_layer_calls"][k]["ms_per_step"] > 0
-        for mode in ("two_lanes", "chained_launches", "persistent_kernel"):
+        for mode in ("lanes", "chained_launches", "persistent_kernel"):
             assert j["stack_modes"][mode][k]["bit_identical_to_per_layer_calls"] is True
     assert roof["in_step"]["frac"] == pytest.approx(roof["in_step"]["achieved"] / roof["peak"], abs=1e-3)
