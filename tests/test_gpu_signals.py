@@ -33,6 +33,7 @@ def _signals(clada, ctx, z, tok, dtype="f32"):
 @pytest.mark.parametrize("cfg_name,B,V,temp", [
     ("c1", 16, 1000, 1.0), ("c2", 1, 32000, 1.0), ("c3", 8, 32000, 0.25), ("c3", 8, 32000, 16.0),
     ("c4", 1, 128256, 1.0), ("c4", 3, 128256, 4.0), ("c1", 5, 4097, 1.0), ("c1", 2, 7, 1.0), ("c1", 1, 1, 1.0),
+    ("c4", 2, 262144, 1.0), ("c4", 2, 262145, 1.0), ("c4", 3, 500001, 2.0),     # long vocabularies: hundreds of block partials per row
 ])
 def test_signals_parity(clada, ctx, cfg_name, B, V, temp):
     cfg = synth.CONFIGS[cfg_name]
@@ -130,7 +131,7 @@ def test_threshold_parity_all_indicator_patterns(clada, ctx):
 
 
 @pytest.mark.parametrize("cfg_name,B,V,L", [("c1", 16, 1000, 1), ("c2", 1, 32000, 32), ("c4", 3, 128256, 200),
-                                            ("c5", 16, 32000, 40), ("c1", 64, 4097, 4096)])
+                                            ("c5", 16, 32000, 40), ("c1", 64, 4097, 4096), ("c4", 2, 300001, 8)])
 def test_signals_and_thresholds_in_one_launch(clada, ctx, cfg_name, B, V, L):
     """clada_signals_threshold against the oracle's signals and threshold, every indicator pattern and both
     signs of the coefficients; and bit for bit against the two separate calls."""

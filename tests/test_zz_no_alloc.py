@@ -30,12 +30,13 @@ def _call(lib, fn, h, z, tok):
 def test_static_scratch_entry_point_matches_workspace_entry_point():
     import paper_2502_19078_amd as clada
     lib = clada.load_library()
-    with_ws = clada.Context(0, clada.workspace_bytes(0, 0, 16, 0, 128256))
+    with_ws = clada.Context(0, clada.workspace_bytes(0, 0, 16, 0, 400000))
     h0 = C.c_void_p()
     assert lib.clada_create(C.byref(h0), 0, 0) == 0                 # no workspace: this context allocates nothing
     try:
-        # two calls in a row on the shared array, the second with fewer rows and a shorter vocabulary
-        for cfg_name, B, V in (("c4", 16, 128256), ("c2", 3, 32000), ("c1", 1, 1000), ("c4", 5, 128256)):
+        # calls in a row on the shared array, most with fewer rows or a shorter vocabulary than the one before
+        for cfg_name, B, V in (("c4", 4, 400000), ("c4", 2, 300001), ("c4", 16, 128256), ("c2", 3, 32000), ("c1", 1, 1000),
+                               ("c4", 5, 128256), ("c4", 1, 262145)):
             cfg = synth.CONFIGS[cfg_name]
             z, _ = synth.logits(cfg, 9, 0, B=B, V=V)
             tok = synth.draw_tokens(cfg, 9, 0, z)
