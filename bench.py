@@ -501,6 +501,11 @@ def main():
                      "call": {"us": round(call_us, 2), "finalize_us": round(nat["finalize_us"], 2),
                               "achieved": round(achieved_call, 1), "frac": round(achieved_call / HBM_PEAK_GBS, 4)},
                      "us_per_layer_in_step": round(step_us_per_layer, 2),
+                     "note": ("achieved/frac: the kernel of a per-layer call with the chip to itself, timed by kernel-own HIP "
+                              "events on the timed steps' inputs (rocprofv3 row of the balanced instance at B = 1).  The "
+                              "launches of the timed step run in lanes and overlap, so the duration of a single one of them "
+                              "(rocprofv3 rows of the lane instance) is not the time it costs: in_step divides the same bytes "
+                              "by the interval at which launches complete, step time / L"),
                      # the timed step itself: with two lanes two launches share the chip at any time, so the
                      # duration of one launch says little; what counts is the rate at which launches complete
                      # (step time / L, the signals launch included)
