@@ -248,7 +248,12 @@ clada_status clada_cognitive_signals_static(clada_ctx *ctx, const void *logits, 
  * union of kept neurons (entries past the count are left untouched);
  * n_active [1+B] = {union count, per-token counts}; mask_bits
  * [B][ceil(d_ff/32)] bit j%32 of word j/32 set iff keep_bj.
- * The result is bit-reproducible from run to run (fixed summation order). */
+ * The result is bit-reproducible from run to run (fixed summation order).
+ * Paths: B = 1 with rows of whole KiB runs the row-streaming kernel (vector ALUs); bf16
+ * batches of 2 and more run on the matrix cores, 16 tokens per pass, every weight row read
+ * once per pass.  Everything else -- fp32 batches in particular -- runs a generic kernel
+ * that works through the tokens one by one and reads the kept rows once PER TOKEN: correct
+ * and tested, but its HBM traffic grows with B (a limit of this library, not of the method). */
 clada_status clada_sparse_ffn_decode(clada_ctx *ctx, const clada_layer *layer, const void *x,
                                      int32_t B, const float *tau_final, void *y,
                                      int32_t *active_idx, int32_t *n_active,
