@@ -210,7 +210,7 @@ def main():
                                               sur.data_ptr(), ent.data_ptr(), tau_final.data_ptr(), sp))
 
     # B = 1: the FFN stack of a step goes through the whole-stack call (the layers of the workload are
-    # independent problems; by default the library runs even and odd layers on two streams); the per-layer
+    # independent problems; by default the library sends the layers round two or three streams); the per-layer
     # calls are measured beside it.  B >= 2: per-layer calls.
     use_stack = not args.per_layer
     arr = binding.layer_array(layers)
@@ -506,7 +506,7 @@ def main():
                               "launches of the timed step run in lanes and overlap, so the duration of a single one of them "
                               "(rocprofv3 rows of the lane instance) is not the time it costs: in_step divides the same bytes "
                               "by the interval at which launches complete, step time / L"),
-                     # the timed step itself: with two lanes two launches share the chip at any time, so the
+                     # the timed step itself: in lanes several launches share the chip at any time, so the
                      # duration of one launch says little; what counts is the rate at which launches complete
                      # (step time / L, the signals launch included)
                      "in_step": {"lanes": n_lanes,

@@ -18,8 +18,8 @@ struct clada_ctx {
     int opt_decode_b1;           // batch-1 split-d kernel: 0 off (generic kernels), 1 balancing where it pays, 2 never, 3 always
     int opt_decode_own_first;    // K0 of the balanced kernel; 0 = default
     int opt_decode_batched;      // 1: MFMA path for 2 <= B <= 16 (bf16), 0: generic kernels
-    int opt_decode_stack;        // whole-stack calls: 0 = L per-layer calls, 1 = one persistent kernel, 2 = chained launches, 3 = two lanes (default)
-    int opt_decode_lane_occ2;    // two lanes, 8 KiB gated rows: 1 = the instance that fits two workgroups per compute unit
+    int opt_decode_stack;        // whole-stack calls: 0 = L per-layer calls, 1 = one persistent kernel, 2 = chained launches, 3 = lanes (default)
+    int opt_decode_lane_occ2;    // lanes at B = 1, rows of 4, 5, 8 KiB: 1 = the instance of which two workgroups fit a compute unit
     int opt_decode_spin_limit;   // polls a balanced batch-1 kernel makes before it gives up (see clada.h)
     int opt_prefix_tile;         // gate/up prefill GEMM: 0 choose by T, 1 = 128-token tiles, 2 = 256-token tiles
     int opt_diag_events;         // 1: decode calls record HIP events around their kernels (clada_diag_kernel_times)

@@ -26,7 +26,8 @@
 namespace {
 
 // The partial-output region at the start of the decode scratch: [P][B][d] fp32 for up to CLADA_MAX_DECODE_WGS
-// workgroups, and at least three buffers of [COOP_MAX_WGS][d] for the whole-stack kernel (B = 1).
+// workgroups, and at least four buffers of [COOP_MAX_WGS][d] for the whole-stack calls at B = 1 (one per lane, two
+// for chained launches, three for the persistent kernel).
 size_t ws_partial_bytes(int B, int d)
 {
     size_t rows = (size_t)CLADA_MAX_DECODE_WGS * B;

@@ -1,5 +1,5 @@
 """GPU parity: the whole-stack calls against the per-layer calls, bit for bit, and against the fp64 oracle.
-Modes of the call (option decode.stack): 3 = two lanes, the default (even and odd layers on two streams);
+Modes of the call (option decode.stack): 3 = lanes, the default (the layers go round two or three streams);
 2 = chained launches (every layer's kernel also sums the previous layer's partial outputs); 1 = one
 persistent launch for the L layers; 0 = the per-layer calls."""
 import numpy as np
@@ -144,7 +144,7 @@ def test_stack_call_rejects_mixed_layers_and_bad_arguments(clada):
         ctx.check(ctx._lib.clada_sparse_ffn_stack_decode(ctx._h, None, 2, xd.data_ptr(), 1, td.data_ptr(), xd.data_ptr(), None, None))
 
 
-@pytest.mark.parametrize("mode", [1, 2])      # (two lanes run kernels that wait for nobody)
+@pytest.mark.parametrize("mode", [1, 2])      # (the lanes run kernels that wait for nobody)
 def test_bounded_waits_of_the_stack_kernel_give_up_cleanly(clada, mode):
     """Spin limit forced to zero from the host: every workgroup still runs to its end, the outputs are NaN
     and the context reports the fault."""
@@ -164,14 +164,14 @@ def test_bounded_waits_of_the_stack_kernel_give_up_cleanly(clada, mode):
 
 
 def test_stack_call_modes_agree_and_replay_from_a_graph(clada):
-    """The modes give the same bits; captured calls (two lanes: a fork and a join inside the capture; chained
+    """The modes give the same bits; captured calls (lanes: a fork and a join inside the capture; chained
     launches) replay correctly on changed inputs."""
     cfg, ws, layers, x = _stack(clada, "c2", 4096, 11008, 4, seed=26)
     ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
     ctx.set_option("decode.b1", 2)                      # no balancing: every mode then adds in the same order
     xd, td = to_dev(x, cfg.dtype), torch.full((4,), 0.25, dtype=torch.float32, device=DEV)
     y2, cnt = clada.sparse_ffn_stack_decode(ctx, layers, xd, td, want_counts=True)
-    y2 = clada.sparse_ffn_stack_decode(ctx, layers, xd, td).clone()          # default: two lanes
+    y2 = clada.sparse_ffn_stack_decode(ctx, layers, xd, td).clone()          # default: lanes
     for mode in (0, 1, 2):
         ctx.set_option("decode.stack", mode)
         assert torch.equal(clada.sparse_ffn_stack_decode(ctx, layers, xd, td), y2), f"mode {mode}"
@@ -181,7 +181,7 @@ def test_stack_call_modes_agree_and_replay_from_a_graph(clada):
         yl, _, cl, _ = clada.sparse_ffn_decode(ctx, layers[l], xd[l:l + 1].contiguous(), td[l:l + 1].contiguous(), want_lists=True)
         assert torch.equal(y2[l], yl[0]) and torch.equal(cnt[l], cl)
     # graph: static input and output buffers, replays with other inputs and thresholds in between eager work;
-    # two lanes, and chained launches of the balanced kernel (whose call counter the chain advances itself)
+    # lanes, and chained launches of the balanced kernel (whose call counter the chain advances itself)
     for mode, b1 in ((3, 1), (2, 1), (2, 2)):
         ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
         ctx.set_option("decode.stack", mode)
