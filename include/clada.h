@@ -362,6 +362,20 @@ clada_status clada_mask_sparse_encode(clada_ctx *ctx, const uint32_t *mask_bits,
 clada_status clada_mask_sparse_decode(clada_ctx *ctx, const uint8_t *stream, const int32_t *n_bytes,
                                       int32_t stream_capacity, const uint32_t *ref_bits, int32_t d_ff,
                                       uint32_t *mask_bits, void *hip_stream);
+/* The same for n_masks masks in one launch (1 <= n_masks <= 65535; one workgroup per mask), e.g. the
+ * B masks of a layer against its prefix-static mask, or every token's mask against the previous
+ * token's: mask m = mask_bits + m * ceil(d_ff/32) words; its reference = ref_bits + m * ref_stride_words
+ * (0: one reference for all masks; ref_bits NULL: none); its stream = stream + m * stream_capacity;
+ * n_out [n_masks][2]; the decoder reads the byte count of stream m at n_bytes[m * n_bytes_stride]
+ * (2 reads the encoder's n_out in place). */
+clada_status clada_mask_sparse_encode_batch(clada_ctx *ctx, const uint32_t *mask_bits, const uint32_t *ref_bits,
+                                            int64_t ref_stride_words, int32_t d_ff, int32_t n_masks,
+                                            uint8_t *stream, int32_t stream_capacity, int32_t *n_out,
+                                            void *hip_stream);
+clada_status clada_mask_sparse_decode_batch(clada_ctx *ctx, const uint8_t *stream, const int32_t *n_bytes,
+                                            int64_t n_bytes_stride, int32_t stream_capacity,
+                                            const uint32_t *ref_bits, int64_t ref_stride_words, int32_t d_ff,
+                                            int32_t n_masks, uint32_t *mask_bits, void *hip_stream);
 
 /* Sparse SwiGLU FFN over a given neuron list (the sparse forward pass of the
  * algorithm "CLADA Inference" with a mask that does not depend on the token):

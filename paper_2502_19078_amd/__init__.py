@@ -11,6 +11,7 @@ from .binding import (Context, Layer, PrefixStats, CladaError, cognitive_signals
                       sparse_ffn_decode, threshold, threshold_calibrate, signals_threshold,
                       threshold_search_cett, cett_eval, static_mask_threshold,
                       static_mask_topk, static_ffn_decode, mask_pack, mask_unpack,
-                      mask_sparse_encode, mask_sparse_decode, sparse_ffn_stack_decode,
+                      mask_sparse_encode, mask_sparse_decode, mask_sparse_encode_batch,
+                      mask_sparse_decode_batch, sparse_ffn_stack_decode,
                       dense_ffn_stack_decode, layer_array,
                       workspace_bytes, Graph, graph_begin, graph_end)

@@ -93,6 +93,10 @@ def load_library() -> C.CDLL:
     lib.clada_mask_sparse_encode.restype = C.c_int
     lib.clada_mask_sparse_decode.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp]
     lib.clada_mask_sparse_decode.restype = C.c_int
+    lib.clada_mask_sparse_encode_batch.argtypes = [vp, vp, vp, C.c_int64, i32, i32, vp, i32, vp, vp]
+    lib.clada_mask_sparse_encode_batch.restype = C.c_int
+    lib.clada_mask_sparse_decode_batch.argtypes = [vp, vp, vp, C.c_int64, i32, vp, C.c_int64, i32, i32, vp, vp]
+    lib.clada_mask_sparse_decode_batch.restype = C.c_int
     lib.clada_device_fault.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.clada_graph_begin.argtypes = [vp, vp]
     lib.clada_graph_end.argtypes = [vp, vp, C.POINTER(vp)]
@@ -438,6 +442,46 @@ def mask_sparse_decode(ctx: Context, stream: torch.Tensor, n_bytes: torch.Tensor
         out = torch.empty((d_ff + 31) // 32, dtype=torch.int32, device=stream.device)
     ctx.check(ctx._lib.clada_mask_sparse_decode(ctx._h, _ptr(stream), _ptr(n_bytes), int(stream.numel()), _ptr(ref_bits),
                                                 int(d_ff), _ptr(out), _stream(stream)))
+    return out
+
+
+def _ref_stride(ref_bits, n, words):
+    if ref_bits is None or ref_bits.dim() == 1:
+        return 0
+    assert ref_bits.shape == (n, words)
+    return words
+
+
+def mask_sparse_encode_batch(ctx: Context, mask_bits: torch.Tensor, ref_bits: torch.Tensor | None, d_ff: int,
+                             capacity: int | None = None):
+    """mask_bits [n][words] against ref_bits ([words] shared, [n][words] one each, or None)
+    -> (streams uint8 [n][capacity], n_out int32 [n][2])."""
+    words = (d_ff + 31) // 32
+    assert mask_bits.is_cuda and mask_bits.dtype == torch.int32 and mask_bits.dim() == 2 and mask_bits.shape[1] == words
+    assert mask_bits.is_contiguous() and (ref_bits is None or (ref_bits.is_cuda and ref_bits.dtype == torch.int32
+                                                               and ref_bits.is_contiguous()))
+    n = mask_bits.shape[0]
+    if capacity is None:
+        capacity = int(ctx._lib.clada_mask_sparse_max_bytes(int(d_ff)))
+    streams = torch.empty(n, max(capacity, 1), dtype=torch.uint8, device=mask_bits.device)
+    n_out = torch.empty(n, 2, dtype=torch.int32, device=mask_bits.device)
+    ctx.check(ctx._lib.clada_mask_sparse_encode_batch(ctx._h, _ptr(mask_bits), _ptr(ref_bits), _ref_stride(ref_bits, n, words),
+                                                      int(d_ff), n, _ptr(streams), int(streams.shape[1]), _ptr(n_out),
+                                                      _stream(mask_bits)))
+    return streams, n_out
+
+
+def mask_sparse_decode_batch(ctx: Context, streams: torch.Tensor, n_out: torch.Tensor, ref_bits: torch.Tensor | None,
+                             d_ff: int) -> torch.Tensor:
+    """Streams [n][capacity] with the encoder's n_out [n][2] -> bit masks [n][words] int32."""
+    words = (d_ff + 31) // 32
+    assert streams.is_cuda and streams.dtype == torch.uint8 and streams.dim() == 2 and streams.is_contiguous()
+    n = streams.shape[0]
+    assert n_out.is_cuda and n_out.dtype == torch.int32 and n_out.shape == (n, 2) and n_out.is_contiguous()
+    out = torch.empty(n, words, dtype=torch.int32, device=streams.device)
+    ctx.check(ctx._lib.clada_mask_sparse_decode_batch(ctx._h, _ptr(streams), _ptr(n_out), 2, int(streams.shape[1]),
+                                                      _ptr(ref_bits), _ref_stride(ref_bits, n, words), int(d_ff), n,
+                                                      _ptr(out), _stream(streams)))
     return out
 
 

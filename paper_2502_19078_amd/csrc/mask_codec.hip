@@ -47,12 +47,18 @@ __device__ __forceinline__ int gap_bytes(int gap) { return 1 + (gap >= 128 ? 1 :
 
 // Thread t owns the words [t*per, (t+1)*per): the gap of its first position needs the last position of
 // the threads before it (an exclusive max-scan), the byte offset an exclusive sum of the byte counts.
+// One workgroup per mask: mask m at mask + m * words, its reference at ref + m * ref_stride (0: one for all),
+// its stream at out + m * cap, its two counts at n_out + 2 m.
 __global__ void __launch_bounds__(NT)
-k_mask_sparse_encode(const unsigned int *__restrict__ mask, const unsigned int *__restrict__ ref, int F,
+k_mask_sparse_encode(const unsigned int *__restrict__ mask, const unsigned int *__restrict__ ref, size_t ref_stride, int F,
                      unsigned char *__restrict__ out, int cap, int *__restrict__ n_out)
 {
     __shared__ int s_wave[NT / 64];
     const int words = (F + 31) / 32;
+    mask += (size_t)blockIdx.x * words;
+    if (ref) ref += (size_t)blockIdx.x * ref_stride;
+    out += (size_t)blockIdx.x * cap;
+    n_out += 2 * (size_t)blockIdx.x;
     const int per = (words + NT - 1) / NT;
     const int w0 = min(words, (int)threadIdx.x * per), w1 = min(words, w0 + per);
     auto diff = [&](int w) {
@@ -110,12 +116,16 @@ k_mask_sparse_encode(const unsigned int *__restrict__ mask, const unsigned int *
 // malformed stream can only name positions >= F, which are ignored; bytes after the last complete number
 // are ignored as well.
 __global__ void __launch_bounds__(NT)
-k_mask_sparse_decode(const unsigned char *__restrict__ in, const int *__restrict__ n_bytes, int cap,
-                     const unsigned int *ref, int F, unsigned int *out)
+k_mask_sparse_decode(const unsigned char *__restrict__ in, const int *__restrict__ n_bytes, size_t n_stride, int cap,
+                     const unsigned int *ref, size_t ref_stride, int F, unsigned int *out)
 {
     __shared__ int s_wave[NT / 64];
     __shared__ unsigned int s_bits[MAX_WORDS];
     const int words = (F + 31) / 32;
+    in += (size_t)blockIdx.x * cap;
+    n_bytes += (size_t)blockIdx.x * n_stride;
+    if (ref) ref += (size_t)blockIdx.x * ref_stride;      // (out may be ref: every word is read before it is written)
+    out += (size_t)blockIdx.x * words;
     for (int w = threadIdx.x; w < words; w += NT) s_bits[w] = 0u;
     const int n = min(max(n_bytes[0], 0), cap);
     const int per = (n + NT - 1) / NT;
@@ -156,32 +166,57 @@ extern "C" size_t clada_mask_sparse_max_bytes(int32_t d_ff)
     return (size_t)d_ff + (size_t)d_ff / 128 + (size_t)d_ff / 16384;
 }
 
+static clada_status check_codec(clada_ctx *ctx, int32_t d_ff, int32_t n_masks, int32_t stream_capacity, int64_t ref_stride)
+{
+    if (d_ff < 1 || d_ff > CLADA_MAX_DFF) return clada_fail(ctx, CLADA_ERR_SHAPE, "d_ff=%d outside [1,%d]", d_ff, CLADA_MAX_DFF);
+    if (n_masks < 1 || n_masks > 65535) return clada_fail(ctx, CLADA_ERR_SHAPE, "n_masks=%d outside [1,65535]", n_masks);
+    if (stream_capacity < 0) return clada_fail(ctx, CLADA_ERR_SHAPE, "stream_capacity=%d is negative", stream_capacity);
+    if (ref_stride < 0) return clada_fail(ctx, CLADA_ERR_SHAPE, "ref_stride_words=%lld is negative", (long long)ref_stride);
+    if (!ctx->ws) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "the context has no workspace (no device)");
+    return CLADA_OK;
+}
+
+extern "C" clada_status clada_mask_sparse_encode_batch(clada_ctx *ctx, const uint32_t *mask_bits, const uint32_t *ref_bits,
+                                                       int64_t ref_stride_words, int32_t d_ff, int32_t n_masks,
+                                                       uint8_t *stream, int32_t stream_capacity, int32_t *n_out,
+                                                       void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    if (!mask_bits || !stream || !n_out) return clada_fail(ctx, CLADA_ERR_NULL, "mask_bits, stream or n_out is NULL");
+    clada_status cs = check_codec(ctx, d_ff, n_masks, stream_capacity, ref_stride_words);
+    if (cs != CLADA_OK) return cs;
+    hipLaunchKernelGGL(k_mask_sparse_encode, dim3(n_masks), dim3(NT), 0, (hipStream_t)hip_stream, mask_bits, ref_bits,
+                       (size_t)ref_stride_words, d_ff, stream, stream_capacity, n_out);
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    return CLADA_OK;
+}
+
+extern "C" clada_status clada_mask_sparse_decode_batch(clada_ctx *ctx, const uint8_t *stream, const int32_t *n_bytes,
+                                                       int64_t n_bytes_stride, int32_t stream_capacity,
+                                                       const uint32_t *ref_bits, int64_t ref_stride_words, int32_t d_ff,
+                                                       int32_t n_masks, uint32_t *mask_bits, void *hip_stream)
+{
+    if (!ctx) return CLADA_ERR_NULL;
+    if (!stream || !n_bytes || !mask_bits) return clada_fail(ctx, CLADA_ERR_NULL, "stream, n_bytes or mask_bits is NULL");
+    clada_status cs = check_codec(ctx, d_ff, n_masks, stream_capacity, ref_stride_words);
+    if (cs != CLADA_OK) return cs;
+    if (n_bytes_stride < 1) return clada_fail(ctx, CLADA_ERR_SHAPE, "n_bytes_stride=%lld below 1", (long long)n_bytes_stride);
+    hipLaunchKernelGGL(k_mask_sparse_decode, dim3(n_masks), dim3(NT), 0, (hipStream_t)hip_stream, stream, n_bytes,
+                       (size_t)n_bytes_stride, stream_capacity, ref_bits, (size_t)ref_stride_words, d_ff, mask_bits);
+    CLADA_CHECK_HIP(ctx, hipGetLastError());
+    return CLADA_OK;
+}
+
 extern "C" clada_status clada_mask_sparse_encode(clada_ctx *ctx, const uint32_t *mask_bits, const uint32_t *ref_bits,
                                                  int32_t d_ff, uint8_t *stream, int32_t stream_capacity,
                                                  int32_t *n_out, void *hip_stream)
 {
-    if (!ctx) return CLADA_ERR_NULL;
-    if (!mask_bits || !stream || !n_out) return clada_fail(ctx, CLADA_ERR_NULL, "mask_bits, stream or n_out is NULL");
-    if (d_ff < 1 || d_ff > CLADA_MAX_DFF) return clada_fail(ctx, CLADA_ERR_SHAPE, "d_ff=%d outside [1,%d]", d_ff, CLADA_MAX_DFF);
-    if (stream_capacity < 0) return clada_fail(ctx, CLADA_ERR_SHAPE, "stream_capacity=%d is negative", stream_capacity);
-    if (!ctx->ws) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "the context has no workspace (no device)");
-    hipLaunchKernelGGL(k_mask_sparse_encode, dim3(1), dim3(NT), 0, (hipStream_t)hip_stream, mask_bits, ref_bits, d_ff,
-                       stream, stream_capacity, n_out);
-    CLADA_CHECK_HIP(ctx, hipGetLastError());
-    return CLADA_OK;
+    return clada_mask_sparse_encode_batch(ctx, mask_bits, ref_bits, 0, d_ff, 1, stream, stream_capacity, n_out, hip_stream);
 }
 
 extern "C" clada_status clada_mask_sparse_decode(clada_ctx *ctx, const uint8_t *stream, const int32_t *n_bytes,
                                                  int32_t stream_capacity, const uint32_t *ref_bits, int32_t d_ff,
                                                  uint32_t *mask_bits, void *hip_stream)
 {
-    if (!ctx) return CLADA_ERR_NULL;
-    if (!stream || !n_bytes || !mask_bits) return clada_fail(ctx, CLADA_ERR_NULL, "stream, n_bytes or mask_bits is NULL");
-    if (d_ff < 1 || d_ff > CLADA_MAX_DFF) return clada_fail(ctx, CLADA_ERR_SHAPE, "d_ff=%d outside [1,%d]", d_ff, CLADA_MAX_DFF);
-    if (stream_capacity < 0) return clada_fail(ctx, CLADA_ERR_SHAPE, "stream_capacity=%d is negative", stream_capacity);
-    if (!ctx->ws) return clada_fail(ctx, CLADA_ERR_WORKSPACE, "the context has no workspace (no device)");
-    hipLaunchKernelGGL(k_mask_sparse_decode, dim3(1), dim3(NT), 0, (hipStream_t)hip_stream, stream, n_bytes,
-                       stream_capacity, ref_bits, d_ff, mask_bits);
-    CLADA_CHECK_HIP(ctx, hipGetLastError());
-    return CLADA_OK;
+    return clada_mask_sparse_decode_batch(ctx, stream, n_bytes, 1, stream_capacity, ref_bits, 0, d_ff, 1, mask_bits, hip_stream);
 }

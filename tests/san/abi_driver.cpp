@@ -79,6 +79,11 @@ int main()
     EXPECT(clada_mask_sparse_decode(ctx, (const uint8_t *)p, (const int32_t *)p, 16, nullptr, 1 << 30, (uint32_t *)p, nullptr), CLADA_ERR_SHAPE);
     EXPECT(clada_mask_sparse_decode(ctx, (const uint8_t *)p, nullptr, 16, nullptr, 64, (uint32_t *)p, nullptr), CLADA_ERR_NULL);
     EXPECT(clada_mask_sparse_decode(ctx, (const uint8_t *)p, (const int32_t *)p, 16, nullptr, 64, (uint32_t *)p, nullptr), CLADA_ERR_WORKSPACE);
+    EXPECT(clada_mask_sparse_encode_batch(ctx, (const uint32_t *)p, nullptr, 0, 64, 0, (uint8_t *)p, 16, (int32_t *)p, nullptr), CLADA_ERR_SHAPE);
+    EXPECT(clada_mask_sparse_encode_batch(ctx, (const uint32_t *)p, nullptr, -1, 64, 2, (uint8_t *)p, 16, (int32_t *)p, nullptr), CLADA_ERR_SHAPE);
+    EXPECT(clada_mask_sparse_encode_batch(ctx, (const uint32_t *)p, nullptr, 0, 64, 2, (uint8_t *)p, 16, (int32_t *)p, nullptr), CLADA_ERR_WORKSPACE);
+    EXPECT(clada_mask_sparse_decode_batch(ctx, (const uint8_t *)p, (const int32_t *)p, 2, 16, nullptr, 0, 64, 70000, (uint32_t *)p, nullptr), CLADA_ERR_SHAPE);
+    EXPECT(clada_mask_sparse_decode_batch(ctx, (const uint8_t *)p, (const int32_t *)p, 2, 16, nullptr, 0, 64, 2, (uint32_t *)p, nullptr), CLADA_ERR_WORKSPACE);
     {
         clada_layer two[2] = {ok, ok};
         EXPECT(clada_sparse_ffn_stack_decode(ctx, nullptr, 2, p, 1, (const float *)p, p, nullptr, nullptr), CLADA_ERR_NULL);

@@ -133,3 +133,45 @@ def test_bit_mask_pack_unpack_against_oracle(clada, ctx, F):
     assert _host_words(bits) == mc.pack(keep, F)
     idx2, n2 = clada.mask_unpack(ctx, bits, F)
     assert idx2[: int(n2)].cpu().tolist() == mc.unpack(_host_words(bits), F) == keep.tolist()
+
+
+@pytest.mark.parametrize("d_ff,n,mode", [(300, 5, "shared"), (11008, 16, "shared"), (11008, 16, "chain"), (14336, 7, "none"),
+                                         (262144, 3, "chain"), (33, 64, "shared")])
+def test_batch_calls_are_the_single_calls_mask_by_mask(clada, ctx, d_ff, n, mode):
+    """n masks in one launch: one shared reference (a layer's prefix-static mask), one reference each (the
+    previous token's mask) or none.  Streams, counts and decoded masks are the oracle's, mask by mask; a
+    capacity that some streams do not fit marks exactly those."""
+    r = np.random.default_rng(d_ff + n)
+    base = r.random(d_ff) < 0.5
+    masks = [base ^ (r.random(d_ff) < 0.002 * (m + 1)) for m in range(n)]
+    words = [mc.pack(np.flatnonzero(m), d_ff) for m in masks]
+    if mode == "shared":
+        refs = [mc.pack(np.flatnonzero(base), d_ff)] * n
+        rd = _dev_words(refs[0])
+    elif mode == "chain":
+        refs = [mc.pack(np.flatnonzero(base), d_ff)] + words[:-1]
+        rd = torch.stack([_dev_words(w) for w in refs])
+    else:
+        refs, rd = [None] * n, None
+    wd = torch.stack([_dev_words(w) for w in words])
+    streams, n_out = clada.mask_sparse_encode_batch(ctx, wd, rd, d_ff)
+    back = clada.mask_sparse_decode_batch(ctx, streams, n_out, rd, d_ff)
+    torch.cuda.synchronize()
+    want = [mc.sparse_encode(words[m], refs[m], d_ff) for m in range(n)]
+    for m in range(n):
+        nb, npos = (int(v) for v in n_out[m].cpu())
+        assert (nb, npos) == (len(want[m][0]), want[m][1]), m
+        assert bytes(streams[m, :nb].cpu().numpy()) == want[m][0], m
+        assert _host_words(back[m]) == words[m], m
+    # a capacity between the shortest and the longest stream
+    lens = sorted(len(w[0]) for w in want)
+    if lens[0] < lens[-1]:
+        cap = (lens[0] + lens[-1]) // 2
+        streams2, n2 = clada.mask_sparse_encode_batch(ctx, wd, rd, d_ff, capacity=cap)
+        torch.cuda.synchronize()
+        for m in range(n):
+            nb = int(n2[m, 0])
+            assert nb == (len(want[m][0]) if len(want[m][0]) <= cap else -1), m
+            assert int(n2[m, 1]) == want[m][1]
+            if nb >= 0:
+                assert bytes(streams2[m, :nb].cpu().numpy()) == want[m][0]
