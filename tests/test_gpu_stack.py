@@ -225,6 +225,8 @@ BATCH_CASES = [
     ("c3", 4096, 3000, 5, 8),
     ("c5", 5120, 2100, 4, 16),
     ("c3", 4096, 1500, 3, 20),
+    ("c3", 4096, 1024, 2, 64),
+    ("c3", 2048, 2048, 3, 33),
     ("c3", 2048, 1024, 1, 4),
     ("c1", 512, 700, 3, 4),
     ("c3", 1536, 900, 3, 3),
