@@ -291,3 +291,32 @@ def test_batched_stack_call_replays_from_a_graph(clada):
                 assert torch.equal(got[l], clada.sparse_ffn_decode(ctx, layers[l], xs[l], ts[l])), f"replay {rep} layer {l}"
             stream.synchronize()
     assert not ctx.device_fault()
+
+
+def test_stack_call_inside_a_torch_graph(clada):
+    """A capture that the library does not own (torch.cuda.graph on a side stream): the lanes join it through
+    their fork and join events; replays on changed inputs give the eager bits."""
+    cfg, ws, layers, x = _stack(clada, "c2", 4096, 11008, 6, seed=27)
+    ctx = clada.Context(0, clada.workspace_bytes(4096, 11008, 1, 0, 0))
+    xd = to_dev(x, cfg.dtype)
+    xs, ts, ys = xd.clone(), torch.full((6,), 0.25, dtype=torch.float32, device=DEV), torch.empty_like(xd)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        clada.sparse_ffn_stack_decode(ctx, layers, xs, ts, y=ys)            # first call: creates the lane streams
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        clada.sparse_ffn_stack_decode(ctx, layers, xs, ts, y=ys)
+    for rep in range(3):
+        xs.copy_(torch.roll(xd, rep + 1, dims=0))
+        ts.fill_(0.15 + 0.1 * rep)
+        ys.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got = ys.clone()
+        want = clada.sparse_ffn_stack_decode(ctx, layers, xs, ts)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {rep}"
+    assert not ctx.device_fault()
